@@ -1,0 +1,179 @@
+/*
+ * cafeq.h -- C ABI of the MI355X (gfx950) CafeQ hot-path library.
+ *
+ * CafeQ (arxiv 2511.19705) learns a block-diagonal transform M per weight matrix so
+ * that round-to-nearest quantization of the transformed weight loses less, using
+ * losses that need no calibration data.  This library evaluates the inner loop of
+ * that optimisation on one GPU:
+ *   transform -> per-group absmax scale -> b-bit round-to-nearest -> dequantize ->
+ *   inverse transform -> reduce the data-free proxy losses and the gradient of the
+ *   differentiable surrogate with respect to the transform,
+ * for a single matrix (paper Sec. 4.1), for a coupled pair sharing M / M^-1
+ * (Sec. 4.2), and one iteration of the alternating adaptive rounding (Sec. 5, Alg. 1).
+ *
+ * Conventions (all entry points)
+ *  - Weights are row-major 2-D arrays W[rows][cols] with leading dimension `ld`
+ *    (elements), float32 or bfloat16 storage; all arithmetic is float32 (float64 for
+ *    final reductions and for the small k x k solves).
+ *  - A transform is `nb` dense k x k float32 blocks, T[nb][k][k] row-major, with its
+ *    blockwise inverse Tinv[nb][k][k].  It acts along one axis of W:
+ *      CAFEQ_AXIS_COL: Z = W . blockdiag(X)      (nb*k == cols; contiguous axis)
+ *      CAFEQ_AXIS_ROW: Z = blockdiag(X) . W      (nb*rep*k == rows; row-block q of k
+ *                      rows uses block q / rep -- grouped-query heads share a block)
+ *    With PyTorch's [out][in] weight layout the paper's M (acting on the contraction
+ *    dimension) is T^T on AXIS_COL.
+ *  - Quantization groups are `group` consecutive elements along cfg->axis
+ *    (group == 0: the whole line).  Scale layout: AXIS_COL -> scales[rows][cols/group],
+ *    AXIS_ROW -> scales[rows/group][cols].  Codes are one int8 per element, [rows][cols]
+ *    dense (leading dimension == cols).
+ *  - Symmetric grid (CAFEQ_Q_SYM_ABSMAX): a = max|z| over the group, qmax = 2^(b-1)-1,
+ *    inv = fl32(qmax / a), q = clamp(rint(fl32(z*inv)), -2^(b-1), qmax) (ties to even),
+ *    s = fl32(a / qmax), dequantized value fl32(q*s); a == 0 gives s = 0, q = 0.
+ *  - Every pointer named in a signature is a DEVICE pointer owned by the caller unless
+ *    stated otherwise; descriptor structs themselves are host memory, read during the
+ *    call only.  Nothing is allocated or freed by the library; scratch memory is the
+ *    caller's `ws` buffer, sized by cafeq_workspace_bytes() and 256-byte aligned.
+ *  - `stream` is a hipStream_t (NULL = default stream).  Calls enqueue work and return;
+ *    outputs are valid once the stream has been synchronised.  Results (losses too) are
+ *    written to device memory, never returned through the host.
+ *  - Return value: CAFEQ_OK (0) or a negative cafeq_status.  Argument errors are
+ *    detected on the host before anything is launched.  No exceptions cross the ABI.
+ *  - Calls that share a `ws` buffer must be ordered on one stream.
+ */
+#ifndef CAFEQ_H
+#define CAFEQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CAFEQ_OK = 0,
+  CAFEQ_ERR_INVALID_ARG = -1, /* NULL where a pointer is required, bad enum value   */
+  CAFEQ_ERR_BAD_SHAPE = -2,   /* sizes not divisible as the operation requires      */
+  CAFEQ_ERR_BAD_ALIGN = -3,   /* pointer / leading dimension alignment              */
+  CAFEQ_ERR_UNSUPPORTED = -4, /* valid request this build has no kernel for         */
+  CAFEQ_ERR_SINGULAR = -5,    /* reserved for host-visible singularity reports      */
+  CAFEQ_ERR_LAUNCH = -6,      /* the HIP runtime refused a launch                   */
+  CAFEQ_ERR_WORKSPACE = -7    /* ws is NULL or smaller than cafeq_workspace_bytes() */
+} cafeq_status;
+
+typedef enum { CAFEQ_F32 = 0, CAFEQ_BF16 = 1 } cafeq_dtype;
+typedef enum { CAFEQ_AXIS_COL = 0, CAFEQ_AXIS_ROW = 1 } cafeq_axis;
+typedef enum { CAFEQ_SIDE_T = 0, CAFEQ_SIDE_TINV = 1 } cafeq_side;
+typedef enum { CAFEQ_Q_SYM_ABSMAX = 0, CAFEQ_Q_ASYM_MINMAX = 1 } cafeq_qmode;
+
+/* Row-major matrix view. data: device pointer, 16-byte aligned; ld in elements, a
+ * multiple of 4 (float32) or 8 (bfloat16); dtype: cafeq_dtype. */
+typedef struct {
+  const void* data;
+  int64_t rows, cols, ld;
+  int32_t dtype;
+} cafeq_mat;
+
+/* Block-diagonal transform. T and Tinv: device, [nb][k][k] float32, 16-byte aligned.
+ * k in {32, 64, 128, 256}.  rep >= 1: number of consecutive row-blocks sharing one
+ * block (AXIS_ROW only; must be 1 on AXIS_COL). */
+typedef struct {
+  const float* T;
+  const float* Tinv;
+  int32_t k, nb, rep;
+} cafeq_xform;
+
+/* bits in [2, 8]; group: elements per scale along `axis` (0 = whole line);
+ * axis: cafeq_axis; mode: cafeq_qmode (only CAFEQ_Q_SYM_ABSMAX has kernels). */
+typedef struct {
+  int32_t bits, group, axis, mode;
+} cafeq_quant_cfg;
+
+typedef enum {
+  CAFEQ_CALL_RTN_QUANTIZE = 0,
+  CAFEQ_CALL_PROXY_LOSS = 1,
+  CAFEQ_CALL_DUAL_PROXY_LOSS = 2,
+  CAFEQ_CALL_ADAPTIVE_ROUND = 3
+} cafeq_call_id;
+
+const char* cafeq_strerror(int status);
+/* Library version as major*10000 + minor*100 + patch. */
+int cafeq_version(void);
+
+/* Bytes of scratch the given call needs for these arguments (0 on invalid input).
+ * `a` is the only matrix for single-matrix calls; `b` and `x` may be NULL where the
+ * call does not use them.  Only shapes are read, data pointers are ignored. */
+size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b,
+                             const cafeq_xform* x, const cafeq_quant_cfg* cfg);
+
+/* Blockwise inverse and the squared norms the surrogate needs (paper Sec. 4.1: the
+ * (M^-1)_{ij}^2 factors).  Tinv[nb][k][k] = T^-1 per block (Gauss-Jordan with partial
+ * pivoting, float64 internally).  rho_row[nb*k] / rho_col[nb*k] (either may be NULL):
+ * squared row / column norms of Tinv.  status[nb] (may be NULL): 0 ok, 1 singular to
+ * working precision (Tinv of that block is then unspecified).  k <= 256. */
+int cafeq_block_inverse(const float* T, int k, int nb, float* Tinv, float* rho_row,
+                        float* rho_col, int* status, void* stream);
+
+/* Plain per-group round-to-nearest of W (paper Eq. (1)'s rounding rule on the symmetric
+ * grid above; no transform).  codes[rows][cols], scales (layout above); err_sq[1]
+ * (may be NULL) receives sum (dequant - w)^2.  Any group size dividing the line. */
+int cafeq_rtn_quantize(const cafeq_mat* W, const cafeq_quant_cfg* cfg, int8_t* codes,
+                       float* scales, float* err_sq, void* ws, void* stream);
+
+/* Z = W.blockdiag(X) or blockdiag(X).W with X = T (CAFEQ_SIDE_T) or Tinv
+ * (CAFEQ_SIDE_TINV)  (paper Sec. 4.1 block-diagonal M; Sec. 4.2 U = W1 M, V = M^-1 W2).
+ * Z: float32 [rows][cols] dense, must not alias W. */
+int cafeq_apply_transform(const cafeq_mat* W, const cafeq_xform* x, int axis, int side,
+                          float* Z, void* stream);
+
+/* One evaluation for a single matrix (paper Sec. 4 and 4.1), transform along cfg->axis:
+ *   Z = transform(W, T); Zq = dequant(Q(Z)); E = Zq - Z; D = transform(E, Tinv)
+ *   losses[0] = ||D||_F^2   (= ||M^-1 Q(MW) - W||_F^2, the l2 proxy)
+ *   losses[1] = ||E||_F^2
+ *   losses[2] = ||W||_F^2
+ *   losses[3] = L_sur = beta * sum_G a_G^2 * sum_{j in G} rho_j, beta = 1/(4 qmax^2):
+ *               the stochastic-rounding upper bound gradient descent runs on, written
+ *               for per-group scales (a_G: group absmax of Z, rho_j: squared norm of the
+ *               row (AXIS_COL) / column (AXIS_ROW) j of Tinv)
+ *   gradT[nb][k][k] (may be NULL: forward only) = d L_sur / d T with Tinv = T^-1,
+ *               absmax differentiated at its arg-max element.
+ *   codes / scales (may be NULL): Q(Z) as in cafeq_rtn_quantize.
+ * group must satisfy max(group, k) <= 256 and divide / be divided by k. */
+int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x,
+                             const cafeq_quant_cfg* cfg, float* losses, float* gradT,
+                             int8_t* codes, float* scales, void* ws, void* stream);
+
+/* One evaluation for a coupled pair (paper Sec. 4.2): A [d1][nb*k] gets T on its columns
+ * (U = A T), B [nb*rep*k][d3] gets Tinv on its rows (V = Tinv B).  cfg->axis is ignored
+ * (A is quantized along its columns, B along its rows).
+ *   losses[0] = ||Q(U)-U||_F^2      losses[1] = ||Q(V)-V||_F^2
+ *   losses[2] = ||Q(U) Tinv - A||_F^2   losses[3] = ||T Q(V) - B||_F^2
+ *   losses[4] = LSE = (1/t) log( sum over every group G of U and of V of exp(t a_G) )
+ *   losses[5] = number of groups (as float)
+ *   gradT[nb][k][k] (may be NULL) = d LSE / d T.
+ * codesU/scalesU/codesV/scalesV (may be NULL): Q(U), Q(V). */
+int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B,
+                                  const cafeq_xform* x, const cafeq_quant_cfg* cfg,
+                                  float lse_t, float* losses, float* gradT,
+                                  int8_t* codesU, float* scalesU, int8_t* codesV,
+                                  float* scalesV, void* ws, void* stream);
+
+/* One iteration of Alg. 1 in transformed coordinates (W1 := U [rowsA][nb*k], float32,
+ * W2 := V [nb*rep*k][colsB], float32), per head b (column block b of U, row-blocks
+ * q with q / rep == b of V), the pseudoinverse formed from k x k normal equations:
+ *   half 0 or 1 (line 3):  Vq <- Q( (Uq^T Uq)^-1 Uq^T U_b . V_q )
+ *   half 0 or 2 (line 4):  Uq_b <- Q( U_b . (V_[b] Vq_[b]^T)(Vq_[b] Vq_[b]^T)^-1 )
+ * where Uq / Vq are the dequantized current codes (in/out: codesU, scalesU, codesV,
+ * scalesV; U groups along columns, V groups along rows).  status[2*nb] (may be NULL):
+ * per head and line, 0 ok, 1 the Gram matrix was not positive definite to working
+ * precision (that head's codes are then left unchanged by that line). */
+int cafeq_adaptive_round_step(const float* U, const float* V, int64_t rowsA, int64_t colsA,
+                              int64_t rowsB, int64_t colsB, const cafeq_quant_cfg* cfg,
+                              int k, int nb, int rep, int half, int8_t* codesU,
+                              float* scalesU, int8_t* codesV, float* scalesV, int* status,
+                              void* ws, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CAFEQ_H */

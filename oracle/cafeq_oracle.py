@@ -98,7 +98,7 @@ def rtn_sym(Z, bits, group, axis, arith="f32"):
     zhat = q * s, with qmax = 2^(b-1) - 1, qmin = -2^(b-1); ties to even.
     ``arith="f64"`` evaluates exactly that in float64.  ``arith="f32"`` is the
     single-precision realisation both sides agree on for deciding the integer:
-    z is rounded to float32, inv = fl(qmax / a), q = nearest_int(fl(z * inv)),
+    z is rounded to float32, inv = min(fl(qmax / a), FLT_MAX), q = nearest_int(fl(z * inv)),
     s = fl(a / qmax), zhat = fl(q * s).  An all-zero group gives s = 0, q = 0.
 
     Returns (codes int8 [R][C], scales [groups layout], zhat [R][C] float64).
@@ -110,7 +110,9 @@ def rtn_sym(Z, bits, group, axis, arith="f32"):
     a = np.max(np.abs(Zg), axis=1)                      # [groups]
     safe = np.where(a > 0, a, ft(1))
     if arith == "f32":
-        inv = (ft(qmax) / safe).astype(ft)
+        with np.errstate(over="ignore"):
+            # capped so that a denormal absmax cannot produce inf (and 0 * inf = nan)
+            inv = np.minimum((ft(qmax) / safe).astype(ft), np.finfo(np.float32).max)
         x = (Zg * inv[:, None]).astype(ft)
     else:
         x = Zg / (safe / qmax)[:, None]

@@ -1,0 +1,148 @@
+"""ctypes binding of libcafeq.so: argument marshalling only.
+
+Every function takes torch CUDA tensors (used purely as device memory), builds the
+C descriptors of include/cafeq.h and enqueues the call on torch's current stream.
+There is no fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcafeq.so")
+
+AXIS_COL, AXIS_ROW = 0, 1
+SIDE_T, SIDE_TINV = 0, 1
+F32, BF16 = 0, 1
+CALL_RTN, CALL_PROXY, CALL_DUAL, CALL_ADAPTIVE = 0, 1, 2, 3
+
+EXPORTS = (
+    "cafeq_strerror", "cafeq_version", "cafeq_workspace_bytes", "cafeq_block_inverse",
+    "cafeq_rtn_quantize", "cafeq_apply_transform", "cafeq_proxy_loss_fwd_bwd",
+    "cafeq_dual_proxy_loss_fwd_bwd", "cafeq_adaptive_round_step",
+)
+
+
+class CafeqError(RuntimeError):
+    pass
+
+
+class Mat(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("ld", ctypes.c_int64), ("dtype", ctypes.c_int32)]
+
+
+class Xform(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_void_p), ("Tinv", ctypes.c_void_p), ("k", ctypes.c_int32),
+                ("nb", ctypes.c_int32), ("rep", ctypes.c_int32)]
+
+
+class QuantCfg(ctypes.Structure):
+    _fields_ = [("bits", ctypes.c_int32), ("group", ctypes.c_int32), ("axis", ctypes.c_int32),
+                ("mode", ctypes.c_int32)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise CafeqError("libcafeq.so has not been built (run `python __graft_entry__.py`): " + LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    missing = [n for n in EXPORTS if not hasattr(lib, n)]
+    if missing:
+        raise CafeqError("libcafeq.so lacks exports: %s" % missing)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+    lib.cafeq_strerror.restype = ctypes.c_char_p
+    lib.cafeq_strerror.argtypes = [i32]
+    lib.cafeq_version.restype = i32
+    lib.cafeq_workspace_bytes.restype = ctypes.c_size_t
+    lib.cafeq_workspace_bytes.argtypes = [i32, ctypes.POINTER(Mat), ctypes.POINTER(Mat),
+                                          ctypes.POINTER(Xform), ctypes.POINTER(QuantCfg)]
+    lib.cafeq_block_inverse.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
+    lib.cafeq_rtn_quantize.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(QuantCfg), vp, vp, vp, vp, vp]
+    lib.cafeq_apply_transform.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Xform), i32, i32, vp, vp]
+    lib.cafeq_proxy_loss_fwd_bwd.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Xform),
+                                             ctypes.POINTER(QuantCfg), vp, vp, vp, vp, vp, vp]
+    lib.cafeq_dual_proxy_loss_fwd_bwd.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Mat),
+                                                  ctypes.POINTER(Xform), ctypes.POINTER(QuantCfg),
+                                                  ctypes.c_float, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.cafeq_adaptive_round_step.argtypes = [vp, vp, i64, i64, i64, i64, ctypes.POINTER(QuantCfg),
+                                              i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    for n in EXPORTS[3:]:
+        getattr(lib, n).restype = i32
+    return lib
+
+
+lib = _load()
+
+
+def _check(rc):
+    if rc != 0:
+        raise CafeqError("cafeq call failed: %s (%d)" % (lib.cafeq_strerror(rc).decode(), rc))
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def mat(t):
+    """Descriptor of a 2-D CUDA tensor (float32 or bfloat16, unit column stride)."""
+    if t.dim() != 2 or t.stride(1) != 1 or not t.is_cuda:
+        raise CafeqError("need a 2-D CUDA tensor with unit column stride")
+    if t.dtype == torch.float32:
+        dt = F32
+    elif t.dtype == torch.bfloat16:
+        dt = BF16
+    else:
+        raise CafeqError("dtype must be float32 or bfloat16")
+    return Mat(t.data_ptr(), t.shape[0], t.shape[1], t.stride(0), dt)
+
+
+def xform(T, Tinv, rep=1):
+    for x in (T, Tinv):
+        if x is not None and (x.dtype != torch.float32 or not x.is_contiguous() or x.dim() != 3):
+            raise CafeqError("transform blocks must be contiguous float32 [nb][k][k]")
+    return Xform(_ptr(T), _ptr(Tinv), T.shape[1], T.shape[0], rep)
+
+
+_ws_cache = {}
+
+
+def workspace(nbytes, device):
+    """A cached scratch buffer (device memory owned by the binding, grown on demand)."""
+    key = (device.type, device.index)
+    buf = _ws_cache.get(key)
+    if buf is None or buf.numel() < nbytes:
+        buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+        _ws_cache[key] = buf
+    return buf
+
+
+def workspace_bytes(call_id, a, b=None, x=None, cfg=None):
+    return int(lib.cafeq_workspace_bytes(call_id, ctypes.byref(a), ctypes.byref(b) if b else None,
+                                         ctypes.byref(x) if x else None,
+                                         ctypes.byref(cfg) if cfg else None))
+
+
+def _scale_shape(rows, cols, group, axis):
+    if axis == AXIS_COL:
+        return (rows, cols // (group or cols))
+    return (rows // (group or rows), cols)
+
+
+def rtn_quantize(W, bits, group, axis=AXIS_COL, want_err=False):
+    m = mat(W)
+    cfg = QuantCfg(bits, group, axis, 0)
+    R, C = W.shape
+    codes = torch.empty((R, C), dtype=torch.int8, device=W.device)
+    scales = torch.empty(_scale_shape(R, C, group, axis), dtype=torch.float32, device=W.device)
+    err = torch.empty(1, dtype=torch.float32, device=W.device) if want_err else None
+    ws = workspace(workspace_bytes(CALL_RTN, m, cfg=cfg), W.device) if want_err else None
+    _check(lib.cafeq_rtn_quantize(ctypes.byref(m), ctypes.byref(cfg), _ptr(codes), _ptr(scales),
+                                  _ptr(err), _ptr(ws), _stream()))
+    return codes, scales, err
