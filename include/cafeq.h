@@ -93,7 +93,8 @@ typedef enum {
   CAFEQ_CALL_RTN_QUANTIZE = 0,
   CAFEQ_CALL_PROXY_LOSS = 1,
   CAFEQ_CALL_DUAL_PROXY_LOSS = 2,
-  CAFEQ_CALL_ADAPTIVE_ROUND = 3
+  CAFEQ_CALL_ADAPTIVE_ROUND = 3,
+  CAFEQ_CALL_BLOCK_INVERSE = 4 /* reads x->k and x->nb only */
 } cafeq_call_id;
 
 const char* cafeq_strerror(int status);
@@ -112,7 +113,7 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
  * squared row / column norms of Tinv.  status[nb] (may be NULL): 0 ok, 1 singular to
  * working precision (Tinv of that block is then unspecified).  k <= 256. */
 int cafeq_block_inverse(const float* T, int k, int nb, float* Tinv, float* rho_row,
-                        float* rho_col, int* status, void* stream);
+                        float* rho_col, int* status, void* ws, void* stream);
 
 /* Plain per-group round-to-nearest of W (paper Eq. (1)'s rounding rule on the symmetric
  * grid above; no transform).  codes[rows][cols], scales (layout above); err_sq[1]

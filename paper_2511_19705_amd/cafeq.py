@@ -59,7 +59,7 @@ def _load():
     lib.cafeq_workspace_bytes.restype = ctypes.c_size_t
     lib.cafeq_workspace_bytes.argtypes = [i32, ctypes.POINTER(Mat), ctypes.POINTER(Mat),
                                           ctypes.POINTER(Xform), ctypes.POINTER(QuantCfg)]
-    lib.cafeq_block_inverse.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
+    lib.cafeq_block_inverse.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.cafeq_rtn_quantize.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(QuantCfg), vp, vp, vp, vp, vp]
     lib.cafeq_apply_transform.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Xform), i32, i32, vp, vp]
     lib.cafeq_proxy_loss_fwd_bwd.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Xform),
@@ -146,3 +146,72 @@ def rtn_quantize(W, bits, group, axis=AXIS_COL, want_err=False):
     _check(lib.cafeq_rtn_quantize(ctypes.byref(m), ctypes.byref(cfg), _ptr(codes), _ptr(scales),
                                   _ptr(err), _ptr(ws), _stream()))
     return codes, scales, err
+
+
+def block_inverse(T, want_rho=False):
+    """Tinv (and optionally rho_row, rho_col) plus per-block status."""
+    nb, k, _ = T.shape
+    dev = T.device
+    Tinv = torch.empty_like(T)
+    rr = torch.empty(nb * k, dtype=torch.float32, device=dev) if want_rho else None
+    rc_ = torch.empty(nb * k, dtype=torch.float32, device=dev) if want_rho else None
+    status = torch.empty(nb, dtype=torch.int32, device=dev)
+    x = Xform(_ptr(T), 0, k, nb, 1)
+    ws = workspace(int(lib.cafeq_workspace_bytes(4, None, None, ctypes.byref(x), None)), dev)
+    _check(lib.cafeq_block_inverse(_ptr(T), k, nb, _ptr(Tinv), _ptr(rr), _ptr(rc_), _ptr(status),
+                                   _ptr(ws), _stream()))
+    return (Tinv, rr, rc_, status) if want_rho else (Tinv, status)
+
+
+def apply_transform(W, T, Tinv=None, axis=AXIS_COL, side=SIDE_T, rep=1):
+    m = mat(W)
+    x = xform(T, Tinv, rep)
+    Z = torch.empty(W.shape, dtype=torch.float32, device=W.device)
+    _check(lib.cafeq_apply_transform(ctypes.byref(m), ctypes.byref(x), axis, side, _ptr(Z), _stream()))
+    return Z
+
+
+def proxy_loss_fwd_bwd(W, T, Tinv, bits, group, axis=AXIS_COL, rep=1, want_grad=True, want_codes=False):
+    """Returns (losses[4], gradT or None, codes or None, scales or None)."""
+    m = mat(W)
+    x = xform(T, Tinv, rep)
+    cfg = QuantCfg(bits, group, axis, 0)
+    dev = W.device
+    losses = torch.empty(4, dtype=torch.float32, device=dev)
+    grad = torch.empty_like(T) if want_grad else None
+    R, C = W.shape
+    codes = torch.empty((R, C), dtype=torch.int8, device=dev) if want_codes else None
+    scales = torch.empty(_scale_shape(R, C, group, axis), dtype=torch.float32, device=dev) if want_codes else None
+    nbytes = workspace_bytes(CALL_PROXY, m, x=x, cfg=cfg)
+    if nbytes == 0:
+        raise CafeqError("unsupported proxy-loss configuration (workspace query returned 0)")
+    ws = workspace(nbytes, dev)
+    _check(lib.cafeq_proxy_loss_fwd_bwd(ctypes.byref(m), ctypes.byref(x), ctypes.byref(cfg), _ptr(losses),
+                                        _ptr(grad), _ptr(codes), _ptr(scales), _ptr(ws), _stream()))
+    return losses, grad, codes, scales
+
+
+def dual_proxy_loss_fwd_bwd(A, B, T, Tinv, bits, group, rep=1, lse_t=5.0, want_grad=True, want_codes=False):
+    """Returns (losses[6], gradT or None, (codesU, scalesU, codesV, scalesV) or None)."""
+    ma, mb = mat(A), mat(B)
+    x = xform(T, Tinv, rep)
+    cfg = QuantCfg(bits, group, 0, 0)
+    dev = A.device
+    losses = torch.empty(6, dtype=torch.float32, device=dev)
+    grad = torch.empty_like(T) if want_grad else None
+    outs = None
+    cu = su = cv = sv = None
+    if want_codes:
+        cu = torch.empty(A.shape, dtype=torch.int8, device=dev)
+        su = torch.empty(_scale_shape(A.shape[0], A.shape[1], group, AXIS_COL), dtype=torch.float32, device=dev)
+        cv = torch.empty(B.shape, dtype=torch.int8, device=dev)
+        sv = torch.empty(_scale_shape(B.shape[0], B.shape[1], group, AXIS_ROW), dtype=torch.float32, device=dev)
+        outs = (cu, su, cv, sv)
+    nbytes = workspace_bytes(CALL_DUAL, ma, mb, x, cfg)
+    if nbytes == 0:
+        raise CafeqError("unsupported dual configuration (workspace query returned 0)")
+    ws = workspace(nbytes, dev)
+    _check(lib.cafeq_dual_proxy_loss_fwd_bwd(ctypes.byref(ma), ctypes.byref(mb), ctypes.byref(x),
+                                             ctypes.byref(cfg), ctypes.c_float(lse_t), _ptr(losses), _ptr(grad),
+                                             _ptr(cu), _ptr(su), _ptr(cv), _ptr(sv), _ptr(ws), _stream()))
+    return losses, grad, outs

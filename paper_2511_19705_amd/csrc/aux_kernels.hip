@@ -1,0 +1,451 @@
+// Small kernels around the fused core: squared norms of the inverse transform (the
+// (M^-1)_{ij}^2 factors of the paper's surrogate, Sec. 4.1), fixed-order reduction of the
+// per-workgroup partials, the k x k products of the gradient's path through M^-1, and the
+// blockwise inverse.  All are off the bandwidth path (k x k sized per block).
+#include "xform_core.hpp"
+
+namespace cafeq {
+
+namespace {
+
+// rho[b*K + j]: squared norm of row j (by_row) or column j of P_b.
+__global__ __launch_bounds__(256) void rho_kernel(const float* __restrict__ P, int K, int by_row,
+                                                   float* __restrict__ rho) {
+  const float* Pb = P + size_t(blockIdx.x) * K * K;
+  for (int j = threadIdx.x; j < K; j += blockDim.x) {
+    double acc = 0;
+    for (int i = 0; i < K; ++i) {
+      const float v = by_row ? Pb[j * K + i] : Pb[i * K + j];
+      acc += double(v) * v;
+    }
+    rho[size_t(blockIdx.x) * K + j] = float(acc);
+  }
+}
+
+// rG[gi] = sum of rho over the axis indices of group gi (axis index a -> block (a/K)/rep, a%K).
+__global__ __launch_bounds__(256) void rho_group_kernel(const float* __restrict__ rho, int K, int rep,
+                                                         int G, int64_t ngroups, float* __restrict__ rG) {
+  const int64_t gi = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (gi >= ngroups) return;
+  double acc = 0;
+  for (int e = 0; e < G; ++e) {
+    const int64_t a = gi * G + e;
+    acc += rho[((a / K) / rep) * K + a % K];
+  }
+  rG[gi] = float(acc);
+}
+
+// ---------------------------------------------------------------------------------------
+// reduction of the per-(workgroup, segment) partials
+// ---------------------------------------------------------------------------------------
+// workgroups whose chunk of macro-tiles intersects segment `seg`: [lo, hi)
+__device__ void seg_wg_range(int64_t seg, int64_t mt_per_seg, int64_t n_mt, int nwg, int* lo, int* hi) {
+  const int64_t t0 = seg * mt_per_seg, t1 = t0 + mt_per_seg;
+  int a = int((t0 * nwg) / n_mt);
+  while (a > 0 && chunk_begin(a, n_mt, nwg) > t0) --a;
+  while (a + 1 < nwg && chunk_begin(a + 1, n_mt, nwg) <= t0) ++a;
+  int b = a;
+  while (b < nwg && chunk_begin(b, n_mt, nwg) < t1) ++b;
+  *lo = a;
+  *hi = b;
+}
+
+struct ReduceArgs {
+  const float* slot_grad;
+  const float* slot_hdr;
+  int64_t mt_per_seg, n_mt;
+  int nwg, nseg;
+  int K, NBLK, NGRP, G, rep;
+  int transpose_out;     // 1: out[m][j] = acc[j][m]
+  float t;               // kLossLse: temperature; scale of a partial = exp(t (m_ref - m*)) / S
+  const double* lse_ms;  // kLossLse: [0] = m*, [1] = S  (null for kLossSur)
+  float* out;            // [nb][K][K]
+};
+
+// grid: nb transform blocks.  out_b = sum over the rep row-blocks q of block b, and over the
+// partials of q's segment, in fixed order.
+__global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceArgs a) {
+  const int b = blockIdx.x;
+  const int K = a.K;
+  for (int i = threadIdx.x; i < K * K; i += blockDim.x) {
+    float acc = 0.f;
+    for (int q = b * a.rep; q < (b + 1) * a.rep; ++q) {
+      const int seg = q / a.NBLK, blk = q % a.NBLK;
+      int lo, hi;
+      seg_wg_range(seg, a.mt_per_seg, a.n_mt, a.nwg, &lo, &hi);
+      for (int w = lo; w < hi; ++w) {
+        const int64_t slot = int64_t(w) + seg;
+        float sc = 1.f;
+        if (a.lse_ms) {
+          const float mref = a.slot_hdr[slot * kHdrFloats + kHdrMref];
+          sc = float(exp(double(a.t) * (double(mref) - a.lse_ms[0])) / a.lse_ms[1]);
+        }
+        acc += sc * a.slot_grad[slot * int64_t(a.NBLK) * K * K + int64_t(blk) * K * K + i];
+      }
+    }
+    const int r = i / K, c = i % K;
+    a.out[size_t(b) * K * K + (a.transpose_out ? c * K + r : i)] = acc;
+  }
+}
+
+// v[axis index] = beta * sum over partials of the group's sum a^2, expanded per index, then
+// Mmid_b = diag(v_b) P_b (scale_rows) or P_b diag(v_b).  For AXIS_ROW with rep > 1 the rep
+// row-blocks of a transform block add up.   grid: nb transform blocks.
+struct VArgs {
+  const float* slot_hdr;
+  int64_t mt_per_seg, n_mt;
+  int nwg;
+  int K, L, G, rep;
+  float beta;
+  const float* P;
+  int scale_rows;
+  float* Mmid;
+};
+__global__ __launch_bounds__(256) void build_mmid_kernel(const VArgs a) {
+  __shared__ float v[256];
+  const int b = blockIdx.x, K = a.K;
+  for (int n = threadIdx.x; n < K; n += blockDim.x) {
+    double acc = 0;
+    for (int q = b * a.rep; q < (b + 1) * a.rep; ++q) {
+      const int64_t ax = int64_t(q) * K + n;        // axis index
+      const int64_t seg = ax / a.L;
+      const int gi = int((ax % a.L) / a.G);
+      int lo, hi;
+      seg_wg_range(seg, a.mt_per_seg, a.n_mt, a.nwg, &lo, &hi);
+      for (int w = lo; w < hi; ++w) acc += a.slot_hdr[(int64_t(w) + seg) * kHdrFloats + kHdrVa2 + gi];
+    }
+    v[n] = float(acc * a.beta);
+  }
+  __syncthreads();
+  const float* Pb = a.P + size_t(b) * K * K;
+  float* Mb = a.Mmid + size_t(b) * K * K;
+  for (int i = threadIdx.x; i < K * K; i += blockDim.x) Mb[i] = Pb[i] * (a.scale_rows ? v[i / K] : v[i % K]);
+}
+
+// losses: fixed-order float64 sums over every partial header.
+struct LossArgs {
+  const float* hdrA; int nslotA;     // member A (or the single matrix)
+  const float* hdrB; int nslotB;     // member B (dual only)
+  int kind; float beta, t;
+  int64_t ngroups;
+  float* losses;
+  double* lse_ms;                    // out: [m*, S]
+};
+__device__ double block_sum(double v, double* red) {
+  red[threadIdx.x] = v;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  const double r = red[0];
+  __syncthreads();
+  return r;
+}
+__device__ double block_max(double v, double* red) {
+  red[threadIdx.x] = v;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (threadIdx.x < s) red[threadIdx.x] = fmax(red[threadIdx.x], red[threadIdx.x + s]);
+    __syncthreads();
+  }
+  const double r = red[0];
+  __syncthreads();
+  return r;
+}
+__device__ double hdr_sum(const float* hdr, int n, int field, double* red) {
+  double t = 0;
+  for (int i = threadIdx.x; i < n; i += 256) t += hdr[size_t(i) * kHdrFloats + field];
+  return block_sum(t, red);
+}
+__global__ __launch_bounds__(256) void reduce_losses_kernel(const LossArgs a) {
+  __shared__ double red[256];
+  if (a.kind == kLossSur) {
+    const double l2 = hdr_sum(a.hdrA, a.nslotA, kHdrL2, red);
+    const double ez = hdr_sum(a.hdrA, a.nslotA, kHdrErrZ, red);
+    const double ws = hdr_sum(a.hdrA, a.nslotA, kHdrWsq, red);
+    const double su = hdr_sum(a.hdrA, a.nslotA, kHdrSur, red);
+    if (threadIdx.x == 0) {
+      a.losses[0] = float(l2); a.losses[1] = float(ez); a.losses[2] = float(ws);
+      a.losses[3] = float(su * a.beta);
+    }
+    return;
+  }
+  const double ezA = hdr_sum(a.hdrA, a.nslotA, kHdrErrZ, red);
+  const double ezB = hdr_sum(a.hdrB, a.nslotB, kHdrErrZ, red);
+  const double l2A = hdr_sum(a.hdrA, a.nslotA, kHdrL2, red);
+  const double l2B = hdr_sum(a.hdrB, a.nslotB, kHdrL2, red);
+  // global reference and normaliser of the exponentials
+  double m = -INFINITY;
+  for (int i = threadIdx.x; i < a.nslotA; i += 256) m = fmax(m, double(a.hdrA[size_t(i) * kHdrFloats + kHdrMref]));
+  for (int i = threadIdx.x; i < a.nslotB; i += 256) m = fmax(m, double(a.hdrB[size_t(i) * kHdrFloats + kHdrMref]));
+  m = block_max(m, red);
+  double s = 0;
+  for (int i = threadIdx.x; i < a.nslotA; i += 256) {
+    const float* h = a.hdrA + size_t(i) * kHdrFloats;
+    if (h[kHdrSur] > 0.f) s += double(h[kHdrSur]) * exp(double(a.t) * (double(h[kHdrMref]) - m));
+  }
+  for (int i = threadIdx.x; i < a.nslotB; i += 256) {
+    const float* h = a.hdrB + size_t(i) * kHdrFloats;
+    if (h[kHdrSur] > 0.f) s += double(h[kHdrSur]) * exp(double(a.t) * (double(h[kHdrMref]) - m));
+  }
+  s = block_sum(s, red);
+  if (threadIdx.x == 0) {
+    a.losses[0] = float(ezA); a.losses[1] = float(ezB); a.losses[2] = float(l2A); a.losses[3] = float(l2B);
+    a.losses[4] = float(m + log(s) / double(a.t));
+    a.losses[5] = float(a.ngroups);
+    a.lse_ms[0] = m; a.lse_ms[1] = s;
+  }
+}
+
+// Partial headers that were never written (slots no workgroup owns) must read as empty.
+__global__ __launch_bounds__(256) void init_hdr_kernel(float* hdr, int64_t nslot) {
+  const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i >= nslot * kHdrFloats) return;
+  hdr[i] = (i % kHdrFloats) == kHdrMref ? -INFINITY : 0.f;
+}
+
+// ---------------------------------------------------------------------------------------
+// batched k x k product  C_b = alpha * op(A_b) op(B_b) + beta * C_b   (64 x 64 tile / workgroup)
+// ---------------------------------------------------------------------------------------
+template <bool TA, bool TB>
+__global__ __launch_bounds__(256) void bgemm_kernel(const float* __restrict__ A, const float* __restrict__ B,
+                                                     float* __restrict__ C, int K, float alpha, float beta) {
+  __shared__ float sa[16][68];   // [l][i]
+  __shared__ float sb[16][68];   // [l][j]
+  const int tpr = K / 64;
+  const int b = blockIdx.x / (tpr * tpr), tile = blockIdx.x % (tpr * tpr);
+  const int i0 = (tile / tpr) * 64, j0 = (tile % tpr) * 64;
+  const float* Ab = A + size_t(b) * K * K;
+  const float* Bb = B + size_t(b) * K * K;
+  float* Cb = C + size_t(b) * K * K;
+  const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+  float acc[4][4] = {};
+  for (int l0 = 0; l0 < K; l0 += 16) {
+    for (int e = threadIdx.x; e < 16 * 64; e += 256) {
+      const int l = e / 64, i = e % 64;
+      sa[l][i] = TA ? Ab[(l0 + l) * K + i0 + i] : Ab[(i0 + i) * K + l0 + l];
+      sb[l][i] = TB ? Bb[(j0 + i) * K + l0 + l] : Bb[(l0 + l) * K + j0 + i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int l = 0; l < 16; ++l) {
+      float av[4], bv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { av[u] = sa[l][ty * 4 + u]; bv[u] = sb[l][tx * 4 + u]; }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[u][v] = fmaf(av[u], bv[v], acc[u][v]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      float* dst = Cb + (i0 + ty * 4 + u) * K + j0 + tx * 4 + v;
+      *dst = alpha * acc[u][v] + (beta != 0.f ? beta * *dst : 0.f);
+    }
+}
+
+// K == 32: one 32 x 32 tile per workgroup, thread per output element group
+template <bool TA, bool TB>
+__global__ __launch_bounds__(256) void bgemm32_kernel(const float* __restrict__ A, const float* __restrict__ B,
+                                                       float* __restrict__ C, float alpha, float beta) {
+  constexpr int K = 32;
+  __shared__ float sa[K][K + 1], sb[K][K + 1];
+  const float* Ab = A + size_t(blockIdx.x) * K * K;
+  const float* Bb = B + size_t(blockIdx.x) * K * K;
+  float* Cb = C + size_t(blockIdx.x) * K * K;
+  for (int e = threadIdx.x; e < K * K; e += 256) {
+    const int r = e / K, c = e % K;
+    sa[r][c] = TA ? Ab[c * K + r] : Ab[e];   // sa[i][l]
+    sb[r][c] = TB ? Bb[c * K + r] : Bb[e];   // sb[l][j]
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < K * K; e += 256) {
+    const int i = e / K, j = e % K;
+    float acc = 0.f;
+#pragma unroll
+    for (int l = 0; l < K; ++l) acc = fmaf(sa[i][l], sb[l][j], acc);
+    Cb[e] = alpha * acc + (beta != 0.f ? beta * Cb[e] : 0.f);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// blockwise inverse: Gauss-Jordan with partial pivoting in float64, one workgroup per block,
+// working copy [K][2K] (A | I) in the caller's workspace.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void block_inverse_kernel(const float* __restrict__ T, int K,
+                                                              double* __restrict__ work, float* __restrict__ Tinv,
+                                                              float* __restrict__ rho_row, float* __restrict__ rho_col,
+                                                              int* __restrict__ status) {
+  __shared__ double pv_val[1024];
+  __shared__ int pv_idx[1024];
+  __shared__ double prow[512];
+  __shared__ double colk[256];
+  __shared__ int singular;
+  const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
+  const int W2 = 2 * K;
+  double* M = work + size_t(b) * K * W2;
+  const float* Tb = T + size_t(b) * K * K;
+  double anorm = 0;
+  for (int e = tid; e < K * W2; e += nt) {
+    const int r = e / W2, c = e % W2;
+    const double v = c < K ? double(Tb[r * K + c]) : (c - K == r ? 1.0 : 0.0);
+    M[e] = v;
+    if (c < K) anorm = fmax(anorm, fabs(v));
+  }
+  pv_val[tid] = anorm;
+  if (tid == 0) singular = 0;
+  __syncthreads();
+  for (int s = nt / 2; s > 0; s >>= 1) {
+    if (tid < s) pv_val[tid] = fmax(pv_val[tid], pv_val[tid + s]);
+    __syncthreads();
+  }
+  anorm = pv_val[0];
+  __syncthreads();
+  for (int k = 0; k < K; ++k) {
+    // pivot search in column k, rows k..K-1
+    double best = -1.0;
+    int bi = k;
+    for (int r = k + tid; r < K; r += nt) {
+      const double v = fabs(M[r * W2 + k]);
+      if (v > best) { best = v; bi = r; }
+    }
+    pv_val[tid] = best; pv_idx[tid] = bi;
+    __syncthreads();
+    for (int s = nt / 2; s > 0; s >>= 1) {
+      if (tid < s) {
+        if (pv_val[tid + s] > pv_val[tid] || (pv_val[tid + s] == pv_val[tid] && pv_idx[tid + s] < pv_idx[tid])) {
+          pv_val[tid] = pv_val[tid + s]; pv_idx[tid] = pv_idx[tid + s];
+        }
+      }
+      __syncthreads();
+    }
+    const int p = pv_idx[0];
+    const double pval = pv_val[0];
+    __syncthreads();
+    if (!(pval > anorm * 1e-13)) {
+      if (tid == 0) singular = 1;
+      __syncthreads();
+      break;
+    }
+    // swap rows p and k, normalise the pivot row into shared memory
+    const double piv = M[p * W2 + k];
+    for (int c = tid; c < W2; c += nt) {
+      const double vp = M[p * W2 + c], vk = M[k * W2 + c];
+      prow[c] = vp / piv;
+      if (p != k) M[p * W2 + c] = vk;
+    }
+    __syncthreads();
+    for (int r = tid; r < K; r += nt) colk[r] = (r == k) ? 0.0 : M[r * W2 + k];
+    __syncthreads();
+    for (int e = tid; e < K * W2; e += nt) {
+      const int r = e / W2, c = e % W2;
+      M[e] = (r == k) ? prow[c] : M[e] - colk[r] * prow[c];
+    }
+    __syncthreads();
+  }
+  if (status && tid == 0) status[b] = singular;
+  float* Pb = Tinv + size_t(b) * K * K;
+  for (int e = tid; e < K * K; e += nt) Pb[e] = float(M[(e / K) * W2 + K + e % K]);
+  __syncthreads();
+  for (int j = tid; j < K; j += nt) {
+    double rr = 0, cc = 0;
+    for (int i = 0; i < K; ++i) {
+      const double a = M[j * W2 + K + i], c = M[i * W2 + K + j];
+      rr += a * a; cc += c * c;
+    }
+    if (rho_row) rho_row[size_t(b) * K + j] = float(rr);
+    if (rho_col) rho_col[size_t(b) * K + j] = float(cc);
+  }
+}
+
+}  // namespace
+
+int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_t st) {
+  hipLaunchKernelGGL(rho_kernel, dim3(nb), dim3(256), 0, st, P, K, by_row, rho);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+int launch_rho_groups(const float* rho, int K, int rep, int G, int64_t ngroups, float* rG, hipStream_t st) {
+  hipLaunchKernelGGL(rho_group_kernel, dim3(unsigned((ngroups + 255) / 256)), dim3(256), 0, st, rho, K, rep, G,
+                     ngroups, rG);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+int launch_init_hdr(float* hdr, int64_t nslot, hipStream_t st) {
+  const int64_t n = nslot * kHdrFloats;
+  hipLaunchKernelGGL(init_hdr_kernel, dim3(unsigned((n + 255) / 256)), dim3(256), 0, st, hdr, nslot);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+int launch_reduce_grad(const CoreParams& p, int K, int G, int nb, int transpose_out, const double* lse_ms,
+                       float* out, hipStream_t st) {
+  ReduceArgs a;
+  const int L = K > G ? K : G;
+  a.slot_grad = p.slot_grad; a.slot_hdr = p.slot_hdr; a.mt_per_seg = p.mt_per_seg; a.n_mt = p.n_mt;
+  a.nwg = p.nwg; a.nseg = p.nseg; a.K = K; a.NBLK = L / K; a.NGRP = L / G; a.G = G; a.rep = p.rep;
+  a.transpose_out = transpose_out; a.t = p.lse_t; a.lse_ms = lse_ms; a.out = out;
+  hipLaunchKernelGGL(reduce_grad_kernel, dim3(nb), dim3(256), 0, st, a);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+int launch_build_mmid(const CoreParams& p, int K, int G, int nb, const float* P, int scale_rows, float* Mmid,
+                      hipStream_t st) {
+  VArgs a;
+  a.slot_hdr = p.slot_hdr; a.mt_per_seg = p.mt_per_seg; a.n_mt = p.n_mt; a.nwg = p.nwg;
+  a.K = K; a.L = K > G ? K : G; a.G = G; a.rep = p.rep; a.beta = p.beta; a.P = P;
+  a.scale_rows = scale_rows; a.Mmid = Mmid;
+  hipLaunchKernelGGL(build_mmid_kernel, dim3(nb), dim3(256), 0, st, a);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+int launch_reduce_losses(int kind, const float* hdrA, int nslotA, const float* hdrB, int nslotB, float beta,
+                         float t, int64_t ngroups, float* losses, double* lse_ms, hipStream_t st) {
+  LossArgs a;
+  a.hdrA = hdrA; a.nslotA = nslotA; a.hdrB = hdrB; a.nslotB = nslotB; a.kind = kind; a.beta = beta; a.t = t;
+  a.ngroups = ngroups; a.losses = losses; a.lse_ms = lse_ms;
+  hipLaunchKernelGGL(reduce_losses_kernel, dim3(1), dim3(256), 0, st, a);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+int launch_bgemm(bool ta, bool tb, const float* A, const float* B, float* C, int K, int nb, float alpha,
+                 float beta, hipStream_t st) {
+  if (K == 32) {
+#define CAFEQ_G32(TA, TB) hipLaunchKernelGGL((bgemm32_kernel<TA, TB>), dim3(nb), dim3(256), 0, st, A, B, C, alpha, beta)
+    if (ta && tb) CAFEQ_G32(true, true); else if (ta) CAFEQ_G32(true, false);
+    else if (tb) CAFEQ_G32(false, true); else CAFEQ_G32(false, false);
+#undef CAFEQ_G32
+  } else {
+    const unsigned grid = unsigned(nb) * (K / 64) * (K / 64);
+#define CAFEQ_G64(TA, TB) hipLaunchKernelGGL((bgemm_kernel<TA, TB>), dim3(grid), dim3(256), 0, st, A, B, C, K, alpha, beta)
+    if (ta && tb) CAFEQ_G64(true, true); else if (ta) CAFEQ_G64(true, false);
+    else if (tb) CAFEQ_G64(false, true); else CAFEQ_G64(false, false);
+#undef CAFEQ_G64
+  }
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+int launch_block_inverse(const float* T, int K, int nb, double* work, float* Tinv, float* rho_row,
+                         float* rho_col, int* status, hipStream_t st) {
+  hipLaunchKernelGGL(block_inverse_kernel, dim3(nb), dim3(1024), 0, st, T, K, work, Tinv, rho_row, rho_col, status);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+
+int device_cu_count() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    cus = n;
+  }
+  return cus;
+}
+
+}  // namespace cafeq

@@ -1,5 +1,5 @@
 // extern "C" entry points: argument validation and dispatch.  See include/cafeq.h.
-#include "cafeq_internal.hpp"
+#include "xform_core.hpp"
 
 using namespace cafeq;
 
@@ -26,6 +26,142 @@ int check_cfg(const cafeq_quant_cfg* c, bool need_axis) {
   return CAFEQ_OK;
 }
 
+
+// ---------------------------------------------------------------------------------------
+// planning of one fused-core launch and its scratch layout
+// ---------------------------------------------------------------------------------------
+struct CorePlan {
+  int K, G, L, NBLK, NGRP, nseg, nwg;
+  int64_t nlines, naxis, mt_per_seg, n_mt, nslot;
+  size_t slot_grad_floats;   // per slot
+};
+
+bool supported_block(int k) { return k == 32 || k == 64 || k == 128 || k == 256; }
+
+int make_plan(int K, int G, int64_t nlines, int64_t naxis, CorePlan* pl) {
+  if (!supported_block(K)) return CAFEQ_ERR_UNSUPPORTED;
+  if (!(G == 32 || G == 64 || G == 128 || G == 256)) return CAFEQ_ERR_UNSUPPORTED;
+  pl->K = K; pl->G = G; pl->L = K > G ? K : G;
+  if (naxis % pl->L != 0) return CAFEQ_ERR_BAD_SHAPE;
+  pl->NBLK = pl->L / K; pl->NGRP = pl->L / G;
+  pl->nlines = nlines; pl->naxis = naxis;
+  pl->nseg = int(naxis / pl->L);
+  pl->mt_per_seg = (nlines + kMacroLines - 1) / kMacroLines;
+  pl->n_mt = pl->mt_per_seg * pl->nseg;
+  int64_t nwg = std::min<int64_t>(pl->n_mt, device_cu_count());
+  if (nwg > 8) nwg -= nwg % 8;
+  pl->nwg = int(nwg);
+  pl->nslot = pl->nwg + pl->nseg;
+  pl->slot_grad_floats = size_t(pl->NBLK) * K * K;
+  return CAFEQ_OK;
+}
+
+struct Carver {
+  char* base; size_t off;
+  explicit Carver(void* b) : base(static_cast<char*>(b)), off(0) {}
+  template <typename T> T* take(size_t n) {
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off = align_up(off + n * sizeof(T), 256);
+    return p;
+  }
+};
+
+struct SingleWs {
+  float *rho, *rG, *slot_grad, *slot_hdr, *mmid, *x1; double* lse_ms; size_t bytes;
+};
+SingleWs carve_single(void* ws, const CorePlan& pl, int nb, bool grad) {
+  Carver c(ws);
+  SingleWs w;
+  w.lse_ms = c.take<double>(2);
+  w.rho = c.take<float>(size_t(nb) * pl.K);
+  w.rG = c.take<float>(size_t(pl.naxis / pl.G));
+  w.slot_hdr = c.take<float>(size_t(pl.nslot) * kHdrFloats);
+  w.slot_grad = c.take<float>(grad ? size_t(pl.nslot) * pl.slot_grad_floats : 0);
+  w.mmid = c.take<float>(grad ? size_t(nb) * pl.K * pl.K : 0);
+  w.x1 = c.take<float>(grad ? size_t(nb) * pl.K * pl.K : 0);
+  w.bytes = c.off;
+  return w;
+}
+
+struct DualWs {
+  float *hdrA, *hdrB, *gradA, *gradB, *gp, *x1; double* lse_ms; size_t bytes;
+};
+DualWs carve_dual(void* ws, const CorePlan& pa, const CorePlan& pb, int nb, bool grad) {
+  Carver c(ws);
+  DualWs w;
+  w.lse_ms = c.take<double>(2);
+  w.hdrA = c.take<float>(size_t(pa.nslot + pb.nslot) * kHdrFloats);   // A then B, contiguous
+  w.hdrB = w.hdrA ? w.hdrA + size_t(pa.nslot) * kHdrFloats : nullptr;
+  w.gradA = c.take<float>(grad ? size_t(pa.nslot) * pa.slot_grad_floats : 0);
+  w.gradB = c.take<float>(grad ? size_t(pb.nslot) * pb.slot_grad_floats : 0);
+  w.gp = c.take<float>(grad ? size_t(nb) * pa.K * pa.K : 0);
+  w.x1 = c.take<float>(grad ? size_t(nb) * pa.K * pa.K : 0);
+  w.bytes = c.off;
+  return w;
+}
+
+int check_xform(const cafeq_xform* x, bool need_inv) {
+  if (!x || !x->T || (need_inv && !x->Tinv)) return CAFEQ_ERR_INVALID_ARG;
+  if (!supported_block(x->k)) return CAFEQ_ERR_UNSUPPORTED;
+  if (x->nb <= 0 || x->rep <= 0) return CAFEQ_ERR_BAD_SHAPE;
+  if (!aligned16(x->T) || (x->Tinv && !aligned16(x->Tinv))) return CAFEQ_ERR_BAD_ALIGN;
+  return CAFEQ_OK;
+}
+
+int check_axis_len(const cafeq_mat* W, const cafeq_xform* x, int axis) {
+  if (axis == CAFEQ_AXIS_COL) {
+    if (x->rep != 1 || W->cols != int64_t(x->nb) * x->k) return CAFEQ_ERR_BAD_SHAPE;
+  } else if (axis == CAFEQ_AXIS_ROW) {
+    if (W->rows != int64_t(x->nb) * x->rep * x->k) return CAFEQ_ERR_BAD_SHAPE;
+  } else {
+    return CAFEQ_ERR_INVALID_ARG;
+  }
+  return CAFEQ_OK;
+}
+
+int resolve_group(const cafeq_quant_cfg* cfg, int64_t naxis, int* G) {
+  const int64_t g = cfg->group == 0 ? naxis : cfg->group;
+  if (naxis % g != 0) return CAFEQ_ERR_BAD_SHAPE;
+  if (!(g == 32 || g == 64 || g == 128 || g == 256)) return CAFEQ_ERR_UNSUPPORTED;
+  *G = int(g);
+  return CAFEQ_OK;
+}
+
+void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep) {
+  p->W = W->data; p->dtype = W->dtype; p->rows = W->rows; p->cols = W->cols; p->ld = W->ld;
+  p->rep = rep; p->nseg = pl.nseg; p->nlines = pl.nlines; p->mt_per_seg = pl.mt_per_seg;
+  p->n_mt = pl.n_mt; p->nwg = pl.nwg;
+  p->do_inverse = 0; p->do_grad = 0; p->loss_kind = kLossSur; p->beta = 0.f; p->lse_t = 0.f;
+  p->rG = nullptr; p->Zout = nullptr; p->codes = nullptr; p->scales = nullptr;
+  p->slot_grad = nullptr; p->slot_hdr = nullptr;
+  p->grid = make_grid(4);
+}
+
+}  // namespace
+
+namespace cafeq {
+int launch_core(int K, int G, int axis, const CoreParams& p, hipStream_t st) {
+  switch (K) {
+    case 32: return launch_core_k32(G, axis, p, st);
+    case 64: return launch_core_k64(G, axis, p, st);
+    case 128: return launch_core_k128(G, axis, p, st);
+    case 256: return launch_core_k256(G, axis, p, st);
+    default: return CAFEQ_ERR_UNSUPPORTED;
+  }
+}
+size_t core_lds_bytes(int K, int G, bool do_grad) {
+  switch (K) {
+    case 32: return core_lds_bytes_k32(G, do_grad);
+    case 64: return core_lds_bytes_k64(G, do_grad);
+    case 128: return core_lds_bytes_k128(G, do_grad);
+    case 256: return core_lds_bytes_k256(G, do_grad);
+    default: return 0;
+  }
+}
+}  // namespace cafeq
+
+namespace {
+constexpr size_t kLdsLimit = 160 * 1024;
 }  // namespace
 
 extern "C" {
@@ -48,11 +184,30 @@ int cafeq_version(void) { return 100; }
 
 size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b, const cafeq_xform* x,
                              const cafeq_quant_cfg* cfg) {
-  (void)b; (void)x; (void)cfg;
-  if (!a) return 0;
   switch (call_id) {
     case CAFEQ_CALL_RTN_QUANTIZE:
+      if (!a) return 0;
       return align_up(rtn_partials_capacity(a->rows, a->cols) * sizeof(double), 256);
+    case CAFEQ_CALL_BLOCK_INVERSE:
+      if (!x) return 0;
+      return align_up(size_t(x->nb) * x->k * 2 * x->k * sizeof(double), 256);
+    case CAFEQ_CALL_PROXY_LOSS: {
+      if (!a || !x || !cfg) return 0;
+      const bool col = cfg->axis == CAFEQ_AXIS_COL;
+      const int64_t naxis = col ? a->cols : a->rows, nlines = col ? a->rows : a->cols;
+      int G;
+      CorePlan pl;
+      if (resolve_group(cfg, naxis, &G) || make_plan(x->k, G, nlines, naxis, &pl)) return 0;
+      return carve_single(nullptr, pl, x->nb, true).bytes;
+    }
+    case CAFEQ_CALL_DUAL_PROXY_LOSS: {
+      if (!a || !b || !x || !cfg) return 0;
+      int GA, GB;
+      CorePlan pa, pb;
+      if (resolve_group(cfg, a->cols, &GA) || resolve_group(cfg, b->rows, &GB)) return 0;
+      if (make_plan(x->k, GA, a->rows, a->cols, &pa) || make_plan(x->k, GB, b->cols, b->rows, &pb)) return 0;
+      return carve_dual(nullptr, pa, pb, x->nb, true).bytes;
+    }
     default:
       return 0;
   }
@@ -80,31 +235,149 @@ int cafeq_rtn_quantize(const cafeq_mat* W, const cafeq_quant_cfg* cfg, int8_t* c
 }
 
 int cafeq_block_inverse(const float* T, int k, int nb, float* Tinv, float* rho_row, float* rho_col,
-                        int* status, void* stream) {
-  (void)T; (void)k; (void)nb; (void)Tinv; (void)rho_row; (void)rho_col; (void)status; (void)stream;
-  return CAFEQ_ERR_UNSUPPORTED;
+                        int* status, void* ws, void* stream) {
+  if (!T || !Tinv) return CAFEQ_ERR_INVALID_ARG;
+  if (k < 1 || k > 256 || nb < 1) return CAFEQ_ERR_BAD_SHAPE;
+  if (!ws) return CAFEQ_ERR_WORKSPACE;
+  return launch_block_inverse(T, k, nb, static_cast<double*>(ws), Tinv, rho_row, rho_col, status,
+                              static_cast<hipStream_t>(stream));
 }
 
 int cafeq_apply_transform(const cafeq_mat* W, const cafeq_xform* x, int axis, int side, float* Z,
                           void* stream) {
-  (void)W; (void)x; (void)axis; (void)side; (void)Z; (void)stream;
-  return CAFEQ_ERR_UNSUPPORTED;
+  int rc = check_mat(W);
+  if (rc) return rc;
+  if (side != CAFEQ_SIDE_T && side != CAFEQ_SIDE_TINV) return CAFEQ_ERR_INVALID_ARG;
+  rc = check_xform(x, side == CAFEQ_SIDE_TINV);
+  if (rc) return rc;
+  rc = check_axis_len(W, x, axis);
+  if (rc) return rc;
+  if (!Z) return CAFEQ_ERR_INVALID_ARG;
+  if (!aligned16(Z)) return CAFEQ_ERR_BAD_ALIGN;
+  const bool col = axis == CAFEQ_AXIS_COL;
+  CorePlan pl;
+  rc = make_plan(x->k, x->k, col ? W->rows : W->cols, col ? W->cols : W->rows, &pl);
+  if (rc) return rc;
+  CoreParams p;
+  fill_common(&p, W, pl, x->rep);
+  p.Afwd = side == CAFEQ_SIDE_T ? x->T : x->Tinv;
+  p.afwd_trans = col ? 1 : 0;
+  p.Ainv = nullptr; p.ainv_trans = 0;
+  p.Zout = Z;
+  return launch_core(x->k, x->k, axis, p, static_cast<hipStream_t>(stream));
 }
 
 int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const cafeq_quant_cfg* cfg,
                              float* losses, float* gradT, int8_t* codes, float* scales, void* ws,
                              void* stream) {
-  (void)W; (void)x; (void)cfg; (void)losses; (void)gradT; (void)codes; (void)scales; (void)ws; (void)stream;
-  return CAFEQ_ERR_UNSUPPORTED;
+  int rc = check_mat(W);
+  if (rc) return rc;
+  rc = check_cfg(cfg, true);
+  if (rc) return rc;
+  rc = check_xform(x, true);
+  if (rc) return rc;
+  rc = check_axis_len(W, x, cfg->axis);
+  if (rc) return rc;
+  if (!losses) return CAFEQ_ERR_INVALID_ARG;
+  if (!ws) return CAFEQ_ERR_WORKSPACE;
+  if ((codes && !aligned16(codes)) || (scales && !aligned16(scales)) || (gradT && !aligned16(gradT)))
+    return CAFEQ_ERR_BAD_ALIGN;
+  const bool col = cfg->axis == CAFEQ_AXIS_COL;
+  const int64_t naxis = col ? W->cols : W->rows, nlines = col ? W->rows : W->cols;
+  int G;
+  rc = resolve_group(cfg, naxis, &G);
+  if (rc) return rc;
+  const int K = x->k, nb = x->nb;
+  CorePlan pl;
+  rc = make_plan(K, G, nlines, naxis, &pl);
+  if (rc) return rc;
+  if (core_lds_bytes(K, G, gradT != nullptr) > kLdsLimit) return CAFEQ_ERR_UNSUPPORTED;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  SingleWs w = carve_single(ws, pl, nb, gradT != nullptr);
+  const QGrid grid = make_grid(cfg->bits);
+  const float beta = 1.f / (4.f * grid.qmax * grid.qmax);
+
+  if ((rc = launch_init_hdr(w.slot_hdr, pl.nslot, st))) return rc;
+  if ((rc = launch_rho(x->Tinv, K, nb, col ? 1 : 0, w.rho, st))) return rc;
+  if ((rc = launch_rho_groups(w.rho, K, x->rep, G, naxis / G, w.rG, st))) return rc;
+
+  CoreParams p;
+  fill_common(&p, W, pl, x->rep);
+  p.Afwd = x->T; p.Ainv = x->Tinv;
+  p.afwd_trans = p.ainv_trans = col ? 1 : 0;
+  p.grid = grid; p.do_inverse = 1; p.do_grad = gradT ? 1 : 0; p.loss_kind = kLossSur; p.beta = beta;
+  p.rG = w.rG; p.codes = codes; p.scales = scales; p.slot_grad = w.slot_grad; p.slot_hdr = w.slot_hdr;
+  if ((rc = launch_core(K, G, cfg->axis, p, st))) return rc;
+  if ((rc = launch_reduce_losses(kLossSur, w.slot_hdr, int(pl.nslot), nullptr, 0, beta, 0.f, 0, losses,
+                                 w.lse_ms, st)))
+    return rc;
+  if (gradT) {
+    // path through Z, then the path through rho(P): -2 P^T Mmid P^T
+    if ((rc = launch_reduce_grad(p, K, G, nb, col ? 1 : 0, nullptr, gradT, st))) return rc;
+    if ((rc = launch_build_mmid(p, K, G, nb, x->Tinv, col ? 1 : 0, w.mmid, st))) return rc;
+    if ((rc = launch_bgemm(true, false, x->Tinv, w.mmid, w.x1, K, nb, 1.f, 0.f, st))) return rc;
+    if ((rc = launch_bgemm(false, true, w.x1, x->Tinv, gradT, K, nb, -2.f, 1.f, st))) return rc;
+  }
+  return CAFEQ_OK;
 }
 
 int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const cafeq_xform* x,
                                   const cafeq_quant_cfg* cfg, float lse_t, float* losses, float* gradT,
                                   int8_t* codesU, float* scalesU, int8_t* codesV, float* scalesV,
                                   void* ws, void* stream) {
-  (void)A; (void)B; (void)x; (void)cfg; (void)lse_t; (void)losses; (void)gradT; (void)codesU;
-  (void)scalesU; (void)codesV; (void)scalesV; (void)ws; (void)stream;
-  return CAFEQ_ERR_UNSUPPORTED;
+  int rc = check_mat(A);
+  if (rc) return rc;
+  rc = check_mat(B);
+  if (rc) return rc;
+  rc = check_cfg(cfg, false);
+  if (rc) return rc;
+  rc = check_xform(x, true);
+  if (rc) return rc;
+  if (!losses) return CAFEQ_ERR_INVALID_ARG;
+  if (!(lse_t > 0.f)) return CAFEQ_ERR_INVALID_ARG;
+  if (!ws) return CAFEQ_ERR_WORKSPACE;
+  const int K = x->k, nb = x->nb;
+  if (A->cols != int64_t(nb) * K || B->rows != int64_t(nb) * x->rep * K) return CAFEQ_ERR_BAD_SHAPE;
+  int GA, GB;
+  if ((rc = resolve_group(cfg, A->cols, &GA))) return rc;
+  if ((rc = resolve_group(cfg, B->rows, &GB))) return rc;
+  CorePlan pa, pb;
+  if ((rc = make_plan(K, GA, A->rows, A->cols, &pa))) return rc;
+  if ((rc = make_plan(K, GB, B->cols, B->rows, &pb))) return rc;
+  const bool grad = gradT != nullptr;
+  if (core_lds_bytes(K, GA, grad) > kLdsLimit || core_lds_bytes(K, GB, grad) > kLdsLimit)
+    return CAFEQ_ERR_UNSUPPORTED;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  DualWs w = carve_dual(ws, pa, pb, nb, grad);
+  const QGrid grid = make_grid(cfg->bits);
+  if ((rc = launch_init_hdr(w.hdrA, pa.nslot + pb.nslot, st))) return rc;
+
+  CoreParams a;
+  fill_common(&a, A, pa, 1);
+  a.Afwd = x->T; a.Ainv = x->Tinv; a.afwd_trans = a.ainv_trans = 1;
+  a.grid = grid; a.do_inverse = 1; a.do_grad = grad ? 1 : 0; a.loss_kind = kLossLse; a.lse_t = lse_t;
+  a.codes = codesU; a.scales = scalesU; a.slot_grad = w.gradA; a.slot_hdr = w.hdrA;
+  if ((rc = launch_core(K, GA, CAFEQ_AXIS_COL, a, st))) return rc;
+
+  CoreParams b;
+  fill_common(&b, B, pb, x->rep);
+  b.Afwd = x->Tinv; b.Ainv = x->T; b.afwd_trans = b.ainv_trans = 0;
+  b.grid = grid; b.do_inverse = 1; b.do_grad = grad ? 1 : 0; b.loss_kind = kLossLse; b.lse_t = lse_t;
+  b.codes = codesV; b.scales = scalesV; b.slot_grad = w.gradB; b.slot_hdr = w.hdrB;
+  if ((rc = launch_core(K, GB, CAFEQ_AXIS_ROW, b, st))) return rc;
+
+  const int64_t ngroups = A->rows * (A->cols / GA) + (B->rows / GB) * B->cols;
+  if ((rc = launch_reduce_losses(kLossLse, w.hdrA, int(pa.nslot), w.hdrB, int(pb.nslot), 0.f, lse_t, ngroups,
+                                 losses, w.lse_ms, st)))
+    return rc;
+  if (grad) {
+    if ((rc = launch_reduce_grad(a, K, GA, nb, 1, w.lse_ms, gradT, st))) return rc;
+    // member B: G_P of transform block b sums its rep row-blocks; d/dT = -P^T G_P P^T
+    if ((rc = launch_reduce_grad(b, K, GB, nb, 0, w.lse_ms, w.gp, st))) return rc;
+    if ((rc = launch_bgemm(true, false, x->Tinv, w.gp, w.x1, K, nb, 1.f, 0.f, st))) return rc;
+    if ((rc = launch_bgemm(false, true, w.x1, x->Tinv, gradT, K, nb, -1.f, 1.f, st))) return rc;
+  }
+  return CAFEQ_OK;
 }
 
 int cafeq_adaptive_round_step(const float* U, const float* V, int64_t rowsA, int64_t colsA, int64_t rowsB,

@@ -21,4 +21,39 @@ struct RtnArgs {
 size_t rtn_partials_capacity(int64_t rows, int64_t cols);
 int launch_rtn(const RtnArgs& a, hipStream_t st);
 
+
+// ---------------------------------------------------------------------------
+// fused transform core (xform_core.hpp, instantiated per block size in xform_k*.hip)
+// ---------------------------------------------------------------------------
+struct CoreParams;
+// Launches the core for (K, G, axis); returns CAFEQ_ERR_UNSUPPORTED when that combination
+// has no instantiation or its LDS footprint does not fit.
+int launch_core(int K, int G, int axis, const CoreParams& p, hipStream_t st);
+int launch_core_k32(int G, int axis, const CoreParams& p, hipStream_t st);
+int launch_core_k64(int G, int axis, const CoreParams& p, hipStream_t st);
+int launch_core_k128(int G, int axis, const CoreParams& p, hipStream_t st);
+int launch_core_k256(int G, int axis, const CoreParams& p, hipStream_t st);
+// LDS bytes the core needs (0 if the gradient accumulator cannot fit with do_grad)
+size_t core_lds_bytes(int K, int G, bool do_grad);
+size_t core_lds_bytes_k32(int G, bool do_grad);
+size_t core_lds_bytes_k64(int G, bool do_grad);
+size_t core_lds_bytes_k128(int G, bool do_grad);
+size_t core_lds_bytes_k256(int G, bool do_grad);
+int device_cu_count();
+
+// aux_kernels.hip
+int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_t st);
+int launch_rho_groups(const float* rho, int K, int rep, int G, int64_t ngroups, float* rG, hipStream_t st);
+int launch_init_hdr(float* hdr, int64_t nslot, hipStream_t st);
+int launch_reduce_grad(const CoreParams& p, int K, int G, int nb, int transpose_out, const double* lse_ms,
+                       float* out, hipStream_t st);
+int launch_build_mmid(const CoreParams& p, int K, int G, int nb, const float* P, int scale_rows, float* Mmid,
+                      hipStream_t st);
+int launch_reduce_losses(int kind, const float* hdrA, int nslotA, const float* hdrB, int nslotB, float beta,
+                         float t, int64_t ngroups, float* losses, double* lse_ms, hipStream_t st);
+int launch_bgemm(bool ta, bool tb, const float* A, const float* B, float* C, int K, int nb, float alpha,
+                 float beta, hipStream_t st);
+int launch_block_inverse(const float* T, int K, int nb, double* work, float* Tinv, float* rho_row,
+                         float* rho_col, int* status, hipStream_t st);
+
 }  // namespace cafeq

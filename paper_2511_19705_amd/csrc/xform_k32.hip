@@ -1,0 +1,6 @@
+// Instantiations of the fused transform core for 32 x 32 transform blocks.
+#include "xform_launch.hpp"
+namespace cafeq {
+int launch_core_k32(int G, int axis, const CoreParams& p, hipStream_t st) { return launch_core_k<32>(G, axis, p, st); }
+size_t core_lds_bytes_k32(int G, bool do_grad) { return core_lds_bytes_k<32>(G, do_grad); }
+}  // namespace cafeq

@@ -1,0 +1,60 @@
+// Host launcher template for the fused core; included by the per-K instantiation files.
+#pragma once
+#include "xform_core.hpp"
+
+namespace cafeq {
+
+constexpr size_t kMaxLds = 160 * 1024;
+
+template <int K, int G>
+constexpr size_t core_lds_bytes_t(bool do_grad) {
+  using g = Geo<K, G>;
+  return sizeof(float) * (size_t(g::RING_FLOATS) + (do_grad ? size_t(g::GACC_FLOATS) : 0) +
+                          size_t(kNW) * kHdrFloats + kNW + 4);
+}
+
+template <int K, int G, int AXIS>
+int launch_core_t(const CoreParams& p, hipStream_t st) {
+  const size_t lds = core_lds_bytes_t<K, G>(p.do_grad != 0);
+  if (lds > kMaxLds) return CAFEQ_ERR_UNSUPPORTED;
+  auto kern = xform_core_kernel<K, G, AXIS>;
+  static bool attr_set = false;   // per instantiation
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            int(kMaxLds)) != hipSuccess)
+      return CAFEQ_ERR_LAUNCH;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(unsigned(p.nwg)), dim3(kThreads), lds, st, p);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+
+template <int K>
+int launch_core_k(int G, int axis, const CoreParams& p, hipStream_t st) {
+#define CAFEQ_CORE_CASE(GG)                                                           \
+  case GG:                                                                            \
+    return axis == CAFEQ_AXIS_COL ? launch_core_t<K, GG, CAFEQ_AXIS_COL>(p, st)       \
+                                  : launch_core_t<K, GG, CAFEQ_AXIS_ROW>(p, st);
+  switch (G) {
+    CAFEQ_CORE_CASE(32)
+    CAFEQ_CORE_CASE(64)
+    CAFEQ_CORE_CASE(128)
+    CAFEQ_CORE_CASE(256)
+    default: return CAFEQ_ERR_UNSUPPORTED;
+  }
+#undef CAFEQ_CORE_CASE
+}
+
+template <int K>
+size_t core_lds_bytes_k(int G, bool do_grad) {
+  switch (G) {
+    case 32: return core_lds_bytes_t<K, 32>(do_grad);
+    case 64: return core_lds_bytes_t<K, 64>(do_grad);
+    case 128: return core_lds_bytes_t<K, 128>(do_grad);
+    case 256: return core_lds_bytes_t<K, 256>(do_grad);
+    default: return 0;
+  }
+}
+
+}  // namespace cafeq
