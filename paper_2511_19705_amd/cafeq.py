@@ -215,3 +215,23 @@ def dual_proxy_loss_fwd_bwd(A, B, T, Tinv, bits, group, rep=1, lse_t=5.0, want_g
                                              ctypes.byref(cfg), ctypes.c_float(lse_t), _ptr(losses), _ptr(grad),
                                              _ptr(cu), _ptr(su), _ptr(cv), _ptr(sv), _ptr(ws), _stream()))
     return losses, grad, outs
+
+
+def adaptive_round_step(U, V, codesU, scalesU, codesV, scalesV, bits, group, k, rep=1, half=0):
+    """One iteration of Alg. 1; codes/scales are updated in place.  Returns status[2*nb]."""
+    for t in (U, V):
+        if t.dtype != torch.float32 or not t.is_contiguous():
+            raise CafeqError("U and V must be contiguous float32")
+    nb = U.shape[1] // k
+    cfg = QuantCfg(bits, group, 0, 0)
+    mu, mv = mat(U), mat(V)
+    x = Xform(0, 0, k, nb, rep)
+    status = torch.zeros(2 * nb, dtype=torch.int32, device=U.device)
+    nbytes = workspace_bytes(CALL_ADAPTIVE, mu, mv, x, cfg)
+    if nbytes == 0:
+        raise CafeqError("unsupported adaptive-rounding configuration (workspace query returned 0)")
+    ws = workspace(nbytes, U.device)
+    _check(lib.cafeq_adaptive_round_step(_ptr(U), _ptr(V), U.shape[0], U.shape[1], V.shape[0], V.shape[1],
+                                         ctypes.byref(cfg), k, nb, rep, half, _ptr(codesU), _ptr(scalesU),
+                                         _ptr(codesV), _ptr(scalesV), _ptr(status), _ptr(ws), _stream()))
+    return status

@@ -1,7 +1,6 @@
 // Small kernels around the fused core: squared norms of the inverse transform (the
 // (M^-1)_{ij}^2 factors of the paper's surrogate, Sec. 4.1), fixed-order reduction of the
-// per-workgroup partials, the k x k products of the gradient's path through M^-1, and the
-// blockwise inverse.  All are off the bandwidth path (k x k sized per block).
+// per-workgroup partials and the k x k products of the gradient's path through M^-1.  All are off the bandwidth path (k x k sized per block).
 #include "xform_core.hpp"
 
 namespace cafeq {
@@ -23,16 +22,19 @@ __global__ __launch_bounds__(256) void rho_kernel(const float* __restrict__ P, i
 }
 
 // rG[gi] = sum of rho over the axis indices of group gi (axis index a -> block (a/K)/rep, a%K).
+// One wave per group.
 __global__ __launch_bounds__(256) void rho_group_kernel(const float* __restrict__ rho, int K, int rep,
                                                          int G, int64_t ngroups, float* __restrict__ rG) {
-  const int64_t gi = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int64_t gi = int64_t(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave;
   if (gi >= ngroups) return;
-  double acc = 0;
-  for (int e = 0; e < G; ++e) {
+  const int lane = threadIdx.x % kWave;
+  float acc = 0.f;
+  for (int e = lane; e < G; e += kWave) {
     const int64_t a = gi * G + e;
     acc += rho[((a / K) / rep) * K + a % K];
   }
-  rG[gi] = float(acc);
+  acc = wave_sum(acc);
+  if (lane == 0) rG[gi] = acc;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -65,26 +67,53 @@ struct ReduceArgs {
 // grid: nb transform blocks.  out_b = sum over the rep row-blocks q of block b, and over the
 // partials of q's segment, in fixed order.
 __global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceArgs a) {
+  constexpr int kBatch = 64;
+  __shared__ const float* src[kBatch];
+  __shared__ float scl[kBatch];
+  __shared__ int nsrc, more, next_q, next_w;
   const int b = blockIdx.x;
   const int K = a.K;
-  for (int i = threadIdx.x; i < K * K; i += blockDim.x) {
-    float acc = 0.f;
-    for (int q = b * a.rep; q < (b + 1) * a.rep; ++q) {
-      const int seg = q / a.NBLK, blk = q % a.NBLK;
-      int lo, hi;
-      seg_wg_range(seg, a.mt_per_seg, a.n_mt, a.nwg, &lo, &hi);
-      for (int w = lo; w < hi; ++w) {
-        const int64_t slot = int64_t(w) + seg;
-        float sc = 1.f;
-        if (a.lse_ms) {
-          const float mref = a.slot_hdr[slot * kHdrFloats + kHdrMref];
-          sc = float(exp(double(a.t) * (double(mref) - a.lse_ms[0])) / a.lse_ms[1]);
+  if (threadIdx.x == 0) { next_q = b * a.rep; next_w = -1; }
+  __syncthreads();
+  for (int batch = 0;; ++batch) {
+    if (threadIdx.x == 0) {
+      // gather up to kBatch (partial, scale) pairs, resuming where the last batch stopped
+      int n = 0, q = next_q, wres = next_w;
+      bool full = false;
+      for (; q < (b + 1) * a.rep && !full; ++q) {
+        const int seg = q / a.NBLK, blk = q % a.NBLK;
+        int lo, hi;
+        seg_wg_range(seg, a.mt_per_seg, a.n_mt, a.nwg, &lo, &hi);
+        int w = wres >= 0 ? wres : lo;
+        wres = -1;
+        for (; w < hi; ++w) {
+          if (n == kBatch) { full = true; wres = w; break; }
+          const int64_t slot = int64_t(w) + seg;
+          float sc = 1.f;
+          if (a.lse_ms) {
+            const float mref = a.slot_hdr[slot * kHdrFloats + kHdrMref];
+            sc = float(exp(double(a.t) * (double(mref) - a.lse_ms[0])) / a.lse_ms[1]);
+          }
+          src[n] = a.slot_grad + slot * int64_t(a.NBLK) * K * K + int64_t(blk) * K * K;
+          scl[n] = sc;
+          ++n;
         }
-        acc += sc * a.slot_grad[slot * int64_t(a.NBLK) * K * K + int64_t(blk) * K * K + i];
+        if (full) break;
       }
+      nsrc = n; more = full ? 1 : 0; next_q = q; next_w = wres;
     }
-    const int r = i / K, c = i % K;
-    a.out[size_t(b) * K * K + (a.transpose_out ? c * K + r : i)] = acc;
+    __syncthreads();
+    const int n = nsrc;
+    for (int i = threadIdx.x; i < K * K; i += blockDim.x) {
+      float acc = 0.f;
+      for (int s = 0; s < n; ++s) acc += scl[s] * src[s][i];
+      const int r = i / K, c = i % K;
+      float* dst = a.out + size_t(b) * K * K + (a.transpose_out ? c * K + r : i);
+      *dst = batch == 0 ? acc : *dst + acc;
+    }
+    const int again = more;
+    __syncthreads();
+    if (!again) break;
   }
 }
 
@@ -273,96 +302,6 @@ __global__ __launch_bounds__(256) void bgemm32_kernel(const float* __restrict__ 
   }
 }
 
-// ---------------------------------------------------------------------------------------
-// blockwise inverse: Gauss-Jordan with partial pivoting in float64, one workgroup per block,
-// working copy [K][2K] (A | I) in the caller's workspace.
-// ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void block_inverse_kernel(const float* __restrict__ T, int K,
-                                                              double* __restrict__ work, float* __restrict__ Tinv,
-                                                              float* __restrict__ rho_row, float* __restrict__ rho_col,
-                                                              int* __restrict__ status) {
-  __shared__ double pv_val[1024];
-  __shared__ int pv_idx[1024];
-  __shared__ double prow[512];
-  __shared__ double colk[256];
-  __shared__ int singular;
-  const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
-  const int W2 = 2 * K;
-  double* M = work + size_t(b) * K * W2;
-  const float* Tb = T + size_t(b) * K * K;
-  double anorm = 0;
-  for (int e = tid; e < K * W2; e += nt) {
-    const int r = e / W2, c = e % W2;
-    const double v = c < K ? double(Tb[r * K + c]) : (c - K == r ? 1.0 : 0.0);
-    M[e] = v;
-    if (c < K) anorm = fmax(anorm, fabs(v));
-  }
-  pv_val[tid] = anorm;
-  if (tid == 0) singular = 0;
-  __syncthreads();
-  for (int s = nt / 2; s > 0; s >>= 1) {
-    if (tid < s) pv_val[tid] = fmax(pv_val[tid], pv_val[tid + s]);
-    __syncthreads();
-  }
-  anorm = pv_val[0];
-  __syncthreads();
-  for (int k = 0; k < K; ++k) {
-    // pivot search in column k, rows k..K-1
-    double best = -1.0;
-    int bi = k;
-    for (int r = k + tid; r < K; r += nt) {
-      const double v = fabs(M[r * W2 + k]);
-      if (v > best) { best = v; bi = r; }
-    }
-    pv_val[tid] = best; pv_idx[tid] = bi;
-    __syncthreads();
-    for (int s = nt / 2; s > 0; s >>= 1) {
-      if (tid < s) {
-        if (pv_val[tid + s] > pv_val[tid] || (pv_val[tid + s] == pv_val[tid] && pv_idx[tid + s] < pv_idx[tid])) {
-          pv_val[tid] = pv_val[tid + s]; pv_idx[tid] = pv_idx[tid + s];
-        }
-      }
-      __syncthreads();
-    }
-    const int p = pv_idx[0];
-    const double pval = pv_val[0];
-    __syncthreads();
-    if (!(pval > anorm * 1e-13)) {
-      if (tid == 0) singular = 1;
-      __syncthreads();
-      break;
-    }
-    // swap rows p and k, normalise the pivot row into shared memory
-    const double piv = M[p * W2 + k];
-    for (int c = tid; c < W2; c += nt) {
-      const double vp = M[p * W2 + c], vk = M[k * W2 + c];
-      prow[c] = vp / piv;
-      if (p != k) M[p * W2 + c] = vk;
-    }
-    __syncthreads();
-    for (int r = tid; r < K; r += nt) colk[r] = (r == k) ? 0.0 : M[r * W2 + k];
-    __syncthreads();
-    for (int e = tid; e < K * W2; e += nt) {
-      const int r = e / W2, c = e % W2;
-      M[e] = (r == k) ? prow[c] : M[e] - colk[r] * prow[c];
-    }
-    __syncthreads();
-  }
-  if (status && tid == 0) status[b] = singular;
-  float* Pb = Tinv + size_t(b) * K * K;
-  for (int e = tid; e < K * K; e += nt) Pb[e] = float(M[(e / K) * W2 + K + e % K]);
-  __syncthreads();
-  for (int j = tid; j < K; j += nt) {
-    double rr = 0, cc = 0;
-    for (int i = 0; i < K; ++i) {
-      const double a = M[j * W2 + K + i], c = M[i * W2 + K + j];
-      rr += a * a; cc += c * c;
-    }
-    if (rho_row) rho_row[size_t(b) * K + j] = float(rr);
-    if (rho_col) rho_col[size_t(b) * K + j] = float(cc);
-  }
-}
-
 }  // namespace
 
 int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_t st) {
@@ -371,7 +310,7 @@ int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_
   return CAFEQ_OK;
 }
 int launch_rho_groups(const float* rho, int K, int rep, int G, int64_t ngroups, float* rG, hipStream_t st) {
-  hipLaunchKernelGGL(rho_group_kernel, dim3(unsigned((ngroups + 255) / 256)), dim3(256), 0, st, rho, K, rep, G,
+  hipLaunchKernelGGL(rho_group_kernel, dim3(unsigned((ngroups + 3) / 4)), dim3(256), 0, st, rho, K, rep, G,
                      ngroups, rG);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
@@ -429,13 +368,6 @@ int launch_bgemm(bool ta, bool tb, const float* A, const float* B, float* C, int
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }
-int launch_block_inverse(const float* T, int K, int nb, double* work, float* Tinv, float* rho_row,
-                         float* rho_col, int* status, hipStream_t st) {
-  hipLaunchKernelGGL(block_inverse_kernel, dim3(nb), dim3(1024), 0, st, T, K, work, Tinv, rho_row, rho_col, status);
-  CAFEQ_CHECK_LAUNCH();
-  return CAFEQ_OK;
-}
-
 int device_cu_count() {
   static int cus = 0;
   if (cus == 0) {

@@ -127,6 +127,40 @@ int resolve_group(const cafeq_quant_cfg* cfg, int64_t naxis, int* G) {
   return CAFEQ_OK;
 }
 
+struct AdaptivePlan {
+  int GA, GB, nchunkA, nchunkB;
+  int64_t chunkA, chunkB;
+  CorePlan planU, planV;
+  size_t partial_floats, bytes;
+};
+void split_contraction(int64_t tlen, int units, int64_t* chunk, int* nchunk) {
+  // aim at about two workgroups per compute unit, chunks of at least 64 and a multiple of 16
+  int64_t want = (2 * int64_t(device_cu_count()) + units - 1) / units;
+  want = std::max<int64_t>(1, std::min<int64_t>(want, (tlen + 63) / 64));
+  int64_t ch = (tlen + want - 1) / want;
+  ch = (ch + 15) / 16 * 16;
+  *chunk = ch;
+  *nchunk = int((tlen + ch - 1) / ch);
+}
+int plan_adaptive(const cafeq_quant_cfg* cfg, int k, int nb, int rep, int64_t rowsA, int64_t colsA,
+                  int64_t rowsB, int64_t colsB, AdaptivePlan* ap) {
+  int rc;
+  if ((rc = resolve_group(cfg, colsA, &ap->GA))) return rc;
+  if ((rc = resolve_group(cfg, rowsB, &ap->GB))) return rc;
+  if ((rc = make_plan(k, ap->GA, rowsA, colsA, &ap->planU))) return rc;
+  if ((rc = make_plan(k, ap->GB, colsB, rowsB, &ap->planV))) return rc;
+  split_contraction(rowsA, nb * (k / 32), &ap->chunkA, &ap->nchunkA);
+  split_contraction(colsB, nb * rep * (k / 32), &ap->chunkB, &ap->nchunkB);
+  const size_t nz = size_t(std::max(ap->nchunkA, rep * ap->nchunkB));
+  ap->partial_floats = size_t(nb) * nz * 2 * k * k;
+  Carver c(nullptr);
+  c.take<float>(ap->partial_floats);
+  c.take<double>(size_t(nb) * k * 2 * k);
+  c.take<float>(size_t(nb) * k * k);
+  ap->bytes = c.off;
+  return CAFEQ_OK;
+}
+
 void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep) {
   p->W = W->data; p->dtype = W->dtype; p->rows = W->rows; p->cols = W->cols; p->ld = W->ld;
   p->rep = rep; p->nseg = pl.nseg; p->nlines = pl.nlines; p->mt_per_seg = pl.mt_per_seg;
@@ -207,6 +241,13 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
       if (resolve_group(cfg, a->cols, &GA) || resolve_group(cfg, b->rows, &GB)) return 0;
       if (make_plan(x->k, GA, a->rows, a->cols, &pa) || make_plan(x->k, GB, b->cols, b->rows, &pb)) return 0;
       return carve_dual(nullptr, pa, pb, x->nb, true).bytes;
+    }
+    case CAFEQ_CALL_ADAPTIVE_ROUND: {
+      // a: U [rowsA][nb*k], b: V [nb*rep*k][colsB]
+      if (!a || !b || !x || !cfg) return 0;
+      AdaptivePlan ap;
+      if (plan_adaptive(cfg, x->k, x->nb, x->rep, a->rows, a->cols, b->rows, b->cols, &ap)) return 0;
+      return ap.bytes;
     }
     default:
       return 0;
@@ -384,10 +425,53 @@ int cafeq_adaptive_round_step(const float* U, const float* V, int64_t rowsA, int
                               int64_t colsB, const cafeq_quant_cfg* cfg, int k, int nb, int rep, int half,
                               int8_t* codesU, float* scalesU, int8_t* codesV, float* scalesV, int* status,
                               void* ws, void* stream) {
-  (void)U; (void)V; (void)rowsA; (void)colsA; (void)rowsB; (void)colsB; (void)cfg; (void)k; (void)nb;
-  (void)rep; (void)half; (void)codesU; (void)scalesU; (void)codesV; (void)scalesV; (void)status;
-  (void)ws; (void)stream;
-  return CAFEQ_ERR_UNSUPPORTED;
+  int rc = check_cfg(cfg, false);
+  if (rc) return rc;
+  if (!U || !V || !codesU || !scalesU || !codesV || !scalesV) return CAFEQ_ERR_INVALID_ARG;
+  if (half < 0 || half > 2) return CAFEQ_ERR_INVALID_ARG;
+  if (!supported_block(k)) return CAFEQ_ERR_UNSUPPORTED;
+  if (nb <= 0 || rep <= 0 || rowsA <= 0 || colsB <= 0) return CAFEQ_ERR_BAD_SHAPE;
+  if (colsA != int64_t(nb) * k || rowsB != int64_t(nb) * rep * k || colsB % 4 != 0) return CAFEQ_ERR_BAD_SHAPE;
+  if (!aligned16(U) || !aligned16(V) || !aligned16(codesU) || !aligned16(codesV) || !aligned16(scalesU) ||
+      !aligned16(scalesV))
+    return CAFEQ_ERR_BAD_ALIGN;
+  if (!ws) return CAFEQ_ERR_WORKSPACE;
+  AdaptivePlan ap;
+  if ((rc = plan_adaptive(cfg, k, nb, rep, rowsA, colsA, rowsB, colsB, &ap))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Carver c(ws);
+  float* partial = c.take<float>(ap.partial_floats);
+  double* work = c.take<double>(size_t(nb) * k * 2 * k);
+  float* Cmat = c.take<float>(size_t(nb) * k * k);
+  const QGrid grid = make_grid(cfg->bits);
+
+  if (half == 0 || half == 1) {
+    // line 3: C = pinv(Uq_b) U_b per head, Vq <- Q(C V_q)
+    if ((rc = launch_gram_pair(CAFEQ_AXIS_COL, U, codesU, scalesU, rowsA, colsA, k, ap.GA, nb, 1, ap.chunkA,
+                               ap.nchunkA, partial, st)))
+      return rc;
+    if ((rc = launch_gj_solve(k, nb, ap.nchunkA, partial, work, Cmat, status, 2, 0, st))) return rc;
+    cafeq_mat mv{V, rowsB, colsB, colsB, CAFEQ_F32};
+    CoreParams p;
+    fill_common(&p, &mv, ap.planV, rep);
+    p.Afwd = Cmat; p.afwd_trans = 0; p.Ainv = nullptr; p.ainv_trans = 0;
+    p.grid = grid; p.codes = codesV; p.scales = scalesV;
+    if ((rc = launch_core(k, ap.GB, CAFEQ_AXIS_ROW, p, st))) return rc;
+  }
+  if (half == 0 || half == 2) {
+    // line 4: C^T = V_[b] pinv(Vq_[b]) per head, Uq_b <- Q(U_b C^T)
+    if ((rc = launch_gram_pair(CAFEQ_AXIS_ROW, V, codesV, scalesV, rowsB, colsB, k, ap.GB, nb, rep, ap.chunkB,
+                               ap.nchunkB, partial, st)))
+      return rc;
+    if ((rc = launch_gj_solve(k, nb, rep * ap.nchunkB, partial, work, Cmat, status, 2, 1, st))) return rc;
+    cafeq_mat mu{U, rowsA, colsA, colsA, CAFEQ_F32};
+    CoreParams p;
+    fill_common(&p, &mu, ap.planU, 1);
+    p.Afwd = Cmat; p.afwd_trans = 0; p.Ainv = nullptr; p.ainv_trans = 0;
+    p.grid = grid; p.codes = codesU; p.scales = scalesU;
+    if ((rc = launch_core(k, ap.GA, CAFEQ_AXIS_COL, p, st))) return rc;
+  }
+  return CAFEQ_OK;
 }
 
 }  // extern "C"

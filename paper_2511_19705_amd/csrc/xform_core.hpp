@@ -213,7 +213,7 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
   for (int64_t mt = mt0; mt < mt1; ++mt) {
     const int64_t seg = mt / p.mt_per_seg;
     if (seg != cur_seg) {
-      flush(cur_seg);
+      if (p.do_inverse || p.do_grad) flush(cur_seg);   // partial buffers exist only for loss calls
       cur_seg = seg;
     }
     const int64_t line = (mt - seg * p.mt_per_seg) * kMacroLines + wave * kStripLines + ln;

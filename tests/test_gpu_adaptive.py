@@ -1,0 +1,135 @@
+"""GPU parity: cafeq_adaptive_round_step (Alg. 1) and cafeq_block_inverse against the oracle.
+
+Each line of Alg. 1 is checked on inputs produced by the oracle, so that a handful of
+tie-flipped codes from one line cannot leak into the other line's normal equations; the
+chained call (half = 0) is then checked through the paired quantization error it reaches.
+"""
+import numpy as np
+import pytest
+
+from oracle import cafeq_oracle as O
+from paper_2511_19705_amd import workloads as WL
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2511_19705_amd import cafeq
+    return torch, cafeq
+
+
+def _dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def _pair(rowsA, colsB, k, nb, rep, seed):
+    """Transformed pair (U, V) in float32, built on the host from a seeded raw pair."""
+    A, B, T = WL.small_pair(rowsA, nb * k, k, rep, seed, eps=0.05)
+    B = np.ascontiguousarray(B[:, :colsB])
+    P = O.block_inverse(T)
+    U = O.blockdiag_apply(A, T, O.COL).astype(np.float32)
+    V = O.blockdiag_apply(B, P, O.ROW, rep).astype(np.float32)
+    return U, V
+
+
+def _dequant(codes, scales, group, axis):
+    return codes.astype(np.float64) * np.repeat(scales.astype(np.float64), group, axis=1 if axis == O.COL else 0)
+
+
+@pytest.mark.parametrize("k,group,rep,bits", [(64, 64, 2, 4), (32, 32, 1, 3), (128, 64, 2, 4), (256, 64, 1, 4)])
+def test_each_line_against_oracle(env, k, group, rep, bits):
+    torch, cafeq = env
+    nb = 2
+    U, V = _pair(200, 136, k, nb, rep, 500 + k)
+    cu, su, _ = O.rtn_sym(U, bits, group, O.COL)
+    Uh = _dequant(cu, su, group, O.COL)
+    # oracle: line 3 then line 4
+    Uh1, Vh1, Vt, Ut = O.adaptive_round_step(U, V, Uh, bits, group, k, rep, half=0)
+    cv_ref, sv_ref, _ = O.rtn_sym(Vt, bits, group, O.ROW)
+    cu_ref, su_ref, _ = O.rtn_sym(Ut, bits, group, O.COL)
+
+    Ud, Vd = _dev(torch, U), _dev(torch, V)
+    # line 3 on the device, from the oracle's (bit-identical) codes of U
+    dcu, dsu = _dev(torch, cu), _dev(torch, su.astype(np.float32))
+    dcv = torch.zeros(V.shape, dtype=torch.int8, device="cuda:0")
+    dsv = torch.zeros(sv_ref.shape, dtype=torch.float32, device="cuda:0")
+    st = cafeq.adaptive_round_step(Ud, Vd, dcu, dsu, dcv, dsv, bits, group, k, rep, half=1)
+    torch.cuda.synchronize()
+    assert int(st.abs().sum()) == 0
+    parity.check_scales(dsv.cpu().numpy(), sv_ref)
+    parity.check_codes(dcv.cpu().numpy(), cv_ref, Vt, sv_ref, O.ROW, group)
+    # line 4 on the device, from the oracle's codes of V
+    dcv2, dsv2 = _dev(torch, cv_ref), _dev(torch, sv_ref.astype(np.float32))
+    dcu2 = torch.zeros(U.shape, dtype=torch.int8, device="cuda:0")
+    dsu2 = torch.zeros(su_ref.shape, dtype=torch.float32, device="cuda:0")
+    st = cafeq.adaptive_round_step(Ud, Vd, dcu2, dsu2, dcv2, dsv2, bits, group, k, rep, half=2)
+    torch.cuda.synchronize()
+    assert int(st.abs().sum()) == 0
+    parity.check_scales(dsu2.cpu().numpy(), su_ref)
+    parity.check_codes(dcu2.cpu().numpy(), cu_ref, Ut, su_ref, O.COL, group)
+
+
+def test_chained_iterations_reach_the_oracle_pqe(env):
+    torch, cafeq = env
+    k, group, rep, bits, nb = 64, 64, 2, 4, 2
+    U, V = _pair(264, 200, k, nb, rep, 600)
+    cu, su, _ = O.rtn_sym(U, bits, group, O.COL)
+    Uh = _dequant(cu, su, group, O.COL)
+    Vh0 = O.rtn_sym(V, bits, group, O.ROW)[2]
+    p_indep, _ = O.pqe(U, V, Uh, Vh0, k, rep)
+    Uh_o, Vh_o = Uh, None
+    for _ in range(3):
+        Uh_o, Vh_o, _, _ = O.adaptive_round_step(U, V, Uh_o, bits, group, k, rep)
+    p_ref, _ = O.pqe(U, V, Uh_o, Vh_o, k, rep)
+
+    Ud, Vd = _dev(torch, U), _dev(torch, V)
+    dcu, dsu = _dev(torch, cu), _dev(torch, su.astype(np.float32))
+    dcv = torch.zeros(V.shape, dtype=torch.int8, device="cuda:0")
+    dsv = torch.zeros((V.shape[0] // group, V.shape[1]), dtype=torch.float32, device="cuda:0")
+    for _ in range(3):
+        cafeq.adaptive_round_step(Ud, Vd, dcu, dsu, dcv, dsv, bits, group, k, rep, half=0)
+    torch.cuda.synchronize()
+    Uh_g = _dequant(dcu.cpu().numpy(), dsu.cpu().numpy(), group, O.COL)
+    Vh_g = _dequant(dcv.cpu().numpy(), dsv.cpu().numpy(), group, O.ROW)
+    p_gpu, _ = O.pqe(U, V, Uh_g, Vh_g, k, rep)
+    assert p_ref < 0.95 * p_indep              # the algorithm helps on this input
+    assert abs(p_gpu - p_ref) <= 2e-3 * p_ref  # and the device lands on the same error level
+
+
+def test_rank_deficient_head_falls_back_to_plain_rounding(env):
+    torch, cafeq = env
+    k, group, rep, bits, nb = 32, 32, 1, 4, 2
+    U, V = _pair(136, 72, k, nb, rep, 700)
+    U[:, 5] = U[:, 3]                          # head 0: two identical columns -> singular Gram
+    cu, su, _ = O.rtn_sym(U, bits, group, O.COL)
+    Ud, Vd = _dev(torch, U), _dev(torch, V)
+    dcu, dsu = _dev(torch, cu), _dev(torch, su.astype(np.float32))
+    dcv = torch.zeros(V.shape, dtype=torch.int8, device="cuda:0")
+    dsv = torch.zeros((V.shape[0] // group, V.shape[1]), dtype=torch.float32, device="cuda:0")
+    st = cafeq.adaptive_round_step(Ud, Vd, dcu, dsu, dcv, dsv, bits, group, k, rep, half=1).cpu().numpy()
+    assert st[0] == 1 and st[2] == 0
+    c_plain, s_plain, _ = O.rtn_sym(V[:k], bits, group, O.ROW)
+    np.testing.assert_array_equal(dcv.cpu().numpy()[:k], c_plain)
+    np.testing.assert_array_equal(dsv.cpu().numpy()[:1], s_plain.astype(np.float32))
+
+
+@pytest.mark.parametrize("k", [32, 64, 128, 256])
+def test_block_inverse(env, k):
+    torch, cafeq = env
+    T = WL.perturbed_blocks(3, k, 800 + k, eps=0.3)
+    T[1] = 0
+    T[1, :, 0] = 1.0                            # block 1 is singular
+    Tinv, rr, rc_, status = cafeq.block_inverse(_dev(torch, T), want_rho=True)
+    torch.cuda.synchronize()
+    status = status.cpu().numpy()
+    assert list(status) == [0, 1, 0]
+    for b in (0, 2):
+        ref = np.linalg.inv(T[b].astype(np.float64))
+        np.testing.assert_allclose(Tinv[b].cpu().numpy(), ref, rtol=0, atol=2e-6 * np.abs(ref).max())
+        rho_r = O.rho_from_inverse(ref[None], O.COL)
+        rho_c = O.rho_from_inverse(ref[None], O.ROW)
+        np.testing.assert_allclose(rr.cpu().numpy()[b * k:(b + 1) * k], rho_r, rtol=1e-5)
+        np.testing.assert_allclose(rc_.cpu().numpy()[b * k:(b + 1) * k], rho_c, rtol=1e-5)
