@@ -43,7 +43,8 @@ def _dequant(codes, scales, group, axis):
 def test_each_line_against_oracle(env, k, group, rep, bits):
     torch, cafeq = env
     nb = 2
-    U, V = _pair(200, 136, k, nb, rep, 500 + k)
+    # rows of U and columns of V: at least k (full rank), ragged against the 128-line macro-tile
+    U, V = _pair(200 if k <= 128 else 328, 136 if k <= 128 else 296, k, nb, rep, 500 + k)
     cu, su, _ = O.rtn_sym(U, bits, group, O.COL)
     Uh = _dequant(cu, su, group, O.COL)
     # oracle: line 3 then line 4
@@ -114,6 +115,21 @@ def test_rank_deficient_head_falls_back_to_plain_rounding(env):
     c_plain, s_plain, _ = O.rtn_sym(V[:k], bits, group, O.ROW)
     np.testing.assert_array_equal(dcv.cpu().numpy()[:k], c_plain)
     np.testing.assert_array_equal(dsv.cpu().numpy()[:1], s_plain.astype(np.float32))
+
+
+def test_fewer_rows_than_columns_is_flagged(env):
+    # U_b is 40 x 64: its Gram matrix has rank <= 40, the normal equations do not apply
+    torch, cafeq = env
+    k, group, rep, bits, nb = 64, 64, 1, 4, 1
+    U, V = _pair(40, 72, k, nb, rep, 710)
+    cu, su, _ = O.rtn_sym(U, bits, group, O.COL)
+    dcv = torch.zeros(V.shape, dtype=torch.int8, device="cuda:0")
+    dsv = torch.zeros((V.shape[0] // group, V.shape[1]), dtype=torch.float32, device="cuda:0")
+    st = cafeq.adaptive_round_step(_dev(torch, U), _dev(torch, V), _dev(torch, cu), _dev(torch, su.astype(np.float32)),
+                                   dcv, dsv, bits, group, k, rep, half=1).cpu().numpy()
+    assert st[0] == 1
+    c_plain, _, _ = O.rtn_sym(V, bits, group, O.ROW)
+    np.testing.assert_array_equal(dcv.cpu().numpy(), c_plain)
 
 
 @pytest.mark.parametrize("k", [32, 64, 128, 256])
