@@ -174,6 +174,14 @@ int cafeq_adaptive_round_step(const float* U, const float* V, int64_t rowsA, int
                               float* scalesU, int8_t* codesV, float* scalesV, int* status,
                               void* ws, void* stream);
 
+/* Measurement aid (not part of the method): while enabled, every launch of the fused
+ * transform kernel is bracketed by HIP events recorded on the launch stream.
+ * cafeq_profile_read synchronises those events, returns the number of launches seen since
+ * the last read and stores the sum of their durations in *total_ms (host pointer), then
+ * forgets them.  Not thread-safe; at most 4096 launches are kept between reads. */
+int cafeq_profile_enable(int on);
+int cafeq_profile_read(float* total_ms);
+
 #ifdef __cplusplus
 }
 #endif

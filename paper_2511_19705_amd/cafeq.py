@@ -23,6 +23,7 @@ EXPORTS = (
     "cafeq_strerror", "cafeq_version", "cafeq_workspace_bytes", "cafeq_block_inverse",
     "cafeq_rtn_quantize", "cafeq_apply_transform", "cafeq_proxy_loss_fwd_bwd",
     "cafeq_dual_proxy_loss_fwd_bwd", "cafeq_adaptive_round_step",
+    "cafeq_profile_enable", "cafeq_profile_read",
 )
 
 
@@ -69,6 +70,8 @@ def _load():
                                                   ctypes.c_float, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.cafeq_adaptive_round_step.argtypes = [vp, vp, i64, i64, i64, i64, ctypes.POINTER(QuantCfg),
                                               i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.cafeq_profile_enable.argtypes = [i32]
+    lib.cafeq_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float)]
     for n in EXPORTS[3:]:
         getattr(lib, n).restype = i32
     return lib
@@ -235,3 +238,14 @@ def adaptive_round_step(U, V, codesU, scalesU, codesV, scalesV, bits, group, k, 
                                          ctypes.byref(cfg), k, nb, rep, half, _ptr(codesU), _ptr(scalesU),
                                          _ptr(codesV), _ptr(scalesV), _ptr(status), _ptr(ws), _stream()))
     return status
+
+
+def profile_enable(on):
+    lib.cafeq_profile_enable(1 if on else 0)
+
+
+def profile_read():
+    """(number of fused-kernel launches since the last read, sum of their durations in ms)."""
+    ms = ctypes.c_float(0.0)
+    n = lib.cafeq_profile_read(ctypes.byref(ms))
+    return n, float(ms.value)

@@ -64,8 +64,8 @@ struct ReduceArgs {
   float* out;            // [nb][K][K]
 };
 
-// grid: nb transform blocks.  out_b = sum over the rep row-blocks q of block b, and over the
-// partials of q's segment, in fixed order.
+// grid: (nb transform blocks, K*K/1024).  out_b = sum over the rep row-blocks q of block b, and
+// over the partials of q's segment, in fixed order; each thread owns four consecutive elements.
 __global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceArgs a) {
   constexpr int kBatch = 64;
   __shared__ const float* src[kBatch];
@@ -73,9 +73,11 @@ __global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceArgs a) {
   __shared__ int nsrc, more, next_q, next_w;
   const int b = blockIdx.x;
   const int K = a.K;
+  const int i = (blockIdx.y * 256 + threadIdx.x) * 4;     // first of this thread's elements
   if (threadIdx.x == 0) { next_q = b * a.rep; next_w = -1; }
   __syncthreads();
-  for (int batch = 0;; ++batch) {
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (;;) {
     if (threadIdx.x == 0) {
       // gather up to kBatch (partial, scale) pairs, resuming where the last batch stopped
       int n = 0, q = next_q, wres = next_w;
@@ -104,16 +106,26 @@ __global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceArgs a) {
     }
     __syncthreads();
     const int n = nsrc;
-    for (int i = threadIdx.x; i < K * K; i += blockDim.x) {
-      float acc = 0.f;
-      for (int s = 0; s < n; ++s) acc += scl[s] * src[s][i];
-      const int r = i / K, c = i % K;
-      float* dst = a.out + size_t(b) * K * K + (a.transpose_out ? c * K + r : i);
-      *dst = batch == 0 ? acc : *dst + acc;
+    if (i < K * K) {
+      for (int s = 0; s < n; ++s) {
+        const float4 v = *reinterpret_cast<const float4*>(src[s] + i);
+        const float sc = scl[s];
+        acc.x += sc * v.x; acc.y += sc * v.y; acc.z += sc * v.z; acc.w += sc * v.w;
+      }
     }
     const int again = more;
     __syncthreads();
     if (!again) break;
+  }
+  if (i < K * K) {
+    float* dst = a.out + size_t(b) * K * K;
+    if (a.transpose_out) {
+      const int r = i / K, c = i % K;          // K is a multiple of 4: the four share a row
+      dst[(c + 0) * K + r] = acc.x; dst[(c + 1) * K + r] = acc.y;
+      dst[(c + 2) * K + r] = acc.z; dst[(c + 3) * K + r] = acc.w;
+    } else {
+      *reinterpret_cast<float4*>(dst + i) = acc;
+    }
   }
 }
 
@@ -328,7 +340,7 @@ int launch_reduce_grad(const CoreParams& p, int K, int G, int nb, int transpose_
   a.slot_grad = p.slot_grad; a.slot_hdr = p.slot_hdr; a.mt_per_seg = p.mt_per_seg; a.n_mt = p.n_mt;
   a.nwg = p.nwg; a.nseg = p.nseg; a.K = K; a.NBLK = L / K; a.NGRP = L / G; a.G = G; a.rep = p.rep;
   a.transpose_out = transpose_out; a.t = p.lse_t; a.lse_ms = lse_ms; a.out = out;
-  hipLaunchKernelGGL(reduce_grad_kernel, dim3(nb), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(reduce_grad_kernel, dim3(nb, (K * K + 1023) / 1024), dim3(256), 0, st, a);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }

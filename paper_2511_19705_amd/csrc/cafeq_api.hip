@@ -1,4 +1,7 @@
 // extern "C" entry points: argument validation and dispatch.  See include/cafeq.h.
+#include <utility>
+#include <vector>
+
 #include "xform_core.hpp"
 
 using namespace cafeq;
@@ -155,7 +158,9 @@ int plan_adaptive(const cafeq_quant_cfg* cfg, int k, int nb, int rep, int64_t ro
   ap->partial_floats = size_t(nb) * nz * 2 * k * k;
   Carver c(nullptr);
   c.take<float>(ap->partial_floats);
-  c.take<double>(size_t(nb) * k * 2 * k);
+  c.take<double>(size_t(nb) * k * 4 * k);
+  c.take<float>(size_t(nb) * k * k);
+  c.take<float>(size_t(nb) * k * k);
   c.take<float>(size_t(nb) * k * k);
   ap->bytes = c.off;
   return CAFEQ_OK;
@@ -174,7 +179,12 @@ void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep)
 }  // namespace
 
 namespace cafeq {
-int launch_core(int K, int G, int axis, const CoreParams& p, hipStream_t st) {
+namespace {
+struct ProfileState {
+  bool on = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> ev;
+} g_prof;
+int launch_core_raw(int K, int G, int axis, const CoreParams& p, hipStream_t st) {
   switch (K) {
     case 32: return launch_core_k32(G, axis, p, st);
     case 64: return launch_core_k64(G, axis, p, st);
@@ -182,6 +192,17 @@ int launch_core(int K, int G, int axis, const CoreParams& p, hipStream_t st) {
     case 256: return launch_core_k256(G, axis, p, st);
     default: return CAFEQ_ERR_UNSUPPORTED;
   }
+}
+}  // namespace
+int launch_core(int K, int G, int axis, const CoreParams& p, hipStream_t st) {
+  if (!g_prof.on || g_prof.ev.size() >= 4096) return launch_core_raw(K, G, axis, p, st);
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return CAFEQ_ERR_LAUNCH;
+  (void)hipEventRecord(e0, st);
+  const int rc = launch_core_raw(K, G, axis, p, st);
+  (void)hipEventRecord(e1, st);
+  g_prof.ev.emplace_back(e0, e1);
+  return rc;
 }
 size_t core_lds_bytes(int K, int G, bool do_grad) {
   switch (K) {
@@ -215,6 +236,28 @@ const char* cafeq_strerror(int status) {
 }
 
 int cafeq_version(void) { return 100; }
+
+int cafeq_profile_enable(int on) {
+  cafeq::g_prof.on = on != 0;
+  return CAFEQ_OK;
+}
+
+int cafeq_profile_read(float* total_ms) {
+  float total = 0.f;
+  int n = 0;
+  for (auto& pr : cafeq::g_prof.ev) {
+    float ms = 0.f;
+    if (hipEventSynchronize(pr.second) == hipSuccess && hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) {
+      total += ms;
+      ++n;
+    }
+    (void)hipEventDestroy(pr.first);
+    (void)hipEventDestroy(pr.second);
+  }
+  cafeq::g_prof.ev.clear();
+  if (total_ms) *total_ms = total;
+  return n;
+}
 
 size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b, const cafeq_xform* x,
                              const cafeq_quant_cfg* cfg) {
@@ -441,8 +484,10 @@ int cafeq_adaptive_round_step(const float* U, const float* V, int64_t rowsA, int
   hipStream_t st = static_cast<hipStream_t>(stream);
   Carver c(ws);
   float* partial = c.take<float>(ap.partial_floats);
-  double* work = c.take<double>(size_t(nb) * k * 2 * k);
+  double* work = c.take<double>(size_t(nb) * k * 4 * k);
   float* Cmat = c.take<float>(size_t(nb) * k * k);
+  float* Sinv = c.take<float>(size_t(nb) * k * k);
+  float* Rsum = c.take<float>(size_t(nb) * k * k);
   const QGrid grid = make_grid(cfg->bits);
 
   if (half == 0 || half == 1) {
@@ -450,7 +495,7 @@ int cafeq_adaptive_round_step(const float* U, const float* V, int64_t rowsA, int
     if ((rc = launch_gram_pair(CAFEQ_AXIS_COL, U, codesU, scalesU, rowsA, colsA, k, ap.GA, nb, 1, ap.chunkA,
                                ap.nchunkA, partial, st)))
       return rc;
-    if ((rc = launch_gj_solve(k, nb, ap.nchunkA, partial, work, Cmat, status, 2, 0, st))) return rc;
+    if ((rc = launch_gj_solve(k, nb, ap.nchunkA, partial, work, Sinv, Rsum, Cmat, status, 2, 0, st))) return rc;
     cafeq_mat mv{V, rowsB, colsB, colsB, CAFEQ_F32};
     CoreParams p;
     fill_common(&p, &mv, ap.planV, rep);
@@ -463,7 +508,7 @@ int cafeq_adaptive_round_step(const float* U, const float* V, int64_t rowsA, int
     if ((rc = launch_gram_pair(CAFEQ_AXIS_ROW, V, codesV, scalesV, rowsB, colsB, k, ap.GB, nb, rep, ap.chunkB,
                                ap.nchunkB, partial, st)))
       return rc;
-    if ((rc = launch_gj_solve(k, nb, rep * ap.nchunkB, partial, work, Cmat, status, 2, 1, st))) return rc;
+    if ((rc = launch_gj_solve(k, nb, rep * ap.nchunkB, partial, work, Sinv, Rsum, Cmat, status, 2, 1, st))) return rc;
     cafeq_mat mu{U, rowsA, colsA, colsA, CAFEQ_F32};
     CoreParams p;
     fill_common(&p, &mu, ap.planU, 1);

@@ -57,8 +57,8 @@ int launch_bgemm(bool ta, bool tb, const float* A, const float* B, float* C, int
 int launch_gram_pair(int axis, const float* X, const int8_t* codes, const float* scales, int64_t rows,
                      int64_t cols, int K, int G, int nb, int rep, int64_t chunk, int nchunk, float* partial,
                      hipStream_t st);
-int launch_gj_solve(int K, int nb, int nz, const float* partial, double* work, float* out, int* status,
-                    int status_stride, int status_offset, hipStream_t st);
+int launch_gj_solve(int K, int nb, int nz, const float* partial, double* work, float* Sinv, float* R,
+                    float* out, int* status, int status_stride, int status_offset, hipStream_t st);
 int launch_block_inverse(const float* T, int K, int nb, double* work, float* Tinv, float* rho_row,
                          float* rho_col, int* status, hipStream_t st);
 
