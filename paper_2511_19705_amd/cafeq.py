@@ -12,7 +12,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libcafeq.so")
+LIB_PATH = os.environ.get("CAFEQ_LIBRARY", os.path.join(_HERE, "libcafeq.so"))
 
 AXIS_COL, AXIS_ROW = 0, 1
 SIDE_T, SIDE_TINV = 0, 1

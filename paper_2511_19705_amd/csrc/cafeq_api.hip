@@ -166,6 +166,9 @@ int plan_adaptive(const cafeq_quant_cfg* cfg, int k, int nb, int rep, int64_t ro
   return CAFEQ_OK;
 }
 
+#ifdef CAFEQ_CORE_TIMING
+long long* g_core_dbg = nullptr;
+#endif
 void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep) {
   p->W = W->data; p->dtype = W->dtype; p->rows = W->rows; p->cols = W->cols; p->ld = W->ld;
   p->rep = rep; p->nseg = pl.nseg; p->nlines = pl.nlines; p->mt_per_seg = pl.mt_per_seg;
@@ -174,6 +177,9 @@ void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep)
   p->rG = nullptr; p->Zout = nullptr; p->codes = nullptr; p->scales = nullptr;
   p->slot_grad = nullptr; p->slot_hdr = nullptr;
   p->grid = make_grid(4);
+#ifdef CAFEQ_CORE_TIMING
+  p->dbg = g_core_dbg;
+#endif
 }
 
 }  // namespace
@@ -236,6 +242,10 @@ const char* cafeq_strerror(int status) {
 }
 
 int cafeq_version(void) { return 100; }
+
+#ifdef CAFEQ_CORE_TIMING
+void cafeq_debug_set_timing_buffer(long long* buf) { g_core_dbg = buf; }
+#endif
 
 int cafeq_profile_enable(int on) {
   cafeq::g_prof.on = on != 0;

@@ -45,7 +45,8 @@ struct Geo {
   static constexpr int NGRP = L / G;      // groups per segment
   static constexpr int RPG = G / 2;       // accumulator registers per group per lane
   static constexpr int LDA = K + 4;       // LDS row stride of a transform tile (floats)
-  static constexpr int RING_FLOATS = 2 * 32 * LDA;
+  static constexpr int RING_STAGES = 3;
+  static constexpr int RING_FLOATS = RING_STAGES * 32 * LDA;
   static constexpr int GACC_FLOATS = NBLK * K * (K + 1);
   static constexpr int A_VEC_PER_THREAD = (32 * K / 4 + kThreads - 1) / kThreads;
 };
@@ -77,10 +78,47 @@ struct CoreParams {
   float* scales;
   float* slot_grad;   // [nwg + nseg][NBLK*K*K]
   float* slot_hdr;    // [nwg + nseg][kHdrFloats]
+#ifdef CAFEQ_CORE_TIMING
+  long long* dbg;     // [nwg][8] phase cycle counts of wave 0 (experiments only)
+#endif
 };
 
 __device__ __forceinline__ int64_t chunk_begin(int64_t w, int64_t n_mt, int64_t nwg) {
   return (w * n_mt) / nwg;
+}
+
+// One 32 x K transform tile times the strip: 4 MFMAs per 128-bit LDS read, the reads issued
+// one group (four reads) ahead of the MFMAs that consume them.  bop(i) is the B operand of
+// MFMA i (i = 4*c + e uses input index 8c + 4h + e of the tile).
+template <int K, typename BF>
+__device__ __forceinline__ floatx16 tile_mfma(const float* abuf, BF bop) {
+  constexpr int NC = K / 8, PF = 4, NG = NC / PF;
+  floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float4 a[2][PF];
+#pragma unroll
+  for (int j = 0; j < PF; ++j) a[0][j] = *reinterpret_cast<const float4*>(abuf + 8 * j);
+#pragma unroll
+  for (int gq = 0; gq < NG; ++gq) {
+    if (gq + 1 < NG) {
+#pragma unroll
+      for (int j = 0; j < PF; ++j)
+        a[(gq + 1) & 1][j] = *reinterpret_cast<const float4*>(abuf + 8 * ((gq + 1) * PF + j));
+    }
+    // keep the reads above this point: the scheduler otherwise sinks each read to just
+    // before its first use and the matrix pipe idles for the whole LDS latency
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < PF; ++j) {
+      const int c = gq * PF + j;
+      const float4 v = a[gq & 1][j];
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(v.x, bop(4 * c + 0), acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(v.y, bop(4 * c + 1), acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(v.z, bop(4 * c + 2), acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(v.w, bop(4 * c + 3), acc, 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  return acc;
 }
 
 template <int K, int G, int AXIS>
@@ -104,42 +142,50 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
   if (mt0 >= mt1) return;
 
   const int tiles_per_mt = p.do_inverse ? 2 * NT : NT;
-  const int64_t total_tiles = (mt1 - mt0) * tiles_per_mt;
+  const int total_tiles = int(mt1 - mt0) * tiles_per_mt;
 
-  // Tile number `tile` (counted from the start of the chunk) is the 32 x K slab
-  // [32 outputs][K inputs] of one transform block.  Stored [out][in] it is contiguous;
-  // stored [in][out] (the caller's T used as T^T) it is a 32-column stripe, transposed
-  // on its way into LDS.
+  // The transform tiles are consumed in a fixed order: for each macro-tile, the NT forward
+  // tiles then (loss calls) the NT inverse tiles of its segment.  A tile is the 32 x K slab
+  // [32 outputs][K inputs] of one transform block.  Stored [out][in] it is contiguous; stored
+  // [in][out] (the caller's T used as T^T) it is a 32-column stripe, transposed on its way
+  // into LDS.  The fetch cursor runs two tiles ahead of the consumer and advances without
+  // divisions.
+  const int seg_first = int(mt0 / p.mt_per_seg);
+  const int mis_first = int(mt0 - int64_t(seg_first) * p.mt_per_seg);   // macro-tile within segment
+  const int mt_per_seg = int(p.mt_per_seg);
+  int f_tau = 0, f_seg = seg_first, f_mis = mis_first;   // fetch cursor
   float4 areg[g::A_VEC_PER_THREAD];
   bool areg_trans = false;
-  auto tile_fetch = [&](int64_t tile) {
-    const int64_t mt = mt0 + tile / tiles_per_mt;
-    int tau = int(tile % tiles_per_mt);
+  auto tile_fetch_next = [&]() {
+    int tau = f_tau;
     const float* base = p.Afwd;
     areg_trans = p.afwd_trans != 0;
     if (tau >= NT) { tau -= NT; base = p.Ainv; areg_trans = p.ainv_trans != 0; }
-    const int64_t seg = mt / p.mt_per_seg;
-    const int64_t blk = seg * NBLK + tau / KT;
-    const int64_t b = AXIS == CAFEQ_AXIS_ROW ? blk / p.rep : blk;
+    const int blk = f_seg * NBLK + tau / KT;
+    const int b = (AXIS == CAFEQ_AXIS_ROW && p.rep != 1) ? blk / p.rep : blk;
     const int t32 = tau % KT;
     if (!areg_trans) {
-      const float4* src = reinterpret_cast<const float4*>(base + (b * K + t32 * 32) * K);
+      const float4* src = reinterpret_cast<const float4*>(base + (int64_t(b) * K + t32 * 32) * K);
 #pragma unroll
       for (int i = 0; i < g::A_VEC_PER_THREAD; ++i) {
         const int id = tid + i * kThreads;
         if (id < 32 * K / 4) areg[i] = src[id];
       }
     } else {
-      const float* src = base + b * K * K + t32 * 32;
+      const float* src = base + int64_t(b) * K * K + t32 * 32;
 #pragma unroll
       for (int i = 0; i < g::A_VEC_PER_THREAD; ++i) {
         const int id = tid + i * kThreads;       // input row m = id / 8, four outputs 4*(id % 8)..
         if (id < 32 * K / 4) areg[i] = *reinterpret_cast<const float4*>(src + (id >> 3) * K + 4 * (id & 7));
       }
     }
+    if (++f_tau == tiles_per_mt) {
+      f_tau = 0;
+      if (++f_mis == mt_per_seg) { f_mis = 0; ++f_seg; }
+    }
   };
-  auto tile_commit = [&](int64_t tile) {
-    float* dst = ring + (tile & 1) * (32 * LDA);
+  auto tile_commit = [&](int stage) {
+    float* dst = ring + stage * (32 * LDA);
 #pragma unroll
     for (int i = 0; i < g::A_VEC_PER_THREAD; ++i) {
       const int id = tid + i * kThreads;
@@ -160,8 +206,12 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
 
   if (p.do_grad)
     for (int i = tid; i < g::GACC_FLOATS; i += kThreads) gacc[i] = 0.f;
-  tile_fetch(0);
+  tile_fetch_next();
   tile_commit(0);
+  if (total_tiles > 1) {
+    tile_fetch_next();
+    tile_commit(1);
+  }
   __syncthreads();
 
   // running partial sums (per lane)
@@ -171,10 +221,11 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
   for (int i = 0; i < NGRP; ++i) s_va2[i] = 0.f;
   float m_ref = -INFINITY;  // kLossLse: reference of this workgroup's exponentials
 
-  int64_t cur_seg = mt0 / p.mt_per_seg;
-  int64_t tile = 0;
+  int cur_seg = seg_first;
+  int tile = 0;        // tiles consumed so far
+  int stage = 0;       // ring stage of the tile being consumed; tile + 2 goes to stage + 2 (mod 3)
 
-  auto flush = [&](int64_t seg) {
+  auto flush = [&](int seg) {
     // reduce the per-lane sums and publish this (workgroup, segment) partial
     const int64_t slot = w + seg;
     float vals[kHdrVa2 + NGRP];
@@ -210,18 +261,13 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
     m_ref = -INFINITY;
   };
 
-  for (int64_t mt = mt0; mt < mt1; ++mt) {
-    const int64_t seg = mt / p.mt_per_seg;
-    if (seg != cur_seg) {
-      if (p.do_inverse || p.do_grad) flush(cur_seg);   // partial buffers exist only for loss calls
-      cur_seg = seg;
-    }
-    const int64_t line = (mt - seg * p.mt_per_seg) * kMacroLines + wave * kStripLines + ln;
+  // ---- weights of a strip: B operands, element j(f, h) of the lane's line in wreg[f].
+  // Loaded one macro-tile ahead (after the last use of the previous strip's weights).
+  float wreg[L / 2];
+  auto load_w = [&](int seg, int mis) {
+    const int64_t line = int64_t(mis) * kMacroLines + wave * kStripLines + ln;
     const bool valid = line < p.nlines;
-    const int64_t ax0 = seg * L;  // first axis index of the segment
-
-    // ---- weights of this strip: B operands, element j(f, h) of line `line` in wreg[f]
-    float wreg[L / 2];
+    const int64_t ax0 = int64_t(seg) * L;
     if (AXIS == CAFEQ_AXIS_COL) {
       if (p.dtype == CAFEQ_F32) {
         const float* src = static_cast<const float*>(p.W) + line * p.ld + ax0 + 4 * h;
@@ -251,31 +297,46 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
           wreg[f] = valid ? bf16_bits_to_f32(src[int64_t(8 * (f / 4) + (f % 4)) * p.ld]) : 0.f;
       }
     }
+  };
+  load_w(seg_first, mis_first);
+
+#ifdef CAFEQ_CORE_TIMING
+  long long tph[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  long long tlast = __builtin_readcyclecounter();
+#define CAFEQ_STAMP(i) { const long long tn = __builtin_readcyclecounter(); tph[i] += tn - tlast; tlast = tn; }
+#else
+#define CAFEQ_STAMP(i)
+#endif
+  int seg = seg_first, mis = mis_first;
+  for (int64_t mt = mt0; mt < mt1; ++mt) {
+    CAFEQ_STAMP(0)
+    if (seg != cur_seg) {
+      if (p.do_inverse || p.do_grad) flush(cur_seg);   // partial buffers exist only for loss calls
+      cur_seg = seg;
+    }
+    const int64_t line = int64_t(mis) * kMacroLines + wave * kStripLines + ln;
+    const bool valid = line < p.nlines;
+    const int64_t ax0 = int64_t(seg) * L;  // first axis index of the segment
+    // the macro-tile after this one
+    int nseg_ = seg, nmis = mis + 1;
+    if (nmis == mt_per_seg) { nmis = 0; ++nseg_; }
 
     // ---- forward transform: acc[t] = Afwd tile t (32 x K) times the strip's block
     floatx16 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      const bool more = tile + 1 < total_tiles;
-      if (more) tile_fetch(tile + 1);
-      const float* abuf = ring + (tile & 1) * (32 * LDA) + ln * LDA + 4 * h;
-      floatx16 a16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      constexpr int dummy = 0; (void)dummy;
+      const bool more = tile + 2 < total_tiles;
+      if (more) tile_fetch_next();
+      const float* abuf = ring + stage * (32 * LDA) + ln * LDA + 4 * h;
       const int wb = (t / KT) * (K / 2);
-#pragma unroll
-      for (int c = 0; c < K / 8; ++c) {
-        const float4 a = *reinterpret_cast<const float4*>(abuf + 8 * c);
-        a16 = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, wreg[wb + 4 * c + 0], a16, 0, 0, 0);
-        a16 = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, wreg[wb + 4 * c + 1], a16, 0, 0, 0);
-        a16 = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, wreg[wb + 4 * c + 2], a16, 0, 0, 0);
-        a16 = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, wreg[wb + 4 * c + 3], a16, 0, 0, 0);
-      }
-      acc[t] = a16;
-      if (more) tile_commit(tile + 1);
+      acc[t] = tile_mfma<K>(abuf, [&](int i) { return wreg[wb + i]; });
+      if (more) tile_commit(stage == 0 ? 2 : stage - 1);
       __syncthreads();
       ++tile;
+      stage = stage == 2 ? 0 : stage + 1;
     }
 
+    CAFEQ_STAMP(1)
     // ---- optional raw output Z
     if (p.Zout && valid) {
       if (AXIS == CAFEQ_AXIS_COL) {
@@ -295,6 +356,7 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
       }
     }
 
+    CAFEQ_STAMP(2)
     const bool want_q = p.codes || p.scales || p.do_inverse;
     if (want_q) {
       // ---- per-group absmax (+ argmax), codes, error in place
@@ -409,33 +471,39 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
       }
     }
 
+    CAFEQ_STAMP(3)
+    // ---- the next strip's weights: wreg is dead from here on, the loads land during the
+    // inverse phase
+    if (mt + 1 < mt1) load_w(nseg_, nmis);
+
+    CAFEQ_STAMP(4)
     // ---- inverse transform of the error and the l2 proxy
     if (p.do_inverse) {
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
-        const bool more = tile + 1 < total_tiles;
-        if (more) tile_fetch(tile + 1);
-        const float* abuf = ring + (tile & 1) * (32 * LDA) + ln * LDA + 4 * h;
-        floatx16 d = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        const bool more = tile + 2 < total_tiles;
+        if (more) tile_fetch_next();
+        const float* abuf = ring + stage * (32 * LDA) + ln * LDA + 4 * h;
         const int eb = (t / KT) * (K / 2);   // first error register of this tile's block
-#pragma unroll
-        for (int c = 0; c < K / 8; ++c) {
-          const float4 a = *reinterpret_cast<const float4*>(abuf + 8 * c);
-          const int f = eb + 4 * c;
-          d = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, acc[(f + 0) / 16][(f + 0) % 16], d, 0, 0, 0);
-          d = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, acc[(f + 1) / 16][(f + 1) % 16], d, 0, 0, 0);
-          d = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, acc[(f + 2) / 16][(f + 2) % 16], d, 0, 0, 0);
-          d = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, acc[(f + 3) / 16][(f + 3) % 16], d, 0, 0, 0);
-        }
+        const floatx16 d = tile_mfma<K>(abuf, [&](int i) { return acc[(eb + i) / 16][(eb + i) % 16]; });
 #pragma unroll
         for (int v = 0; v < 16; ++v) s_l2 = fmaf(d[v], d[v], s_l2);
-        if (more) tile_commit(tile + 1);
+        if (more) tile_commit(stage == 0 ? 2 : stage - 1);
         __syncthreads();
         ++tile;
+        stage = stage == 2 ? 0 : stage + 1;
       }
     }
+    CAFEQ_STAMP(5)
+    seg = nseg_;
+    mis = nmis;
   }
   if (p.do_inverse || p.do_grad) flush(cur_seg);
+#ifdef CAFEQ_CORE_TIMING
+  CAFEQ_STAMP(6)
+  if (p.dbg && lane == 0 && wave == 0)
+    for (int i = 0; i < 8; ++i) p.dbg[blockIdx.x * 8 + i] = tph[i];
+#endif
 }
 
 }  // namespace cafeq

@@ -27,6 +27,7 @@ def check_codes(codes_gpu, codes_ref, z_ref, scales_ref, axis, group, tie_tol=2e
         s_el = np.repeat(scales_ref.astype(np.float64), g, axis=1 if axis == 0 else 0)
         x = np.abs(z_ref[diff] / s_el[diff])
         assert np.all(np.abs(x - np.floor(x) - 0.5) < tie_tol), "a differing code is not at a rounding tie"
+    print("codes differing from the oracle: %d of %d (%.2e)" % (n_bad, codes_ref.size, n_bad / codes_ref.size))
     return n_bad
 
 
