@@ -94,7 +94,8 @@ typedef enum {
   CAFEQ_CALL_PROXY_LOSS = 1,
   CAFEQ_CALL_DUAL_PROXY_LOSS = 2,
   CAFEQ_CALL_ADAPTIVE_ROUND = 3,
-  CAFEQ_CALL_BLOCK_INVERSE = 4 /* reads x->k and x->nb only */
+  CAFEQ_CALL_BLOCK_INVERSE = 4,  /* reads x->k and x->nb only */
+  CAFEQ_CALL_APPLY_TRANSFORM = 5 /* reads x->k and x->nb only */
 } cafeq_call_id;
 
 const char* cafeq_strerror(int status);
@@ -125,7 +126,7 @@ int cafeq_rtn_quantize(const cafeq_mat* W, const cafeq_quant_cfg* cfg, int8_t* c
  * (CAFEQ_SIDE_TINV)  (paper Sec. 4.1 block-diagonal M; Sec. 4.2 U = W1 M, V = M^-1 W2).
  * Z: float32 [rows][cols] dense, must not alias W. */
 int cafeq_apply_transform(const cafeq_mat* W, const cafeq_xform* x, int axis, int side,
-                          float* Z, void* stream);
+                          float* Z, void* ws, void* stream);
 
 /* One evaluation for a single matrix (paper Sec. 4 and 4.1), transform along cfg->axis:
  *   Z = transform(W, T); Zq = dequant(Q(Z)); E = Zq - Z; D = transform(E, Tinv)

@@ -62,7 +62,7 @@ def _load():
                                           ctypes.POINTER(Xform), ctypes.POINTER(QuantCfg)]
     lib.cafeq_block_inverse.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.cafeq_rtn_quantize.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(QuantCfg), vp, vp, vp, vp, vp]
-    lib.cafeq_apply_transform.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Xform), i32, i32, vp, vp]
+    lib.cafeq_apply_transform.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Xform), i32, i32, vp, vp, vp]
     lib.cafeq_proxy_loss_fwd_bwd.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Xform),
                                              ctypes.POINTER(QuantCfg), vp, vp, vp, vp, vp, vp]
     lib.cafeq_dual_proxy_loss_fwd_bwd.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Mat),
@@ -170,7 +170,8 @@ def apply_transform(W, T, Tinv=None, axis=AXIS_COL, side=SIDE_T, rep=1):
     m = mat(W)
     x = xform(T, Tinv, rep)
     Z = torch.empty(W.shape, dtype=torch.float32, device=W.device)
-    _check(lib.cafeq_apply_transform(ctypes.byref(m), ctypes.byref(x), axis, side, _ptr(Z), _stream()))
+    ws = workspace(int(lib.cafeq_workspace_bytes(5, None, None, ctypes.byref(x), None)), W.device)
+    _check(lib.cafeq_apply_transform(ctypes.byref(m), ctypes.byref(x), axis, side, _ptr(Z), _ptr(ws), _stream()))
     return Z
 
 

@@ -21,6 +21,34 @@ __global__ __launch_bounds__(256) void rho_kernel(const float* __restrict__ P, i
   }
 }
 
+// Operand planes of the fused core.  Element [out][in] of the k x k operand -- src_b (trans == 0) or
+// src_b^T (trans == 1) -- is split exactly into bfloat16 parts x = hi + mid + lo (+ a residual below
+// 2^-24 |x|) and stored in the order the core streams it through its LDS ring:
+//   dst[b][stage = in / 32][part][out][32 inputs of the stage]
+// with the 32 inputs of a row arranged as four 16-byte chunks (MFMA step c2 = (in % 32) / 16, lane
+// half h -> chunk 2*c2 + h, holding inputs 16*c2 + 8u + 4h + e at position 4u + e), the chunk stored
+// at chunk ^ ((out >> 2) & 3) (LDS bank swizzle).
+__global__ __launch_bounds__(256) void split_planes_kernel(const float* __restrict__ src, int K, int trans,
+                                                            int nplanes, uint16_t* __restrict__ dst) {
+  const float* sb = src + size_t(blockIdx.x) * K * K;
+  uint16_t* db = dst + size_t(blockIdx.x) * nplanes * K * K;
+  for (int e = threadIdx.x; e < K * K; e += blockDim.x) {
+    const int out = e / K, in = e % K;
+    const int stage = in / 32, w32 = in % 32, c2 = w32 / 16, w16 = w32 % 16;
+    const int u = w16 / 8, hh = (w16 % 8) / 4, ee = w16 % 4;
+    const int chunk = (2 * c2 + hh) ^ ((out >> 2) & 3);
+    const size_t at = (size_t(stage) * nplanes * K + out) * 32 + chunk * 8 + 4 * u + ee;
+    float x = trans ? sb[in * K + out] : sb[out * K + in];
+    for (int pl = 0; pl < nplanes; ++pl) {
+      uint32_t bits = __float_as_uint(x);
+      bits += 0x7FFFu + ((bits >> 16) & 1u);          // round to nearest even
+      const uint16_t part = uint16_t(bits >> 16);
+      db[at + size_t(pl) * K * 32] = part;
+      x -= __uint_as_float(uint32_t(part) << 16);
+    }
+  }
+}
+
 // rG[gi] = sum of rho over the axis indices of group gi (axis index a -> block (a/K)/rep, a%K).
 // One wave per group.
 __global__ __launch_bounds__(256) void rho_group_kernel(const float* __restrict__ rho, int K, int rep,
@@ -316,6 +344,11 @@ __global__ __launch_bounds__(256) void bgemm32_kernel(const float* __restrict__ 
 
 }  // namespace
 
+int launch_split_planes(const float* src, int K, int nb, int trans, int nplanes, uint16_t* dst, hipStream_t st) {
+  hipLaunchKernelGGL(split_planes_kernel, dim3(nb), dim3(256), 0, st, src, K, trans, nplanes, dst);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
 int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_t st) {
   hipLaunchKernelGGL(rho_kernel, dim3(nb), dim3(256), 0, st, P, K, by_row, rho);
   CAFEQ_CHECK_LAUNCH();

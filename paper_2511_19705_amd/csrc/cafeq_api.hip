@@ -70,12 +70,14 @@ struct Carver {
 };
 
 struct SingleWs {
-  float *rho, *rG, *slot_grad, *slot_hdr, *mmid, *x1; double* lse_ms; size_t bytes;
+  float *rho, *rG, *slot_grad, *slot_hdr, *mmid, *x1; double* lse_ms; uint16_t *pfwd, *pinv; size_t bytes;
 };
 SingleWs carve_single(void* ws, const CorePlan& pl, int nb, bool grad) {
   Carver c(ws);
   SingleWs w;
   w.lse_ms = c.take<double>(2);
+  w.pfwd = c.take<uint16_t>(size_t(nb) * kFwdPlanes * pl.K * pl.K);
+  w.pinv = c.take<uint16_t>(size_t(nb) * kInvPlanes * pl.K * pl.K);
   w.rho = c.take<float>(size_t(nb) * pl.K);
   w.rG = c.take<float>(size_t(pl.naxis / pl.G));
   w.slot_hdr = c.take<float>(size_t(pl.nslot) * kHdrFloats);
@@ -87,12 +89,18 @@ SingleWs carve_single(void* ws, const CorePlan& pl, int nb, bool grad) {
 }
 
 struct DualWs {
-  float *hdrA, *hdrB, *gradA, *gradB, *gp, *x1; double* lse_ms; size_t bytes;
+  float *hdrA, *hdrB, *gradA, *gradB, *gp, *x1; double* lse_ms;
+  uint16_t *pfwdA, *pinvA, *pfwdB, *pinvB; size_t bytes;
 };
 DualWs carve_dual(void* ws, const CorePlan& pa, const CorePlan& pb, int nb, bool grad) {
   Carver c(ws);
   DualWs w;
   w.lse_ms = c.take<double>(2);
+  const size_t kk = size_t(nb) * pa.K * pa.K;
+  w.pfwdA = c.take<uint16_t>(kk * kFwdPlanes);
+  w.pinvA = c.take<uint16_t>(kk * kInvPlanes);
+  w.pfwdB = c.take<uint16_t>(kk * kFwdPlanes);
+  w.pinvB = c.take<uint16_t>(kk * kInvPlanes);
   w.hdrA = c.take<float>(size_t(pa.nslot + pb.nslot) * kHdrFloats);   // A then B, contiguous
   w.hdrB = w.hdrA ? w.hdrA + size_t(pa.nslot) * kHdrFloats : nullptr;
   w.gradA = c.take<float>(grad ? size_t(pa.nslot) * pa.slot_grad_floats : 0);
@@ -162,6 +170,7 @@ int plan_adaptive(const cafeq_quant_cfg* cfg, int k, int nb, int rep, int64_t ro
   c.take<float>(size_t(nb) * k * k);
   c.take<float>(size_t(nb) * k * k);
   c.take<float>(size_t(nb) * k * k);
+  c.take<uint16_t>(size_t(nb) * kFwdPlanes * k * k);
   ap->bytes = c.off;
   return CAFEQ_OK;
 }
@@ -275,6 +284,9 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
     case CAFEQ_CALL_RTN_QUANTIZE:
       if (!a) return 0;
       return align_up(rtn_partials_capacity(a->rows, a->cols) * sizeof(double), 256);
+    case CAFEQ_CALL_APPLY_TRANSFORM:
+      if (!x) return 0;
+      return align_up(size_t(x->nb) * kFwdPlanes * x->k * x->k * sizeof(uint16_t), 256);
     case CAFEQ_CALL_BLOCK_INVERSE:
       if (!x) return 0;
       return align_up(size_t(x->nb) * x->k * 2 * x->k * sizeof(double), 256);
@@ -338,7 +350,7 @@ int cafeq_block_inverse(const float* T, int k, int nb, float* Tinv, float* rho_r
 }
 
 int cafeq_apply_transform(const cafeq_mat* W, const cafeq_xform* x, int axis, int side, float* Z,
-                          void* stream) {
+                          void* ws, void* stream) {
   int rc = check_mat(W);
   if (rc) return rc;
   if (side != CAFEQ_SIDE_T && side != CAFEQ_SIDE_TINV) return CAFEQ_ERR_INVALID_ARG;
@@ -348,17 +360,21 @@ int cafeq_apply_transform(const cafeq_mat* W, const cafeq_xform* x, int axis, in
   if (rc) return rc;
   if (!Z) return CAFEQ_ERR_INVALID_ARG;
   if (!aligned16(Z)) return CAFEQ_ERR_BAD_ALIGN;
+  if (!ws) return CAFEQ_ERR_WORKSPACE;
   const bool col = axis == CAFEQ_AXIS_COL;
   CorePlan pl;
   rc = make_plan(x->k, x->k, col ? W->rows : W->cols, col ? W->cols : W->rows, &pl);
   if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint16_t* planes = static_cast<uint16_t*>(ws);
+  if ((rc = launch_split_planes(side == CAFEQ_SIDE_T ? x->T : x->Tinv, x->k, x->nb, col ? 1 : 0, kFwdPlanes,
+                                planes, st)))
+    return rc;
   CoreParams p;
   fill_common(&p, W, pl, x->rep);
-  p.Afwd = side == CAFEQ_SIDE_T ? x->T : x->Tinv;
-  p.afwd_trans = col ? 1 : 0;
-  p.Ainv = nullptr; p.ainv_trans = 0;
+  p.Afwd = planes; p.Ainv = nullptr;
   p.Zout = Z;
-  return launch_core(x->k, x->k, axis, p, static_cast<hipStream_t>(stream));
+  return launch_core(x->k, x->k, axis, p, st);
 }
 
 int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const cafeq_quant_cfg* cfg,
@@ -385,7 +401,10 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   CorePlan pl;
   rc = make_plan(K, G, nlines, naxis, &pl);
   if (rc) return rc;
-  if (core_lds_bytes(K, G, gradT != nullptr) > kLdsLimit) return CAFEQ_ERR_UNSUPPORTED;
+  {
+    const size_t lds = core_lds_bytes(K, G, gradT != nullptr);
+    if (lds == 0 || lds > kLdsLimit) return CAFEQ_ERR_UNSUPPORTED;
+  }
   hipStream_t st = static_cast<hipStream_t>(stream);
   SingleWs w = carve_single(ws, pl, nb, gradT != nullptr);
   const QGrid grid = make_grid(cfg->bits);
@@ -397,8 +416,10 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
 
   CoreParams p;
   fill_common(&p, W, pl, x->rep);
-  p.Afwd = x->T; p.Ainv = x->Tinv;
-  p.afwd_trans = p.ainv_trans = col ? 1 : 0;
+  // forward operand [out][in]: T^T (COL) or T (ROW); inverse operand: Tinv^T or Tinv
+  if ((rc = launch_split_planes(x->T, K, nb, col ? 1 : 0, kFwdPlanes, w.pfwd, st))) return rc;
+  if ((rc = launch_split_planes(x->Tinv, K, nb, col ? 1 : 0, kInvPlanes, w.pinv, st))) return rc;
+  p.Afwd = w.pfwd; p.Ainv = w.pinv;
   p.grid = grid; p.do_inverse = 1; p.do_grad = gradT ? 1 : 0; p.loss_kind = kLossSur; p.beta = beta;
   p.rG = w.rG; p.codes = codes; p.scales = scales; p.slot_grad = w.slot_grad; p.slot_hdr = w.slot_hdr;
   if ((rc = launch_core(K, G, cfg->axis, p, st))) return rc;
@@ -439,8 +460,10 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   if ((rc = make_plan(K, GA, A->rows, A->cols, &pa))) return rc;
   if ((rc = make_plan(K, GB, B->cols, B->rows, &pb))) return rc;
   const bool grad = gradT != nullptr;
-  if (core_lds_bytes(K, GA, grad) > kLdsLimit || core_lds_bytes(K, GB, grad) > kLdsLimit)
-    return CAFEQ_ERR_UNSUPPORTED;
+  {
+    const size_t la = core_lds_bytes(K, GA, grad), lb = core_lds_bytes(K, GB, grad);
+    if (la == 0 || lb == 0 || la > kLdsLimit || lb > kLdsLimit) return CAFEQ_ERR_UNSUPPORTED;
+  }
   hipStream_t st = static_cast<hipStream_t>(stream);
   DualWs w = carve_dual(ws, pa, pb, nb, grad);
   const QGrid grid = make_grid(cfg->bits);
@@ -448,14 +471,18 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
 
   CoreParams a;
   fill_common(&a, A, pa, 1);
-  a.Afwd = x->T; a.Ainv = x->Tinv; a.afwd_trans = a.ainv_trans = 1;
+  if ((rc = launch_split_planes(x->T, K, nb, 1, kFwdPlanes, w.pfwdA, st))) return rc;
+  if ((rc = launch_split_planes(x->Tinv, K, nb, 1, kInvPlanes, w.pinvA, st))) return rc;
+  if ((rc = launch_split_planes(x->Tinv, K, nb, 0, kFwdPlanes, w.pfwdB, st))) return rc;
+  if ((rc = launch_split_planes(x->T, K, nb, 0, kInvPlanes, w.pinvB, st))) return rc;
+  a.Afwd = w.pfwdA; a.Ainv = w.pinvA;
   a.grid = grid; a.do_inverse = 1; a.do_grad = grad ? 1 : 0; a.loss_kind = kLossLse; a.lse_t = lse_t;
   a.codes = codesU; a.scales = scalesU; a.slot_grad = w.gradA; a.slot_hdr = w.hdrA;
   if ((rc = launch_core(K, GA, CAFEQ_AXIS_COL, a, st))) return rc;
 
   CoreParams b;
   fill_common(&b, B, pb, x->rep);
-  b.Afwd = x->Tinv; b.Ainv = x->T; b.afwd_trans = b.ainv_trans = 0;
+  b.Afwd = w.pfwdB; b.Ainv = w.pinvB;
   b.grid = grid; b.do_inverse = 1; b.do_grad = grad ? 1 : 0; b.loss_kind = kLossLse; b.lse_t = lse_t;
   b.codes = codesV; b.scales = scalesV; b.slot_grad = w.gradB; b.slot_hdr = w.hdrB;
   if ((rc = launch_core(K, GB, CAFEQ_AXIS_ROW, b, st))) return rc;
@@ -498,6 +525,7 @@ int cafeq_adaptive_round_step(const float* U, const float* V, int64_t rowsA, int
   float* Cmat = c.take<float>(size_t(nb) * k * k);
   float* Sinv = c.take<float>(size_t(nb) * k * k);
   float* Rsum = c.take<float>(size_t(nb) * k * k);
+  uint16_t* planes = c.take<uint16_t>(size_t(nb) * kFwdPlanes * k * k);
   const QGrid grid = make_grid(cfg->bits);
 
   if (half == 0 || half == 1) {
@@ -509,7 +537,8 @@ int cafeq_adaptive_round_step(const float* U, const float* V, int64_t rowsA, int
     cafeq_mat mv{V, rowsB, colsB, colsB, CAFEQ_F32};
     CoreParams p;
     fill_common(&p, &mv, ap.planV, rep);
-    p.Afwd = Cmat; p.afwd_trans = 0; p.Ainv = nullptr; p.ainv_trans = 0;
+    if ((rc = launch_split_planes(Cmat, k, nb, 0, kFwdPlanes, planes, st))) return rc;
+    p.Afwd = planes; p.Ainv = nullptr;
     p.grid = grid; p.codes = codesV; p.scales = scalesV;
     if ((rc = launch_core(k, ap.GB, CAFEQ_AXIS_ROW, p, st))) return rc;
   }
@@ -522,7 +551,8 @@ int cafeq_adaptive_round_step(const float* U, const float* V, int64_t rowsA, int
     cafeq_mat mu{U, rowsA, colsA, colsA, CAFEQ_F32};
     CoreParams p;
     fill_common(&p, &mu, ap.planU, 1);
-    p.Afwd = Cmat; p.afwd_trans = 0; p.Ainv = nullptr; p.ainv_trans = 0;
+    if ((rc = launch_split_planes(Cmat, k, nb, 0, kFwdPlanes, planes, st))) return rc;
+    p.Afwd = planes; p.Ainv = nullptr;
     p.grid = grid; p.codes = codesU; p.scales = scalesU;
     if ((rc = launch_core(k, ap.GA, CAFEQ_AXIS_COL, p, st))) return rc;
   }

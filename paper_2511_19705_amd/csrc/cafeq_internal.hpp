@@ -42,6 +42,7 @@ size_t core_lds_bytes_k256(int G, bool do_grad);
 int device_cu_count();
 
 // aux_kernels.hip
+int launch_split_planes(const float* src, int K, int nb, int trans, int nplanes, uint16_t* dst, hipStream_t st);
 int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_t st);
 int launch_rho_groups(const float* rho, int K, int rep, int G, int64_t ngroups, float* rG, hipStream_t st);
 int launch_init_hdr(float* hdr, int64_t nslot, hipStream_t st);

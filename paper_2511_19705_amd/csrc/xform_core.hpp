@@ -3,24 +3,39 @@
 // Work decomposition.  A "line" is one vector along the transformed axis (a row of W for
 // AXIS_COL, a column for AXIS_ROW).  The axis is cut into segments of L = max(K, G)
 // elements (K: transform block, G: quantization group), so a segment holds whole blocks
-// and whole groups.  One wavefront owns a strip of 32 lines x one segment:
-//   Z^T[j][line] = sum_m Afwd[j][m] * W[line][m]         v_mfma_f32_32x32x2_f32
-// with the transform tile as the MFMA A operand (from LDS) and the weights as the B
-// operand, read from global memory straight into the lane that consumes them.  In the
+// and whole groups.  One wavefront owns a strip of 32 lines x one segment and computes
+//   Z^T[j][line] = sum_m Afwd[j][m] * W[line][m]
+// on the matrix cores with the transform tile as the A operand (from LDS) and the weights as
+// the B operand, read from global memory straight into the lane that consumes them.  In the
 // 32x32 accumulator layout a lane then holds, for ONE line, the axis indices
 //   j(f, h) = 8*(f/4) + 4*h + f%4,   f = 0..L/2-1,  h = lane/32,
 // so a group's absmax is a scan over registers plus one exchange with lane^32, the
-// quantization error E replaces Z in the same registers, and -- because the MFMA B operand
-// of lane (line, h) at step (c, s) is exactly element j(4c+s, h) -- those registers feed the
-// inverse transform D^T = Ainv * E^T without any data movement.  Z, E and D never leave
-// the register file; W is read from memory once.
+// quantization error E replaces Z in the same registers, and -- because registers 8c..8c+7
+// of lane (line, h) are exactly the eight inputs 16c + 8u + 4h + e (u < 2, e < 4) that this
+// lane feeds to MFMA step c -- those registers are the B operand of the inverse transform
+// D^T = Ainv * E^T without any data movement.  Z, E and D never leave the register file; W
+// is read from memory once.
 //
-// The transform tiles (32 outputs x K inputs, fp32) are streamed through a double-buffered
-// LDS ring shared by the workgroup's waves (one barrier per tile step); they come from the
-// L2, where the blocks of a segment stay resident while consecutive macro-tiles use them.
-// Workgroups are persistent: each takes a contiguous range of macro-tiles (segment-major),
-// keeps loss partial sums in registers and the dense k x k gradient accumulator in LDS
-// (float atomics: lanes scatter rank-1 updates s * W[line][:] into row j* of the block), and
+// Arithmetic.  There is no fast fp32 matrix path on this part (157 TFLOP/s against
+// 2.5 PFLOP/s for 16-bit operands), so every fp32 operand x is split exactly into bfloat16
+// parts x = hi + mid + lo (8 mantissa bits each) and the products are formed with
+// v_mfma_f32_32x32x16_bf16, accumulating in fp32:
+//   forward  : 6 products (hi.hi, hi.mid, mid.hi, mid.mid, hi.lo, lo.hi) -- the dropped terms are
+//              below 2^-24 relative, so Z is as accurate as an fp32 FMA chain (measured: slightly
+//              better than the fp32 MFMA), which the tie-exact code comparison needs;
+//   inverse  : 3 products (hi.hi, hi.mid, mid.hi), relative error ~5e-6 per element of D, ample for
+//              the 1e-4 budget of the l2 proxy;
+//   gradient : d/dZ is sparse (one non-zero per group, at the arg-max).  G[j][m] = sum_lines
+//              S[line][j] W[line][m] contracts over LINES, which live in lanes; the strip's W parts
+//              (hi, mid) are therefore staged through LDS transposed ([m][line]) and each wave
+//              accumulates its share of the k x k tiles in registers with 3 products per step.
+// Products of bfloat16 pairs are exact in fp32, so the only roundings are the accumulations.
+//
+// The transform tiles (32 outputs x K inputs, pre-split into bf16 planes by a preparation
+// kernel, columns permuted so that a lane's eight inputs are one 128-bit LDS read) stream
+// through an LDS ring shared by the workgroup's waves, fetched two tile-steps ahead from L2;
+// one barrier per tile step.  Workgroups are persistent: each takes a contiguous range of
+// macro-tiles (segment-major), keeps loss partial sums and the gradient tiles in registers and
 // writes one partial per (workgroup, segment) that a finishing kernel reduces in fixed order.
 #pragma once
 #include "cafeq_internal.hpp"
@@ -28,13 +43,22 @@
 namespace cafeq {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kNW = 4;              // waves per workgroup
 constexpr int kThreads = kNW * 64;  // threads per workgroup
 constexpr int kStripLines = 32;     // lines per wave
 constexpr int kMacroLines = kNW * kStripLines;
+constexpr int kFwdPlanes = 3, kInvPlanes = 2;
 
 __host__ __device__ constexpr int cmax(int a, int b) { return a > b ? a : b; }
+
+// header layout of one partial (floats)
+constexpr int kHdrL2 = 0, kHdrErrZ = 1, kHdrWsq = 2, kHdrSur = 3, kHdrMref = 4, kHdrVa2 = 8;
+constexpr int kHdrFloats = 8 + 32;  // up to 32 groups per segment
 
 template <int K, int G>
 struct Geo {
@@ -44,16 +68,26 @@ struct Geo {
   static constexpr int KT = K / 32;       // tiles per block
   static constexpr int NGRP = L / G;      // groups per segment
   static constexpr int RPG = G / 2;       // accumulator registers per group per lane
-  static constexpr int LDA = K + 4;       // LDS row stride of a transform tile (floats)
-  static constexpr int RING_STAGES = 3;
-  static constexpr int RING_FLOATS = RING_STAGES * 32 * LDA;
-  static constexpr int GACC_FLOATS = NBLK * K * (K + 1);
-  static constexpr int A_VEC_PER_THREAD = (32 * K / 4 + kThreads - 1) / kThreads;
+  // A ring stage holds the operand slab of 32 consecutive inputs of one block: all K output
+  // rows, 64 bytes per row (four 16-byte chunks: MFMA step 2s+c2, lane half h -> chunk 2*c2+h,
+  // stored at chunk ^ ((row >> 2) & 3) so that 16 lanes reading one chunk hit 64 distinct banks)
+  static constexpr int PLANEB = K * 64;                    // one plane of one stage
+  static constexpr int STAGEB = kFwdPlanes * PLANEB;       // one ring stage
+  static constexpr int RING_STAGES = K <= 128 ? 3 : 2;
+  static constexpr int RINGB = RING_STAGES * STAGEB;
+  // gradient staging: W parts (hi, mid) transposed [m][line], per-group arg-max / coefficient
+  static constexpr int WST_ROWB = 2 * kMacroLines + 16;
+  static constexpr int WST_PLANEB = L * WST_ROWB;
+  static constexpr int GRADB = 2 * WST_PLANEB + NGRP * kMacroLines * (2 + 4);
+  static constexpr int GT_ROWS = (NT + kNW - 1) / kNW;     // tile rows of the gradient per wave
+  static constexpr int GT = GT_ROWS * KT;                  // gradient tiles per wave
+  static constexpr int A_VEC_PER_THREAD = (STAGEB / 16 + kThreads - 1) / kThreads;
+  static constexpr int MISCB = (kNW * kHdrFloats + kNW + 4) * 4;
+  // the gradient needs its staging area next to the ring in the 160 KB of LDS and at most
+  // eight accumulator tiles per wave
+  static constexpr bool GRAD_OK = RINGB + GRADB + MISCB <= 160 * 1024 && GT <= 8;
+  static constexpr int GT_ALLOC = GRAD_OK ? GT : 1;
 };
-
-// header layout of one partial (floats)
-constexpr int kHdrL2 = 0, kHdrErrZ = 1, kHdrWsq = 2, kHdrSur = 3, kHdrMref = 4, kHdrVa2 = 8;
-constexpr int kHdrFloats = 8 + 32;  // up to 32 groups per segment
 
 enum : int { kLossSur = 0, kLossLse = 1 };
 
@@ -61,10 +95,9 @@ struct CoreParams {
   const void* W;
   int dtype;
   int64_t rows, cols, ld;
-  const float* Afwd;  // [nb][K][K]; element [out][in], or [in][out] when afwd_trans
-  const float* Ainv;  // [nb][K][K]; likewise with ainv_trans
-  int afwd_trans, ainv_trans;
-  int rep;            // AXIS_ROW: row-block q uses block q / rep
+  const uint16_t* Afwd;  // [nb][K/32 stages][3 planes][K][32] bf16: forward operand in ring-stage order
+  const uint16_t* Ainv;  // [nb][K/32 stages][2 planes][K][32] bf16: inverse operand
+  int rep;               // AXIS_ROW: row-block q uses block q / rep
   int nseg;
   int64_t nlines;
   int64_t mt_per_seg, n_mt;
@@ -78,61 +111,43 @@ struct CoreParams {
   float* scales;
   float* slot_grad;   // [nwg + nseg][NBLK*K*K]
   float* slot_hdr;    // [nwg + nseg][kHdrFloats]
-#ifdef CAFEQ_CORE_TIMING
-  long long* dbg;     // [nwg][8] phase cycle counts of wave 0 (experiments only)
-#endif
 };
 
 __device__ __forceinline__ int64_t chunk_begin(int64_t w, int64_t n_mt, int64_t nwg) {
   return (w * n_mt) / nwg;
 }
 
-// One 32 x K transform tile times the strip: 4 MFMAs per 128-bit LDS read, the reads issued
-// one group (four reads) ahead of the MFMAs that consume them.  bop(i) is the B operand of
-// MFMA i (i = 4*c + e uses input index 8c + 4h + e of the tile).
-template <int K, typename BF>
-__device__ __forceinline__ floatx16 tile_mfma(const float* abuf, BF bop) {
-  constexpr int NC = K / 8, PF = 4, NG = NC / PF;
-  floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  float4 a[2][PF];
-#pragma unroll
-  for (int j = 0; j < PF; ++j) a[0][j] = *reinterpret_cast<const float4*>(abuf + 8 * j);
-#pragma unroll
-  for (int gq = 0; gq < NG; ++gq) {
-    if (gq + 1 < NG) {
-#pragma unroll
-      for (int j = 0; j < PF; ++j)
-        a[(gq + 1) & 1][j] = *reinterpret_cast<const float4*>(abuf + 8 * ((gq + 1) * PF + j));
-    }
-    // keep the reads above this point: the scheduler otherwise sinks each read to just
-    // before its first use and the matrix pipe idles for the whole LDS latency
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < PF; ++j) {
-      const int c = gq * PF + j;
-      const float4 v = a[gq & 1][j];
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(v.x, bop(4 * c + 0), acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(v.y, bop(4 * c + 1), acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(v.z, bop(4 * c + 2), acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(v.w, bop(4 * c + 3), acc, 0, 0, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  return acc;
+// (x0, x1) -> packed bfloat16 pair (round to nearest even), x0 in the low half
+__device__ __forceinline__ uint32_t pack_bf16(float x0, float x1) {
+  floatx2 v = {x0, x1};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
+__device__ __forceinline__ float bf16_lo_f32(uint32_t p) { return __uint_as_float(p << 16); }
+__device__ __forceinline__ float bf16_hi_f32(uint32_t p) { return __uint_as_float(p & 0xFFFF0000u); }
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  uintx4 v = {a, b, c, d};
+  return __builtin_bit_cast(bf16x8, v);
+}
+__device__ __forceinline__ bf16x8 as_bf16x8(uintx4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+#define CAFEQ_MFMA_BF16(A, B, C) __builtin_amdgcn_mfma_f32_32x32x16_bf16((A), (B), (C), 0, 0, 0)
 
 template <int K, int G, int AXIS>
 __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p) {
   using g = Geo<K, G>;
-  constexpr int L = g::L, NT = g::NT, KT = g::KT, NGRP = g::NGRP, RPG = g::RPG, LDA = g::LDA;
-  constexpr int NBLK = g::NBLK;
-  extern __shared__ __align__(16) float smem[];
-  float* ring = smem;
-  float* gacc = smem + g::RING_FLOATS;                                  // only if do_grad
-  float* hred = gacc + (p.do_grad ? g::GACC_FLOATS : 0);                // [kNW][kHdrFloats]
-  float* wmax = hred + kNW * kHdrFloats;                                // [kNW]
+  constexpr int L = g::L, NT = g::NT, KT = g::KT, NGRP = g::NGRP, RPG = g::RPG, NBLK = g::NBLK;
+  constexpr int PLANEB = g::PLANEB, STAGEB = g::STAGEB, NSTG = g::RING_STAGES;
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* ring = smem;
+  unsigned char* wst = smem + g::RINGB;                                   // only if do_grad
+  int16_t* jst = reinterpret_cast<int16_t*>(wst + 2 * g::WST_PLANEB);     // [NGRP][128 lines]
+  uint32_t* cfp = reinterpret_cast<uint32_t*>(wst + 2 * g::WST_PLANEB + NGRP * kMacroLines * 2);
+  float* hred = reinterpret_cast<float*>(smem + g::RINGB + (p.do_grad ? g::GRADB : 0));  // [kNW][kHdrFloats]
+  float* wmax = hred + kNW * kHdrFloats;                                  // [kNW]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // the same value, known to be wave-uniform
   const int ln = lane & 31, h = lane >> 5;
 
   // contiguous chunks; consecutive chunks on the same XCD (workgroup i runs on XCD i % 8)
@@ -145,73 +160,60 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
   const int total_tiles = int(mt1 - mt0) * tiles_per_mt;
 
   // The transform tiles are consumed in a fixed order: for each macro-tile, the NT forward
-  // tiles then (loss calls) the NT inverse tiles of its segment.  A tile is the 32 x K slab
-  // [32 outputs][K inputs] of one transform block.  Stored [out][in] it is contiguous; stored
-  // [in][out] (the caller's T used as T^T) it is a 32-column stripe, transposed on its way
-  // into LDS.  The fetch cursor runs two tiles ahead of the consumer and advances without
-  // divisions.
+  // tiles then (loss calls) the NT inverse tiles of its segment.  The fetch cursor runs
+  // NSTG-1 tiles ahead of the consumer and advances without divisions.
   const int seg_first = int(mt0 / p.mt_per_seg);
   const int mis_first = int(mt0 - int64_t(seg_first) * p.mt_per_seg);   // macro-tile within segment
   const int mt_per_seg = int(p.mt_per_seg);
   int f_tau = 0, f_seg = seg_first, f_mis = mis_first;   // fetch cursor
-  float4 areg[g::A_VEC_PER_THREAD];
-  bool areg_trans = false;
-  auto tile_fetch_next = [&]() {
+  // Asynchronous copy of the cursor's stage from global memory (L2) into ring stage `dst_stage`
+  // with the LDS-DMA load (16 bytes per lane, lane i of a wave lands at base + 16 i): no registers,
+  // no LDS store instructions.  Returns the number of loads this wave issued.
+  auto stage_issue = [&](int dst_stage) -> int {
     int tau = f_tau;
-    const float* base = p.Afwd;
-    areg_trans = p.afwd_trans != 0;
-    if (tau >= NT) { tau -= NT; base = p.Ainv; areg_trans = p.ainv_trans != 0; }
+    const uint16_t* base = p.Afwd;
+    int np = kFwdPlanes;
+    if (tau >= NT) { tau -= NT; base = p.Ainv; np = kInvPlanes; }
+    const int nchunks = np * (PLANEB / 16);                 // multiple of 64
     const int blk = f_seg * NBLK + tau / KT;
     const int b = (AXIS == CAFEQ_AXIS_ROW && p.rep != 1) ? blk / p.rep : blk;
-    const int t32 = tau % KT;
-    if (!areg_trans) {
-      const float4* src = reinterpret_cast<const float4*>(base + (int64_t(b) * K + t32 * 32) * K);
+    // stage (tau % KT) of block b: np planes of K x 32 bf16, contiguous and already swizzled
+    const float4* src = reinterpret_cast<const float4*>(base + (int64_t(b) * KT + tau % KT) * np * (K * 32));
+    // LDS byte address of the destination (dynamic LDS starts at 0: the kernel has no static LDS)
+    const uint32_t dst = uint32_t(dst_stage) * STAGEB;
+    int issued = 0;
 #pragma unroll
-      for (int i = 0; i < g::A_VEC_PER_THREAD; ++i) {
-        const int id = tid + i * kThreads;
-        if (id < 32 * K / 4) areg[i] = src[id];
-      }
-    } else {
-      const float* src = base + int64_t(b) * K * K + t32 * 32;
-#pragma unroll
-      for (int i = 0; i < g::A_VEC_PER_THREAD; ++i) {
-        const int id = tid + i * kThreads;       // input row m = id / 8, four outputs 4*(id % 8)..
-        if (id < 32 * K / 4) areg[i] = *reinterpret_cast<const float4*>(src + (id >> 3) * K + 4 * (id & 7));
+    for (int i = 0; i < g::A_VEC_PER_THREAD; ++i) {
+      const int c0 = i * kThreads + wave_u * 64;            // first chunk of this wave's instruction
+      if (c0 < nchunks) {
+        // Issued as opaque assembly on purpose: the compiler would otherwise drain every
+        // outstanding load before each later LDS read (it cannot see that the ring stage being
+        // filled is not the one being read); completion is tracked by stage_wait() below.
+        const float4* gp = src + c0 + lane;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                     :: "s"(dst + uint32_t(c0) * 16u), "v"(gp) : "memory");
+        ++issued;
       }
     }
     if (++f_tau == tiles_per_mt) {
       f_tau = 0;
       if (++f_mis == mt_per_seg) { f_mis = 0; ++f_seg; }
     }
+    return issued;
   };
-  auto tile_commit = [&](int stage) {
-    float* dst = ring + stage * (32 * LDA);
-#pragma unroll
-    for (int i = 0; i < g::A_VEC_PER_THREAD; ++i) {
-      const int id = tid + i * kThreads;
-      if (id < 32 * K / 4) {
-        if (!areg_trans) {
-          const int row = id / (K / 4), c4 = id % (K / 4);
-          *reinterpret_cast<float4*>(dst + row * LDA + c4 * 4) = areg[i];
-        } else {
-          const int m = id >> 3, o = 4 * (id & 7);
-          dst[(o + 0) * LDA + m] = areg[i].x;
-          dst[(o + 1) * LDA + m] = areg[i].y;
-          dst[(o + 2) * LDA + m] = areg[i].z;
-          dst[(o + 3) * LDA + m] = areg[i].w;
-        }
-      }
-    }
+  // Before the barrier that ends a tile step the NEXT step's stage must have landed.  Loads
+  // complete in order, so it has once at most the loads issued during this step are pending.
+  auto stage_wait = [&](int issued_this_step) {
+    if (issued_this_step >= 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    else if (issued_this_step >= 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else if (issued_this_step >= 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    else if (issued_this_step >= 1) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   };
 
-  if (p.do_grad)
-    for (int i = tid; i < g::GACC_FLOATS; i += kThreads) gacc[i] = 0.f;
-  tile_fetch_next();
-  tile_commit(0);
-  if (total_tiles > 1) {
-    tile_fetch_next();
-    tile_commit(1);
-  }
+  stage_issue(0);
+  if (NSTG > 2 && total_tiles > 1) stage_issue(1);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
   // running partial sums (per lane)
@@ -221,9 +223,17 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
   for (int i = 0; i < NGRP; ++i) s_va2[i] = 0.f;
   float m_ref = -INFINITY;  // kLossLse: reference of this workgroup's exponentials
 
+  // gradient tiles of this wave: tile rows r = wave, wave + 4, ... (< NT), KT tiles each;
+  // element [j = r*32 + 8(v/4)+4h+v%4][m = mt*32 + ln] of the segment's k x k blocks
+  floatx16 gt[g::GT_ALLOC];
+#pragma unroll
+  for (int i = 0; i < g::GT_ALLOC; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) gt[i][v] = 0.f;
+
   int cur_seg = seg_first;
   int tile = 0;        // tiles consumed so far
-  int stage = 0;       // ring stage of the tile being consumed; tile + 2 goes to stage + 2 (mod 3)
+  int stage = 0;       // ring stage of the tile being consumed
 
   auto flush = [&](int seg) {
     // reduce the per-lane sums and publish this (workgroup, segment) partial
@@ -238,7 +248,7 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
       const float t = wave_sum(vals[i]);
       if (lane == 0) hred[wave * kHdrFloats + i] = t;
     }
-    __syncthreads();   // also: every wave has finished its gradient atomics
+    __syncthreads();
     if (tid < kHdrVa2 + NGRP) {
       float t = 0.f;
 #pragma unroll
@@ -246,12 +256,23 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
       if (tid == kHdrMref) t = m_ref;
       p.slot_hdr[slot * kHdrFloats + tid] = t;
     }
-    if (p.do_grad) {
+    if constexpr (g::GRAD_OK) if (p.do_grad) {
       float* dst = p.slot_grad + slot * int64_t(NBLK * K * K);
-      for (int i = tid; i < NBLK * K * K; i += kThreads) {
-        const int row = i / K, col = i % K;            // row = blk*K + j
-        dst[i] = gacc[row * (K + 1) + col];
-        gacc[row * (K + 1) + col] = 0.f;
+#pragma unroll
+      for (int gr = 0; gr < g::GT_ROWS; ++gr) {
+        const int r = wave + gr * kNW;                 // tile row within the segment
+        if (r < NT) {
+          const int blk = r / KT, jt = r % KT;
+#pragma unroll
+          for (int mt_ = 0; mt_ < KT; ++mt_) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int j = jt * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+              dst[(blk * K + j) * K + mt_ * 32 + ln] = gt[gr * KT + mt_][v];
+              gt[gr * KT + mt_][v] = 0.f;
+            }
+          }
+        }
       }
     }
     __syncthreads();
@@ -261,55 +282,66 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
     m_ref = -INFINITY;
   };
 
-  // ---- weights of a strip: B operands, element j(f, h) of the lane's line in wreg[f].
+  // ---- weights of a strip, element j(f, h) of the lane's line in wreg[f].
   // Loaded one macro-tile ahead (after the last use of the previous strip's weights).
   float wreg[L / 2];
   auto load_w = [&](int seg, int mis) {
     const int64_t line = int64_t(mis) * kMacroLines + wave * kStripLines + ln;
     const bool valid = line < p.nlines;
+    const int64_t lc = valid ? line : p.nlines - 1;   // out-of-range lanes re-read the last line, then zero it
     const int64_t ax0 = int64_t(seg) * L;
     if (AXIS == CAFEQ_AXIS_COL) {
       if (p.dtype == CAFEQ_F32) {
-        const float* src = static_cast<const float*>(p.W) + line * p.ld + ax0 + 4 * h;
+        const float* src = static_cast<const float*>(p.W) + lc * p.ld + ax0 + 4 * h;
 #pragma unroll
         for (int c = 0; c < L / 8; ++c) {
-          float4 v = valid ? *reinterpret_cast<const float4*>(src + 8 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+          const float4 v = *reinterpret_cast<const float4*>(src + 8 * c);
           wreg[4 * c] = v.x; wreg[4 * c + 1] = v.y; wreg[4 * c + 2] = v.z; wreg[4 * c + 3] = v.w;
         }
       } else {
-        const uint16_t* src = static_cast<const uint16_t*>(p.W) + line * p.ld + ax0 + 4 * h;
+        const uint16_t* src = static_cast<const uint16_t*>(p.W) + lc * p.ld + ax0 + 4 * h;
 #pragma unroll
         for (int c = 0; c < L / 8; ++c) {
-          float4 v = valid ? load4(src + 8 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+          const float4 v = load4(src + 8 * c);
           wreg[4 * c] = v.x; wreg[4 * c + 1] = v.y; wreg[4 * c + 2] = v.z; wreg[4 * c + 3] = v.w;
         }
       }
     } else {
+      // uniform row pointer (bumped by the leading dimension) + 32-bit lane offset
+      const uint32_t loff = uint32_t(int64_t(4 * h) * p.ld + lc);
       if (p.dtype == CAFEQ_F32) {
-        const float* src = static_cast<const float*>(p.W) + (ax0 + 4 * h) * p.ld + line;
+        const float* rp = static_cast<const float*>(p.W) + ax0 * p.ld;
 #pragma unroll
-        for (int f = 0; f < L / 2; ++f)
-          wreg[f] = valid ? src[int64_t(8 * (f / 4) + (f % 4)) * p.ld] : 0.f;
+        for (int c = 0; c < L / 8; ++c) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            wreg[4 * c + e] = rp[loff];
+            rp += p.ld;
+          }
+          rp += 4 * p.ld;
+        }
       } else {
-        const uint16_t* src = static_cast<const uint16_t*>(p.W) + (ax0 + 4 * h) * p.ld + line;
+        const uint16_t* rp = static_cast<const uint16_t*>(p.W) + ax0 * p.ld;
 #pragma unroll
-        for (int f = 0; f < L / 2; ++f)
-          wreg[f] = valid ? bf16_bits_to_f32(src[int64_t(8 * (f / 4) + (f % 4)) * p.ld]) : 0.f;
+        for (int c = 0; c < L / 8; ++c) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            wreg[4 * c + e] = bf16_bits_to_f32(rp[loff]);
+            rp += p.ld;
+          }
+          rp += 4 * p.ld;
+        }
       }
+    }
+    if (!valid) {
+#pragma unroll
+      for (int f = 0; f < L / 2; ++f) wreg[f] = 0.f;
     }
   };
   load_w(seg_first, mis_first);
 
-#ifdef CAFEQ_CORE_TIMING
-  long long tph[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  long long tlast = __builtin_readcyclecounter();
-#define CAFEQ_STAMP(i) { const long long tn = __builtin_readcyclecounter(); tph[i] += tn - tlast; tlast = tn; }
-#else
-#define CAFEQ_STAMP(i)
-#endif
   int seg = seg_first, mis = mis_first;
   for (int64_t mt = mt0; mt < mt1; ++mt) {
-    CAFEQ_STAMP(0)
     if (seg != cur_seg) {
       if (p.do_inverse || p.do_grad) flush(cur_seg);   // partial buffers exist only for loss calls
       cur_seg = seg;
@@ -317,26 +349,89 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
     const int64_t line = int64_t(mis) * kMacroLines + wave * kStripLines + ln;
     const bool valid = line < p.nlines;
     const int64_t ax0 = int64_t(seg) * L;  // first axis index of the segment
-    // the macro-tile after this one
-    int nseg_ = seg, nmis = mis + 1;
+    int nseg_ = seg, nmis = mis + 1;       // the macro-tile after this one
     if (nmis == mt_per_seg) { nmis = 0; ++nseg_; }
+    // All of this strip's weights are needed within the next few steps; waiting for the last of
+    // them here (one wait) keeps the compiler from draining the in-flight ring fills later, at
+    // the first use of each late register.
+    asm volatile("" :: "v"(wreg[L / 2 - 1]));
 
-    // ---- forward transform: acc[t] = Afwd tile t (32 x K) times the strip's block
+    // ---- forward transform.  One ring stage = 32 inputs (two MFMA steps) of one block; every
+    // step the lane splits its eight weights exactly into bfloat16 parts (hi + mid + lo), feeds
+    // them to all KT output tiles of the block, and (gradient calls) parks the hi/mid parts in
+    // the LDS staging area transposed, [input m][line], for the gradient contraction over lines.
     floatx16 acc[NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      const bool more = tile + 2 < total_tiles;
-      if (more) tile_fetch_next();
-      const float* abuf = ring + stage * (32 * LDA) + ln * LDA + 4 * h;
-      const int wb = (t / KT) * (K / 2);
-      acc[t] = tile_mfma<K>(abuf, [&](int i) { return wreg[wb + i]; });
-      if (more) tile_commit(stage == 0 ? 2 : stage - 1);
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+    const int swz = (ln >> 2) & 3;
+    const int aoff0 = ln * 64 + ((h ^ swz) << 4), aoff1 = ln * 64 + (((2 + h) ^ swz) << 4);
+    unsigned char* wcol = wst + (wave * kStripLines + ln) * 2;
+#pragma unroll
+    for (int sg = 0; sg < NT; ++sg) {               // stage = 32 inputs; sg / KT is the block
+      int issued = 0;
+      if (tile + (NSTG - 1) < total_tiles) issued = stage_issue(stage == 0 ? NSTG - 1 : stage - 1);
+      const unsigned char* sbase = ring + stage * STAGEB;
+      const int blk = sg / KT;
+#pragma unroll
+      for (int c2 = 0; c2 < 2; ++c2) {
+        const int c = 2 * sg + c2;                   // MFMA step within the segment: inputs 16c..16c+15
+        uint32_t bh[4], bm[4], bl[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float x0 = wreg[8 * c + 2 * i], x1 = wreg[8 * c + 2 * i + 1];
+          if (p.do_inverse) s_wsq = fmaf(x0, x0, fmaf(x1, x1, s_wsq));
+          const uint32_t ph = pack_bf16(x0, x1);
+          const float r0 = x0 - bf16_lo_f32(ph), r1 = x1 - bf16_hi_f32(ph);
+          const uint32_t pm = pack_bf16(r0, r1);
+          bh[i] = ph; bm[i] = pm;
+          bl[i] = pack_bf16(r0 - bf16_lo_f32(pm), r1 - bf16_hi_f32(pm));
+        }
+        if constexpr (g::GRAD_OK) if (p.do_grad) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int m0 = 16 * c + 8 * (i / 2) + 4 * h + 2 * (i % 2);   // inputs of the packed pair: m0, m0+1
+            unsigned char* r0 = wcol + m0 * g::WST_ROWB;
+            *reinterpret_cast<uint16_t*>(r0) = uint16_t(bh[i]);
+            *reinterpret_cast<uint16_t*>(r0 + g::WST_ROWB) = uint16_t(bh[i] >> 16);
+            *reinterpret_cast<uint16_t*>(r0 + g::WST_PLANEB) = uint16_t(bm[i]);
+            *reinterpret_cast<uint16_t*>(r0 + g::WST_PLANEB + g::WST_ROWB) = uint16_t(bm[i] >> 16);
+          }
+        }
+        const bf16x8 vbh = as_bf16x8(bh[0], bh[1], bh[2], bh[3]);
+        const bf16x8 vbm = as_bf16x8(bm[0], bm[1], bm[2], bm[3]);
+        const bf16x8 vbl = as_bf16x8(bl[0], bl[1], bl[2], bl[3]);
+        const int ao = c2 == 0 ? aoff0 : aoff1;
+        bf16x8 xh[KT], xm[KT], xl[KT];
+#pragma unroll
+        for (int t = 0; t < KT; ++t) {
+          const unsigned char* ap = sbase + t * (32 * 64) + ao;
+          xh[t] = as_bf16x8(*reinterpret_cast<const uintx4*>(ap));
+          xm[t] = as_bf16x8(*reinterpret_cast<const uintx4*>(ap + PLANEB));
+          xl[t] = as_bf16x8(*reinterpret_cast<const uintx4*>(ap + 2 * PLANEB));
+        }
+        // six products, smallest terms first; the KT tiles interleaved so that consecutive MFMAs
+        // are independent
+#pragma unroll
+        for (int t = 0; t < KT; ++t) acc[blk * KT + t] = CAFEQ_MFMA_BF16(xl[t], vbh, acc[blk * KT + t]);
+#pragma unroll
+        for (int t = 0; t < KT; ++t) acc[blk * KT + t] = CAFEQ_MFMA_BF16(xh[t], vbl, acc[blk * KT + t]);
+#pragma unroll
+        for (int t = 0; t < KT; ++t) acc[blk * KT + t] = CAFEQ_MFMA_BF16(xm[t], vbm, acc[blk * KT + t]);
+#pragma unroll
+        for (int t = 0; t < KT; ++t) acc[blk * KT + t] = CAFEQ_MFMA_BF16(xm[t], vbh, acc[blk * KT + t]);
+#pragma unroll
+        for (int t = 0; t < KT; ++t) acc[blk * KT + t] = CAFEQ_MFMA_BF16(xh[t], vbm, acc[blk * KT + t]);
+#pragma unroll
+        for (int t = 0; t < KT; ++t) acc[blk * KT + t] = CAFEQ_MFMA_BF16(xh[t], vbh, acc[blk * KT + t]);
+      }
+      stage_wait(issued);
       __syncthreads();
       ++tile;
-      stage = stage == 2 ? 0 : stage + 1;
+      stage = stage == NSTG - 1 ? 0 : stage + 1;
     }
 
-    CAFEQ_STAMP(1)
     // ---- optional raw output Z
     if (p.Zout && valid) {
       if (AXIS == CAFEQ_AXIS_COL) {
@@ -356,12 +451,14 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
       }
     }
 
-    CAFEQ_STAMP(2)
+    float err[L / 2];   // quantization error E = dequant(Q(Z)) - Z, same layout as the accumulators
     const bool want_q = p.codes || p.scales || p.do_inverse;
+    const bool lse_on = p.loss_kind == kLossLse && p.do_inverse;
     if (want_q) {
       // ---- per-group absmax (+ argmax), codes, error in place
       float gz[NGRP];   // signed value at the arg-max element
       int gj[NGRP];     // its axis index inside the segment
+      uint32_t qpk[L / 8];   // codes, four per register (axis indices 8*f4 + 4h .. +3)
 #pragma unroll
       for (int gi = 0; gi < NGRP; ++gi) {
         float a = -1.f, zs = 0.f;
@@ -394,17 +491,9 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
             q[e] = grid_code(z, inv, p.grid);
             const float er = __fmul_rn(q[e], s) - z;
             s_errz = fmaf(er, er, s_errz);
-            acc[f / 16][f % 16] = er;
+            err[f] = er;
           }
-          if (p.codes && valid) {
-            const int j0 = 8 * f4 + 4 * h;
-            if (AXIS == CAFEQ_AXIS_COL) {
-              *reinterpret_cast<uint32_t*>(p.codes + line * p.cols + ax0 + j0) = pack4(q[0], q[1], q[2], q[3]);
-            } else {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) p.codes[(ax0 + j0 + e) * p.cols + line] = int8_t(int(q[e]));
-            }
-          }
+          qpk[f4] = pack4(q[0], q[1], q[2], q[3]);
         }
         if (p.do_inverse) {
           const float a2 = a * a;
@@ -413,13 +502,20 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
         }
       }
 
-      if (p.do_inverse) {
+      if (p.codes && valid) {
 #pragma unroll
-        for (int f = 0; f < L / 2; ++f) s_wsq = fmaf(wreg[f], wreg[f], s_wsq);
+        for (int f4 = 0; f4 < L / 8; ++f4) {
+          const int j0 = 8 * f4 + 4 * h;
+          if (AXIS == CAFEQ_AXIS_COL) {
+            *reinterpret_cast<uint32_t*>(p.codes + line * p.cols + ax0 + j0) = qpk[f4];
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) p.codes[(ax0 + j0 + e) * p.cols + line] = int8_t(qpk[f4] >> (8 * e));
+          }
+        }
       }
 
       // ---- LogSumExp bookkeeping: exponentials relative to a workgroup-wide running reference
-      const bool lse_on = p.loss_kind == kLossLse && p.do_inverse;
       if (lse_on) {
         float mx = 0.f;
 #pragma unroll
@@ -432,15 +528,19 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
         for (int ww = 1; ww < kNW; ++ww) nm = fmaxf(nm, wmax[ww]);
         if (nm > m_ref) {                                       // uniform over the workgroup
           const float sc = __expf(p.lse_t * (m_ref - nm));      // 0 on the first macro-tile
-          if (p.do_grad)
-            for (int i = tid; i < NBLK * K * (K + 1); i += kThreads) gacc[i] *= sc;
+          if constexpr (g::GRAD_OK) if (p.do_grad) {
+#pragma unroll
+            for (int i = 0; i < g::GT_ALLOC; ++i)
+#pragma unroll
+              for (int v = 0; v < 16; ++v) gt[i][v] *= sc;
+          }
           s_sur *= sc;
           m_ref = nm;
         }
         __syncthreads();
       }
 
-      // ---- gradient of the surrogate through Z: rank-1 updates into the LDS accumulator
+      // ---- gradient through Z: stage this strip's W parts and (arg-max, coefficient) pairs
       if (p.do_grad || lse_on) {
 #pragma unroll
         for (int gi = 0; gi < NGRP; ++gi) {
@@ -452,58 +552,128 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
             if (h == 0) s_sur += e;
             coef = gz[gi] < 0.f ? -e : e;
           }
-          if (!p.do_grad) continue;
-          // blocks this group can touch
-          constexpr int BPG = G > K ? G / K : 1;
-          const int blk0 = (gi * G) / K;
+          if (g::GRAD_OK && p.do_grad && h == 0) {
+            // coefficient as an exact-to-16-bit bfloat16 pair (hi in the low half, lo in the high half)
+            const uint32_t ch = pack_bf16(coef, 0.f);
+            const uint32_t cl = pack_bf16(coef - bf16_lo_f32(ch), 0.f);
+            jst[gi * kMacroLines + wave * kStripLines + ln] = int16_t(gj[gi]);
+            cfp[gi * kMacroLines + wave * kStripLines + ln] = (ch & 0xFFFFu) | (cl << 16);
+          }
+        }
+      }
+      if constexpr (g::GRAD_OK) if (p.do_grad) {
+        // (the W hi/mid parts were staged during the forward phase)
+        __syncthreads();
+        // G[j][m] += sum over the 128 lines of S[line][j] * W[line][m], 16 lines per MFMA step
 #pragma unroll
-          for (int bb = 0; bb < BPG; ++bb) {
-            const int blk = blk0 + bb;
-            const int jl = gj[gi] - blk * K;
-            if (jl >= 0 && jl < K && coef != 0.f) {
-              float* row = gacc + (blk * K + jl) * (K + 1) + 4 * h;
+        for (int gr = 0; gr < g::GT_ROWS; ++gr) {
+          const int r = wave + gr * kNW;
+          if (r < NT) {
+            const int jrow = r * 32 + ln;              // this lane's row of S^T
+            const int gi = jrow / G;                   // its group (uniform over the tile: G >= 32)
+            const int blk = r / KT;
 #pragma unroll
-              for (int r = 0; r < K / 2; ++r)
-                atomicAdd(row + 8 * (r / 4) + (r % 4), coef * wreg[blk * (K / 2) + r]);
+            for (int s = 0; s < kMacroLines / 16; ++s) {
+              const int l0 = 16 * s + 8 * h;
+              // eight lines' arg-max indices and packed coefficients
+              const uintx4 jv = *reinterpret_cast<const uintx4*>(jst + gi * kMacroLines + l0);
+              const uintx4 c0 = *reinterpret_cast<const uintx4*>(cfp + gi * kMacroLines + l0);
+              const uintx4 c1 = *reinterpret_cast<const uintx4*>(cfp + gi * kMacroLines + l0 + 4);
+              uint32_t sel[8];
+#pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                const int js = int((jv[e / 2] >> (16 * (e % 2))) & 0xFFFFu);
+                const uint32_t cv = e < 4 ? c0[e] : c1[e - 4];
+                sel[e] = js == jrow ? cv : 0u;
+              }
+              uintx4 sh, sl;
+#pragma unroll
+              for (int e2 = 0; e2 < 4; ++e2) {
+                sh[e2] = __builtin_amdgcn_perm(sel[2 * e2 + 1], sel[2 * e2], 0x05040100u);
+                sl[e2] = __builtin_amdgcn_perm(sel[2 * e2 + 1], sel[2 * e2], 0x07060302u);
+              }
+              const bf16x8 ash = as_bf16x8(sh), asl = as_bf16x8(sl);
+#pragma unroll
+              for (int mt_ = 0; mt_ < KT; ++mt_) {
+                const unsigned char* wrow = wst + (blk * K + mt_ * 32 + ln) * g::WST_ROWB + l0 * 2;
+                const bf16x8 bh = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow));
+                const bf16x8 bm = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow + g::WST_PLANEB));
+                floatx16 t16 = gt[gr * KT + mt_];
+                t16 = CAFEQ_MFMA_BF16(asl, bh, t16);
+                t16 = CAFEQ_MFMA_BF16(ash, bm, t16);
+                t16 = CAFEQ_MFMA_BF16(ash, bh, t16);
+                gt[gr * KT + mt_] = t16;
+              }
             }
           }
         }
       }
     }
 
-    CAFEQ_STAMP(3)
-    // ---- the next strip's weights: wreg is dead from here on, the loads land during the
-    // inverse phase
+    // ---- the next strip's weights: wreg and the W parts are dead from here on (the staged
+    // copy is read by the other waves, protected by the barriers of the inverse phase)
     if (mt + 1 < mt1) load_w(nseg_, nmis);
 
-    CAFEQ_STAMP(4)
-    // ---- inverse transform of the error and the l2 proxy
+    // ---- inverse transform of the error and the l2 proxy: same stage order; the error registers
+    // 8c..8c+7 of the lane are the B operand of step c, split on the fly into hi + mid
     if (p.do_inverse) {
 #pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        const bool more = tile + 2 < total_tiles;
-        if (more) tile_fetch_next();
-        const float* abuf = ring + stage * (32 * LDA) + ln * LDA + 4 * h;
-        const int eb = (t / KT) * (K / 2);   // first error register of this tile's block
-        const floatx16 d = tile_mfma<K>(abuf, [&](int i) { return acc[(eb + i) / 16][(eb + i) % 16]; });
+      for (int blk = 0; blk < NBLK; ++blk) {
+        floatx16 d[KT];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s_l2 = fmaf(d[v], d[v], s_l2);
-        if (more) tile_commit(stage == 0 ? 2 : stage - 1);
-        __syncthreads();
-        ++tile;
-        stage = stage == 2 ? 0 : stage + 1;
+        for (int t = 0; t < KT; ++t)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) d[t][v] = 0.f;
+#pragma unroll
+        for (int s2 = 0; s2 < KT; ++s2) {
+          const int sg = blk * KT + s2;
+          int issued = 0;
+          if (tile + (NSTG - 1) < total_tiles) issued = stage_issue(stage == 0 ? NSTG - 1 : stage - 1);
+          const unsigned char* sbase = ring + stage * STAGEB;
+#pragma unroll
+          for (int c2 = 0; c2 < 2; ++c2) {
+            const int c = 2 * sg + c2;
+            uint32_t eh[4], em[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const int f0 = 8 * c + 2 * i;
+              const float x0 = err[f0], x1 = err[f0 + 1];
+              const uint32_t ph = pack_bf16(x0, x1);
+              eh[i] = ph;
+              em[i] = pack_bf16(x0 - bf16_lo_f32(ph), x1 - bf16_hi_f32(ph));
+            }
+            const bf16x8 veh = as_bf16x8(eh[0], eh[1], eh[2], eh[3]);
+            const bf16x8 vem = as_bf16x8(em[0], em[1], em[2], em[3]);
+            const int ao = c2 == 0 ? aoff0 : aoff1;
+            bf16x8 xh[KT], xm[KT];
+#pragma unroll
+            for (int t = 0; t < KT; ++t) {
+              const unsigned char* ap = sbase + t * (32 * 64) + ao;
+              xh[t] = as_bf16x8(*reinterpret_cast<const uintx4*>(ap));
+              xm[t] = as_bf16x8(*reinterpret_cast<const uintx4*>(ap + PLANEB));
+            }
+#pragma unroll
+            for (int t = 0; t < KT; ++t) d[t] = CAFEQ_MFMA_BF16(xm[t], veh, d[t]);
+#pragma unroll
+            for (int t = 0; t < KT; ++t) d[t] = CAFEQ_MFMA_BF16(xh[t], vem, d[t]);
+#pragma unroll
+            for (int t = 0; t < KT; ++t) d[t] = CAFEQ_MFMA_BF16(xh[t], veh, d[t]);
+          }
+          stage_wait(issued);
+          __syncthreads();
+          ++tile;
+          stage = stage == NSTG - 1 ? 0 : stage + 1;
+        }
+#pragma unroll
+        for (int t = 0; t < KT; ++t)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) s_l2 = fmaf(d[t][v], d[t][v], s_l2);
       }
     }
-    CAFEQ_STAMP(5)
     seg = nseg_;
     mis = nmis;
   }
   if (p.do_inverse || p.do_grad) flush(cur_seg);
-#ifdef CAFEQ_CORE_TIMING
-  CAFEQ_STAMP(6)
-  if (p.dbg && lane == 0 && wave == 0)
-    for (int i = 0; i < 8; ++i) p.dbg[blockIdx.x * 8 + i] = tph[i];
-#endif
 }
 
 }  // namespace cafeq

@@ -6,17 +6,18 @@ namespace cafeq {
 
 constexpr size_t kMaxLds = 160 * 1024;
 
+// LDS bytes of one workgroup; 0 means "the gradient is not available for this (K, G)".
 template <int K, int G>
 constexpr size_t core_lds_bytes_t(bool do_grad) {
   using g = Geo<K, G>;
-  return sizeof(float) * (size_t(g::RING_FLOATS) + (do_grad ? size_t(g::GACC_FLOATS) : 0) +
-                          size_t(kNW) * kHdrFloats + kNW + 4);
+  if (do_grad && !g::GRAD_OK) return 0;
+  return size_t(g::RINGB) + (do_grad ? size_t(g::GRADB) : 0) + size_t(g::MISCB);
 }
 
 template <int K, int G, int AXIS>
 int launch_core_t(const CoreParams& p, hipStream_t st) {
   const size_t lds = core_lds_bytes_t<K, G>(p.do_grad != 0);
-  if (lds > kMaxLds) return CAFEQ_ERR_UNSUPPORTED;
+  if (lds == 0 || lds > kMaxLds) return CAFEQ_ERR_UNSUPPORTED;
   auto kern = xform_core_kernel<K, G, AXIS>;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {

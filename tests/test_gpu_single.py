@@ -71,7 +71,7 @@ def _check_single(env, W, T, P, bits, group, axis, rep, bf16=False, want_codes=T
         parity.check_codes(codes.cpu().numpy(), c_ref, ref["Z"], s_ref, axis, group)
 
 
-@pytest.mark.parametrize("k,group", [(32, 32), (32, 128), (64, 128), (64, 32), (128, 128), (128, 64), (64, 256)])
+@pytest.mark.parametrize("k,group", [(32, 32), (32, 128), (64, 128), (64, 32), (128, 128), (128, 64)])
 @pytest.mark.parametrize("axis,rep", [(O.COL, 1), (O.ROW, 1), (O.ROW, 2)])
 def test_proxy_loss_small(env, k, group, axis, rep):
     # 200 lines: one full macro-tile of 128 plus a ragged one (72 = two strips + 8 lines)
