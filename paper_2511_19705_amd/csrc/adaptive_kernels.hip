@@ -279,127 +279,196 @@ struct StaticFor<E, E> {
   static __device__ __forceinline__ void run(F&) {}
 };
 
+__device__ __forceinline__ uint32_t dpp_u32_max(uint32_t v, uint32_t o) { return v > o ? v : o; }
+__device__ __forceinline__ uint32_t wave_allmax_u32(uint32_t v) {
+  v = dpp_u32_max(v, uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0xB1, 0xF, 0xF, true)));    // quad_perm [1,0,3,2]
+  v = dpp_u32_max(v, uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0x4E, 0xF, 0xF, true)));    // quad_perm [2,3,0,1]
+  v = dpp_u32_max(v, uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0x141, 0xF, 0xF, true)));   // row_half_mirror
+  v = dpp_u32_max(v, uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0x140, 0xF, 0xF, true)));   // row_mirror
+  v = dpp_u32_max(v, uint32_t(__shfl_xor(int(v), 16)));
+  v = dpp_u32_max(v, uint32_t(__shfl_xor(int(v), 32)));
+  return v;
+}
+
+__device__ __forceinline__ double fma_s(double a, double b, double c) { return __builtin_fma(a, b, c); }
+__device__ __forceinline__ float fma_s(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+
 // Register-resident in-place Gauss-Jordan inversion, one workgroup per block.
-// Thread (r, qd) keeps columns [qd*CPT, (qd+1)*CPT) of row r in registers.  Step k: the owners
-// of column k publish it, every wave finds the pivot among the rows not yet used (no physical
-// row swaps: the pivot order is a permutation undone on output), the pivot row is published
-// scaled, and every thread updates its CPT registers -- two barriers per step, and only
-// 2K values per step go through LDS.  The step loop is unrolled over the register index so
-// that all register accesses are static.
+// Thread (rt, ct) of an NRT x NCT thread grid keeps the RT x CT elements (rt + i*NRT, ct + j*NCT)
+// in registers (both strides interleaved, so the LDS reads of a step are either broadcasts or
+// run over consecutive addresses).  Step k: the owners of column k publish it, every wave finds
+// the pivot p among the rows not yet used (no physical row swaps: the pivot order is a
+// permutation undone on output), the owners of row p publish it divided by the pivot, and every
+// thread updates its tile from RT column values and CT row values -- two barriers and RT + CT
+// LDS reads per RT*CT fused multiply-adds.  The kernel is bound by instruction issue, so the
+// step is written without branches that change registers: column k becomes the unit vector e_p
+// by selects, and row p goes through the same update as the others with the multiplier
+// (pivot - 1), for which row - (pivot - 1) * row / pivot = row / pivot.  That identity loses
+// accuracy only for |pivot| >> 1, so the block is first scaled by a power of two to
+// max |a_ij| in (1/2, 1].  A singular block keeps running (on infinities) and is zeroed at the
+// end.  The step loop is unrolled over the register column index so that all register accesses
+// are static.
 //   A = T_b (float32) when partial == nullptr, else the float64 sum over nz chunk partials
 //   of S (first of the two K x K matrices of each partial).  out = A^-1 (zeros if singular).
-template <int K, int CPT, typename S>
-__global__ __launch_bounds__(K*(K / CPT)) void gj_reg_kernel(const GjArgs a) {
-  constexpr int NQ = K / CPT, NTHR = K * NQ, NWAVE = (NTHR + 63) / 64;
-  __shared__ S colbuf[2][K];
-  __shared__ S rowbuf[2][K];
+template <int K, int RT, int CT, typename S>
+__global__ __launch_bounds__((K / RT) * (K / CT)) void gj_reg_kernel(const GjArgs a) {
+  constexpr int NRT = K / RT, NCT = K / CT, NTHR = NRT * NCT, NWAVE = (NTHR + 63) / 64;
+  __shared__ __align__(16) S colbuf[2][K];
+  __shared__ __align__(16) S rowbuf[2][K];
   __shared__ int pk[K], kinv[K], used[K];
+  __shared__ float cn[K];
   __shared__ S wred[16];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
-  const int r = tid / NQ, qd = tid % NQ;
-  S reg[CPT];
+  const int rt = tid / NCT, ct = tid % NCT;
+  S reg[RT][CT];
+  if (a.partial == nullptr) {
+    const float* src = a.T + size_t(b) * K * K;
+#pragma unroll
+    for (int i = 0; i < RT; ++i)
+#pragma unroll
+      for (int j = 0; j < CT; ++j) reg[i][j] = S(src[(rt + i * NRT) * K + ct + j * NCT]);
+  } else {
+    const float* src = a.partial + size_t(b) * a.nz * 2 * K * K;
+#pragma unroll
+    for (int i = 0; i < RT; ++i)
+#pragma unroll
+      for (int j = 0; j < CT; ++j) reg[i][j] = 0;
+    for (int z = 0; z < a.nz; ++z) {
+      // float64 accumulation; the float GJ (K = 256) rounds the sum once
+      double t[RT][CT];
+#pragma unroll
+      for (int i = 0; i < RT; ++i)
+#pragma unroll
+        for (int j = 0; j < CT; ++j) t[i][j] = double(src[size_t(z) * 2 * K * K + (rt + i * NRT) * K + ct + j * NCT]);
+#pragma unroll
+      for (int i = 0; i < RT; ++i)
+#pragma unroll
+        for (int j = 0; j < CT; ++j) reg[i][j] = S(double(reg[i][j]) + t[i][j]);
+    }
+  }
   S anorm = 0;
 #pragma unroll
-  for (int j = 0; j < CPT; ++j) {
-    const int e = r * K + qd * CPT + j;
-    S v;
-    if (a.partial == nullptr) {
-      v = S(a.T[size_t(b) * K * K + e]);
-    } else {
-      const float* p = a.partial + size_t(b) * a.nz * 2 * K * K + e;
-      double acc = 0;
-      for (int z = 0; z < a.nz; ++z) acc += double(p[size_t(z) * 2 * K * K]);
-      v = S(acc);
-    }
-    reg[j] = v;
-    anorm = fmax(anorm, fabs(v));
-  }
+  for (int i = 0; i < RT; ++i)
+#pragma unroll
+    for (int j = 0; j < CT; ++j) anorm = fmax(anorm, fabs(reg[i][j]));
   for (int m = 1; m < 64; m <<= 1) anorm = fmax(anorm, __shfl_xor(anorm, m));
   if (lane == 0) wred[tid >> 6] = anorm;
-  if (tid < K) used[tid] = 0;
+  if (tid < K) { used[tid] = 0; cn[tid] = 0.f; }
   __syncthreads();
   anorm = 0;
   for (int i = 0; i < NWAVE; ++i) anorm = fmax(anorm, wred[i]);
-  const S tol = anorm * S(a.partial ? 1e-5 : (sizeof(S) == 8 ? 1e-12 : 1e-6));
+  int ex = 0;
+  (void)frexp(double(anorm), &ex);
+  const S scale = S(ldexp(1.0, -ex));    // exact power of two; 1 if the block is all zero
+#pragma unroll
+  for (int i = 0; i < RT; ++i)
+#pragma unroll
+    for (int j = 0; j < CT; ++j) reg[i][j] *= scale;
+  const S tol = anorm * scale * S(a.partial ? 1e-5 : (sizeof(S) == 8 ? 1e-12 : 1e-6));
   bool dead = false;   // uniform over the workgroup
 
-  for (int kb = 0; kb < NQ; ++kb) {
-    // one elimination step for column kb*CPT + kk, kk a compile-time register index
-    auto step = [&](auto kk_c) {
-      constexpr int kk = decltype(kk_c)::value;
-      const int k = kb * CPT + kk, buf = k & 1;
-      if (qd == kb) colbuf[buf][r] = reg[kk];
-      __syncthreads();
-      if (!dead) {
-        S best = -1;
-        int bi = K;
-        for (int rr = lane; rr < K; rr += 64) {
-          const S v = used[rr] ? S(-1) : fabs(colbuf[buf][rr]);
-          if (v > best) { best = v; bi = rr; }
-        }
-        for (int m = 1; m < 64; m <<= 1) {
-          const S ob = __shfl_xor(best, m);
-          const int oi = __shfl_xor(bi, m);
-          if (ob > best || (ob == best && oi < bi)) { best = ob; bi = oi; }
-        }
-        if (!(best > tol)) {
-          dead = true;
-        } else {
-          const int p = bi;
-          const S ipiv = S(1) / colbuf[buf][p];
-          if (r == p) {
+  // elimination steps for the columns k = cc + jj*NCT, jj a compile-time register index
+  auto steps = [&](auto jj_c) {
+    constexpr int jj = decltype(jj_c)::value;
+    for (int cc = 0; cc < NCT; ++cc) {
+      const int k = cc + jj * NCT, buf = cc & 1;
+      if (ct == cc) {
 #pragma unroll
-            for (int j = 0; j < CPT; ++j) {
-              const S v = ((qd == kb && j == kk) ? S(1) : reg[j]) * ipiv;
-              reg[j] = v;
-              rowbuf[buf][qd * CPT + j] = v;
-            }
-          }
-          if (tid == 0) pk[k] = p;
-          __syncthreads();
-          if (r != p) {
-            const S f = colbuf[buf][r];
-            if (qd == kb) reg[kk] = 0;
-#pragma unroll
-            for (int j = 0; j < CPT; ++j) reg[j] -= f * rowbuf[buf][qd * CPT + j];
-          }
-          if (tid == 0) used[p] = 1;
-        }
+        for (int i = 0; i < RT; ++i) colbuf[buf][rt + i * NRT] = reg[i][jj];
       }
-    };
-    StaticFor<0, CPT>::run(step);
-  }
+      __syncthreads();
+      // pivot = (approximately) largest |entry| of column k among the unused rows.  Every wave
+      // reduces a 32-bit key (magnitude as float bits with the low byte replaced by 255 - row,
+      // so ties go to the lowest row and the winner's row comes for free) with DPP.
+      uint32_t key = 0;
+#pragma unroll
+      for (int rr = lane; rr < K; rr += 64) {
+        const float mag = float(fabs(colbuf[buf][rr]));
+        const uint32_t kk_ = used[rr] ? 0u : ((__float_as_uint(mag) & 0xFFFFFF00u) | uint32_t(255 - rr));
+        key = key > kk_ ? key : kk_;
+      }
+      key = wave_allmax_u32(key);
+      const int p = (255 - int(key & 0xFFu)) & (K - 1);
+      const S pv = colbuf[buf][p];
+      dead = dead || (key >> 8) == 0 || !(S(fabs(pv)) > tol);
+      // reciprocal of the pivot: hardware estimate + Newton steps (full precision)
+      S ipiv = S(__builtin_amdgcn_rcpf(float(pv)));
+      ipiv = ipiv * (S(2) - pv * ipiv);
+      ipiv = ipiv * (S(2) - pv * ipiv);
+      if (sizeof(S) == 8) ipiv = ipiv * (S(2) - pv * ipiv);
+      const int prt = p % NRT, pi = p / NRT;
+      // publish row p (with the in-place 1 at column k) divided by the pivot
+#pragma unroll
+      for (int i = 0; i < RT; ++i)
+        if (rt == prt && i == pi) {
+#pragma unroll
+          for (int j = 0; j < CT; ++j)
+            rowbuf[buf][ct + j * NCT] = ((j == jj && ct == cc) ? S(1) : reg[i][j]) * ipiv;
+        }
+      if (tid == 0) pk[k] = p;
+      __syncthreads();
+      if (tid == 0) used[p] = 1;   // after the barrier: other waves may still be searching before it
+      S row[CT];
+#pragma unroll
+      for (int j = 0; j < CT; ++j) row[j] = rowbuf[buf][ct + j * NCT];
+#pragma unroll
+      for (int i = 0; i < RT; ++i) {
+        const int r = rt + i * NRT;
+        const S nf = r == p ? S(1) - pv : -colbuf[buf][r];
+        if (ct == cc) reg[i][jj] = r == p ? S(1) : S(0);
+#pragma unroll
+        for (int j = 0; j < CT; ++j) reg[i][j] = fma_s(nf, row[j], reg[i][j]);
+      }
+    }
+  };
+  StaticFor<0, CT>::run(steps);
   __syncthreads();
   if (a.status && tid == 0) a.status[size_t(b) * a.status_stride + a.status_offset] = dead ? 1 : 0;
   float* O = a.out + size_t(b) * K * K;
   if (dead) {
 #pragma unroll
-    for (int j = 0; j < CPT; ++j) O[r * K + qd * CPT + j] = 0.f;
+    for (int i = 0; i < RT; ++i)
+#pragma unroll
+      for (int j = 0; j < CT; ++j) O[(rt + i * NRT) * K + ct + j * NCT] = 0.f;
+    if (tid < K) {
+      if (a.rho_row) a.rho_row[size_t(b) * K + tid] = 0.f;
+      if (a.rho_col) a.rho_col[size_t(b) * K + tid] = 0.f;
+    }
     return;
   }
   if (tid < K) kinv[pk[tid]] = tid;
   __syncthreads();
-  // register (r, c) is element (kinv[r], pk[c]) of the inverse
-  const int orow = kinv[r];
-  S rr = 0;
+  // register (r, c) is element (kinv[r], pk[c]) of the inverse of the scaled block
+  int ocol[CT];
 #pragma unroll
-  for (int j = 0; j < CPT; ++j) {
-    O[orow * K + pk[qd * CPT + j]] = float(reg[j]);
-    rr += reg[j] * reg[j];
-  }
-  if (a.rho_row || a.rho_col) {
-    // squared row norms: sum over this row's NQ threads (adjacent lanes); column norms by atomics in LDS
-    for (int m = 1; m < NQ; m <<= 1) rr += __shfl_xor(rr, m);
-    if (a.rho_row && qd == 0) a.rho_row[size_t(b) * K + orow] = float(rr);
-    if (a.rho_col) {
-      __shared__ float cn[K];
-      if (tid < K) cn[tid] = 0.f;
-      __syncthreads();
+  for (int j = 0; j < CT; ++j) ocol[j] = pk[ct + j * NCT];
 #pragma unroll
-      for (int j = 0; j < CPT; ++j) atomicAdd(&cn[pk[qd * CPT + j]], float(reg[j] * reg[j]));
-      __syncthreads();
-      if (tid < K) a.rho_col[size_t(b) * K + tid] = cn[tid];
+  for (int i = 0; i < RT; ++i) {
+    const int orow = kinv[rt + i * NRT];
+    S rr = 0;
+#pragma unroll
+    for (int j = 0; j < CT; ++j) {
+      reg[i][j] *= scale;
+      O[orow * K + ocol[j]] = float(reg[i][j]);
+      rr += reg[i][j] * reg[i][j];
     }
+    if (a.rho_row) {
+      // squared row norms: sum over this row's NCT threads (adjacent lanes)
+      for (int m = 1; m < NCT; m <<= 1) rr += __shfl_xor(rr, m);
+      if (ct == 0) a.rho_row[size_t(b) * K + orow] = float(rr);
+    }
+  }
+  if (a.rho_col) {
+    // squared column norms: this thread's RT rows first, then atomics in LDS
+#pragma unroll
+    for (int j = 0; j < CT; ++j) {
+      S c2 = 0;
+#pragma unroll
+      for (int i = 0; i < RT; ++i) c2 += reg[i][j] * reg[i][j];
+      atomicAdd(&cn[ocol[j]], float(c2));
+    }
+    __syncthreads();
+    if (tid < K) a.rho_col[size_t(b) * K + tid] = cn[tid];
   }
 }
 
@@ -499,10 +568,10 @@ __global__ __launch_bounds__(256) void eye_minus_kernel(const double* __restrict
 namespace {
 int launch_gj(const GjArgs& a, int nb, hipStream_t st) {
   switch (a.K) {
-    case 32: hipLaunchKernelGGL((gj_reg_kernel<32, 16, double>), dim3(nb), dim3(64), 0, st, a); break;
-    case 64: hipLaunchKernelGGL((gj_reg_kernel<64, 32, double>), dim3(nb), dim3(128), 0, st, a); break;
-    case 128: hipLaunchKernelGGL((gj_reg_kernel<128, 32, double>), dim3(nb), dim3(512), 0, st, a); break;
-    case 256: hipLaunchKernelGGL((gj_reg_kernel<256, 64, float>), dim3(nb), dim3(1024), 0, st, a); break;
+    case 32: hipLaunchKernelGGL((gj_reg_kernel<32, 4, 4, double>), dim3(nb), dim3(64), 0, st, a); break;
+    case 64: hipLaunchKernelGGL((gj_reg_kernel<64, 4, 8, double>), dim3(nb), dim3(128), 0, st, a); break;
+    case 128: hipLaunchKernelGGL((gj_reg_kernel<128, 4, 8, double>), dim3(nb), dim3(512), 0, st, a); break;
+    case 256: hipLaunchKernelGGL((gj_reg_kernel<256, 8, 8, float>), dim3(nb), dim3(1024), 0, st, a); break;
     default: hipLaunchKernelGGL(gj_solve_kernel, dim3(nb), dim3(1024), 0, st, a); break;
   }
   CAFEQ_CHECK_LAUNCH();

@@ -28,25 +28,41 @@ __global__ __launch_bounds__(256) void rho_kernel(const float* __restrict__ P, i
 // with the 32 inputs of a row arranged as four 16-byte chunks (MFMA step c2 = (in % 32) / 16, lane
 // half h -> chunk 2*c2 + h, holding inputs 16*c2 + 8u + 4h + e at position 4u + e), the chunk stored
 // at chunk ^ ((out >> 2) & 3) (LDS bank swizzle).
-__global__ __launch_bounds__(256) void split_planes_kernel(const float* __restrict__ src, int K, int trans,
-                                                            int nplanes, uint16_t* __restrict__ dst) {
-  const float* sb = src + size_t(blockIdx.x) * K * K;
-  uint16_t* db = dst + size_t(blockIdx.x) * nplanes * K * K;
-  for (int e = threadIdx.x; e < K * K; e += blockDim.x) {
-    const int out = e / K, in = e % K;
-    const int stage = in / 32, w32 = in % 32, c2 = w32 / 16, w16 = w32 % 16;
+struct SplitJob { const float* src; uint16_t* dst; int trans, nplanes; };
+struct SplitJobs { SplitJob job[4]; int njobs, K; };
+// grid: (nb, njobs).  Reads are linear in the source; the 2-byte writes scatter inside the block.
+__global__ __launch_bounds__(256) void split_planes_kernel(const SplitJobs js) {
+  // one workgroup per (block, job, stage of 32 contraction indices): the stage's planes are
+  // assembled in LDS in their final order and leave as whole 16-byte vectors
+  __shared__ __align__(16) uint16_t lds[3 * 256 * 32];
+  const int K = js.K, nst = K / 32;
+  const SplitJob jb = js.job[blockIdx.y / nst];
+  const int stage = blockIdx.y % nst, nplanes = jb.nplanes;
+  const float* sb = jb.src + size_t(blockIdx.x) * K * K;
+  uint16_t* db = jb.dst + (size_t(blockIdx.x) * nst + stage) * nplanes * K * 32;
+  const int lk = 31 - __builtin_clz(unsigned(K));
+  for (int e = threadIdx.x; e < K * 32; e += 256) {
+    int r, c;
+    if (jb.trans) { r = 32 * stage + (e >> lk); c = e & (K - 1); }
+    else          { r = e >> 5; c = 32 * stage + (e & 31); }
+    const int out = jb.trans ? c : r, w32 = (jb.trans ? r : c) & 31;
+    const int c2 = w32 / 16, w16 = w32 % 16;
     const int u = w16 / 8, hh = (w16 % 8) / 4, ee = w16 % 4;
     const int chunk = (2 * c2 + hh) ^ ((out >> 2) & 3);
-    const size_t at = (size_t(stage) * nplanes * K + out) * 32 + chunk * 8 + 4 * u + ee;
-    float x = trans ? sb[in * K + out] : sb[out * K + in];
+    const int at = out * 32 + chunk * 8 + 4 * u + ee;
+    float x = sb[r * K + c];
     for (int pl = 0; pl < nplanes; ++pl) {
       uint32_t bits = __float_as_uint(x);
       bits += 0x7FFFu + ((bits >> 16) & 1u);          // round to nearest even
       const uint16_t part = uint16_t(bits >> 16);
-      db[at + size_t(pl) * K * 32] = part;
+      lds[at + pl * K * 32] = part;
       x -= __uint_as_float(uint32_t(part) << 16);
     }
   }
+  __syncthreads();
+  const uint4* s4 = reinterpret_cast<const uint4*>(lds);
+  uint4* d4 = reinterpret_cast<uint4*>(db);
+  for (int e = threadIdx.x; e < nplanes * K * 4; e += 256) d4[e] = s4[e];
 }
 
 // rG[gi] = sum of rho over the axis indices of group gi (axis index a -> block (a/K)/rep, a%K).
@@ -318,6 +334,56 @@ __global__ __launch_bounds__(256) void bgemm_kernel(const float* __restrict__ A,
     }
 }
 
+// Same product on the matrix cores (v_mfma_f32_32x32x2_f32) for K a multiple of 64: one 64 x 64
+// output tile per workgroup, four waves of one 32 x 32 tile each, the operand panels staged in
+// LDS as [contraction index][64 tile indices] (row stride 97 floats: transposing stores, whose
+// lanes walk the contraction index, and the MFMA operand reads, whose lane halves take rows l
+// and l+1, both stay clear of bank conflicts).  Contraction in chunks of 128 (K = 64: one of 64).
+template <bool TA, bool TB>
+__global__ __launch_bounds__(256) void bgemm_mfma_kernel(const float* __restrict__ A, const float* __restrict__ B,
+                                                          float* __restrict__ C, int K, float alpha, float beta) {
+  constexpr int LD = 97, CH = 128;
+  __shared__ float sa[CH * LD];
+  __shared__ float sb[CH * LD];
+  const int tpr = K / 64;
+  const int b = blockIdx.x / (tpr * tpr), tile = blockIdx.x % (tpr * tpr);
+  const int i0 = (tile / tpr) * 64, j0 = (tile % tpr) * 64;
+  const float* Ab = A + size_t(b) * K * K;
+  const float* Bb = B + size_t(b) * K * K;
+  float* Cb = C + size_t(b) * K * K;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ln = lane & 31, h = lane >> 5;
+  const int wi = wave >> 1, wj = wave & 1;
+  floatx16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  for (int l0 = 0; l0 < K; l0 += CH) {
+    const int nl = K - l0 < CH ? K - l0 : CH;   // 64 or 128
+    const int sh = nl == 64 ? 6 : 7;
+    for (int e = tid; e < nl * 64; e += 256) {
+      // sa[l][i] = op(A)[i0 + i][l0 + l];  sb[l][j] = op(B)[l0 + l][j0 + j]
+      if (TA) { const int l = e / 64, i = e % 64; sa[l * LD + i] = Ab[(l0 + l) * K + i0 + i]; }
+      else    { const int i = e >> sh, l = e & (nl - 1); sa[l * LD + i] = Ab[(i0 + i) * K + l0 + l]; }
+      if (TB) { const int j = e >> sh, l = e & (nl - 1); sb[l * LD + j] = Bb[(j0 + j) * K + l0 + l]; }
+      else    { const int l = e / 64, j = e % 64; sb[l * LD + j] = Bb[(l0 + l) * K + j0 + j]; }
+    }
+    __syncthreads();
+    const float* pa = sa + h * LD + wi * 32 + ln;
+    const float* pb = sb + h * LD + wj * 32 + ln;
+    for (int s0 = 0; s0 < nl / 2; s0 += 8) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[2 * (s0 + u) * LD], pb[2 * (s0 + u) * LD], acc, 0, 0, 0);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int i = i0 + wi * 32 + 8 * (v / 4) + 4 * h + (v % 4), j = j0 + wj * 32 + ln;
+    float* dst = Cb + i * K + j;
+    *dst = alpha * acc[v] + (beta != 0.f ? beta * *dst : 0.f);
+  }
+}
+
 // K == 32: one 32 x 32 tile per workgroup, thread per output element group
 template <bool TA, bool TB>
 __global__ __launch_bounds__(256) void bgemm32_kernel(const float* __restrict__ A, const float* __restrict__ B,
@@ -344,10 +410,20 @@ __global__ __launch_bounds__(256) void bgemm32_kernel(const float* __restrict__ 
 
 }  // namespace
 
-int launch_split_planes(const float* src, int K, int nb, int trans, int nplanes, uint16_t* dst, hipStream_t st) {
-  hipLaunchKernelGGL(split_planes_kernel, dim3(nb), dim3(256), 0, st, src, K, trans, nplanes, dst);
+int launch_split_planes_multi(const SplitRequest* req, int n, int K, int nb, hipStream_t st) {
+  SplitJobs js;
+  js.njobs = n; js.K = K;
+  for (int i = 0; i < n && i < 4; ++i) {
+    js.job[i].src = req[i].src; js.job[i].dst = req[i].dst;
+    js.job[i].trans = req[i].trans; js.job[i].nplanes = req[i].nplanes;
+  }
+  hipLaunchKernelGGL(split_planes_kernel, dim3(nb, n * (K / 32)), dim3(256), 0, st, js);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
+}
+int launch_split_planes(const float* src, int K, int nb, int trans, int nplanes, uint16_t* dst, hipStream_t st) {
+  SplitRequest r{src, dst, trans, nplanes};
+  return launch_split_planes_multi(&r, 1, K, nb, st);
 }
 int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_t st) {
   hipLaunchKernelGGL(rho_kernel, dim3(nb), dim3(256), 0, st, P, K, by_row, rho);
@@ -405,7 +481,7 @@ int launch_bgemm(bool ta, bool tb, const float* A, const float* B, float* C, int
 #undef CAFEQ_G32
   } else {
     const unsigned grid = unsigned(nb) * (K / 64) * (K / 64);
-#define CAFEQ_G64(TA, TB) hipLaunchKernelGGL((bgemm_kernel<TA, TB>), dim3(grid), dim3(256), 0, st, A, B, C, K, alpha, beta)
+#define CAFEQ_G64(TA, TB) hipLaunchKernelGGL((bgemm_mfma_kernel<TA, TB>), dim3(grid), dim3(256), 0, st, A, B, C, K, alpha, beta)
     if (ta && tb) CAFEQ_G64(true, true); else if (ta) CAFEQ_G64(true, false);
     else if (tb) CAFEQ_G64(false, true); else CAFEQ_G64(false, false);
 #undef CAFEQ_G64

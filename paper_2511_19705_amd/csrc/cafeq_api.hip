@@ -417,8 +417,10 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   CoreParams p;
   fill_common(&p, W, pl, x->rep);
   // forward operand [out][in]: T^T (COL) or T (ROW); inverse operand: Tinv^T or Tinv
-  if ((rc = launch_split_planes(x->T, K, nb, col ? 1 : 0, kFwdPlanes, w.pfwd, st))) return rc;
-  if ((rc = launch_split_planes(x->Tinv, K, nb, col ? 1 : 0, kInvPlanes, w.pinv, st))) return rc;
+  {
+    const SplitRequest req[2] = {{x->T, w.pfwd, col ? 1 : 0, kFwdPlanes}, {x->Tinv, w.pinv, col ? 1 : 0, kInvPlanes}};
+    if ((rc = launch_split_planes_multi(req, 2, K, nb, st))) return rc;
+  }
   p.Afwd = w.pfwd; p.Ainv = w.pinv;
   p.grid = grid; p.do_inverse = 1; p.do_grad = gradT ? 1 : 0; p.loss_kind = kLossSur; p.beta = beta;
   p.rG = w.rG; p.codes = codes; p.scales = scales; p.slot_grad = w.slot_grad; p.slot_hdr = w.slot_hdr;
@@ -471,10 +473,11 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
 
   CoreParams a;
   fill_common(&a, A, pa, 1);
-  if ((rc = launch_split_planes(x->T, K, nb, 1, kFwdPlanes, w.pfwdA, st))) return rc;
-  if ((rc = launch_split_planes(x->Tinv, K, nb, 1, kInvPlanes, w.pinvA, st))) return rc;
-  if ((rc = launch_split_planes(x->Tinv, K, nb, 0, kFwdPlanes, w.pfwdB, st))) return rc;
-  if ((rc = launch_split_planes(x->T, K, nb, 0, kInvPlanes, w.pinvB, st))) return rc;
+  {
+    const SplitRequest req[4] = {{x->T, w.pfwdA, 1, kFwdPlanes}, {x->Tinv, w.pinvA, 1, kInvPlanes},
+                                 {x->Tinv, w.pfwdB, 0, kFwdPlanes}, {x->T, w.pinvB, 0, kInvPlanes}};
+    if ((rc = launch_split_planes_multi(req, 4, K, nb, st))) return rc;
+  }
   a.Afwd = w.pfwdA; a.Ainv = w.pinvA;
   a.grid = grid; a.do_inverse = 1; a.do_grad = grad ? 1 : 0; a.loss_kind = kLossLse; a.lse_t = lse_t;
   a.codes = codesU; a.scales = scalesU; a.slot_grad = w.gradA; a.slot_hdr = w.hdrA;
