@@ -112,7 +112,8 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
  * (M^-1)_{ij}^2 factors).  Tinv[nb][k][k] = T^-1 per block (Gauss-Jordan with partial
  * pivoting, float64 internally).  rho_row[nb*k] / rho_col[nb*k] (either may be NULL):
  * squared row / column norms of Tinv.  status[nb] (may be NULL): 0 ok, 1 singular to
- * working precision (Tinv of that block is then unspecified).  k <= 256. */
+ * working precision (Tinv, rho_row and rho_col of that block are then zero).
+ * k in {32, 64, 128, 256} (else CAFEQ_ERR_UNSUPPORTED). */
 int cafeq_block_inverse(const float* T, int k, int nb, float* Tinv, float* rho_row,
                         float* rho_col, int* status, void* ws, void* stream);
 
@@ -140,7 +141,8 @@ int cafeq_apply_transform(const cafeq_mat* W, const cafeq_xform* x, int axis, in
  *   gradT[nb][k][k] (may be NULL: forward only) = d L_sur / d T with Tinv = T^-1,
  *               absmax differentiated at its arg-max element.
  *   codes / scales (may be NULL): Q(Z) as in cafeq_rtn_quantize.
- * group must satisfy max(group, k) <= 256 and divide / be divided by k. */
+ * group must satisfy max(group, k) <= 256 and divide / be divided by k.  gradT != NULL is
+ * CAFEQ_ERR_UNSUPPORTED for k = 256 and for group = 256 with k >= 64 (forward only works). */
 int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x,
                              const cafeq_quant_cfg* cfg, float* losses, float* gradT,
                              int8_t* codes, float* scales, void* ws, void* stream);
@@ -167,8 +169,10 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B,
  *   half 0 or 2 (line 4):  Uq_b <- Q( U_b . (V_[b] Vq_[b]^T)(Vq_[b] Vq_[b]^T)^-1 )
  * where Uq / Vq are the dequantized current codes (in/out: codesU, scalesU, codesV,
  * scalesV; U groups along columns, V groups along rows).  status[2*nb] (may be NULL):
- * per head and line, 0 ok, 1 the Gram matrix was not positive definite to working
- * precision (that head's codes are then left unchanged by that line). */
+ * per head and line, 0 ok, 1 the Gram matrix was singular to working precision (a pivot
+ * below 1e-5 of its largest entry: the quantized block is rank deficient); that line then
+ * falls back to plain rounding of the head's target, i.e. the correction matrix is the
+ * identity. */
 int cafeq_adaptive_round_step(const float* U, const float* V, int64_t rowsA, int64_t colsA,
                               int64_t rowsB, int64_t colsB, const cafeq_quant_cfg* cfg,
                               int k, int nb, int rep, int half, int8_t* codesU,

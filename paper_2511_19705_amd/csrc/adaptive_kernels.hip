@@ -14,9 +14,9 @@
 //   gram_pair_kernel : fp32 MFMA (v_mfma_f32_32x32x2_f32), one workgroup per (head, 32-row
 //                      output stripe, chunk of the contraction range); codes are dequantized
 //                      on the fly; chunk partials are written out, not atomically added.
-//   gj_solve_kernel  : sums the chunk partials in float64 and runs Gauss-Jordan elimination
-//                      with partial pivoting on [S | R]; also serves cafeq_block_inverse
-//                      ([T | I]).
+//   gj_reg_kernel    : sums the chunk partials of S in float64 and inverts it by register-
+//                      resident Gauss-Jordan elimination with partial pivoting; also serves
+//                      cafeq_block_inverse.  C = I - S^-1 R follows as a batched product.
 #include <type_traits>
 
 #include "xform_core.hpp"
@@ -153,116 +153,16 @@ __global__ __launch_bounds__(256) void gram_pair_kernel(const GramArgs a) {
     }
 }
 
-// Gauss-Jordan on the augmented [A | B] (K x 2K, float64, in `work`), one workgroup per block.
-//   mode 0: A = T_b (float32), B = I;            out = A^-1            (block inverse)
-//   mode 1: A = sum_z partial S, B = sum_z partial R;  out = I - A^-1 B (adaptive rounding)
-// status[b] = 1 when a pivot vanishes to working precision; out is then the identity.
+// Arguments of the Gauss-Jordan inversion kernel (one workgroup per block).
 struct GjArgs {
   int mode, K, nz;
-  const float* T;        // mode 0
-  const float* partial;  // mode 1: [nb][nz][2][K][K]
-  double* work;          // [nb][K][2K]
+  const float* T;        // matrix to invert when partial == nullptr
+  const float* partial;  // else [nb][nz][2][K][K]: chunk partials whose first matrix is summed and inverted
+  double* work;          // unused by the register-resident kernel
   float* out;            // [nb][K][K]
-  float* rho_row; float* rho_col;  // mode 0, optional
+  float* rho_row; float* rho_col;  // optional squared row / column norms of the inverse
   int* status; int status_stride, status_offset;
 };
-__global__ __launch_bounds__(1024) void gj_solve_kernel(const GjArgs a) {
-  __shared__ double pv_val[1024];
-  __shared__ int pv_idx[1024];
-  __shared__ double prow[512];
-  __shared__ double colk[256];
-  __shared__ int singular;
-  const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x, K = a.K, W2 = 2 * K;
-  double* M = a.work + size_t(b) * K * W2;
-  double anorm = 0;
-  for (int e = tid; e < K * W2; e += nt) {
-    const int r = e / W2, c = e % W2;
-    double v;
-    if (a.mode == 0) {
-      v = c < K ? double(a.T[size_t(b) * K * K + r * K + c]) : (c - K == r ? 1.0 : 0.0);
-    } else {
-      const float* p = a.partial + size_t(b) * a.nz * 2 * K * K + (c < K ? 0 : size_t(K) * K) + size_t(r) * K + (c % K);
-      v = 0;
-      for (int z = 0; z < a.nz; ++z) v += double(p[size_t(z) * 2 * K * K]);
-    }
-    M[e] = v;
-    if (c < K) anorm = fmax(anorm, fabs(v));
-  }
-  pv_val[tid] = anorm;
-  if (tid == 0) singular = 0;
-  __syncthreads();
-  for (int s = nt / 2; s > 0; s >>= 1) {
-    if (tid < s) pv_val[tid] = fmax(pv_val[tid], pv_val[tid + s]);
-    __syncthreads();
-  }
-  anorm = pv_val[0];
-  __syncthreads();
-  for (int k = 0; k < K; ++k) {
-    double best = -1.0;
-    int bi = k;
-    for (int r = k + tid; r < K; r += nt) {
-      const double v = fabs(M[r * W2 + k]);
-      if (v > best) { best = v; bi = r; }
-    }
-    pv_val[tid] = best; pv_idx[tid] = bi;
-    __syncthreads();
-    for (int s = nt / 2; s > 0; s >>= 1) {
-      if (tid < s) {
-        if (pv_val[tid + s] > pv_val[tid] || (pv_val[tid + s] == pv_val[tid] && pv_idx[tid + s] < pv_idx[tid])) {
-          pv_val[tid] = pv_val[tid + s]; pv_idx[tid] = pv_idx[tid + s];
-        }
-      }
-      __syncthreads();
-    }
-    const int p = pv_idx[0];
-    const double pval = pv_val[0];
-    __syncthreads();
-    // float32-sourced Gram sums carry ~1e-6 relative noise: smaller pivots are not information
-    if (!(pval > anorm * (a.mode == 1 ? 1e-5 : 1e-12))) {          // uniform over the workgroup
-      if (tid == 0) singular = 1;
-      break;
-    }
-    const double piv = M[p * W2 + k];
-    for (int c = tid; c < W2; c += nt) {
-      const double vp = M[p * W2 + c], vk = M[k * W2 + c];
-      prow[c] = vp / piv;
-      if (p != k) M[p * W2 + c] = vk;
-    }
-    __syncthreads();
-    for (int r = tid; r < K; r += nt) colk[r] = (r == k) ? 0.0 : M[r * W2 + k];
-    __syncthreads();
-    for (int e = tid; e < K * W2; e += nt) {
-      const int r = e / W2, c = e % W2;
-      M[e] = (r == k) ? prow[c] : M[e] - colk[r] * prow[c];
-    }
-    __syncthreads();
-  }
-  __syncthreads();
-  const int bad = singular;
-  if (a.status && tid == 0) a.status[size_t(b) * a.status_stride + a.status_offset] = bad;
-  float* O = a.out + size_t(b) * K * K;
-  for (int e = tid; e < K * K; e += nt) {
-    const int r = e / K, c = e % K;
-    const double x = M[r * W2 + K + c];
-    float v;
-    if (bad) v = (a.mode == 1 && r == c) ? 1.f : (a.mode == 1 ? 0.f : float(x));
-    else v = a.mode == 0 ? float(x) : float((r == c ? 1.0 : 0.0) - x);
-    O[e] = v;
-  }
-  if (a.mode == 0 && (a.rho_row || a.rho_col)) {
-    __syncthreads();
-    for (int j = tid; j < K; j += nt) {
-      double rr = 0, cc = 0;
-      for (int i = 0; i < K; ++i) {
-        const double x = M[j * W2 + K + i], y = M[i * W2 + K + j];
-        rr += x * x; cc += y * y;
-      }
-      if (a.rho_row) a.rho_row[size_t(b) * K + j] = float(rr);
-      if (a.rho_col) a.rho_col[size_t(b) * K + j] = float(cc);
-    }
-  }
-}
-
 
 // Compile-time loop: f(integral_constant<int, I>) for I in [B, E).
 template <int B, int E>
@@ -280,14 +180,25 @@ struct StaticFor<E, E> {
 };
 
 __device__ __forceinline__ uint32_t dpp_u32_max(uint32_t v, uint32_t o) { return v > o ? v : o; }
+// maximum over the wave, returned as a wave-uniform value: DPP inside each row of 16 lanes,
+// then the four row results are read back as scalars
 __device__ __forceinline__ uint32_t wave_allmax_u32(uint32_t v) {
   v = dpp_u32_max(v, uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0xB1, 0xF, 0xF, true)));    // quad_perm [1,0,3,2]
   v = dpp_u32_max(v, uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0x4E, 0xF, 0xF, true)));    // quad_perm [2,3,0,1]
   v = dpp_u32_max(v, uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0x141, 0xF, 0xF, true)));   // row_half_mirror
   v = dpp_u32_max(v, uint32_t(__builtin_amdgcn_update_dpp(0, int(v), 0x140, 0xF, 0xF, true)));   // row_mirror
-  v = dpp_u32_max(v, uint32_t(__shfl_xor(int(v), 16)));
-  v = dpp_u32_max(v, uint32_t(__shfl_xor(int(v), 32)));
-  return v;
+  const uint32_t a = uint32_t(__builtin_amdgcn_readlane(int(v), 0)), b = uint32_t(__builtin_amdgcn_readlane(int(v), 16));
+  const uint32_t c = uint32_t(__builtin_amdgcn_readlane(int(v), 32)), d = uint32_t(__builtin_amdgcn_readlane(int(v), 48));
+  return dpp_u32_max(dpp_u32_max(a, b), dpp_u32_max(c, d));
+}
+// value held by lane `src` (wave-uniform) of a per-lane variable
+__device__ __forceinline__ double read_lane(double x, int src) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(x), src);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(x), src);
+  return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ float read_lane(float x, int src) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src));
 }
 
 __device__ __forceinline__ double fma_s(double a, double b, double c) { return __builtin_fma(a, b, c); }
@@ -380,20 +291,30 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_reg_kernel(const GjArg
       // pivot = (approximately) largest |entry| of column k among the unused rows.  Every wave
       // reduces a 32-bit key (magnitude as float bits with the low byte replaced by 255 - row,
       // so ties go to the lowest row and the winner's row comes for free) with DPP.
+      constexpr int NC = (K + 63) / 64;
+      S cand[NC];
       uint32_t key = 0;
 #pragma unroll
-      for (int rr = lane; rr < K; rr += 64) {
-        const float mag = float(fabs(colbuf[buf][rr]));
-        const uint32_t kk_ = used[rr] ? 0u : ((__float_as_uint(mag) & 0xFFFFFF00u) | uint32_t(255 - rr));
+      for (int q = 0; q < NC; ++q) {
+        const int rr = lane + 64 * q;
+        cand[q] = rr < K ? colbuf[buf][rr] : S(0);
+        const float mag = float(fabs(cand[q]));
+        const uint32_t kk_ = (rr >= K || used[rr < K ? rr : 0]) ? 0u
+                                                                 : ((__float_as_uint(mag) & 0xFFFFFF00u) | uint32_t(255 - rr));
         key = key > kk_ ? key : kk_;
       }
       key = wave_allmax_u32(key);
       const int p = (255 - int(key & 0xFFu)) & (K - 1);
-      const S pv = colbuf[buf][p];
+      // the pivot value comes from the register of the lane that holds it
+      S pv = read_lane(cand[0], p & 63);
+#pragma unroll
+      for (int q = 1; q < NC; ++q) {
+        const S alt = read_lane(cand[q], p & 63);
+        pv = (p >> 6) == q ? alt : pv;
+      }
       dead = dead || (key >> 8) == 0 || !(S(fabs(pv)) > tol);
-      // reciprocal of the pivot: hardware estimate + Newton steps (full precision)
+      // reciprocal of the pivot: hardware estimate (2^-22) + Newton steps to full precision
       S ipiv = S(__builtin_amdgcn_rcpf(float(pv)));
-      ipiv = ipiv * (S(2) - pv * ipiv);
       ipiv = ipiv * (S(2) - pv * ipiv);
       if (sizeof(S) == 8) ipiv = ipiv * (S(2) - pv * ipiv);
       const int prt = p % NRT, pi = p / NRT;
@@ -411,10 +332,13 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_reg_kernel(const GjArg
       S row[CT];
 #pragma unroll
       for (int j = 0; j < CT; ++j) row[j] = rowbuf[buf][ct + j * NCT];
+      S cv[RT];
+#pragma unroll
+      for (int i = 0; i < RT; ++i) cv[i] = colbuf[buf][rt + i * NRT];
 #pragma unroll
       for (int i = 0; i < RT; ++i) {
         const int r = rt + i * NRT;
-        const S nf = r == p ? S(1) - pv : -colbuf[buf][r];
+        const S nf = r == p ? S(1) - pv : -cv[i];
         if (ct == cc) reg[i][jj] = r == p ? S(1) : S(0);
 #pragma unroll
         for (int j = 0; j < CT; ++j) reg[i][j] = fma_s(nf, row[j], reg[i][j]);
@@ -572,7 +496,7 @@ int launch_gj(const GjArgs& a, int nb, hipStream_t st) {
     case 64: hipLaunchKernelGGL((gj_reg_kernel<64, 4, 8, double>), dim3(nb), dim3(128), 0, st, a); break;
     case 128: hipLaunchKernelGGL((gj_reg_kernel<128, 4, 8, double>), dim3(nb), dim3(512), 0, st, a); break;
     case 256: hipLaunchKernelGGL((gj_reg_kernel<256, 8, 8, float>), dim3(nb), dim3(1024), 0, st, a); break;
-    default: hipLaunchKernelGGL(gj_solve_kernel, dim3(nb), dim3(1024), 0, st, a); break;
+    default: return CAFEQ_ERR_UNSUPPORTED;
   }
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;

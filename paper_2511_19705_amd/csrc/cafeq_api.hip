@@ -175,9 +175,6 @@ int plan_adaptive(const cafeq_quant_cfg* cfg, int k, int nb, int rep, int64_t ro
   return CAFEQ_OK;
 }
 
-#ifdef CAFEQ_CORE_TIMING
-long long* g_core_dbg = nullptr;
-#endif
 void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep) {
   p->W = W->data; p->dtype = W->dtype; p->rows = W->rows; p->cols = W->cols; p->ld = W->ld;
   p->rep = rep; p->nseg = pl.nseg; p->nlines = pl.nlines; p->mt_per_seg = pl.mt_per_seg;
@@ -186,9 +183,6 @@ void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep)
   p->rG = nullptr; p->Zout = nullptr; p->codes = nullptr; p->scales = nullptr;
   p->slot_grad = nullptr; p->slot_hdr = nullptr;
   p->grid = make_grid(4);
-#ifdef CAFEQ_CORE_TIMING
-  p->dbg = g_core_dbg;
-#endif
 }
 
 }  // namespace
@@ -252,9 +246,6 @@ const char* cafeq_strerror(int status) {
 
 int cafeq_version(void) { return 100; }
 
-#ifdef CAFEQ_CORE_TIMING
-void cafeq_debug_set_timing_buffer(long long* buf) { g_core_dbg = buf; }
-#endif
 
 int cafeq_profile_enable(int on) {
   cafeq::g_prof.on = on != 0;
@@ -343,7 +334,8 @@ int cafeq_rtn_quantize(const cafeq_mat* W, const cafeq_quant_cfg* cfg, int8_t* c
 int cafeq_block_inverse(const float* T, int k, int nb, float* Tinv, float* rho_row, float* rho_col,
                         int* status, void* ws, void* stream) {
   if (!T || !Tinv) return CAFEQ_ERR_INVALID_ARG;
-  if (k < 1 || k > 256 || nb < 1) return CAFEQ_ERR_BAD_SHAPE;
+  if (nb < 1) return CAFEQ_ERR_BAD_SHAPE;
+  if (k != 32 && k != 64 && k != 128 && k != 256) return CAFEQ_ERR_UNSUPPORTED;
   if (!ws) return CAFEQ_ERR_WORKSPACE;
   return launch_block_inverse(T, k, nb, static_cast<double*>(ws), Tinv, rho_row, rho_col, status,
                               static_cast<hipStream_t>(stream));

@@ -1,8 +1,9 @@
 """Shared comparison rules for the GPU parity tests (tolerances and why).
 
 * integer outputs on the untransformed path: bit-exact.
-* transformed path: the GPU forms Z in float32 (fp32 MFMA accumulation), the oracle in
-  float64 then rounds to float32; both decide the code with the same float32 recipe, so
+* transformed path: the GPU forms Z with float32-level accuracy (exact three-way bfloat16
+  operand split on the matrix cores, float32 accumulation), the oracle in float64 then
+  rounds to float32; both decide the code with the same float32 recipe, so
   codes may differ only where Z sits within accumulation error of a rounding tie: at most
   1e-5 of the codes (at least one allowed on tiny inputs), each by exactly 1, each at a tie.
 * Z itself: |err| <= k * 2^-24 * (|W| . |T|) elementwise (the standard dot-product bound).

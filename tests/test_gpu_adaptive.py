@@ -149,3 +149,46 @@ def test_block_inverse(env, k):
         rho_c = O.rho_from_inverse(ref[None], O.ROW)
         np.testing.assert_allclose(rr.cpu().numpy()[b * k:(b + 1) * k], rho_r, rtol=1e-5)
         np.testing.assert_allclose(rc_.cpu().numpy()[b * k:(b + 1) * k], rho_c, rtol=1e-5)
+
+
+@pytest.mark.parametrize("k", [32, 128, 256])
+@pytest.mark.parametrize("scale", [1e-4, 1.0, 3e3])
+def test_block_inverse_general_matrices(env, k, scale):
+    """Dense Gaussian blocks (condition number of order k, pivots far from 1, rows that need
+    pivoting) at several magnitudes: the elimination pre-scales by a power of two, so the
+    accuracy relative to the inverse's largest entry must not depend on the magnitude."""
+    torch, cafeq = env
+    rng = np.random.default_rng(900 + k)
+    T = (rng.standard_normal((4, k, k)) * scale).astype(np.float32)
+    T[2, 0, 0] = 0.0                            # a zero in the first pivot position
+    Tinv, rr, rc_, status = cafeq.block_inverse(_dev(torch, T), want_rho=True)
+    torch.cuda.synchronize()
+    assert list(status.cpu().numpy()) == [0, 0, 0, 0]
+    for b in range(4):
+        A = T[b].astype(np.float64)
+        ref = np.linalg.inv(A)
+        got = Tinv[b].cpu().numpy().astype(np.float64)
+        # float32 output rounding plus conditioning: residual check against the identity
+        res = np.abs(got @ A - np.eye(k)).max()
+        assert res <= 2e-6 * np.linalg.cond(A), (b, res)
+        np.testing.assert_allclose(got, ref, rtol=0, atol=4e-6 * np.abs(ref).max())
+        np.testing.assert_allclose(rr.cpu().numpy()[b * k:(b + 1) * k], (ref ** 2).sum(1), rtol=2e-5)
+        np.testing.assert_allclose(rc_.cpu().numpy()[b * k:(b + 1) * k], (ref ** 2).sum(0), rtol=2e-5)
+
+
+def test_block_inverse_singular_block_is_zeroed(env):
+    torch, cafeq = env
+    T = WL.perturbed_blocks(2, 64, 77, eps=0.2)
+    T[0, 5] = T[0, 9]                           # two equal rows
+    Tinv, rr, rc_, status = cafeq.block_inverse(_dev(torch, T), want_rho=True)
+    torch.cuda.synchronize()
+    assert list(status.cpu().numpy()) == [1, 0]
+    assert float(Tinv[0].abs().max()) == 0.0
+    assert float(rr[:64].abs().max()) == 0.0 and float(rc_[:64].abs().max()) == 0.0
+
+
+def test_block_inverse_rejects_other_block_sizes(env):
+    torch, cafeq = env
+    T = np.stack([np.eye(48, dtype=np.float32)] * 2)
+    with pytest.raises(Exception):
+        cafeq.block_inverse(_dev(torch, T))
