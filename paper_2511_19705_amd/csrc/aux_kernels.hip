@@ -359,12 +359,21 @@ __global__ __launch_bounds__(256) void bgemm_mfma_kernel(const float* __restrict
   for (int l0 = 0; l0 < K; l0 += CH) {
     const int nl = K - l0 < CH ? K - l0 : CH;   // 64 or 128
     const int sh = nl == 64 ? 6 : 7;
-    for (int e = tid; e < nl * 64; e += 256) {
-      // sa[l][i] = op(A)[i0 + i][l0 + l];  sb[l][j] = op(B)[l0 + l][j0 + j]
-      if (TA) { const int l = e / 64, i = e % 64; sa[l * LD + i] = Ab[(l0 + l) * K + i0 + i]; }
-      else    { const int i = e >> sh, l = e & (nl - 1); sa[l * LD + i] = Ab[(i0 + i) * K + l0 + l]; }
-      if (TB) { const int j = e >> sh, l = e & (nl - 1); sb[l * LD + j] = Bb[(j0 + j) * K + l0 + l]; }
-      else    { const int l = e / 64, j = e % 64; sb[l * LD + j] = Bb[(l0 + l) * K + j0 + j]; }
+    // sa[l][i] = op(A)[i0 + i][l0 + l];  sb[l][j] = op(B)[l0 + l][j0 + j]; eight elements of
+    // each panel per thread and round, all loads of a round issued before the first LDS store
+    for (int e0 = tid; e0 < nl * 64; e0 += 8 * 256) {
+      float va[8], vb[8];
+      int da[8], db[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int e = e0 + u * 256;
+        if (TA) { const int l = e >> 6, i = e & 63; da[u] = l * LD + i; va[u] = Ab[(l0 + l) * K + i0 + i]; }
+        else    { const int i = e >> sh, l = e & (nl - 1); da[u] = l * LD + i; va[u] = Ab[(i0 + i) * K + l0 + l]; }
+        if (TB) { const int j = e >> sh, l = e & (nl - 1); db[u] = l * LD + j; vb[u] = Bb[(j0 + j) * K + l0 + l]; }
+        else    { const int l = e >> 6, j = e & 63; db[u] = l * LD + j; vb[u] = Bb[(l0 + l) * K + j0 + j]; }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { sa[da[u]] = va[u]; sb[db[u]] = vb[u]; }
     }
     __syncthreads();
     const float* pa = sa + h * LD + wi * 32 + ln;
