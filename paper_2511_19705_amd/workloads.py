@@ -158,22 +158,45 @@ def config5_shapes(d_model=4608, d_ff=36864, n_q=32, n_kv=16, head=128):
     ]
 
 
-def config5(scale=1):
-    """All seven weights of the 27B-shaped layer as bf16 bit patterns (uint16).
-    ``scale`` divides d_model and d_ff (for CPU-sized twins)."""
+def config5_meta(scale=1):
+    """Sizes and transforms of the 27B-shaped layer (``scale`` divides d_model and d_ff)."""
     d_model, d_ff = 4608 // scale, 36864 // scale
     n_q, n_kv, head = 32 // scale if scale <= 2 else max(2, 32 // scale), \
         16 // scale if scale <= 2 else max(1, 16 // scale), 128
+    return dict(k=128, group=128, bits=(3, 4), d_model=d_model, d_ff=d_ff,
+                n_q=n_q, n_kv=n_kv, head=head, rep=n_q // n_kv)
+
+
+def config5_transform(which, scale=1):
+    """Haar blocks of the layer: 'single' (input dim of q, k, gate), 'mlp' (down/up pair),
+    'vo' (one block per kv head)."""
+    m = config5_meta(scale)
+    if which == "single":
+        return haar_blocks(m["d_model"] // 128, 128, 508)
+    if which == "mlp":
+        return haar_blocks(m["d_ff"] // 128, 128, 509)
+    return haar_blocks(m["n_kv"], 128, 510)
+
+
+def config5_tensor(name, scale=1):
+    """One weight of the 27B-shaped layer as bf16 bit patterns (uint16) + its axis and role."""
+    m = config5_meta(scale)
+    for i, (nm, r, c, axis, role) in enumerate(
+            config5_shapes(m["d_model"], m["d_ff"], m["n_q"], m["n_kv"], m["head"])):
+        if nm == name:
+            return dict(bits16=to_bf16_bits(student_t3((r, c), 501 + i)), axis=axis, role=role)
+    raise KeyError(name)
+
+
+def config5(scale=1):
+    """All seven weights of the 27B-shaped layer as bf16 bit patterns (uint16).
+    ``scale`` divides d_model and d_ff (for CPU-sized twins)."""
+    m = config5_meta(scale)
     out = {}
-    for i, (name, r, c, axis, role) in enumerate(
-            config5_shapes(d_model, d_ff, n_q, n_kv, head)):
-        out[name] = dict(bits16=to_bf16_bits(student_t3((r, c), 501 + i)),
-                         axis=axis, role=role)
-    out["_meta"] = dict(k=128, group=128, bits=(3, 4), d_model=d_model, d_ff=d_ff,
-                        n_q=n_q, n_kv=n_kv, head=head, rep=n_q // n_kv,
-                        T_single=haar_blocks(d_model // 128, 128, 508),
-                        T_mlp=haar_blocks(d_ff // 128, 128, 509),
-                        T_vo=haar_blocks(n_kv, 128, 510))
+    for nm, _, _, _, _ in config5_shapes(m["d_model"], m["d_ff"], m["n_q"], m["n_kv"], m["head"]):
+        out[nm] = config5_tensor(nm, scale)
+    out["_meta"] = dict(m, T_single=config5_transform("single", scale),
+                        T_mlp=config5_transform("mlp", scale), T_vo=config5_transform("vo", scale))
     return out
 
 
