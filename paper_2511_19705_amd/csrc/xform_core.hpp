@@ -73,7 +73,7 @@ struct Geo {
   // stored at chunk ^ ((row >> 2) & 3) so that 16 lanes reading one chunk hit 64 distinct banks)
   static constexpr int PLANEB = K * 64;                    // one plane of one stage
   static constexpr int STAGEB = kFwdPlanes * PLANEB;       // one ring stage
-  static constexpr int RING_STAGES = K <= 128 ? 3 : 2;
+  static constexpr int RING_STAGES = (L == 32 || K > 128) ? 2 : 3;   // fetch distance RING_STAGES - 1 <= NT
   static constexpr int RINGB = RING_STAGES * STAGEB;
   // gradient staging: W parts (hi, mid) transposed [m][line], per-group arg-max / coefficient
   static constexpr int WST_ROWB = 2 * kMacroLines + 16;
@@ -133,6 +133,24 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uintx4 v) { return __builtin_bit_cas
 
 #define CAFEQ_MFMA_BF16(A, B, C) __builtin_amdgcn_mfma_f32_32x32x16_bf16((A), (B), (C), 0, 0, 0)
 
+// s_waitcnt vmcnt(n) for a value of n that is a compile-time constant after unrolling (n is
+// clamped to the counter's 6 bits; a smaller n only waits for more).
+#define CAFEQ_VMW(N) case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
+__device__ __forceinline__ void vm_wait(int n) {
+  switch (n > 63 ? 63 : n) {
+    CAFEQ_VMW(0) CAFEQ_VMW(1) CAFEQ_VMW(2) CAFEQ_VMW(3) CAFEQ_VMW(4) CAFEQ_VMW(5) CAFEQ_VMW(6) CAFEQ_VMW(7)
+    CAFEQ_VMW(8) CAFEQ_VMW(9) CAFEQ_VMW(10) CAFEQ_VMW(11) CAFEQ_VMW(12) CAFEQ_VMW(13) CAFEQ_VMW(14) CAFEQ_VMW(15)
+    CAFEQ_VMW(16) CAFEQ_VMW(17) CAFEQ_VMW(18) CAFEQ_VMW(19) CAFEQ_VMW(20) CAFEQ_VMW(21) CAFEQ_VMW(22) CAFEQ_VMW(23)
+    CAFEQ_VMW(24) CAFEQ_VMW(25) CAFEQ_VMW(26) CAFEQ_VMW(27) CAFEQ_VMW(28) CAFEQ_VMW(29) CAFEQ_VMW(30) CAFEQ_VMW(31)
+    CAFEQ_VMW(32) CAFEQ_VMW(33) CAFEQ_VMW(34) CAFEQ_VMW(35) CAFEQ_VMW(36) CAFEQ_VMW(37) CAFEQ_VMW(38) CAFEQ_VMW(39)
+    CAFEQ_VMW(40) CAFEQ_VMW(41) CAFEQ_VMW(42) CAFEQ_VMW(43) CAFEQ_VMW(44) CAFEQ_VMW(45) CAFEQ_VMW(46) CAFEQ_VMW(47)
+    CAFEQ_VMW(48) CAFEQ_VMW(49) CAFEQ_VMW(50) CAFEQ_VMW(51) CAFEQ_VMW(52) CAFEQ_VMW(53) CAFEQ_VMW(54) CAFEQ_VMW(55)
+    CAFEQ_VMW(56) CAFEQ_VMW(57) CAFEQ_VMW(58) CAFEQ_VMW(59) CAFEQ_VMW(60) CAFEQ_VMW(61) CAFEQ_VMW(62)
+    default: asm volatile("s_waitcnt vmcnt(63)" ::: "memory"); break;
+  }
+}
+#undef CAFEQ_VMW
+
 template <int K, int G, int AXIS>
 __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p) {
   using g = Geo<K, G>;
@@ -156,63 +174,49 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
   const int64_t mt0 = chunk_begin(w, p.n_mt, p.nwg), mt1 = chunk_begin(w + 1, p.n_mt, p.nwg);
   if (mt0 >= mt1) return;
 
-  const int tiles_per_mt = p.do_inverse ? 2 * NT : NT;
-  const int total_tiles = int(mt1 - mt0) * tiles_per_mt;
-
-  // The transform tiles are consumed in a fixed order: for each macro-tile, the NT forward
-  // tiles then (loss calls) the NT inverse tiles of its segment.  The fetch cursor runs
-  // NSTG-1 tiles ahead of the consumer and advances without divisions.
+  // The operand stages are consumed in a fixed order: for each macro-tile, the NT forward stages
+  // of its segment, then (loss calls) the NT inverse stages.  The fill of the stage NSTG-1 steps
+  // ahead is issued at the top of every step; which stage that is follows from the (unrolled)
+  // step index, so the fetch needs no cursor: only the block ids of this macro-tile's segment
+  // (cb) and of the next macro-tile's (nbk).
   const int seg_first = int(mt0 / p.mt_per_seg);
   const int mis_first = int(mt0 - int64_t(seg_first) * p.mt_per_seg);   // macro-tile within segment
   const int mt_per_seg = int(p.mt_per_seg);
-  int f_tau = 0, f_seg = seg_first, f_mis = mis_first;   // fetch cursor
-  // Asynchronous copy of the cursor's stage from global memory (L2) into ring stage `dst_stage`
-  // with the LDS-DMA load (16 bytes per lane, lane i of a wave lands at base + 16 i): no registers,
-  // no LDS store instructions.  Returns the number of loads this wave issued.
-  auto stage_issue = [&](int dst_stage) -> int {
-    int tau = f_tau;
-    const uint16_t* base = p.Afwd;
-    int np = kFwdPlanes;
-    if (tau >= NT) { tau -= NT; base = p.Ainv; np = kInvPlanes; }
-    const int nchunks = np * (PLANEB / 16);                 // multiple of 64
-    const int blk = f_seg * NBLK + tau / KT;
-    const int b = (AXIS == CAFEQ_AXIS_ROW && p.rep != 1) ? blk / p.rep : blk;
-    // stage (tau % KT) of block b: np planes of K x 32 bf16, contiguous and already swizzled
-    const float4* src = reinterpret_cast<const float4*>(base + (int64_t(b) * KT + tau % KT) * np * (K * 32));
-    // LDS byte address of the destination (dynamic LDS starts at 0: the kernel has no static LDS)
-    const uint32_t dst = uint32_t(dst_stage) * STAGEB;
-    int issued = 0;
+  constexpr int D = NSTG - 1;
+  constexpr int NFW = kFwdPlanes * PLANEB / 16 / kThreads;   // loads every wave issues per forward stage
+  constexpr int NIW = kInvPlanes * PLANEB / 16 / kThreads;   // ... per inverse stage (K = 32: some waves one more)
+  constexpr int NWL = AXIS == CAFEQ_AXIS_COL ? L / 8 : L / 2; // load instructions of one strip's weights
+  const uint32_t voff = uint32_t(tid) * 16u;
+  auto blk_id = [&](int sg_, int blk) {
+    const int gb = sg_ * NBLK + blk;
+    return (AXIS == CAFEQ_AXIS_ROW && p.rep != 1) ? gb / p.rep : gb;
+  };
+  // Asynchronous copy of stage s of block bid (np planes of K x 32 bf16, contiguous and already
+  // swizzled) from global memory (L2) into ring stage dst_stage with the LDS-DMA load: 16 bytes
+  // per lane, lane i of a wave lands at base + 16 i; no registers, no LDS store instructions.
+  // Issued as opaque assembly on purpose: the compiler would otherwise drain every outstanding
+  // load before each later LDS read (it cannot see that the ring stage being filled is not the
+  // one being read); completion is tracked with vm_wait() below.  The LDS byte address assumes
+  // that dynamic LDS starts at 0 (the kernel has no static LDS).
+  auto dma = [&](const uint16_t* base, int np, int bid, int s_, int dst_stage) {
+    const unsigned char* src = reinterpret_cast<const unsigned char*>(base) +
+                               (int64_t(bid) * KT + s_) * (int64_t(np) * PLANEB);
+    const uint32_t dst = uint32_t(dst_stage) * STAGEB + uint32_t(wave_u) * 1024u;
+    const int nch = np * (PLANEB / 16);
 #pragma unroll
     for (int i = 0; i < g::A_VEC_PER_THREAD; ++i) {
-      const int c0 = i * kThreads + wave_u * 64;            // first chunk of this wave's instruction
-      if (c0 < nchunks) {
-        // Issued as opaque assembly on purpose: the compiler would otherwise drain every
-        // outstanding load before each later LDS read (it cannot see that the ring stage being
-        // filled is not the one being read); completion is tracked by stage_wait() below.
-        const float4* gp = src + c0 + lane;
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                     :: "s"(dst + uint32_t(c0) * 16u), "v"(gp) : "memory");
-        ++issued;
+      if (i * kThreads + 3 * 64 < nch || i * kThreads + wave_u * 64 < nch) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :: "s"(dst + uint32_t(i) * 4096u), "v"(voff), "s"(src + i * 4096) : "memory");
       }
     }
-    if (++f_tau == tiles_per_mt) {
-      f_tau = 0;
-      if (++f_mis == mt_per_seg) { f_mis = 0; ++f_seg; }
-    }
-    return issued;
   };
-  // Before the barrier that ends a tile step the NEXT step's stage must have landed.  Loads
-  // complete in order, so it has once at most the loads issued during this step are pending.
-  auto stage_wait = [&](int issued_this_step) {
-    if (issued_this_step >= 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-    else if (issued_this_step >= 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    else if (issued_this_step >= 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-    else if (issued_this_step >= 1) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  };
+  int cb[NBLK], nbk[NBLK];
+#pragma unroll
+  for (int i = 0; i < NBLK; ++i) cb[i] = nbk[i] = blk_id(seg_first, i);
 
-  stage_issue(0);
-  if (NSTG > 2 && total_tiles > 1) stage_issue(1);
+  dma(p.Afwd, kFwdPlanes, cb[0], 0, 0);
+  if (D == 2) dma(p.Afwd, kFwdPlanes, cb[1 / KT], 1 % KT, 1);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
@@ -232,8 +236,7 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
     for (int v = 0; v < 16; ++v) gt[i][v] = 0.f;
 
   int cur_seg = seg_first;
-  int tile = 0;        // tiles consumed so far
-  int stage = 0;       // ring stage of the tile being consumed
+  int stage = 0;       // ring stage being consumed
 
   auto flush = [&](int seg) {
     // reduce the per-lane sums and publish this (workgroup, segment) partial
@@ -351,6 +354,13 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
     const int64_t ax0 = int64_t(seg) * L;  // first axis index of the segment
     int nseg_ = seg, nmis = mis + 1;       // the macro-tile after this one
     if (nmis == mt_per_seg) { nmis = 0; ++nseg_; }
+    // what the prefetches of this macro-tile aim at: the next macro-tile, or (last one of the
+    // workgroup) this one again, so that every step issues the same loads and the waits on the
+    // memory counter are compile-time constants
+    const bool has_next = mt + 1 < mt1;
+    const int pseg = has_next ? nseg_ : seg, pmis = has_next ? nmis : mis;
+#pragma unroll
+    for (int i = 0; i < NBLK; ++i) nbk[i] = blk_id(pseg, i);
     // All of this strip's weights are needed within the next few steps; waiting for the last of
     // them here (one wait) keeps the compiler from draining the in-flight ring fills later, at
     // the first use of each late register.
@@ -370,8 +380,17 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
     unsigned char* wcol = wst + (wave * kStripLines + ln) * 2;
 #pragma unroll
     for (int sg = 0; sg < NT; ++sg) {               // stage = 32 inputs; sg / KT is the block
-      int issued = 0;
-      if (tile + (NSTG - 1) < total_tiles) issued = stage_issue(stage == 0 ? NSTG - 1 : stage - 1);
+      int nw = NFW;
+      {
+        const int tq = sg + D, dst = stage == 0 ? NSTG - 1 : stage - 1;
+        if (tq < NT) {
+          dma(p.Afwd, kFwdPlanes, cb[tq / KT], tq % KT, dst);
+        } else {
+          nw = NIW;
+          if (p.do_inverse) dma(p.Ainv, kInvPlanes, cb[(tq - NT) / KT], (tq - NT) % KT, dst);
+          else dma(p.Afwd, kFwdPlanes, nbk[(tq - NT) / KT], (tq - NT) % KT, dst);
+        }
+      }
       const unsigned char* sbase = ring + stage * STAGEB;
       const int blk = sg / KT;
 #pragma unroll
@@ -426,9 +445,11 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
 #pragma unroll
         for (int t = 0; t < KT; ++t) acc[blk * KT + t] = CAFEQ_MFMA_BF16(xh[t], vbh, acc[blk * KT + t]);
       }
-      stage_wait(issued);
+      // The stage consumed D steps from now was issued D - 1 steps ago and must have landed
+      // before the barrier.  Loads complete in order, so it has once only younger loads are
+      // pending: this step's fill when D = 2, nothing when D = 1.
+      vm_wait(D == 2 ? nw : 0);
       __syncthreads();
-      ++tile;
       stage = stage == NSTG - 1 ? 0 : stage + 1;
     }
 
@@ -612,11 +633,25 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
 
     // ---- the next strip's weights: wreg and the W parts are dead from here on (the staged
     // copy is read by the other waves, protected by the barriers of the inverse phase)
-    if (mt + 1 < mt1) load_w(nseg_, nmis);
+    if (!p.do_inverse) load_w(pseg, pmis);
 
     // ---- inverse transform of the error and the l2 proxy: same stage order; the error registers
     // 8c..8c+7 of the lane are the B operand of step c, split on the fly into hi + mid
     if (p.do_inverse) {
+      // B operand of MFMA step c: the lane's error registers 8c..8c+7 as bfloat16 hi and mid parts
+      auto split_e = [&](int c, bf16x8& vh, bf16x8& vm) {
+        uint32_t eh[4], em[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int f0 = 8 * c + 2 * i;
+          const float x0 = err[f0], x1 = err[f0 + 1];
+          const uint32_t ph = pack_bf16(x0, x1);
+          eh[i] = ph;
+          em[i] = pack_bf16(x0 - bf16_lo_f32(ph), x1 - bf16_hi_f32(ph));
+        }
+        vh = as_bf16x8(eh[0], eh[1], eh[2], eh[3]);
+        vm = as_bf16x8(em[0], em[1], em[2], em[3]);
+      };
 #pragma unroll
       for (int blk = 0; blk < NBLK; ++blk) {
         floatx16 d[KT];
@@ -624,26 +659,28 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
         for (int t = 0; t < KT; ++t)
 #pragma unroll
           for (int v = 0; v < 16; ++v) d[t][v] = 0.f;
+        bf16x8 veh, vem;
+        split_e(2 * blk * KT, veh, vem);
 #pragma unroll
         for (int s2 = 0; s2 < KT; ++s2) {
           const int sg = blk * KT + s2;
-          int issued = 0;
-          if (tile + (NSTG - 1) < total_tiles) issued = stage_issue(stage == 0 ? NSTG - 1 : stage - 1);
+          int nw = NIW;
+          {
+            const int tq = sg + D, dst = stage == 0 ? NSTG - 1 : stage - 1;
+            if (tq < NT) {
+              dma(p.Ainv, kInvPlanes, cb[tq / KT], tq % KT, dst);
+            } else {
+              nw = NFW;
+              dma(p.Afwd, kFwdPlanes, nbk[(tq - NT) / KT], (tq - NT) % KT, dst);
+            }
+          }
+          // The next strip's weights, right behind the first inverse stage's fill: they are
+          // younger than that fill, so the two following waits may leave them pending.
+          if (sg == 0) load_w(pseg, pmis);
           const unsigned char* sbase = ring + stage * STAGEB;
 #pragma unroll
           for (int c2 = 0; c2 < 2; ++c2) {
             const int c = 2 * sg + c2;
-            uint32_t eh[4], em[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const int f0 = 8 * c + 2 * i;
-              const float x0 = err[f0], x1 = err[f0 + 1];
-              const uint32_t ph = pack_bf16(x0, x1);
-              eh[i] = ph;
-              em[i] = pack_bf16(x0 - bf16_lo_f32(ph), x1 - bf16_hi_f32(ph));
-            }
-            const bf16x8 veh = as_bf16x8(eh[0], eh[1], eh[2], eh[3]);
-            const bf16x8 vem = as_bf16x8(em[0], em[1], em[2], em[3]);
             const int ao = c2 == 0 ? aoff0 : aoff1;
             bf16x8 xh[KT], xm[KT];
 #pragma unroll
@@ -652,16 +689,27 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
               xh[t] = as_bf16x8(*reinterpret_cast<const uintx4*>(ap));
               xm[t] = as_bf16x8(*reinterpret_cast<const uintx4*>(ap + PLANEB));
             }
+            __builtin_amdgcn_sched_barrier(0);   // all operand reads in flight before the first MFMA
+            // the next step's operand split runs in the shadow of this step's MFMAs
+            bf16x8 nveh = veh, nvem = vem;
+            const bool more = !(s2 == KT - 1 && c2 == 1);
+            if (more) split_e(c + 1, nveh, nvem);
 #pragma unroll
             for (int t = 0; t < KT; ++t) d[t] = CAFEQ_MFMA_BF16(xm[t], veh, d[t]);
 #pragma unroll
             for (int t = 0; t < KT; ++t) d[t] = CAFEQ_MFMA_BF16(xh[t], vem, d[t]);
 #pragma unroll
             for (int t = 0; t < KT; ++t) d[t] = CAFEQ_MFMA_BF16(xh[t], veh, d[t]);
+            // requested issue order: one MFMA, then three vector instructions of the split
+#pragma unroll
+            for (int i = 0; i < 3 * KT; ++i) {
+              __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+              __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+            }
+            veh = nveh; vem = nvem;
           }
-          stage_wait(issued);
+          vm_wait((D == 2 ? nw : 0) + (sg < D ? NWL : 0));   // the weights loads are younger for D steps
           __syncthreads();
-          ++tile;
           stage = stage == NSTG - 1 ? 0 : stage + 1;
         }
 #pragma unroll
@@ -672,7 +720,10 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
     }
     seg = nseg_;
     mis = nmis;
+#pragma unroll
+    for (int i = 0; i < NBLK; ++i) cb[i] = nbk[i];
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the last macro-tile's (unused) prefetches
   if (p.do_inverse || p.do_grad) flush(cur_seg);
 }
 
