@@ -41,7 +41,9 @@ struct CorePlan {
 
 bool supported_block(int k) { return k == 32 || k == 64 || k == 128 || k == 256; }
 
-int make_plan(int K, int G, int64_t nlines, int64_t naxis, CorePlan* pl) {
+// grad: the launch will ask for the gradient.  Without it, segments of up to 128 run two
+// workgroups per compute unit.
+int make_plan(int K, int G, int64_t nlines, int64_t naxis, CorePlan* pl, bool grad = true) {
   if (!supported_block(K)) return CAFEQ_ERR_UNSUPPORTED;
   if (!(G == 32 || G == 64 || G == 128 || G == 256)) return CAFEQ_ERR_UNSUPPORTED;
   pl->K = K; pl->G = G; pl->L = K > G ? K : G;
@@ -51,7 +53,8 @@ int make_plan(int K, int G, int64_t nlines, int64_t naxis, CorePlan* pl) {
   pl->nseg = int(naxis / pl->L);
   pl->mt_per_seg = (nlines + kMacroLines - 1) / kMacroLines;
   pl->n_mt = pl->mt_per_seg * pl->nseg;
-  int64_t nwg = std::min<int64_t>(pl->n_mt, device_cu_count());
+  const int per_cu = (!grad && pl->L <= 128) ? 2 : 1;
+  int64_t nwg = std::min<int64_t>(pl->n_mt, int64_t(device_cu_count()) * per_cu);
   if (nwg > 8) nwg -= nwg % 8;
   pl->nwg = int(nwg);
   pl->nslot = pl->nwg + pl->nseg;
@@ -158,8 +161,8 @@ int plan_adaptive(const cafeq_quant_cfg* cfg, int k, int nb, int rep, int64_t ro
   int rc;
   if ((rc = resolve_group(cfg, colsA, &ap->GA))) return rc;
   if ((rc = resolve_group(cfg, rowsB, &ap->GB))) return rc;
-  if ((rc = make_plan(k, ap->GA, rowsA, colsA, &ap->planU))) return rc;
-  if ((rc = make_plan(k, ap->GB, colsB, rowsB, &ap->planV))) return rc;
+  if ((rc = make_plan(k, ap->GA, rowsA, colsA, &ap->planU, false))) return rc;
+  if ((rc = make_plan(k, ap->GB, colsB, rowsB, &ap->planV, false))) return rc;
   split_contraction(rowsA, nb * (k / 32), &ap->chunkA, &ap->nchunkA);
   split_contraction(colsB, nb * rep * (k / 32), &ap->chunkB, &ap->nchunkB);
   const size_t nz = size_t(std::max(ap->nchunkA, rep * ap->nchunkB));
@@ -287,16 +290,22 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
       const int64_t naxis = col ? a->cols : a->rows, nlines = col ? a->rows : a->cols;
       int G;
       CorePlan pl;
-      if (resolve_group(cfg, naxis, &G) || make_plan(x->k, G, nlines, naxis, &pl)) return 0;
-      return carve_single(nullptr, pl, x->nb, true).bytes;
+      CorePlan pn;
+      if (resolve_group(cfg, naxis, &G) || make_plan(x->k, G, nlines, naxis, &pl, true) ||
+          make_plan(x->k, G, nlines, naxis, &pn, false))
+        return 0;
+      return std::max(carve_single(nullptr, pl, x->nb, true).bytes, carve_single(nullptr, pn, x->nb, false).bytes);
     }
     case CAFEQ_CALL_DUAL_PROXY_LOSS: {
       if (!a || !b || !x || !cfg) return 0;
       int GA, GB;
       CorePlan pa, pb;
       if (resolve_group(cfg, a->cols, &GA) || resolve_group(cfg, b->rows, &GB)) return 0;
-      if (make_plan(x->k, GA, a->rows, a->cols, &pa) || make_plan(x->k, GB, b->cols, b->rows, &pb)) return 0;
-      return carve_dual(nullptr, pa, pb, x->nb, true).bytes;
+      CorePlan na, nbp;
+      if (make_plan(x->k, GA, a->rows, a->cols, &pa, true) || make_plan(x->k, GB, b->cols, b->rows, &pb, true) ||
+          make_plan(x->k, GA, a->rows, a->cols, &na, false) || make_plan(x->k, GB, b->cols, b->rows, &nbp, false))
+        return 0;
+      return std::max(carve_dual(nullptr, pa, pb, x->nb, true).bytes, carve_dual(nullptr, na, nbp, x->nb, false).bytes);
     }
     case CAFEQ_CALL_ADAPTIVE_ROUND: {
       // a: U [rowsA][nb*k], b: V [nb*rep*k][colsB]
@@ -355,7 +364,7 @@ int cafeq_apply_transform(const cafeq_mat* W, const cafeq_xform* x, int axis, in
   if (!ws) return CAFEQ_ERR_WORKSPACE;
   const bool col = axis == CAFEQ_AXIS_COL;
   CorePlan pl;
-  rc = make_plan(x->k, x->k, col ? W->rows : W->cols, col ? W->cols : W->rows, &pl);
+  rc = make_plan(x->k, x->k, col ? W->rows : W->cols, col ? W->cols : W->rows, &pl, false);
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   uint16_t* planes = static_cast<uint16_t*>(ws);
@@ -391,7 +400,7 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   if (rc) return rc;
   const int K = x->k, nb = x->nb;
   CorePlan pl;
-  rc = make_plan(K, G, nlines, naxis, &pl);
+  rc = make_plan(K, G, nlines, naxis, &pl, gradT != nullptr);
   if (rc) return rc;
   {
     const size_t lds = core_lds_bytes(K, G, gradT != nullptr);
@@ -451,9 +460,9 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   if ((rc = resolve_group(cfg, A->cols, &GA))) return rc;
   if ((rc = resolve_group(cfg, B->rows, &GB))) return rc;
   CorePlan pa, pb;
-  if ((rc = make_plan(K, GA, A->rows, A->cols, &pa))) return rc;
-  if ((rc = make_plan(K, GB, B->cols, B->rows, &pb))) return rc;
   const bool grad = gradT != nullptr;
+  if ((rc = make_plan(K, GA, A->rows, A->cols, &pa, grad))) return rc;
+  if ((rc = make_plan(K, GB, B->cols, B->rows, &pb, grad))) return rc;
   {
     const size_t la = core_lds_bytes(K, GA, grad), lb = core_lds_bytes(K, GB, grad);
     if (la == 0 || lb == 0 || la > kLdsLimit || lb > kLdsLimit) return CAFEQ_ERR_UNSUPPORTED;

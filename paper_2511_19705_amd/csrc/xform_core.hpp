@@ -151,9 +151,14 @@ __device__ __forceinline__ void vm_wait(int n) {
 }
 #undef CAFEQ_VMW
 
-template <int K, int G, int AXIS>
-__global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p) {
+// GRAD = false compiles the gradient out: for segments of up to 128 that variant fits in half
+// the register file and needs no weight staging area, so two workgroups share a compute unit
+// (two waves per SIMD).
+template <int K, int G, int AXIS, bool GRAD>
+__global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) void xform_core_kernel(const CoreParams p) {
   using g = Geo<K, G>;
+  constexpr bool GRAD_ON = GRAD && g::GRAD_OK;
+  constexpr int GTN = GRAD_ON ? g::GT : 1;
   constexpr int L = g::L, NT = g::NT, KT = g::KT, NGRP = g::NGRP, RPG = g::RPG, NBLK = g::NBLK;
   constexpr int PLANEB = g::PLANEB, STAGEB = g::STAGEB, NSTG = g::RING_STAGES;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -229,9 +234,9 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
 
   // gradient tiles of this wave: tile rows r = wave, wave + 4, ... (< NT), KT tiles each;
   // element [j = r*32 + 8(v/4)+4h+v%4][m = mt*32 + ln] of the segment's k x k blocks
-  floatx16 gt[g::GT_ALLOC];
+  floatx16 gt[GTN];
 #pragma unroll
-  for (int i = 0; i < g::GT_ALLOC; ++i)
+  for (int i = 0; i < GTN; ++i)
 #pragma unroll
     for (int v = 0; v < 16; ++v) gt[i][v] = 0.f;
 
@@ -259,7 +264,7 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
       if (tid == kHdrMref) t = m_ref;
       p.slot_hdr[slot * kHdrFloats + tid] = t;
     }
-    if constexpr (g::GRAD_OK) if (p.do_grad) {
+    if constexpr (GRAD_ON) if (p.do_grad) {
       float* dst = p.slot_grad + slot * int64_t(NBLK * K * K);
 #pragma unroll
       for (int gr = 0; gr < g::GT_ROWS; ++gr) {
@@ -407,7 +412,7 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
           bh[i] = ph; bm[i] = pm;
           bl[i] = pack_bf16(r0 - bf16_lo_f32(pm), r1 - bf16_hi_f32(pm));
         }
-        if constexpr (g::GRAD_OK) if (p.do_grad) {
+        if constexpr (GRAD_ON) if (p.do_grad) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const int m0 = 16 * c + 8 * (i / 2) + 4 * h + 2 * (i % 2);   // inputs of the packed pair: m0, m0+1
@@ -464,11 +469,15 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
             *reinterpret_cast<float4*>(dst + 32 * t + 8 * q) =
                 make_float4(acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]);
       } else {
-        float* dst = p.Zout + (ax0 + 4 * h) * p.cols + line;
+        // uniform row pointer (bumped by whole rows) + 32-bit lane offset
+        const uint32_t loff = uint32_t(4 * h) * uint32_t(p.cols) + uint32_t(line);
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) dst[int64_t(32 * t + 8 * (v / 4) + (v % 4)) * p.cols] = acc[t][v];
+          for (int v = 0; v < 16; ++v) {
+            float* rowp = p.Zout + (ax0 + 32 * t + 8 * (v / 4) + (v % 4)) * p.cols;
+            rowp[loff] = acc[t][v];
+          }
       }
     }
 
@@ -483,13 +492,14 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
 #pragma unroll
       for (int gi = 0; gi < NGRP; ++gi) {
         float a = -1.f, zs = 0.f;
-        int j = 0;
+        int jf = 0;   // arg-max index without the lane-half term 4h: an immediate per register
 #pragma unroll
         for (int f = gi * RPG; f < (gi + 1) * RPG; ++f) {
           const float z = acc[f / 16][f % 16];
           const float v = fabsf(z);
-          if (v > a) { a = v; zs = z; j = 8 * (f / 4) + 4 * h + (f % 4); }
+          if (v > a) { a = v; zs = z; jf = 8 * (f / 4) + (f % 4); }
         }
+        int j = jf + 4 * h;
         const float oz = __shfl_xor(zs, 32);
         const int oj = __shfl_xor(j, 32);
         const float oa = fabsf(oz);
@@ -530,8 +540,11 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
           if (AXIS == CAFEQ_AXIS_COL) {
             *reinterpret_cast<uint32_t*>(p.codes + line * p.cols + ax0 + j0) = qpk[f4];
           } else {
+            // uniform row pointer + 32-bit lane offset
+            int8_t* rowp = p.codes + (ax0 + 8 * f4) * p.cols;
+            const uint32_t loff = uint32_t(4 * h) * uint32_t(p.cols) + uint32_t(line);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) p.codes[(ax0 + j0 + e) * p.cols + line] = int8_t(qpk[f4] >> (8 * e));
+            for (int e = 0; e < 4; ++e) rowp[loff + uint32_t(e) * uint32_t(p.cols)] = int8_t(qpk[f4] >> (8 * e));
           }
         }
       }
@@ -549,9 +562,9 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
         for (int ww = 1; ww < kNW; ++ww) nm = fmaxf(nm, wmax[ww]);
         if (nm > m_ref) {                                       // uniform over the workgroup
           const float sc = __expf(p.lse_t * (m_ref - nm));      // 0 on the first macro-tile
-          if constexpr (g::GRAD_OK) if (p.do_grad) {
+          if constexpr (GRAD_ON) if (p.do_grad) {
 #pragma unroll
-            for (int i = 0; i < g::GT_ALLOC; ++i)
+            for (int i = 0; i < GTN; ++i)
 #pragma unroll
               for (int v = 0; v < 16; ++v) gt[i][v] *= sc;
           }
@@ -573,7 +586,7 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
             if (h == 0) s_sur += e;
             coef = gz[gi] < 0.f ? -e : e;
           }
-          if (g::GRAD_OK && p.do_grad && h == 0) {
+          if (GRAD_ON && p.do_grad && h == 0) {
             // coefficient as an exact-to-16-bit bfloat16 pair (hi in the low half, lo in the high half)
             const uint32_t ch = pack_bf16(coef, 0.f);
             const uint32_t cl = pack_bf16(coef - bf16_lo_f32(ch), 0.f);
@@ -582,7 +595,7 @@ __global__ __launch_bounds__(kThreads) void xform_core_kernel(const CoreParams p
           }
         }
       }
-      if constexpr (g::GRAD_OK) if (p.do_grad) {
+      if constexpr (GRAD_ON) if (p.do_grad) {
         // (the W hi/mid parts were staged during the forward phase)
         __syncthreads();
         // G[j][m] += sum over the 128 lines of S[line][j] * W[line][m], 16 lines per MFMA step

@@ -14,11 +14,9 @@ constexpr size_t core_lds_bytes_t(bool do_grad) {
   return size_t(g::RINGB) + (do_grad ? size_t(g::GRADB) : 0) + size_t(g::MISCB);
 }
 
-template <int K, int G, int AXIS>
-int launch_core_t(const CoreParams& p, hipStream_t st) {
-  const size_t lds = core_lds_bytes_t<K, G>(p.do_grad != 0);
-  if (lds == 0 || lds > kMaxLds) return CAFEQ_ERR_UNSUPPORTED;
-  auto kern = xform_core_kernel<K, G, AXIS>;
+template <int K, int G, int AXIS, bool GRAD>
+int launch_core_v(const CoreParams& p, size_t lds, hipStream_t st) {
+  auto kern = xform_core_kernel<K, G, AXIS, GRAD>;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -29,6 +27,16 @@ int launch_core_t(const CoreParams& p, hipStream_t st) {
   hipLaunchKernelGGL(kern, dim3(unsigned(p.nwg)), dim3(kThreads), lds, st, p);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
+}
+
+template <int K, int G, int AXIS>
+int launch_core_t(const CoreParams& p, hipStream_t st) {
+  const size_t lds = core_lds_bytes_t<K, G>(p.do_grad != 0);
+  if (lds == 0 || lds > kMaxLds) return CAFEQ_ERR_UNSUPPORTED;
+  if constexpr (Geo<K, G>::GRAD_OK) {
+    if (p.do_grad) return launch_core_v<K, G, AXIS, true>(p, lds, st);
+  }
+  return launch_core_v<K, G, AXIS, false>(p, lds, st);
 }
 
 template <int K>
