@@ -105,6 +105,7 @@ struct ReduceArgs {
   int transpose_out;     // 1: out[m][j] = acc[j][m]
   float t;               // kLossLse: temperature; scale of a partial = exp(t (m_ref - m*)) / S
   const double* lse_ms;  // kLossLse: [0] = m*, [1] = S  (null for kLossSur)
+  const float* member_ref;  // kLossLse, two-pass gradient: every partial is relative to this value
   float* out;            // [nb][K][K]
 };
 
@@ -137,7 +138,7 @@ __global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceArgs a) {
           const int64_t slot = int64_t(w) + seg;
           float sc = 1.f;
           if (a.lse_ms) {
-            const float mref = a.slot_hdr[slot * kHdrFloats + kHdrMref];
+            const float mref = a.member_ref ? *a.member_ref : a.slot_hdr[slot * kHdrFloats + kHdrMref];
             sc = float(exp(double(a.t) * (double(mref) - a.lse_ms[0])) / a.lse_ms[1]);
           }
           src[n] = a.slot_grad + slot * int64_t(a.NBLK) * K * K + int64_t(blk) * K * K;
@@ -452,12 +453,12 @@ int launch_init_hdr(float* hdr, int64_t nslot, hipStream_t st) {
   return CAFEQ_OK;
 }
 int launch_reduce_grad(const CoreParams& p, int K, int G, int nb, int transpose_out, const double* lse_ms,
-                       float* out, hipStream_t st) {
+                       const float* member_ref, float* out, hipStream_t st) {
   ReduceArgs a;
   const int L = K > G ? K : G;
   a.slot_grad = p.slot_grad; a.slot_hdr = p.slot_hdr; a.mt_per_seg = p.mt_per_seg; a.n_mt = p.n_mt;
   a.nwg = p.nwg; a.nseg = p.nseg; a.K = K; a.NBLK = L / K; a.NGRP = L / G; a.G = G; a.rep = p.rep;
-  a.transpose_out = transpose_out; a.t = p.lse_t; a.lse_ms = lse_ms; a.out = out;
+  a.transpose_out = transpose_out; a.t = p.lse_t; a.lse_ms = lse_ms; a.member_ref = member_ref; a.out = out;
   hipLaunchKernelGGL(reduce_grad_kernel, dim3(nb, (K * K + 1023) / 1024), dim3(256), 0, st, a);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;

@@ -41,9 +41,14 @@ struct CorePlan {
 
 bool supported_block(int k) { return k == 32 || k == 64 || k == 128 || k == 256; }
 
+// The gradient through the transformed weights is computed by a second pass over the weights
+// (from the first pass's arg-max records) where that is faster than the fused kernel: the
+// gradient-free first pass then runs at two waves per SIMD.
+bool two_pass_gradient(int K, int G) { return K == 128 && G <= 128; }
+
 // grad: the launch will ask for the gradient.  Without it, segments of up to 128 run two
 // workgroups per compute unit.
-int make_plan(int K, int G, int64_t nlines, int64_t naxis, CorePlan* pl, bool grad = true) {
+int make_plan(int K, int G, int64_t nlines, int64_t naxis, CorePlan* pl, bool grad = true, bool two_per_cu = false) {
   if (!supported_block(K)) return CAFEQ_ERR_UNSUPPORTED;
   if (!(G == 32 || G == 64 || G == 128 || G == 256)) return CAFEQ_ERR_UNSUPPORTED;
   pl->K = K; pl->G = G; pl->L = K > G ? K : G;
@@ -53,7 +58,7 @@ int make_plan(int K, int G, int64_t nlines, int64_t naxis, CorePlan* pl, bool gr
   pl->nseg = int(naxis / pl->L);
   pl->mt_per_seg = (nlines + kMacroLines - 1) / kMacroLines;
   pl->n_mt = pl->mt_per_seg * pl->nseg;
-  const int per_cu = (!grad && pl->L <= 128) ? 2 : 1;
+  const int per_cu = ((!grad && pl->L <= 128) || two_per_cu) ? 2 : 1;
   int64_t nwg = std::min<int64_t>(pl->n_mt, int64_t(device_cu_count()) * per_cu);
   if (nwg > 8) nwg -= nwg % 8;
   pl->nwg = int(nwg);
@@ -73,32 +78,42 @@ struct Carver {
 };
 
 struct SingleWs {
-  float *rho, *rG, *slot_grad, *slot_hdr, *mmid, *x1; double* lse_ms; uint16_t *pfwd, *pinv; size_t bytes;
+  float *rho, *rG, *slot_grad, *slot_hdr, *mmid, *x1; double* lse_ms; uint16_t *pfwd, *pinv;
+  float2* rec; float* member_ref; size_t bytes;
 };
-SingleWs carve_single(void* ws, const CorePlan& pl, int nb, bool grad) {
+// pl: plan of the (first) pass that writes the partial headers; pg: plan of the pass that writes
+// the gradient partials (the same plan unless the gradient runs as a second pass)
+SingleWs carve_single(void* ws, const CorePlan& pl, const CorePlan& pg, int nb, bool grad, bool two_pass) {
   Carver c(ws);
   SingleWs w;
   w.lse_ms = c.take<double>(2);
+  w.member_ref = c.take<float>(4);
   w.pfwd = c.take<uint16_t>(size_t(nb) * kFwdPlanes * pl.K * pl.K);
   w.pinv = c.take<uint16_t>(size_t(nb) * kInvPlanes * pl.K * pl.K);
   w.rho = c.take<float>(size_t(nb) * pl.K);
   w.rG = c.take<float>(size_t(pl.naxis / pl.G));
   w.slot_hdr = c.take<float>(size_t(pl.nslot) * kHdrFloats);
-  w.slot_grad = c.take<float>(grad ? size_t(pl.nslot) * pl.slot_grad_floats : 0);
+  w.slot_grad = c.take<float>(grad ? size_t(pg.nslot) * pg.slot_grad_floats : 0);
   w.mmid = c.take<float>(grad ? size_t(nb) * pl.K * pl.K : 0);
   w.x1 = c.take<float>(grad ? size_t(nb) * pl.K * pl.K : 0);
+  w.rec = c.take<float2>(grad && two_pass ? size_t(pl.naxis / pl.G) * size_t(pl.nlines) : 0);
   w.bytes = c.off;
   return w;
 }
 
 struct DualWs {
   float *hdrA, *hdrB, *gradA, *gradB, *gp, *x1; double* lse_ms;
-  uint16_t *pfwdA, *pinvA, *pfwdB, *pinvB; size_t bytes;
+  uint16_t *pfwdA, *pinvA, *pfwdB, *pinvB;
+  float2 *recA, *recB; float* member_ref; size_t bytes;
 };
-DualWs carve_dual(void* ws, const CorePlan& pa, const CorePlan& pb, int nb, bool grad) {
+// pa, pb: plans of the passes that write the partial headers; ga, gb: plans of the passes that
+// write the gradient partials
+DualWs carve_dual(void* ws, const CorePlan& pa, const CorePlan& pb, const CorePlan& ga, const CorePlan& gb, int nb,
+                  bool grad, bool two_a, bool two_b) {
   Carver c(ws);
   DualWs w;
   w.lse_ms = c.take<double>(2);
+  w.member_ref = c.take<float>(4);   // [0]: member A, [1]: member B
   const size_t kk = size_t(nb) * pa.K * pa.K;
   w.pfwdA = c.take<uint16_t>(kk * kFwdPlanes);
   w.pinvA = c.take<uint16_t>(kk * kInvPlanes);
@@ -106,12 +121,26 @@ DualWs carve_dual(void* ws, const CorePlan& pa, const CorePlan& pb, int nb, bool
   w.pinvB = c.take<uint16_t>(kk * kInvPlanes);
   w.hdrA = c.take<float>(size_t(pa.nslot + pb.nslot) * kHdrFloats);   // A then B, contiguous
   w.hdrB = w.hdrA ? w.hdrA + size_t(pa.nslot) * kHdrFloats : nullptr;
-  w.gradA = c.take<float>(grad ? size_t(pa.nslot) * pa.slot_grad_floats : 0);
-  w.gradB = c.take<float>(grad ? size_t(pb.nslot) * pb.slot_grad_floats : 0);
+  w.gradA = c.take<float>(grad ? size_t(ga.nslot) * ga.slot_grad_floats : 0);
+  w.gradB = c.take<float>(grad ? size_t(gb.nslot) * gb.slot_grad_floats : 0);
   w.gp = c.take<float>(grad ? size_t(nb) * pa.K * pa.K : 0);
   w.x1 = c.take<float>(grad ? size_t(nb) * pa.K * pa.K : 0);
+  w.recA = c.take<float2>(grad && two_a ? size_t(pa.naxis / pa.G) * size_t(pa.nlines) : 0);
+  w.recB = c.take<float2>(grad && two_b ? size_t(pb.naxis / pb.G) * size_t(pb.nlines) : 0);
   w.bytes = c.off;
   return w;
+}
+
+// Plans of one matrix for a call with / without gradient: `first` is the pass that computes
+// the losses, `gpass` the pass that writes the gradient partials (== first unless two-pass).
+struct PassPlans { CorePlan first, gpass; bool two; };
+int plan_passes(int K, int G, int64_t nlines, int64_t naxis, bool grad, PassPlans* pp) {
+  pp->two = grad && two_pass_gradient(K, G);
+  int rc = make_plan(K, G, nlines, naxis, &pp->first, grad && !pp->two);
+  if (rc) return rc;
+  if (pp->two) return make_plan(K, G, nlines, naxis, &pp->gpass, true, true);
+  pp->gpass = pp->first;
+  return CAFEQ_OK;
 }
 
 int check_xform(const cafeq_xform* x, bool need_inv) {
@@ -185,6 +214,7 @@ void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep)
   p->do_inverse = 0; p->do_grad = 0; p->loss_kind = kLossSur; p->beta = 0.f; p->lse_t = 0.f;
   p->rG = nullptr; p->Zout = nullptr; p->codes = nullptr; p->scales = nullptr;
   p->slot_grad = nullptr; p->slot_hdr = nullptr;
+  p->rec = nullptr; p->hdr_ref = nullptr; p->nslot_ref = 0; p->member_ref = nullptr;
   p->grid = make_grid(4);
 }
 
@@ -289,23 +319,22 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
       const bool col = cfg->axis == CAFEQ_AXIS_COL;
       const int64_t naxis = col ? a->cols : a->rows, nlines = col ? a->rows : a->cols;
       int G;
-      CorePlan pl;
-      CorePlan pn;
-      if (resolve_group(cfg, naxis, &G) || make_plan(x->k, G, nlines, naxis, &pl, true) ||
-          make_plan(x->k, G, nlines, naxis, &pn, false))
-        return 0;
-      return std::max(carve_single(nullptr, pl, x->nb, true).bytes, carve_single(nullptr, pn, x->nb, false).bytes);
+      if (resolve_group(cfg, naxis, &G)) return 0;
+      PassPlans pg, pn;
+      if (plan_passes(x->k, G, nlines, naxis, true, &pg) || plan_passes(x->k, G, nlines, naxis, false, &pn)) return 0;
+      return std::max(carve_single(nullptr, pg.first, pg.gpass, x->nb, true, pg.two).bytes,
+                      carve_single(nullptr, pn.first, pn.gpass, x->nb, false, false).bytes);
     }
     case CAFEQ_CALL_DUAL_PROXY_LOSS: {
       if (!a || !b || !x || !cfg) return 0;
       int GA, GB;
-      CorePlan pa, pb;
       if (resolve_group(cfg, a->cols, &GA) || resolve_group(cfg, b->rows, &GB)) return 0;
-      CorePlan na, nbp;
-      if (make_plan(x->k, GA, a->rows, a->cols, &pa, true) || make_plan(x->k, GB, b->cols, b->rows, &pb, true) ||
-          make_plan(x->k, GA, a->rows, a->cols, &na, false) || make_plan(x->k, GB, b->cols, b->rows, &nbp, false))
+      PassPlans ga, gb, na, nbp;
+      if (plan_passes(x->k, GA, a->rows, a->cols, true, &ga) || plan_passes(x->k, GB, b->cols, b->rows, true, &gb) ||
+          plan_passes(x->k, GA, a->rows, a->cols, false, &na) || plan_passes(x->k, GB, b->cols, b->rows, false, &nbp))
         return 0;
-      return std::max(carve_dual(nullptr, pa, pb, x->nb, true).bytes, carve_dual(nullptr, na, nbp, x->nb, false).bytes);
+      return std::max(carve_dual(nullptr, ga.first, gb.first, ga.gpass, gb.gpass, x->nb, true, ga.two, gb.two).bytes,
+                      carve_dual(nullptr, na.first, nbp.first, na.gpass, nbp.gpass, x->nb, false, false, false).bytes);
     }
     case CAFEQ_CALL_ADAPTIVE_ROUND: {
       // a: U [rowsA][nb*k], b: V [nb*rep*k][colsB]
@@ -399,15 +428,16 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   rc = resolve_group(cfg, naxis, &G);
   if (rc) return rc;
   const int K = x->k, nb = x->nb;
-  CorePlan pl;
-  rc = make_plan(K, G, nlines, naxis, &pl, gradT != nullptr);
+  PassPlans pp;
+  rc = plan_passes(K, G, nlines, naxis, gradT != nullptr, &pp);
   if (rc) return rc;
+  const CorePlan& pl = pp.first;
   {
-    const size_t lds = core_lds_bytes(K, G, gradT != nullptr);
+    const size_t lds = core_lds_bytes(K, G, gradT != nullptr && !pp.two);
     if (lds == 0 || lds > kLdsLimit) return CAFEQ_ERR_UNSUPPORTED;
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
-  SingleWs w = carve_single(ws, pl, nb, gradT != nullptr);
+  SingleWs w = carve_single(ws, pl, pp.gpass, nb, gradT != nullptr, pp.two);
   const QGrid grid = make_grid(cfg->bits);
   const float beta = 1.f / (4.f * grid.qmax * grid.qmax);
 
@@ -423,15 +453,23 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
     if ((rc = launch_split_planes_multi(req, 2, K, nb, st))) return rc;
   }
   p.Afwd = w.pfwd; p.Ainv = w.pinv;
-  p.grid = grid; p.do_inverse = 1; p.do_grad = gradT ? 1 : 0; p.loss_kind = kLossSur; p.beta = beta;
+  p.grid = grid; p.do_inverse = 1; p.do_grad = (gradT && !pp.two) ? 1 : 0; p.loss_kind = kLossSur; p.beta = beta;
   p.rG = w.rG; p.codes = codes; p.scales = scales; p.slot_grad = w.slot_grad; p.slot_hdr = w.slot_hdr;
+  p.rec = pp.two ? w.rec : nullptr;
   if ((rc = launch_core(K, G, cfg->axis, p, st))) return rc;
   if ((rc = launch_reduce_losses(kLossSur, w.slot_hdr, int(pl.nslot), nullptr, 0, beta, 0.f, 0, losses,
                                  w.lse_ms, st)))
     return rc;
   if (gradT) {
-    // path through Z, then the path through rho(P): -2 P^T Mmid P^T
-    if ((rc = launch_reduce_grad(p, K, G, nb, col ? 1 : 0, nullptr, gradT, st))) return rc;
+    // path through Z (fused into the pass above, or a second pass over the weights from its
+    // arg-max records), then the path through rho(P): -2 P^T Mmid P^T
+    CoreParams pg = p;
+    if (pp.two) {
+      fill_common(&pg, W, pp.gpass, x->rep);
+      pg.loss_kind = kLossSur; pg.beta = beta; pg.rG = w.rG; pg.slot_grad = w.slot_grad; pg.rec = w.rec;
+      if ((rc = launch_grad_k128(G, cfg->axis, pg, st))) return rc;
+    }
+    if ((rc = launch_reduce_grad(pg, K, G, nb, col ? 1 : 0, nullptr, nullptr, gradT, st))) return rc;
     if ((rc = launch_build_mmid(p, K, G, nb, x->Tinv, col ? 1 : 0, w.mmid, st))) return rc;
     if ((rc = launch_bgemm(true, false, x->Tinv, w.mmid, w.x1, K, nb, 1.f, 0.f, st))) return rc;
     if ((rc = launch_bgemm(false, true, w.x1, x->Tinv, gradT, K, nb, -2.f, 1.f, st))) return rc;
@@ -459,46 +497,68 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   int GA, GB;
   if ((rc = resolve_group(cfg, A->cols, &GA))) return rc;
   if ((rc = resolve_group(cfg, B->rows, &GB))) return rc;
-  CorePlan pa, pb;
   const bool grad = gradT != nullptr;
-  if ((rc = make_plan(K, GA, A->rows, A->cols, &pa, grad))) return rc;
-  if ((rc = make_plan(K, GB, B->cols, B->rows, &pb, grad))) return rc;
+  PassPlans qa, qb;
+  if ((rc = plan_passes(K, GA, A->rows, A->cols, grad, &qa))) return rc;
+  if ((rc = plan_passes(K, GB, B->cols, B->rows, grad, &qb))) return rc;
+  const CorePlan &pa = qa.first, &pb = qb.first;
   {
-    const size_t la = core_lds_bytes(K, GA, grad), lb = core_lds_bytes(K, GB, grad);
+    const size_t la = core_lds_bytes(K, GA, grad && !qa.two), lb = core_lds_bytes(K, GB, grad && !qb.two);
     if (la == 0 || lb == 0 || la > kLdsLimit || lb > kLdsLimit) return CAFEQ_ERR_UNSUPPORTED;
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
-  DualWs w = carve_dual(ws, pa, pb, nb, grad);
+  DualWs w = carve_dual(ws, pa, pb, qa.gpass, qb.gpass, nb, grad, qa.two, qb.two);
   const QGrid grid = make_grid(cfg->bits);
   if ((rc = launch_init_hdr(w.hdrA, pa.nslot + pb.nslot, st))) return rc;
 
-  CoreParams a;
-  fill_common(&a, A, pa, 1);
   {
     const SplitRequest req[4] = {{x->T, w.pfwdA, 1, kFwdPlanes}, {x->Tinv, w.pinvA, 1, kInvPlanes},
                                  {x->Tinv, w.pfwdB, 0, kFwdPlanes}, {x->T, w.pinvB, 0, kInvPlanes}};
     if ((rc = launch_split_planes_multi(req, 4, K, nb, st))) return rc;
   }
+  // Each member: the loss pass, then (two-pass gradient) straight away the gradient pass over
+  // the same weights, while they are still in the memory-side cache.  The gradient pass takes
+  // its exponentials relative to the member's own largest group maximum; the final reduction
+  // rescales to the pair's.
+  CoreParams a, ag;
+  fill_common(&a, A, pa, 1);
   a.Afwd = w.pfwdA; a.Ainv = w.pinvA;
-  a.grid = grid; a.do_inverse = 1; a.do_grad = grad ? 1 : 0; a.loss_kind = kLossLse; a.lse_t = lse_t;
+  a.grid = grid; a.do_inverse = 1; a.do_grad = (grad && !qa.two) ? 1 : 0; a.loss_kind = kLossLse; a.lse_t = lse_t;
   a.codes = codesU; a.scales = scalesU; a.slot_grad = w.gradA; a.slot_hdr = w.hdrA;
+  a.rec = qa.two ? w.recA : nullptr;
   if ((rc = launch_core(K, GA, CAFEQ_AXIS_COL, a, st))) return rc;
+  ag = a;
+  if (qa.two) {
+    fill_common(&ag, A, qa.gpass, 1);
+    ag.loss_kind = kLossLse; ag.lse_t = lse_t; ag.slot_grad = w.gradA; ag.rec = w.recA;
+    ag.hdr_ref = w.hdrA; ag.nslot_ref = int(pa.nslot); ag.member_ref = w.member_ref;
+    if ((rc = launch_grad_k128(GA, CAFEQ_AXIS_COL, ag, st))) return rc;
+  }
 
-  CoreParams b;
+  CoreParams b, bg;
   fill_common(&b, B, pb, x->rep);
   b.Afwd = w.pfwdB; b.Ainv = w.pinvB;
-  b.grid = grid; b.do_inverse = 1; b.do_grad = grad ? 1 : 0; b.loss_kind = kLossLse; b.lse_t = lse_t;
+  b.grid = grid; b.do_inverse = 1; b.do_grad = (grad && !qb.two) ? 1 : 0; b.loss_kind = kLossLse; b.lse_t = lse_t;
   b.codes = codesV; b.scales = scalesV; b.slot_grad = w.gradB; b.slot_hdr = w.hdrB;
+  b.rec = qb.two ? w.recB : nullptr;
   if ((rc = launch_core(K, GB, CAFEQ_AXIS_ROW, b, st))) return rc;
+  bg = b;
+  if (qb.two) {
+    fill_common(&bg, B, qb.gpass, x->rep);
+    bg.loss_kind = kLossLse; bg.lse_t = lse_t; bg.slot_grad = w.gradB; bg.rec = w.recB;
+    bg.hdr_ref = w.hdrB; bg.nslot_ref = int(pb.nslot); bg.member_ref = w.member_ref + 1;
+    if ((rc = launch_grad_k128(GB, CAFEQ_AXIS_ROW, bg, st))) return rc;
+  }
 
   const int64_t ngroups = A->rows * (A->cols / GA) + (B->rows / GB) * B->cols;
   if ((rc = launch_reduce_losses(kLossLse, w.hdrA, int(pa.nslot), w.hdrB, int(pb.nslot), 0.f, lse_t, ngroups,
                                  losses, w.lse_ms, st)))
     return rc;
   if (grad) {
-    if ((rc = launch_reduce_grad(a, K, GA, nb, 1, w.lse_ms, gradT, st))) return rc;
+    if ((rc = launch_reduce_grad(ag, K, GA, nb, 1, w.lse_ms, qa.two ? w.member_ref : nullptr, gradT, st))) return rc;
     // member B: G_P of transform block b sums its rep row-blocks; d/dT = -P^T G_P P^T
-    if ((rc = launch_reduce_grad(b, K, GB, nb, 0, w.lse_ms, w.gp, st))) return rc;
+    if ((rc = launch_reduce_grad(bg, K, GB, nb, 0, w.lse_ms, qb.two ? w.member_ref + 1 : nullptr, w.gp, st)))
+      return rc;
     if ((rc = launch_bgemm(true, false, x->Tinv, w.gp, w.x1, K, nb, 1.f, 0.f, st))) return rc;
     if ((rc = launch_bgemm(false, true, w.x1, x->Tinv, gradT, K, nb, -1.f, 1.f, st))) return rc;
   }

@@ -33,6 +33,8 @@ int launch_core_k32(int G, int axis, const CoreParams& p, hipStream_t st);
 int launch_core_k64(int G, int axis, const CoreParams& p, hipStream_t st);
 int launch_core_k128(int G, int axis, const CoreParams& p, hipStream_t st);
 int launch_core_k256(int G, int axis, const CoreParams& p, hipStream_t st);
+// gradient pass of the two-pass scheme (K = 128, segments up to 128)
+int launch_grad_k128(int G, int axis, const CoreParams& p, hipStream_t st);
 // LDS bytes the core needs (0 if the gradient accumulator cannot fit with do_grad)
 size_t core_lds_bytes(int K, int G, bool do_grad);
 size_t core_lds_bytes_k32(int G, bool do_grad);
@@ -50,7 +52,7 @@ int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_
 int launch_rho_groups(const float* rho, int K, int rep, int G, int64_t ngroups, float* rG, hipStream_t st);
 int launch_init_hdr(float* hdr, int64_t nslot, hipStream_t st);
 int launch_reduce_grad(const CoreParams& p, int K, int G, int nb, int transpose_out, const double* lse_ms,
-                       float* out, hipStream_t st);
+                       const float* member_ref, float* out, hipStream_t st);
 int launch_build_mmid(const CoreParams& p, int K, int G, int nb, const float* P, int scale_rows, float* Mmid,
                       hipStream_t st);
 int launch_reduce_losses(int kind, const float* hdrA, int nslotA, const float* hdrB, int nslotB, float beta,

@@ -1,0 +1,190 @@
+// Gradient pass of the two-pass scheme: gradT_b += W_b^T S_b (columns) / S_b W_b^T (rows), where
+// S has one non-zero per (line, group), at the group's arg-max, recorded by the gradient-free
+// pass of the fused kernel.  (Paper Sec. 4.1: gradient of the surrogate through the transformed
+// weights; Sec. 4.2: of the LogSumExp surrogate.)
+//
+// Same decomposition as the fused kernel: a workgroup owns a contiguous, segment-major range of
+// macro-tiles (128 lines x one segment), a wave 32 lines.  Per macro-tile the waves split their
+// weights exactly into bfloat16 hi + mid parts and park them in LDS transposed, [input m][line];
+// then wave r accumulates tile row r of the segment's k x k gradient blocks over the 128 lines on
+// the matrix cores (three part products, float32 accumulation, operands: S^T built in registers
+// from the records, W parts from LDS).  One partial per (workgroup, segment), reduced in fixed
+// order by reduce_grad_kernel.
+#pragma once
+#include "xform_core.hpp"
+
+namespace cafeq {
+
+template <int K, int G, int AXIS>
+__global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p) {
+  using g = Geo<K, G>;
+  static_assert(g::GRAD_OK, "no gradient for this (K, G)");
+  constexpr int L = g::L, NT = g::NT, KT = g::KT, NGRP = g::NGRP, NBLK = g::NBLK;
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* wst = smem;                                              // [2 parts][L][WST_ROWB]
+  int16_t* jst = reinterpret_cast<int16_t*>(wst + 2 * g::WST_PLANEB);     // [NGRP][128 lines]
+  uint32_t* cfp = reinterpret_cast<uint32_t*>(wst + 2 * g::WST_PLANEB + NGRP * kMacroLines * 2);
+  float* red = reinterpret_cast<float*>(smem + g::GRADB);                 // [kNW]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ln = lane & 31, h = lane >> 5;
+
+  int64_t w = blockIdx.x;
+  if ((p.nwg & 7) == 0) w = int64_t(blockIdx.x & 7) * (p.nwg >> 3) + (blockIdx.x >> 3);
+  const int64_t mt0 = chunk_begin(w, p.n_mt, p.nwg), mt1 = chunk_begin(w + 1, p.n_mt, p.nwg);
+
+  // kLossLse: exponentials relative to the member's largest group maximum
+  float m_mem = 0.f;
+  if (p.loss_kind == kLossLse) {
+    float m = -INFINITY;
+    for (int i = tid; i < p.nslot_ref; i += kThreads) m = fmaxf(m, p.hdr_ref[int64_t(i) * kHdrFloats + kHdrMref]);
+    m = cluster_allmax<64>(m);
+    if (lane == 0) red[wave] = m;
+    __syncthreads();
+    m_mem = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    if (blockIdx.x == 0 && tid == 0) *p.member_ref = m_mem;
+  }
+  if (mt0 >= mt1) return;
+
+  const int mt_per_seg = int(p.mt_per_seg);
+  int seg = int(mt0 / p.mt_per_seg);
+  int mis = int(mt0 - int64_t(seg) * p.mt_per_seg);
+  int cur_seg = seg;
+
+  // gradient tiles of this wave: tile rows r = wave, wave + 4, ... (< NT), KT tiles each;
+  // element [j = r*32 + 8(v/4)+4h+v%4][m = mt*32 + ln] of the segment's k x k blocks
+  floatx16 gt[g::GT];
+#pragma unroll
+  for (int i = 0; i < g::GT; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) gt[i][v] = 0.f;
+
+  auto flush = [&](int sg_) {
+    float* dst = p.slot_grad + (w + sg_) * int64_t(NBLK * K * K);
+#pragma unroll
+    for (int gr = 0; gr < g::GT_ROWS; ++gr) {
+      const int r = wave + gr * kNW;
+      if (r < NT) {
+        const int blk = r / KT, jt = r % KT;
+#pragma unroll
+        for (int mt_ = 0; mt_ < KT; ++mt_) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int j = jt * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+            dst[(blk * K + j) * K + mt_ * 32 + ln] = gt[gr * KT + mt_][v];
+            gt[gr * KT + mt_][v] = 0.f;
+          }
+        }
+      }
+    }
+  };
+
+  float wreg[L / 2];
+  load_strip<L, AXIS>(p, wreg, seg, mis, wave, ln, h);
+  unsigned char* wcol = wst + (wave * kStripLines + ln) * 2;
+
+  for (int64_t mt = mt0; mt < mt1; ++mt) {
+    if (seg != cur_seg) {
+      flush(cur_seg);
+      cur_seg = seg;
+    }
+    const int64_t line = int64_t(mis) * kMacroLines + wave * kStripLines + ln;
+    const bool valid = line < p.nlines;
+    int nseg_ = seg, nmis = mis + 1;
+    if (nmis == mt_per_seg) { nmis = 0; ++nseg_; }
+
+    // ---- this strip's weights as bfloat16 hi + mid parts, transposed into the staging area
+#pragma unroll
+    for (int c = 0; c < L / 16; ++c) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float x0 = wreg[8 * c + 2 * i], x1 = wreg[8 * c + 2 * i + 1];
+        const uint32_t ph = pack_bf16(x0, x1);
+        const uint32_t pm = pack_bf16(x0 - bf16_lo_f32(ph), x1 - bf16_hi_f32(ph));
+        const int m0 = 16 * c + 8 * (i / 2) + 4 * h + 2 * (i % 2);   // inputs of the packed pair: m0, m0+1
+        unsigned char* r0 = wcol + m0 * g::WST_ROWB;
+        *reinterpret_cast<uint16_t*>(r0) = uint16_t(ph);
+        *reinterpret_cast<uint16_t*>(r0 + g::WST_ROWB) = uint16_t(ph >> 16);
+        *reinterpret_cast<uint16_t*>(r0 + g::WST_PLANEB) = uint16_t(pm);
+        *reinterpret_cast<uint16_t*>(r0 + g::WST_PLANEB + g::WST_ROWB) = uint16_t(pm >> 16);
+      }
+    }
+    // ---- (arg-max, coefficient) of every group of this line
+    if (h == 0) {
+#pragma unroll
+      for (int gi = 0; gi < NGRP; ++gi) {
+        float coef = 0.f;
+        int j = 0;
+        if (valid) {
+          const float2 r = p.rec[(int64_t(seg) * NGRP + gi) * p.nlines + line];
+          j = __float_as_int(r.y);
+          if (p.loss_kind == kLossSur) {
+            coef = 2.f * p.beta * p.rG[seg * NGRP + gi] * r.x;
+          } else {
+            const float e = __expf(p.lse_t * (fabsf(r.x) - m_mem));
+            coef = r.x < 0.f ? -e : e;
+          }
+        }
+        // coefficient as an exact-to-16-bit bfloat16 pair (hi in the low half, lo in the high half)
+        const uint32_t ch = pack_bf16(coef, 0.f);
+        const uint32_t cl = pack_bf16(coef - bf16_lo_f32(ch), 0.f);
+        jst[gi * kMacroLines + wave * kStripLines + ln] = int16_t(j);
+        cfp[gi * kMacroLines + wave * kStripLines + ln] = (ch & 0xFFFFu) | (cl << 16);
+      }
+    }
+    // ---- the next strip's weights land while the matrix cores work
+    if (mt + 1 < mt1) load_strip<L, AXIS>(p, wreg, nseg_, nmis, wave, ln, h);
+    __syncthreads();
+
+    // ---- G[j][m] += sum over the 128 lines of S[line][j] * W[line][m], 16 lines per MFMA step
+#pragma unroll
+    for (int gr = 0; gr < g::GT_ROWS; ++gr) {
+      const int r = wave + gr * kNW;
+      if (r < NT) {
+        const int jrow = r * 32 + ln;              // this lane's row of S^T
+        const int gi = jrow / G;                   // its group (uniform over the tile: G >= 32)
+        const int blk = r / KT;
+#pragma unroll
+        for (int s = 0; s < kMacroLines / 16; ++s) {
+          const int l0 = 16 * s + 8 * h;
+          // eight lines' arg-max indices and packed coefficients
+          const uintx4 jv = *reinterpret_cast<const uintx4*>(jst + gi * kMacroLines + l0);
+          const uintx4 c0 = *reinterpret_cast<const uintx4*>(cfp + gi * kMacroLines + l0);
+          const uintx4 c1 = *reinterpret_cast<const uintx4*>(cfp + gi * kMacroLines + l0 + 4);
+          uint32_t sel[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int js = int((jv[e / 2] >> (16 * (e % 2))) & 0xFFFFu);
+            const uint32_t cv = e < 4 ? c0[e] : c1[e - 4];
+            sel[e] = js == jrow ? cv : 0u;
+          }
+          uintx4 sh, sl;
+#pragma unroll
+          for (int e2 = 0; e2 < 4; ++e2) {
+            sh[e2] = __builtin_amdgcn_perm(sel[2 * e2 + 1], sel[2 * e2], 0x05040100u);
+            sl[e2] = __builtin_amdgcn_perm(sel[2 * e2 + 1], sel[2 * e2], 0x07060302u);
+          }
+          const bf16x8 ash = as_bf16x8(sh), asl = as_bf16x8(sl);
+#pragma unroll
+          for (int mt_ = 0; mt_ < KT; ++mt_) {
+            const unsigned char* wrow = wst + (blk * K + mt_ * 32 + ln) * g::WST_ROWB + l0 * 2;
+            const bf16x8 bh = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow));
+            const bf16x8 bm = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow + g::WST_PLANEB));
+            floatx16 t16 = gt[gr * KT + mt_];
+            t16 = CAFEQ_MFMA_BF16(asl, bh, t16);
+            t16 = CAFEQ_MFMA_BF16(ash, bm, t16);
+            t16 = CAFEQ_MFMA_BF16(ash, bh, t16);
+            gt[gr * KT + mt_] = t16;
+          }
+        }
+      }
+    }
+    __syncthreads();   // the staging area is rewritten by the next macro-tile
+    seg = nseg_;
+    mis = nmis;
+  }
+  flush(cur_seg);
+}
+
+}  // namespace cafeq

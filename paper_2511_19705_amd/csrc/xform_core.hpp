@@ -111,6 +111,12 @@ struct CoreParams {
   float* scales;
   float* slot_grad;   // [nwg + nseg][NBLK*K*K]
   float* slot_hdr;    // [nwg + nseg][kHdrFloats]
+  // two-pass gradient: the gradient-free pass records, per (group, line), the signed value at the
+  // group's arg-max and its axis index inside the segment; the gradient pass reads them back
+  float2* rec;              // [nseg * NGRP][nlines]: (value, index as int bits); may be null
+  const float* hdr_ref;     // gradient pass, kLossLse: the first pass's partial headers ...
+  int nslot_ref;            // ... and their number: the member's reference is their largest m_ref
+  float* member_ref;        // gradient pass, kLossLse: [1] receives that reference
 };
 
 __device__ __forceinline__ int64_t chunk_begin(int64_t w, int64_t n_mt, int64_t nwg) {
@@ -150,6 +156,64 @@ __device__ __forceinline__ void vm_wait(int n) {
   }
 }
 #undef CAFEQ_VMW
+
+// Weights of one strip (32 lines x one segment of L axis indices): element j(f, h) = 8(f/4) + 4h + f%4
+// of the lane's line goes to wreg[f].  Lines beyond the matrix re-read the last line and are zeroed.
+template <int L, int AXIS>
+__device__ __forceinline__ void load_strip(const CoreParams& p, float (&wreg)[L / 2], int seg, int mis, int wave,
+                                           int ln, int h) {
+  const int64_t line = int64_t(mis) * kMacroLines + wave * kStripLines + ln;
+  const bool valid = line < p.nlines;
+  const int64_t lc = valid ? line : p.nlines - 1;   // out-of-range lanes re-read the last line, then zero it
+  const int64_t ax0 = int64_t(seg) * L;
+  if (AXIS == CAFEQ_AXIS_COL) {
+    if (p.dtype == CAFEQ_F32) {
+      const float* src = static_cast<const float*>(p.W) + lc * p.ld + ax0 + 4 * h;
+#pragma unroll
+      for (int c = 0; c < L / 8; ++c) {
+        const float4 v = *reinterpret_cast<const float4*>(src + 8 * c);
+        wreg[4 * c] = v.x; wreg[4 * c + 1] = v.y; wreg[4 * c + 2] = v.z; wreg[4 * c + 3] = v.w;
+      }
+    } else {
+      const uint16_t* src = static_cast<const uint16_t*>(p.W) + lc * p.ld + ax0 + 4 * h;
+#pragma unroll
+      for (int c = 0; c < L / 8; ++c) {
+        const float4 v = load4(src + 8 * c);
+        wreg[4 * c] = v.x; wreg[4 * c + 1] = v.y; wreg[4 * c + 2] = v.z; wreg[4 * c + 3] = v.w;
+      }
+    }
+  } else {
+    // uniform row pointer (bumped by the leading dimension) + 32-bit lane offset
+    const uint32_t loff = uint32_t(int64_t(4 * h) * p.ld + lc);
+    if (p.dtype == CAFEQ_F32) {
+      const float* rp = static_cast<const float*>(p.W) + ax0 * p.ld;
+#pragma unroll
+      for (int c = 0; c < L / 8; ++c) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          wreg[4 * c + e] = rp[loff];
+          rp += p.ld;
+        }
+        rp += 4 * p.ld;
+      }
+    } else {
+      const uint16_t* rp = static_cast<const uint16_t*>(p.W) + ax0 * p.ld;
+#pragma unroll
+      for (int c = 0; c < L / 8; ++c) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          wreg[4 * c + e] = bf16_bits_to_f32(rp[loff]);
+          rp += p.ld;
+        }
+        rp += 4 * p.ld;
+      }
+    }
+  }
+  if (!valid) {
+#pragma unroll
+    for (int f = 0; f < L / 2; ++f) wreg[f] = 0.f;
+  }
+}
 
 // GRAD = false compiles the gradient out: for segments of up to 128 that variant fits in half
 // the register file and needs no weight staging area, so two workgroups share a compute unit
@@ -290,62 +354,10 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
     m_ref = -INFINITY;
   };
 
-  // ---- weights of a strip, element j(f, h) of the lane's line in wreg[f].
-  // Loaded one macro-tile ahead (after the last use of the previous strip's weights).
+  // ---- weights of a strip, loaded one macro-tile ahead (after the last use of the previous
+  // strip's weights)
   float wreg[L / 2];
-  auto load_w = [&](int seg, int mis) {
-    const int64_t line = int64_t(mis) * kMacroLines + wave * kStripLines + ln;
-    const bool valid = line < p.nlines;
-    const int64_t lc = valid ? line : p.nlines - 1;   // out-of-range lanes re-read the last line, then zero it
-    const int64_t ax0 = int64_t(seg) * L;
-    if (AXIS == CAFEQ_AXIS_COL) {
-      if (p.dtype == CAFEQ_F32) {
-        const float* src = static_cast<const float*>(p.W) + lc * p.ld + ax0 + 4 * h;
-#pragma unroll
-        for (int c = 0; c < L / 8; ++c) {
-          const float4 v = *reinterpret_cast<const float4*>(src + 8 * c);
-          wreg[4 * c] = v.x; wreg[4 * c + 1] = v.y; wreg[4 * c + 2] = v.z; wreg[4 * c + 3] = v.w;
-        }
-      } else {
-        const uint16_t* src = static_cast<const uint16_t*>(p.W) + lc * p.ld + ax0 + 4 * h;
-#pragma unroll
-        for (int c = 0; c < L / 8; ++c) {
-          const float4 v = load4(src + 8 * c);
-          wreg[4 * c] = v.x; wreg[4 * c + 1] = v.y; wreg[4 * c + 2] = v.z; wreg[4 * c + 3] = v.w;
-        }
-      }
-    } else {
-      // uniform row pointer (bumped by the leading dimension) + 32-bit lane offset
-      const uint32_t loff = uint32_t(int64_t(4 * h) * p.ld + lc);
-      if (p.dtype == CAFEQ_F32) {
-        const float* rp = static_cast<const float*>(p.W) + ax0 * p.ld;
-#pragma unroll
-        for (int c = 0; c < L / 8; ++c) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            wreg[4 * c + e] = rp[loff];
-            rp += p.ld;
-          }
-          rp += 4 * p.ld;
-        }
-      } else {
-        const uint16_t* rp = static_cast<const uint16_t*>(p.W) + ax0 * p.ld;
-#pragma unroll
-        for (int c = 0; c < L / 8; ++c) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            wreg[4 * c + e] = bf16_bits_to_f32(rp[loff]);
-            rp += p.ld;
-          }
-          rp += 4 * p.ld;
-        }
-      }
-    }
-    if (!valid) {
-#pragma unroll
-      for (int f = 0; f < L / 2; ++f) wreg[f] = 0.f;
-    }
-  };
+  auto load_w = [&](int seg, int mis) { load_strip<L, AXIS>(p, wreg, seg, mis, wave, ln, h); };
   load_w(seg_first, mis_first);
 
   int seg = seg_first, mis = mis_first;
@@ -505,6 +517,8 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
         const float oa = fabsf(oz);
         if (oa > a || (oa == a && oj < j)) { a = oa; zs = oz; j = oj; }
         gz[gi] = zs; gj[gi] = j;
+        if (p.rec && valid && h == 0)
+          p.rec[(int64_t(seg) * NGRP + gi) * p.nlines + line] = make_float2(zs, __int_as_float(j));
         const float inv = grid_inv(a, p.grid.qmax);
         const float s = grid_scale(a, p.grid.qmax);
         if (p.scales && valid && h == 0) {
