@@ -15,6 +15,57 @@
 
 namespace cafeq {
 
+// The weights of one strip, fetched in L/8 chunks of four axis indices each (same register
+// layout as load_strip) so that the loads can be spread over the matrix-core phase of the
+// previous macro-tile.  begin() fixes the strip, chunk(c) must be called for c = 0 .. L/8-1 in
+// order, finish() zeroes the lines beyond the matrix.
+template <int L, int AXIS>
+struct StripLoader {
+  const CoreParams& p;
+  float (&wreg)[L / 2];
+  const unsigned char* rp;   // AXIS_ROW: uniform row pointer, bumped as the chunks go by
+  const unsigned char* lp;   // AXIS_COL: this lane's line
+  uint32_t loff;
+  bool valid;
+  __device__ __forceinline__ StripLoader(const CoreParams& p_, float (&w_)[L / 2]) : p(p_), wreg(w_) {}
+  __device__ __forceinline__ void begin(int seg, int mis, int wave, int ln, int h) {
+    const int64_t line = int64_t(mis) * kMacroLines + wave * kStripLines + ln;
+    valid = line < p.nlines;
+    const int64_t lc = valid ? line : p.nlines - 1;
+    const int64_t ax0 = int64_t(seg) * L;
+    const int es = p.dtype == CAFEQ_F32 ? 4 : 2;
+    if (AXIS == CAFEQ_AXIS_COL) {
+      lp = static_cast<const unsigned char*>(p.W) + (lc * p.ld + ax0 + 4 * h) * es;
+    } else {
+      loff = uint32_t((int64_t(4 * h) * p.ld + lc) * es);
+      rp = static_cast<const unsigned char*>(p.W) + ax0 * p.ld * es;
+    }
+  }
+  __device__ __forceinline__ void chunk(int c) {
+    if (AXIS == CAFEQ_AXIS_COL) {
+      float4 v;
+      if (p.dtype == CAFEQ_F32) v = *reinterpret_cast<const float4*>(lp + 32 * c);
+      else v = load4(reinterpret_cast<const uint16_t*>(lp + 16 * c));
+      wreg[4 * c] = v.x; wreg[4 * c + 1] = v.y; wreg[4 * c + 2] = v.z; wreg[4 * c + 3] = v.w;
+    } else {
+      const int64_t rowb = p.ld * (p.dtype == CAFEQ_F32 ? 4 : 2);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        wreg[4 * c + e] = p.dtype == CAFEQ_F32 ? *reinterpret_cast<const float*>(rp + loff)
+                                               : bf16_bits_to_f32(*reinterpret_cast<const uint16_t*>(rp + loff));
+        rp += rowb;
+      }
+      rp += 4 * rowb;
+    }
+  }
+  __device__ __forceinline__ void finish() {
+    if (!valid) {
+#pragma unroll
+      for (int f = 0; f < L / 2; ++f) wreg[f] = 0.f;
+    }
+  }
+};
+
 template <int K, int G, int AXIS>
 __global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p) {
   using g = Geo<K, G>;
@@ -81,8 +132,26 @@ __global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p)
   };
 
   float wreg[L / 2];
-  load_strip<L, AXIS>(p, wreg, seg, mis, wave, ln, h);
-  unsigned char* wcol = wst + (wave * kStripLines + ln) * 2;
+  StripLoader<L, AXIS> loader(p, wreg);
+  loader.begin(seg, mis, wave, ln, h);
+#pragma unroll
+  for (int c = 0; c < L / 8; ++c) loader.chunk(c);
+  loader.finish();
+  // the records of a strip (lanes of the first half only) are fetched with its weights
+  float2 recv[NGRP];
+  auto load_rec = [&](int sg_, int ms_) {
+    const int64_t line = int64_t(ms_) * kMacroLines + wave * kStripLines + ln;
+#pragma unroll
+    for (int gi = 0; gi < NGRP; ++gi) {
+      recv[gi] = make_float2(0.f, 0.f);
+      if (h == 0 && line < p.nlines) recv[gi] = p.rec[(int64_t(sg_) * NGRP + gi) * p.nlines + line];
+    }
+  };
+  load_rec(seg, mis);
+  // even lane: (own low half, neighbour's low half) -> row m0, lines (ln, ln+1);
+  // odd lane: (neighbour's high half, own high half) -> row m0+1, lines (ln-1, ln)
+  const uint32_t pair_sel = (ln & 1) ? 0x03020706u : 0x05040100u;
+  unsigned char* wpair = wst + (ln & 1) * g::WST_ROWB + (wave * kStripLines + (ln & ~1)) * 2;
 
   for (int64_t mt = mt0; mt < mt1; ++mt) {
     if (seg != cur_seg) {
@@ -94,7 +163,10 @@ __global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p)
     int nseg_ = seg, nmis = mis + 1;
     if (nmis == mt_per_seg) { nmis = 0; ++nseg_; }
 
-    // ---- this strip's weights as bfloat16 hi + mid parts, transposed into the staging area
+    // ---- this strip's weights as bfloat16 hi + mid parts, transposed into the staging area.
+    // A lane holds (m0, m0+1) of its line; it swaps one half with the neighbouring line's lane
+    // (DPP), so that the even lane owns (line, line+1) of input m0 and the odd lane of m0+1:
+    // one aligned 32-bit LDS store per packed pair instead of two 16-bit ones.
 #pragma unroll
     for (int c = 0; c < L / 16; ++c) {
 #pragma unroll
@@ -102,12 +174,12 @@ __global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p)
         const float x0 = wreg[8 * c + 2 * i], x1 = wreg[8 * c + 2 * i + 1];
         const uint32_t ph = pack_bf16(x0, x1);
         const uint32_t pm = pack_bf16(x0 - bf16_lo_f32(ph), x1 - bf16_hi_f32(ph));
+        const uint32_t oh = uint32_t(__builtin_amdgcn_update_dpp(0, int(ph), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+        const uint32_t om = uint32_t(__builtin_amdgcn_update_dpp(0, int(pm), 0xB1, 0xF, 0xF, true));
         const int m0 = 16 * c + 8 * (i / 2) + 4 * h + 2 * (i % 2);   // inputs of the packed pair: m0, m0+1
-        unsigned char* r0 = wcol + m0 * g::WST_ROWB;
-        *reinterpret_cast<uint16_t*>(r0) = uint16_t(ph);
-        *reinterpret_cast<uint16_t*>(r0 + g::WST_ROWB) = uint16_t(ph >> 16);
-        *reinterpret_cast<uint16_t*>(r0 + g::WST_PLANEB) = uint16_t(pm);
-        *reinterpret_cast<uint16_t*>(r0 + g::WST_PLANEB + g::WST_ROWB) = uint16_t(pm >> 16);
+        unsigned char* r0 = wpair + m0 * g::WST_ROWB;
+        *reinterpret_cast<uint32_t*>(r0) = __builtin_amdgcn_perm(oh, ph, pair_sel);
+        *reinterpret_cast<uint32_t*>(r0 + g::WST_PLANEB) = __builtin_amdgcn_perm(om, pm, pair_sel);
       }
     }
     // ---- (arg-max, coefficient) of every group of this line
@@ -117,7 +189,7 @@ __global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p)
         float coef = 0.f;
         int j = 0;
         if (valid) {
-          const float2 r = p.rec[(int64_t(seg) * NGRP + gi) * p.nlines + line];
+          const float2 r = recv[gi];
           j = __float_as_int(r.y);
           if (p.loss_kind == kLossSur) {
             coef = 2.f * p.beta * p.rG[seg * NGRP + gi] * r.x;
@@ -133,8 +205,13 @@ __global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p)
         cfp[gi * kMacroLines + wave * kStripLines + ln] = (ch & 0xFFFFu) | (cl << 16);
       }
     }
-    // ---- the next strip's weights land while the matrix cores work
-    if (mt + 1 < mt1) load_strip<L, AXIS>(p, wreg, nseg_, nmis, wave, ln, h);
+    // ---- the next strip's weights and records: addresses now, the loads spread over the
+    // matrix-core phase below
+    const bool has_next = mt + 1 < mt1;
+    if (has_next) {
+      loader.begin(nseg_, nmis, wave, ln, h);
+      load_rec(nseg_, nmis);
+    }
     __syncthreads();
 
     // ---- G[j][m] += sum over the 128 lines of S[line][j] * W[line][m], 16 lines per MFMA step
@@ -148,6 +225,12 @@ __global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p)
 #pragma unroll
         for (int s = 0; s < kMacroLines / 16; ++s) {
           const int l0 = 16 * s + 8 * h;
+          // this step's share of the next strip's weight loads (spread over the first tile row's steps)
+          if (gr == 0 && has_next) {
+            constexpr int per = (L / 8 + kMacroLines / 16 - 1) / (kMacroLines / 16);
+#pragma unroll
+            for (int c = s * per; c < (s + 1) * per && c < L / 8; ++c) loader.chunk(c);
+          }
           // eight lines' arg-max indices and packed coefficients
           const uintx4 jv = *reinterpret_cast<const uintx4*>(jst + gi * kMacroLines + l0);
           const uintx4 c0 = *reinterpret_cast<const uintx4*>(cfp + gi * kMacroLines + l0);
@@ -166,20 +249,25 @@ __global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p)
             sl[e2] = __builtin_amdgcn_perm(sel[2 * e2 + 1], sel[2 * e2], 0x07060302u);
           }
           const bf16x8 ash = as_bf16x8(sh), asl = as_bf16x8(sl);
+          // operands of all KT tiles first, then the three part products tile-interleaved, so that
+          // consecutive MFMAs never wait on each other's accumulator
+          bf16x8 bh[KT], bm[KT];
 #pragma unroll
           for (int mt_ = 0; mt_ < KT; ++mt_) {
             const unsigned char* wrow = wst + (blk * K + mt_ * 32 + ln) * g::WST_ROWB + l0 * 2;
-            const bf16x8 bh = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow));
-            const bf16x8 bm = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow + g::WST_PLANEB));
-            floatx16 t16 = gt[gr * KT + mt_];
-            t16 = CAFEQ_MFMA_BF16(asl, bh, t16);
-            t16 = CAFEQ_MFMA_BF16(ash, bm, t16);
-            t16 = CAFEQ_MFMA_BF16(ash, bh, t16);
-            gt[gr * KT + mt_] = t16;
+            bh[mt_] = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow));
+            bm[mt_] = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow + g::WST_PLANEB));
           }
+#pragma unroll
+          for (int mt_ = 0; mt_ < KT; ++mt_) gt[gr * KT + mt_] = CAFEQ_MFMA_BF16(asl, bh[mt_], gt[gr * KT + mt_]);
+#pragma unroll
+          for (int mt_ = 0; mt_ < KT; ++mt_) gt[gr * KT + mt_] = CAFEQ_MFMA_BF16(ash, bm[mt_], gt[gr * KT + mt_]);
+#pragma unroll
+          for (int mt_ = 0; mt_ < KT; ++mt_) gt[gr * KT + mt_] = CAFEQ_MFMA_BF16(ash, bh[mt_], gt[gr * KT + mt_]);
         }
       }
     }
+    if (has_next) loader.finish();
     __syncthreads();   // the staging area is rewritten by the next macro-tile
     seg = nseg_;
     mis = nmis;

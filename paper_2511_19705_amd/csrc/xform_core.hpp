@@ -641,17 +641,21 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
                 sl[e2] = __builtin_amdgcn_perm(sel[2 * e2 + 1], sel[2 * e2], 0x07060302u);
               }
               const bf16x8 ash = as_bf16x8(sh), asl = as_bf16x8(sl);
+              // operands of all KT tiles first, then the three part products tile-interleaved, so that
+              // consecutive MFMAs never wait on each other's accumulator
+              bf16x8 bh[KT], bm[KT];
 #pragma unroll
               for (int mt_ = 0; mt_ < KT; ++mt_) {
                 const unsigned char* wrow = wst + (blk * K + mt_ * 32 + ln) * g::WST_ROWB + l0 * 2;
-                const bf16x8 bh = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow));
-                const bf16x8 bm = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow + g::WST_PLANEB));
-                floatx16 t16 = gt[gr * KT + mt_];
-                t16 = CAFEQ_MFMA_BF16(asl, bh, t16);
-                t16 = CAFEQ_MFMA_BF16(ash, bm, t16);
-                t16 = CAFEQ_MFMA_BF16(ash, bh, t16);
-                gt[gr * KT + mt_] = t16;
+                bh[mt_] = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow));
+                bm[mt_] = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow + g::WST_PLANEB));
               }
+#pragma unroll
+              for (int mt_ = 0; mt_ < KT; ++mt_) gt[gr * KT + mt_] = CAFEQ_MFMA_BF16(asl, bh[mt_], gt[gr * KT + mt_]);
+#pragma unroll
+              for (int mt_ = 0; mt_ < KT; ++mt_) gt[gr * KT + mt_] = CAFEQ_MFMA_BF16(ash, bm[mt_], gt[gr * KT + mt_]);
+#pragma unroll
+              for (int mt_ = 0; mt_ < KT; ++mt_) gt[gr * KT + mt_] = CAFEQ_MFMA_BF16(ash, bh[mt_], gt[gr * KT + mt_]);
             }
           }
         }
