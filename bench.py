@@ -12,12 +12,13 @@ Prints ONE JSON line: weight-elements/s over the whole job, the matrix-core roof
 dominant (fused transform) kernel measured with HIP events on the launch stream inside the
 timed region, and the CPU oracle timed on the host cores on a bounded sample.
 
-The fused kernel's three contractions (forward transform, inverse transform of the rounding
-error, dense gradient) run on the bfloat16 matrix pipe with every float32 operand split
-exactly into three bfloat16 parts (6 + 3 + 3 part products, float32 accumulation).  The
-roofline line prices the ALGORITHMIC work, 3 * 2k flop per weight element, against the dense
-bfloat16 peak; the executed part products (4x as many flops) and the float32 matrix peak the
-split replaces are given beside it for context.
+The loss pass of the fused kernel (forward transform, quantizer, inverse transform of the
+rounding error, loss partials) runs its two contractions on the bfloat16 matrix pipe with every
+float32 operand split exactly into three bfloat16 parts (6 + 3 part products, float32
+accumulation); the gradient through the transformed weights is a second, shorter pass over the
+same weights.  The roofline line prices the ALGORITHMIC work of the loss pass, 2 * 2k flop per
+weight element, against the dense bfloat16 peak; the executed part products (4.5x as many
+flops) and the float32 matrix peak the split replaces are given beside it for context.
 """
 from __future__ import annotations
 
@@ -37,7 +38,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the fused kernel on this workload, from the two rocprofv3 --pmc runs
 # summarised in profiles/xform_core_c3_pair.md (FETCH_SIZE and WRITE_SIZE, each scaled by
 # what the same counter reads for a plain 1 GiB copy); None for any other workload.
-MEASURED_TRAFFIC_BYTES = {"c3_pair_3584x14336_k128_g128_b3": (2.0 * 159973 + 23190) * 1024}
+MEASURED_TRAFFIC_BYTES = {"c3_pair_3584x14336_k128_g128_b3": (2.0 * 168382 + 24288) * 1024}
 
 
 def cpu_baseline(cfg, blocks, reps):
@@ -117,14 +118,14 @@ def main():
 
     ms_per_step = dt / args.steps * 1e3
     value = elems * args.steps / dt
-    # dominant kernel: the fused transform core, launched once per member.  Algorithmic work per
-    # launch: forward transform, inverse transform and dense gradient contraction of its member,
-    # 2k flop per element each; it reads every weight once (4 B per element).
+    # dominant kernel: the loss pass of the fused transform core, launched once per member.
+    # Algorithmic work per launch: forward and inverse transform of its member, 2k flop per
+    # element each; it reads every weight once (4 B per element).
     member = elems / 2.0
-    flops_per_launch = 3.0 * 2.0 * k * member
+    flops_per_launch = 2.0 * 2.0 * k * member
     avg_launch_s = core_ms / 1e3 / max(n_launch, 1)
     achieved = flops_per_launch / avg_launch_s / 1e12
-    executed = 12.0 * 2.0 * k * member / avg_launch_s / 1e12
+    executed = 9.0 * 2.0 * k * member / avg_launch_s / 1e12
     result = {
         "metric": "proxy-loss fwd+bwd weight-elements/s (9B-shaped MLP pair, dual transform)",
         "value": value, "unit": "weight-elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -132,15 +133,15 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg["name"], "rows_cols": [list(cfg["A"].shape), list(cfg["B"].shape)],
                    "block": k, "group": g, "bits": bits, "evals_per_s": args.steps / dt,
-                   "step": "block inverse + dual proxy-loss fwd+bwd",
+                   "step": "block inverse + dual proxy-loss fwd+bwd (loss pass + gradient pass per member)",
                    "contraction": "float32 operands split exactly into 3 bfloat16 parts, float32 accumulate",
                    "relative_l2_A": float((losses[2] / float((cfg["A"].astype("float64") ** 2).sum())) ** 0.5)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg["name"]),
-                     "kernel": "xform_core_kernel<128,128,*>", "launches": n_launch,
+                     "kernel": "xform_core_kernel<128,128,*,false> (loss pass)", "launches": n_launch,
                      "avg_launch_us": avg_launch_s * 1e6,
-                     "algorithmic_flop_per_element": 6 * k, "algorithmic_bytes_per_element": 4,
+                     "algorithmic_flop_per_element": 4 * k, "algorithmic_bytes_per_element": 4,
                      "executed_part_product_tflops": executed,
                      "executed_frac_of_bf16_peak": executed / BF16_MFMA_PEAK_TFLOPS,
                      "achieved_over_fp32_mfma_peak": achieved / FP32_MFMA_PEAK_TFLOPS,
