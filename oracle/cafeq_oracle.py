@@ -25,6 +25,13 @@ What each function follows (section / equation of the CafeQ paper):
 * ``pinv``, ``adaptive_round_step``, ``pqe`` -- Algorithm 1 (Sec. 5) and the paired
                             quantization error of Sec. 4.2.
 * ``adaptive_bruteforce_column`` -- exhaustive up/down search used only as a pin.
+* ``orth_penalty``       -- the orthonormality regulariser ||T T^T - I||_F / sqrt(d) of the
+                            appendix on paired-quantization hyperparameters ("Constraints on T").
+* ``sgd_step``, ``adam_step``, ``optimize_single``, ``optimize_pair`` -- the learning
+                            procedure: gradient descent on the surrogate for a single matrix
+                            (Sec. 4.1, "perform gradient descent with [the bound] as the loss"),
+                            Adam on the LogSumExp surrogate for a pair (Sec. 4.2 and the same
+                            appendix), the inverse recomputed every step.
 
 Pinned by tests/test_oracle_*.py against: the paper's 2x2 toy example, Eq. (2),
 closed forms (orthogonal transform, identity transform), central finite
@@ -459,3 +466,71 @@ def adaptive_bruteforce_column(Uh_b, target_prod_col, vt_col, bits, group):
         if val < best_val - 1e-18:
             best_val, best = val, cand
     return best, best_val
+
+
+# ----------------------------------------------------------------------------
+# learning the transform: regulariser, update rules, loops
+# ----------------------------------------------------------------------------
+def orth_penalty(T, lam):
+    """lam * ||T T^T - I||_F / sqrt(d) for the block-diagonal T (d = nb*k, one norm over all
+    blocks) and its gradient w.r.t. the blocks: with R = T T^T - I (symmetric),
+    d||R||_F = <R, dR>/||R||_F and dR = dT T^T + T dT^T give 2 R T / ||R||_F.
+    The gradient is taken as zero where the norm vanishes."""
+    T = np.asarray(T, dtype=np.float64)
+    nb, k, _ = T.shape
+    R = T @ T.transpose(0, 2, 1) - np.eye(k)[None]
+    n = float(np.sqrt((R * R).sum()))
+    d = nb * k
+    val = lam * n / np.sqrt(d)
+    if n <= 1e-30:
+        return val, np.zeros_like(T)
+    return val, (lam / np.sqrt(d)) * 2.0 * (R @ T) / n
+
+
+def sgd_step(T, g, lr):
+    return T - lr * g
+
+
+def adam_step(T, g, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8):
+    """One step of Adam (Kingma & Ba, Algorithm 1) with bias correction; t counts from 1."""
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    mhat = m / (1.0 - beta1 ** t)
+    vhat = v / (1.0 - beta2 ** t)
+    return T - lr * mhat / (np.sqrt(vhat) + eps), m, v
+
+
+def optimize_single(W, T0, bits, group, axis, rep, lr, steps, lam=0.0, normalize=True):
+    """Gradient descent on the surrogate (plus the regulariser) for one matrix.  With
+    ``normalize`` the surrogate is divided by ||W||_F^2 (it then bounds the squared RELATIVE
+    l2 error), which makes the learning rate dimensionless.  Returns (T, history) where
+    history[s] = (l2_sq, err_z_sq, w_sq, surrogate, penalty) evaluated at the T of step s."""
+    W = np.asarray(W, dtype=np.float64)
+    T = np.asarray(T0, dtype=np.float64).copy()
+    hist = []
+    for _ in range(steps):
+        P = block_inverse(T)
+        f = proxy_l2(W, T, P, bits, group, axis, rep)
+        sur, g = surrogate(W, T, P, bits, group, axis, rep)
+        pen, gp = orth_penalty(T, lam)
+        if normalize:
+            g = g / f["w_sq"]
+        hist.append((f["l2_sq"], f["err_z_sq"], f["w_sq"], sur, pen))
+        T = sgd_step(T, g + gp, lr)
+    return T, np.array(hist)
+
+
+def optimize_pair(A, B, T0, bits, group, rep, t, lr, steps, lam=0.0, beta1=0.1, beta2=0.999, eps=1e-8):
+    """Adam on the LogSumExp surrogate (plus the regulariser) for a coupled pair.  Returns
+    (T, history) with history[s] = (errU_sq, errV_sq, l2A_sq, l2B_sq, lse, penalty)."""
+    T = np.asarray(T0, dtype=np.float64).copy()
+    m = np.zeros_like(T)
+    v = np.zeros_like(T)
+    hist = []
+    for s in range(steps):
+        P = block_inverse(T)
+        f = dual_lse(A, B, T, P, bits, group, rep, t)
+        pen, gp = orth_penalty(T, lam)
+        hist.append((f["errU_sq"], f["errV_sq"], f["l2A_sq"], f["l2B_sq"], f["lse"], pen))
+        T, m, v = adam_step(T, f["gradT"] + gp, m, v, s + 1, lr, beta1, beta2, eps)
+    return T, np.array(hist)
