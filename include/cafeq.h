@@ -95,7 +95,10 @@ typedef enum {
   CAFEQ_CALL_DUAL_PROXY_LOSS = 2,
   CAFEQ_CALL_ADAPTIVE_ROUND = 3,
   CAFEQ_CALL_BLOCK_INVERSE = 4,  /* reads x->k and x->nb only */
-  CAFEQ_CALL_APPLY_TRANSFORM = 5 /* reads x->k and x->nb only */
+  CAFEQ_CALL_APPLY_TRANSFORM = 5, /* reads x->k and x->nb only */
+  CAFEQ_CALL_ORTH_PENALTY = 6,    /* reads x->k and x->nb only */
+  CAFEQ_CALL_OPTIMIZE_SINGLE = 7, /* as CAFEQ_CALL_PROXY_LOSS */
+  CAFEQ_CALL_OPTIMIZE_PAIR = 8    /* as CAFEQ_CALL_DUAL_PROXY_LOSS */
 } cafeq_call_id;
 
 const char* cafeq_strerror(int status);
@@ -178,6 +181,54 @@ int cafeq_adaptive_round_step(const float* U, const float* V, int64_t rowsA, int
                               int k, int nb, int rep, int half, int8_t* codesU,
                               float* scalesU, int8_t* codesV, float* scalesV, int* status,
                               void* ws, void* stream);
+
+/* ---- Learning the transform ------------------------------------------------------------
+ * Paper Sec. 4.1: M is initialised block-diagonal with random rotations and learned by
+ * gradient descent on the surrogate; Sec. 4.2 and the appendix on paired-quantization
+ * hyperparameters: pairs are learned with Adam on the LogSumExp surrogate, optionally with
+ * the regulariser ||T T^T - I||_F / sqrt(d) weighted by lambda_orth. */
+
+/* value[1] (may be NULL) = lambda * ||T T^T - I||_F / sqrt(nb*k), one norm over all blocks.
+ * gradT[nb][k][k] (may be NULL) is INCREMENTED by its gradient
+ * 2 lambda (T T^T - I) T / (sqrt(nb*k) ||T T^T - I||_F); nothing is added where the norm
+ * vanishes.  The residual is formed with float64 accumulation. */
+int cafeq_orth_penalty(const float* T, int k, int nb, float lambda, float* value, float* gradT,
+                       void* ws, void* stream);
+
+/* T[i] -= lr * grad[i] / *denom for i < n.  denom: device pointer to one float, NULL = 1. */
+int cafeq_sgd_update(float* T, const float* grad, float lr, const float* denom, int64_t n,
+                     void* stream);
+
+/* One step of Adam with bias correction.  m, v: first / second moment, n floats each, zero
+ * before step 1; step counts from 1.  The hyper-parameters are doubles (1 - beta2 is formed
+ * in double); the element arithmetic is float32. */
+int cafeq_adam_update(float* T, const float* grad, float* m, float* v, int step, double lr,
+                      double beta1, double beta2, double eps, int64_t n, void* stream);
+
+typedef struct {
+  int steps;          /* iterations */
+  float lr;           /* learning rate */
+  float lambda_orth;  /* weight of the orthonormality regulariser, 0 = off */
+  int normalize;      /* single matrix: divide the surrogate's gradient by ||W||_F^2, so that
+                         the loss bounds the squared RELATIVE l2 error and lr is dimensionless */
+  double beta1, beta2, eps; /* Adam (pairs) */
+} cafeq_opt_cfg;
+
+/* steps iterations of { Tinv = T^-1; losses and gradient at T; + regulariser; T -= update },
+ * all enqueued on the stream, no host synchronisation.  T is updated in place; on return
+ * (stream order) Tinv is the inverse of the final T and status[nb] (may be NULL) that
+ * inversion's status.  history[steps][8] (device): the losses evaluated at the T of each
+ * step, before its update:
+ *   single: l2_sq, err_z_sq, w_sq, surrogate, penalty, 0, 0, 0     (gradient descent)
+ *   pair:   errU_sq, errV_sq, l2A_sq, l2B_sq, lse, n_groups, penalty, 0   (Adam)
+ * moments (pair): 2*nb*k*k floats of optimiser state, zeroed by the call. */
+int cafeq_optimize_single(const cafeq_mat* W, float* T, float* Tinv, int k, int nb, int rep,
+                          const cafeq_quant_cfg* cfg, const cafeq_opt_cfg* opt, float* history,
+                          int* status, void* ws, void* stream);
+int cafeq_optimize_pair(const cafeq_mat* A, const cafeq_mat* B, float* T, float* Tinv, int k,
+                        int nb, int rep, const cafeq_quant_cfg* cfg, float lse_t,
+                        const cafeq_opt_cfg* opt, float* moments, float* history, int* status,
+                        void* ws, void* stream);
 
 /* Measurement aid (not part of the method): while enabled, every launch of the fused
  * transform kernel is bracketed by HIP events recorded on the launch stream.

@@ -23,7 +23,8 @@ EXPORTS = (
     "cafeq_strerror", "cafeq_version", "cafeq_workspace_bytes", "cafeq_block_inverse",
     "cafeq_rtn_quantize", "cafeq_apply_transform", "cafeq_proxy_loss_fwd_bwd",
     "cafeq_dual_proxy_loss_fwd_bwd", "cafeq_adaptive_round_step",
-    "cafeq_profile_enable", "cafeq_profile_read",
+    "cafeq_orth_penalty", "cafeq_sgd_update", "cafeq_adam_update", "cafeq_optimize_single",
+    "cafeq_optimize_pair", "cafeq_profile_enable", "cafeq_profile_read",
 )
 
 
@@ -44,6 +45,12 @@ class Xform(ctypes.Structure):
 class QuantCfg(ctypes.Structure):
     _fields_ = [("bits", ctypes.c_int32), ("group", ctypes.c_int32), ("axis", ctypes.c_int32),
                 ("mode", ctypes.c_int32)]
+
+
+class OptCfg(ctypes.Structure):
+    _fields_ = [("steps", ctypes.c_int32), ("lr", ctypes.c_float), ("lambda_orth", ctypes.c_float),
+                ("normalize", ctypes.c_int32), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
+                ("eps", ctypes.c_double)]
 
 
 def _load():
@@ -70,6 +77,15 @@ def _load():
                                                   ctypes.c_float, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.cafeq_adaptive_round_step.argtypes = [vp, vp, i64, i64, i64, i64, ctypes.POINTER(QuantCfg),
                                               i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    f32 = ctypes.c_float
+    lib.cafeq_orth_penalty.argtypes = [vp, i32, i32, f32, vp, vp, vp, vp]
+    lib.cafeq_sgd_update.argtypes = [vp, vp, f32, vp, i64, vp]
+    f64 = ctypes.c_double
+    lib.cafeq_adam_update.argtypes = [vp, vp, vp, vp, i32, f64, f64, f64, f64, i64, vp]
+    lib.cafeq_optimize_single.argtypes = [ctypes.POINTER(Mat), vp, vp, i32, i32, i32, ctypes.POINTER(QuantCfg),
+                                          ctypes.POINTER(OptCfg), vp, vp, vp, vp]
+    lib.cafeq_optimize_pair.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Mat), vp, vp, i32, i32, i32,
+                                        ctypes.POINTER(QuantCfg), f32, ctypes.POINTER(OptCfg), vp, vp, vp, vp, vp]
     lib.cafeq_profile_enable.argtypes = [i32]
     lib.cafeq_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float)]
     for n in EXPORTS[3:]:
@@ -250,3 +266,58 @@ def profile_read():
     ms = ctypes.c_float(0.0)
     n = lib.cafeq_profile_read(ctypes.byref(ms))
     return n, float(ms.value)
+
+
+def orth_penalty(T, lam, grad=None):
+    """(value[1], grad) with grad incremented in place when given."""
+    nb, k, _ = T.shape
+    x = Xform(_ptr(T), 0, k, nb, 1)
+    ws = workspace(int(lib.cafeq_workspace_bytes(6, None, None, ctypes.byref(x), None)), T.device)
+    value = torch.empty(1, dtype=torch.float32, device=T.device)
+    _check(lib.cafeq_orth_penalty(_ptr(T), k, nb, lam, _ptr(value), _ptr(grad), _ptr(ws), _stream()))
+    return value, grad
+
+
+def sgd_update(T, grad, lr, denom=None):
+    _check(lib.cafeq_sgd_update(_ptr(T), _ptr(grad), lr, _ptr(denom), T.numel(), _stream()))
+
+
+def adam_update(T, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8):
+    _check(lib.cafeq_adam_update(_ptr(T), _ptr(grad), _ptr(m), _ptr(v), step, lr, beta1, beta2, eps, T.numel(),
+                                 _stream()))
+
+
+def optimize_single(W, T, bits, group, axis=AXIS_COL, rep=1, lr=1.0, steps=10, lambda_orth=0.0, normalize=True):
+    """Gradient descent on the surrogate, T updated in place.  Returns (Tinv, history[steps][8], status)."""
+    m = mat(W)
+    nb, k, _ = T.shape
+    Tinv = torch.empty_like(T)
+    x = Xform(_ptr(T), _ptr(Tinv), k, nb, rep)
+    cfg = QuantCfg(bits, group, axis, 0)
+    opt = OptCfg(steps, lr, lambda_orth, 1 if normalize else 0, 0.0, 0.0, 0.0)
+    ws = workspace(int(lib.cafeq_workspace_bytes(7, ctypes.byref(m), None, ctypes.byref(x), ctypes.byref(cfg))), W.device)
+    history = torch.empty((max(steps, 1), 8), dtype=torch.float32, device=W.device)
+    status = torch.empty(nb, dtype=torch.int32, device=W.device)
+    _check(lib.cafeq_optimize_single(ctypes.byref(m), _ptr(T), _ptr(Tinv), k, nb, rep, ctypes.byref(cfg),
+                                     ctypes.byref(opt), _ptr(history), _ptr(status), _ptr(ws), _stream()))
+    return Tinv, history[:steps], status
+
+
+def optimize_pair(A, B, T, bits, group, rep=1, lse_t=5.0, lr=1e-2, steps=10, lambda_orth=0.0, beta1=0.1,
+                  beta2=0.999, eps=1e-8):
+    """Adam on the LogSumExp surrogate, T updated in place.  Returns (Tinv, history[steps][8], status)."""
+    ma, mb = mat(A), mat(B)
+    nb, k, _ = T.shape
+    Tinv = torch.empty_like(T)
+    x = Xform(_ptr(T), _ptr(Tinv), k, nb, rep)
+    cfg = QuantCfg(bits, group, 0, 0)
+    opt = OptCfg(steps, lr, lambda_orth, 0, beta1, beta2, eps)
+    ws = workspace(int(lib.cafeq_workspace_bytes(8, ctypes.byref(ma), ctypes.byref(mb), ctypes.byref(x),
+                                                 ctypes.byref(cfg))), A.device)
+    moments = torch.empty(2 * T.numel(), dtype=torch.float32, device=A.device)
+    history = torch.empty((max(steps, 1), 8), dtype=torch.float32, device=A.device)
+    status = torch.empty(nb, dtype=torch.int32, device=A.device)
+    _check(lib.cafeq_optimize_pair(ctypes.byref(ma), ctypes.byref(mb), _ptr(T), _ptr(Tinv), k, nb, rep,
+                                   ctypes.byref(cfg), lse_t, ctypes.byref(opt), _ptr(moments), _ptr(history),
+                                   _ptr(status), _ptr(ws), _stream()))
+    return Tinv, history[:steps], status

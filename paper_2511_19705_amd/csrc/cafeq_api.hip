@@ -279,6 +279,78 @@ const char* cafeq_strerror(int status) {
 
 int cafeq_version(void) { return 100; }
 
+namespace {
+struct OptWs { float* grad; void* orth; void* sub; };
+OptWs carve_opt(void* ws, int k, int nb) {
+  char* base = static_cast<char*>(ws);
+  OptWs w;
+  w.grad = reinterpret_cast<float*>(base);
+  w.orth = base + align_up(size_t(nb) * k * k * sizeof(float), 256);
+  w.sub = static_cast<char*>(w.orth) + orth_workspace_bytes(k, nb);
+  return w;
+}
+int check_opt(const cafeq_opt_cfg* opt) {
+  if (!opt) return CAFEQ_ERR_INVALID_ARG;
+  if (opt->steps < 0 || !(opt->lr >= 0.f) || !(opt->lambda_orth >= 0.f)) return CAFEQ_ERR_INVALID_ARG;
+  return CAFEQ_OK;
+}
+}  // namespace
+
+int cafeq_optimize_single(const cafeq_mat* W, float* T, float* Tinv, int k, int nb, int rep,
+                          const cafeq_quant_cfg* cfg, const cafeq_opt_cfg* opt, float* history, int* status,
+                          void* ws, void* stream) {
+  int rc = check_opt(opt);
+  if (rc) return rc;
+  if (!T || !Tinv || !history) return CAFEQ_ERR_INVALID_ARG;
+  if (!ws) return CAFEQ_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const OptWs w = carve_opt(ws, k, nb);
+  const int64_t n = int64_t(nb) * k * k;
+  cafeq_xform x{T, Tinv, k, nb, rep};
+  if ((rc = launch_fill(history, 0.f, int64_t(opt->steps) * 8, st))) return rc;
+  for (int s = 0; s < opt->steps; ++s) {
+    float* h = history + size_t(s) * 8;
+    if ((rc = cafeq_block_inverse(T, k, nb, Tinv, nullptr, nullptr, status, w.sub, stream))) return rc;
+    if ((rc = cafeq_proxy_loss_fwd_bwd(W, &x, cfg, h, w.grad, nullptr, nullptr, w.sub, stream))) return rc;
+    // surrogate / ||W||^2 (history[s][2]) when normalised, then the regulariser's gradient on top
+    if (opt->normalize && (rc = launch_div_by_device_scalar(w.grad, h + 2, n, st))) return rc;
+    if (opt->lambda_orth > 0.f &&
+        (rc = cafeq_orth_penalty(T, k, nb, opt->lambda_orth, h + 4, w.grad, w.orth, stream)))
+      return rc;
+    if ((rc = cafeq_sgd_update(T, w.grad, opt->lr, nullptr, n, stream))) return rc;
+  }
+  return cafeq_block_inverse(T, k, nb, Tinv, nullptr, nullptr, status, w.sub, stream);
+}
+
+int cafeq_optimize_pair(const cafeq_mat* A, const cafeq_mat* B, float* T, float* Tinv, int k, int nb, int rep,
+                        const cafeq_quant_cfg* cfg, float lse_t, const cafeq_opt_cfg* opt, float* moments,
+                        float* history, int* status, void* ws, void* stream) {
+  int rc = check_opt(opt);
+  if (rc) return rc;
+  if (!T || !Tinv || !history || !moments) return CAFEQ_ERR_INVALID_ARG;
+  if (!ws) return CAFEQ_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const OptWs w = carve_opt(ws, k, nb);
+  const int64_t n = int64_t(nb) * k * k;
+  cafeq_xform x{T, Tinv, k, nb, rep};
+  if ((rc = launch_fill(history, 0.f, int64_t(opt->steps) * 8, st))) return rc;
+  if ((rc = launch_fill(moments, 0.f, 2 * n, st))) return rc;
+  for (int s = 0; s < opt->steps; ++s) {
+    float* h = history + size_t(s) * 8;
+    if ((rc = cafeq_block_inverse(T, k, nb, Tinv, nullptr, nullptr, status, w.sub, stream))) return rc;
+    if ((rc = cafeq_dual_proxy_loss_fwd_bwd(A, B, &x, cfg, lse_t, h, w.grad, nullptr, nullptr, nullptr, nullptr, w.sub,
+                                            stream)))
+      return rc;
+    if (opt->lambda_orth > 0.f &&
+        (rc = cafeq_orth_penalty(T, k, nb, opt->lambda_orth, h + 6, w.grad, w.orth, stream)))
+      return rc;
+    if ((rc = cafeq_adam_update(T, w.grad, moments, moments + n, s + 1, opt->lr, opt->beta1, opt->beta2, opt->eps, n,
+                                stream)))
+      return rc;
+  }
+  return cafeq_block_inverse(T, k, nb, Tinv, nullptr, nullptr, status, w.sub, stream);
+}
+
 
 int cafeq_profile_enable(int on) {
   cafeq::g_prof.on = on != 0;
@@ -335,6 +407,20 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
         return 0;
       return std::max(carve_dual(nullptr, ga.first, gb.first, ga.gpass, gb.gpass, x->nb, true, ga.two, gb.two).bytes,
                       carve_dual(nullptr, na.first, nbp.first, na.gpass, nbp.gpass, x->nb, false, false, false).bytes);
+    }
+    case CAFEQ_CALL_ORTH_PENALTY:
+      if (!x) return 0;
+      return orth_workspace_bytes(x->k, x->nb);
+    case CAFEQ_CALL_OPTIMIZE_SINGLE:
+    case CAFEQ_CALL_OPTIMIZE_PAIR: {
+      // gradient buffer + regulariser scratch + the larger of the sub-calls' workspaces
+      if (!x) return 0;
+      const size_t sub = std::max(
+          cafeq_workspace_bytes(call_id == CAFEQ_CALL_OPTIMIZE_SINGLE ? CAFEQ_CALL_PROXY_LOSS : CAFEQ_CALL_DUAL_PROXY_LOSS,
+                                a, b, x, cfg),
+          cafeq_workspace_bytes(CAFEQ_CALL_BLOCK_INVERSE, a, b, x, cfg));
+      if (sub == 0) return 0;
+      return align_up(size_t(x->nb) * x->k * x->k * sizeof(float), 256) + orth_workspace_bytes(x->k, x->nb) + sub;
     }
     case CAFEQ_CALL_ADAPTIVE_ROUND: {
       // a: U [rowsA][nb*k], b: V [nb*rep*k][colsB]

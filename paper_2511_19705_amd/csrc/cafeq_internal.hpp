@@ -68,4 +68,7 @@ int launch_gj_solve(int K, int nb, int nz, const float* partial, double* work, f
 int launch_block_inverse(const float* T, int K, int nb, double* work, float* Tinv, float* rho_row,
                          float* rho_col, int* status, hipStream_t st);
 
+int launch_fill(float* p, float value, int64_t n, hipStream_t st);
+size_t orth_workspace_bytes(int k, int nb);
+int launch_div_by_device_scalar(float* g, const float* denom, int64_t n, hipStream_t st);
 }  // namespace cafeq
