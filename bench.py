@@ -41,15 +41,18 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {"c3_pair_3584x14336_k128_g128_b3": (2.0 * 168382 + 24288) * 1024}
 
 
+def _cores():
+    try:
+        from threadpoolctl import threadpool_info
+        return int(max([p.get("num_threads", 1) for p in threadpool_info()] + [1]))
+    except Exception:
+        return os.cpu_count() or 1
+
+
 def cpu_baseline(cfg, blocks, reps):
     """The oracle as it stands, on the first `blocks` transform blocks of the pair."""
     import numpy as np
     from oracle import cafeq_oracle as O
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        cores = os.cpu_count() or 1
     k = cfg["k"]
     A = np.ascontiguousarray(cfg["A"][:, :blocks * k])
     B = np.ascontiguousarray(cfg["B"][:blocks * k, :])
@@ -60,9 +63,119 @@ def cpu_baseline(cfg, blocks, reps):
         O.dual_lse(A, B, T, P, cfg["bits"][0], cfg["group"], cfg["rep"], 5.0)
     dt = time.perf_counter() - t0
     elems = A.size + B.size
-    return {"value": elems * reps / dt, "unit": "weight-elements/s", "cores": int(cores), "kind": "oracle",
+    return {"value": elems * reps / dt, "unit": "weight-elements/s", "cores": _cores(), "kind": "oracle",
             "sample": "%d of %d transform blocks of the same pair (%.1f M weights), %d x (block inverse + "
                       "fwd+bwd), %.1f s" % (blocks, cfg["T"].shape[0], elems / 1e6, reps, dt)}
+
+
+def other_workload(args):
+    """Secondary workloads (not the headline metric): one JSON line each, same fields.
+       c3_optimize : Adam iterations on the 9B-shaped pair (inverse + paired fwd+bwd + update)
+       c2_single   : single-matrix fwd+bwd on the 2B-shaped down projection (k = 64, fused gradient)
+       c4_adaptive : Alg. 1 iterations on the 9B-shaped attention V/O pair (k = 256)"""
+    import numpy as np
+    import torch
+    from paper_2511_19705_amd import cafeq, workloads as WL
+    dev = torch.device("cuda:0")
+    cores = _cores()
+    if args.workload == "c3_optimize":
+        cfg = WL.config3()
+        A, B = torch.from_numpy(cfg["A"]).to(dev), torch.from_numpy(cfg["B"]).to(dev)
+        T = torch.from_numpy(cfg["T"].copy()).to(dev)
+        elems, k = A.numel() + B.numel(), cfg["k"]
+        run = lambda n: cafeq.optimize_pair(A, B, T, cfg["bits"][0], cfg["group"], 1, 5.0, 1e-3, n)
+        metric = "learning iterations, weight-elements/s (Adam on the LogSumExp surrogate, 9B-shaped MLP pair)"
+        flop_el, parts, kern = 4 * k, 9, "xform_core_kernel<128,128,*,false> (loss pass)"
+
+        def cpu():
+            from oracle import cafeq_oracle as O
+            nbk = 16
+            a = np.ascontiguousarray(cfg["A"][:, :nbk * k]); b = np.ascontiguousarray(cfg["B"][:nbk * k, :])
+            t0 = time.perf_counter()
+            O.optimize_pair(a, b, cfg["T"][:nbk], cfg["bits"][0], cfg["group"], 1, 5.0, 1e-3, 2)
+            dt = time.perf_counter() - t0
+            return (a.size + b.size) * 2 / dt, "%d of %d blocks of the pair, 2 Adam iterations, %.1f s" % (nbk, cfg["T"].shape[0], dt)
+    elif args.workload == "c2_single":
+        cfg = WL.config2()
+        W = torch.from_numpy(cfg["W"]).to(dev)
+        T = torch.from_numpy(cfg["T"]).to(dev)
+        elems, k = W.numel(), cfg["k"]
+
+        def run(n):
+            for _ in range(n):
+                P, _ = cafeq.block_inverse(T)
+                cafeq.proxy_loss_fwd_bwd(W, T, P, cfg["bits"][0], cfg["group"], 0, 1, want_grad=True)
+        metric = "proxy-loss fwd+bwd weight-elements/s (2B-shaped down projection, single transform)"
+        flop_el, parts, kern = 6 * k, 12, "xform_core_kernel<64,128,COL,true> (fused)"
+
+        def cpu():
+            from oracle import cafeq_oracle as O
+            nbk = 48
+            w = np.ascontiguousarray(cfg["W"][:, :nbk * k]); t = cfg["T"][:nbk]
+            t0 = time.perf_counter()
+            for _ in range(3):
+                p_ = O.block_inverse(t)
+                O.proxy_l2(w, t, p_, cfg["bits"][0], cfg["group"], 0, 1)
+                O.surrogate(w, t, p_, cfg["bits"][0], cfg["group"], 0, 1)
+            dt = time.perf_counter() - t0
+            return w.size * 3 / dt, "%d of %d blocks, 3 x (inverse + fwd+bwd), %.1f s" % (nbk, cfg["T"].shape[0], dt)
+    else:
+        cfg = WL.config4()
+        k, rep, g, bits = cfg["k"], cfg["rep"], cfg["group"], cfg["bits"][0]
+        A, B = torch.from_numpy(cfg["A"]).to(dev), torch.from_numpy(cfg["B"]).to(dev)
+        T = torch.from_numpy(cfg["T"]).to(dev)
+        P, _ = cafeq.block_inverse(T)
+        U = cafeq.apply_transform(A, T, P, 0, cafeq.SIDE_T, 1)
+        V = cafeq.apply_transform(B, T, P, 1, cafeq.SIDE_TINV, rep)
+        cu, su, _ = cafeq.rtn_quantize(U, bits, g, 0)
+        cv, sv, _ = cafeq.rtn_quantize(V, bits, g, 1)
+        elems = U.numel() + V.numel()
+
+        def run(n):
+            for _ in range(n):
+                cafeq.adaptive_round_step(U, V, cu, su, cv, sv, bits, g, k, rep, half=0)
+        metric = "adaptive-rounding iterations, weight-elements/s (Alg. 1, 9B-shaped attention V/O pair)"
+        flop_el, parts, kern = 2 * k, 6, "xform_core_kernel<256,64,*,false> (transform + requantize)"
+
+        def cpu():
+            from oracle import cafeq_oracle as O
+            Un, Vn = U.cpu().numpy(), V.cpu().numpy()
+            nh = 2
+            u = np.ascontiguousarray(Un[:, :nh * k]); v = np.ascontiguousarray(Vn[:nh * rep * k, :])
+            c0, s0, _ = O.rtn_sym(u, bits, g, O.COL)
+            uh = c0.astype(np.float64) * np.repeat(s0.astype(np.float64), g, axis=1)
+            t0 = time.perf_counter()
+            O.adaptive_round_step(u, v, uh, bits, g, k, rep)
+            dt = time.perf_counter() - t0
+            return (u.size + v.size) / dt, "%d of %d heads, 1 iteration (SVD pseudoinverse), %.1f s" % (nh, cfg["T"].shape[0], dt)
+
+    run(max(args.warmup, 1))
+    torch.cuda.synchronize()
+    cafeq.profile_enable(True)
+    cafeq.profile_read()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    n_launch, core_ms = cafeq.profile_read()
+    cafeq.profile_enable(False)
+    avg = core_ms / 1e3 / max(n_launch, 1)
+    per_launch_el = elems * args.steps / max(n_launch, 1)
+    achieved = flop_el * per_launch_el / avg / 1e12
+    out = {"metric": metric, "value": elems * args.steps / dt, "unit": "weight-elements/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": cfg["name"] + ("_adam" if args.workload == "c3_optimize" else ""),
+                      "block": k, "group": cfg["group"], "bits": cfg["bits"][0]},
+           "roofline": {"bound": "mfma", "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": None, "kernel": kern,
+                        "launches": n_launch, "avg_launch_us": avg * 1e6,
+                        "algorithmic_flop_per_element": flop_el,
+                        "executed_part_product_tflops": achieved * parts * 2 * k / flop_el}}
+    if not args.no_cpu_baseline:
+        v, sample = cpu()
+        out["cpu_baseline"] = {"value": v, "unit": "weight-elements/s", "cores": cores, "kind": "oracle", "sample": sample}
+    print(json.dumps(out))
 
 
 def main():
@@ -73,6 +186,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-blocks", type=int, default=112)
     ap.add_argument("--cpu-reps", type=int, default=4)
+    ap.add_argument("--workload", default="c3_pair", choices=["c3_pair", "c3_optimize", "c2_single", "c4_adaptive"],
+                    help="c3_pair is the headline metric; the others are secondary measurements")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for the profiler's byte counters)")
     args = ap.parse_args()
@@ -84,6 +199,8 @@ def main():
     from paper_2511_19705_amd import cafeq, workloads as WL
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.workload != "c3_pair":
+        return other_workload(args)
     dev = torch.device("cuda:0")
     cfg = WL.config3()
     k, g, bits, rep = cfg["k"], cfg["group"], cfg["bits"][0], cfg["rep"]
