@@ -38,104 +38,138 @@ struct GramArgs {
 };
 
 // AXIS == COL: t = row i, free index = column;  AXIS == ROW: t = column c, free index = row.
-template <int AXIS>
+// One workgroup per (head, 32-row output stripe jt1, chunk of the contraction range).  Per step
+// of 16 contraction indices the workgroup loads the head's 16 x K slab of codes, scales and
+// originals with wide coalesced loads, dequantizes it ONCE (Xq and E = Xq - X) into LDS laid out
+// [t][free index], and every wave feeds its MFMAs from there: A = Xq[t][stripe columns] (shared
+// by the waves), B = Xq / E [t][its output tiles].  The next slab's loads are in flight while
+// the matrix cores work on the current one.
+template <int AXIS, int K>
 __global__ __launch_bounds__(256) void gram_pair_kernel(const GramArgs a) {
-  const int K = a.K, KT = K / 32;
+  // row stride of the LDS slab: 16-byte aligned rows for the vector stores of the column case;
+  // K + 2 for the row case, whose transposing scalar stores then spread over all banks
+  constexpr int KT = K / 32, LD = AXIS == CAFEQ_AXIS_COL ? K + 4 : K + 2;
+  __shared__ __align__(16) float qs[16 * LD];
+  __shared__ __align__(16) float es[16 * LD];
   const int b = blockIdx.x, jt1 = blockIdx.y;
   const int z = blockIdx.z;                      // (row-block within head, chunk)
   const int qi = z / a.nchunk, ch = z % a.nchunk;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, ln = lane & 31, h = lane >> 5;
-  if (wave >= KT) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ln = lane & 31, h = lane >> 5;
   const int64_t t0 = int64_t(ch) * a.chunk;
   const int64_t t1 = t0 + a.chunk < a.tlen ? t0 + a.chunk : a.tlen;
   // free-index origin of this head / row-block
   const int64_t f0 = AXIS == CAFEQ_AXIS_COL ? int64_t(b) * K : (int64_t(b) * a.rep + qi) * K;
+  const int64_t C = a.cols;
 
   floatx16 accS[2], accR[2];
 #pragma unroll
   for (int u = 0; u < 2; ++u)
 #pragma unroll
     for (int v = 0; v < 16; ++v) { accS[u][v] = 0.f; accR[u][v] = 0.f; }
-  const int nt2 = (KT - wave + 3) / 4;           // output tiles of this wave: jt2 = wave + 4u
+  const int nt2 = wave < KT ? (KT - wave + 3) / 4 : 0;   // output tiles of this wave: jt2 = wave + 4u
 
-  if (AXIS == CAFEQ_AXIS_COL) {
-    const int64_t C = a.cols, SG = a.cols / a.G;
-    for (int64_t t = t0; t < t1; t += 16) {
-      // eight MFMA steps: step e covers rows t + 2e + h
-      float xa[8], xb[2][8], eb[2][8];
+  // ---- loader roles.  COL: thread -> (t = l / (K/EPT), EPT consecutive columns);
+  // ROW: NP passes of 64 rows, thread -> (row = pass*64 + l/4, four consecutive t = 4*(l%4) ..)
+  constexpr int EPT = K >= 64 ? K / 16 : 4;          // COL: columns per thread
+  constexpr int NLD = 16 * K / EPT;                  // COL: active loader threads
+  constexpr int NP = (K + 63) / 64;                  // ROW: passes
+  uint32_t rc[AXIS == CAFEQ_AXIS_COL ? EPT / 4 : NP];
+  float4 rx[AXIS == CAFEQ_AXIS_COL ? EPT / 4 : NP];
+  float4 rs[AXIS == CAFEQ_AXIS_COL ? 1 : NP];        // COL: .x only
+  bool rok[AXIS == CAFEQ_AXIS_COL ? 1 : NP];
+
+  auto issue = [&](int64_t t) {
+    if (AXIS == CAFEQ_AXIS_COL) {
+      const int tt = tid / (K / EPT), c0 = (tid % (K / EPT)) * EPT;
+      const int64_t i = t + tt;
+      rok[0] = tid < NLD && i < t1;
+      if (rok[0]) {
+        const int64_t col = f0 + c0;
+        rs[0].x = a.scales[i * (C / a.G) + col / a.G];
+#pragma unroll
+        for (int j = 0; j < EPT / 4; ++j) {
+          rc[j] = *reinterpret_cast<const uint32_t*>(a.codes + i * C + col + 4 * j);
+          rx[j] = *reinterpret_cast<const float4*>(a.X + i * C + col + 4 * j);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int pz = 0; pz < NP; ++pz) {
+        const int r = pz * 64 + tid / 4;
+        const int64_t c = t + 4 * (tid % 4);
+        rok[pz] = r < K && c < t1;                  // tlen and chunk are multiples of 4
+        if (rok[pz]) {
+          const int64_t row = f0 + r;
+          rs[pz] = *reinterpret_cast<const float4*>(a.scales + (row / a.G) * C + c);
+          rc[pz] = *reinterpret_cast<const uint32_t*>(a.codes + row * C + c);
+          rx[pz] = *reinterpret_cast<const float4*>(a.X + row * C + c);
+        }
+      }
+    }
+  };
+  auto commit = [&]() {
+    if (AXIS == CAFEQ_AXIS_COL) {
+      if (tid < NLD) {
+        const int tt = tid / (K / EPT), c0 = (tid % (K / EPT)) * EPT;
+#pragma unroll
+        for (int j = 0; j < EPT / 4; ++j) {
+          float4 q = make_float4(0.f, 0.f, 0.f, 0.f), e = q;
+          if (rok[0]) {
+            const uint32_t cw = rc[j];
+            q.x = __fmul_rn(float(int8_t(cw)), rs[0].x);
+            q.y = __fmul_rn(float(int8_t(cw >> 8)), rs[0].x);
+            q.z = __fmul_rn(float(int8_t(cw >> 16)), rs[0].x);
+            q.w = __fmul_rn(float(int8_t(cw >> 24)), rs[0].x);
+            e = make_float4(q.x - rx[j].x, q.y - rx[j].y, q.z - rx[j].z, q.w - rx[j].w);
+          }
+          *reinterpret_cast<float4*>(qs + tt * LD + c0 + 4 * j) = q;
+          *reinterpret_cast<float4*>(es + tt * LD + c0 + 4 * j) = e;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int pz = 0; pz < NP; ++pz) {
+        const int r = pz * 64 + tid / 4, tq = 4 * (tid % 4);
+        if (r < K) {
+          float q[4] = {0.f, 0.f, 0.f, 0.f}, e[4] = {0.f, 0.f, 0.f, 0.f};
+          if (rok[pz]) {
+            const uint32_t cw = rc[pz];
+            q[0] = __fmul_rn(float(int8_t(cw)), rs[pz].x);
+            q[1] = __fmul_rn(float(int8_t(cw >> 8)), rs[pz].y);
+            q[2] = __fmul_rn(float(int8_t(cw >> 16)), rs[pz].z);
+            q[3] = __fmul_rn(float(int8_t(cw >> 24)), rs[pz].w);
+            e[0] = q[0] - rx[pz].x; e[1] = q[1] - rx[pz].y; e[2] = q[2] - rx[pz].z; e[3] = q[3] - rx[pz].w;
+          }
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            qs[(tq + j) * LD + r] = q[j];
+            es[(tq + j) * LD + r] = e[j];
+          }
+        }
+      }
+    }
+  };
+
+  issue(t0);
+  for (int64_t t = t0; t < t1; t += 16) {
+    commit();
+    __syncthreads();
+    if (t + 16 < t1) issue(t + 16);
+    if (nt2 > 0) {
+      const float* pa = qs + h * LD + jt1 * 32 + ln;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const int64_t i = t + 2 * e + h;
-        const bool ok = i < t1;
-        const int64_t ca = f0 + jt1 * 32 + ln;
-        xa[e] = ok ? __fmul_rn(float(a.codes[i * C + ca]), a.scales[i * SG + ca / a.G]) : 0.f;
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const int64_t cb = f0 + (wave + 4 * u) * 32 + ln;
-          if (u < nt2 && ok) {
-            const float q = __fmul_rn(float(a.codes[i * C + cb]), a.scales[i * SG + cb / a.G]);
-            xb[u][e] = q;
-            eb[u][e] = q - a.X[i * C + cb];
-          } else {
-            xb[u][e] = 0.f; eb[u][e] = 0.f;
-          }
-        }
-      }
-#pragma unroll
-      for (int e = 0; e < 8; ++e)
+        const float xa = pa[2 * e * LD];
 #pragma unroll
         for (int u = 0; u < 2; ++u)
           if (u < nt2) {
-            accS[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[e], xb[u][e], accS[u], 0, 0, 0);
-            accR[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[e], eb[u][e], accR[u], 0, 0, 0);
+            const int off = (2 * e + h) * LD + (wave + 4 * u) * 32 + ln;
+            accS[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa, qs[off], accS[u], 0, 0, 0);
+            accR[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa, es[off], accR[u], 0, 0, 0);
           }
-    }
-  } else {
-    const int64_t C = a.cols;
-    for (int64_t t = t0; t < t1; t += 16) {
-      // two groups of four steps: step (g4, e) covers columns t + 8*g4 + 4h + e
-      float xa[8], xb[2][8], eb[2][8];
-#pragma unroll
-      for (int g4 = 0; g4 < 2; ++g4) {
-        const int64_t c = t + 8 * g4 + 4 * h;
-        const bool ok = c < t1;                   // tlen and chunk are multiples of 4
-        const int64_t ra = f0 + jt1 * 32 + ln;
-        float4 s4 = make_float4(0.f, 0.f, 0.f, 0.f);
-        uint32_t cw = 0;
-        if (ok) {
-          s4 = *reinterpret_cast<const float4*>(a.scales + (ra / a.G) * C + c);
-          cw = *reinterpret_cast<const uint32_t*>(a.codes + ra * C + c);
-        }
-        xa[4 * g4 + 0] = __fmul_rn(float(int8_t(cw)), s4.x);
-        xa[4 * g4 + 1] = __fmul_rn(float(int8_t(cw >> 8)), s4.y);
-        xa[4 * g4 + 2] = __fmul_rn(float(int8_t(cw >> 16)), s4.z);
-        xa[4 * g4 + 3] = __fmul_rn(float(int8_t(cw >> 24)), s4.w);
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const int64_t rb = f0 + (wave + 4 * u) * 32 + ln;
-          float4 sb = make_float4(0.f, 0.f, 0.f, 0.f), xv = make_float4(0.f, 0.f, 0.f, 0.f);
-          uint32_t cb = 0;
-          if (u < nt2 && ok) {
-            sb = *reinterpret_cast<const float4*>(a.scales + (rb / a.G) * C + c);
-            cb = *reinterpret_cast<const uint32_t*>(a.codes + rb * C + c);
-            xv = *reinterpret_cast<const float4*>(a.X + rb * C + c);
-          }
-          const float q0 = __fmul_rn(float(int8_t(cb)), sb.x), q1 = __fmul_rn(float(int8_t(cb >> 8)), sb.y);
-          const float q2 = __fmul_rn(float(int8_t(cb >> 16)), sb.z), q3 = __fmul_rn(float(int8_t(cb >> 24)), sb.w);
-          xb[u][4 * g4 + 0] = q0; xb[u][4 * g4 + 1] = q1; xb[u][4 * g4 + 2] = q2; xb[u][4 * g4 + 3] = q3;
-          eb[u][4 * g4 + 0] = q0 - xv.x; eb[u][4 * g4 + 1] = q1 - xv.y;
-          eb[u][4 * g4 + 2] = q2 - xv.z; eb[u][4 * g4 + 3] = q3 - xv.w;
-        }
       }
-#pragma unroll
-      for (int e = 0; e < 8; ++e)
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-          if (u < nt2) {
-            accS[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[e], xb[u][e], accS[u], 0, 0, 0);
-            accR[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[e], eb[u][e], accR[u], 0, 0, 0);
-          }
     }
+    __syncthreads();
   }
 
   // partial[b][z][0|1][row][col]
@@ -512,8 +546,16 @@ int launch_gram_pair(int axis, const float* X, const int8_t* codes, const float*
   a.tlen = axis == CAFEQ_AXIS_COL ? rows : cols;
   a.chunk = chunk; a.nchunk = nchunk; a.partial = partial;
   dim3 grid(nb, K / 32, a.rep * nchunk);
-  if (axis == CAFEQ_AXIS_COL) hipLaunchKernelGGL(gram_pair_kernel<CAFEQ_AXIS_COL>, grid, dim3(256), 0, st, a);
-  else hipLaunchKernelGGL(gram_pair_kernel<CAFEQ_AXIS_ROW>, grid, dim3(256), 0, st, a);
+#define CAFEQ_GRAM(KK)                                                                                      \
+  case KK:                                                                                                  \
+    if (axis == CAFEQ_AXIS_COL) hipLaunchKernelGGL((gram_pair_kernel<CAFEQ_AXIS_COL, KK>), grid, dim3(256), 0, st, a); \
+    else hipLaunchKernelGGL((gram_pair_kernel<CAFEQ_AXIS_ROW, KK>), grid, dim3(256), 0, st, a);             \
+    break;
+  switch (K) {
+    CAFEQ_GRAM(32) CAFEQ_GRAM(64) CAFEQ_GRAM(128) CAFEQ_GRAM(256)
+    default: return CAFEQ_ERR_UNSUPPORTED;
+  }
+#undef CAFEQ_GRAM
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }
