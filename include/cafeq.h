@@ -98,7 +98,8 @@ typedef enum {
   CAFEQ_CALL_APPLY_TRANSFORM = 5, /* reads x->k and x->nb only */
   CAFEQ_CALL_ORTH_PENALTY = 6,    /* reads x->k and x->nb only */
   CAFEQ_CALL_OPTIMIZE_SINGLE = 7, /* as CAFEQ_CALL_PROXY_LOSS */
-  CAFEQ_CALL_OPTIMIZE_PAIR = 8    /* as CAFEQ_CALL_DUAL_PROXY_LOSS */
+  CAFEQ_CALL_OPTIMIZE_PAIR = 8,   /* as CAFEQ_CALL_DUAL_PROXY_LOSS */
+  CAFEQ_CALL_PQE = 9              /* as CAFEQ_CALL_ADAPTIVE_ROUND */
 } cafeq_call_id;
 
 const char* cafeq_strerror(int status);
@@ -181,6 +182,19 @@ int cafeq_adaptive_round_step(const float* U, const float* V, int64_t rowsA, int
                               int k, int nb, int rep, int half, int8_t* codesU,
                               float* scalesU, int8_t* codesV, float* scalesV, int* status,
                               void* ws, void* stream);
+
+/* Paired quantization error of a transformed pair (paper Sec. 4.2, || W1 W2 - Q(W1) Q(W2) ||_F: the
+ * quantity Alg. 1 lowers and the paper's tables on pairs report), per head as in
+ * cafeq_adaptive_round_step: with Uq, Vq the dequantized codes,
+ *   out[0] = sum over heads b and their row-blocks q of || Uq_b Vq_q - U_b V_q ||_F^2
+ *   out[1] = sum of || U_b V_q ||_F^2            (relative PQE = sqrt(out[0] / out[1]))
+ * The d1 x d3 products are never formed: both sums are traces of products of k x k Gram
+ * matrices of each member (float32 matrix-core sums, float64 from there on), written on the
+ * rounding errors so that no large terms cancel. */
+int cafeq_pqe(const float* U, const float* V, int64_t rowsA, int64_t colsA, int64_t rowsB,
+              int64_t colsB, const cafeq_quant_cfg* cfg, int k, int nb, int rep,
+              const int8_t* codesU, const float* scalesU, const int8_t* codesV,
+              const float* scalesV, float* out, void* ws, void* stream);
 
 /* ---- Learning the transform ------------------------------------------------------------
  * Paper Sec. 4.1: M is initialised block-diagonal with random rotations and learned by

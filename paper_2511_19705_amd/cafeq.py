@@ -24,7 +24,7 @@ EXPORTS = (
     "cafeq_rtn_quantize", "cafeq_apply_transform", "cafeq_proxy_loss_fwd_bwd",
     "cafeq_dual_proxy_loss_fwd_bwd", "cafeq_adaptive_round_step",
     "cafeq_orth_penalty", "cafeq_sgd_update", "cafeq_adam_update", "cafeq_optimize_single",
-    "cafeq_optimize_pair", "cafeq_profile_enable", "cafeq_profile_read",
+    "cafeq_optimize_pair", "cafeq_pqe", "cafeq_profile_enable", "cafeq_profile_read",
 )
 
 
@@ -86,6 +86,8 @@ def _load():
                                           ctypes.POINTER(OptCfg), vp, vp, vp, vp]
     lib.cafeq_optimize_pair.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Mat), vp, vp, i32, i32, i32,
                                         ctypes.POINTER(QuantCfg), f32, ctypes.POINTER(OptCfg), vp, vp, vp, vp, vp]
+    lib.cafeq_pqe.argtypes = [vp, vp, i64, i64, i64, i64, ctypes.POINTER(QuantCfg), i32, i32, i32, vp, vp, vp, vp,
+                              vp, vp, vp]
     lib.cafeq_profile_enable.argtypes = [i32]
     lib.cafeq_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float)]
     for n in EXPORTS[3:]:
@@ -321,3 +323,17 @@ def optimize_pair(A, B, T, bits, group, rep=1, lse_t=5.0, lr=1e-2, steps=10, lam
                                    ctypes.byref(cfg), lse_t, ctypes.byref(opt), _ptr(moments), _ptr(history),
                                    _ptr(status), _ptr(ws), _stream()))
     return Tinv, history[:steps], status
+
+
+def pqe(U, V, codesU, scalesU, codesV, scalesV, bits, group, k, rep=1):
+    """out[2] (device): sum of squared paired quantization errors over heads, and of the squared products."""
+    nb = U.shape[1] // k
+    mu, mv = mat(U), mat(V)
+    x = Xform(0, 0, k, nb, rep)
+    cfg = QuantCfg(bits, group, 0, 0)
+    ws = workspace(int(lib.cafeq_workspace_bytes(9, ctypes.byref(mu), ctypes.byref(mv), ctypes.byref(x),
+                                                 ctypes.byref(cfg))), U.device)
+    out = torch.empty(2, dtype=torch.float32, device=U.device)
+    _check(lib.cafeq_pqe(_ptr(U), _ptr(V), U.shape[0], U.shape[1], V.shape[0], V.shape[1], ctypes.byref(cfg), k, nb,
+                         rep, _ptr(codesU), _ptr(scalesU), _ptr(codesV), _ptr(scalesV), _ptr(out), _ptr(ws), _stream()))
+    return out

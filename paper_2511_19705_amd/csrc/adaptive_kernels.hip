@@ -34,7 +34,7 @@ struct GramArgs {
   int64_t tlen;          // contraction length per row-block (rows of U / columns of V)
   int64_t chunk;         // contraction elements per workgroup (multiple of 16)
   int nchunk;            // chunks per row-block
-  float* partial;        // [nb][rep*nchunk][2][K][K]
+  float* partial;        // [nb][rep*nchunk][2 or 3][K][K]: Gram(Xq,Xq), Gram(Xq,E) and, TRIPLE, Gram(E,E)
 };
 
 // AXIS == COL: t = row i, free index = column;  AXIS == ROW: t = column c, free index = row.
@@ -44,7 +44,7 @@ struct GramArgs {
 // [t][free index], and every wave feeds its MFMAs from there: A = Xq[t][stripe columns] (shared
 // by the waves), B = Xq / E [t][its output tiles].  The next slab's loads are in flight while
 // the matrix cores work on the current one.
-template <int AXIS, int K>
+template <int AXIS, int K, bool TRIPLE>
 __global__ __launch_bounds__(256) void gram_pair_kernel(const GramArgs a) {
   // row stride of the LDS slab: 16-byte aligned rows for the vector stores of the column case;
   // K + 2 for the row case, whose transposing scalar stores then spread over all banks
@@ -61,11 +61,11 @@ __global__ __launch_bounds__(256) void gram_pair_kernel(const GramArgs a) {
   const int64_t f0 = AXIS == CAFEQ_AXIS_COL ? int64_t(b) * K : (int64_t(b) * a.rep + qi) * K;
   const int64_t C = a.cols;
 
-  floatx16 accS[2], accR[2];
+  floatx16 accS[2], accR[2], accT[TRIPLE ? 2 : 1];
 #pragma unroll
   for (int u = 0; u < 2; ++u)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) { accS[u][v] = 0.f; accR[u][v] = 0.f; }
+    for (int v = 0; v < 16; ++v) { accS[u][v] = 0.f; accR[u][v] = 0.f; accT[TRIPLE ? u : 0][v] = 0.f; }
   const int nt2 = wave < KT ? (KT - wave + 3) / 4 : 0;   // output tiles of this wave: jt2 = wave + 4u
 
   // ---- loader roles.  COL: thread -> (t = l / (K/EPT), EPT consecutive columns);
@@ -157,23 +157,26 @@ __global__ __launch_bounds__(256) void gram_pair_kernel(const GramArgs a) {
     if (t + 16 < t1) issue(t + 16);
     if (nt2 > 0) {
       const float* pa = qs + h * LD + jt1 * 32 + ln;
+      const float* pe = es + h * LD + jt1 * 32 + ln;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const float xa = pa[2 * e * LD];
+        const float ea = TRIPLE ? pe[2 * e * LD] : 0.f;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
           if (u < nt2) {
             const int off = (2 * e + h) * LD + (wave + 4 * u) * 32 + ln;
             accS[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa, qs[off], accS[u], 0, 0, 0);
             accR[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa, es[off], accR[u], 0, 0, 0);
+            if (TRIPLE) accT[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(ea, es[off], accT[TRIPLE ? u : 0], 0, 0, 0);
           }
       }
     }
     __syncthreads();
   }
 
-  // partial[b][z][0|1][row][col]
-  float* out = a.partial + ((size_t(b) * gridDim.z + z) * 2) * size_t(K) * K;
+  // partial[b][z][0|1(|2)][row][col]
+  float* out = a.partial + ((size_t(b) * gridDim.z + z) * (TRIPLE ? 3 : 2)) * size_t(K) * K;
 #pragma unroll
   for (int u = 0; u < 2; ++u)
     if (u < nt2) {
@@ -183,8 +186,61 @@ __global__ __launch_bounds__(256) void gram_pair_kernel(const GramArgs a) {
         const int row = jt1 * 32 + 8 * (v / 4) + 4 * h + (v % 4);
         out[size_t(row) * K + col] = accS[u][v];
         out[size_t(K) * K + size_t(row) * K + col] = accR[u][v];
+        if (TRIPLE) out[2 * size_t(K) * K + size_t(row) * K + col] = accT[TRIPLE ? u : 0][v];
       }
     }
+}
+
+// ---- paired quantization error from the Gram triples -------------------------------------------
+// sums[(g)][m][K][K] (float64) = sum over the nchunk chunk partials of group g, m < 3
+__global__ __launch_bounds__(256) void sum_triple_kernel(const float* __restrict__ partial, int nchunk, int K,
+                                                          double* __restrict__ sums) {
+  const int g = blockIdx.x, m = blockIdx.y;
+  const size_t kk = size_t(K) * K;
+  for (size_t e = size_t(blockIdx.z) * 256 + threadIdx.x; e < kk; e += size_t(gridDim.z) * 256) {
+    double acc = 0.0;
+    for (int c = 0; c < nchunk; ++c) acc += double(partial[((size_t(g) * nchunk + c) * 3 + m) * kk + e]);
+    sums[(size_t(g) * 3 + m) * kk + e] = acc;
+  }
+}
+
+// One workgroup per row-block q of V (head b = q / rep).  With SU = Uq^T Uq, RU = Uq^T E_U, TU = E_U^T E_U
+// of head b and SV = Vq Vq^T, RV = Vq E_V^T, TV = E_V E_V^T of row-block q (E = dequantized - original):
+//   Uq Vq - U V = Uq E_V + E_U V, so
+//   ||Uq Vq - U V||_F^2 = tr(SU TV) + 2 tr(RU (RV - TV)) + tr(TU (SV - RV - RV^T + TV)),
+//   ||U V||_F^2         = tr((SU - RU - RU^T + TU)(SV - RV - RV^T + TV));
+// every term of the first line is at the scale of the rounding error (no cancellation).
+__global__ __launch_bounds__(256) void pqe_trace_kernel(const double* __restrict__ su, const double* __restrict__ sv,
+                                                         int K, int rep, double* __restrict__ perq) {
+  __shared__ double red[2][4];
+  const int q = blockIdx.x, b = q / rep;
+  const size_t kk = size_t(K) * K;
+  const double *SU = su + size_t(b) * 3 * kk, *RU = SU + kk, *TU = RU + kk;
+  const double *SV = sv + size_t(q) * 3 * kk, *RV = SV + kk, *TV = RV + kk;
+  double num = 0.0, den = 0.0;
+  for (int e = threadIdx.x; e < K * K; e += 256) {
+    const int i = e / K, j = e % K;
+    const size_t ij = size_t(i) * K + j, ji = size_t(j) * K + i;
+    const double vvt = SV[ji] - RV[ji] - RV[ij] + TV[ji];          // (V V^T)[j][i]
+    const double utu = SU[ij] - RU[ij] - RU[ji] + TU[ij];          // (U^T U)[i][j]
+    num += SU[ij] * TV[ji] + 2.0 * RU[ij] * (RV[ji] - TV[ji]) + TU[ij] * vvt;
+    den += utu * vvt;
+  }
+  for (int m = 1; m < 64; m <<= 1) { num += __shfl_xor(num, m); den += __shfl_xor(den, m); }
+  if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = num; red[1][threadIdx.x >> 6] = den; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    perq[2 * q] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+    perq[2 * q + 1] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+  }
+}
+
+__global__ void pqe_finish_kernel(const double* __restrict__ perq, int nq, float* __restrict__ out) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  double num = 0.0, den = 0.0;
+  for (int q = 0; q < nq; ++q) { num += perq[2 * q]; den += perq[2 * q + 1]; }
+  out[0] = float(num);
+  out[1] = float(den);
 }
 
 // Arguments of the Gauss-Jordan inversion kernel (one workgroup per block).
@@ -537,19 +593,51 @@ int launch_gj(const GjArgs& a, int nb, hipStream_t st) {
 }
 }  // namespace
 
+int launch_gram(int axis, const float* X, const int8_t* codes, const float* scales, int64_t rows, int64_t cols,
+                int K, int G, int nb, int rep, int64_t chunk, int nchunk, bool triple, float* partial, hipStream_t st);
 int launch_gram_pair(int axis, const float* X, const int8_t* codes, const float* scales, int64_t rows,
                      int64_t cols, int K, int G, int nb, int rep, int64_t chunk, int nchunk, float* partial,
                      hipStream_t st) {
+  return launch_gram(axis, X, codes, scales, rows, cols, K, G, nb, rep, chunk, nchunk, false, partial, st);
+}
+// Paired quantization error from Gram triples.  partialU / partialV: 3 k x k matrices per (head, chunk) /
+// (row-block, chunk); sums: 3 * (nb + nb*rep) * k * k doubles + 2 * nb * rep doubles.
+int launch_pqe(const float* U, const float* V, int64_t rowsA, int64_t colsA, int64_t rowsB, int64_t colsB, int K,
+               int GA, int GB, int nb, int rep, const int8_t* codesU, const float* scalesU, const int8_t* codesV,
+               const float* scalesV, int64_t chunkA, int nchunkA, int64_t chunkB, int nchunkB, float* partialU,
+               float* partialV, double* sums, float* out, hipStream_t st) {
+  int rc = launch_gram(CAFEQ_AXIS_COL, U, codesU, scalesU, rowsA, colsA, K, GA, nb, 1, chunkA, nchunkA, true, partialU, st);
+  if (rc) return rc;
+  rc = launch_gram(CAFEQ_AXIS_ROW, V, codesV, scalesV, rowsB, colsB, K, GB, nb, rep, chunkB, nchunkB, true, partialV, st);
+  if (rc) return rc;
+  const size_t kk = size_t(K) * K;
+  double* su = sums;
+  double* sv = sums + size_t(nb) * 3 * kk;
+  double* perq = sv + size_t(nb) * rep * 3 * kk;
+  hipLaunchKernelGGL(sum_triple_kernel, dim3(nb, 3, 16), dim3(256), 0, st, partialU, nchunkA, K, su);
+  hipLaunchKernelGGL(sum_triple_kernel, dim3(nb * rep, 3, 16), dim3(256), 0, st, partialV, nchunkB, K, sv);
+  hipLaunchKernelGGL(pqe_trace_kernel, dim3(nb * rep), dim3(256), 0, st, su, sv, K, rep, perq);
+  hipLaunchKernelGGL(pqe_finish_kernel, dim3(1), dim3(64), 0, st, perq, nb * rep, out);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+int launch_gram(int axis, const float* X, const int8_t* codes, const float* scales, int64_t rows, int64_t cols,
+                int K, int G, int nb, int rep, int64_t chunk, int nchunk, bool triple, float* partial, hipStream_t st) {
   GramArgs a;
   a.X = X; a.codes = codes; a.scales = scales; a.rows = rows; a.cols = cols; a.K = K; a.G = G;
   a.rep = axis == CAFEQ_AXIS_COL ? 1 : rep;
   a.tlen = axis == CAFEQ_AXIS_COL ? rows : cols;
   a.chunk = chunk; a.nchunk = nchunk; a.partial = partial;
   dim3 grid(nb, K / 32, a.rep * nchunk);
-#define CAFEQ_GRAM(KK)                                                                                      \
-  case KK:                                                                                                  \
-    if (axis == CAFEQ_AXIS_COL) hipLaunchKernelGGL((gram_pair_kernel<CAFEQ_AXIS_COL, KK>), grid, dim3(256), 0, st, a); \
-    else hipLaunchKernelGGL((gram_pair_kernel<CAFEQ_AXIS_ROW, KK>), grid, dim3(256), 0, st, a);             \
+#define CAFEQ_GRAM(KK)                                                                                          \
+  case KK:                                                                                                      \
+    if (axis == CAFEQ_AXIS_COL) {                                                                               \
+      if (triple) hipLaunchKernelGGL((gram_pair_kernel<CAFEQ_AXIS_COL, KK, true>), grid, dim3(256), 0, st, a);  \
+      else hipLaunchKernelGGL((gram_pair_kernel<CAFEQ_AXIS_COL, KK, false>), grid, dim3(256), 0, st, a);        \
+    } else {                                                                                                    \
+      if (triple) hipLaunchKernelGGL((gram_pair_kernel<CAFEQ_AXIS_ROW, KK, true>), grid, dim3(256), 0, st, a);  \
+      else hipLaunchKernelGGL((gram_pair_kernel<CAFEQ_AXIS_ROW, KK, false>), grid, dim3(256), 0, st, a);        \
+    }                                                                                                           \
     break;
   switch (K) {
     CAFEQ_GRAM(32) CAFEQ_GRAM(64) CAFEQ_GRAM(128) CAFEQ_GRAM(256)

@@ -277,6 +277,31 @@ const char* cafeq_strerror(int status) {
   }
 }
 
+int cafeq_pqe(const float* U, const float* V, int64_t rowsA, int64_t colsA, int64_t rowsB, int64_t colsB,
+              const cafeq_quant_cfg* cfg, int k, int nb, int rep, const int8_t* codesU, const float* scalesU,
+              const int8_t* codesV, const float* scalesV, float* out, void* ws, void* stream) {
+  int rc = check_cfg(cfg, false);
+  if (rc) return rc;
+  if (!U || !V || !codesU || !scalesU || !codesV || !scalesV || !out) return CAFEQ_ERR_INVALID_ARG;
+  if (!supported_block(k)) return CAFEQ_ERR_UNSUPPORTED;
+  if (nb <= 0 || rep <= 0 || rowsA <= 0 || colsB <= 0) return CAFEQ_ERR_BAD_SHAPE;
+  if (colsA != int64_t(nb) * k || rowsB != int64_t(nb) * rep * k || colsB % 4 != 0) return CAFEQ_ERR_BAD_SHAPE;
+  if (!aligned16(U) || !aligned16(V) || !aligned16(codesU) || !aligned16(codesV) || !aligned16(scalesU) ||
+      !aligned16(scalesV))
+    return CAFEQ_ERR_BAD_ALIGN;
+  if (!ws) return CAFEQ_ERR_WORKSPACE;
+  AdaptivePlan ap;
+  if ((rc = plan_adaptive(cfg, k, nb, rep, rowsA, colsA, rowsB, colsB, &ap))) return rc;
+  const size_t kk = size_t(k) * k;
+  Carver c(ws);
+  float* partialU = c.take<float>(size_t(nb) * ap.nchunkA * 3 * kk);
+  float* partialV = c.take<float>(size_t(nb) * rep * ap.nchunkB * 3 * kk);
+  double* sums = c.take<double>(size_t(nb) * (1 + rep) * 3 * kk + 2 * size_t(nb) * rep);
+  return launch_pqe(U, V, rowsA, colsA, rowsB, colsB, k, ap.GA, ap.GB, nb, rep, codesU, scalesU, codesV, scalesV,
+                    ap.chunkA, ap.nchunkA, ap.chunkB, ap.nchunkB, partialU, partialV, sums, out,
+                    static_cast<hipStream_t>(stream));
+}
+
 int cafeq_version(void) { return 100; }
 
 namespace {
@@ -421,6 +446,17 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
           cafeq_workspace_bytes(CAFEQ_CALL_BLOCK_INVERSE, a, b, x, cfg));
       if (sub == 0) return 0;
       return align_up(size_t(x->nb) * x->k * x->k * sizeof(float), 256) + orth_workspace_bytes(x->k, x->nb) + sub;
+    }
+    case CAFEQ_CALL_PQE: {
+      if (!a || !b || !x || !cfg) return 0;
+      AdaptivePlan ap;
+      if (plan_adaptive(cfg, x->k, x->nb, x->rep, a->rows, a->cols, b->rows, b->cols, &ap)) return 0;
+      const size_t kk = size_t(x->k) * x->k;
+      Carver c(nullptr);
+      c.take<float>(size_t(x->nb) * ap.nchunkA * 3 * kk);
+      c.take<float>(size_t(x->nb) * x->rep * ap.nchunkB * 3 * kk);
+      c.take<double>(size_t(x->nb) * (1 + x->rep) * 3 * kk + 2 * size_t(x->nb) * x->rep);
+      return c.off;
     }
     case CAFEQ_CALL_ADAPTIVE_ROUND: {
       // a: U [rowsA][nb*k], b: V [nb*rep*k][colsB]

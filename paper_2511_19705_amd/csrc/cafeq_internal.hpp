@@ -68,6 +68,10 @@ int launch_gj_solve(int K, int nb, int nz, const float* partial, double* work, f
 int launch_block_inverse(const float* T, int K, int nb, double* work, float* Tinv, float* rho_row,
                          float* rho_col, int* status, hipStream_t st);
 
+int launch_pqe(const float* U, const float* V, int64_t rowsA, int64_t colsA, int64_t rowsB, int64_t colsB, int K,
+               int GA, int GB, int nb, int rep, const int8_t* codesU, const float* scalesU, const int8_t* codesV,
+               const float* scalesV, int64_t chunkA, int nchunkA, int64_t chunkB, int nchunkB, float* partialU,
+               float* partialV, double* sums, float* out, hipStream_t st);
 int launch_fill(float* p, float value, int64_t n, hipStream_t st);
 size_t orth_workspace_bytes(int k, int nb);
 int launch_div_by_device_scalar(float* g, const float* denom, int64_t n, hipStream_t st);

@@ -192,3 +192,32 @@ def test_block_inverse_rejects_other_block_sizes(env):
     T = np.stack([np.eye(48, dtype=np.float32)] * 2)
     with pytest.raises(Exception):
         cafeq.block_inverse(_dev(torch, T))
+
+
+@pytest.mark.parametrize("k,group,rep,bits", [(32, 32, 1, 3), (64, 64, 2, 4), (128, 64, 2, 4), (256, 64, 1, 4)])
+def test_paired_quantization_error_against_the_definition(env, k, group, rep, bits):
+    """cafeq_pqe gets the paired quantization error from k x k Gram matrices; the oracle forms the
+    d1 x d3 products of the definition.  Checked on independently rounded members and again on
+    the codes of one iteration of Alg. 1."""
+    torch, cafeq = env
+    nb = 2
+    U, V = _pair(200 if k <= 128 else 328, 136 if k <= 128 else 296, k, nb, rep, 1200 + k)
+    cu, su, _ = O.rtn_sym(U, bits, group, O.COL)
+    cv, sv, _ = O.rtn_sym(V, bits, group, O.ROW)
+    Uh, Vh = _dequant(cu, su, group, O.COL), _dequant(cv, sv, group, O.ROW)
+    p_abs, p_rel = O.pqe(U, V, Uh, Vh, k, rep)
+    Ud, Vd = _dev(torch, U), _dev(torch, V)
+    dcu, dsu = _dev(torch, cu), _dev(torch, su.astype(np.float32))
+    dcv, dsv = _dev(torch, cv), _dev(torch, sv.astype(np.float32))
+    out = cafeq.pqe(Ud, Vd, dcu, dsu, dcv, dsv, bits, group, k, rep).cpu().numpy().astype(np.float64)
+    parity.check_scalar(out[0], p_abs ** 2, what="pqe_sq")
+    parity.check_scalar(np.sqrt(out[0] / out[1]), p_rel, what="relative pqe")
+    # after one iteration of Alg. 1 (the oracle's): a smaller error made of correlated roundings
+    _, _, Vt, Ut = O.adaptive_round_step(U, V, Uh, bits, group, k, rep, half=0)
+    cv1, sv1, _ = O.rtn_sym(Vt, bits, group, O.ROW)
+    cu1, su1, _ = O.rtn_sym(Ut, bits, group, O.COL)
+    p1_abs, _ = O.pqe(U, V, _dequant(cu1, su1, group, O.COL), _dequant(cv1, sv1, group, O.ROW), k, rep)
+    out1 = cafeq.pqe(Ud, Vd, _dev(torch, cu1), _dev(torch, su1.astype(np.float32)), _dev(torch, cv1),
+                     _dev(torch, sv1.astype(np.float32)), bits, group, k, rep).cpu().numpy().astype(np.float64)
+    parity.check_scalar(out1[0], p1_abs ** 2, what="pqe_sq after Alg. 1")
+    assert p1_abs < p_abs and out1[0] < out[0]

@@ -90,6 +90,25 @@ def test_config4_transform_and_adaptive_step_full_size(env):
     parity.check_codes(dcu2.cpu().numpy(), cu_ref, Ut, su_ref, O.COL, group)
 
 
+def test_config4_paired_quantization_error_full_size(env):
+    """PQE of the independently rounded attention pair: Gram-trace evaluation on the device against
+    the oracle's d1 x d3 products."""
+    torch, cafeq = env
+    c = WL.config4()
+    A, B, T, k, rep, group, bits = c["A"], c["B"], c["T"], c["k"], c["rep"], c["group"], c["bits"][0]
+    P = O.block_inverse(T)
+    U = O.blockdiag_apply(A, T, O.COL).astype(np.float32)
+    V = O.blockdiag_apply(B, P, O.ROW, rep).astype(np.float32)
+    cu, su, _ = O.rtn_sym(U, bits, group, O.COL)
+    cv, sv, _ = O.rtn_sym(V, bits, group, O.ROW)
+    p_abs, p_rel = O.pqe(U, V, _dequant(cu, su, group, O.COL), _dequant(cv, sv, group, O.ROW), k, rep)
+    out = cafeq.pqe(_dev(torch, U), _dev(torch, V), _dev(torch, cu), _dev(torch, su.astype(np.float32)),
+                    _dev(torch, cv), _dev(torch, sv.astype(np.float32)), bits, group, k, rep)
+    out = out.cpu().numpy().astype(np.float64)
+    parity.check_scalar(out[0], p_abs ** 2, what="pqe_sq")
+    parity.check_scalar(np.sqrt(out[0] / out[1]), p_rel, what="relative pqe")
+
+
 def test_config4_dual_forward_full_size(env):
     """The pair's losses at k = 256 (forward only: the gradient is not available for k = 256)."""
     torch, cafeq = env
