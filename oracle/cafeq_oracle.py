@@ -133,24 +133,36 @@ def rtn_sym(Z, bits, group, axis, arith="f32"):
             _from_groups(zhat.astype(np.float64), shape, axis, group))
 
 
-def rtn_asym(Z, bits, group, axis):
+def rtn_asym(Z, bits, group, axis, arith="f64"):
     """Eq. (1): s = (max - min)/(2^b - 1), q = nearest_int((z - min)/s) in
     [0, 2^b - 1], zhat = s*q + min; a constant group gives q = 0, zhat = min.
-    float64 throughout.  Returns (codes, scales, zeros(min), zhat)."""
+    ``arith="f64"`` evaluates exactly that in float64.  ``arith="f32"`` is the
+    single-precision realisation both sides agree on for deciding the integer (same pattern as
+    ``rtn_sym``): z rounded to float32, r = fl(max - min), inv = min(fl((2^b-1) / r), FLT_MAX),
+    q = nearest_int(fl(fl(z - min) * inv)), s = fl(r / (2^b-1)), zhat = fl(fl(q * s) + min).
+    Returns (codes, scales, zeros(min), zhat)."""
     levels = 2 ** bits - 1
-    Zg = _to_groups(np.asarray(Z, dtype=np.float64), axis, group)
+    ft = np.float32 if arith == "f32" else np.float64
+    Zg = _to_groups(np.asarray(Z, dtype=np.float64), axis, group).astype(ft)
     lo = Zg.min(axis=1)
     hi = Zg.max(axis=1)
-    s = (hi - lo) / levels
-    safe = np.where(s > 0, s, 1.0)
-    q = np.clip(np.rint((Zg - lo[:, None]) / safe[:, None]), 0, levels)
-    q = np.where((s > 0)[:, None], q, 0.0)
-    zhat = s[:, None] * q + lo[:, None]
+    rng = (hi - lo).astype(ft)
+    s = (rng / ft(levels)).astype(ft)
+    safe = np.where(rng > 0, rng, ft(1))
+    if arith == "f32":
+        with np.errstate(over="ignore"):
+            inv = np.minimum((ft(levels) / safe).astype(ft), np.finfo(np.float32).max)
+        x = ((Zg - lo[:, None]).astype(ft) * inv[:, None]).astype(ft)
+    else:
+        x = (Zg - lo[:, None]) / (safe / levels)[:, None]
+    q = np.clip(np.rint(x), 0, levels)
+    q = np.where((rng > 0)[:, None], q, 0.0)
+    zhat = ((q.astype(ft) * s[:, None]).astype(ft) + lo[:, None]).astype(ft)
     shape = np.shape(Z)
     return (_from_groups(q, shape, axis, group).astype(np.int16),
             _group_values_layout(s, shape, axis, group),
             _group_values_layout(lo, shape, axis, group),
-            _from_groups(zhat, shape, axis, group))
+            _from_groups(zhat.astype(np.float64), shape, axis, group))
 
 
 def quantize(Z, bits, group, axis, mode=SYM, arith="f32"):

@@ -109,6 +109,30 @@ def test_asym_error_bound_eq2(bits):
         assert codes.min() >= 0 and codes.max() <= 2 ** bits - 1
 
 
+def test_asym_f32_recipe_differs_from_exact_only_at_ties():
+    Z = _rand((256, 512), 13)
+    c64, s64, lo64, z64 = O.rtn_asym(Z, 4, 128, O.COL, "f64")
+    c32, s32, lo32, z32 = O.rtn_asym(Z, 4, 128, O.COL, "f32")
+    np.testing.assert_array_equal(lo32, lo64)                      # min / max are exact in float32
+    np.testing.assert_allclose(s32, s64, rtol=2e-7)
+    diff = c64 != c32
+    assert diff.mean() <= 1e-4
+    if diff.any():
+        assert np.abs(c64.astype(int) - c32.astype(int))[diff].max() == 1
+        s_el = np.repeat(s64, 128, axis=1)
+        l_el = np.repeat(lo64, 128, axis=1)
+        frac = (Z.astype(np.float64)[diff] - l_el[diff]) / s_el[diff]
+        assert np.all(np.abs(frac - np.floor(frac) - 0.5) < 1e-4)
+    # the dequantized value obeys Eq. (2)'s bound up to float32 rounding
+    rng_ = np.repeat(15.0 * s64, 128, axis=1)
+    assert np.all(np.abs(z32 - Z) <= rng_ / 30.0 * (1 + 1e-5) + 1e-9)
+    # a constant group: code 0, value reproduced exactly
+    C = np.full((4, 128), 0.37, dtype=np.float32)
+    c, s_, lo_, zq = O.rtn_asym(C, 3, 128, O.COL, "f32")
+    assert c.max() == 0 and float(s_.max()) == 0.0
+    np.testing.assert_array_equal(zq, C.astype(np.float64))
+
+
 def _read_gold(name):
     out = {}
     for line in open(os.path.join(GOLD, name)):
