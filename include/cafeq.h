@@ -127,6 +127,17 @@ int cafeq_block_inverse(const float* T, int k, int nb, float* Tinv, float* rho_r
 int cafeq_rtn_quantize(const cafeq_mat* W, const cafeq_quant_cfg* cfg, int8_t* codes,
                        float* scales, float* err_sq, void* ws, void* stream);
 
+/* The uniform min/max quantizer exactly as the paper's Eq. (1) states it, per group:
+ *   s = (max - min) / (2^b - 1),  q = nearest_int((w - min) / s) in [0, 2^b - 1],  w^ = s q + min.
+ * Single-precision recipe: r = fl(max - min), inv = min(fl((2^b-1) / r), FLT_MAX) (0 for a constant
+ * group, whose codes are 0), q = clamp(rint(fl(fl(w - min) * inv))), s = fl(r / (2^b-1)),
+ * w^ = fl(fl(q s) + min); ties to even.  codes: unsigned bytes [rows][cols]; scales and mins
+ * (either may be NULL) in the layout of cafeq_rtn_quantize's scales; err_sq as there.
+ * bits in [1, 8]; cfg->mode is ignored; any group length dividing the line, 0 = the whole line
+ * (the per-channel setting of the paper's experiments). */
+int cafeq_rtn_quantize_minmax(const cafeq_mat* W, const cafeq_quant_cfg* cfg, uint8_t* codes,
+                              float* scales, float* mins, float* err_sq, void* ws, void* stream);
+
 /* Z = W.blockdiag(X) or blockdiag(X).W with X = T (CAFEQ_SIDE_T) or Tinv
  * (CAFEQ_SIDE_TINV)  (paper Sec. 4.1 block-diagonal M; Sec. 4.2 U = W1 M, V = M^-1 W2).
  * Z: float32 [rows][cols] dense, must not alias W. */

@@ -24,7 +24,8 @@ EXPORTS = (
     "cafeq_rtn_quantize", "cafeq_apply_transform", "cafeq_proxy_loss_fwd_bwd",
     "cafeq_dual_proxy_loss_fwd_bwd", "cafeq_adaptive_round_step",
     "cafeq_orth_penalty", "cafeq_sgd_update", "cafeq_adam_update", "cafeq_optimize_single",
-    "cafeq_optimize_pair", "cafeq_pqe", "cafeq_profile_enable", "cafeq_profile_read",
+    "cafeq_optimize_pair", "cafeq_pqe", "cafeq_rtn_quantize_minmax", "cafeq_profile_enable",
+    "cafeq_profile_read",
 )
 
 
@@ -86,6 +87,7 @@ def _load():
                                           ctypes.POINTER(OptCfg), vp, vp, vp, vp]
     lib.cafeq_optimize_pair.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Mat), vp, vp, i32, i32, i32,
                                         ctypes.POINTER(QuantCfg), f32, ctypes.POINTER(OptCfg), vp, vp, vp, vp, vp]
+    lib.cafeq_rtn_quantize_minmax.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(QuantCfg), vp, vp, vp, vp, vp, vp]
     lib.cafeq_pqe.argtypes = [vp, vp, i64, i64, i64, i64, ctypes.POINTER(QuantCfg), i32, i32, i32, vp, vp, vp, vp,
                               vp, vp, vp]
     lib.cafeq_profile_enable.argtypes = [i32]
@@ -337,3 +339,19 @@ def pqe(U, V, codesU, scalesU, codesV, scalesV, bits, group, k, rep=1):
     _check(lib.cafeq_pqe(_ptr(U), _ptr(V), U.shape[0], U.shape[1], V.shape[0], V.shape[1], ctypes.byref(cfg), k, nb,
                          rep, _ptr(codesU), _ptr(scalesU), _ptr(codesV), _ptr(scalesV), _ptr(out), _ptr(ws), _stream()))
     return out
+
+
+def rtn_quantize_minmax(W, bits, group, axis=AXIS_COL, want_err=False):
+    """Eq. (1) grid: (codes uint8, scales, mins, err or None)."""
+    m = mat(W)
+    cfg = QuantCfg(bits, group, axis, 1)
+    R, C = W.shape
+    codes = torch.empty((R, C), dtype=torch.uint8, device=W.device)
+    shape = _scale_shape(R, C, group, axis)
+    scales = torch.empty(shape, dtype=torch.float32, device=W.device)
+    mins = torch.empty(shape, dtype=torch.float32, device=W.device)
+    err = torch.empty(1, dtype=torch.float32, device=W.device) if want_err else None
+    ws = workspace(workspace_bytes(CALL_RTN, m, cfg=cfg), W.device) if want_err else None
+    _check(lib.cafeq_rtn_quantize_minmax(ctypes.byref(m), ctypes.byref(cfg), _ptr(codes), _ptr(scales), _ptr(mins),
+                                         _ptr(err), _ptr(ws), _stream()))
+    return codes, scales, mins, err

@@ -485,10 +485,31 @@ int cafeq_rtn_quantize(const cafeq_mat* W, const cafeq_quant_cfg* cfg, int8_t* c
   RtnArgs a;
   a.W = W->data; a.dtype = W->dtype; a.rows = W->rows; a.cols = W->cols; a.ld = W->ld;
   a.axis = cfg->axis; a.group = cfg->group; a.grid = make_grid(cfg->bits);
-  a.codes = codes; a.scales = scales;
+  a.codes = codes; a.scales = scales; a.mins = nullptr;
   a.partial = err_sq ? static_cast<double*>(ws) : nullptr;
   a.err_sq = err_sq;
   return launch_rtn(a, static_cast<hipStream_t>(stream));
+}
+
+int cafeq_rtn_quantize_minmax(const cafeq_mat* W, const cafeq_quant_cfg* cfg, uint8_t* codes, float* scales,
+                              float* mins, float* err_sq, void* ws, void* stream) {
+  int rc = check_mat(W);
+  if (rc) return rc;
+  if (!cfg || cfg->bits < 1 || cfg->bits > 8 || cfg->group < 0) return CAFEQ_ERR_INVALID_ARG;
+  if (cfg->axis != CAFEQ_AXIS_COL && cfg->axis != CAFEQ_AXIS_ROW) return CAFEQ_ERR_INVALID_ARG;
+  if (!codes) return CAFEQ_ERR_INVALID_ARG;
+  if (!aligned16(codes) || (scales && !aligned16(scales)) || (mins && !aligned16(mins))) return CAFEQ_ERR_BAD_ALIGN;
+  const int64_t line = cfg->axis == CAFEQ_AXIS_COL ? W->cols : W->rows;
+  const int64_t g = cfg->group == 0 ? line : cfg->group;
+  if (line % g != 0) return CAFEQ_ERR_BAD_SHAPE;
+  if (err_sq && !ws) return CAFEQ_ERR_WORKSPACE;
+  RtnArgs a;
+  a.W = W->data; a.dtype = W->dtype; a.rows = W->rows; a.cols = W->cols; a.ld = W->ld;
+  a.axis = cfg->axis; a.group = cfg->group; a.grid = make_grid(2);
+  a.codes = reinterpret_cast<int8_t*>(codes); a.scales = scales; a.mins = mins;
+  a.partial = err_sq ? static_cast<double*>(ws) : nullptr;
+  a.err_sq = err_sq;
+  return launch_rtn_minmax(a, cfg->bits, static_cast<hipStream_t>(stream));
 }
 
 int cafeq_block_inverse(const float* T, int k, int nb, float* Tinv, float* rho_row, float* rho_col,

@@ -15,10 +15,12 @@ struct RtnArgs {
   QGrid grid;
   int8_t* codes;
   float* scales;   // may be null
+  float* mins;     // min/max grid only: per-group minimum, may be null
   double* partial; // workspace for per-workgroup squared-error partials; null = no error output
   float* err_sq;
 };
 size_t rtn_partials_capacity(int64_t rows, int64_t cols);
+int launch_rtn_minmax(const RtnArgs& a, int bits, hipStream_t st);
 int launch_rtn(const RtnArgs& a, hipStream_t st);
 
 

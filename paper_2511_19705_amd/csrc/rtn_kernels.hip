@@ -196,6 +196,138 @@ __global__ __launch_bounds__(256) void rtn_row_any(
   if (partial) block_store_partial(err, partial);
 }
 
+// ---- the min/max grid of the paper's Eq. (1) ------------------------------------------------
+// Single-precision recipe: r = fl(max - min), inv = min(fl(levels / r), FLT_MAX) (0 for a
+// constant group), q = clamp(rint(fl(fl(z - min) * inv)), 0, levels), s = fl(r / levels),
+// dequantized value fl(fl(q * s) + min); levels = 2^b - 1.
+struct MinMaxGrid { float levels; };
+__device__ __forceinline__ float mm_inv(float r, float levels) {
+  return r > 0.f ? fminf(__fdiv_rn(levels, r), FLT_MAX) : 0.f;
+}
+__device__ __forceinline__ float mm_code(float z, float lo, float inv, float levels) {
+  const float q = __builtin_rintf(__fmul_rn(__fsub_rn(z, lo), inv));
+  return fminf(fmaxf(q, 0.f), levels);
+}
+
+// groups along the contiguous axis, g = 4 * LPG <= 256 (same lane ownership as rtn_col_fast)
+template <typename Tag, int LPG, bool DENSE>
+__global__ __launch_bounds__(kColThreads) void rtn_col_minmax_fast(
+    const typename Tag::elem* __restrict__ W, uint32_t nvec, uint32_t cols4, int64_t ld, float levels,
+    uint32_t* __restrict__ codes, float* __restrict__ scales, float* __restrict__ mins,
+    double* __restrict__ partial) {
+  const uint32_t base = blockIdx.x * (kColThreads * kColUnroll) + threadIdx.x;
+  float err = 0.f;
+#pragma unroll
+  for (int j = 0; j < kColUnroll; ++j) {
+    const uint32_t v = base + j * kColThreads;
+    const bool live = v < nvec;
+    float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (live) {
+      size_t off;
+      if constexpr (DENSE) {
+        off = size_t(v) * 4;
+      } else {
+        const uint32_t r = v / cols4;
+        off = size_t(r) * ld + size_t(v - r * cols4) * 4;
+      }
+      x = load4(W + off);
+    }
+    float hi = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
+    float nlo = fmaxf(fmaxf(-x.x, -x.y), fmaxf(-x.z, -x.w));     // -min, so that one reduction serves both
+    hi = cluster_allmax<LPG>(hi);
+    nlo = cluster_allmax<LPG>(nlo);
+    const float lo = -nlo, r = __fsub_rn(hi, lo);
+    const float inv = mm_inv(r, levels), s = __fdiv_rn(r, levels);
+    const float q0 = mm_code(x.x, lo, inv, levels), q1 = mm_code(x.y, lo, inv, levels);
+    const float q2 = mm_code(x.z, lo, inv, levels), q3 = mm_code(x.w, lo, inv, levels);
+    if (live) {
+      codes[v] = uint32_t(q0) | (uint32_t(q1) << 8) | (uint32_t(q2) << 16) | (uint32_t(q3) << 24);
+      if ((threadIdx.x % LPG) == 0) {
+        if (scales) scales[v / LPG] = s;
+        if (mins) mins[v / LPG] = lo;
+      }
+      if (partial) {
+        const float e0 = __fadd_rn(__fmul_rn(q0, s), lo) - x.x, e1 = __fadd_rn(__fmul_rn(q1, s), lo) - x.y;
+        const float e2 = __fadd_rn(__fmul_rn(q2, s), lo) - x.z, e3 = __fadd_rn(__fmul_rn(q3, s), lo) - x.w;
+        err += e0 * e0 + e1 * e1 + e2 * e2 + e3 * e3;
+      }
+    }
+  }
+  if (partial) block_store_partial(err, partial);
+}
+
+// One wave per group along the contiguous axis, any group length (whole channels included).
+template <typename Tag>
+__global__ __launch_bounds__(256) void rtn_col_minmax_any(
+    const typename Tag::elem* __restrict__ W, int64_t rows, int64_t cols, int64_t ld, int64_t g, float levels,
+    uint8_t* __restrict__ codes, float* __restrict__ scales, float* __restrict__ mins,
+    double* __restrict__ partial) {
+  const int lane = threadIdx.x % kWave;
+  const int64_t gpr = cols / g, ngroups = rows * gpr;
+  const int64_t wave0 = int64_t(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int64_t wstride = int64_t(gridDim.x) * (blockDim.x / kWave);
+  float err = 0.f;
+  for (int64_t gi = wave0; gi < ngroups; gi += wstride) {
+    const int64_t r = gi / gpr, c0 = (gi - r * gpr) * g;
+    const typename Tag::elem* src = W + r * ld + c0;
+    float hi = -FLT_MAX, nlo = -FLT_MAX;
+    for (int64_t i = lane; i < g; i += kWave) {
+      const float z = load1(src + i);
+      hi = fmaxf(hi, z);
+      nlo = fmaxf(nlo, -z);
+    }
+    hi = cluster_allmax<64>(hi);
+    nlo = cluster_allmax<64>(nlo);
+    const float lo = -nlo, rg = __fsub_rn(hi, lo);
+    const float inv = mm_inv(rg, levels), s = __fdiv_rn(rg, levels);
+    if (lane == 0) {
+      if (scales) scales[gi] = s;
+      if (mins) mins[gi] = lo;
+    }
+    for (int64_t i = lane; i < g; i += kWave) {
+      const float z = load1(src + i);
+      const float q = mm_code(z, lo, inv, levels);
+      codes[r * cols + c0 + i] = uint8_t(int(q));
+      const float e = __fadd_rn(__fmul_rn(q, s), lo) - z;
+      err += e * e;
+    }
+  }
+  if (partial) block_store_partial(err, partial);
+}
+
+// One thread per (group, column): groups along the strided axis, any group length.
+template <typename Tag>
+__global__ __launch_bounds__(256) void rtn_row_minmax_any(
+    const typename Tag::elem* __restrict__ W, int64_t rows, int64_t cols, int64_t ld, int64_t g, float levels,
+    uint8_t* __restrict__ codes, float* __restrict__ scales, float* __restrict__ mins,
+    double* __restrict__ partial) {
+  const int64_t total = (rows / g) * cols;
+  float err = 0.f;
+  for (int64_t id = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; id < total;
+       id += int64_t(gridDim.x) * blockDim.x) {
+    const int64_t gr = id / cols, c = id - gr * cols;
+    const typename Tag::elem* src = W + gr * g * ld + c;
+    float hi = -FLT_MAX, lo = FLT_MAX;
+    for (int64_t i = 0; i < g; ++i) {
+      const float z = load1(src + i * ld);
+      hi = fmaxf(hi, z);
+      lo = fminf(lo, z);
+    }
+    const float rg = __fsub_rn(hi, lo);
+    const float inv = mm_inv(rg, levels), s = __fdiv_rn(rg, levels);
+    if (scales) scales[id] = s;
+    if (mins) mins[id] = lo;
+    for (int64_t i = 0; i < g; ++i) {
+      const float z = load1(src + i * ld);
+      const float q = mm_code(z, lo, inv, levels);
+      codes[(gr * g + i) * cols + c] = uint8_t(int(q));
+      const float e = __fadd_rn(__fmul_rn(q, s), lo) - z;
+      err += e * e;
+    }
+  }
+  if (partial) block_store_partial(err, partial);
+}
+
 __global__ __launch_bounds__(256) void sum_partials_kernel(const double* __restrict__ partial, int n,
                                                             float* __restrict__ out) {
   __shared__ double red[256];
@@ -281,7 +413,70 @@ int launch_rtn_typed(const RtnArgs& a, hipStream_t st, int* nparts) {
   return CAFEQ_OK;
 }
 
+template <typename Tag, int LPG>
+void launch_col_minmax_fast(const RtnArgs& a, float levels, uint32_t nblk, hipStream_t st) {
+  using E = typename Tag::elem;
+  const uint32_t nvec = uint32_t(a.rows * a.cols / 4), cols4 = uint32_t(a.cols / 4);
+  if (a.ld == a.cols)
+    hipLaunchKernelGGL((rtn_col_minmax_fast<Tag, LPG, true>), dim3(nblk), dim3(kColThreads), 0, st, (const E*)a.W,
+                       nvec, cols4, a.ld, levels, (uint32_t*)a.codes, a.scales, a.mins, a.partial);
+  else
+    hipLaunchKernelGGL((rtn_col_minmax_fast<Tag, LPG, false>), dim3(nblk), dim3(kColThreads), 0, st, (const E*)a.W,
+                       nvec, cols4, a.ld, levels, (uint32_t*)a.codes, a.scales, a.mins, a.partial);
+}
+
+template <typename Tag>
+int launch_minmax_typed(const RtnArgs& a, float levels, hipStream_t st, int* nparts) {
+  using E = typename Tag::elem;
+  const int64_t line = a.axis == CAFEQ_AXIS_COL ? a.cols : a.rows;
+  const int64_t g = a.group == 0 ? line : a.group;
+  if (a.axis == CAFEQ_AXIS_COL) {
+    const bool pow2 = (g & (g - 1)) == 0;
+    if (pow2 && g >= 4 && g <= 256 && a.rows * a.cols / 4 < (int64_t(1) << 31)) {
+      const int64_t nvec = a.rows * a.cols / 4;
+      const uint32_t nblk = uint32_t((nvec + kColThreads * kColUnroll - 1) / (kColThreads * kColUnroll));
+      *nparts = int(nblk);
+      switch (g / 4) {
+        case 1: launch_col_minmax_fast<Tag, 1>(a, levels, nblk, st); break;
+        case 2: launch_col_minmax_fast<Tag, 2>(a, levels, nblk, st); break;
+        case 4: launch_col_minmax_fast<Tag, 4>(a, levels, nblk, st); break;
+        case 8: launch_col_minmax_fast<Tag, 8>(a, levels, nblk, st); break;
+        case 16: launch_col_minmax_fast<Tag, 16>(a, levels, nblk, st); break;
+        case 32: launch_col_minmax_fast<Tag, 32>(a, levels, nblk, st); break;
+        default: launch_col_minmax_fast<Tag, 64>(a, levels, nblk, st); break;
+      }
+    } else {
+      const int64_t ngroups = a.rows * (a.cols / g);
+      const int nblk = int(std::min<int64_t>((ngroups + 3) / 4, 4096));
+      *nparts = nblk;
+      hipLaunchKernelGGL((rtn_col_minmax_any<Tag>), dim3(nblk), dim3(256), 0, st, (const E*)a.W, a.rows, a.cols,
+                         a.ld, g, levels, (uint8_t*)a.codes, a.scales, a.mins, a.partial);
+    }
+  } else {
+    const int64_t total = (a.rows / g) * a.cols;
+    const int nblk = int(std::min<int64_t>((total + 255) / 256, 4096));
+    *nparts = nblk;
+    hipLaunchKernelGGL((rtn_row_minmax_any<Tag>), dim3(nblk), dim3(256), 0, st, (const E*)a.W, a.rows, a.cols,
+                       a.ld, g, levels, (uint8_t*)a.codes, a.scales, a.mins, a.partial);
+  }
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+
 }  // namespace
+
+int launch_rtn_minmax(const RtnArgs& a, int bits, hipStream_t st) {
+  int nparts = 0;
+  const float levels = float((1 << bits) - 1);
+  int rc = a.dtype == CAFEQ_BF16 ? launch_minmax_typed<BF16Tag>(a, levels, st, &nparts)
+                                 : launch_minmax_typed<F32Tag>(a, levels, st, &nparts);
+  if (rc != CAFEQ_OK) return rc;
+  if (a.partial) {
+    hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(256), 0, st, a.partial, nparts, a.err_sq);
+    CAFEQ_CHECK_LAUNCH();
+  }
+  return CAFEQ_OK;
+}
 
 size_t rtn_partials_capacity(int64_t rows, int64_t cols) {
   // upper bound on the number of workgroups any of the four kernels launches

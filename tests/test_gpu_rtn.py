@@ -91,3 +91,48 @@ def test_argument_errors(env):
         cafeq.rtn_quantize(W, 4, 48, O.COL)            # 64 % 48 != 0
     with pytest.raises(cafeq.CafeqError):
         cafeq.rtn_quantize(W, 9, 32, O.COL)            # bits out of range
+
+
+# ---- the min/max grid of Eq. (1) ------------------------------------------------------------
+def _run_minmax(env, W_np, bits, group, axis, bf16=False):
+    torch, cafeq = env
+    dev = torch.device("cuda:0")
+    if bf16:
+        bits16 = WL.to_bf16_bits(W_np)
+        W_ref = WL.bf16_bits_to_f32(bits16)
+        Wd = torch.from_numpy(bits16.view(np.int16)).to(dev).view(torch.bfloat16)
+    else:
+        W_ref = W_np
+        Wd = torch.from_numpy(W_np).to(dev)
+    codes, scales, mins, err = cafeq.rtn_quantize_minmax(Wd, bits, group, axis, want_err=True)
+    torch.cuda.synchronize()
+    c_ref, s_ref, lo_ref, zh = O.rtn_asym(W_ref, bits, group, axis, "f32")
+    np.testing.assert_array_equal(codes.cpu().numpy().astype(np.int16), c_ref)
+    np.testing.assert_array_equal(scales.cpu().numpy(), s_ref.astype(np.float32))
+    np.testing.assert_array_equal(mins.cpu().numpy(), lo_ref.astype(np.float32))
+    ref = float(((zh - W_ref.astype(np.float64)) ** 2).sum())
+    assert abs(float(err.item()) - ref) <= 1e-5 * ref + 1e-30
+
+
+@pytest.mark.parametrize("bits", [1, 3, 4, 8])
+@pytest.mark.parametrize("group", [4, 64, 256, 0, 96])
+def test_minmax_col_groups(env, bits, group):
+    W = WL.student_t3((37, 768), 930 + bits)
+    WL.scale_random_columns(W, 2, 10.0, 6)
+    W[5, :96] = 0.25                                   # a constant group (and part of larger ones)
+    _run_minmax(env, W, bits, group, O.COL)
+
+
+@pytest.mark.parametrize("bits,group", [(4, 64), (3, 0), (4, 48)])
+def test_minmax_row_groups_and_bf16(env, bits, group):
+    W = WL.student_t3((768, 332), 940 + bits)
+    _run_minmax(env, W, bits, group, O.ROW)
+    _run_minmax(env, np.ascontiguousarray(W.T[:64]), bits, 128 if group else 0, O.COL, bf16=True)
+
+
+def test_minmax_per_channel_on_the_2b_shaped_matrix(env):
+    """Per-channel Eq. (1) (one group per output channel, the setting of the paper's tables) at the
+    size of configuration 2, bit-exact."""
+    c2 = WL.config2()
+    _run_minmax(env, c2["W"], 4, 0, O.COL)
+    _run_minmax(env, c2["W"], 4, 256, O.COL)
