@@ -217,65 +217,72 @@ struct LossArgs {
   float* losses;
   double* lse_ms;                    // out: [m*, S]
 };
-__device__ double block_sum(double v, double* red) {
-  red[threadIdx.x] = v;
-  __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+constexpr int kLossThreads = 256;
+__global__ __launch_bounds__(kLossThreads) void reduce_losses_kernel(const LossArgs a) {
+  __shared__ double red[5 * (kLossThreads / 64)];
+  // four sums and one maximum over the workgroup, fixed order
+  auto reduce5 = [&](double& v0, double& v1, double& v2, double& v3, double& vmax) {
+    for (int k = 1; k < 64; k <<= 1) {
+      v0 += __shfl_xor(v0, k); v1 += __shfl_xor(v1, k); v2 += __shfl_xor(v2, k); v3 += __shfl_xor(v3, k);
+      vmax = fmax(vmax, __shfl_xor(vmax, k));
+    }
+    constexpr int NW = kLossThreads / 64;
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) {
+      red[w] = v0; red[NW + w] = v1; red[2 * NW + w] = v2; red[3 * NW + w] = v3; red[4 * NW + w] = vmax;
+    }
     __syncthreads();
-  }
-  const double r = red[0];
-  __syncthreads();
-  return r;
-}
-__device__ double block_max(double v, double* red) {
-  red[threadIdx.x] = v;
-  __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if (threadIdx.x < s) red[threadIdx.x] = fmax(red[threadIdx.x], red[threadIdx.x + s]);
+    v0 = v1 = v2 = v3 = 0;
+    vmax = -INFINITY;
+    for (int k = 0; k < NW; ++k) {
+      v0 += red[k]; v1 += red[NW + k]; v2 += red[2 * NW + k]; v3 += red[3 * NW + k];
+      vmax = fmax(vmax, red[4 * NW + k]);
+    }
     __syncthreads();
-  }
-  const double r = red[0];
-  __syncthreads();
-  return r;
-}
-__device__ double hdr_sum(const float* hdr, int n, int field, double* red) {
-  double t = 0;
-  for (int i = threadIdx.x; i < n; i += 256) t += hdr[size_t(i) * kHdrFloats + field];
-  return block_sum(t, red);
-}
-__global__ __launch_bounds__(256) void reduce_losses_kernel(const LossArgs a) {
-  __shared__ double red[256];
+  };
   if (a.kind == kLossSur) {
-    const double l2 = hdr_sum(a.hdrA, a.nslotA, kHdrL2, red);
-    const double ez = hdr_sum(a.hdrA, a.nslotA, kHdrErrZ, red);
-    const double ws = hdr_sum(a.hdrA, a.nslotA, kHdrWsq, red);
-    const double su = hdr_sum(a.hdrA, a.nslotA, kHdrSur, red);
+    double l2 = 0, ez = 0, ws = 0, su = 0, dummy = 0;
+    for (int i = threadIdx.x; i < a.nslotA; i += kLossThreads) {
+      const float* h = a.hdrA + size_t(i) * kHdrFloats;
+      l2 += h[kHdrL2]; ez += h[kHdrErrZ]; ws += h[kHdrWsq]; su += h[kHdrSur];
+    }
+    reduce5(l2, ez, ws, su, dummy);
     if (threadIdx.x == 0) {
       a.losses[0] = float(l2); a.losses[1] = float(ez); a.losses[2] = float(ws);
       a.losses[3] = float(su * a.beta);
     }
     return;
   }
-  const double ezA = hdr_sum(a.hdrA, a.nslotA, kHdrErrZ, red);
-  const double ezB = hdr_sum(a.hdrB, a.nslotB, kHdrErrZ, red);
-  const double l2A = hdr_sum(a.hdrA, a.nslotA, kHdrL2, red);
-  const double l2B = hdr_sum(a.hdrB, a.nslotB, kHdrL2, red);
-  // global reference and normaliser of the exponentials
-  double m = -INFINITY;
-  for (int i = threadIdx.x; i < a.nslotA; i += 256) m = fmax(m, double(a.hdrA[size_t(i) * kHdrFloats + kHdrMref]));
-  for (int i = threadIdx.x; i < a.nslotB; i += 256) m = fmax(m, double(a.hdrB[size_t(i) * kHdrFloats + kHdrMref]));
-  m = block_max(m, red);
+  // one pass over both members' headers: four sums and the largest reference; each thread keeps
+  // its slots' (sum of exponentials, reference) pairs for the second step
+  constexpr int kMaxPer = 8;                       // slots per thread held in registers
+  const int ntot = a.nslotA + a.nslotB;
+  double ezA = 0, ezB = 0, l2A = 0, l2B = 0, m = -INFINITY;
+  float sur[kMaxPer], mref[kMaxPer];
+  int cnt = 0;
+  for (int i = threadIdx.x; i < ntot; i += kLossThreads, ++cnt) {
+    const bool isA = i < a.nslotA;
+    const float* h = isA ? a.hdrA + size_t(i) * kHdrFloats : a.hdrB + size_t(i - a.nslotA) * kHdrFloats;
+    const float ez = h[kHdrErrZ], l2 = h[kHdrL2], su = h[kHdrSur], mr = h[kHdrMref];
+    if (isA) { ezA += ez; l2A += l2; } else { ezB += ez; l2B += l2; }
+    m = fmax(m, double(mr));
+    if (cnt < kMaxPer) { sur[cnt] = su; mref[cnt] = mr; }
+  }
+  reduce5(ezA, ezB, l2A, l2B, m);
+  // global normaliser of the exponentials
   double s = 0;
-  for (int i = threadIdx.x; i < a.nslotA; i += 256) {
-    const float* h = a.hdrA + size_t(i) * kHdrFloats;
-    if (h[kHdrSur] > 0.f) s += double(h[kHdrSur]) * exp(double(a.t) * (double(h[kHdrMref]) - m));
+  cnt = 0;
+  for (int i = threadIdx.x; i < ntot; i += kLossThreads, ++cnt) {
+    float su, mr;
+    if (cnt < kMaxPer) { su = sur[cnt]; mr = mref[cnt]; }
+    else {
+      const float* h = i < a.nslotA ? a.hdrA + size_t(i) * kHdrFloats : a.hdrB + size_t(i - a.nslotA) * kHdrFloats;
+      su = h[kHdrSur]; mr = h[kHdrMref];
+    }
+    if (su > 0.f) s += double(su) * exp(double(a.t) * (double(mr) - m));
   }
-  for (int i = threadIdx.x; i < a.nslotB; i += 256) {
-    const float* h = a.hdrB + size_t(i) * kHdrFloats;
-    if (h[kHdrSur] > 0.f) s += double(h[kHdrSur]) * exp(double(a.t) * (double(h[kHdrMref]) - m));
-  }
-  s = block_sum(s, red);
+  double z1 = 0, z2 = 0, z3 = 0, zm = 0;
+  reduce5(s, z1, z2, z3, zm);
   if (threadIdx.x == 0) {
     a.losses[0] = float(ezA); a.losses[1] = float(ezB); a.losses[2] = float(l2A); a.losses[3] = float(l2B);
     a.losses[4] = float(m + log(s) / double(a.t));
@@ -339,11 +346,12 @@ __global__ __launch_bounds__(256) void bgemm_kernel(const float* __restrict__ A,
 // output tile per workgroup, four waves of one 32 x 32 tile each, the operand panels staged in
 // LDS as [contraction index][64 tile indices] (row stride 97 floats: transposing stores, whose
 // lanes walk the contraction index, and the MFMA operand reads, whose lane halves take rows l
-// and l+1, both stay clear of bank conflicts).  Contraction in chunks of 128 (K = 64: one of 64).
+// and l+1, both stay clear of bank conflicts).  Contraction in chunks of 64 (50 KB of LDS: three
+// workgroups per compute unit).
 template <bool TA, bool TB>
 __global__ __launch_bounds__(256) void bgemm_mfma_kernel(const float* __restrict__ A, const float* __restrict__ B,
                                                           float* __restrict__ C, int K, float alpha, float beta) {
-  constexpr int LD = 97, CH = 128;
+  constexpr int LD = 97, CH = 64;
   __shared__ float sa[CH * LD];
   __shared__ float sb[CH * LD];
   const int tpr = K / 64;
@@ -358,8 +366,8 @@ __global__ __launch_bounds__(256) void bgemm_mfma_kernel(const float* __restrict
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
   for (int l0 = 0; l0 < K; l0 += CH) {
-    const int nl = K - l0 < CH ? K - l0 : CH;   // 64 or 128
-    const int sh = nl == 64 ? 6 : 7;
+    const int nl = CH;
+    const int sh = 6;
     // sa[l][i] = op(A)[i0 + i][l0 + l];  sb[l][j] = op(B)[l0 + l][j0 + j]; eight elements of
     // each panel per thread and round, all loads of a round issued before the first LDS store
     for (int e0 = tid; e0 < nl * 64; e0 += 8 * 256) {
@@ -478,7 +486,7 @@ int launch_reduce_losses(int kind, const float* hdrA, int nslotA, const float* h
   LossArgs a;
   a.hdrA = hdrA; a.nslotA = nslotA; a.hdrB = hdrB; a.nslotB = nslotB; a.kind = kind; a.beta = beta; a.t = t;
   a.ngroups = ngroups; a.losses = losses; a.lse_ms = lse_ms;
-  hipLaunchKernelGGL(reduce_losses_kernel, dim3(1), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(reduce_losses_kernel, dim3(1), dim3(kLossThreads), 0, st, a);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }

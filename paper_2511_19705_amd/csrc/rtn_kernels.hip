@@ -141,6 +141,42 @@ __global__ __launch_bounds__(NW * kWave) void rtn_row_fast(
   if (partial) block_store_partial(err, partial);
 }
 
+// One wave per group, group length a multiple of 4: 128-bit loads, four codes per store.
+template <typename Tag>
+__global__ __launch_bounds__(256) void rtn_col_vec(
+    const typename Tag::elem* __restrict__ W, int64_t rows, int64_t cols, int64_t ld, int64_t g,
+    QGrid grid, int8_t* __restrict__ codes, float* __restrict__ scales, double* __restrict__ partial) {
+  const int lane = threadIdx.x % kWave;
+  const int64_t gpr = cols / g, ngroups = rows * gpr;
+  const int64_t wave0 = int64_t(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int64_t wstride = int64_t(gridDim.x) * (blockDim.x / kWave);
+  float err = 0.f;
+  for (int64_t gi = wave0; gi < ngroups; gi += wstride) {
+    const int64_t r = gi / gpr, c0 = (gi - r * gpr) * g;
+    const typename Tag::elem* src = W + r * ld + c0;
+    float a = 0.f;
+    for (int64_t i = int64_t(lane) * 4; i < g; i += kWave * 4) {
+      const float4 z = load4(src + i);
+      a = fmaxf(a, fmaxf(fmaxf(fabsf(z.x), fabsf(z.y)), fmaxf(fabsf(z.z), fabsf(z.w))));
+    }
+    a = cluster_allmax<64>(a);
+    const float inv = grid_inv(a, grid.qmax), s = grid_scale(a, grid.qmax);
+    if (lane == 0 && scales) scales[gi] = s;
+    for (int64_t i = int64_t(lane) * 4; i < g; i += kWave * 4) {
+      const float4 z = load4(src + i);
+      const float q0 = grid_code(z.x, inv, grid), q1 = grid_code(z.y, inv, grid);
+      const float q2 = grid_code(z.z, inv, grid), q3 = grid_code(z.w, inv, grid);
+      *reinterpret_cast<uint32_t*>(codes + r * cols + c0 + i) = pack4(q0, q1, q2, q3);
+      if (partial) {
+        const float e0 = __fmul_rn(q0, s) - z.x, e1 = __fmul_rn(q1, s) - z.y;
+        const float e2 = __fmul_rn(q2, s) - z.z, e3 = __fmul_rn(q3, s) - z.w;
+        err += e0 * e0 + e1 * e1 + e2 * e2 + e3 * e3;
+      }
+    }
+  }
+  if (partial) block_store_partial(err, partial);
+}
+
 // One wave per group, any group length.
 template <typename Tag>
 __global__ __launch_bounds__(256) void rtn_col_any(
@@ -256,7 +292,53 @@ __global__ __launch_bounds__(kColThreads) void rtn_col_minmax_fast(
   if (partial) block_store_partial(err, partial);
 }
 
-// One wave per group along the contiguous axis, any group length (whole channels included).
+// One wave per group along the contiguous axis, group length a multiple of 4 (whole channels
+// included): 128-bit loads, four codes per 32-bit store; the second pass re-reads the group
+// from cache.
+template <typename Tag>
+__global__ __launch_bounds__(256) void rtn_col_minmax_vec(
+    const typename Tag::elem* __restrict__ W, int64_t rows, int64_t cols, int64_t ld, int64_t g, float levels,
+    uint8_t* __restrict__ codes, float* __restrict__ scales, float* __restrict__ mins,
+    double* __restrict__ partial) {
+  const int lane = threadIdx.x % kWave;
+  const int64_t gpr = cols / g, ngroups = rows * gpr;
+  const int64_t wave0 = int64_t(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int64_t wstride = int64_t(gridDim.x) * (blockDim.x / kWave);
+  float err = 0.f;
+  for (int64_t gi = wave0; gi < ngroups; gi += wstride) {
+    const int64_t r = gi / gpr, c0 = (gi - r * gpr) * g;
+    const typename Tag::elem* src = W + r * ld + c0;
+    float hi = -FLT_MAX, nlo = -FLT_MAX;
+    for (int64_t i = int64_t(lane) * 4; i < g; i += kWave * 4) {
+      const float4 z = load4(src + i);
+      hi = fmaxf(hi, fmaxf(fmaxf(z.x, z.y), fmaxf(z.z, z.w)));
+      nlo = fmaxf(nlo, fmaxf(fmaxf(-z.x, -z.y), fmaxf(-z.z, -z.w)));
+    }
+    hi = cluster_allmax<64>(hi);
+    nlo = cluster_allmax<64>(nlo);
+    const float lo = -nlo, rg = __fsub_rn(hi, lo);
+    const float inv = mm_inv(rg, levels), s = __fdiv_rn(rg, levels);
+    if (lane == 0) {
+      if (scales) scales[gi] = s;
+      if (mins) mins[gi] = lo;
+    }
+    for (int64_t i = int64_t(lane) * 4; i < g; i += kWave * 4) {
+      const float4 z = load4(src + i);
+      const float q0 = mm_code(z.x, lo, inv, levels), q1 = mm_code(z.y, lo, inv, levels);
+      const float q2 = mm_code(z.z, lo, inv, levels), q3 = mm_code(z.w, lo, inv, levels);
+      *reinterpret_cast<uint32_t*>(codes + r * cols + c0 + i) =
+          uint32_t(q0) | (uint32_t(q1) << 8) | (uint32_t(q2) << 16) | (uint32_t(q3) << 24);
+      if (partial) {
+        const float e0 = __fadd_rn(__fmul_rn(q0, s), lo) - z.x, e1 = __fadd_rn(__fmul_rn(q1, s), lo) - z.y;
+        const float e2 = __fadd_rn(__fmul_rn(q2, s), lo) - z.z, e3 = __fadd_rn(__fmul_rn(q3, s), lo) - z.w;
+        err += e0 * e0 + e1 * e1 + e2 * e2 + e3 * e3;
+      }
+    }
+  }
+  if (partial) block_store_partial(err, partial);
+}
+
+// One wave per group along the contiguous axis, any group length.
 template <typename Tag>
 __global__ __launch_bounds__(256) void rtn_col_minmax_any(
     const typename Tag::elem* __restrict__ W, int64_t rows, int64_t cols, int64_t ld, int64_t g, float levels,
@@ -379,8 +461,12 @@ int launch_rtn_typed(const RtnArgs& a, hipStream_t st, int* nparts) {
       const int64_t ngroups = a.rows * (a.cols / g);
       const int nblk = int(std::min<int64_t>((ngroups + 3) / 4, 4096));
       *nparts = nblk;
-      hipLaunchKernelGGL((rtn_col_any<Tag>), dim3(nblk), dim3(256), 0, st, (const E*)a.W, a.rows, a.cols,
-                         a.ld, g, a.grid, a.codes, a.scales, a.partial);
+      if (g % 4 == 0 && a.ld % 4 == 0 && a.cols % 4 == 0)
+        hipLaunchKernelGGL((rtn_col_vec<Tag>), dim3(nblk), dim3(256), 0, st, (const E*)a.W, a.rows, a.cols,
+                           a.ld, g, a.grid, a.codes, a.scales, a.partial);
+      else
+        hipLaunchKernelGGL((rtn_col_any<Tag>), dim3(nblk), dim3(256), 0, st, (const E*)a.W, a.rows, a.cols,
+                           a.ld, g, a.grid, a.codes, a.scales, a.partial);
     }
   } else {
     const int nw = int(g / kRowRPW);
@@ -449,8 +535,13 @@ int launch_minmax_typed(const RtnArgs& a, float levels, hipStream_t st, int* npa
       const int64_t ngroups = a.rows * (a.cols / g);
       const int nblk = int(std::min<int64_t>((ngroups + 3) / 4, 4096));
       *nparts = nblk;
-      hipLaunchKernelGGL((rtn_col_minmax_any<Tag>), dim3(nblk), dim3(256), 0, st, (const E*)a.W, a.rows, a.cols,
-                         a.ld, g, levels, (uint8_t*)a.codes, a.scales, a.mins, a.partial);
+      // load4 needs 16-byte (float32) / 8-byte (bfloat16) aligned groups; the code stores 4-byte aligned ones
+      if (g % 4 == 0 && a.ld % 4 == 0 && a.cols % 4 == 0)
+        hipLaunchKernelGGL((rtn_col_minmax_vec<Tag>), dim3(nblk), dim3(256), 0, st, (const E*)a.W, a.rows, a.cols,
+                           a.ld, g, levels, (uint8_t*)a.codes, a.scales, a.mins, a.partial);
+      else
+        hipLaunchKernelGGL((rtn_col_minmax_any<Tag>), dim3(nblk), dim3(256), 0, st, (const E*)a.W, a.rows, a.cols,
+                           a.ld, g, levels, (uint8_t*)a.codes, a.scales, a.mins, a.partial);
     }
   } else {
     const int64_t total = (a.rows / g) * a.cols;
