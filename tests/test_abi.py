@@ -43,3 +43,57 @@ def test_host_side_argument_validation_needs_no_gpu():
     # NULL descriptors are rejected on the host before any launch
     rc = lib.cafeq_rtn_quantize(None, None, None, None, None, None, None)
     assert rc == -1
+
+
+def test_argument_errors_of_every_entry_point_are_reported_before_any_launch():
+    """NULL / malformed arguments come back as negative status codes from the host-side checks
+    (no GPU needed, nothing is launched)."""
+    if not os.path.exists(LIB):
+        pytest.skip("library not built")
+    lib = ctypes.CDLL(LIB)
+
+    class Mat(ctypes.Structure):
+        _fields_ = [("data", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                    ("ld", ctypes.c_int64), ("dtype", ctypes.c_int32)]
+
+    class Cfg(ctypes.Structure):
+        _fields_ = [("bits", ctypes.c_int32), ("group", ctypes.c_int32), ("axis", ctypes.c_int32),
+                    ("mode", ctypes.c_int32)]
+
+    for name in ("cafeq_rtn_quantize", "cafeq_rtn_quantize_minmax", "cafeq_block_inverse", "cafeq_apply_transform",
+                 "cafeq_proxy_loss_fwd_bwd", "cafeq_dual_proxy_loss_fwd_bwd", "cafeq_adaptive_round_step",
+                 "cafeq_pqe", "cafeq_orth_penalty", "cafeq_sgd_update", "cafeq_adam_update",
+                 "cafeq_optimize_single", "cafeq_optimize_pair"):
+        getattr(lib, name).restype = ctypes.c_int
+    vp = ctypes.c_void_p
+    null = vp(0)
+    fake = vp(4096)          # a non-null, 16-byte aligned address that is never dereferenced on these paths
+    assert lib.cafeq_block_inverse(null, 64, 1, null, null, null, null, null, null) < 0
+    lib.cafeq_block_inverse.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, vp, vp, vp, vp, vp]
+    assert lib.cafeq_block_inverse(fake, 48, 1, fake, null, null, null, fake, null) < 0      # unsupported block size
+    assert lib.cafeq_block_inverse(fake, 64, 0, fake, null, null, null, fake, null) < 0      # no blocks
+    assert lib.cafeq_block_inverse(fake, 64, 1, fake, null, null, null, null, null) < 0      # no workspace
+    m = Mat(4096, 8, 100, 100, 0)                                                              # 100 columns
+    cfg = Cfg(4, 32, 0, 0)                                                                     # groups of 32: 100 % 32 != 0
+    lib.cafeq_rtn_quantize.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Cfg), vp, vp, vp, vp, vp]
+    assert lib.cafeq_rtn_quantize(ctypes.byref(m), ctypes.byref(cfg), fake, null, null, null, null) < 0
+    bad_bits = Cfg(9, 0, 0, 0)
+    assert lib.cafeq_rtn_quantize(ctypes.byref(m), ctypes.byref(bad_bits), fake, null, null, null, null) < 0
+    lib.cafeq_rtn_quantize_minmax.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Cfg), vp, vp, vp, vp, vp, vp]
+    assert lib.cafeq_rtn_quantize_minmax(ctypes.byref(m), ctypes.byref(cfg), fake, null, null, null, null, null) < 0
+    misaligned = Mat(4100, 8, 128, 128, 0)
+    ok_cfg = Cfg(4, 32, 0, 0)
+    assert lib.cafeq_rtn_quantize(ctypes.byref(misaligned), ctypes.byref(ok_cfg), fake, null, null, null, null) < 0
+    lib.cafeq_orth_penalty.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_float, vp, vp, vp, vp]
+    assert lib.cafeq_orth_penalty(fake, 64, 1, 0.1, null, null, fake, null) < 0               # nothing to compute
+    assert lib.cafeq_orth_penalty(fake, 40, 1, 0.1, fake, null, fake, null) < 0               # unsupported block size
+    lib.cafeq_sgd_update.argtypes = [vp, vp, ctypes.c_float, vp, ctypes.c_int64, vp]
+    assert lib.cafeq_sgd_update(null, fake, 0.1, null, 16, null) < 0
+    assert lib.cafeq_sgd_update(fake, fake, 0.1, null, 0, null) < 0
+    lib.cafeq_adam_update.argtypes = [vp, vp, vp, vp, ctypes.c_int, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+                                      ctypes.c_double, ctypes.c_int64, vp]
+    assert lib.cafeq_adam_update(fake, fake, fake, fake, 0, 1e-3, 0.9, 0.999, 1e-8, 16, null) < 0    # steps count from 1
+    assert lib.cafeq_adam_update(fake, fake, fake, fake, 1, 1e-3, 1.0, 0.999, 1e-8, 16, null) < 0    # beta1 must be < 1
+    lib.cafeq_strerror.restype = ctypes.c_char_p
+    for code in range(-8, 1):
+        assert len(lib.cafeq_strerror(code)) > 0
