@@ -25,6 +25,9 @@ What each function follows (section / equation of the CafeQ paper):
 * ``pinv``, ``adaptive_round_step``, ``pqe`` -- Algorithm 1 (Sec. 5) and the paired
                             quantization error of Sec. 4.2.
 * ``adaptive_bruteforce_column`` -- exhaustive up/down search used only as a pin.
+* ``hadamard_matrix``, ``hadamard_apply``, ``hadamard_baseline`` -- the paper's "random" comparison
+                            (caption of the block-size table in Sec. 4.1): a block-diagonal transform whose
+                            blocks are randomized Hadamard matrices, then the same quantizer.
 * ``orth_penalty``       -- the orthonormality regulariser ||T T^T - I||_F / sqrt(d) of the
                             appendix on paired-quantization hyperparameters ("Constraints on T").
 * ``sgd_step``, ``adam_step``, ``optimize_single``, ``optimize_pair`` -- the learning
@@ -546,3 +549,41 @@ def optimize_pair(A, B, T0, bits, group, rep, t, lr, steps, lam=0.0, beta1=0.1, 
         hist.append((f["errU_sq"], f["errV_sq"], f["l2A_sq"], f["l2B_sq"], f["lse"], pen))
         T, m, v = adam_step(T, f["gradT"] + gp, m, v, s + 1, lr, beta1, beta2, eps)
     return T, np.array(hist)
+
+
+# ----------------------------------------------------------------------------
+# randomized-Hadamard baseline
+# ----------------------------------------------------------------------------
+def hadamard_matrix(n):
+    """Sylvester's construction: H_1 = [1], H_2m = [[H_m, H_m], [H_m, -H_m]] (n a power of two)."""
+    H = np.ones((1, 1))
+    while H.shape[0] < n:
+        H = np.block([[H, H], [H, -H]])
+    assert H.shape[0] == n
+    return H
+
+
+def hadamard_apply(W, signs, blk):
+    """Z = W . blockdiag(D_b H / sqrt(blk)) along the columns: the elements of each block of `blk`
+    consecutive columns are multiplied by their random signs, then by the normalised Hadamard
+    matrix (an orthogonal transform)."""
+    W = np.asarray(W, dtype=np.float64)
+    R, C = W.shape
+    H = hadamard_matrix(blk) / np.sqrt(blk)
+    X = (W * np.asarray(signs, dtype=np.float64)[None, :]).reshape(R, C // blk, blk)
+    return (X @ H).reshape(R, C)
+
+
+def hadamard_baseline(W, signs, blk, bits, group, arith="f32"):
+    """The 'random' row of the paper's block-size table: transform with randomized Hadamard blocks,
+    quantize, transform back.  Returns dict(l2_sq, err_z_sq, w_sq, Z, Zhat); the transform is
+    orthogonal, so the two errors coincide (the way back is written out here, not assumed)."""
+    W = np.asarray(W, dtype=np.float64)
+    Z = hadamard_apply(W, signs, blk)
+    Zhat = quantize(Z, bits, group, COL, SYM, arith)
+    E = Zhat - Z
+    R, C = W.shape
+    H = hadamard_matrix(blk) / np.sqrt(blk)
+    D = ((E.reshape(R, C // blk, blk) @ H.T).reshape(R, C)) * np.asarray(signs, dtype=np.float64)[None, :]
+    return dict(l2_sq=float((D * D).sum()), err_z_sq=float((E * E).sum()), w_sq=float((W * W).sum()),
+                Z=Z, Zhat=Zhat)

@@ -217,3 +217,9 @@ def small_pair(d_model, d_mid, k, rep, seed, eps=0.0):
     nb = d_mid // k
     T = perturbed_blocks(nb, k, seed + 2, eps) if eps else haar_blocks(nb, k, seed + 2)
     return A, B, T
+
+
+def random_signs(n, seed):
+    """n random +-1 values (float32): the diagonal of a randomized Hadamard transform."""
+    rng = np.random.default_rng(seed)
+    return (rng.integers(0, 2, size=n).astype(np.float32) * 2.0 - 1.0)
