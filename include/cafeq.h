@@ -138,6 +138,19 @@ int cafeq_rtn_quantize(const cafeq_mat* W, const cafeq_quant_cfg* cfg, int8_t* c
 int cafeq_rtn_quantize_minmax(const cafeq_mat* W, const cafeq_quant_cfg* cfg, uint8_t* codes,
                               float* scales, float* mins, float* err_sq, void* ws, void* stream);
 
+/* The paper's "random" comparison (caption of the block-size table in Sec. 4.1: "a block diagonal
+ * matrix with block size 1024, where each block is a random Hadamard matrix"): every block of
+ * `block` (256, 512 or 1024) consecutive columns of W is multiplied by its random signs
+ * (signs[cols], +-1) and by the normalised Walsh-Hadamard matrix in Sylvester's ordering, then
+ * quantized as in cafeq_rtn_quantize (groups of cfg->group columns, a power of two in
+ * [32, block]; cfg->axis must be CAFEQ_AXIS_COL).  The transform is orthogonal, so
+ *   losses[0] = ||Q(Z) - Z||_F^2 = ||M^-1 Q(M W) - W||_F^2 (the l2 proxy),  losses[1] = ||W||_F^2.
+ * Z (float32 [rows][cols]), codes, scales: optional outputs, dense.  Workspace:
+ * cafeq_hadamard_workspace_bytes(rows, cols, block). */
+size_t cafeq_hadamard_workspace_bytes(int64_t rows, int64_t cols, int block);
+int cafeq_hadamard_rtn(const cafeq_mat* W, const float* signs, int block, const cafeq_quant_cfg* cfg,
+                       float* Z, int8_t* codes, float* scales, float* losses, void* ws, void* stream);
+
 /* Z = W.blockdiag(X) or blockdiag(X).W with X = T (CAFEQ_SIDE_T) or Tinv
  * (CAFEQ_SIDE_TINV)  (paper Sec. 4.1 block-diagonal M; Sec. 4.2 U = W1 M, V = M^-1 W2).
  * Z: float32 [rows][cols] dense, must not alias W. */

@@ -24,7 +24,7 @@ EXPORTS = (
     "cafeq_rtn_quantize", "cafeq_apply_transform", "cafeq_proxy_loss_fwd_bwd",
     "cafeq_dual_proxy_loss_fwd_bwd", "cafeq_adaptive_round_step",
     "cafeq_orth_penalty", "cafeq_sgd_update", "cafeq_adam_update", "cafeq_optimize_single",
-    "cafeq_optimize_pair", "cafeq_pqe", "cafeq_rtn_quantize_minmax", "cafeq_profile_enable",
+    "cafeq_optimize_pair", "cafeq_pqe", "cafeq_rtn_quantize_minmax", "cafeq_hadamard_rtn", "cafeq_profile_enable",
     "cafeq_profile_read",
 )
 
@@ -88,6 +88,9 @@ def _load():
     lib.cafeq_optimize_pair.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Mat), vp, vp, i32, i32, i32,
                                         ctypes.POINTER(QuantCfg), f32, ctypes.POINTER(OptCfg), vp, vp, vp, vp, vp]
     lib.cafeq_rtn_quantize_minmax.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(QuantCfg), vp, vp, vp, vp, vp, vp]
+    lib.cafeq_hadamard_workspace_bytes.restype = ctypes.c_size_t
+    lib.cafeq_hadamard_workspace_bytes.argtypes = [i64, i64, i32]
+    lib.cafeq_hadamard_rtn.argtypes = [ctypes.POINTER(Mat), vp, i32, ctypes.POINTER(QuantCfg), vp, vp, vp, vp, vp, vp]
     lib.cafeq_pqe.argtypes = [vp, vp, i64, i64, i64, i64, ctypes.POINTER(QuantCfg), i32, i32, i32, vp, vp, vp, vp,
                               vp, vp, vp]
     lib.cafeq_profile_enable.argtypes = [i32]
@@ -355,3 +358,19 @@ def rtn_quantize_minmax(W, bits, group, axis=AXIS_COL, want_err=False):
     _check(lib.cafeq_rtn_quantize_minmax(ctypes.byref(m), ctypes.byref(cfg), _ptr(codes), _ptr(scales), _ptr(mins),
                                          _ptr(err), _ptr(ws), _stream()))
     return codes, scales, mins, err
+
+
+def hadamard_rtn(W, signs, block, bits, group, want_z=False, want_codes=False):
+    """Randomized-Hadamard baseline: (losses[2] = (err_sq, w_sq), Z or None, codes or None, scales or None)."""
+    m = mat(W)
+    cfg = QuantCfg(bits, group, AXIS_COL, 0)
+    R, C = W.shape
+    dev = W.device
+    Z = torch.empty((R, C), dtype=torch.float32, device=dev) if want_z else None
+    codes = torch.empty((R, C), dtype=torch.int8, device=dev) if want_codes else None
+    scales = torch.empty((R, C // group), dtype=torch.float32, device=dev) if want_codes else None
+    losses = torch.empty(2, dtype=torch.float32, device=dev)
+    ws = workspace(int(lib.cafeq_hadamard_workspace_bytes(R, C, block)), dev)
+    _check(lib.cafeq_hadamard_rtn(ctypes.byref(m), _ptr(signs), block, ctypes.byref(cfg), _ptr(Z), _ptr(codes),
+                                  _ptr(scales), _ptr(losses), _ptr(ws), _stream()))
+    return losses, Z, codes, scales
