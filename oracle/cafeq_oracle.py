@@ -28,6 +28,9 @@ What each function follows (section / equation of the CafeQ paper):
 * ``hadamard_matrix``, ``hadamard_apply``, ``hadamard_baseline`` -- the paper's "random" comparison
                             (caption of the block-size table in Sec. 4.1): a block-diagonal transform whose
                             blocks are randomized Hadamard matrices, then the same quantizer.
+* ``dequantize``, ``infer_single`` -- the inference side of a single transformed matrix (Sec. 4.1, the
+                            display Y^ = X M^-1 Q(MW)): the activations take the inverse transform, then the
+                            product with the dequantized transformed weight.
 * ``orth_penalty``       -- the orthonormality regulariser ||T T^T - I||_F / sqrt(d) of the
                             appendix on paired-quantization hyperparameters ("Constraints on T").
 * ``sgd_step``, ``adam_step``, ``optimize_single``, ``optimize_pair`` -- the learning
@@ -587,3 +590,44 @@ def hadamard_baseline(W, signs, blk, bits, group, arith="f32"):
     D = ((E.reshape(R, C // blk, blk) @ H.T).reshape(R, C)) * np.asarray(signs, dtype=np.float64)[None, :]
     return dict(l2_sq=float((D * D).sum()), err_z_sq=float((E * E).sum()), w_sq=float((W * W).sum()),
                 Z=Z, Zhat=Zhat)
+
+
+# ----------------------------------------------------------------------------
+# inference side of a single transformed matrix
+# ----------------------------------------------------------------------------
+def dequantize(codes, scales, group, axis=COL):
+    """Symmetric grid: zhat = fl32(q * s), the scale of an element's group spread over the group."""
+    q = np.asarray(codes).astype(np.float32)
+    R, C = q.shape
+    s = np.asarray(scales, dtype=np.float32)
+    if axis == COL:
+        g = C if group == 0 else group
+        full = np.repeat(s.reshape(R, C // g), g, axis=1)
+    else:
+        g = R if group == 0 else group
+        full = np.repeat(s.reshape(R // g, C), g, axis=0)
+    return (q * full).astype(np.float64)
+
+
+def infer_single(X, P, codes, scales, group):
+    """Layer output with the quantized transformed weight (Sec. 4.1): Y^ = X M^-1 Q(MW).
+
+    Orientation: the paper's weight is [in][out] and M acts on its left; here weights are [out][in] and
+    Z = W . blockdiag(T) (axis COL), so Q(MW) = Zhat^T and M^-1 = blockdiag(P)^T with P = T^-1 blockwise.
+    X: [n][in] activations; P: [nb][k][k] or None (no transform: the plain quantized layer);
+    codes [out][in], scales [out][in/group].  Returns Y^ [n][out] (float64)."""
+    X = np.asarray(X, dtype=np.float64)
+    n, d = X.shape
+    Zhat = dequantize(codes, scales, group, COL)            # [out][in]
+    assert Zhat.shape[1] == d
+    if P is None:
+        XM = X
+    else:
+        P = np.asarray(P, dtype=np.float64)
+        nb, k, _ = P.shape
+        assert nb * k == d
+        Minv = np.zeros((d, d))
+        for b in range(nb):
+            Minv[b * k:(b + 1) * k, b * k:(b + 1) * k] = P[b].T
+        XM = X @ Minv
+    return XM @ Zhat.T
