@@ -178,6 +178,68 @@ def other_workload(args):
     print(json.dumps(out))
 
 
+def infer_workload(args):
+    """Inference side of a single transformed matrix (Sec. 4.1; the block-size table's extra wall-clock row):
+    one token through the quantized down projection, with and without the inverse transform on the
+    activations.  c2_infer: the table's matrix (in 9216, out 2304); c3_infer: the 9B-shaped one (in 14336,
+    out 3584).  Codes and scales are synthetic (the entry point sees nothing else of the weight)."""
+    import numpy as np
+    import torch
+    from paper_2511_19705_amd import cafeq
+    dev = torch.device("cuda:0")
+    out_f, in_f = (2304, 9216) if args.workload == "c2_infer" else (3584, 14336)
+    k, g, bits, n = 128, 128, 4, 1
+    gen = torch.Generator(device="cpu").manual_seed(77)
+    codes_h = torch.randint(-8, 8, (out_f, in_f), dtype=torch.int8, generator=gen)
+    scales_h = torch.exp(torch.randn((out_f, in_f // g), generator=gen) * 0.5 - 5.0)
+    P_h = torch.eye(k).repeat(in_f // k, 1, 1) + 0.05 * torch.randn((in_f // k, k, k), generator=gen) / k ** 0.5
+    X_h = torch.randn((n, in_f), generator=gen)
+    codes, scales, P, X = codes_h.to(dev), scales_h.to(dev), P_h.to(dev), X_h.to(dev)
+    Y = torch.empty((n, out_f), device=dev)
+
+    def timed(fn, reps):
+        for _ in range(max(args.warmup, 1)):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3, (time.perf_counter() - t0) / reps
+
+    plain_ev, _ = timed(lambda: cafeq.infer_single(X, None, codes, scales, g, out=Y), args.steps)
+    xf_ev, xf_wall = timed(lambda: cafeq.infer_single(X, P, codes, scales, g, out=Y), args.steps)
+    byts = out_f * in_f + out_f * (in_f // g) * 4 + n * in_f * 4 + n * out_f * 4
+    achieved = byts / plain_ev / 1e9
+    res = {"metric": "tokens/s through one quantized transformed layer (activation transform + dequantize + product)",
+           "value": n / xf_wall, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": xf_wall * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "%s_%dx%d_k%d_g%d_%dbit_tokens%d" % (args.workload, out_f, in_f, k, g, bits, n)},
+           "roofline": {"bound": "hbm", "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0,
+                        "traffic": None, "kernel": "dequant_gemv_kernel<1,*> (plain quantized layer)",
+                        "avg_launch_us": plain_ev * 1e6, "algorithmic_bytes": byts},
+           "transform": {"plain_us": plain_ev * 1e6, "with_transform_us": xf_ev * 1e6,
+                         "extra_wall_clock_pct": (xf_ev / plain_ev - 1) * 100,
+                         "extra_flops_pct": 100.0 * k / out_f, "extra_bytes_pct": 100.0 * 4 * k / out_f}}
+    if not args.no_cpu_baseline:
+        from oracle import cafeq_oracle as O
+        rows = 256
+        c, sc = codes_h[:rows].numpy(), scales_h[:rows].numpy()
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            O.infer_single(X_h.numpy(), P_h.numpy(), c, sc, g)
+            reps += 1
+        dt = (time.perf_counter() - t0) / reps
+        res["cpu_baseline"] = {"value": n / (dt * out_f / rows), "unit": "tokens/s", "cores": _cores(), "kind": "oracle",
+                               "sample": "%d of %d output rows (dense inverse transform included), %d repetitions, scaled" % (rows, out_f, reps)}
+    print(json.dumps(res))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -186,7 +248,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-blocks", type=int, default=112)
     ap.add_argument("--cpu-reps", type=int, default=4)
-    ap.add_argument("--workload", default="c3_pair", choices=["c3_pair", "c3_optimize", "c2_single", "c4_adaptive"],
+    ap.add_argument("--workload", default="c3_pair", choices=["c3_pair", "c3_optimize", "c2_single", "c4_adaptive", "c2_infer", "c3_infer"],
                     help="c3_pair is the headline metric; the others are secondary measurements")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for the profiler's byte counters)")
@@ -199,6 +261,8 @@ def main():
     from paper_2511_19705_amd import cafeq, workloads as WL
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.workload in ("c2_infer", "c3_infer"):
+        return infer_workload(args)
     if args.workload != "c3_pair":
         return other_workload(args)
     dev = torch.device("cuda:0")

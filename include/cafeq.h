@@ -151,6 +151,23 @@ size_t cafeq_hadamard_workspace_bytes(int64_t rows, int64_t cols, int block);
 int cafeq_hadamard_rtn(const cafeq_mat* W, const float* signs, int block, const cafeq_quant_cfg* cfg,
                        float* Z, int8_t* codes, float* scales, float* losses, void* ws, void* stream);
 
+/* Inference side of a single transformed matrix (paper Sec. 4.1, the display Y^ = X M^-1 Q(MW); the
+ * block-size table's "extra FLOPs / extra wall-clock time" rows price its first factor).  With the
+ * [out][in] layout and Z = W . blockdiag(T) of this library:
+ *   x'[t][b*k + i] = sum_j Tinv[b][i][j] X[t][b*k + j],   Y[t][o] = sum_c scales[o][c/group] codes[o][c] x'[t][c].
+ * X: float32 [n][in] (leading dimension ldx, a multiple of 4; 16-byte aligned), n >= 1 tokens -- the
+ * kernels are laid out for a handful of tokens (the codes are re-read once per 4 tokens);
+ * xf: the transform (only Tinv, k, nb are read; nb*k == in, rep == 1), or NULL for the plain quantized
+ * layer Y = X Q(W)^T with no transform; codes int8 [out][in] and scales float32 [out][in/group] as
+ * written by cafeq_rtn_quantize / cafeq_proxy_loss_fwd_bwd on CAFEQ_AXIS_COL (group 0 = the whole
+ * line; in and group multiples of 16, in <= 65536); Y: float32 [n][out] (leading dimension ldy).
+ * ws: cafeq_infer_workspace_bytes(n, in) bytes (holds x'; not needed when xf is NULL).
+ * float32 accumulation throughout; the summation order is fixed (results are reproducible). */
+size_t cafeq_infer_workspace_bytes(int n, int64_t in);
+int cafeq_infer_single(const float* X, int n, int64_t ldx, const cafeq_xform* xf, const int8_t* codes,
+                       const float* scales, int64_t out, int64_t in, int group, float* Y, int64_t ldy,
+                       void* ws, void* stream);
+
 /* Z = W.blockdiag(X) or blockdiag(X).W with X = T (CAFEQ_SIDE_T) or Tinv
  * (CAFEQ_SIDE_TINV)  (paper Sec. 4.1 block-diagonal M; Sec. 4.2 U = W1 M, V = M^-1 W2).
  * Z: float32 [rows][cols] dense, must not alias W. */

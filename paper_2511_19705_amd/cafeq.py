@@ -24,7 +24,8 @@ EXPORTS = (
     "cafeq_rtn_quantize", "cafeq_apply_transform", "cafeq_proxy_loss_fwd_bwd",
     "cafeq_dual_proxy_loss_fwd_bwd", "cafeq_adaptive_round_step",
     "cafeq_orth_penalty", "cafeq_sgd_update", "cafeq_adam_update", "cafeq_optimize_single",
-    "cafeq_optimize_pair", "cafeq_pqe", "cafeq_rtn_quantize_minmax", "cafeq_hadamard_rtn", "cafeq_profile_enable",
+    "cafeq_optimize_pair", "cafeq_pqe", "cafeq_rtn_quantize_minmax", "cafeq_hadamard_rtn", "cafeq_hadamard_workspace_bytes",
+    "cafeq_infer_single", "cafeq_infer_workspace_bytes", "cafeq_profile_enable",
     "cafeq_profile_read",
 )
 
@@ -90,6 +91,9 @@ def _load():
     lib.cafeq_rtn_quantize_minmax.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(QuantCfg), vp, vp, vp, vp, vp, vp]
     lib.cafeq_hadamard_workspace_bytes.restype = ctypes.c_size_t
     lib.cafeq_hadamard_workspace_bytes.argtypes = [i64, i64, i32]
+    lib.cafeq_infer_workspace_bytes.restype = ctypes.c_size_t
+    lib.cafeq_infer_workspace_bytes.argtypes = [i32, i64]
+    lib.cafeq_infer_single.argtypes = [vp, i32, i64, ctypes.POINTER(Xform), vp, vp, i64, i64, i32, vp, i64, vp, vp]
     lib.cafeq_hadamard_rtn.argtypes = [ctypes.POINTER(Mat), vp, i32, ctypes.POINTER(QuantCfg), vp, vp, vp, vp, vp, vp]
     lib.cafeq_pqe.argtypes = [vp, vp, i64, i64, i64, i64, ctypes.POINTER(QuantCfg), i32, i32, i32, vp, vp, vp, vp,
                               vp, vp, vp]
@@ -374,3 +378,20 @@ def hadamard_rtn(W, signs, block, bits, group, want_z=False, want_codes=False):
     _check(lib.cafeq_hadamard_rtn(ctypes.byref(m), _ptr(signs), block, ctypes.byref(cfg), _ptr(Z), _ptr(codes),
                                   _ptr(scales), _ptr(losses), _ptr(ws), _stream()))
     return losses, Z, codes, scales
+
+
+def infer_single(X, Tinv, codes, scales, group, out=None):
+    """Y[n][out] = (X . blockdiag(Tinv)^T) . dequant(codes, scales)^T; Tinv None = no transform."""
+    n, d = X.shape
+    O = codes.shape[0]
+    Y = out if out is not None else torch.empty((n, O), dtype=torch.float32, device=X.device)
+    if Tinv is not None:
+        nb, k, _ = Tinv.shape
+        xf = Xform(None, _ptr(Tinv), k, nb, 1)
+        ws = workspace(int(lib.cafeq_infer_workspace_bytes(n, d)), X.device)
+        xfp = ctypes.byref(xf)
+    else:
+        ws, xfp = None, None
+    _check(lib.cafeq_infer_single(_ptr(X), n, X.stride(0), xfp, _ptr(codes), _ptr(scales), O, d, group, _ptr(Y),
+                                  Y.stride(0), _ptr(ws), _stream()))
+    return Y

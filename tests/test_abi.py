@@ -94,6 +94,27 @@ def test_argument_errors_of_every_entry_point_are_reported_before_any_launch():
                                       ctypes.c_double, ctypes.c_int64, vp]
     assert lib.cafeq_adam_update(fake, fake, fake, fake, 0, 1e-3, 0.9, 0.999, 1e-8, 16, null) < 0    # steps count from 1
     assert lib.cafeq_adam_update(fake, fake, fake, fake, 1, 1e-3, 1.0, 0.999, 1e-8, 16, null) < 0    # beta1 must be < 1
+    class Xf(ctypes.Structure):
+        _fields_ = [("T", vp), ("Tinv", vp), ("k", ctypes.c_int32), ("nb", ctypes.c_int32), ("rep", ctypes.c_int32)]
+
+    i64 = ctypes.c_int64
+    lib.cafeq_infer_single.restype = ctypes.c_int
+    lib.cafeq_infer_single.argtypes = [vp, ctypes.c_int, i64, ctypes.POINTER(Xf), vp, vp, i64, i64, ctypes.c_int, vp,
+                                       i64, vp, vp]
+    assert lib.cafeq_infer_single(null, 1, 256, None, fake, fake, 8, 256, 32, fake, 8, null, null) == -1   # no X
+    assert lib.cafeq_infer_single(fake, 1, 250, None, fake, fake, 8, 250, 0, fake, 8, null, null) == -2    # in % 16
+    assert lib.cafeq_infer_single(fake, 1, 256, None, fake, fake, 8, 256, 24, fake, 8, null, null) == -2   # group % 16
+    assert lib.cafeq_infer_single(fake, 1, 256, None, fake, fake, 8, 256, 32, fake, 4, null, null) == -2   # ldy < out
+    xf = Xf(null, fake, 64, 3, 1)
+    assert lib.cafeq_infer_single(fake, 1, 256, ctypes.byref(xf), fake, fake, 8, 256, 32, fake, 8, fake, null) == -2
+    xf = Xf(null, fake, 64, 4, 1)
+    assert lib.cafeq_infer_single(fake, 1, 256, ctypes.byref(xf), fake, fake, 8, 256, 32, fake, 8, null, null) == -7
+    xf = Xf(null, fake, 48, 4, 1)
+    assert lib.cafeq_infer_single(fake, 1, 192, ctypes.byref(xf), fake, fake, 8, 192, 32, fake, 8, fake, null) == -4
+    lib.cafeq_infer_workspace_bytes.restype = ctypes.c_size_t
+    lib.cafeq_infer_workspace_bytes.argtypes = [ctypes.c_int, i64]
+    assert lib.cafeq_infer_workspace_bytes(3, 256) == 3 * 256 * 4
+    assert lib.cafeq_infer_workspace_bytes(0, 256) == 0
     lib.cafeq_strerror.restype = ctypes.c_char_p
     for code in range(-8, 1):
         assert len(lib.cafeq_strerror(code)) > 0
