@@ -14,7 +14,7 @@
 //   gram_pair_kernel : fp32 MFMA (v_mfma_f32_32x32x2_f32), one workgroup per (head, 32-row
 //                      output stripe, chunk of the contraction range); codes are dequantized
 //                      on the fly; chunk partials are written out, not atomically added.
-//   gj_reg_kernel    : sums the chunk partials of S in float64 and inverts it by register-
+//   gj_panel_kernel  : sums the chunk partials of S in float64 and inverts it by register-
 //                      resident Gauss-Jordan elimination with partial pivoting; also serves
 //                      cafeq_block_inverse.  C = I - S^-1 R follows as a batched product.
 #include <type_traits>
@@ -291,32 +291,39 @@ __device__ __forceinline__ float read_lane(float x, int src) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src));
 }
 
+// |x| as an unsigned key that orders like |x|: the leading 32 bits of the number without its sign
+__device__ __forceinline__ uint32_t mag_bits(double x) { return uint32_t(__double2hiint(x)) & 0x7FFFFFFFu; }
+__device__ __forceinline__ uint32_t mag_bits(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
+
 __device__ __forceinline__ double fma_s(double a, double b, double c) { return __builtin_fma(a, b, c); }
 __device__ __forceinline__ float fma_s(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
 
-// Register-resident in-place Gauss-Jordan inversion, one workgroup per block.
+// Register-resident in-place Gauss-Jordan inversion with partial pivoting, one workgroup per block.
 // Thread (rt, ct) of an NRT x NCT thread grid keeps the RT x CT elements (rt + i*NRT, ct + j*NCT)
-// in registers (both strides interleaved, so the LDS reads of a step are either broadcasts or
-// run over consecutive addresses).  Step k: the owners of column k publish it, every wave finds
-// the pivot p among the rows not yet used (no physical row swaps: the pivot order is a
-// permutation undone on output), the owners of row p publish it divided by the pivot, and every
-// thread updates its tile from RT column values and CT row values -- two barriers and RT + CT
-// LDS reads per RT*CT fused multiply-adds.  The kernel is bound by instruction issue, so the
-// step is written without branches that change registers: column k becomes the unit vector e_p
-// by selects, and row p goes through the same update as the others with the multiplier
-// (pivot - 1), for which row - (pivot - 1) * row / pivot = row / pivot.  That identity loses
-// accuracy only for |pivot| >> 1, so the block is first scaled by a power of two to
-// max |a_ij| in (1/2, 1].  A singular block keeps running (on infinities) and is zeroed at the
-// end.  The step loop is unrolled over the register column index so that all register accesses
-// are static.
+// in registers (both strides interleaved, so the LDS reads are either broadcasts or run over
+// consecutive addresses).  No physical row swaps: the pivot of column k is the largest entry among
+// the rows not yet used, and the pivot order is a permutation undone on output.  One elimination
+// step replaces column k by the unit vector e_p and adds multiples of row p / pivot to every row;
+// row p itself goes through the same update with the multiplier (1 - pivot), which loses accuracy
+// only for |pivot| >> 1, so the block is first scaled by a power of two to max |a_ij| in (1/2, 1].
+// The steps of NB = 8 columns (a panel) are taken by the first wave on the K x NB panel alone -- rows
+// in registers (lane l holds rows l, l + 64, ...), pivot search by DPP, pivot row through scalar lane
+// reads, no barriers -- and their combined effect on the other columns, the rank-NB update
+// R += C . X  (C: the panel after its steps minus the unit vectors of the pivot rows, X: the NB pivot
+// rows as they were before the panel), is applied by all threads at once: three barriers per panel.
+// A singular block keeps running (on infinities) and is zeroed at the end.
 //   A = T_b (float32) when partial == nullptr, else the float64 sum over nz chunk partials
 //   of S (first of the two K x K matrices of each partial).  out = A^-1 (zeros if singular).
 template <int K, int RT, int CT, typename S>
-__global__ __launch_bounds__((K / RT) * (K / CT)) void gj_reg_kernel(const GjArgs a) {
+__global__ __launch_bounds__((K / RT) * (K / CT)) void gj_panel_kernel(const GjArgs a) {
   constexpr int NRT = K / RT, NCT = K / CT, NTHR = NRT * NCT, NWAVE = (NTHR + 63) / 64;
-  __shared__ __align__(16) S colbuf[2][K];
-  __shared__ __align__(16) S rowbuf[2][K];
-  __shared__ int pk[K], kinv[K], used[K];
+  constexpr int NB = 8, NPH = NCT / NB, NRW = (K + 63) / 64;
+  static_assert(NCT % NB == 0, "panel width");
+  __shared__ __align__(16) S pan[2][K][NB];
+  __shared__ __align__(16) S xrow[2][NB][K];
+  __shared__ int pk[K], kinv[K];
+  __shared__ int pvt[2][NB];
+  __shared__ int deadflag;
   __shared__ float cn[K];
   __shared__ S wred[16];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
@@ -335,7 +342,7 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_reg_kernel(const GjArg
 #pragma unroll
       for (int j = 0; j < CT; ++j) reg[i][j] = 0;
     for (int z = 0; z < a.nz; ++z) {
-      // float64 accumulation; the float GJ (K = 256) rounds the sum once
+      // float64 accumulation; the float elimination (K = 256) rounds the sum once
       double t[RT][CT];
 #pragma unroll
       for (int i = 0; i < RT; ++i)
@@ -354,7 +361,8 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_reg_kernel(const GjArg
     for (int j = 0; j < CT; ++j) anorm = fmax(anorm, fabs(reg[i][j]));
   for (int m = 1; m < 64; m <<= 1) anorm = fmax(anorm, __shfl_xor(anorm, m));
   if (lane == 0) wred[tid >> 6] = anorm;
-  if (tid < K) { used[tid] = 0; cn[tid] = 0.f; }
+  if (tid < K) cn[tid] = 0.f;
+  if (tid == 0) deadflag = 0;
   __syncthreads();
   anorm = 0;
   for (int i = 0; i < NWAVE; ++i) anorm = fmax(anorm, wred[i]);
@@ -366,77 +374,135 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_reg_kernel(const GjArg
 #pragma unroll
     for (int j = 0; j < CT; ++j) reg[i][j] *= scale;
   const S tol = anorm * scale * S(a.partial ? 1e-5 : (sizeof(S) == 8 ? 1e-12 : 1e-6));
-  bool dead = false;   // uniform over the workgroup
+  uint32_t usedbits = 0;   // first wave only: bit q = row lane + 64 q has been a pivot
 
-  // elimination steps for the columns k = cc + jj*NCT, jj a compile-time register index
-  auto steps = [&](auto jj_c) {
+  auto panels = [&](auto jj_c) {
     constexpr int jj = decltype(jj_c)::value;
-    for (int cc = 0; cc < NCT; ++cc) {
-      const int k = cc + jj * NCT, buf = cc & 1;
-      if (ct == cc) {
+    for (int h = 0; h < NPH; ++h) {
+      const int buf = (jj * NPH + h) & 1;
+      const int q_own = ct - h * NB;
+      const bool owner = q_own >= 0 && q_own < NB;
+      if (owner) {
 #pragma unroll
-        for (int i = 0; i < RT; ++i) colbuf[buf][rt + i * NRT] = reg[i][jj];
+        for (int i = 0; i < RT; ++i) pan[buf][rt + i * NRT][q_own] = reg[i][jj];
       }
       __syncthreads();
-      // pivot = (approximately) largest |entry| of column k among the unused rows.  Every wave
-      // reduces a 32-bit key (magnitude as float bits with the low byte replaced by 255 - row,
-      // so ties go to the lowest row and the winner's row comes for free) with DPP.
-      constexpr int NC = (K + 63) / 64;
-      S cand[NC];
-      uint32_t key = 0;
+      if (tid < 64) {
+        S prow[NRW][NB];
 #pragma unroll
-      for (int q = 0; q < NC; ++q) {
-        const int rr = lane + 64 * q;
-        cand[q] = rr < K ? colbuf[buf][rr] : S(0);
-        const float mag = float(fabs(cand[q]));
-        const uint32_t kk_ = (rr >= K || used[rr < K ? rr : 0]) ? 0u
-                                                                 : ((__float_as_uint(mag) & 0xFFFFFF00u) | uint32_t(255 - rr));
-        key = key > kk_ ? key : kk_;
-      }
-      key = wave_allmax_u32(key);
-      const int p = (255 - int(key & 0xFFu)) & (K - 1);
-      // the pivot value comes from the register of the lane that holds it
-      S pv = read_lane(cand[0], p & 63);
+        for (int q = 0; q < NRW; ++q) {
+          const int rr = lane + 64 * q;
 #pragma unroll
-      for (int q = 1; q < NC; ++q) {
-        const S alt = read_lane(cand[q], p & 63);
-        pv = (p >> 6) == q ? alt : pv;
-      }
-      dead = dead || (key >> 8) == 0 || !(S(fabs(pv)) > tol);
-      // reciprocal of the pivot: hardware estimate (2^-22) + Newton steps to full precision
-      S ipiv = S(__builtin_amdgcn_rcpf(float(pv)));
-      ipiv = ipiv * (S(2) - pv * ipiv);
-      if (sizeof(S) == 8) ipiv = ipiv * (S(2) - pv * ipiv);
-      const int prt = p % NRT, pi = p / NRT;
-      // publish row p (with the in-place 1 at column k) divided by the pivot
-#pragma unroll
-      for (int i = 0; i < RT; ++i)
-        if (rt == prt && i == pi) {
-#pragma unroll
-          for (int j = 0; j < CT; ++j)
-            rowbuf[buf][ct + j * NCT] = ((j == jj && ct == cc) ? S(1) : reg[i][j]) * ipiv;
+          for (int c = 0; c < NB; ++c) prow[q][c] = rr < K ? pan[buf][rr < K ? rr : 0][c] : S(0);
         }
-      if (tid == 0) pk[k] = p;
+        int pivs[NB];
+        bool dd = false;
+#pragma unroll
+        for (int s = 0; s < NB; ++s) {
+          // pivot = (approximately) largest |entry| of the column among the unused rows: a 32-bit key
+          // (leading bits of the magnitude, low byte 255 - row: ties go to the lowest row) reduced by DPP
+          S colv[NRW];
+          uint32_t key = 0;
+#pragma unroll
+          for (int q = 0; q < NRW; ++q) {
+            const int rr = lane + 64 * q;
+            colv[q] = prow[q][s];
+            const uint32_t kk_ = (rr >= K || ((usedbits >> q) & 1u)) ? 0u
+                                                                     : ((mag_bits(colv[q]) & 0xFFFFFF00u) | uint32_t(255 - rr));
+            key = key > kk_ ? key : kk_;
+          }
+          key = wave_allmax_u32(key);
+          const int p = (255 - int(key & 0xFFu)) & (K - 1);
+          const int pl = p & 63, pq = p >> 6;
+          S pv = read_lane(colv[0], pl);
+#pragma unroll
+          for (int q = 1; q < NRW; ++q) {
+            const S alt = read_lane(colv[q], pl);
+            pv = pq == q ? alt : pv;
+          }
+          dd = dd || (key >> 8) == 0 || !(S(fabs(pv)) > tol);
+          // reciprocal of the pivot: hardware estimate (2^-22) + Newton steps to full precision
+          S ipiv = S(__builtin_amdgcn_rcpf(float(pv)));
+          ipiv = ipiv * (S(2) - pv * ipiv);
+          if (sizeof(S) == 8) ipiv = ipiv * (S(2) - pv * ipiv);
+          // row p of the panel, with the in-place 1 in the column of this step
+          S rowp[NB];
+#pragma unroll
+          for (int c = 0; c < NB; ++c) {
+            S mine = prow[0][c];
+#pragma unroll
+            for (int q = 1; q < NRW; ++q) mine = pq == q ? prow[q][c] : mine;
+            rowp[c] = c == s ? S(1) : read_lane(mine, pl);
+          }
+#pragma unroll
+          for (int q = 0; q < NRW; ++q) {
+            const bool isp = (lane + 64 * q) == p;
+            const S f = (isp ? S(1) - pv : -colv[q]) * ipiv;
+#pragma unroll
+            for (int c = 0; c < NB; ++c)
+              prow[q][c] = c == s ? (isp ? S(1) : S(0)) + f : fma_s(f, rowp[c], prow[q][c]);
+            usedbits |= uint32_t(isp) << q;
+          }
+          pivs[s] = p;
+        }
+        // hand over C = (panel after its steps) - (unit vectors of the pivot rows), and the pivots
+#pragma unroll
+        for (int q = 0; q < NRW; ++q) {
+          const int rr = lane + 64 * q;
+          if (rr < K) {
+#pragma unroll
+            for (int c = 0; c < NB; ++c) pan[buf][rr][c] = prow[q][c] - (rr == pivs[c] ? S(1) : S(0));
+          }
+        }
+        if (lane == 0) {
+#pragma unroll
+          for (int c = 0; c < NB; ++c) {
+            pvt[buf][c] = pivs[c];
+            pk[jj * NCT + h * NB + c] = pivs[c];
+          }
+          if (dd) deadflag = 1;
+        }
+      }
       __syncthreads();
-      if (tid == 0) used[p] = 1;   // after the barrier: other waves may still be searching before it
-      S row[CT];
+      // the owners of the pivot rows publish them as they were before the panel
 #pragma unroll
-      for (int j = 0; j < CT; ++j) row[j] = rowbuf[buf][ct + j * NCT];
-      S cv[RT];
+      for (int c = 0; c < NB; ++c) {
+        const int p = pvt[buf][c];
+        const int prt = p % NRT, pi = p / NRT;
 #pragma unroll
-      for (int i = 0; i < RT; ++i) cv[i] = colbuf[buf][rt + i * NRT];
+        for (int i = 0; i < RT; ++i)
+          if (rt == prt && i == pi) {
 #pragma unroll
-      for (int i = 0; i < RT; ++i) {
-        const int r = rt + i * NRT;
-        const S nf = r == p ? S(1) - pv : -cv[i];
-        if (ct == cc) reg[i][jj] = r == p ? S(1) : S(0);
+            for (int j = 0; j < CT; ++j) xrow[buf][c][ct + j * NCT] = reg[i][j];
+          }
+      }
+      __syncthreads();
+#pragma unroll 2
+      for (int c = 0; c < NB; ++c) {
+        S xv[CT], cr[RT];
 #pragma unroll
-        for (int j = 0; j < CT; ++j) reg[i][j] = fma_s(nf, row[j], reg[i][j]);
+        for (int j = 0; j < CT; ++j) xv[j] = xrow[buf][c][ct + j * NCT];
+#pragma unroll
+        for (int i = 0; i < RT; ++i) cr[i] = pan[buf][rt + i * NRT][c];
+#pragma unroll
+        for (int i = 0; i < RT; ++i)
+#pragma unroll
+          for (int j = 0; j < CT; ++j) reg[i][j] = fma_s(cr[i], xv[j], reg[i][j]);
+      }
+      // a panel column becomes the panel's own result
+      if (owner) {
+        const int pq = pvt[buf][q_own];
+#pragma unroll
+        for (int i = 0; i < RT; ++i) {
+          const int r = rt + i * NRT;
+          reg[i][jj] = pan[buf][r][q_own] + (r == pq ? S(1) : S(0));
+        }
       }
     }
   };
-  StaticFor<0, CT>::run(steps);
+  StaticFor<0, CT>::run(panels);
   __syncthreads();
+  const bool dead = deadflag != 0;
   if (a.status && tid == 0) a.status[size_t(b) * a.status_stride + a.status_offset] = dead ? 1 : 0;
   float* O = a.out + size_t(b) * K * K;
   if (dead) {
@@ -467,13 +533,11 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_reg_kernel(const GjArg
       rr += reg[i][j] * reg[i][j];
     }
     if (a.rho_row) {
-      // squared row norms: sum over this row's NCT threads (adjacent lanes)
       for (int m = 1; m < NCT; m <<= 1) rr += __shfl_xor(rr, m);
       if (ct == 0) a.rho_row[size_t(b) * K + orow] = float(rr);
     }
   }
   if (a.rho_col) {
-    // squared column norms: this thread's RT rows first, then atomics in LDS
 #pragma unroll
     for (int j = 0; j < CT; ++j) {
       S c2 = 0;
@@ -582,10 +646,10 @@ __global__ __launch_bounds__(256) void eye_minus_kernel(const double* __restrict
 namespace {
 int launch_gj(const GjArgs& a, int nb, hipStream_t st) {
   switch (a.K) {
-    case 32: hipLaunchKernelGGL((gj_reg_kernel<32, 4, 4, double>), dim3(nb), dim3(64), 0, st, a); break;
-    case 64: hipLaunchKernelGGL((gj_reg_kernel<64, 4, 8, double>), dim3(nb), dim3(128), 0, st, a); break;
-    case 128: hipLaunchKernelGGL((gj_reg_kernel<128, 4, 8, double>), dim3(nb), dim3(512), 0, st, a); break;
-    case 256: hipLaunchKernelGGL((gj_reg_kernel<256, 8, 8, float>), dim3(nb), dim3(1024), 0, st, a); break;
+    case 32: hipLaunchKernelGGL((gj_panel_kernel<32, 4, 4, double>), dim3(nb), dim3(64), 0, st, a); break;
+    case 64: hipLaunchKernelGGL((gj_panel_kernel<64, 4, 8, double>), dim3(nb), dim3(128), 0, st, a); break;
+    case 128: hipLaunchKernelGGL((gj_panel_kernel<128, 4, 8, double>), dim3(nb), dim3(512), 0, st, a); break;
+    case 256: hipLaunchKernelGGL((gj_panel_kernel<256, 8, 16, float>), dim3(nb), dim3(512), 0, st, a); break;
     default: return CAFEQ_ERR_UNSUPPORTED;
   }
   CAFEQ_CHECK_LAUNCH();
