@@ -41,22 +41,33 @@ __global__ __launch_bounds__(256) void split_planes_kernel(const SplitJobs js) {
   const float* sb = jb.src + size_t(blockIdx.x) * K * K;
   uint16_t* db = jb.dst + (size_t(blockIdx.x) * nst + stage) * nplanes * K * 32;
   const int lk = 31 - __builtin_clz(unsigned(K));
-  for (int e = threadIdx.x; e < K * 32; e += 256) {
-    int r, c;
-    if (jb.trans) { r = 32 * stage + (e >> lk); c = e & (K - 1); }
-    else          { r = e >> 5; c = 32 * stage + (e & 31); }
-    const int out = jb.trans ? c : r, w32 = (jb.trans ? r : c) & 31;
-    const int c2 = w32 / 16, w16 = w32 % 16;
-    const int u = w16 / 8, hh = (w16 % 8) / 4, ee = w16 % 4;
+  // a thread takes four inputs that are adjacent in the plane (e = 0..3 of one (row, step, half, u)):
+  // one 128-bit load (or four coalesced loads of a transposed source) and one 64-bit LDS store per plane
+  for (int qd = threadIdx.x; qd < K * 8; qd += 256) {
+    int out, wq;
+    float x[4];
+    if (jb.trans) {
+      out = qd & (K - 1); wq = qd >> lk;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[e] = sb[size_t(32 * stage + 4 * wq + e) * K + out];
+    } else {
+      out = qd >> 3; wq = qd & 7;
+      const float4 v = *reinterpret_cast<const float4*>(sb + size_t(out) * K + 32 * stage + 4 * wq);
+      x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+    }
+    const int c2 = wq >> 2, u = (wq >> 1) & 1, hh = wq & 1;
     const int chunk = (2 * c2 + hh) ^ ((out >> 2) & 3);
-    const int at = out * 32 + chunk * 8 + 4 * u + ee;
-    float x = sb[r * K + c];
+    const int at = out * 32 + chunk * 8 + 4 * u;
     for (int pl = 0; pl < nplanes; ++pl) {
-      uint32_t bits = __float_as_uint(x);
-      bits += 0x7FFFu + ((bits >> 16) & 1u);          // round to nearest even
-      const uint16_t part = uint16_t(bits >> 16);
-      lds[at + pl * K * 32] = part;
-      x -= __uint_as_float(uint32_t(part) << 16);
+      uint32_t part[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        uint32_t bits = __float_as_uint(x[e]);
+        bits += 0x7FFFu + ((bits >> 16) & 1u);          // round to nearest even
+        part[e] = bits >> 16;
+        x[e] -= __uint_as_float(part[e] << 16);
+      }
+      *reinterpret_cast<uint2*>(lds + at + pl * K * 32) = make_uint2(part[0] | (part[1] << 16), part[2] | (part[3] << 16));
     }
   }
   __syncthreads();
