@@ -302,7 +302,8 @@ __device__ __forceinline__ float fma_s(float a, float b, float c) { return __bui
 // Thread (rt, ct) of an NRT x NCT thread grid keeps the RT x CT elements (rt + i*NRT, ct + j*NCT)
 // in registers (both strides interleaved, so the LDS reads are either broadcasts or run over
 // consecutive addresses).  No physical row swaps: the pivot of column k is the largest entry among
-// the rows not yet used, and the pivot order is a permutation undone on output.  One elimination
+// the rows not yet used (PIV; for symmetric positive definite input, PIV == false, it is the diagonal
+// entry), and the pivot order is a permutation undone on output.  One elimination
 // step replaces column k by the unit vector e_p and adds multiples of row p / pivot to every row;
 // row p itself goes through the same update with the multiplier (1 - pivot), which loses accuracy
 // only for |pivot| >> 1, so the block is first scaled by a power of two to max |a_ij| in (1/2, 1].
@@ -314,7 +315,7 @@ __device__ __forceinline__ float fma_s(float a, float b, float c) { return __bui
 // A singular block keeps running (on infinities) and is zeroed at the end.
 //   A = T_b (float32) when partial == nullptr, else the float64 sum over nz chunk partials
 //   of S (first of the two K x K matrices of each partial).  out = A^-1 (zeros if singular).
-template <int K, int RT, int CT, typename S>
+template <int K, int RT, int CT, typename S, bool PIV>
 __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_panel_kernel(const GjArgs a) {
   constexpr int NRT = K / RT, NCT = K / CT, NTHR = NRT * NCT, NWAVE = (NTHR + 63) / 64;
   constexpr int NB = 8, NPH = NCT / NB, NRW = (K + 63) / 64;
@@ -401,18 +402,24 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_panel_kernel(const GjA
         for (int s = 0; s < NB; ++s) {
           // pivot = (approximately) largest |entry| of the column among the unused rows: a 32-bit key
           // (leading bits of the magnitude, low byte 255 - row: ties go to the lowest row) reduced by DPP
+          // (PIV == false, for symmetric positive definite input: the diagonal entry, no search)
           S colv[NRW];
-          uint32_t key = 0;
+          uint32_t key = 0x100u;
 #pragma unroll
-          for (int q = 0; q < NRW; ++q) {
-            const int rr = lane + 64 * q;
-            colv[q] = prow[q][s];
-            const uint32_t kk_ = (rr >= K || ((usedbits >> q) & 1u)) ? 0u
-                                                                     : ((mag_bits(colv[q]) & 0xFFFFFF00u) | uint32_t(255 - rr));
-            key = key > kk_ ? key : kk_;
+          for (int q = 0; q < NRW; ++q) colv[q] = prow[q][s];
+          int p = jj * NCT + h * NB + s;
+          if (PIV) {
+            key = 0;
+#pragma unroll
+            for (int q = 0; q < NRW; ++q) {
+              const int rr = lane + 64 * q;
+              const uint32_t kk_ = (rr >= K || ((usedbits >> q) & 1u)) ? 0u
+                                                                       : ((mag_bits(colv[q]) & 0xFFFFFF00u) | uint32_t(255 - rr));
+              key = key > kk_ ? key : kk_;
+            }
+            key = wave_allmax_u32(key);
+            p = (255 - int(key & 0xFFu)) & (K - 1);
           }
-          key = wave_allmax_u32(key);
-          const int p = (255 - int(key & 0xFFu)) & (K - 1);
           const int pl = p & 63, pq = p >> 6;
           S pv = read_lane(colv[0], pl);
 #pragma unroll
@@ -420,7 +427,7 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_panel_kernel(const GjA
             const S alt = read_lane(colv[q], pl);
             pv = pq == q ? alt : pv;
           }
-          dd = dd || (key >> 8) == 0 || !(S(fabs(pv)) > tol);
+          dd = dd || (key >> 8) == 0 || !((PIV ? S(fabs(pv)) : pv) > tol);
           // reciprocal of the pivot: hardware estimate (2^-22) + Newton steps to full precision
           S ipiv = S(__builtin_amdgcn_rcpf(float(pv)));
           ipiv = ipiv * (S(2) - pv * ipiv);
@@ -645,13 +652,19 @@ __global__ __launch_bounds__(256) void eye_minus_kernel(const double* __restrict
 
 namespace {
 int launch_gj(const GjArgs& a, int nb, hipStream_t st) {
+  // the Gram matrices of the adaptive rounding are symmetric positive definite: no pivot search there
+  const bool piv = a.partial == nullptr;
+#define CAFEQ_GJ(K_, RT_, CT_, S_, THR_)                                                                      \
+  if (piv) hipLaunchKernelGGL((gj_panel_kernel<K_, RT_, CT_, S_, true>), dim3(nb), dim3(THR_), 0, st, a);     \
+  else hipLaunchKernelGGL((gj_panel_kernel<K_, RT_, CT_, S_, false>), dim3(nb), dim3(THR_), 0, st, a)
   switch (a.K) {
-    case 32: hipLaunchKernelGGL((gj_panel_kernel<32, 4, 4, double>), dim3(nb), dim3(64), 0, st, a); break;
-    case 64: hipLaunchKernelGGL((gj_panel_kernel<64, 4, 8, double>), dim3(nb), dim3(128), 0, st, a); break;
-    case 128: hipLaunchKernelGGL((gj_panel_kernel<128, 4, 8, double>), dim3(nb), dim3(512), 0, st, a); break;
-    case 256: hipLaunchKernelGGL((gj_panel_kernel<256, 8, 16, float>), dim3(nb), dim3(512), 0, st, a); break;
+    case 32: CAFEQ_GJ(32, 4, 4, double, 64); break;
+    case 64: CAFEQ_GJ(64, 4, 8, double, 128); break;
+    case 128: CAFEQ_GJ(128, 4, 8, double, 512); break;
+    case 256: CAFEQ_GJ(256, 8, 16, float, 512); break;
     default: return CAFEQ_ERR_UNSUPPORTED;
   }
+#undef CAFEQ_GJ
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }
