@@ -29,13 +29,19 @@ __global__ __launch_bounds__(256) void rho_kernel(const float* __restrict__ P, i
 // half h -> chunk 2*c2 + h, holding inputs 16*c2 + 8u + 4h + e at position 4u + e), the chunk stored
 // at chunk ^ ((out >> 2) & 3) (LDS bank swizzle).
 struct SplitJob { const float* src; uint16_t* dst; int trans, nplanes; };
-struct SplitJobs { SplitJob job[4]; int njobs, K; };
+struct SplitJobs { SplitJob job[4]; int njobs, K; float* hdr; int64_t nhdr; };   // hdr: partial headers to reset (may be null)
 // grid: (nb, njobs).  Reads are linear in the source; the 2-byte writes scatter inside the block.
 __global__ __launch_bounds__(256) void split_planes_kernel(const SplitJobs js) {
   // one workgroup per (block, job, stage of 32 contraction indices): the stage's planes are
   // assembled in LDS in their final order and leave as whole 16-byte vectors
   __shared__ __align__(16) uint16_t lds[3 * 256 * 32];
   const int K = js.K, nst = K / 32;
+  // partial headers that no workgroup of the core writes (slots nobody owns) must read as empty
+  if (js.hdr) {
+    const int64_t nthr = int64_t(gridDim.x) * gridDim.y * 256;
+    for (int64_t i = (int64_t(blockIdx.y) * gridDim.x + blockIdx.x) * 256 + threadIdx.x; i < js.nhdr; i += nthr)
+      js.hdr[i] = (i % kHdrFloats) == kHdrMref ? -INFINITY : 0.f;
+  }
   const SplitJob jb = js.job[blockIdx.y / nst];
   const int stage = blockIdx.y % nst, nplanes = jb.nplanes;
   const float* sb = jb.src + size_t(blockIdx.x) * K * K;
@@ -302,13 +308,6 @@ __global__ __launch_bounds__(kLossThreads) void reduce_losses_kernel(const LossA
   }
 }
 
-// Partial headers that were never written (slots no workgroup owns) must read as empty.
-__global__ __launch_bounds__(256) void init_hdr_kernel(float* hdr, int64_t nslot) {
-  const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (i >= nslot * kHdrFloats) return;
-  hdr[i] = (i % kHdrFloats) == kHdrMref ? -INFINITY : 0.f;
-}
-
 // ---------------------------------------------------------------------------------------
 // batched k x k product  C_b = alpha * op(A_b) op(B_b) + beta * C_b   (64 x 64 tile / workgroup)
 // ---------------------------------------------------------------------------------------
@@ -439,9 +438,10 @@ __global__ __launch_bounds__(256) void bgemm32_kernel(const float* __restrict__ 
 
 }  // namespace
 
-int launch_split_planes_multi(const SplitRequest* req, int n, int K, int nb, hipStream_t st) {
+int launch_split_planes_multi(const SplitRequest* req, int n, int K, int nb, hipStream_t st, float* hdr,
+                              int64_t nslot) {
   SplitJobs js;
-  js.njobs = n; js.K = K;
+  js.njobs = n; js.K = K; js.hdr = hdr; js.nhdr = nslot * kHdrFloats;
   for (int i = 0; i < n && i < 4; ++i) {
     js.job[i].src = req[i].src; js.job[i].dst = req[i].dst;
     js.job[i].trans = req[i].trans; js.job[i].nplanes = req[i].nplanes;
@@ -462,12 +462,6 @@ int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_
 int launch_rho_groups(const float* rho, int K, int rep, int G, int64_t ngroups, float* rG, hipStream_t st) {
   hipLaunchKernelGGL(rho_group_kernel, dim3(unsigned((ngroups + 3) / 4)), dim3(256), 0, st, rho, K, rep, G,
                      ngroups, rG);
-  CAFEQ_CHECK_LAUNCH();
-  return CAFEQ_OK;
-}
-int launch_init_hdr(float* hdr, int64_t nslot, hipStream_t st) {
-  const int64_t n = nslot * kHdrFloats;
-  hipLaunchKernelGGL(init_hdr_kernel, dim3(unsigned((n + 255) / 256)), dim3(256), 0, st, hdr, nslot);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }

@@ -584,7 +584,6 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   const QGrid grid = make_grid(cfg->bits);
   const float beta = 1.f / (4.f * grid.qmax * grid.qmax);
 
-  if ((rc = launch_init_hdr(w.slot_hdr, pl.nslot, st))) return rc;
   if ((rc = launch_rho(x->Tinv, K, nb, col ? 1 : 0, w.rho, st))) return rc;
   if ((rc = launch_rho_groups(w.rho, K, x->rep, G, naxis / G, w.rG, st))) return rc;
 
@@ -593,7 +592,7 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   // forward operand [out][in]: T^T (COL) or T (ROW); inverse operand: Tinv^T or Tinv
   {
     const SplitRequest req[2] = {{x->T, w.pfwd, col ? 1 : 0, kFwdPlanes}, {x->Tinv, w.pinv, col ? 1 : 0, kInvPlanes}};
-    if ((rc = launch_split_planes_multi(req, 2, K, nb, st))) return rc;
+    if ((rc = launch_split_planes_multi(req, 2, K, nb, st, w.slot_hdr, pl.nslot))) return rc;
   }
   p.Afwd = w.pfwd; p.Ainv = w.pinv;
   p.grid = grid; p.do_inverse = 1; p.do_grad = (gradT && !pp.two) ? 1 : 0; p.loss_kind = kLossSur; p.beta = beta;
@@ -652,12 +651,11 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   hipStream_t st = static_cast<hipStream_t>(stream);
   DualWs w = carve_dual(ws, pa, pb, qa.gpass, qb.gpass, nb, grad, qa.two, qb.two);
   const QGrid grid = make_grid(cfg->bits);
-  if ((rc = launch_init_hdr(w.hdrA, pa.nslot + pb.nslot, st))) return rc;
 
   {
     const SplitRequest req[4] = {{x->T, w.pfwdA, 1, kFwdPlanes}, {x->Tinv, w.pinvA, 1, kInvPlanes},
                                  {x->Tinv, w.pfwdB, 0, kFwdPlanes}, {x->T, w.pinvB, 0, kInvPlanes}};
-    if ((rc = launch_split_planes_multi(req, 4, K, nb, st))) return rc;
+    if ((rc = launch_split_planes_multi(req, 4, K, nb, st, w.hdrA, pa.nslot + pb.nslot))) return rc;
   }
   // Each member: the loss pass, then (two-pass gradient) straight away the gradient pass over
   // the same weights, while they are still in the memory-side cache.  The gradient pass takes

@@ -48,11 +48,11 @@ int device_cu_count();
 // aux_kernels.hip
 struct SplitRequest { const float* src; uint16_t* dst; int trans, nplanes; };
 int launch_split_planes(const float* src, int K, int nb, int trans, int nplanes, uint16_t* dst, hipStream_t st);
-// up to four splits in one launch
-int launch_split_planes_multi(const SplitRequest* req, int n, int K, int nb, hipStream_t st);
+// up to four splits in one launch; hdr (may be null): nslot partial headers reset by the same launch
+int launch_split_planes_multi(const SplitRequest* req, int n, int K, int nb, hipStream_t st, float* hdr = nullptr,
+                              int64_t nslot = 0);
 int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_t st);
 int launch_rho_groups(const float* rho, int K, int rep, int G, int64_t ngroups, float* rG, hipStream_t st);
-int launch_init_hdr(float* hdr, int64_t nslot, hipStream_t st);
 int launch_reduce_grad(const CoreParams& p, int K, int G, int nb, int transpose_out, const double* lse_ms,
                        const float* member_ref, float* out, hipStream_t st);
 int launch_build_mmid(const CoreParams& p, int K, int G, int nb, const float* P, int scale_rows, float* Mmid,
