@@ -28,9 +28,12 @@ __global__ __launch_bounds__(256) void rho_kernel(const float* __restrict__ P, i
 // with the 32 inputs of a row arranged as four 16-byte chunks (MFMA step c2 = (in % 32) / 16, lane
 // half h -> chunk 2*c2 + h, holding inputs 16*c2 + 8u + 4h + e at position 4u + e), the chunk stored
 // at chunk ^ ((out >> 2) & 3) (LDS bank swizzle).
-struct SplitJob { const float* src; uint16_t* dst; int trans, nplanes; };
+struct SplitJob { const float* src; uint16_t* dst; int trans, nplanes; float* fscale; };   // fscale: see below
 struct SplitJobs { SplitJob job[4]; int njobs, K; float* hdr; int64_t nhdr; };   // hdr: partial headers to reset (may be null)
-// grid: (nb, njobs).  Reads are linear in the source; the 2-byte writes scatter inside the block.
+// A job with fscale != null writes TWO float16 planes instead: the block is first scaled by the power of
+// two that puts its largest magnitude into [2^14, 2^15) (so that the low parts stay normal numbers), then
+// x = hi + lo with both parts rounded to nearest; fscale[b] receives the factor that undoes the scale.
+// grid: (nb, njobs * K / 32).
 __global__ __launch_bounds__(256) void split_planes_kernel(const SplitJobs js) {
   // one workgroup per (block, job, stage of 32 contraction indices): the stage's planes are
   // assembled in LDS in their final order and leave as whole 16-byte vectors
@@ -47,6 +50,23 @@ __global__ __launch_bounds__(256) void split_planes_kernel(const SplitJobs js) {
   const float* sb = jb.src + size_t(blockIdx.x) * K * K;
   uint16_t* db = jb.dst + (size_t(blockIdx.x) * nst + stage) * nplanes * K * 32;
   const int lk = 31 - __builtin_clz(unsigned(K));
+  float hsc = 1.f;   // float16 job: the block's scale
+  if (jb.fscale) {
+    __shared__ float wmx[4];
+    float m = 0.f;
+    for (int e = threadIdx.x * 4; e < K * K; e += 256 * 4) {
+      const float4 v = *reinterpret_cast<const float4*>(sb + e);
+      m = fmaxf(fmaxf(m, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+    }
+    m = cluster_allmax<64>(m);
+    if ((threadIdx.x & 63) == 0) wmx[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(wmx[0], wmx[1]), fmaxf(wmx[2], wmx[3]));
+    int ex = int(__float_as_uint(m) >> 23);
+    ex = ex < 32 ? 32 : (ex > 254 ? 254 : ex);
+    hsc = __uint_as_float(uint32_t(268 - ex) << 23);                       // 2^(14 - (ex - 127))
+    if (stage == 0 && threadIdx.x == 0) jb.fscale[blockIdx.x] = __uint_as_float(uint32_t(ex - 14) << 23);
+  }
   // a thread takes four inputs that are adjacent in the plane (e = 0..3 of one (row, step, half, u)):
   // one 128-bit load (or four coalesced loads of a transposed source) and one 64-bit LDS store per plane
   for (int qd = threadIdx.x; qd < K * 8; qd += 256) {
@@ -64,6 +84,20 @@ __global__ __launch_bounds__(256) void split_planes_kernel(const SplitJobs js) {
     const int c2 = wq >> 2, u = (wq >> 1) & 1, hh = wq & 1;
     const int chunk = (2 * c2 + hh) ^ ((out >> 2) & 3);
     const int at = out * 32 + chunk * 8 + 4 * u;
+    if (jb.fscale) {
+      uint32_t hi[4], lo[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float y = x[e] * hsc;
+        const _Float16 a = _Float16(y);
+        const _Float16 b = _Float16(y - float(a));
+        hi[e] = __builtin_bit_cast(uint16_t, a);
+        lo[e] = __builtin_bit_cast(uint16_t, b);
+      }
+      *reinterpret_cast<uint2*>(lds + at) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
+      *reinterpret_cast<uint2*>(lds + at + K * 32) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+      continue;
+    }
     for (int pl = 0; pl < nplanes; ++pl) {
       uint32_t part[4];
 #pragma unroll
@@ -444,7 +478,8 @@ int launch_split_planes_multi(const SplitRequest* req, int n, int K, int nb, hip
   js.njobs = n; js.K = K; js.hdr = hdr; js.nhdr = nslot * kHdrFloats;
   for (int i = 0; i < n && i < 4; ++i) {
     js.job[i].src = req[i].src; js.job[i].dst = req[i].dst;
-    js.job[i].trans = req[i].trans; js.job[i].nplanes = req[i].nplanes;
+    js.job[i].trans = req[i].trans; js.job[i].nplanes = req[i].fscale ? 2 : req[i].nplanes;
+    js.job[i].fscale = req[i].fscale;
   }
   hipLaunchKernelGGL(split_planes_kernel, dim3(nb, n * (K / 32)), dim3(256), 0, st, js);
   CAFEQ_CHECK_LAUNCH();

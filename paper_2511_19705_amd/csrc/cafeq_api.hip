@@ -80,6 +80,7 @@ struct Carver {
 struct SingleWs {
   float *rho, *rG, *slot_grad, *slot_hdr, *mmid, *x1; double* lse_ms; uint16_t *pfwd, *pinv;
   float2* rec; float* member_ref; size_t bytes;
+  float* fs;   // per-block factors of the half-precision forward operand
 };
 // pl: plan of the (first) pass that writes the partial headers; pg: plan of the pass that writes
 // the gradient partials (the same plan unless the gradient runs as a second pass)
@@ -88,6 +89,7 @@ SingleWs carve_single(void* ws, const CorePlan& pl, const CorePlan& pg, int nb, 
   SingleWs w;
   w.lse_ms = c.take<double>(2);
   w.member_ref = c.take<float>(4);
+  w.fs = c.take<float>(nb);
   w.pfwd = c.take<uint16_t>(size_t(nb) * kFwdPlanes * pl.K * pl.K);
   w.pinv = c.take<uint16_t>(size_t(nb) * kInvPlanes * pl.K * pl.K);
   w.rho = c.take<float>(size_t(nb) * pl.K);
@@ -105,6 +107,7 @@ struct DualWs {
   float *hdrA, *hdrB, *gradA, *gradB, *gp, *x1; double* lse_ms;
   uint16_t *pfwdA, *pinvA, *pfwdB, *pinvB;
   float2 *recA, *recB; float* member_ref; size_t bytes;
+  float *fsA, *fsB;   // per-block factors of the half-precision forward operands
 };
 // pa, pb: plans of the passes that write the partial headers; ga, gb: plans of the passes that
 // write the gradient partials
@@ -114,6 +117,8 @@ DualWs carve_dual(void* ws, const CorePlan& pa, const CorePlan& pb, const CorePl
   DualWs w;
   w.lse_ms = c.take<double>(2);
   w.member_ref = c.take<float>(4);   // [0]: member A, [1]: member B
+  w.fsA = c.take<float>(nb);
+  w.fsB = c.take<float>(nb);
   const size_t kk = size_t(nb) * pa.K * pa.K;
   w.pfwdA = c.take<uint16_t>(kk * kFwdPlanes);
   w.pinvA = c.take<uint16_t>(kk * kInvPlanes);
@@ -133,6 +138,11 @@ DualWs carve_dual(void* ws, const CorePlan& pa, const CorePlan& pb, const CorePl
 
 // Plans of one matrix for a call with / without gradient: `first` is the pass that computes
 // the losses, `gpass` the pass that writes the gradient partials (== first unless two-pass).
+// Whether the loss pass for (K, G) runs its forward contraction on two-part half-precision operands: the
+// gradient-free kernel variant over 128 x 128 blocks with one block per segment (with a gradient these
+// shapes take the two-pass scheme, so their loss pass is always gradient-free).
+bool core_forward_f16(int K, int G) { return K == 128 && G <= 128; }
+
 struct PassPlans { CorePlan first, gpass; bool two; };
 int plan_passes(int K, int G, int64_t nlines, int64_t naxis, bool grad, PassPlans* pp) {
   pp->two = grad && two_pass_gradient(K, G);
@@ -215,6 +225,7 @@ void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep)
   p->rG = nullptr; p->Zout = nullptr; p->codes = nullptr; p->scales = nullptr;
   p->slot_grad = nullptr; p->slot_hdr = nullptr;
   p->rec = nullptr; p->hdr_ref = nullptr; p->nslot_ref = 0; p->member_ref = nullptr;
+  p->fscale = nullptr;
   p->grid = make_grid(4);
 }
 
@@ -540,12 +551,16 @@ int cafeq_apply_transform(const cafeq_mat* W, const cafeq_xform* x, int axis, in
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   uint16_t* planes = static_cast<uint16_t*>(ws);
-  if ((rc = launch_split_planes(side == CAFEQ_SIDE_T ? x->T : x->Tinv, x->k, x->nb, col ? 1 : 0, kFwdPlanes,
-                                planes, st)))
-    return rc;
+  // half-precision forward operands where the kernel variant exists: two planes, and the per-block factors
+  // in the room of the third
+  float* fs = core_forward_f16(x->k, x->k) ? reinterpret_cast<float*>(planes + size_t(x->nb) * 2 * x->k * x->k) : nullptr;
+  {
+    const SplitRequest req{side == CAFEQ_SIDE_T ? x->T : x->Tinv, planes, col ? 1 : 0, kFwdPlanes, fs};
+    if ((rc = launch_split_planes_multi(&req, 1, x->k, x->nb, st))) return rc;
+  }
   CoreParams p;
   fill_common(&p, W, pl, x->rep);
-  p.Afwd = planes; p.Ainv = nullptr;
+  p.Afwd = planes; p.Ainv = nullptr; p.fscale = fs;
   p.Zout = Z;
   return launch_core(x->k, x->k, axis, p, st);
 }
@@ -591,10 +606,11 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   fill_common(&p, W, pl, x->rep);
   // forward operand [out][in]: T^T (COL) or T (ROW); inverse operand: Tinv^T or Tinv
   {
-    const SplitRequest req[2] = {{x->T, w.pfwd, col ? 1 : 0, kFwdPlanes}, {x->Tinv, w.pinv, col ? 1 : 0, kInvPlanes}};
+    const SplitRequest req[2] = {{x->T, w.pfwd, col ? 1 : 0, kFwdPlanes, core_forward_f16(K, G) ? w.fs : nullptr},
+                                 {x->Tinv, w.pinv, col ? 1 : 0, kInvPlanes}};
     if ((rc = launch_split_planes_multi(req, 2, K, nb, st, w.slot_hdr, pl.nslot))) return rc;
   }
-  p.Afwd = w.pfwd; p.Ainv = w.pinv;
+  p.Afwd = w.pfwd; p.Ainv = w.pinv; p.fscale = core_forward_f16(K, G) ? w.fs : nullptr;
   p.grid = grid; p.do_inverse = 1; p.do_grad = (gradT && !pp.two) ? 1 : 0; p.loss_kind = kLossSur; p.beta = beta;
   p.rG = w.rG; p.codes = codes; p.scales = scales; p.slot_grad = w.slot_grad; p.slot_hdr = w.slot_hdr;
   p.rec = pp.two ? w.rec : nullptr;
@@ -651,10 +667,12 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   hipStream_t st = static_cast<hipStream_t>(stream);
   DualWs w = carve_dual(ws, pa, pb, qa.gpass, qb.gpass, nb, grad, qa.two, qb.two);
   const QGrid grid = make_grid(cfg->bits);
+  // the gradient-free pass over 128 x 128 blocks (one block per segment) takes half-precision forward operands
+  const bool f16A = core_forward_f16(K, GA), f16B = core_forward_f16(K, GB);
 
   {
-    const SplitRequest req[4] = {{x->T, w.pfwdA, 1, kFwdPlanes}, {x->Tinv, w.pinvA, 1, kInvPlanes},
-                                 {x->Tinv, w.pfwdB, 0, kFwdPlanes}, {x->T, w.pinvB, 0, kInvPlanes}};
+    const SplitRequest req[4] = {{x->T, w.pfwdA, 1, kFwdPlanes, f16A ? w.fsA : nullptr}, {x->Tinv, w.pinvA, 1, kInvPlanes},
+                                 {x->Tinv, w.pfwdB, 0, kFwdPlanes, f16B ? w.fsB : nullptr}, {x->T, w.pinvB, 0, kInvPlanes}};
     if ((rc = launch_split_planes_multi(req, 4, K, nb, st, w.hdrA, pa.nslot + pb.nslot))) return rc;
   }
   // Each member: the loss pass, then (two-pass gradient) straight away the gradient pass over
@@ -667,6 +685,7 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   a.grid = grid; a.do_inverse = 1; a.do_grad = (grad && !qa.two) ? 1 : 0; a.loss_kind = kLossLse; a.lse_t = lse_t;
   a.codes = codesU; a.scales = scalesU; a.slot_grad = w.gradA; a.slot_hdr = w.hdrA;
   a.rec = qa.two ? w.recA : nullptr;
+  a.fscale = f16A ? w.fsA : nullptr;
   if ((rc = launch_core(K, GA, CAFEQ_AXIS_COL, a, st))) return rc;
   ag = a;
   if (qa.two) {
@@ -682,6 +701,7 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   b.grid = grid; b.do_inverse = 1; b.do_grad = (grad && !qb.two) ? 1 : 0; b.loss_kind = kLossLse; b.lse_t = lse_t;
   b.codes = codesV; b.scales = scalesV; b.slot_grad = w.gradB; b.slot_hdr = w.hdrB;
   b.rec = qb.two ? w.recB : nullptr;
+  b.fscale = f16B ? w.fsB : nullptr;
   if ((rc = launch_core(K, GB, CAFEQ_AXIS_ROW, b, st))) return rc;
   bg = b;
   if (qb.two) {

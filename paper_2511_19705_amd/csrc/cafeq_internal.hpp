@@ -46,7 +46,8 @@ size_t core_lds_bytes_k256(int G, bool do_grad);
 int device_cu_count();
 
 // aux_kernels.hip
-struct SplitRequest { const float* src; uint16_t* dst; int trans, nplanes; };
+// fscale != null: two float16 planes of the block scaled by a power of two; fscale[block] = the factor back
+struct SplitRequest { const float* src; uint16_t* dst; int trans, nplanes; float* fscale = nullptr; };
 int launch_split_planes(const float* src, int K, int nb, int trans, int nplanes, uint16_t* dst, hipStream_t st);
 // up to four splits in one launch; hdr (may be null): nslot partial headers reset by the same launch
 int launch_split_planes_multi(const SplitRequest* req, int n, int K, int nb, hipStream_t st, float* hdr = nullptr,

@@ -97,6 +97,8 @@ struct CoreParams {
   int64_t rows, cols, ld;
   const uint16_t* Afwd;  // [nb][K/32 stages][3 planes][K][32] bf16: forward operand in ring-stage order
   const uint16_t* Ainv;  // [nb][K/32 stages][2 planes][K][32] bf16: inverse operand
+  const float* fscale;   // half-precision forward (F16 variant; else null): Afwd holds two float16 planes per stage of
+                         // the block scaled by a power of two, fscale[block] is the factor that undoes that scale
   int rep;               // AXIS_ROW: row-block q uses block q / rep
   int nseg;
   int64_t nlines;
@@ -138,6 +140,14 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint32_t a, uint32_t b, uint32_t c, 
 __device__ __forceinline__ bf16x8 as_bf16x8(uintx4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 #define CAFEQ_MFMA_BF16(A, B, C) __builtin_amdgcn_mfma_f32_32x32x16_bf16((A), (B), (C), 0, 0, 0)
+
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ halfx8 as_halfx8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  uintx4 v = {a, b, c, d};
+  return __builtin_bit_cast(halfx8, v);
+}
+__device__ __forceinline__ halfx8 as_halfx8(uintx4 v) { return __builtin_bit_cast(halfx8, v); }
+#define CAFEQ_MFMA_F16(A, B, C) __builtin_amdgcn_mfma_f32_32x32x16_f16((A), (B), (C), 0, 0, 0)
 
 // s_waitcnt vmcnt(n) for a value of n that is a compile-time constant after unrolling (n is
 // clamped to the counter's 6 bits; a smaller n only waits for more).
@@ -218,8 +228,15 @@ __device__ __forceinline__ void load_strip(const CoreParams& p, float (&wreg)[L 
 // GRAD = false compiles the gradient out: for segments of up to 128 that variant fits in half
 // the register file and needs no weight staging area, so two workgroups share a compute unit
 // (two waves per SIMD).
-template <int K, int G, int AXIS, bool GRAD>
+// F16 (gradient-free variant, one block per segment): the forward contraction runs on two-part
+// half-precision operands -- the strip's weights scaled per line, the transform block scaled per block,
+// each by a power of two that puts its largest magnitude into [2^14, 2^15) -- with three part products
+// (hi.hi, hi.lo, lo.hi; relative error per term below 2^-20, the same order as the float32
+// accumulation) instead of six bfloat16 ones; the accumulators are scaled back before anything reads
+// them.  The inverse transform keeps the bfloat16 parts.
+template <int K, int G, int AXIS, bool GRAD, bool F16 = false>
 __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) void xform_core_kernel(const CoreParams p) {
+  static_assert(!F16 || (!GRAD && Geo<K, G>::NBLK == 1), "half-precision forward: gradient-free, one block per segment");
   using g = Geo<K, G>;
   constexpr bool GRAD_ON = GRAD && g::GRAD_OK;
   constexpr int GTN = GRAD_ON ? g::GT : 1;
@@ -252,7 +269,8 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
   const int mis_first = int(mt0 - int64_t(seg_first) * p.mt_per_seg);   // macro-tile within segment
   const int mt_per_seg = int(p.mt_per_seg);
   constexpr int D = NSTG - 1;
-  constexpr int NFW = kFwdPlanes * PLANEB / 16 / kThreads;   // loads every wave issues per forward stage
+  constexpr int FWDP = F16 ? 2 : kFwdPlanes;                 // operand planes of a forward stage
+  constexpr int NFW = FWDP * PLANEB / 16 / kThreads;         // loads every wave issues per forward stage
   constexpr int NIW = kInvPlanes * PLANEB / 16 / kThreads;   // ... per inverse stage (K = 32: some waves one more)
   constexpr int NWL = AXIS == CAFEQ_AXIS_COL ? L / 8 : L / 2; // load instructions of one strip's weights
   const uint32_t voff = uint32_t(tid) * 16u;
@@ -284,8 +302,8 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
 #pragma unroll
   for (int i = 0; i < NBLK; ++i) cb[i] = nbk[i] = blk_id(seg_first, i);
 
-  dma(p.Afwd, kFwdPlanes, cb[0], 0, 0);
-  if (D == 2) dma(p.Afwd, kFwdPlanes, cb[1 / KT], 1 % KT, 1);
+  dma(p.Afwd, FWDP, cb[0], 0, 0);
+  if (D == 2) dma(p.Afwd, FWDP, cb[1 / KT], 1 % KT, 1);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
@@ -387,6 +405,19 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
     // step the lane splits its eight weights exactly into bfloat16 parts (hi + mid + lo), feeds
     // them to all KT output tiles of the block, and (gradient calls) parks the hi/mid parts in
     // the LDS staging area transposed, [input m][line], for the gradient contraction over lines.
+    // F16: power-of-two scale of this line's weights (largest magnitude of the segment -> [2^14, 2^15))
+    // and the factor that takes the accumulators back (times the block's own factor)
+    float wsc = 1.f, usc = 1.f;
+    if constexpr (F16) {
+      float m = 0.f;
+#pragma unroll
+      for (int f = 0; f < L / 2; ++f) m = fmaxf(m, fabsf(wreg[f]));
+      m = fmaxf(m, __shfl_xor(m, 32));
+      int e = int(__float_as_uint(m) >> 23);     // biased exponent
+      e = e < 32 ? 32 : (e > 254 ? 254 : e);     // lines of (almost) zeros: any scale will do
+      wsc = __uint_as_float(uint32_t(268 - e) << 23);          // 2^(14 - (e - 127))
+      usc = __uint_as_float(uint32_t(e - 14) << 23) * p.fscale[cb[0]];
+    }
     floatx16 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
@@ -401,11 +432,11 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
       {
         const int tq = sg + D, dst = stage == 0 ? NSTG - 1 : stage - 1;
         if (tq < NT) {
-          dma(p.Afwd, kFwdPlanes, cb[tq / KT], tq % KT, dst);
+          dma(p.Afwd, FWDP, cb[tq / KT], tq % KT, dst);
         } else {
           nw = NIW;
           if (p.do_inverse) dma(p.Ainv, kInvPlanes, cb[(tq - NT) / KT], (tq - NT) % KT, dst);
-          else dma(p.Afwd, kFwdPlanes, nbk[(tq - NT) / KT], (tq - NT) % KT, dst);
+          else dma(p.Afwd, FWDP, nbk[(tq - NT) / KT], (tq - NT) % KT, dst);
         }
       }
       const unsigned char* sbase = ring + stage * STAGEB;
@@ -413,6 +444,35 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
 #pragma unroll
       for (int c2 = 0; c2 < 2; ++c2) {
         const int c = 2 * sg + c2;                   // MFMA step within the segment: inputs 16c..16c+15
+        if constexpr (F16) {
+          uint32_t bh[4], bl[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float x0 = wreg[8 * c + 2 * i], x1 = wreg[8 * c + 2 * i + 1];
+            if (p.do_inverse) s_wsq = fmaf(x0, x0, fmaf(x1, x1, s_wsq));
+            const float y0 = x0 * wsc, y1 = x1 * wsc;
+            const auto hh = __builtin_amdgcn_cvt_pkrtz(y0, y1);
+            const auto hl = __builtin_amdgcn_cvt_pkrtz(y0 - float(hh[0]), y1 - float(hh[1]));
+            bh[i] = __builtin_bit_cast(uint32_t, hh);
+            bl[i] = __builtin_bit_cast(uint32_t, hl);
+          }
+          const halfx8 vbh = as_halfx8(bh[0], bh[1], bh[2], bh[3]);
+          const halfx8 vbl = as_halfx8(bl[0], bl[1], bl[2], bl[3]);
+          const int ao = c2 == 0 ? aoff0 : aoff1;
+          halfx8 xh[KT], xl[KT];
+#pragma unroll
+          for (int t = 0; t < KT; ++t) {
+            const unsigned char* ap = sbase + t * (32 * 64) + ao;
+            xh[t] = as_halfx8(*reinterpret_cast<const uintx4*>(ap));
+            xl[t] = as_halfx8(*reinterpret_cast<const uintx4*>(ap + PLANEB));
+          }
+#pragma unroll
+          for (int t = 0; t < KT; ++t) acc[blk * KT + t] = CAFEQ_MFMA_F16(xl[t], vbh, acc[blk * KT + t]);
+#pragma unroll
+          for (int t = 0; t < KT; ++t) acc[blk * KT + t] = CAFEQ_MFMA_F16(xh[t], vbl, acc[blk * KT + t]);
+#pragma unroll
+          for (int t = 0; t < KT; ++t) acc[blk * KT + t] = CAFEQ_MFMA_F16(xh[t], vbh, acc[blk * KT + t]);
+        } else {
         uint32_t bh[4], bm[4], bl[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -461,6 +521,7 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
         for (int t = 0; t < KT; ++t) acc[blk * KT + t] = CAFEQ_MFMA_BF16(xh[t], vbm, acc[blk * KT + t]);
 #pragma unroll
         for (int t = 0; t < KT; ++t) acc[blk * KT + t] = CAFEQ_MFMA_BF16(xh[t], vbh, acc[blk * KT + t]);
+        }
       }
       // The stage consumed D steps from now was issued D - 1 steps ago and must have landed
       // before the barrier.  Loads complete in order, so it has once only younger loads are
@@ -468,6 +529,13 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
       vm_wait(D == 2 ? nw : 0);
       __syncthreads();
       stage = stage == NSTG - 1 ? 0 : stage + 1;
+    }
+    if constexpr (F16) {
+      // back to the units of Z: exact (powers of two) unless the result leaves the float32 range
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] *= usc;
     }
 
     // ---- optional raw output Z
@@ -702,7 +770,7 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
               dma(p.Ainv, kInvPlanes, cb[tq / KT], tq % KT, dst);
             } else {
               nw = NFW;
-              dma(p.Afwd, kFwdPlanes, nbk[(tq - NT) / KT], (tq - NT) % KT, dst);
+              dma(p.Afwd, FWDP, nbk[(tq - NT) / KT], (tq - NT) % KT, dst);
             }
           }
           // The next strip's weights, right behind the first inverse stage's fill: they are

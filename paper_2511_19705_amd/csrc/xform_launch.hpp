@@ -14,9 +14,13 @@ constexpr size_t core_lds_bytes_t(bool do_grad) {
   return size_t(g::RINGB) + (do_grad ? size_t(g::GRADB) : 0) + size_t(g::MISCB);
 }
 
-template <int K, int G, int AXIS, bool GRAD>
+// The half-precision forward variant exists for 128 x 128 blocks with one block per segment.
+template <int K, int G>
+constexpr bool core_has_f16() { return K == 128 && Geo<K, G>::NBLK == 1; }
+
+template <int K, int G, int AXIS, bool GRAD, bool F16 = false>
 int launch_core_v(const CoreParams& p, size_t lds, hipStream_t st) {
-  auto kern = xform_core_kernel<K, G, AXIS, GRAD>;
+  auto kern = xform_core_kernel<K, G, AXIS, GRAD, F16>;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -33,8 +37,13 @@ template <int K, int G, int AXIS>
 int launch_core_t(const CoreParams& p, hipStream_t st) {
   const size_t lds = core_lds_bytes_t<K, G>(p.do_grad != 0);
   if (lds == 0 || lds > kMaxLds) return CAFEQ_ERR_UNSUPPORTED;
+  // half-precision forward planes (p.fscale set): only for the gradient-free variant, where it exists
+  if (p.fscale && (p.do_grad || !core_has_f16<K, G>())) return CAFEQ_ERR_INVALID_ARG;
   if constexpr (Geo<K, G>::GRAD_OK) {
     if (p.do_grad) return launch_core_v<K, G, AXIS, true>(p, lds, st);
+  }
+  if constexpr (core_has_f16<K, G>()) {
+    if (p.fscale) return launch_core_v<K, G, AXIS, false, true>(p, lds, st);
   }
   return launch_core_v<K, G, AXIS, false>(p, lds, st);
 }
