@@ -13,12 +13,14 @@ dominant (fused transform) kernel measured with HIP events on the launch stream 
 timed region, and the CPU oracle timed on the host cores on a bounded sample.
 
 The loss pass of the fused kernel (forward transform, quantizer, inverse transform of the
-rounding error, loss partials) runs its two contractions on the bfloat16 matrix pipe with every
-float32 operand split exactly into three bfloat16 parts (6 + 3 part products, float32
-accumulation); the gradient through the transformed weights is a second, shorter pass over the
-same weights.  The roofline line prices the ALGORITHMIC work of the loss pass, 2 * 2k flop per
-weight element, against the dense bfloat16 peak; the executed part products (4.5x as many
-flops) and the float32 matrix peak the split replaces are given beside it for context.
+rounding error, loss partials) runs its two contractions on the 16-bit matrix pipe with float32
+operands split into 16-bit parts: the forward transform on two float16 parts per operand (scaled
+by powers of two per line and per block; three part products), the inverse transform of the
+error on bfloat16 parts (three part products), float32 accumulation; the gradient through the
+transformed weights is a second, shorter pass over the same weights.  The roofline line prices
+the ALGORITHMIC work of the loss pass, 2 * 2k flop per weight element, against the dense 16-bit
+peak (2.5 PFLOP/s for float16 and bfloat16 alike); the executed part products (3x as many flops)
+and the float32 matrix peak the split replaces are given beside it for context.
 """
 from __future__ import annotations
 
@@ -38,7 +40,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the fused kernel on this workload, from the two rocprofv3 --pmc runs
 # summarised in profiles/xform_core_c3_pair.md (FETCH_SIZE and WRITE_SIZE, each scaled by
 # what the same counter reads for a plain 1 GiB copy); None for any other workload.
-MEASURED_TRAFFIC_BYTES = {"c3_pair_3584x14336_k128_g128_b3": (2.0 * 168382 + 24288) * 1024}
+MEASURED_TRAFFIC_BYTES = {"c3_pair_3584x14336_k128_g128_b3": (2.0 * 151724 + 21500) * 1024}
 
 
 def _cores():
@@ -85,7 +87,7 @@ def other_workload(args):
         elems, k = A.numel() + B.numel(), cfg["k"]
         run = lambda n: cafeq.optimize_pair(A, B, T, cfg["bits"][0], cfg["group"], 1, 5.0, 1e-3, n)
         metric = "learning iterations, weight-elements/s (Adam on the LogSumExp surrogate, 9B-shaped MLP pair)"
-        flop_el, parts, kern = 4 * k, 9, "xform_core_kernel<128,128,*,false> (loss pass)"
+        flop_el, parts, kern = 4 * k, 6, "xform_core_kernel<128,128,*,false,true> (loss pass)"
 
         def cpu():
             from oracle import cafeq_oracle as O
@@ -306,7 +308,7 @@ def main():
     flops_per_launch = 2.0 * 2.0 * k * member
     avg_launch_s = core_ms / 1e3 / max(n_launch, 1)
     achieved = flops_per_launch / avg_launch_s / 1e12
-    executed = 9.0 * 2.0 * k * member / avg_launch_s / 1e12
+    executed = 6.0 * 2.0 * k * member / avg_launch_s / 1e12   # 3 + 3 part products per contraction index
     result = {
         "metric": "proxy-loss fwd+bwd weight-elements/s (9B-shaped MLP pair, dual transform)",
         "value": value, "unit": "weight-elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -315,12 +317,12 @@ def main():
         "config": {"workload": cfg["name"], "rows_cols": [list(cfg["A"].shape), list(cfg["B"].shape)],
                    "block": k, "group": g, "bits": bits, "evals_per_s": args.steps / dt,
                    "step": "block inverse + dual proxy-loss fwd+bwd (loss pass + gradient pass per member)",
-                   "contraction": "float32 operands split exactly into 3 bfloat16 parts, float32 accumulate",
+                   "contraction": "forward: 2 float16 parts per operand, 3 products; inverse: bfloat16 parts, 3 products; float32 accumulate",
                    "relative_l2_A": float((losses[2] / float((cfg["A"].astype("float64") ** 2).sum())) ** 0.5)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg["name"]),
-                     "kernel": "xform_core_kernel<128,128,*,false> (loss pass)", "launches": n_launch,
+                     "kernel": "xform_core_kernel<128,128,*,false,true> (loss pass)", "launches": n_launch,
                      "avg_launch_us": avg_launch_s * 1e6,
                      "algorithmic_flop_per_element": 4 * k, "algorithmic_bytes_per_element": 4,
                      "executed_part_product_tflops": executed,
