@@ -30,6 +30,9 @@
 //              (hi, mid) are therefore staged through LDS transposed ([m][line]) and each wave
 //              accumulates its share of the k x k tiles in registers with 3 products per step.
 // Products of bfloat16 pairs are exact in fp32, so the only roundings are the accumulations.
+// The gradient-free variant over 128 x 128 blocks (F16 below) runs the forward contraction on TWO
+// float16 parts per operand instead (11 significant bits each; three products hi.hi, hi.lo, lo.hi;
+// power-of-two scaling per line and per block keeps the parts inside float16's exponent range).
 //
 // The transform tiles (32 outputs x K inputs, pre-split into bf16 planes by a preparation
 // kernel, columns permuted so that a lane's eight inputs are one 128-bit LDS read) stream
