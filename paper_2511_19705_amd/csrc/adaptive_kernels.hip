@@ -252,6 +252,7 @@ struct GjArgs {
   float* out;            // [nb][K][K]
   float* rho_row; float* rho_col;  // optional squared row / column norms of the inverse
   int* status; int status_stride, status_offset;
+  const int* need;       // optional [nb]: blocks whose entry is 0 are already done (see rotation_inverse_kernel)
 };
 
 // Compile-time loop: f(integral_constant<int, I>) for I in [B, E).
@@ -328,6 +329,7 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_panel_kernel(const GjA
   __shared__ float cn[K];
   __shared__ S wred[16];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  if (a.need && a.need[b] == 0) return;   // uniform over the workgroup
   const int rt = tid / NCT, ct = tid % NCT;
   S reg[RT][CT];
   if (a.partial == nullptr) {
@@ -651,6 +653,100 @@ __global__ __launch_bounds__(256) void eye_minus_kernel(const double* __restrict
 }  // namespace
 
 namespace {
+// Fast path of the blockwise inverse for blocks that are rotations to float32 accuracy -- the paper's
+// initialisation of the transform: the inverse is then the transpose.  One workgroup per block, one wave
+// per 32 x 32 tile: T goes to LDS in both orientations (row stride K + 1 words: rows and columns are both
+// read without bank conflicts), R = I - T T^T is formed on the float32 matrix pipe, and if max |R| is at the
+// level of its own accumulation noise (2e-6) the block is finished here: Tinv = T^T, its squared row /
+// column norms, status 0, need[b] = 0.  Any other block is left to the elimination kernel (need[b] = 1),
+// which skips the finished ones.  (Newton rounds X <- X + X R on this pipe were tried for blocks a little
+// further from a rotation: each round leaves about 3e-6 of relative error, the noise of R; not kept.)
+template <int K>
+__global__ __launch_bounds__((K / 32) * (K / 32) * 64) void rotation_inverse_kernel(
+    const float* __restrict__ T, float* __restrict__ Tinv, float* __restrict__ rho_row, float* __restrict__ rho_col,
+    int* __restrict__ status, int* __restrict__ need) {
+  constexpr int NTL = K / 32, NW = NTL * NTL, NTHR = NW * 64, LD = K + 1;
+  extern __shared__ __align__(16) float nsm[];
+  float* bufT = nsm;                 // T[i][l]
+  float* bufX = nsm + K * LD;        // T^T[l][j]
+  float* red = bufX + K * LD;        // [NW]
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ln = lane & 31, h = lane >> 5, wi = wave / NTL, wj = wave % NTL;
+  const float* Tb = T + size_t(b) * K * K;
+  for (int e = tid * 4; e < K * K; e += NTHR * 4) {
+    const float4 v = *reinterpret_cast<const float4*>(Tb + e);
+    const int r = e / K, c = e % K;
+    float* d = bufT + r * LD + c;
+    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+    bufX[(c + 0) * LD + r] = v.x; bufX[(c + 1) * LD + r] = v.y;
+    bufX[(c + 2) * LD + r] = v.z; bufX[(c + 3) * LD + r] = v.w;
+  }
+  __syncthreads();
+  // cheap necessary condition first: rows of unit length (most blocks that are no rotations leave here)
+  {
+    float dev = 0.f;
+    if (tid < K) {
+      float n2 = 0.f;
+      for (int c = 0; c < K; ++c) { const float x = bufX[c * LD + tid]; n2 = fmaf(x, x, n2); }
+      dev = fabsf(n2 - 1.f);
+      if (!(dev <= 3.0e38f)) dev = INFINITY;
+    }
+    dev = cluster_allmax<64>(dev);
+    if (lane == 0) red[wave] = dev;
+    __syncthreads();
+    float dmax = red[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) dmax = fmaxf(dmax, red[w]);
+    __syncthreads();
+    if (!(dmax <= 4e-6f)) {
+      if (tid == 0) need[b] = 1;
+      return;
+    }
+  }
+  floatx16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  {
+    const float* pa = bufT + (wi * 32 + ln) * LD + h;   // a(l, i) = T[i][l], l = 2 s + h
+    const float* pb = bufX + h * LD + wj * 32 + ln;      // b(l, j) = T^T[l][j]
+#pragma unroll 8
+    for (int s2 = 0; s2 < K / 2; ++s2) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[2 * s2], pb[2 * s2 * LD], acc, 0, 0, 0);
+  }
+  float m = 0.f;
+  bool bad = false;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int i = wi * 32 + 8 * (v / 4) + 4 * h + (v % 4), j = wj * 32 + ln;
+    const float ar = fabsf((i == j ? 1.f : 0.f) - acc[v]);
+    bad = bad || !(ar <= 3.0e38f);             // infinity or not a number
+    m = fmaxf(m, ar);
+  }
+  if (bad) m = INFINITY;
+  m = cluster_allmax<64>(m);
+  if (lane == 0) red[wave] = m;
+  __syncthreads();
+  float rmax = red[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) rmax = fmaxf(rmax, red[w]);
+  const bool ok = rmax <= 2e-6f;
+  if (tid == 0) need[b] = ok ? 0 : 1;
+  if (!ok) return;
+  float* O = Tinv + size_t(b) * K * K;
+  for (int e = tid; e < K * K; e += NTHR) O[e] = bufX[(e / K) * LD + (e % K)];
+  if (tid < K) {
+    float rr = 0.f, rc = 0.f;
+    for (int c = 0; c < K; ++c) {
+      const float x = bufX[tid * LD + c], d = bufX[c * LD + tid];
+      rr = fmaf(x, x, rr); rc = fmaf(d, d, rc);
+    }
+    if (rho_row) rho_row[size_t(b) * K + tid] = rr;
+    if (rho_col) rho_col[size_t(b) * K + tid] = rc;
+  }
+  if (status && tid == 0) status[b] = 0;
+}
+}  // namespace
+
+namespace {
 int launch_gj(const GjArgs& a, int nb, hipStream_t st) {
   // the Gram matrices of the adaptive rounding are symmetric positive definite: no pivot search there
   const bool piv = a.partial == nullptr;
@@ -733,6 +829,7 @@ int launch_gj_solve(int K, int nb, int nz, const float* partial, double* work, f
                     float* out, int* status, int status_stride, int status_offset, hipStream_t st) {
   GjArgs a;
   a.mode = 0; a.K = K; a.nz = nz; a.T = nullptr; a.partial = partial; a.work = work; a.out = Sinv;
+  a.need = nullptr;
   a.rho_row = a.rho_col = nullptr; a.status = status; a.status_stride = status_stride;
   a.status_offset = status_offset;
   int rc = launch_gj(a, nb, st);
@@ -760,6 +857,27 @@ int launch_block_inverse(const float* T, int K, int nb, double* work, float* Tin
   GjArgs a;
   a.mode = 0; a.K = K; a.nz = 0; a.T = T; a.partial = nullptr; a.work = work; a.out = Tinv;
   a.rho_row = rho_row; a.rho_col = rho_col; a.status = status; a.status_stride = 1; a.status_offset = 0;
+  a.need = nullptr;
+  if (K == 64 || K == 128) {
+    // rotations (to float32 accuracy) are inverted by transposition; the elimination then only runs for
+    // the blocks that are none (flags at the start of the work buffer)
+    int* need = reinterpret_cast<int*>(work);
+    const size_t lds = size_t(2 * K * (K + 1) + (K / 32) * (K / 32)) * sizeof(float);
+    if (K == 128) {
+      static bool attr_set = false;
+      if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(rotation_inverse_kernel<128>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
+          return CAFEQ_ERR_LAUNCH;
+        attr_set = true;
+      }
+      hipLaunchKernelGGL(rotation_inverse_kernel<128>, dim3(nb), dim3(1024), lds, st, T, Tinv, rho_row, rho_col, status, need);
+    } else {
+      hipLaunchKernelGGL(rotation_inverse_kernel<64>, dim3(nb), dim3(256), lds, st, T, Tinv, rho_row, rho_col, status, need);
+    }
+    CAFEQ_CHECK_LAUNCH();
+    a.need = need;
+  }
   if (K != 256) return launch_gj(a, nb, st);
   // K == 256 is eliminated in float32; one Newton step X <- X + X (I - T X) with float64
   // residuals brings the result back to float32 rounding accuracy.
