@@ -221,3 +221,31 @@ def test_paired_quantization_error_against_the_definition(env, k, group, rep, bi
                      _dev(torch, sv1.astype(np.float32)), bits, group, k, rep).cpu().numpy().astype(np.float64)
     parity.check_scalar(out1[0], p1_abs ** 2, what="pqe_sq after Alg. 1")
     assert p1_abs < p_abs and out1[0] < out[0]
+
+
+@pytest.mark.parametrize("k", [64, 128])
+def test_block_inverse_of_rotations_and_of_their_neighbours(env, k):
+    """Blocks that are rotations to float32 accuracy take the transposition path, every other block of
+    the same call the elimination: exact rotations, rotations perturbed at 1e-7 .. 1e-2, a scaled
+    rotation and a reflection, all to the accuracy of the elimination's float32 output."""
+    torch, cafeq = env
+    rng = np.random.default_rng(300 + k)
+    H = WL.haar_blocks(8, k, 301 + k).astype(np.float64)
+    T = H.copy()
+    for b, eps in ((1, 1e-7), (2, 1e-6), (3, 1e-5), (4, 1e-3), (5, 1e-2)):
+        T[b] += eps * rng.standard_normal((k, k))
+    T[6] *= 1.0 + 1e-4                                        # unit directions, wrong length
+    T[7][:, 0] *= -1.0                                        # a reflection is orthogonal too
+    T = T.astype(np.float32)
+    Tinv, rr, rc_, status = cafeq.block_inverse(_dev(torch, T), want_rho=True)
+    torch.cuda.synchronize()
+    assert int(status.abs().sum()) == 0
+    for b in range(8):
+        ref = np.linalg.inv(T[b].astype(np.float64))
+        got = Tinv[b].cpu().numpy().astype(np.float64)
+        np.testing.assert_allclose(got, ref, rtol=0, atol=2e-6 * np.abs(ref).max(), err_msg="block %d" % b)
+        np.testing.assert_allclose(rr.cpu().numpy()[b * k:(b + 1) * k], (ref ** 2).sum(1), rtol=1e-5)
+        np.testing.assert_allclose(rc_.cpu().numpy()[b * k:(b + 1) * k], (ref ** 2).sum(0), rtol=1e-5)
+    # exact rotations come back as the transpose, bit for bit
+    for b in (0, 7):
+        np.testing.assert_array_equal(Tinv[b].cpu().numpy(), T[b].T)
