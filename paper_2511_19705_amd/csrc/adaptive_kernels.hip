@@ -588,12 +588,27 @@ __global__ __launch_bounds__(256) void bgemm_f64acc_kernel(const AT* __restrict_
   double* Cb = C + size_t(b) * K * K;
   const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
   double acc[4][4] = {};
+  // the next chunk of 16 contraction indices is fetched into registers while the current one is multiplied
+  AT pa[4];
+  BT pb[4];
+  auto fetch = [&](int l0) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int e = threadIdx.x + 256 * q;
+      pa[q] = Ab[(i0 + e / 16) * K + l0 + e % 16];
+      pb[q] = Bb[(l0 + e / 64) * K + j0 + e % 64];
+    }
+  };
+  fetch(0);
   for (int l0 = 0; l0 < K; l0 += 16) {
-    for (int e = threadIdx.x; e < 16 * 64; e += 256) {
-      sa[e % 16][e / 16] = double(Ab[(i0 + e / 16) * K + l0 + e % 16]);
-      sb[e / 64][e % 64] = double(Bb[(l0 + e / 64) * K + j0 + e % 64]);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int e = threadIdx.x + 256 * q;
+      sa[e % 16][e / 16] = double(pa[q]);
+      sb[e / 64][e % 64] = double(pb[q]);
     }
     __syncthreads();
+    if (l0 + 16 < K) fetch(l0 + 16);
 #pragma unroll
     for (int l = 0; l < 16; ++l) {
       double av[4], bv[4];
