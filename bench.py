@@ -242,6 +242,58 @@ def infer_workload(args):
     print(json.dumps(res))
 
 
+def rtn_workload(args):
+    """Plain per-group round-to-nearest (no transform) of the first member of the 9B-shaped pair ([3584][14336],
+    groups of 128 along the contiguous axis): the HBM-bound stage of the path.
+    Algorithmic bytes per element: 4 read + 1 code + 4/g scale."""
+    import numpy as np
+    import torch
+    from paper_2511_19705_amd import cafeq, workloads as WL
+    dev = torch.device("cuda:0")
+    cfg = WL.config3()
+    W = torch.from_numpy(cfg["A"]).to(dev)
+    g, bits = cfg["group"], cfg["bits"][0]
+    elems = W.numel()
+    run = lambda: cafeq.rtn_quantize(W, bits, g, 0)
+    for _ in range(max(args.warmup, 1)):
+        run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kern_s = e0.elapsed_time(e1) / args.steps * 1e-3
+    byts = elems * (4 + 1 + 4.0 / g)
+    achieved = byts / kern_s / 1e9
+    res = {"metric": "round-to-nearest weight-elements/s (9B-shaped projection, no transform)",
+           "value": elems * args.steps / dt, "unit": "weight-elements/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "c3_rtn_3584x14336_g%d_b%d" % (g, bits), "group": g, "bits": bits},
+           "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": achieved / HBM_PEAK_GBS,
+                        # FETCH_SIZE x 2.0 + WRITE_SIZE of profiles/rtn_col_fast_c3_member.md, bytes per launch
+                        "traffic": (2.0 * 100383 + 51745) * 1024, "kernel": "rtn_col_fast<F32Tag, 32>",
+                        "avg_launch_us": kern_s * 1e6, "algorithmic_bytes_per_element": 4 + 1 + 4.0 / g}}
+    if not args.no_cpu_baseline:
+        from oracle import cafeq_oracle as O
+        rows = 512
+        w = cfg["A"][:rows]
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            O.rtn_sym(w, bits, g, O.COL)
+            reps += 1
+        dtc = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": w.size * reps / dtc, "unit": "weight-elements/s", "cores": _cores(), "kind": "oracle",
+                               "sample": "%d of %d rows, %d repetitions, %.1f s" % (rows, cfg["A"].shape[0], reps, dtc)}
+    print(json.dumps(res))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -250,7 +302,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-blocks", type=int, default=112)
     ap.add_argument("--cpu-reps", type=int, default=4)
-    ap.add_argument("--workload", default="c3_pair", choices=["c3_pair", "c3_optimize", "c2_single", "c4_adaptive", "c2_infer", "c3_infer"],
+    ap.add_argument("--workload", default="c3_pair", choices=["c3_pair", "c3_optimize", "c2_single", "c4_adaptive", "c2_infer", "c3_infer", "c3_rtn"],
                     help="c3_pair is the headline metric; the others are secondary measurements")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for the profiler's byte counters)")
@@ -265,6 +317,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.workload in ("c2_infer", "c3_infer"):
         return infer_workload(args)
+    if args.workload == "c3_rtn":
+        return rtn_workload(args)
     if args.workload != "c3_pair":
         return other_workload(args)
     dev = torch.device("cuda:0")
