@@ -759,6 +759,123 @@ __global__ __launch_bounds__((K / 32) * (K / 32) * 64) void rotation_inverse_ker
   }
   if (status && tid == 0) status[b] = 0;
 }
+// Warm start for the learning loops, where the transform moves a little per iteration and the previous
+// inverse X_0 is at hand: Newton's iteration  X <- X + X (I - T X), one workgroup per block, one wave per
+// 32 x 32 tile, T and X in LDS; residuals on the float32 matrix pipe, corrections with bfloat16 operands.  The residual R = I - T X is measured every round;
+// at the level of its own accumulation noise (4e-6) X stands, a round that promises max|R^2| <= 4e-6 (by
+// K max|R|^2 or by the squared Frobenius norm) is the last, and a block whose residual is not a safe
+// contraction (Frobenius norm >= 1/2) or is not done in three rounds is left to the elimination kernel
+// (need[b] = 1).  The result carries the noise of R, about 3e-6 relative --
+// below the 16-bit operand parts the loss pass makes of it, but above the elimination's float32 rounding, so
+// the inverse a loop hands back to its caller is always recomputed by the elimination.
+template <int K>
+__global__ __launch_bounds__((K / 32) * (K / 32) * 64) void newton_inverse_kernel(const float* __restrict__ T,
+                                                                                   float* __restrict__ X,
+                                                                                   int* __restrict__ status,
+                                                                                   int* __restrict__ need) {
+  constexpr int NTL = K / 32, NW = NTL * NTL, NTHR = NW * 64, LD = K + 1;
+  extern __shared__ __align__(16) float nsm[];
+  float* bufT = nsm;                 // T[i][l], later R transposed in bfloat16 (rtb)
+  uint16_t* rtb = reinterpret_cast<uint16_t*>(nsm);
+  constexpr int LDB = K + 8;         // bfloat16 elements per row of rtb: 16-byte aligned rows
+  float* bufX = nsm + K * LD;        // X[l][j]
+  float* red = bufX + K * LD;        // [2 NW]: max |R| and sum R^2 of each wave's tile
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ln = lane & 31, h = lane >> 5, wi = wave / NTL, wj = wave % NTL;
+  const float* Tb = T + size_t(b) * K * K;
+  float* Xb = X + size_t(b) * K * K;
+  auto load = [&](const float* src, float* dst) {
+    for (int e = tid * 4; e < K * K; e += NTHR * 4) {
+      const float4 v = *reinterpret_cast<const float4*>(src + e);
+      float* d = dst + (e / K) * LD + (e % K);
+      d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+    }
+  };
+  load(Tb, bufT);
+  load(Xb, bufX);
+  __syncthreads();
+  bool ok = false, changed = false;
+#pragma unroll 1
+  for (int it = 0; it < 3; ++it) {
+    floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    {
+      const float* pa = bufT + (wi * 32 + ln) * LD + h;   // a(l, i) = T[i][l], l = 2 s + h
+      const float* pb = bufX + h * LD + wj * 32 + ln;      // b(l, j) = X[l][j]
+#pragma unroll 8
+      for (int s2 = 0; s2 < K / 2; ++s2) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[2 * s2], pb[2 * s2 * LD], acc, 0, 0, 0);
+    }
+    float r[16], m = 0.f, q = 0.f;
+    bool bad = false;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int i = wi * 32 + 8 * (v / 4) + 4 * h + (v % 4), j = wj * 32 + ln;
+      r[v] = (i == j ? 1.f : 0.f) - acc[v];
+      const float ar = fabsf(r[v]);
+      bad = bad || !(ar <= 3.0e38f);           // infinity or not a number
+      m = fmaxf(m, ar);
+      q = fmaf(ar, ar, q);
+    }
+    if (bad) m = INFINITY;
+    m = cluster_allmax<64>(m);
+    q = wave_sum(q);
+    if (lane == 0) { red[wave] = m; red[NW + wave] = q; }
+    __syncthreads();                           // also: every wave has finished reading bufT
+    float rmax = red[0], fro2 = red[NW];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) { rmax = fmaxf(rmax, red[w]); fro2 += red[NW + w]; }
+    if (!(fro2 < 0.25f)) break;                // ||R||_2 <= ||R||_F; not a contraction to count on: elimination
+    if (rmax <= 4e-6f) { ok = true; break; }   // the residual is float32 accumulation noise: X stands
+    // The correction X R needs no more than 16-bit operands: what their rounding leaves (2^-8 of the
+    // correction) is part of the next round's residual, and below float32 noise in the last round.
+    // R goes to LDS transposed, in bfloat16, over the rows of the old T.
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int i0 = wi * 32 + 8 * g + 4 * h, j = wj * 32 + ln;
+      uint2 pk;
+      pk.x = pack_bf16(r[4 * g], r[4 * g + 1]);
+      pk.y = pack_bf16(r[4 * g + 2], r[4 * g + 3]);
+      *reinterpret_cast<uint2*>(rtb + j * LDB + i0) = pk;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    {
+      const float* pa = bufX + (wi * 32 + ln) * LD + 8 * h;          // a(l, i) = X[i][l], l = 16 s + 8 h + e
+      const uint16_t* pb = rtb + (wj * 32 + ln) * LDB + 8 * h;       // b(l, j) = R[l][j] = RT[j][l]
+#pragma unroll 4
+      for (int s2 = 0; s2 < K / 16; ++s2) {
+        const float* x = pa + 16 * s2;
+        const bf16x8 av = as_bf16x8(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
+        const bf16x8 bv = as_bf16x8(*reinterpret_cast<const uintx4*>(pb + 16 * s2));
+        acc = CAFEQ_MFMA_BF16(av, bv, acc);
+      }
+    }
+    float xn[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int i = wi * 32 + 8 * (v / 4) + 4 * h + (v % 4), j = wj * 32 + ln;
+      xn[v] = bufX[i * LD + j] + acc[v];
+    }
+    __syncthreads();                           // every wave has finished reading bufX and bufT
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int i = wi * 32 + 8 * (v / 4) + 4 * h + (v % 4), j = wj * 32 + ln;
+      bufX[i * LD + j] = xn[v];
+    }
+    changed = true;
+    if (fminf(float(K) * rmax * rmax, fro2) <= 4e-6f) { ok = true; break; }   // max |R^2| is below both
+    load(Tb, bufT);                            // T again for the next round's residual
+    __syncthreads();
+  }
+  __syncthreads();
+  if (tid == 0) need[b] = ok ? 0 : 1;
+  if (!ok) return;
+  if (changed)
+    for (int e = tid; e < K * K; e += NTHR) Xb[e] = bufX[(e / K) * LD + (e % K)];
+  if (status && tid == 0) status[b] = 0;
+}
 }  // namespace
 
 namespace {
@@ -911,6 +1028,31 @@ int launch_block_inverse(const float* T, int K, int nb, double* work, float* Tin
   if (rho_row && (rc = launch_rho(Tinv, K, nb, 1, rho_row, st))) return rc;
   if (rho_col && (rc = launch_rho(Tinv, K, nb, 0, rho_col, st))) return rc;
   return CAFEQ_OK;
+}
+
+// The inverse inside a learning loop: Tinv holds the previous iteration's inverse on entry.
+int launch_block_inverse_warm(const float* T, int K, int nb, double* work, float* Tinv, int* status, hipStream_t st) {
+  if (K != 64 && K != 128) return launch_block_inverse(T, K, nb, work, Tinv, nullptr, nullptr, status, st);
+  int* need = reinterpret_cast<int*>(work);
+  const size_t lds = size_t(2 * K * (K + 1) + 2 * (K / 32) * (K / 32)) * sizeof(float);
+  if (K == 128) {
+    static bool attr_set = false;
+    if (!attr_set) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(newton_inverse_kernel<128>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
+        return CAFEQ_ERR_LAUNCH;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(newton_inverse_kernel<128>, dim3(nb), dim3(1024), lds, st, T, Tinv, status, need);
+  } else {
+    hipLaunchKernelGGL(newton_inverse_kernel<64>, dim3(nb), dim3(256), lds, st, T, Tinv, status, need);
+  }
+  CAFEQ_CHECK_LAUNCH();
+  GjArgs a;
+  a.mode = 0; a.K = K; a.nz = 0; a.T = T; a.partial = nullptr; a.work = work; a.out = Tinv;
+  a.rho_row = a.rho_col = nullptr; a.status = status; a.status_stride = 1; a.status_offset = 0;
+  a.need = need;
+  return launch_gj(a, nb, st);
 }
 
 }  // namespace cafeq

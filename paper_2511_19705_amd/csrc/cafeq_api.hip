@@ -325,6 +325,11 @@ OptWs carve_opt(void* ws, int k, int nb) {
   w.sub = static_cast<char*>(w.orth) + orth_workspace_bytes(k, nb);
   return w;
 }
+// The inverse of iteration s of a learning loop: from scratch first, then warm-started from the previous one.
+int loop_inverse(int s, const float* T, int k, int nb, float* Tinv, int* status, void* ws, void* stream) {
+  if (s == 0 || (k != 64 && k != 128)) return cafeq_block_inverse(T, k, nb, Tinv, nullptr, nullptr, status, ws, stream);
+  return launch_block_inverse_warm(T, k, nb, static_cast<double*>(ws), Tinv, status, static_cast<hipStream_t>(stream));
+}
 int check_opt(const cafeq_opt_cfg* opt) {
   if (!opt) return CAFEQ_ERR_INVALID_ARG;
   if (opt->steps < 0 || !(opt->lr >= 0.f) || !(opt->lambda_orth >= 0.f)) return CAFEQ_ERR_INVALID_ARG;
@@ -346,7 +351,7 @@ int cafeq_optimize_single(const cafeq_mat* W, float* T, float* Tinv, int k, int 
   if ((rc = launch_fill(history, 0.f, int64_t(opt->steps) * 8, st))) return rc;
   for (int s = 0; s < opt->steps; ++s) {
     float* h = history + size_t(s) * 8;
-    if ((rc = cafeq_block_inverse(T, k, nb, Tinv, nullptr, nullptr, status, w.sub, stream))) return rc;
+    if ((rc = loop_inverse(s, T, k, nb, Tinv, status, w.sub, stream))) return rc;
     if ((rc = cafeq_proxy_loss_fwd_bwd(W, &x, cfg, h, w.grad, nullptr, nullptr, w.sub, stream))) return rc;
     // surrogate / ||W||^2 (history[s][2]) when normalised, then the regulariser's gradient on top
     if (opt->normalize && (rc = launch_div_by_device_scalar(w.grad, h + 2, n, st))) return rc;
@@ -373,7 +378,7 @@ int cafeq_optimize_pair(const cafeq_mat* A, const cafeq_mat* B, float* T, float*
   if ((rc = launch_fill(moments, 0.f, 2 * n, st))) return rc;
   for (int s = 0; s < opt->steps; ++s) {
     float* h = history + size_t(s) * 8;
-    if ((rc = cafeq_block_inverse(T, k, nb, Tinv, nullptr, nullptr, status, w.sub, stream))) return rc;
+    if ((rc = loop_inverse(s, T, k, nb, Tinv, status, w.sub, stream))) return rc;
     if ((rc = cafeq_dual_proxy_loss_fwd_bwd(A, B, &x, cfg, lse_t, h, w.grad, nullptr, nullptr, nullptr, nullptr, w.sub,
                                             stream)))
       return rc;

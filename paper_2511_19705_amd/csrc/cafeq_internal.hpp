@@ -68,6 +68,9 @@ int launch_gram_pair(int axis, const float* X, const int8_t* codes, const float*
                      hipStream_t st);
 int launch_gj_solve(int K, int nb, int nz, const float* partial, double* work, float* Sinv, float* R,
                     float* out, int* status, int status_stride, int status_offset, hipStream_t st);
+// inside a learning loop: Tinv holds the previous inverse on entry (Newton warm start, elimination as fallback);
+// accurate to about 3e-6 relative
+int launch_block_inverse_warm(const float* T, int K, int nb, double* work, float* Tinv, int* status, hipStream_t st);
 int launch_block_inverse(const float* T, int K, int nb, double* work, float* Tinv, float* rho_row,
                          float* rho_col, int* status, hipStream_t st);
 
