@@ -74,7 +74,8 @@ def other_workload(args):
     """Secondary workloads (not the headline metric): one JSON line each, same fields.
        c3_optimize : Adam iterations on the 9B-shaped pair (inverse + paired fwd+bwd + update)
        c2_single   : single-matrix fwd+bwd on the 2B-shaped down projection (k = 64, fused gradient)
-       c4_adaptive : Alg. 1 iterations on the 9B-shaped attention V/O pair (k = 256)"""
+       c4_adaptive : Alg. 1 iterations on the 9B-shaped attention V/O pair (k = 256)
+       c5_layer    : fwd+bwd over all seven weights of the 27B-shaped decoder layer (bfloat16 storage)"""
     import numpy as np
     import torch
     from paper_2511_19705_amd import cafeq, workloads as WL
@@ -121,6 +122,40 @@ def other_workload(args):
                 O.surrogate(w, t, p_, cfg["bits"][0], cfg["group"], 0, 1)
             dt = time.perf_counter() - t0
             return w.size * 3 / dt, "%d of %d blocks, 3 x (inverse + fwd+bwd), %.1f s" % (nbk, cfg["T"].shape[0], dt)
+    elif args.workload == "c5_layer":
+        # every weight of the 27B-shaped decoder layer, bfloat16 storage: three singles on the model dimension,
+        # the MLP pair (288 blocks) and the attention V/O pair (16 blocks, two query heads per kv head)
+        meta = WL.config5_meta()
+        k, g, bits, rep = meta["k"], meta["group"], meta["bits"][0], meta["rep"]
+        cfg = {"name": "c5_27b_layer_bf16_k%d_g%d_b%d" % (k, g, bits), "group": g, "bits": (bits,)}
+        host = {nm: WL.config5_tensor(nm) for nm in ("q", "k", "gate", "down", "up", "v", "o")}
+        Wd = {nm: torch.from_numpy(t["bits16"].view(np.int16)).to(dev).view(torch.bfloat16) for nm, t in host.items()}
+        Ts = {w: torch.from_numpy(WL.config5_transform(w)).to(dev) for w in ("single", "mlp", "vo")}
+        elems = sum(w.numel() for w in Wd.values())
+
+        def run(n):
+            for _ in range(n):
+                Ps, _ = cafeq.block_inverse(Ts["single"])
+                for nm in ("q", "k", "gate"):
+                    cafeq.proxy_loss_fwd_bwd(Wd[nm], Ts["single"], Ps, bits, g, 0, 1, want_grad=True)
+                Pm, _ = cafeq.block_inverse(Ts["mlp"])
+                cafeq.dual_proxy_loss_fwd_bwd(Wd["down"], Wd["up"], Ts["mlp"], Pm, bits, g, 1, 5.0, want_grad=True)
+                Pv, _ = cafeq.block_inverse(Ts["vo"])
+                cafeq.dual_proxy_loss_fwd_bwd(Wd["v"], Wd["o"], Ts["vo"], Pv, bits, g, rep, 5.0, want_grad=True)
+        metric = "proxy-loss fwd+bwd weight-elements/s (27B-shaped decoder layer: q, k, gate singles; down/up and V/O pairs)"
+        flop_el, parts, kern = 4 * k, 6, "xform_core_kernel<128,128,*,*> (bfloat16 storage; loss passes and fused singles)"
+
+        def cpu():
+            from oracle import cafeq_oracle as O
+            w = WL.bf16_bits_to_f32(host["q"]["bits16"])
+            t = WL.config5_transform("single")
+            t0 = time.perf_counter()
+            for _ in range(4):
+                p_ = O.block_inverse(t)
+                O.proxy_l2(w, t, p_, bits, g, 0, 1)
+                O.surrogate(w, t, p_, bits, g, 0, 1)
+            dt = time.perf_counter() - t0
+            return w.size * 4 / dt, "the q projection (4096 x 4608, 36 blocks), 4 x (inverse + fwd+bwd), %.1f s" % dt
     else:
         cfg = WL.config4()
         k, rep, g, bits = cfg["k"], cfg["rep"], cfg["group"], cfg["bits"][0]
@@ -302,7 +337,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-blocks", type=int, default=112)
     ap.add_argument("--cpu-reps", type=int, default=4)
-    ap.add_argument("--workload", default="c3_pair", choices=["c3_pair", "c3_optimize", "c2_single", "c4_adaptive", "c2_infer", "c3_infer", "c3_rtn"],
+    ap.add_argument("--workload", default="c3_pair", choices=["c3_pair", "c3_optimize", "c2_single", "c4_adaptive", "c5_layer", "c2_infer", "c3_infer", "c3_rtn"],
                     help="c3_pair is the headline metric; the others are secondary measurements")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for the profiler's byte counters)")
