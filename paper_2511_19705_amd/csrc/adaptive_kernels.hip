@@ -574,58 +574,69 @@ __global__ __launch_bounds__(256) void sum_r_init_c_kernel(const float* __restri
 
 
 // Float64-accumulating batched product for the iterative refinement of the K = 256 solve:
-// C_b (double) = alpha * A_b B_b + beta * C_b, A and B float or double, 64 x 64 tile per workgroup.
+// C_b (double) = alpha * A_b B_b + beta * C_b, A and B float or double, a 32 x 64 tile per workgroup
+// (the few blocks of a k = 256 workload then give one workgroup per compute unit), 2 x 4 per thread.
 template <typename AT, typename BT>
 __global__ __launch_bounds__(256) void bgemm_f64acc_kernel(const AT* __restrict__ A, const BT* __restrict__ B,
                                                             double* __restrict__ C, int K, double alpha, double beta) {
-  __shared__ double sa[16][66];   // [l][i]
+  __shared__ double sa[16][34];   // [l][i]
   __shared__ double sb[16][66];   // [l][j]
-  const int tpr = K / 64;
-  const int b = blockIdx.x / (tpr * tpr), tile = blockIdx.x % (tpr * tpr);
-  const int i0 = (tile / tpr) * 64, j0 = (tile % tpr) * 64;
+  const int tpc = K / 64, tpr = K / 32;
+  const int b = blockIdx.x / (tpr * tpc), tile = blockIdx.x % (tpr * tpc);
+  const int i0 = (tile / tpc) * 32, j0 = (tile % tpc) * 64;
   const AT* Ab = A + size_t(b) * K * K;
   const BT* Bb = B + size_t(b) * K * K;
   double* Cb = C + size_t(b) * K * K;
   const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
-  double acc[4][4] = {};
+  double acc[2][4] = {};
   // the next chunk of 16 contraction indices is fetched into registers while the current one is multiplied
-  AT pa[4];
+  AT pa[2];
   BT pb[4];
   auto fetch = [&](int l0) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < 2; ++q) {
       const int e = threadIdx.x + 256 * q;
       pa[q] = Ab[(i0 + e / 16) * K + l0 + e % 16];
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int e = threadIdx.x + 256 * q;
       pb[q] = Bb[(l0 + e / 64) * K + j0 + e % 64];
     }
   };
   fetch(0);
   for (int l0 = 0; l0 < K; l0 += 16) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < 2; ++q) {
       const int e = threadIdx.x + 256 * q;
       sa[e % 16][e / 16] = double(pa[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int e = threadIdx.x + 256 * q;
       sb[e / 64][e % 64] = double(pb[q]);
     }
     __syncthreads();
     if (l0 + 16 < K) fetch(l0 + 16);
 #pragma unroll
     for (int l = 0; l < 16; ++l) {
-      double av[4], bv[4];
+      double av[2], bv[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) { av[u] = sa[l][ty * 4 + u]; bv[u] = sb[l][tx * 4 + u]; }
+      for (int u = 0; u < 2; ++u) av[u] = sa[l][ty * 2 + u];
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int v = 0; v < 4; ++v) bv[v] = sb[l][tx * 4 + v];
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
 #pragma unroll
         for (int v = 0; v < 4; ++v) acc[u][v] = fma(av[u], bv[v], acc[u][v]);
     }
     __syncthreads();
   }
 #pragma unroll
-  for (int u = 0; u < 4; ++u)
+  for (int u = 0; u < 2; ++u)
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-      double* dst = Cb + (i0 + ty * 4 + u) * K + j0 + tx * 4 + v;
+      double* dst = Cb + (i0 + ty * 2 + u) * K + j0 + tx * 4 + v;
       *dst = alpha * acc[u][v] + (beta != 0.0 ? beta * *dst : 0.0);
     }
 }
@@ -973,7 +984,7 @@ int launch_gj_solve(int K, int nb, int nz, const float* partial, double* work, f
   }
   const size_t mat = size_t(nb) * K * K;
   double *S64 = work, *R64 = work + mat, *res = work + 2 * mat, *X64 = work + 3 * mat;
-  const unsigned grid = unsigned(nb) * (K / 64) * (K / 64);
+  const unsigned grid = unsigned(nb) * (K / 32) * (K / 64);
   hipLaunchKernelGGL(sum_partials64_kernel, dim3(nb, 32), dim3(256), 0, st, partial, nz, K, S64, R64, res);
   hipLaunchKernelGGL((bgemm_f64acc_kernel<float, double>), dim3(grid), dim3(256), 0, st, Sinv, R64, X64, K, 1.0, 0.0);
   hipLaunchKernelGGL((bgemm_f64acc_kernel<double, double>), dim3(grid), dim3(256), 0, st, S64, X64, res, K, -1.0, 1.0);
@@ -1018,7 +1029,7 @@ int launch_block_inverse(const float* T, int K, int nb, double* work, float* Tin
   if (rc) return rc;
   const size_t mat = size_t(nb) * K * K;
   double *res = work, *X64 = work + mat;
-  const unsigned grid = unsigned(nb) * (K / 64) * (K / 64);
+  const unsigned grid = unsigned(nb) * (K / 32) * (K / 64);
   const int64_t n = int64_t(mat);
   hipLaunchKernelGGL(eye64_kernel, dim3(unsigned((n + 255) / 256)), dim3(256), 0, st, res, K, n);
   hipLaunchKernelGGL((bgemm_f64acc_kernel<float, float>), dim3(grid), dim3(256), 0, st, T, Tinv, res, K, -1.0, 1.0);
