@@ -61,12 +61,15 @@ __global__ __launch_bounds__(256) void gram_pair_kernel(const GramArgs a) {
   const int64_t f0 = AXIS == CAFEQ_AXIS_COL ? int64_t(b) * K : (int64_t(b) * a.rep + qi) * K;
   const int64_t C = a.cols;
 
-  floatx16 accS[2], accR[2], accT[TRIPLE ? 2 : 1];
+  // output tiles of this wave: jt2 = wave + 4u, u < NU; for K < 128 the waves beyond KT have none.  NU is a
+  // compile-time count so that the accumulators stay where the matrix instructions want them.
+  constexpr int NU = (KT + 3) / 4;
+  const bool active = KT >= 4 || wave < KT;   // known at compile time for K >= 128: no branch around the MFMAs
+  floatx16 accS[NU], accR[NU], accT[TRIPLE ? NU : 1];
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
+  for (int u = 0; u < NU; ++u)
 #pragma unroll
     for (int v = 0; v < 16; ++v) { accS[u][v] = 0.f; accR[u][v] = 0.f; accT[TRIPLE ? u : 0][v] = 0.f; }
-  const int nt2 = wave < KT ? (KT - wave + 3) / 4 : 0;   // output tiles of this wave: jt2 = wave + 4u
 
   // ---- loader roles.  COL: thread -> (t = l / (K/EPT), EPT consecutive columns);
   // ROW: NP passes of 64 rows, thread -> (row = pass*64 + l/4, four consecutive t = 4*(l%4) ..)
@@ -155,7 +158,7 @@ __global__ __launch_bounds__(256) void gram_pair_kernel(const GramArgs a) {
     commit();
     __syncthreads();
     if (t + 16 < t1) issue(t + 16);
-    if (nt2 > 0) {
+    if (active) {
       const float* pa = qs + h * LD + jt1 * 32 + ln;
       const float* pe = es + h * LD + jt1 * 32 + ln;
 #pragma unroll
@@ -163,13 +166,12 @@ __global__ __launch_bounds__(256) void gram_pair_kernel(const GramArgs a) {
         const float xa = pa[2 * e * LD];
         const float ea = TRIPLE ? pe[2 * e * LD] : 0.f;
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-          if (u < nt2) {
-            const int off = (2 * e + h) * LD + (wave + 4 * u) * 32 + ln;
-            accS[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa, qs[off], accS[u], 0, 0, 0);
-            accR[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa, es[off], accR[u], 0, 0, 0);
-            if (TRIPLE) accT[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(ea, es[off], accT[TRIPLE ? u : 0], 0, 0, 0);
-          }
+        for (int u = 0; u < NU; ++u) {
+          const int off = (2 * e + h) * LD + (wave + 4 * u) * 32 + ln;
+          accS[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa, qs[off], accS[u], 0, 0, 0);
+          accR[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa, es[off], accR[u], 0, 0, 0);
+          if (TRIPLE) accT[TRIPLE ? u : 0] = __builtin_amdgcn_mfma_f32_32x32x2f32(ea, es[off], accT[TRIPLE ? u : 0], 0, 0, 0);
+        }
       }
     }
     __syncthreads();
@@ -177,9 +179,9 @@ __global__ __launch_bounds__(256) void gram_pair_kernel(const GramArgs a) {
 
   // partial[b][z][0|1(|2)][row][col]
   float* out = a.partial + ((size_t(b) * gridDim.z + z) * (TRIPLE ? 3 : 2)) * size_t(K) * K;
+  if (active)
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
-    if (u < nt2) {
+    for (int u = 0; u < NU; ++u) {
       const int col = (wave + 4 * u) * 32 + ln;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
