@@ -7,17 +7,28 @@ namespace cafeq {
 
 namespace {
 
-// rho[b*K + j]: squared norm of row j (by_row) or column j of P_b.
+// rho[b*K + j]: squared norm of row j (by_row) or column j of P_b, summed in float64.  256 / K threads share a
+// line (K = 256: one each); they take its elements interleaved and meet in LDS, added in thread order.
 __global__ __launch_bounds__(256) void rho_kernel(const float* __restrict__ P, int K, int by_row,
                                                    float* __restrict__ rho) {
+  __shared__ double part[256];
   const float* Pb = P + size_t(blockIdx.x) * K * K;
-  for (int j = threadIdx.x; j < K; j += blockDim.x) {
-    double acc = 0;
-    for (int i = 0; i < K; ++i) {
-      const float v = by_row ? Pb[j * K + i] : Pb[i * K + j];
-      acc += double(v) * v;
-    }
-    rho[size_t(blockIdx.x) * K + j] = float(acc);
+  const int tpl = 256 / K;                       // threads per line: K is 32, 64, 128 or 256
+  // by_row: neighbouring threads share a row (their loads fall into the same cache lines);
+  // by column: neighbouring threads take neighbouring columns (coalesced rows)
+  const int j = by_row ? threadIdx.x / tpl : threadIdx.x % K;
+  const int s = by_row ? threadIdx.x % tpl : threadIdx.x / K;
+  double acc = 0;
+  for (int i = s; i < K; i += tpl) {
+    const float v = by_row ? Pb[j * K + i] : Pb[i * K + j];
+    acc += double(v) * v;
+  }
+  part[s * K + j] = acc;
+  __syncthreads();
+  if (threadIdx.x < K) {
+    double t = part[threadIdx.x];
+    for (int q = 1; q < tpl; ++q) t += part[q * K + threadIdx.x];
+    rho[size_t(blockIdx.x) * K + threadIdx.x] = float(t);
   }
 }
 
@@ -240,19 +251,27 @@ struct VArgs {
 };
 __global__ __launch_bounds__(256) void build_mmid_kernel(const VArgs a) {
   __shared__ float v[256];
-  const int b = blockIdx.x, K = a.K;
-  for (int n = threadIdx.x; n < K; n += blockDim.x) {
-    double acc = 0;
-    for (int q = b * a.rep; q < (b + 1) * a.rep; ++q) {
-      const int64_t ax = int64_t(q) * K + n;        // axis index
-      const int64_t seg = ax / a.L;
-      const int gi = int((ax % a.L) / a.G);
+  __shared__ int rng[2];
+  const int b = blockIdx.x, K = a.K, n = threadIdx.x;   // K <= 256 = blockDim.x: thread n owns index n
+  double acc = 0;
+  for (int q = b * a.rep; q < (b + 1) * a.rep; ++q) {
+    // the K axis indices of a row-block lie in one segment (L is a multiple of K): its range of
+    // workgroups is found once (64-bit divisions) and shared
+    const int64_t seg = (int64_t(q) * K) / a.L;
+    if (n == 0) {
       int lo, hi;
       seg_wg_range(seg, a.mt_per_seg, a.n_mt, a.nwg, &lo, &hi);
+      rng[0] = lo; rng[1] = hi;
+    }
+    __syncthreads();
+    const int lo = rng[0], hi = rng[1];
+    if (n < K) {
+      const int gi = int(((int64_t(q) * K + n) % a.L) / a.G);
       for (int w = lo; w < hi; ++w) acc += a.slot_hdr[(int64_t(w) + seg) * kHdrFloats + kHdrVa2 + gi];
     }
-    v[n] = float(acc * a.beta);
+    __syncthreads();
   }
+  if (n < K) v[n] = float(acc * a.beta);
   __syncthreads();
   const float* Pb = a.P + size_t(b) * K * K;
   float* Mb = a.Mmid + size_t(b) * K * K;
