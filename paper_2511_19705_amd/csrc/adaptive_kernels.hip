@@ -71,28 +71,30 @@ __global__ __launch_bounds__(256) void gram_pair_kernel(const GramArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) { accS[u][v] = 0.f; accR[u][v] = 0.f; accT[TRIPLE ? u : 0][v] = 0.f; }
 
-  // ---- loader roles.  COL: thread -> (t = l / (K/EPT), EPT consecutive columns);
+  // ---- loader roles.  COL: thread -> (t = l / (K/EPT), EPT/4 chunks of four columns, the chunks of the
+  // K/EPT threads of a row interleaved so that their 16-byte LDS stores fall into distinct banks);
   // ROW: NP passes of 64 rows, thread -> (row = pass*64 + l/4, four consecutive t = 4*(l%4) ..)
   constexpr int EPT = K >= 64 ? K / 16 : 4;          // COL: columns per thread
   constexpr int NLD = 16 * K / EPT;                  // COL: active loader threads
   constexpr int NP = (K + 63) / 64;                  // ROW: passes
   uint32_t rc[AXIS == CAFEQ_AXIS_COL ? EPT / 4 : NP];
   float4 rx[AXIS == CAFEQ_AXIS_COL ? EPT / 4 : NP];
-  float4 rs[AXIS == CAFEQ_AXIS_COL ? 1 : NP];        // COL: .x only
+  float4 rs[AXIS == CAFEQ_AXIS_COL ? EPT / 4 : NP];  // COL: .x only, one scale per chunk
+  constexpr int TPR = K / EPT;                       // COL: threads per slab row; chunk j starts at column 4 (l % TPR) + 4 TPR j
   bool rok[AXIS == CAFEQ_AXIS_COL ? 1 : NP];
 
   auto issue = [&](int64_t t) {
     if (AXIS == CAFEQ_AXIS_COL) {
-      const int tt = tid / (K / EPT), c0 = (tid % (K / EPT)) * EPT;
+      const int tt = tid / TPR, c0 = (tid % TPR) * 4;
       const int64_t i = t + tt;
       rok[0] = tid < NLD && i < t1;
       if (rok[0]) {
-        const int64_t col = f0 + c0;
-        rs[0].x = a.scales[i * (C / a.G) + col / a.G];
 #pragma unroll
         for (int j = 0; j < EPT / 4; ++j) {
-          rc[j] = *reinterpret_cast<const uint32_t*>(a.codes + i * C + col + 4 * j);
-          rx[j] = *reinterpret_cast<const float4*>(a.X + i * C + col + 4 * j);
+          const int64_t col = f0 + c0 + 4 * TPR * j;
+          rs[j].x = a.scales[i * (C / a.G) + col / a.G];
+          rc[j] = *reinterpret_cast<const uint32_t*>(a.codes + i * C + col);
+          rx[j] = *reinterpret_cast<const float4*>(a.X + i * C + col);
         }
       }
     } else {
@@ -113,20 +115,20 @@ __global__ __launch_bounds__(256) void gram_pair_kernel(const GramArgs a) {
   auto commit = [&]() {
     if (AXIS == CAFEQ_AXIS_COL) {
       if (tid < NLD) {
-        const int tt = tid / (K / EPT), c0 = (tid % (K / EPT)) * EPT;
+        const int tt = tid / TPR, c0 = (tid % TPR) * 4;
 #pragma unroll
         for (int j = 0; j < EPT / 4; ++j) {
           float4 q = make_float4(0.f, 0.f, 0.f, 0.f), e = q;
           if (rok[0]) {
             const uint32_t cw = rc[j];
-            q.x = __fmul_rn(float(int8_t(cw)), rs[0].x);
-            q.y = __fmul_rn(float(int8_t(cw >> 8)), rs[0].x);
-            q.z = __fmul_rn(float(int8_t(cw >> 16)), rs[0].x);
-            q.w = __fmul_rn(float(int8_t(cw >> 24)), rs[0].x);
+            q.x = __fmul_rn(float(int8_t(cw)), rs[j].x);
+            q.y = __fmul_rn(float(int8_t(cw >> 8)), rs[j].x);
+            q.z = __fmul_rn(float(int8_t(cw >> 16)), rs[j].x);
+            q.w = __fmul_rn(float(int8_t(cw >> 24)), rs[j].x);
             e = make_float4(q.x - rx[j].x, q.y - rx[j].y, q.z - rx[j].z, q.w - rx[j].w);
           }
-          *reinterpret_cast<float4*>(qs + tt * LD + c0 + 4 * j) = q;
-          *reinterpret_cast<float4*>(es + tt * LD + c0 + 4 * j) = e;
+          *reinterpret_cast<float4*>(qs + tt * LD + c0 + 4 * TPR * j) = q;
+          *reinterpret_cast<float4*>(es + tt * LD + c0 + 4 * TPR * j) = e;
         }
       }
     } else {
