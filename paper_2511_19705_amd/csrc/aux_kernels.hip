@@ -173,7 +173,9 @@ struct ReduceArgs {
 
 // grid: (nb transform blocks, K*K/1024).  out_b = sum over the rep row-blocks q of block b, and
 // over the partials of q's segment, in fixed order; each thread owns four consecutive elements.
-__global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceArgs a) {
+struct ReduceJobs { ReduceArgs job[2]; };   // grid.z picks the job (the two members of a pair in one launch)
+__global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceJobs js) {
+  const ReduceArgs& a = js.job[blockIdx.z];
   constexpr int kBatch = 64;
   __shared__ const float* src[kBatch];
   __shared__ float scl[kBatch];
@@ -519,14 +521,33 @@ int launch_rho_groups(const float* rho, int K, int rep, int G, int64_t ngroups, 
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }
-int launch_reduce_grad(const CoreParams& p, int K, int G, int nb, int transpose_out, const double* lse_ms,
-                       const float* member_ref, float* out, hipStream_t st) {
+namespace {
+ReduceArgs reduce_args(const CoreParams& p, int K, int G, int transpose_out, const double* lse_ms,
+                       const float* member_ref, float* out) {
   ReduceArgs a;
   const int L = K > G ? K : G;
   a.slot_grad = p.slot_grad; a.slot_hdr = p.slot_hdr; a.mt_per_seg = p.mt_per_seg; a.n_mt = p.n_mt;
   a.nwg = p.nwg; a.nseg = p.nseg; a.K = K; a.NBLK = L / K; a.NGRP = L / G; a.G = G; a.rep = p.rep;
   a.transpose_out = transpose_out; a.t = p.lse_t; a.lse_ms = lse_ms; a.member_ref = member_ref; a.out = out;
-  hipLaunchKernelGGL(reduce_grad_kernel, dim3(nb, (K * K + 1023) / 1024), dim3(256), 0, st, a);
+  return a;
+}
+}  // namespace
+int launch_reduce_grad(const CoreParams& p, int K, int G, int nb, int transpose_out, const double* lse_ms,
+                       const float* member_ref, float* out, hipStream_t st) {
+  ReduceJobs js;
+  js.job[0] = js.job[1] = reduce_args(p, K, G, transpose_out, lse_ms, member_ref, out);
+  hipLaunchKernelGGL(reduce_grad_kernel, dim3(nb, (K * K + 1023) / 1024, 1), dim3(256), 0, st, js);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+// Both members of a pair in one launch: pa -> outA (transposed), pb -> outB.
+int launch_reduce_grad_pair(const CoreParams& pa, int GA, const float* refA, float* outA, const CoreParams& pb,
+                            int GB, const float* refB, float* outB, int K, int nb, const double* lse_ms,
+                            hipStream_t st) {
+  ReduceJobs js;
+  js.job[0] = reduce_args(pa, K, GA, 1, lse_ms, refA, outA);
+  js.job[1] = reduce_args(pb, K, GB, 0, lse_ms, refB, outB);
+  hipLaunchKernelGGL(reduce_grad_kernel, dim3(nb, (K * K + 1023) / 1024, 2), dim3(256), 0, st, js);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }

@@ -721,9 +721,9 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
                                  losses, w.lse_ms, st)))
     return rc;
   if (grad) {
-    if ((rc = launch_reduce_grad(ag, K, GA, nb, 1, w.lse_ms, qa.two ? w.member_ref : nullptr, gradT, st))) return rc;
-    // member B: G_P of transform block b sums its rep row-blocks; d/dT = -P^T G_P P^T
-    if ((rc = launch_reduce_grad(bg, K, GB, nb, 0, w.lse_ms, qb.two ? w.member_ref + 1 : nullptr, w.gp, st)))
+    // member A into gradT; member B: G_P of transform block b sums its rep row-blocks; d/dT = -P^T G_P P^T
+    if ((rc = launch_reduce_grad_pair(ag, GA, qa.two ? w.member_ref : nullptr, gradT, bg, GB,
+                                      qb.two ? w.member_ref + 1 : nullptr, w.gp, K, nb, w.lse_ms, st)))
       return rc;
     if ((rc = launch_bgemm(true, false, x->Tinv, w.gp, w.x1, K, nb, 1.f, 0.f, st))) return rc;
     if ((rc = launch_bgemm(false, true, w.x1, x->Tinv, gradT, K, nb, -1.f, 1.f, st))) return rc;

@@ -56,6 +56,9 @@ int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_
 int launch_rho_groups(const float* rho, int K, int rep, int G, int64_t ngroups, float* rG, hipStream_t st);
 int launch_reduce_grad(const CoreParams& p, int K, int G, int nb, int transpose_out, const double* lse_ms,
                        const float* member_ref, float* out, hipStream_t st);
+int launch_reduce_grad_pair(const CoreParams& pa, int GA, const float* refA, float* outA, const CoreParams& pb,
+                            int GB, const float* refB, float* outB, int K, int nb, const double* lse_ms,
+                            hipStream_t st);
 int launch_build_mmid(const CoreParams& p, int K, int G, int nb, const float* P, int scale_rows, float* Mmid,
                       hipStream_t st);
 int launch_reduce_losses(int kind, const float* hdrA, int nslotA, const float* hdrB, int nslotB, float beta,
