@@ -252,6 +252,7 @@ struct GjArgs {
   int mode, K, nz;
   const float* T;        // matrix to invert when partial == nullptr
   const float* partial;  // else [nb][nz][2][K][K]: chunk partials whose first matrix is summed and inverted
+  const double* sum64 = nullptr;  // optional with partial: that float64 sum, already formed, [nb][K][K]
   double* work;          // unused by the register-resident kernel
   float* out;            // [nb][K][K]
   float* rho_row; float* rho_col;  // optional squared row / column norms of the inverse
@@ -338,6 +339,14 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_panel_kernel(const GjA
   S reg[RT][CT];
   if (a.partial == nullptr) {
     const float* src = a.T + size_t(b) * K * K;
+#pragma unroll
+    for (int i = 0; i < RT; ++i)
+#pragma unroll
+      for (int j = 0; j < CT; ++j) reg[i][j] = S(src[(rt + i * NRT) * K + ct + j * NCT]);
+  } else if (a.sum64) {
+    // one workgroup reading nz partials of its block is a long serial prologue when the blocks are few:
+    // the float64 sum then comes from a kernel that spreads that work over the chip
+    const double* src = a.sum64 + size_t(b) * K * K;
 #pragma unroll
     for (int i = 0; i < RT; ++i)
 #pragma unroll
@@ -979,6 +988,14 @@ int launch_gj_solve(int K, int nb, int nz, const float* partial, double* work, f
   a.need = nullptr;
   a.rho_row = a.rho_col = nullptr; a.status = status; a.status_stride = status_stride;
   a.status_offset = status_offset;
+  const size_t mat = size_t(nb) * K * K;
+  double *S64 = work, *R64 = work + mat, *res = work + 2 * mat, *X64 = work + 3 * mat;
+  if (K == 256 || nb <= 64) {
+    // few blocks (always so for K = 256 shapes): the sums over the chunk partials are formed by the whole chip
+    hipLaunchKernelGGL(sum_partials64_kernel, dim3(nb, 32), dim3(256), 0, st, partial, nz, K, S64, R64, res);
+    CAFEQ_CHECK_LAUNCH();
+    a.sum64 = S64;
+  }
   int rc = launch_gj(a, nb, st);
   if (rc) return rc;
   if (K < 256) {
@@ -986,10 +1003,7 @@ int launch_gj_solve(int K, int nb, int nz, const float* partial, double* work, f
     CAFEQ_CHECK_LAUNCH();
     return launch_bgemm(false, false, Sinv, R, out, K, nb, -1.f, 1.f, st);
   }
-  const size_t mat = size_t(nb) * K * K;
-  double *S64 = work, *R64 = work + mat, *res = work + 2 * mat, *X64 = work + 3 * mat;
   const unsigned grid = unsigned(nb) * (K / 32) * (K / 64);
-  hipLaunchKernelGGL(sum_partials64_kernel, dim3(nb, 32), dim3(256), 0, st, partial, nz, K, S64, R64, res);
   hipLaunchKernelGGL((bgemm_f64acc_kernel<float, double>), dim3(grid), dim3(256), 0, st, Sinv, R64, X64, K, 1.0, 0.0);
   hipLaunchKernelGGL((bgemm_f64acc_kernel<double, double>), dim3(grid), dim3(256), 0, st, S64, X64, res, K, -1.0, 1.0);
   hipLaunchKernelGGL((bgemm_f64acc_kernel<float, double>), dim3(grid), dim3(256), 0, st, Sinv, res, X64, K, 1.0, 1.0);
