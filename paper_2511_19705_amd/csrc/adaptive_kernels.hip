@@ -490,13 +490,25 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_panel_kernel(const GjA
 #pragma unroll
       for (int c = 0; c < NB; ++c) {
         const int p = pvt[buf][c];
-        const int prt = p % NRT, pi = p / NRT;
+        const int prt = p % NRT;
+        if constexpr (!PIV && NRT % NCT == 0) {
+          // diagonal pivots p = jj NCT + h NB + c: the register row p / NRT does not depend on h and c
+          constexpr int pi = (jj * NCT) / NRT;
+          if (rt == prt) {
 #pragma unroll
-        for (int i = 0; i < RT; ++i)
-          if (rt == prt && i == pi) {
-#pragma unroll
-            for (int j = 0; j < CT; ++j) xrow[buf][c][ct + j * NCT] = reg[i][j];
+            for (int j = 0; j < CT; ++j) xrow[buf][c][ct + j * NCT] = reg[pi][j];
           }
+        } else {
+          // (one flat condition per register row: nesting the row test inside the thread test made the
+          // compiler index the registers dynamically, through scratch memory)
+          const int pi = p / NRT;
+#pragma unroll
+          for (int i = 0; i < RT; ++i)
+            if (rt == prt && i == pi) {
+#pragma unroll
+              for (int j = 0; j < CT; ++j) xrow[buf][c][ct + j * NCT] = reg[i][j];
+            }
+        }
       }
       __syncthreads();
 #pragma unroll 2
