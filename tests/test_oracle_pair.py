@@ -183,3 +183,147 @@ def test_adaptive_step_lowers_pqe_on_heavy_tailed_pair():
         Uh, Vh, _, _ = O.adaptive_round_step(U, V, Uh, bits, g, 16, 2)
     p1, _ = O.pqe(U, V, Uh, Vh, 16, 2)
     assert p1 < 0.95 * p0
+
+
+# ---------------------------------------------------------------------------------------------
+# Algorithm 1, line 4 (the update of the first matrix) and the paired error over several heads
+# ---------------------------------------------------------------------------------------------
+def _stack_heads(X, k, b, rep):
+    """Row-blocks b*rep .. (b+1)*rep-1 of X (k rows each) side by side, with explicit loops."""
+    d3 = X.shape[1]
+    out = np.zeros((k, rep * d3))
+    for r in range(rep):
+        for i in range(k):
+            for c in range(d3):
+                out[i, r * d3 + c] = X[(b * rep + r) * k + i, c]
+    return out
+
+
+def test_line4_is_line3_of_the_transposed_pair():
+    # W1 W2 Vh^+ = (Vh^T^+ W2^T W1^T)^T: line 4 on (U, V, Vh) is the transpose of line 3 on
+    # (V^T, U^T, Vh^T); line 3 is pinned by the paper's toy example and by brute force above
+    rng = np.random.default_rng(21)
+    k, nb, d1, d3 = 6, 3, 11, 9
+    U = rng.standard_normal((d1, nb * k))
+    V = rng.standard_normal((nb * k, d3))
+    Vh = O.rtn_sym(V, 3, 0, O.ROW, "f64")[2]
+    got = O.adaptive_targets_U(U, V, Vh, k, 1)
+    want = O.adaptive_targets_V(V.T, Vh.T, U.T, k, 1).T
+    np.testing.assert_allclose(got, want, atol=1e-11)
+    # and the full step (with its quantizer on the other axis) obeys the same symmetry
+    Uh0 = O.rtn_sym(U, 3, 0, O.COL, "f64")[2]
+    Uh4, _, _, Ut = O.adaptive_round_step(U, V, Uh0, 3, 0, k, 1, half=2, Vh=Vh, arith="f64")
+    _, Vh3, Vt, _ = O.adaptive_round_step(V.T, U.T, Vh.T, 3, 0, k, 1, half=1, arith="f64")
+    np.testing.assert_allclose(Ut, Vt.T, atol=1e-11)
+    np.testing.assert_allclose(Uh4, Vh3.T, atol=1e-11)
+
+
+def test_line4_normal_equations_with_shared_heads():
+    # U'_b is the least-squares solution of X Vh_[b] = U_b V_[b] over the rep row-blocks of head b
+    # side by side: residual times Vh_[b]^T vanishes.  Everything formed with explicit loops.
+    rng = np.random.default_rng(22)
+    k, nb, rep, d1, d3 = 4, 2, 2, 5, 7
+    U = rng.standard_normal((d1, nb * k))
+    V = rng.standard_normal((nb * rep * k, d3))
+    Vh = O.rtn_sym(V, 3, 0, O.ROW, "f64")[2]
+    Ut = O.adaptive_targets_U(U, V, Vh, k, rep)
+    for b in range(nb):
+        Vs, Vhs = _stack_heads(V, k, b, rep), _stack_heads(Vh, k, b, rep)
+        for i in range(d1):
+            for j in range(k):
+                acc = 0.0
+                for c in range(rep * d3):
+                    got = sum(Ut[i, b * k + l] * Vhs[l, c] for l in range(k))
+                    ref = sum(U[i, b * k + l] * Vs[l, c] for l in range(k))
+                    acc += (got - ref) * Vhs[j, c]
+                assert abs(acc) < 1e-10, (b, i, j, acc)
+        # the same solution from a different library routine (least squares on the transposed system)
+        X = np.linalg.lstsq(Vhs.T, (U[:, b * k:(b + 1) * k] @ Vs).T, rcond=None)[0].T
+        np.testing.assert_allclose(Ut[:, b * k:(b + 1) * k], X, atol=1e-10)
+        # a wrong stacking (heads added instead of placed side by side) is a different matrix
+        wrong = U[:, b * k:(b + 1) * k] @ (sum(V[q * k:(q + 1) * k] for q in range(b * rep, (b + 1) * rep))
+                                           @ O.pinv(sum(Vh[q * k:(q + 1) * k] for q in range(b * rep, (b + 1) * rep))))
+        assert np.abs(wrong - Ut[:, b * k:(b + 1) * k]).max() > 1e-3
+
+
+def test_line4_no_perturbation_lowers_the_paired_error():
+    rng = np.random.default_rng(23)
+    k, nb, rep, d1, d3 = 4, 2, 2, 6, 5
+    U = rng.standard_normal((d1, nb * k))
+    V = rng.standard_normal((nb * rep * k, d3))
+    Vh = O.rtn_sym(V, 3, 0, O.ROW, "f64")[2]
+    Ut = O.adaptive_targets_U(U, V, Vh, k, rep)
+    base = O.pqe(U, V, Ut, Vh, k, rep)[0]
+    for _ in range(50):
+        assert O.pqe(U, V, Ut + 1e-3 * rng.standard_normal(Ut.shape), Vh, k, rep)[0] >= base - 1e-12
+
+
+def test_toy_example_second_half_iteration_by_hand():
+    # Not printed in the paper; worked by hand from Algorithm 1, line 4 on the Sec. 5 toy example after
+    # its first half-iteration:  W1 W2 = diag(1, 0.36),  W2^ = diag(1, 0),  pinv(W2^) = diag(1, 0),
+    # target = diag(1, 0.36) diag(1, 0) = diag(1, 0),  Q(target) = diag(1, 0) on the 1-bit grid {0, 1};
+    # the paired error stays ||diag(1,0) diag(1,0) - diag(1,0.36)||_F = 0.36.
+    g = _gold()
+    W = np.diag([g["w_diag0"], g["w_diag1"]])
+    bits = int(g["bits"])
+    W1h = O.rtn_asym(W, bits, -1, O.COL)[3]
+    Uh, Vh, _, Ut = O.adaptive_round_step(W, W, W1h, bits, -1, k=2, rep=1, half=0, mode=O.ASYM)
+    np.testing.assert_allclose(Ut, np.diag([1.0, 0.0]), atol=1e-15)
+    np.testing.assert_allclose(Uh, np.diag([1.0, 0.0]), atol=1e-15)
+    np.testing.assert_allclose(Vh, np.diag([1.0, 0.0]), atol=1e-15)
+    assert abs(O.pqe(W, W, Uh, Vh, k=2)[0] - 0.36) < 1e-12
+    # a non-commuting case by hand: W1 = [[1, 1], [0, 1]], W2 = I, W2^ = diag(2, 1):
+    # W1 W2 pinv(W2^) = [[1/2, 1], [0, 1]]  (the pseudoinverse on the right scales COLUMNS)
+    W1 = np.array([[1.0, 1.0], [0.0, 1.0]])
+    got = O.adaptive_targets_U(W1, np.eye(2), np.diag([2.0, 1.0]), 2, 1)
+    np.testing.assert_allclose(got, np.array([[0.5, 1.0], [0.0, 1.0]]), atol=1e-15)
+
+
+def test_line4_exactly_representable_second_matrix_reduces_to_plain_quantization():
+    rng = np.random.default_rng(24)
+    k, rep, d3 = 5, 2, 6
+    V = rng.integers(-3, 4, size=(rep * k, d3)).astype(np.float64)
+    V[0, :] = 3                                       # every column group of each row-block has absmax 3
+    V[k, :] = -3
+    Vh = O.rtn_sym(V, 3, k, O.ROW, "f64")[2]
+    np.testing.assert_array_equal(Vh, V)
+    U = rng.standard_normal((9, k))
+    Uh, _, _, Ut = O.adaptive_round_step(U, V, None, 3, k, k, rep, half=2, Vh=Vh, arith="f64")
+    np.testing.assert_allclose(Ut, U, atol=1e-11)      # V_[b] has full row rank: U V pinv(V) = U
+    np.testing.assert_array_equal(Uh, O.rtn_sym(Ut, 3, k, O.COL, "f64")[2])
+
+
+def test_line4_equals_bruteforce_when_rows_of_the_second_matrix_are_orthogonal():
+    rng = np.random.default_rng(25)
+    bits, k, rep, d3 = 3, 5, 2, 7
+    # orthogonal (scaled) rows of the stacked quantized matrix: the problem separates per entry of a row of U'
+    Qm = np.linalg.qr(rng.standard_normal((rep * d3, k)))[0].T * rng.uniform(0.5, 2.0, size=k)[:, None]   # k x rep*d3
+    Vh = np.concatenate([Qm[:, r * d3:(r + 1) * d3] for r in range(rep)], axis=0)                         # rep*k x d3
+    V = Vh + 0.05 * rng.standard_normal(Vh.shape)
+    U = rng.standard_normal((4, k))
+    Uh, _, _, Ut = O.adaptive_round_step(U, V, None, bits, 0, k, rep, half=2, Vh=Vh, arith="f64")
+    Vs = _stack_heads(V, k, 0, rep)
+    for i in range(U.shape[0]):
+        best, _ = O.adaptive_bruteforce_column(Qm.T, (U[i] @ Vs), Ut[i], bits, 0)
+        np.testing.assert_allclose(Uh[i], best, atol=1e-13)
+
+
+def test_pqe_over_shared_heads_is_the_dense_loop():
+    rng = np.random.default_rng(26)
+    k, nb, rep, d1, d3 = 3, 2, 2, 4, 5
+    U = rng.standard_normal((d1, nb * k)); Uh = U + 0.1 * rng.standard_normal(U.shape)
+    V = rng.standard_normal((nb * rep * k, d3)); Vh = V + 0.1 * rng.standard_normal(V.shape)
+    num = den = 0.0
+    for q in range(nb * rep):
+        b = q // rep
+        for i in range(d1):
+            for c in range(d3):
+                ref = sum(U[i, b * k + l] * V[q * k + l, c] for l in range(k))
+                got = sum(Uh[i, b * k + l] * Vh[q * k + l, c] for l in range(k))
+                num += (got - ref) ** 2
+                den += ref ** 2
+    p, rel = O.pqe(U, V, Uh, Vh, k, rep)
+    assert abs(p - np.sqrt(num)) < 1e-12 and abs(rel - np.sqrt(num / den)) < 1e-12
+    # rep = 1 with one head is the plain Frobenius norm of the product difference
+    p1, _ = O.pqe(U[:, :k], V[:k], Uh[:, :k], Vh[:k], k, 1)
+    assert abs(p1 - np.linalg.norm(Uh[:, :k] @ Vh[:k] - U[:, :k] @ V[:k])) < 1e-12

@@ -150,3 +150,16 @@ def test_toy_example_independent_rounding():
     np.testing.assert_array_equal(what, np.eye(2))
     p, _ = O.pqe(W, W, what, what, k=2)
     assert abs(p - g["pqe_independent"]) < 1e-12
+
+
+def test_denormal_absmax_group_stays_finite():
+    # the single-precision recipe caps inv = fl(qmax / a) at FLT_MAX: for a denormal absmax the uncapped
+    # quotient is inf and 0 * inf would be NaN.  With the cap every product is finite, so every code is a
+    # finite integer in range and the dequantized values are finite; a normal group next to it is untouched.
+    tiny = np.float32(1e-42)
+    Z = np.array([[tiny, 0.0, -tiny, 0.0, 1.0, -0.5, 0.25, 0.0]], dtype=np.float32)
+    codes, scales, zh = O.rtn_sym(Z, 4, 4, O.COL, "f32")
+    assert np.all(np.isfinite(zh)) and np.all(np.isfinite(scales))
+    assert codes.min() >= -8 and codes.max() <= 7
+    np.testing.assert_array_equal(codes[0, 4:], [7, -4, 2, 0])      # 1 -> qmax, -0.5*7 = -3.5 -> -4 (even), 0.25*7 = 1.75 -> 2
+    assert np.all(np.abs(zh[0, :4] - Z[0, :4].astype(np.float64)) <= float(tiny))
