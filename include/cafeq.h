@@ -128,6 +128,19 @@ int cafeq_block_inverse(const float* T, int k, int nb, float* Tinv, float* rho_r
 int cafeq_rtn_quantize(const cafeq_mat* W, const cafeq_quant_cfg* cfg, int8_t* codes,
                        float* scales, float* err_sq, void* ws, void* stream);
 
+/* cafeq_rtn_quantize for callers that cannot allocate device memory or hand over a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).  Same inputs, outputs
+ * and arithmetic as cafeq_rtn_quantize; the float64 squared-error partials (one per workgroup) go to a
+ * device array built into the library (512 KB per GPU, held until the process ends) instead of `ws`.
+ * The call allocates and frees nothing.  With err_sq != NULL the matrix may hold at most
+ * 65536 * 1024 * 4 elements along the contiguous axis' fast kernel and 65536 tiles of 16 rows x 256
+ * columns (precisely: at most 65536 partials; larger inputs return CAFEQ_ERR_WORKSPACE before anything
+ * is launched); with err_sq == NULL there is no limit.  Every call on a GPU shares that GPU's array:
+ * calls that overlap on one GPU (different streams, different threads) race on it and must be
+ * ordered by the caller.  Nothing needs clearing between calls (every partial is rewritten). */
+int cafeq_rtn_quantize_static(const cafeq_mat* W, const cafeq_quant_cfg* cfg, int8_t* codes,
+                              float* scales, float* err_sq, void* stream);
+
 /* The uniform min/max quantizer exactly as the paper's Eq. (1) states it, per group:
  *   s = (max - min) / (2^b - 1),  q = nearest_int((w - min) / s) in [0, 2^b - 1],  w^ = s q + min.
  * Single-precision recipe: r = fl(max - min), inv = min(fl((2^b-1) / r), FLT_MAX) (0 for a constant

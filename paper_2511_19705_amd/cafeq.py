@@ -26,7 +26,7 @@ EXPORTS = (
     "cafeq_orth_penalty", "cafeq_sgd_update", "cafeq_adam_update", "cafeq_optimize_single",
     "cafeq_optimize_pair", "cafeq_pqe", "cafeq_rtn_quantize_minmax", "cafeq_hadamard_rtn", "cafeq_hadamard_workspace_bytes",
     "cafeq_infer_single", "cafeq_infer_workspace_bytes", "cafeq_profile_enable",
-    "cafeq_profile_read",
+    "cafeq_profile_read", "cafeq_rtn_quantize_static",
 )
 
 
@@ -71,6 +71,7 @@ def _load():
                                           ctypes.POINTER(Xform), ctypes.POINTER(QuantCfg)]
     lib.cafeq_block_inverse.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.cafeq_rtn_quantize.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(QuantCfg), vp, vp, vp, vp, vp]
+    lib.cafeq_rtn_quantize_static.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(QuantCfg), vp, vp, vp, vp]
     lib.cafeq_apply_transform.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Xform), i32, i32, vp, vp, vp]
     lib.cafeq_proxy_loss_fwd_bwd.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Xform),
                                              ctypes.POINTER(QuantCfg), vp, vp, vp, vp, vp, vp]
@@ -176,6 +177,14 @@ def rtn_quantize(W, bits, group, axis=AXIS_COL, want_err=False):
     _check(lib.cafeq_rtn_quantize(ctypes.byref(m), ctypes.byref(cfg), _ptr(codes), _ptr(scales),
                                   _ptr(err), _ptr(ws), _stream()))
     return codes, scales, err
+
+
+def rtn_quantize_static(W, codes, scales, err, bits, group, axis=AXIS_COL):
+    """The quantizer with built-in scratch: the caller passes every output buffer; nothing is allocated."""
+    m = mat(W)
+    cfg = QuantCfg(bits, group, axis, 0)
+    _check(lib.cafeq_rtn_quantize_static(ctypes.byref(m), ctypes.byref(cfg), _ptr(codes), _ptr(scales),
+                                         _ptr(err), _stream()))
 
 
 def block_inverse(T, want_rho=False):
