@@ -84,7 +84,8 @@ typedef struct {
 } cafeq_xform;
 
 /* bits in [2, 8]; group: elements per scale along `axis` (0 = whole line);
- * axis: cafeq_axis; mode: cafeq_qmode (only CAFEQ_Q_SYM_ABSMAX has kernels). */
+ * axis: cafeq_axis; mode: cafeq_qmode (CAFEQ_Q_SYM_ABSMAX in the fused calls; the min/max grid of the
+ * paper's Eq. (1) has its own entry point, cafeq_rtn_quantize_minmax). */
 typedef struct {
   int32_t bits, group, axis, mode;
 } cafeq_quant_cfg;
@@ -152,8 +153,8 @@ int cafeq_rtn_quantize_static(const cafeq_mat* W, const cafeq_quant_cfg* cfg, in
 int cafeq_rtn_quantize_minmax(const cafeq_mat* W, const cafeq_quant_cfg* cfg, uint8_t* codes,
                               float* scales, float* mins, float* err_sq, void* ws, void* stream);
 
-/* The paper's "random" comparison (caption of the block-size table in Sec. 4.1: "a block diagonal
- * matrix with block size 1024, where each block is a random Hadamard matrix"): every block of
+/* The paper's "random" comparison (caption of the block-size table in Sec. 4.1: a block-diagonal
+ * transform with blocks of 1024 whose blocks are randomized Hadamard matrices): every block of
  * `block` (256, 512 or 1024) consecutive columns of W is multiplied by its random signs
  * (signs[cols], +-1) and by the normalised Walsh-Hadamard matrix in Sylvester's ordering, then
  * quantized as in cafeq_rtn_quantize (groups of cfg->group columns, a power of two in
@@ -200,8 +201,11 @@ int cafeq_apply_transform(const cafeq_mat* W, const cafeq_xform* x, int axis, in
  *   gradT[nb][k][k] (may be NULL: forward only) = d L_sur / d T with Tinv = T^-1,
  *               absmax differentiated at its arg-max element.
  *   codes / scales (may be NULL): Q(Z) as in cafeq_rtn_quantize.
- * group must satisfy max(group, k) <= 256 and divide / be divided by k.  gradT != NULL is
- * CAFEQ_ERR_UNSUPPORTED for k = 256 and for group = 256 with k >= 64 (forward only works). */
+ * Groups: 32, 64, 128 or 256 elements (max(group, k) must divide the axis), or any longer group that is a
+ * multiple of k and divides the axis -- group = 0, the whole channel (the per-channel setting of the paper's
+ * experiments, Sec. 6), included.  A group longer than 256 spans several segments of the kernel: the
+ * transform is then applied twice (a first sweep finds every group's absmax), and the gradient needs the
+ * axis to be a multiple of 128.  Every block size has a gradient for every such group. */
 int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x,
                              const cafeq_quant_cfg* cfg, float* losses, float* gradT,
                              int8_t* codes, float* scales, void* ws, void* stream);
@@ -214,7 +218,9 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x,
  *   losses[4] = LSE = (1/t) log( sum over every group G of U and of V of exp(t a_G) )
  *   losses[5] = number of groups (as float)
  *   gradT[nb][k][k] (may be NULL) = d LSE / d T.
- * codesU/scalesU/codesV/scalesV (may be NULL): Q(U), Q(V). */
+ * codesU/scalesU/codesV/scalesV (may be NULL): Q(U), Q(V).
+ * Groups as in cafeq_proxy_loss_fwd_bwd (with group = 0 the LSE is the paper's sum over the channel
+ * maxima m_u(i), m_v(j) of Sec. 4.2). */
 int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B,
                                   const cafeq_xform* x, const cafeq_quant_cfg* cfg,
                                   float lse_t, float* losses, float* gradT,

@@ -161,9 +161,13 @@ __device__ void seg_wg_range(int64_t seg, int64_t mt_per_seg, int64_t n_mt, int 
 struct ReduceArgs {
   const float* slot_grad;
   const float* slot_hdr;
-  int64_t mt_per_seg, n_mt;
+  int64_t mt_per_seg, n_mt;   // of the pass that wrote the partials
   int nwg, nseg;
-  int K, NBLK, NGRP, G, rep;
+  int K, rep;
+  int seg_len;           // axis indices per segment of that pass
+  int part_floats;       // floats of one partial
+  int msplit;            // 1: a partial holds whole blocks, [seg_len outputs][K inputs];
+                         // 2: K == 256 in halves of the inputs, [256 outputs][128 inputs], segment 2 q + half
   int transpose_out;     // 1: out[m][j] = acc[j][m]
   float t;               // kLossLse: temperature; scale of a partial = exp(t (m_ref - m*)) / S
   const double* lse_ms;  // kLossLse: [0] = m*, [1] = S  (null for kLossSur)
@@ -172,7 +176,8 @@ struct ReduceArgs {
 };
 
 // grid: (nb transform blocks, K*K/1024).  out_b = sum over the rep row-blocks q of block b, and
-// over the partials of q's segment, in fixed order; each thread owns four consecutive elements.
+// over the partials of q's segment, in fixed order; each thread owns four consecutive inputs of one
+// output row, each workgroup 1024 elements that lie in one partial layout (one half when msplit == 2).
 struct ReduceJobs { ReduceArgs job[2]; };   // grid.z picks the job (the two members of a pair in one launch)
 __global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceJobs js) {
   const ReduceArgs& a = js.job[blockIdx.z];
@@ -182,7 +187,14 @@ __global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceJobs js) {
   __shared__ int nsrc, more, next_q, next_w;
   const int b = blockIdx.x;
   const int K = a.K;
-  const int i = (blockIdx.y * 256 + threadIdx.x) * 4;     // first of this thread's elements
+  // this workgroup's 1024 elements: rows of KMr inputs inside one half
+  const int KMr = a.msplit == 2 ? 128 : K;
+  const int rows_per_wg = 1024 / KMr;                       // K = 32: one workgroup covers the block
+  const int nyh = K / rows_per_wg > 0 ? K / rows_per_wg : 1;
+  const int half = int(blockIdx.y) / nyh, rg = int(blockIdx.y) % nyh;
+  const int j = rg * rows_per_wg + (threadIdx.x * 4) / KMr, ml = (threadIdx.x * 4) % KMr;
+  const bool active = j < K;
+  const int poff = j * KMr + ml;                            // offset inside a partial (plus the block's base)
   if (threadIdx.x == 0) { next_q = b * a.rep; next_w = -1; }
   __syncthreads();
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -192,7 +204,9 @@ __global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceJobs js) {
       int n = 0, q = next_q, wres = next_w;
       bool full = false;
       for (; q < (b + 1) * a.rep && !full; ++q) {
-        const int seg = q / a.NBLK, blk = q % a.NBLK;
+        int seg, base;
+        if (a.msplit == 2) { seg = 2 * q + half; base = 0; }
+        else { seg = int((int64_t(q) * K) / a.seg_len); base = int((int64_t(q) * K) % a.seg_len) * K; }
         int lo, hi;
         seg_wg_range(seg, a.mt_per_seg, a.n_mt, a.nwg, &lo, &hi);
         int w = wres >= 0 ? wres : lo;
@@ -205,7 +219,7 @@ __global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceJobs js) {
             const float mref = a.member_ref ? *a.member_ref : a.slot_hdr[slot * kHdrFloats + kHdrMref];
             sc = float(exp(double(a.t) * (double(mref) - a.lse_ms[0])) / a.lse_ms[1]);
           }
-          src[n] = a.slot_grad + slot * int64_t(a.NBLK) * K * K + int64_t(blk) * K * K;
+          src[n] = a.slot_grad + slot * int64_t(a.part_floats) + base;
           scl[n] = sc;
           ++n;
         }
@@ -215,9 +229,9 @@ __global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceJobs js) {
     }
     __syncthreads();
     const int n = nsrc;
-    if (i < K * K) {
+    if (active) {
       for (int s = 0; s < n; ++s) {
-        const float4 v = *reinterpret_cast<const float4*>(src[s] + i);
+        const float4 v = *reinterpret_cast<const float4*>(src[s] + poff);
         const float sc = scl[s];
         acc.x += sc * v.x; acc.y += sc * v.y; acc.z += sc * v.z; acc.w += sc * v.w;
       }
@@ -226,14 +240,14 @@ __global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceJobs js) {
     __syncthreads();
     if (!again) break;
   }
-  if (i < K * K) {
+  if (active) {
     float* dst = a.out + size_t(b) * K * K;
+    const int m = half * 128 + ml;
     if (a.transpose_out) {
-      const int r = i / K, c = i % K;          // K is a multiple of 4: the four share a row
-      dst[(c + 0) * K + r] = acc.x; dst[(c + 1) * K + r] = acc.y;
-      dst[(c + 2) * K + r] = acc.z; dst[(c + 3) * K + r] = acc.w;
+      dst[(m + 0) * K + j] = acc.x; dst[(m + 1) * K + j] = acc.y;
+      dst[(m + 2) * K + j] = acc.z; dst[(m + 3) * K + j] = acc.w;
     } else {
-      *reinterpret_cast<float4*>(dst + i) = acc;
+      *reinterpret_cast<float4*>(dst + j * K + m) = acc;
     }
   }
 }
@@ -522,31 +536,38 @@ int launch_rho_groups(const float* rho, int K, int rep, int G, int64_t ngroups, 
   return CAFEQ_OK;
 }
 namespace {
-ReduceArgs reduce_args(const CoreParams& p, int K, int G, int transpose_out, const double* lse_ms,
+// fused: the partials were written by the fused kernel (segments of max(K, G), [NBLK][K][K]); otherwise by the
+// gradient pass (chunks of 128 inputs; halves of the inputs for K == 256)
+ReduceArgs reduce_args(const CoreParams& p, int K, int G, bool fused, int transpose_out, const double* lse_ms,
                        const float* member_ref, float* out) {
   ReduceArgs a;
-  const int L = K > G ? K : G;
   a.slot_grad = p.slot_grad; a.slot_hdr = p.slot_hdr; a.mt_per_seg = p.mt_per_seg; a.n_mt = p.n_mt;
-  a.nwg = p.nwg; a.nseg = p.nseg; a.K = K; a.NBLK = L / K; a.NGRP = L / G; a.G = G; a.rep = p.rep;
+  a.nwg = p.nwg; a.nseg = p.nseg; a.K = K; a.rep = p.rep;
+  if (fused) {
+    const int L = K > G ? K : G;
+    a.seg_len = L; a.part_floats = L * K; a.msplit = 1;
+  } else {
+    a.seg_len = 128; a.msplit = K == 256 ? 2 : 1; a.part_floats = K == 256 ? 256 * 128 : 128 * K;
+  }
   a.transpose_out = transpose_out; a.t = p.lse_t; a.lse_ms = lse_ms; a.member_ref = member_ref; a.out = out;
   return a;
 }
 }  // namespace
-int launch_reduce_grad(const CoreParams& p, int K, int G, int nb, int transpose_out, const double* lse_ms,
-                       const float* member_ref, float* out, hipStream_t st) {
+int launch_reduce_grad(const CoreParams& p, int K, int G, bool fused, int nb, int transpose_out,
+                       const double* lse_ms, const float* member_ref, float* out, hipStream_t st) {
   ReduceJobs js;
-  js.job[0] = js.job[1] = reduce_args(p, K, G, transpose_out, lse_ms, member_ref, out);
+  js.job[0] = js.job[1] = reduce_args(p, K, G, fused, transpose_out, lse_ms, member_ref, out);
   hipLaunchKernelGGL(reduce_grad_kernel, dim3(nb, (K * K + 1023) / 1024, 1), dim3(256), 0, st, js);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }
 // Both members of a pair in one launch: pa -> outA (transposed), pb -> outB.
-int launch_reduce_grad_pair(const CoreParams& pa, int GA, const float* refA, float* outA, const CoreParams& pb,
-                            int GB, const float* refB, float* outB, int K, int nb, const double* lse_ms,
-                            hipStream_t st) {
+int launch_reduce_grad_pair(const CoreParams& pa, int GA, bool fusedA, const float* refA, float* outA,
+                            const CoreParams& pb, int GB, bool fusedB, const float* refB, float* outB, int K,
+                            int nb, const double* lse_ms, hipStream_t st) {
   ReduceJobs js;
-  js.job[0] = reduce_args(pa, K, GA, 1, lse_ms, refA, outA);
-  js.job[1] = reduce_args(pb, K, GB, 0, lse_ms, refB, outB);
+  js.job[0] = reduce_args(pa, K, GA, fusedA, 1, lse_ms, refA, outA);
+  js.job[1] = reduce_args(pb, K, GB, fusedB, 0, lse_ms, refB, outB);
   hipLaunchKernelGGL(reduce_grad_kernel, dim3(nb, (K * K + 1023) / 1024, 2), dim3(256), 0, st, js);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;

@@ -41,14 +41,32 @@ struct CorePlan {
 
 bool supported_block(int k) { return k == 32 || k == 64 || k == 128 || k == 256; }
 
-// The gradient through the transformed weights is computed by a second pass over the weights
-// (from the first pass's arg-max records) where that is faster than the fused kernel: the
-// gradient-free first pass then runs at two waves per SIMD.
-bool two_pass_gradient(int K, int G) { return K == 128 && G <= 128; }
+// How the quantization groups of one matrix lie over the fused core's segments.  Groups of 32, 64, 128 or
+// 256 are a compile-time parameter of the core (a segment holds whole groups).  Any longer group -- a whole
+// channel, the per-channel setting of the paper's experiments, included -- spans `gspan` segments of `Gk`
+// elements; the core then runs with one group per segment and the group's absmax is assembled from the
+// segments' records (CoreParams::gspan).
+struct GroupPlan {
+  int G;       // group length along the axis
+  int Gk;      // the core's compile-time group
+  int gspan;   // segments per group
+};
+int resolve_group(const cafeq_quant_cfg* cfg, int64_t naxis, int K, GroupPlan* gp) {
+  const int64_t g = cfg->group == 0 ? naxis : cfg->group;
+  if (g <= 0 || naxis % g != 0) return CAFEQ_ERR_BAD_SHAPE;
+  if (g > (int64_t(1) << 30)) return CAFEQ_ERR_UNSUPPORTED;
+  gp->G = int(g);
+  if (g == 32 || g == 64 || g == 128 || g == 256) { gp->Gk = int(g); gp->gspan = 1; return CAFEQ_OK; }
+  int L = K > 128 ? K : 128;
+  if (g % L != 0) L = K;
+  if (g < L || g % L != 0) return CAFEQ_ERR_UNSUPPORTED;
+  gp->Gk = L; gp->gspan = int(g / L);
+  return CAFEQ_OK;
+}
 
-// grad: the launch will ask for the gradient.  Without it, segments of up to 128 run two
+// grad: the launch will ask for the fused gradient.  Without it, segments of up to 128 run two
 // workgroups per compute unit.
-int make_plan(int K, int G, int64_t nlines, int64_t naxis, CorePlan* pl, bool grad = true, bool two_per_cu = false) {
+int make_plan(int K, int G, int64_t nlines, int64_t naxis, CorePlan* pl, bool grad = true) {
   if (!supported_block(K)) return CAFEQ_ERR_UNSUPPORTED;
   if (!(G == 32 || G == 64 || G == 128 || G == 256)) return CAFEQ_ERR_UNSUPPORTED;
   pl->K = K; pl->G = G; pl->L = K > G ? K : G;
@@ -58,12 +76,30 @@ int make_plan(int K, int G, int64_t nlines, int64_t naxis, CorePlan* pl, bool gr
   pl->nseg = int(naxis / pl->L);
   pl->mt_per_seg = (nlines + kMacroLines - 1) / kMacroLines;
   pl->n_mt = pl->mt_per_seg * pl->nseg;
-  const int per_cu = ((!grad && pl->L <= 128) || two_per_cu) ? 2 : 1;
+  const int per_cu = (!grad && pl->L <= 128) ? 2 : 1;
   int64_t nwg = std::min<int64_t>(pl->n_mt, int64_t(device_cu_count()) * per_cu);
   if (nwg > 8) nwg -= nwg % 8;
   pl->nwg = int(nwg);
   pl->nslot = pl->nwg + pl->nseg;
   pl->slot_grad_floats = size_t(pl->NBLK) * K * K;
+  return CAFEQ_OK;
+}
+
+// The gradient pass of the two-pass scheme walks the axis in chunks of 128 inputs, two workgroups per
+// compute unit (one for blocks of 256).
+int make_grad_plan(int K, int64_t nlines, int64_t naxis, CorePlan* pl) {
+  if (!supported_block(K)) return CAFEQ_ERR_UNSUPPORTED;
+  if (naxis % 128 != 0) return CAFEQ_ERR_UNSUPPORTED;
+  pl->K = K; pl->G = 0; pl->L = 128; pl->NBLK = 0; pl->NGRP = 0;
+  pl->nlines = nlines; pl->naxis = naxis;
+  pl->nseg = int(naxis / 128);
+  pl->mt_per_seg = (nlines + kMacroLines - 1) / kMacroLines;
+  pl->n_mt = pl->mt_per_seg * pl->nseg;
+  int64_t nwg = std::min<int64_t>(pl->n_mt, int64_t(device_cu_count()) * (K == 256 ? 1 : 2));
+  if (nwg > 8) nwg -= nwg % 8;
+  pl->nwg = int(nwg);
+  pl->nslot = pl->nwg + pl->nseg;
+  pl->slot_grad_floats = grad_pass_part_floats(K);
   return CAFEQ_OK;
 }
 
@@ -77,80 +113,85 @@ struct Carver {
   }
 };
 
-struct SingleWs {
-  float *rho, *rG, *slot_grad, *slot_hdr, *mmid, *x1; double* lse_ms; uint16_t *pfwd, *pinv;
-  float2* rec; float* member_ref; size_t bytes;
-  float* fs;   // per-block factors of the half-precision forward operand
+// Whether the loss pass for (K, G) runs its forward contraction on two-part half-precision operands: the
+// gradient-free kernel variant over 128 x 128 blocks with one block per segment, for grids of up to 4 bits
+// (two float16 parts carry 22 of float32's 24 bits; the error that leaves in z / scale grows with the number of
+// levels, so finer grids keep the six-product bfloat16 forward).
+bool core_forward_f16(int K, int G, int bits) { return K == 128 && G <= 128 && bits <= 4; }
+
+// Plans of one matrix for a call with / without gradient: `first` is the pass that computes the losses,
+// `gpass` the pass that writes the gradient partials (== first when the gradient is fused into it).
+// The gradient runs as a second pass over the weights, from the loss pass's arg-max records, where the fused
+// kernel has no gradient (blocks of 256, groups of 256 with blocks of 64 or more), where the two passes are
+// faster (blocks of 128), and for groups that span several segments.
+struct PassPlans { CorePlan first, gpass; GroupPlan gp; bool two, fused; };
+int plan_passes(int K, const GroupPlan& gp, int64_t nlines, int64_t naxis, bool grad, PassPlans* pp) {
+  pp->gp = gp;
+  const size_t fl = core_lds_bytes(K, gp.Gk, true);
+  const bool fused_ok = fl != 0 && fl <= 160 * 1024 && gp.gspan == 1 && !(K == 128 && gp.Gk <= 128);
+  pp->two = grad && !fused_ok;
+  pp->fused = grad && fused_ok;
+  int rc = make_plan(K, gp.Gk, nlines, naxis, &pp->first, pp->fused);
+  if (rc) return rc;
+  if (pp->two) return make_grad_plan(K, nlines, naxis, &pp->gpass);
+  pp->gpass = pp->first;
+  return CAFEQ_OK;
+}
+
+// scratch of one matrix's passes
+struct MemberWs {
+  float *rG, *rGreal, *slot_grad, *fs;
+  uint16_t *pfwd, *pinv;
+  float2 *rec, *grec;
 };
-// pl: plan of the (first) pass that writes the partial headers; pg: plan of the pass that writes
-// the gradient partials (the same plan unless the gradient runs as a second pass)
-SingleWs carve_single(void* ws, const CorePlan& pl, const CorePlan& pg, int nb, bool grad, bool two_pass) {
+void carve_member(Carver& c, const PassPlans& pp, int nb, bool grad, bool want_rG, MemberWs* w) {
+  const CorePlan& pl = pp.first;
+  const bool big = pp.gp.gspan > 1;
+  w->fs = c.take<float>(nb);
+  w->pfwd = c.take<uint16_t>(size_t(nb) * kFwdPlanes * pl.K * pl.K);
+  w->pinv = c.take<uint16_t>(size_t(nb) * kInvPlanes * pl.K * pl.K);
+  w->rG = c.take<float>(want_rG ? size_t(pl.naxis / pl.G) : 0);
+  w->rGreal = big && want_rG ? c.take<float>(size_t(pl.naxis / pp.gp.G)) : w->rG;
+  w->slot_grad = c.take<float>(grad ? size_t(pp.gpass.nslot) * pp.gpass.slot_grad_floats : 0);
+  w->rec = c.take<float2>((pp.two || big) ? size_t(pl.naxis / pl.G) * size_t(pl.nlines) : 0);
+  w->grec = big ? c.take<float2>(size_t(pl.naxis / pp.gp.G) * size_t(pl.nlines)) : w->rec;
+}
+
+struct SingleWs {
+  double* lse_ms; float* member_ref; float *rho, *slot_hdr, *mmid, *x1; MemberWs m; size_t bytes;
+};
+SingleWs carve_single(void* ws, const PassPlans& pp, int nb, bool grad) {
   Carver c(ws);
   SingleWs w;
+  const CorePlan& pl = pp.first;
   w.lse_ms = c.take<double>(2);
   w.member_ref = c.take<float>(4);
-  w.fs = c.take<float>(nb);
-  w.pfwd = c.take<uint16_t>(size_t(nb) * kFwdPlanes * pl.K * pl.K);
-  w.pinv = c.take<uint16_t>(size_t(nb) * kInvPlanes * pl.K * pl.K);
   w.rho = c.take<float>(size_t(nb) * pl.K);
-  w.rG = c.take<float>(size_t(pl.naxis / pl.G));
   w.slot_hdr = c.take<float>(size_t(pl.nslot) * kHdrFloats);
-  w.slot_grad = c.take<float>(grad ? size_t(pg.nslot) * pg.slot_grad_floats : 0);
   w.mmid = c.take<float>(grad ? size_t(nb) * pl.K * pl.K : 0);
   w.x1 = c.take<float>(grad ? size_t(nb) * pl.K * pl.K : 0);
-  w.rec = c.take<float2>(grad && two_pass ? size_t(pl.naxis / pl.G) * size_t(pl.nlines) : 0);
+  carve_member(c, pp, nb, grad, true, &w.m);
   w.bytes = c.off;
   return w;
 }
 
 struct DualWs {
-  float *hdrA, *hdrB, *gradA, *gradB, *gp, *x1; double* lse_ms;
-  uint16_t *pfwdA, *pinvA, *pfwdB, *pinvB;
-  float2 *recA, *recB; float* member_ref; size_t bytes;
-  float *fsA, *fsB;   // per-block factors of the half-precision forward operands
+  double* lse_ms; float* member_ref; float *hdrA, *hdrB, *gp, *x1; MemberWs a, b; size_t bytes;
 };
-// pa, pb: plans of the passes that write the partial headers; ga, gb: plans of the passes that
-// write the gradient partials
-DualWs carve_dual(void* ws, const CorePlan& pa, const CorePlan& pb, const CorePlan& ga, const CorePlan& gb, int nb,
-                  bool grad, bool two_a, bool two_b) {
+DualWs carve_dual(void* ws, const PassPlans& qa, const PassPlans& qb, int nb, bool grad) {
   Carver c(ws);
   DualWs w;
+  const int K = qa.first.K;
   w.lse_ms = c.take<double>(2);
   w.member_ref = c.take<float>(4);   // [0]: member A, [1]: member B
-  w.fsA = c.take<float>(nb);
-  w.fsB = c.take<float>(nb);
-  const size_t kk = size_t(nb) * pa.K * pa.K;
-  w.pfwdA = c.take<uint16_t>(kk * kFwdPlanes);
-  w.pinvA = c.take<uint16_t>(kk * kInvPlanes);
-  w.pfwdB = c.take<uint16_t>(kk * kFwdPlanes);
-  w.pinvB = c.take<uint16_t>(kk * kInvPlanes);
-  w.hdrA = c.take<float>(size_t(pa.nslot + pb.nslot) * kHdrFloats);   // A then B, contiguous
-  w.hdrB = w.hdrA ? w.hdrA + size_t(pa.nslot) * kHdrFloats : nullptr;
-  w.gradA = c.take<float>(grad ? size_t(ga.nslot) * ga.slot_grad_floats : 0);
-  w.gradB = c.take<float>(grad ? size_t(gb.nslot) * gb.slot_grad_floats : 0);
-  w.gp = c.take<float>(grad ? size_t(nb) * pa.K * pa.K : 0);
-  w.x1 = c.take<float>(grad ? size_t(nb) * pa.K * pa.K : 0);
-  w.recA = c.take<float2>(grad && two_a ? size_t(pa.naxis / pa.G) * size_t(pa.nlines) : 0);
-  w.recB = c.take<float2>(grad && two_b ? size_t(pb.naxis / pb.G) * size_t(pb.nlines) : 0);
+  w.hdrA = c.take<float>(size_t(qa.first.nslot + qb.first.nslot) * kHdrFloats);   // A then B, contiguous
+  w.hdrB = w.hdrA ? w.hdrA + size_t(qa.first.nslot) * kHdrFloats : nullptr;
+  w.gp = c.take<float>(grad ? size_t(nb) * K * K : 0);
+  w.x1 = c.take<float>(grad ? size_t(nb) * K * K : 0);
+  carve_member(c, qa, nb, grad, false, &w.a);
+  carve_member(c, qb, nb, grad, false, &w.b);
   w.bytes = c.off;
   return w;
-}
-
-// Plans of one matrix for a call with / without gradient: `first` is the pass that computes
-// the losses, `gpass` the pass that writes the gradient partials (== first unless two-pass).
-// Whether the loss pass for (K, G) runs its forward contraction on two-part half-precision operands: the
-// gradient-free kernel variant over 128 x 128 blocks with one block per segment (with a gradient these
-// shapes take the two-pass scheme, so their loss pass is always gradient-free).
-bool core_forward_f16(int K, int G) { return K == 128 && G <= 128; }
-
-struct PassPlans { CorePlan first, gpass; bool two; };
-int plan_passes(int K, int G, int64_t nlines, int64_t naxis, bool grad, PassPlans* pp) {
-  pp->two = grad && two_pass_gradient(K, G);
-  int rc = make_plan(K, G, nlines, naxis, &pp->first, grad && !pp->two);
-  if (rc) return rc;
-  if (pp->two) return make_plan(K, G, nlines, naxis, &pp->gpass, true, true);
-  pp->gpass = pp->first;
-  return CAFEQ_OK;
 }
 
 int check_xform(const cafeq_xform* x, bool need_inv) {
@@ -172,19 +213,12 @@ int check_axis_len(const cafeq_mat* W, const cafeq_xform* x, int axis) {
   return CAFEQ_OK;
 }
 
-int resolve_group(const cafeq_quant_cfg* cfg, int64_t naxis, int* G) {
-  const int64_t g = cfg->group == 0 ? naxis : cfg->group;
-  if (naxis % g != 0) return CAFEQ_ERR_BAD_SHAPE;
-  if (!(g == 32 || g == 64 || g == 128 || g == 256)) return CAFEQ_ERR_UNSUPPORTED;
-  *G = int(g);
-  return CAFEQ_OK;
-}
-
 struct AdaptivePlan {
-  int GA, GB, nchunkA, nchunkB;
+  GroupPlan ga, gb;
+  int nchunkA, nchunkB;
   int64_t chunkA, chunkB;
   CorePlan planU, planV;
-  size_t partial_floats, bytes;
+  size_t partial_floats, rec_entries, grec_entries, bytes;
 };
 void split_contraction(int64_t tlen, int units, int64_t* chunk, int* nchunk) {
   // aim at about two workgroups per compute unit, chunks of at least 64 and a multiple of 16
@@ -195,25 +229,41 @@ void split_contraction(int64_t tlen, int units, int64_t* chunk, int* nchunk) {
   *chunk = ch;
   *nchunk = int((tlen + ch - 1) / ch);
 }
+struct AdaptiveWs {
+  float* partial; double* work; float *Cmat, *Sinv, *Rsum; uint16_t* planes; float2 *rec, *grec;
+};
+AdaptiveWs carve_adaptive(void* ws, const AdaptivePlan& ap, int k, int nb, size_t* bytes) {
+  Carver c(ws);
+  AdaptiveWs w;
+  w.partial = c.take<float>(ap.partial_floats);
+  w.work = c.take<double>(size_t(nb) * k * 4 * k);
+  w.Cmat = c.take<float>(size_t(nb) * k * k);
+  w.Sinv = c.take<float>(size_t(nb) * k * k);
+  w.Rsum = c.take<float>(size_t(nb) * k * k);
+  w.planes = c.take<uint16_t>(size_t(nb) * kFwdPlanes * k * k);
+  w.rec = c.take<float2>(ap.rec_entries);
+  w.grec = c.take<float2>(ap.grec_entries);
+  if (bytes) *bytes = c.off;
+  return w;
+}
 int plan_adaptive(const cafeq_quant_cfg* cfg, int k, int nb, int rep, int64_t rowsA, int64_t colsA,
                   int64_t rowsB, int64_t colsB, AdaptivePlan* ap) {
   int rc;
-  if ((rc = resolve_group(cfg, colsA, &ap->GA))) return rc;
-  if ((rc = resolve_group(cfg, rowsB, &ap->GB))) return rc;
-  if ((rc = make_plan(k, ap->GA, rowsA, colsA, &ap->planU, false))) return rc;
-  if ((rc = make_plan(k, ap->GB, colsB, rowsB, &ap->planV, false))) return rc;
+  if (!supported_block(k)) return CAFEQ_ERR_UNSUPPORTED;
+  if ((rc = resolve_group(cfg, colsA, k, &ap->ga))) return rc;
+  if ((rc = resolve_group(cfg, rowsB, k, &ap->gb))) return rc;
+  if ((rc = make_plan(k, ap->ga.Gk, rowsA, colsA, &ap->planU, false))) return rc;
+  if ((rc = make_plan(k, ap->gb.Gk, colsB, rowsB, &ap->planV, false))) return rc;
   split_contraction(rowsA, nb * (k / 32), &ap->chunkA, &ap->nchunkA);
   split_contraction(colsB, nb * rep * (k / 32), &ap->chunkB, &ap->nchunkB);
   const size_t nz = size_t(std::max(ap->nchunkA, rep * ap->nchunkB));
   ap->partial_floats = size_t(nb) * nz * 2 * k * k;
-  Carver c(nullptr);
-  c.take<float>(ap->partial_floats);
-  c.take<double>(size_t(nb) * k * 4 * k);
-  c.take<float>(size_t(nb) * k * k);
-  c.take<float>(size_t(nb) * k * k);
-  c.take<float>(size_t(nb) * k * k);
-  c.take<uint16_t>(size_t(nb) * kFwdPlanes * k * k);
-  ap->bytes = c.off;
+  // groups that span several segments: records of the requantization's first sweep
+  ap->rec_entries = std::max(ap->ga.gspan > 1 ? size_t(colsA / ap->ga.Gk) * size_t(rowsA) : 0,
+                             ap->gb.gspan > 1 ? size_t(rowsB / ap->gb.Gk) * size_t(colsB) : 0);
+  ap->grec_entries = std::max(ap->ga.gspan > 1 ? size_t(colsA / ap->ga.G) * size_t(rowsA) : 0,
+                              ap->gb.gspan > 1 ? size_t(rowsB / ap->gb.G) * size_t(colsB) : 0);
+  carve_adaptive(nullptr, *ap, k, nb, &ap->bytes);
   return CAFEQ_OK;
 }
 
@@ -221,12 +271,46 @@ void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep)
   p->W = W->data; p->dtype = W->dtype; p->rows = W->rows; p->cols = W->cols; p->ld = W->ld;
   p->rep = rep; p->nseg = pl.nseg; p->nlines = pl.nlines; p->mt_per_seg = pl.mt_per_seg;
   p->n_mt = pl.n_mt; p->nwg = pl.nwg;
+  p->Afwd = nullptr; p->Ainv = nullptr;
   p->do_inverse = 0; p->do_grad = 0; p->loss_kind = kLossSur; p->beta = 0.f; p->lse_t = 0.f;
   p->rG = nullptr; p->Zout = nullptr; p->codes = nullptr; p->scales = nullptr;
   p->slot_grad = nullptr; p->slot_hdr = nullptr;
   p->rec = nullptr; p->hdr_ref = nullptr; p->nslot_ref = 0; p->member_ref = nullptr;
   p->fscale = nullptr;
+  p->longg = 0; p->gspan = 1; p->grec = nullptr; p->grp = 0;
   p->grid = make_grid(4);
+}
+
+// Forward sweep(s) of the fused core over one matrix.  `p` holds everything but the group bookkeeping.  For
+// groups inside a segment this is one launch.  For groups that span gspan segments: a forward-only sweep that
+// records every segment's arg-max, the combination of the records per group, then the sweep proper, which
+// takes each group's absmax from the combined records (both sweeps run the same kernel variant, so they see
+// bit-identical transformed weights).
+int run_core(int K, int axis, const GroupPlan& gp, CoreParams p, float2* rec, float2* grec, bool want_rec,
+             hipStream_t st) {
+  int rc;
+  if (gp.gspan > 1) {
+    CoreParams s1 = p;
+    s1.do_inverse = 0; s1.do_grad = 0; s1.codes = nullptr; s1.scales = nullptr; s1.Zout = nullptr;
+    s1.slot_hdr = nullptr; s1.slot_grad = nullptr; s1.rec = rec; s1.longg = 1; s1.gspan = 1; s1.grec = nullptr;
+    if ((rc = launch_core(K, gp.Gk, axis, s1, st))) return rc;
+    if ((rc = launch_combine_records(rec, gp.gspan, gp.Gk, p.nlines, (p.nseg / gp.gspan), grec, st))) return rc;
+    p.longg = 1; p.gspan = gp.gspan; p.grec = grec; p.rec = nullptr;
+  } else {
+    p.rec = want_rec ? rec : nullptr;
+  }
+  return launch_core(K, gp.Gk, axis, p, st);
+}
+
+// The gradient pass of the two-pass scheme over one matrix (records in, gradient partials out).
+int run_grad_pass(int K, int axis, const cafeq_mat* W, int rep, const PassPlans& pp, const MemberWs& m,
+                  int loss_kind, float beta, float lse_t, const float* hdr_ref, int nslot_ref, float* member_ref,
+                  CoreParams* pg, hipStream_t st) {
+  fill_common(pg, W, pp.gpass, rep);
+  pg->loss_kind = loss_kind; pg->beta = beta; pg->lse_t = lse_t;
+  pg->rG = m.rGreal; pg->slot_grad = m.slot_grad; pg->rec = m.grec; pg->grp = pp.gp.G;
+  pg->hdr_ref = hdr_ref; pg->nslot_ref = nslot_ref; pg->member_ref = member_ref;
+  return launch_grad_pass(K, axis, *pg, st);
 }
 
 }  // namespace
@@ -308,7 +392,7 @@ int cafeq_pqe(const float* U, const float* V, int64_t rowsA, int64_t colsA, int6
   float* partialU = c.take<float>(size_t(nb) * ap.nchunkA * 3 * kk);
   float* partialV = c.take<float>(size_t(nb) * rep * ap.nchunkB * 3 * kk);
   double* sums = c.take<double>(size_t(nb) * (1 + rep) * 3 * kk + 2 * size_t(nb) * rep);
-  return launch_pqe(U, V, rowsA, colsA, rowsB, colsB, k, ap.GA, ap.GB, nb, rep, codesU, scalesU, codesV, scalesV,
+  return launch_pqe(U, V, rowsA, colsA, rowsB, colsB, k, ap.ga.G, ap.gb.G, nb, rep, codesU, scalesU, codesV, scalesV,
                     ap.chunkA, ap.nchunkA, ap.chunkB, ap.nchunkB, partialU, partialV, sums, out,
                     static_cast<hipStream_t>(stream));
 }
@@ -431,23 +515,26 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
       if (!a || !x || !cfg) return 0;
       const bool col = cfg->axis == CAFEQ_AXIS_COL;
       const int64_t naxis = col ? a->cols : a->rows, nlines = col ? a->rows : a->cols;
-      int G;
-      if (resolve_group(cfg, naxis, &G)) return 0;
+      GroupPlan gp;
+      if (resolve_group(cfg, naxis, x->k, &gp)) return 0;
       PassPlans pg, pn;
-      if (plan_passes(x->k, G, nlines, naxis, true, &pg) || plan_passes(x->k, G, nlines, naxis, false, &pn)) return 0;
-      return std::max(carve_single(nullptr, pg.first, pg.gpass, x->nb, true, pg.two).bytes,
-                      carve_single(nullptr, pn.first, pn.gpass, x->nb, false, false).bytes);
+      if (plan_passes(x->k, gp, nlines, naxis, false, &pn)) return 0;
+      size_t bytes = carve_single(nullptr, pn, x->nb, false).bytes;
+      // (where the gradient has no kernel the forward-only size is still reported)
+      if (!plan_passes(x->k, gp, nlines, naxis, true, &pg)) bytes = std::max(bytes, carve_single(nullptr, pg, x->nb, true).bytes);
+      return bytes;
     }
     case CAFEQ_CALL_DUAL_PROXY_LOSS: {
       if (!a || !b || !x || !cfg) return 0;
-      int GA, GB;
-      if (resolve_group(cfg, a->cols, &GA) || resolve_group(cfg, b->rows, &GB)) return 0;
-      PassPlans ga, gb, na, nbp;
-      if (plan_passes(x->k, GA, a->rows, a->cols, true, &ga) || plan_passes(x->k, GB, b->cols, b->rows, true, &gb) ||
-          plan_passes(x->k, GA, a->rows, a->cols, false, &na) || plan_passes(x->k, GB, b->cols, b->rows, false, &nbp))
+      GroupPlan ga, gb;
+      if (resolve_group(cfg, a->cols, x->k, &ga) || resolve_group(cfg, b->rows, x->k, &gb)) return 0;
+      PassPlans qa, qb, na, nbp;
+      if (plan_passes(x->k, ga, a->rows, a->cols, false, &na) || plan_passes(x->k, gb, b->cols, b->rows, false, &nbp))
         return 0;
-      return std::max(carve_dual(nullptr, ga.first, gb.first, ga.gpass, gb.gpass, x->nb, true, ga.two, gb.two).bytes,
-                      carve_dual(nullptr, na.first, nbp.first, na.gpass, nbp.gpass, x->nb, false, false, false).bytes);
+      size_t bytes = carve_dual(nullptr, na, nbp, x->nb, false).bytes;
+      if (!plan_passes(x->k, ga, a->rows, a->cols, true, &qa) && !plan_passes(x->k, gb, b->cols, b->rows, true, &qb))
+        bytes = std::max(bytes, carve_dual(nullptr, qa, qb, x->nb, true).bytes);
+      return bytes;
     }
     case CAFEQ_CALL_ORTH_PENALTY:
       if (!x) return 0;
@@ -558,7 +645,7 @@ int cafeq_apply_transform(const cafeq_mat* W, const cafeq_xform* x, int axis, in
   uint16_t* planes = static_cast<uint16_t*>(ws);
   // half-precision forward operands where the kernel variant exists: two planes, and the per-block factors
   // in the room of the third
-  float* fs = core_forward_f16(x->k, x->k) ? reinterpret_cast<float*>(planes + size_t(x->nb) * 2 * x->k * x->k) : nullptr;
+  float* fs = core_forward_f16(x->k, x->k, 4) ? reinterpret_cast<float*>(planes + size_t(x->nb) * 2 * x->k * x->k) : nullptr;
   {
     const SplitRequest req{side == CAFEQ_SIDE_T ? x->T : x->Tinv, planes, col ? 1 : 0, kFwdPlanes, fs};
     if ((rc = launch_split_planes_multi(&req, 1, x->k, x->nb, st))) return rc;
@@ -587,53 +674,54 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
     return CAFEQ_ERR_BAD_ALIGN;
   const bool col = cfg->axis == CAFEQ_AXIS_COL;
   const int64_t naxis = col ? W->cols : W->rows, nlines = col ? W->rows : W->cols;
-  int G;
-  rc = resolve_group(cfg, naxis, &G);
-  if (rc) return rc;
   const int K = x->k, nb = x->nb;
+  GroupPlan gp;
+  rc = resolve_group(cfg, naxis, K, &gp);
+  if (rc) return rc;
+  const bool grad = gradT != nullptr;
   PassPlans pp;
-  rc = plan_passes(K, G, nlines, naxis, gradT != nullptr, &pp);
+  rc = plan_passes(K, gp, nlines, naxis, grad, &pp);
   if (rc) return rc;
   const CorePlan& pl = pp.first;
   {
-    const size_t lds = core_lds_bytes(K, G, gradT != nullptr && !pp.two);
+    const size_t lds = core_lds_bytes(K, gp.Gk, pp.fused);
     if (lds == 0 || lds > kLdsLimit) return CAFEQ_ERR_UNSUPPORTED;
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
-  SingleWs w = carve_single(ws, pl, pp.gpass, nb, gradT != nullptr, pp.two);
+  SingleWs w = carve_single(ws, pp, nb, grad);
   const QGrid grid = make_grid(cfg->bits);
   const float beta = 1.f / (4.f * grid.qmax * grid.qmax);
+  const bool f16 = core_forward_f16(K, gp.Gk, cfg->bits);
 
+  // rho per axis index, its sums per segment-level group (the loss sweep) and per group (the gradient pass)
   if ((rc = launch_rho(x->Tinv, K, nb, col ? 1 : 0, w.rho, st))) return rc;
-  if ((rc = launch_rho_groups(w.rho, K, x->rep, G, naxis / G, w.rG, st))) return rc;
+  if ((rc = launch_rho_groups(w.rho, K, x->rep, gp.Gk, naxis / gp.Gk, w.m.rG, st))) return rc;
+  if (gp.gspan > 1 && (rc = launch_rho_groups(w.rho, K, x->rep, gp.G, naxis / gp.G, w.m.rGreal, st))) return rc;
 
   CoreParams p;
   fill_common(&p, W, pl, x->rep);
   // forward operand [out][in]: T^T (COL) or T (ROW); inverse operand: Tinv^T or Tinv
   {
-    const SplitRequest req[2] = {{x->T, w.pfwd, col ? 1 : 0, kFwdPlanes, core_forward_f16(K, G) ? w.fs : nullptr},
-                                 {x->Tinv, w.pinv, col ? 1 : 0, kInvPlanes}};
+    const SplitRequest req[2] = {{x->T, w.m.pfwd, col ? 1 : 0, kFwdPlanes, f16 ? w.m.fs : nullptr},
+                                 {x->Tinv, w.m.pinv, col ? 1 : 0, kInvPlanes}};
     if ((rc = launch_split_planes_multi(req, 2, K, nb, st, w.slot_hdr, pl.nslot))) return rc;
   }
-  p.Afwd = w.pfwd; p.Ainv = w.pinv; p.fscale = core_forward_f16(K, G) ? w.fs : nullptr;
-  p.grid = grid; p.do_inverse = 1; p.do_grad = (gradT && !pp.two) ? 1 : 0; p.loss_kind = kLossSur; p.beta = beta;
-  p.rG = w.rG; p.codes = codes; p.scales = scales; p.slot_grad = w.slot_grad; p.slot_hdr = w.slot_hdr;
-  p.rec = pp.two ? w.rec : nullptr;
-  if ((rc = launch_core(K, G, cfg->axis, p, st))) return rc;
+  p.Afwd = w.m.pfwd; p.Ainv = w.m.pinv; p.fscale = f16 ? w.m.fs : nullptr;
+  p.grid = grid; p.do_inverse = 1; p.do_grad = pp.fused ? 1 : 0; p.loss_kind = kLossSur; p.beta = beta;
+  p.rG = w.m.rG; p.codes = codes; p.scales = scales; p.slot_grad = w.m.slot_grad; p.slot_hdr = w.slot_hdr;
+  if ((rc = run_core(K, cfg->axis, gp, p, w.m.rec, w.m.grec, pp.two, st))) return rc;
   if ((rc = launch_reduce_losses(kLossSur, w.slot_hdr, int(pl.nslot), nullptr, 0, beta, 0.f, 0, losses,
                                  w.lse_ms, st)))
     return rc;
-  if (gradT) {
+  if (grad) {
     // path through Z (fused into the pass above, or a second pass over the weights from its
     // arg-max records), then the path through rho(P): -2 P^T Mmid P^T
     CoreParams pg = p;
-    if (pp.two) {
-      fill_common(&pg, W, pp.gpass, x->rep);
-      pg.loss_kind = kLossSur; pg.beta = beta; pg.rG = w.rG; pg.slot_grad = w.slot_grad; pg.rec = w.rec;
-      if ((rc = launch_grad_k128(G, cfg->axis, pg, st))) return rc;
-    }
-    if ((rc = launch_reduce_grad(pg, K, G, nb, col ? 1 : 0, nullptr, nullptr, gradT, st))) return rc;
-    if ((rc = launch_build_mmid(p, K, G, nb, x->Tinv, col ? 1 : 0, w.mmid, st))) return rc;
+    if (pp.two &&
+        (rc = run_grad_pass(K, cfg->axis, W, x->rep, pp, w.m, kLossSur, beta, 0.f, nullptr, 0, nullptr, &pg, st)))
+      return rc;
+    if ((rc = launch_reduce_grad(pg, K, gp.Gk, pp.fused, nb, col ? 1 : 0, nullptr, nullptr, gradT, st))) return rc;
+    if ((rc = launch_build_mmid(p, K, gp.Gk, nb, x->Tinv, col ? 1 : 0, w.mmid, st))) return rc;
     if ((rc = launch_bgemm(true, false, x->Tinv, w.mmid, w.x1, K, nb, 1.f, 0.f, st))) return rc;
     if ((rc = launch_bgemm(false, true, w.x1, x->Tinv, gradT, K, nb, -2.f, 1.f, st))) return rc;
   }
@@ -657,27 +745,27 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   if (!ws) return CAFEQ_ERR_WORKSPACE;
   const int K = x->k, nb = x->nb;
   if (A->cols != int64_t(nb) * K || B->rows != int64_t(nb) * x->rep * K) return CAFEQ_ERR_BAD_SHAPE;
-  int GA, GB;
-  if ((rc = resolve_group(cfg, A->cols, &GA))) return rc;
-  if ((rc = resolve_group(cfg, B->rows, &GB))) return rc;
+  GroupPlan ga, gb;
+  if ((rc = resolve_group(cfg, A->cols, K, &ga))) return rc;
+  if ((rc = resolve_group(cfg, B->rows, K, &gb))) return rc;
   const bool grad = gradT != nullptr;
   PassPlans qa, qb;
-  if ((rc = plan_passes(K, GA, A->rows, A->cols, grad, &qa))) return rc;
-  if ((rc = plan_passes(K, GB, B->cols, B->rows, grad, &qb))) return rc;
+  if ((rc = plan_passes(K, ga, A->rows, A->cols, grad, &qa))) return rc;
+  if ((rc = plan_passes(K, gb, B->cols, B->rows, grad, &qb))) return rc;
   const CorePlan &pa = qa.first, &pb = qb.first;
   {
-    const size_t la = core_lds_bytes(K, GA, grad && !qa.two), lb = core_lds_bytes(K, GB, grad && !qb.two);
+    const size_t la = core_lds_bytes(K, ga.Gk, qa.fused), lb = core_lds_bytes(K, gb.Gk, qb.fused);
     if (la == 0 || lb == 0 || la > kLdsLimit || lb > kLdsLimit) return CAFEQ_ERR_UNSUPPORTED;
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
-  DualWs w = carve_dual(ws, pa, pb, qa.gpass, qb.gpass, nb, grad, qa.two, qb.two);
+  DualWs w = carve_dual(ws, qa, qb, nb, grad);
   const QGrid grid = make_grid(cfg->bits);
   // the gradient-free pass over 128 x 128 blocks (one block per segment) takes half-precision forward operands
-  const bool f16A = core_forward_f16(K, GA), f16B = core_forward_f16(K, GB);
+  const bool f16A = core_forward_f16(K, ga.Gk, cfg->bits), f16B = core_forward_f16(K, gb.Gk, cfg->bits);
 
   {
-    const SplitRequest req[4] = {{x->T, w.pfwdA, 1, kFwdPlanes, f16A ? w.fsA : nullptr}, {x->Tinv, w.pinvA, 1, kInvPlanes},
-                                 {x->Tinv, w.pfwdB, 0, kFwdPlanes, f16B ? w.fsB : nullptr}, {x->T, w.pinvB, 0, kInvPlanes}};
+    const SplitRequest req[4] = {{x->T, w.a.pfwd, 1, kFwdPlanes, f16A ? w.a.fs : nullptr}, {x->Tinv, w.a.pinv, 1, kInvPlanes},
+                                 {x->Tinv, w.b.pfwd, 0, kFwdPlanes, f16B ? w.b.fs : nullptr}, {x->T, w.b.pinv, 0, kInvPlanes}};
     if ((rc = launch_split_planes_multi(req, 4, K, nb, st, w.hdrA, pa.nslot + pb.nslot))) return rc;
   }
   // Each member: the loss pass, then (two-pass gradient) straight away the gradient pass over
@@ -686,43 +774,35 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   // rescales to the pair's.
   CoreParams a, ag;
   fill_common(&a, A, pa, 1);
-  a.Afwd = w.pfwdA; a.Ainv = w.pinvA;
-  a.grid = grid; a.do_inverse = 1; a.do_grad = (grad && !qa.two) ? 1 : 0; a.loss_kind = kLossLse; a.lse_t = lse_t;
-  a.codes = codesU; a.scales = scalesU; a.slot_grad = w.gradA; a.slot_hdr = w.hdrA;
-  a.rec = qa.two ? w.recA : nullptr;
-  a.fscale = f16A ? w.fsA : nullptr;
-  if ((rc = launch_core(K, GA, CAFEQ_AXIS_COL, a, st))) return rc;
+  a.Afwd = w.a.pfwd; a.Ainv = w.a.pinv;
+  a.grid = grid; a.do_inverse = 1; a.do_grad = qa.fused ? 1 : 0; a.loss_kind = kLossLse; a.lse_t = lse_t;
+  a.codes = codesU; a.scales = scalesU; a.slot_grad = w.a.slot_grad; a.slot_hdr = w.hdrA;
+  a.fscale = f16A ? w.a.fs : nullptr;
+  if ((rc = run_core(K, CAFEQ_AXIS_COL, ga, a, w.a.rec, w.a.grec, qa.two, st))) return rc;
   ag = a;
-  if (qa.two) {
-    fill_common(&ag, A, qa.gpass, 1);
-    ag.loss_kind = kLossLse; ag.lse_t = lse_t; ag.slot_grad = w.gradA; ag.rec = w.recA;
-    ag.hdr_ref = w.hdrA; ag.nslot_ref = int(pa.nslot); ag.member_ref = w.member_ref;
-    if ((rc = launch_grad_k128(GA, CAFEQ_AXIS_COL, ag, st))) return rc;
-  }
+  if (qa.two && (rc = run_grad_pass(K, CAFEQ_AXIS_COL, A, 1, qa, w.a, kLossLse, 0.f, lse_t, w.hdrA, int(pa.nslot),
+                                    w.member_ref, &ag, st)))
+    return rc;
 
   CoreParams b, bg;
   fill_common(&b, B, pb, x->rep);
-  b.Afwd = w.pfwdB; b.Ainv = w.pinvB;
-  b.grid = grid; b.do_inverse = 1; b.do_grad = (grad && !qb.two) ? 1 : 0; b.loss_kind = kLossLse; b.lse_t = lse_t;
-  b.codes = codesV; b.scales = scalesV; b.slot_grad = w.gradB; b.slot_hdr = w.hdrB;
-  b.rec = qb.two ? w.recB : nullptr;
-  b.fscale = f16B ? w.fsB : nullptr;
-  if ((rc = launch_core(K, GB, CAFEQ_AXIS_ROW, b, st))) return rc;
+  b.Afwd = w.b.pfwd; b.Ainv = w.b.pinv;
+  b.grid = grid; b.do_inverse = 1; b.do_grad = qb.fused ? 1 : 0; b.loss_kind = kLossLse; b.lse_t = lse_t;
+  b.codes = codesV; b.scales = scalesV; b.slot_grad = w.b.slot_grad; b.slot_hdr = w.hdrB;
+  b.fscale = f16B ? w.b.fs : nullptr;
+  if ((rc = run_core(K, CAFEQ_AXIS_ROW, gb, b, w.b.rec, w.b.grec, qb.two, st))) return rc;
   bg = b;
-  if (qb.two) {
-    fill_common(&bg, B, qb.gpass, x->rep);
-    bg.loss_kind = kLossLse; bg.lse_t = lse_t; bg.slot_grad = w.gradB; bg.rec = w.recB;
-    bg.hdr_ref = w.hdrB; bg.nslot_ref = int(pb.nslot); bg.member_ref = w.member_ref + 1;
-    if ((rc = launch_grad_k128(GB, CAFEQ_AXIS_ROW, bg, st))) return rc;
-  }
+  if (qb.two && (rc = run_grad_pass(K, CAFEQ_AXIS_ROW, B, x->rep, qb, w.b, kLossLse, 0.f, lse_t, w.hdrB, int(pb.nslot),
+                                    w.member_ref + 1, &bg, st)))
+    return rc;
 
-  const int64_t ngroups = A->rows * (A->cols / GA) + (B->rows / GB) * B->cols;
+  const int64_t ngroups = A->rows * (A->cols / ga.G) + (B->rows / gb.G) * B->cols;
   if ((rc = launch_reduce_losses(kLossLse, w.hdrA, int(pa.nslot), w.hdrB, int(pb.nslot), 0.f, lse_t, ngroups,
                                  losses, w.lse_ms, st)))
     return rc;
   if (grad) {
     // member A into gradT; member B: G_P of transform block b sums its rep row-blocks; d/dT = -P^T G_P P^T
-    if ((rc = launch_reduce_grad_pair(ag, GA, qa.two ? w.member_ref : nullptr, gradT, bg, GB,
+    if ((rc = launch_reduce_grad_pair(ag, ga.Gk, qa.fused, qa.two ? w.member_ref : nullptr, gradT, bg, gb.Gk, qb.fused,
                                       qb.two ? w.member_ref + 1 : nullptr, w.gp, K, nb, w.lse_ms, st)))
       return rc;
     if ((rc = launch_bgemm(true, false, x->Tinv, w.gp, w.x1, K, nb, 1.f, 0.f, st))) return rc;
@@ -749,42 +829,36 @@ int cafeq_adaptive_round_step(const float* U, const float* V, int64_t rowsA, int
   AdaptivePlan ap;
   if ((rc = plan_adaptive(cfg, k, nb, rep, rowsA, colsA, rowsB, colsB, &ap))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  Carver c(ws);
-  float* partial = c.take<float>(ap.partial_floats);
-  double* work = c.take<double>(size_t(nb) * k * 4 * k);
-  float* Cmat = c.take<float>(size_t(nb) * k * k);
-  float* Sinv = c.take<float>(size_t(nb) * k * k);
-  float* Rsum = c.take<float>(size_t(nb) * k * k);
-  uint16_t* planes = c.take<uint16_t>(size_t(nb) * kFwdPlanes * k * k);
+  const AdaptiveWs w = carve_adaptive(ws, ap, k, nb, nullptr);
   const QGrid grid = make_grid(cfg->bits);
 
   if (half == 0 || half == 1) {
     // line 3: C = pinv(Uq_b) U_b per head, Vq <- Q(C V_q)
-    if ((rc = launch_gram_pair(CAFEQ_AXIS_COL, U, codesU, scalesU, rowsA, colsA, k, ap.GA, nb, 1, ap.chunkA,
-                               ap.nchunkA, partial, st)))
+    if ((rc = launch_gram_pair(CAFEQ_AXIS_COL, U, codesU, scalesU, rowsA, colsA, k, ap.ga.G, nb, 1, ap.chunkA,
+                               ap.nchunkA, w.partial, st)))
       return rc;
-    if ((rc = launch_gj_solve(k, nb, ap.nchunkA, partial, work, Sinv, Rsum, Cmat, status, 2, 0, st))) return rc;
+    if ((rc = launch_gj_solve(k, nb, ap.nchunkA, w.partial, w.work, w.Sinv, w.Rsum, w.Cmat, status, 2, 0, st))) return rc;
     cafeq_mat mv{V, rowsB, colsB, colsB, CAFEQ_F32};
     CoreParams p;
     fill_common(&p, &mv, ap.planV, rep);
-    if ((rc = launch_split_planes(Cmat, k, nb, 0, kFwdPlanes, planes, st))) return rc;
-    p.Afwd = planes; p.Ainv = nullptr;
+    if ((rc = launch_split_planes(w.Cmat, k, nb, 0, kFwdPlanes, w.planes, st))) return rc;
+    p.Afwd = w.planes; p.Ainv = nullptr;
     p.grid = grid; p.codes = codesV; p.scales = scalesV;
-    if ((rc = launch_core(k, ap.GB, CAFEQ_AXIS_ROW, p, st))) return rc;
+    if ((rc = run_core(k, CAFEQ_AXIS_ROW, ap.gb, p, w.rec, w.grec, false, st))) return rc;
   }
   if (half == 0 || half == 2) {
     // line 4: C^T = V_[b] pinv(Vq_[b]) per head, Uq_b <- Q(U_b C^T)
-    if ((rc = launch_gram_pair(CAFEQ_AXIS_ROW, V, codesV, scalesV, rowsB, colsB, k, ap.GB, nb, rep, ap.chunkB,
-                               ap.nchunkB, partial, st)))
+    if ((rc = launch_gram_pair(CAFEQ_AXIS_ROW, V, codesV, scalesV, rowsB, colsB, k, ap.gb.G, nb, rep, ap.chunkB,
+                               ap.nchunkB, w.partial, st)))
       return rc;
-    if ((rc = launch_gj_solve(k, nb, rep * ap.nchunkB, partial, work, Sinv, Rsum, Cmat, status, 2, 1, st))) return rc;
+    if ((rc = launch_gj_solve(k, nb, rep * ap.nchunkB, w.partial, w.work, w.Sinv, w.Rsum, w.Cmat, status, 2, 1, st))) return rc;
     cafeq_mat mu{U, rowsA, colsA, colsA, CAFEQ_F32};
     CoreParams p;
     fill_common(&p, &mu, ap.planU, 1);
-    if ((rc = launch_split_planes(Cmat, k, nb, 0, kFwdPlanes, planes, st))) return rc;
-    p.Afwd = planes; p.Ainv = nullptr;
+    if ((rc = launch_split_planes(w.Cmat, k, nb, 0, kFwdPlanes, w.planes, st))) return rc;
+    p.Afwd = w.planes; p.Ainv = nullptr;
     p.grid = grid; p.codes = codesU; p.scales = scalesU;
-    if ((rc = launch_core(k, ap.GA, CAFEQ_AXIS_COL, p, st))) return rc;
+    if ((rc = run_core(k, CAFEQ_AXIS_COL, ap.ga, p, w.rec, w.grec, false, st))) return rc;
   }
   return CAFEQ_OK;
 }

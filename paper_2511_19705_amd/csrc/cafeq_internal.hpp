@@ -35,8 +35,12 @@ int launch_core_k32(int G, int axis, const CoreParams& p, hipStream_t st);
 int launch_core_k64(int G, int axis, const CoreParams& p, hipStream_t st);
 int launch_core_k128(int G, int axis, const CoreParams& p, hipStream_t st);
 int launch_core_k256(int G, int axis, const CoreParams& p, hipStream_t st);
-// gradient pass of the two-pass scheme (K = 128, segments up to 128)
-int launch_grad_k128(int G, int axis, const CoreParams& p, hipStream_t st);
+// gradient pass of the two-pass scheme (grad_core.hpp): any block size, p.grp = group length
+int launch_grad_pass(int K, int axis, const CoreParams& p, hipStream_t st);
+size_t grad_pass_part_floats(int K);
+// records of the segments of every group -> one record per group (groups spanning gspan segments of L)
+int launch_combine_records(const float2* rec, int gspan, int L, int64_t nlines, int64_t ngroups, float2* grec,
+                           hipStream_t st);
 // LDS bytes the core needs (0 if the gradient accumulator cannot fit with do_grad)
 size_t core_lds_bytes(int K, int G, bool do_grad);
 size_t core_lds_bytes_k32(int G, bool do_grad);
@@ -54,11 +58,11 @@ int launch_split_planes_multi(const SplitRequest* req, int n, int K, int nb, hip
                               int64_t nslot = 0);
 int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_t st);
 int launch_rho_groups(const float* rho, int K, int rep, int G, int64_t ngroups, float* rG, hipStream_t st);
-int launch_reduce_grad(const CoreParams& p, int K, int G, int nb, int transpose_out, const double* lse_ms,
-                       const float* member_ref, float* out, hipStream_t st);
-int launch_reduce_grad_pair(const CoreParams& pa, int GA, const float* refA, float* outA, const CoreParams& pb,
-                            int GB, const float* refB, float* outB, int K, int nb, const double* lse_ms,
-                            hipStream_t st);
+int launch_reduce_grad(const CoreParams& p, int K, int G, bool fused, int nb, int transpose_out,
+                       const double* lse_ms, const float* member_ref, float* out, hipStream_t st);
+int launch_reduce_grad_pair(const CoreParams& pa, int GA, bool fusedA, const float* refA, float* outA,
+                            const CoreParams& pb, int GB, bool fusedB, const float* refB, float* outB, int K,
+                            int nb, const double* lse_ms, hipStream_t st);
 int launch_build_mmid(const CoreParams& p, int K, int G, int nb, const float* P, int scale_rows, float* Mmid,
                       hipStream_t st);
 int launch_reduce_losses(int kind, const float* hdrA, int nslotA, const float* hdrB, int nslotB, float beta,

@@ -3,12 +3,21 @@
 // pass of the fused kernel.  (Paper Sec. 4.1: gradient of the surrogate through the transformed
 // weights; Sec. 4.2: of the LogSumExp surrogate.)
 //
-// Same decomposition as the fused kernel: a workgroup owns a contiguous, segment-major range of
-// macro-tiles (128 lines x one segment), a wave 32 lines.  Per macro-tile the waves split their
+// The axis is cut into chunks of 128 inputs.  A workgroup owns a contiguous, chunk-major range of
+// macro-tiles (128 lines x one chunk), a wave 32 lines.  Per macro-tile the waves split their
 // weights exactly into bfloat16 hi + mid parts and park them in LDS transposed, [input m][line];
-// then wave r accumulates tile row r of the segment's k x k gradient blocks over the 128 lines on
-// the matrix cores (three part products, float32 accumulation, operands: S^T built in registers
-// from the records, W parts from LDS).  One partial per (workgroup, segment), reduced in fixed
+// then every wave accumulates its tile rows (32 outputs j each) of the k x k gradient blocks the
+// chunk's inputs belong to, over the 128 lines, on the matrix cores (three part products, float32
+// accumulation, operands: S^T built in registers from the records, W parts from LDS):
+//   K <= 128: the chunk holds 128 / K whole blocks; tile row r (r = wave) lies in block 32 r / K and has
+//             K / 32 tiles (the block's inputs);
+//   K == 256: the chunk is one half of a block's inputs; all eight tile rows of the block (two per
+//             wave) meet it, four tiles each -- the two halves are different chunks, so every weight
+//             is still read once.
+// The group length is a run-time value (any multiple of 32, whole channels included): a tile row of
+// 32 outputs lies inside one group, whose record (signed value at the arg-max, index inside the
+// group) decides whether and where the line's coefficient falls into the row.
+// One partial per (workgroup, chunk) -- [128 or 256 outputs][K or 128 inputs] -- reduced in fixed
 // order by reduce_grad_kernel.
 #pragma once
 #include "xform_core.hpp"
@@ -66,16 +75,31 @@ struct StripLoader {
   }
 };
 
-template <int K, int G, int AXIS>
-__global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p) {
-  using g = Geo<K, G>;
-  static_assert(g::GRAD_OK, "no gradient for this (K, G)");
-  constexpr int L = g::L, NT = g::NT, KT = g::KT, NGRP = g::NGRP, NBLK = g::NBLK;
+template <int K>
+struct GradGeo {
+  static constexpr int CH = 128;                        // inputs per chunk
+  static constexpr int KM = K < 128 ? K : 128;          // inputs of one tile row's block inside the chunk
+  static constexpr int MT = KM / 32;                    // tiles per tile row
+  static constexpr int JR = K == 256 ? 8 : 4;           // tile rows that meet a chunk
+  static constexpr int JRW = JR / kNW;                  // ... per wave
+  static constexpr int GT = JRW * MT;                   // accumulator tiles per wave
+  static constexpr int PART = JR * 32 * KM;             // floats of one partial
+  static constexpr int WST_ROWB = 2 * kMacroLines + 16;
+  static constexpr int WST_PLANEB = CH * WST_ROWB;
+  static constexpr int LDSB = 2 * WST_PLANEB + JR * kMacroLines * (2 + 4) + 64;
+};
+
+// (Blocks of 256: eight accumulator tiles per wave next to the 64 weight registers do not fit in half the
+// register file, so that variant runs one workgroup per compute unit.)
+template <int K, int AXIS>
+__global__ __launch_bounds__(kThreads, K == 256 ? 1 : 2) void grad_z_kernel(const CoreParams p) {
+  using g = GradGeo<K>;
+  constexpr int L = g::CH, KM = g::KM, MT = g::MT, JR = g::JR, JRW = g::JRW;
   extern __shared__ __align__(16) unsigned char smem[];
-  unsigned char* wst = smem;                                              // [2 parts][L][WST_ROWB]
-  int16_t* jst = reinterpret_cast<int16_t*>(wst + 2 * g::WST_PLANEB);     // [NGRP][128 lines]
-  uint32_t* cfp = reinterpret_cast<uint32_t*>(wst + 2 * g::WST_PLANEB + NGRP * kMacroLines * 2);
-  float* red = reinterpret_cast<float*>(smem + g::GRADB);                 // [kNW]
+  unsigned char* wst = smem;                                              // [2 parts][128 inputs][WST_ROWB]
+  int16_t* jst = reinterpret_cast<int16_t*>(wst + 2 * g::WST_PLANEB);     // [JR][128 lines]
+  uint32_t* cfp = reinterpret_cast<uint32_t*>(wst + 2 * g::WST_PLANEB + JR * kMacroLines * 2);
+  float* red = reinterpret_cast<float*>(wst + 2 * g::WST_PLANEB + JR * kMacroLines * 6);   // [kNW]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, h = lane >> 5;
@@ -99,12 +123,12 @@ __global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p)
   if (mt0 >= mt1) return;
 
   const int mt_per_seg = int(p.mt_per_seg);
-  int seg = int(mt0 / p.mt_per_seg);
+  int seg = int(mt0 / p.mt_per_seg);                  // chunk of 128 inputs
   int mis = int(mt0 - int64_t(seg) * p.mt_per_seg);
   int cur_seg = seg;
 
-  // gradient tiles of this wave: tile rows r = wave, wave + 4, ... (< NT), KT tiles each;
-  // element [j = r*32 + 8(v/4)+4h+v%4][m = mt*32 + ln] of the segment's k x k blocks
+  // gradient tiles of this wave: tile rows r = wave (+ 4), MT tiles each; element
+  // [j = r*32 + 8(v/4)+4h+v%4][m = mt*32 + ln] of the partial
   floatx16 gt[g::GT];
 #pragma unroll
   for (int i = 0; i < g::GT; ++i)
@@ -112,20 +136,17 @@ __global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p)
     for (int v = 0; v < 16; ++v) gt[i][v] = 0.f;
 
   auto flush = [&](int sg_) {
-    float* dst = p.slot_grad + (w + sg_) * int64_t(NBLK * K * K);
+    float* dst = p.slot_grad + (w + sg_) * int64_t(g::PART);
 #pragma unroll
-    for (int gr = 0; gr < g::GT_ROWS; ++gr) {
+    for (int gr = 0; gr < JRW; ++gr) {
       const int r = wave + gr * kNW;
-      if (r < NT) {
-        const int blk = r / KT, jt = r % KT;
 #pragma unroll
-        for (int mt_ = 0; mt_ < KT; ++mt_) {
+      for (int mt_ = 0; mt_ < MT; ++mt_) {
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int j = jt * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-            dst[(blk * K + j) * K + mt_ * 32 + ln] = gt[gr * KT + mt_][v];
-            gt[gr * KT + mt_][v] = 0.f;
-          }
+        for (int v = 0; v < 16; ++v) {
+          const int j = r * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+          dst[j * KM + mt_ * 32 + ln] = gt[gr * MT + mt_][v];
+          gt[gr * MT + mt_][v] = 0.f;
         }
       }
     }
@@ -137,14 +158,20 @@ __global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p)
 #pragma unroll
   for (int c = 0; c < L / 8; ++c) loader.chunk(c);
   loader.finish();
-  // the records of a strip (lanes of the first half only) are fetched with its weights
-  float2 recv[NGRP];
+  // The records of a strip (lanes of the first half only) are fetched with its weights: one per tile
+  // row, that of the group the row's 32 outputs lie in.  joff: the row's first output inside its group.
+  float2 recv[JR];
+  int joff[JR];
   auto load_rec = [&](int sg_, int ms_) {
     const int64_t line = int64_t(ms_) * kMacroLines + wave * kStripLines + ln;
+    const int64_t a0 = K == 256 ? int64_t(sg_ >> 1) * 256 : int64_t(sg_) * 128;   // first output of tile row 0
 #pragma unroll
-    for (int gi = 0; gi < NGRP; ++gi) {
-      recv[gi] = make_float2(0.f, 0.f);
-      if (h == 0 && line < p.nlines) recv[gi] = p.rec[(int64_t(sg_) * NGRP + gi) * p.nlines + line];
+    for (int r = 0; r < JR; ++r) {
+      const int64_t aj = a0 + 32 * r;
+      const int64_t gi = aj / p.grp;
+      joff[r] = int(aj - gi * p.grp);
+      recv[r] = make_float2(0.f, 0.f);
+      if (h == 0 && line < p.nlines) recv[r] = p.rec[gi * p.nlines + line];
     }
   };
   load_rec(seg, mis);
@@ -182,27 +209,31 @@ __global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p)
         *reinterpret_cast<uint32_t*>(r0 + g::WST_PLANEB) = __builtin_amdgcn_perm(om, pm, pair_sel);
       }
     }
-    // ---- (arg-max, coefficient) of every group of this line
+    // ---- per tile row: where this line's arg-max falls inside the row (-1: not in it) and its coefficient
     if (h == 0) {
 #pragma unroll
-      for (int gi = 0; gi < NGRP; ++gi) {
+      for (int r = 0; r < JR; ++r) {
         float coef = 0.f;
-        int j = 0;
+        int jl = -1;
         if (valid) {
-          const float2 r = recv[gi];
-          j = __float_as_int(r.y);
-          if (p.loss_kind == kLossSur) {
-            coef = 2.f * p.beta * p.rG[seg * NGRP + gi] * r.x;
-          } else {
-            const float e = __expf(p.lse_t * (fabsf(r.x) - m_mem));
-            coef = r.x < 0.f ? -e : e;
+          const float2 rc = recv[r];
+          const int jj = __float_as_int(rc.y) - joff[r];
+          if (jj >= 0 && jj < 32) {
+            jl = jj;
+            if (p.loss_kind == kLossSur) {
+              const int64_t a0 = K == 256 ? int64_t(seg >> 1) * 256 : int64_t(seg) * 128;
+              coef = 2.f * p.beta * p.rG[(a0 + 32 * r) / p.grp] * rc.x;
+            } else {
+              const float e = __expf(p.lse_t * (fabsf(rc.x) - m_mem));
+              coef = rc.x < 0.f ? -e : e;
+            }
           }
         }
         // coefficient as an exact-to-16-bit bfloat16 pair (hi in the low half, lo in the high half)
         const uint32_t ch = pack_bf16(coef, 0.f);
         const uint32_t cl = pack_bf16(coef - bf16_lo_f32(ch), 0.f);
-        jst[gi * kMacroLines + wave * kStripLines + ln] = int16_t(j);
-        cfp[gi * kMacroLines + wave * kStripLines + ln] = (ch & 0xFFFFu) | (cl << 16);
+        jst[r * kMacroLines + wave * kStripLines + ln] = int16_t(jl);
+        cfp[r * kMacroLines + wave * kStripLines + ln] = (ch & 0xFFFFu) | (cl << 16);
       }
     }
     // ---- the next strip's weights and records: addresses now, the loads spread over the
@@ -216,55 +247,51 @@ __global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p)
 
     // ---- G[j][m] += sum over the 128 lines of S[line][j] * W[line][m], 16 lines per MFMA step
 #pragma unroll
-    for (int gr = 0; gr < g::GT_ROWS; ++gr) {
+    for (int gr = 0; gr < JRW; ++gr) {
       const int r = wave + gr * kNW;
-      if (r < NT) {
-        const int jrow = r * 32 + ln;              // this lane's row of S^T
-        const int gi = jrow / G;                   // its group (uniform over the tile: G >= 32)
-        const int blk = r / KT;
+      const int mbase = K < 128 ? ((32 * r) / K) * K : 0;   // first input of the row's block inside the chunk
 #pragma unroll
-        for (int s = 0; s < kMacroLines / 16; ++s) {
-          const int l0 = 16 * s + 8 * h;
-          // this step's share of the next strip's weight loads (spread over the first tile row's steps)
-          if (gr == 0 && has_next) {
-            constexpr int per = (L / 8 + kMacroLines / 16 - 1) / (kMacroLines / 16);
+      for (int s = 0; s < kMacroLines / 16; ++s) {
+        const int l0 = 16 * s + 8 * h;
+        // this step's share of the next strip's weight loads (spread over the first tile row's steps)
+        if (gr == 0 && has_next) {
+          constexpr int per = (L / 8 + kMacroLines / 16 - 1) / (kMacroLines / 16);
 #pragma unroll
-            for (int c = s * per; c < (s + 1) * per && c < L / 8; ++c) loader.chunk(c);
-          }
-          // eight lines' arg-max indices and packed coefficients
-          const uintx4 jv = *reinterpret_cast<const uintx4*>(jst + gi * kMacroLines + l0);
-          const uintx4 c0 = *reinterpret_cast<const uintx4*>(cfp + gi * kMacroLines + l0);
-          const uintx4 c1 = *reinterpret_cast<const uintx4*>(cfp + gi * kMacroLines + l0 + 4);
-          uint32_t sel[8];
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int js = int((jv[e / 2] >> (16 * (e % 2))) & 0xFFFFu);
-            const uint32_t cv = e < 4 ? c0[e] : c1[e - 4];
-            sel[e] = js == jrow ? cv : 0u;
-          }
-          uintx4 sh, sl;
-#pragma unroll
-          for (int e2 = 0; e2 < 4; ++e2) {
-            sh[e2] = __builtin_amdgcn_perm(sel[2 * e2 + 1], sel[2 * e2], 0x05040100u);
-            sl[e2] = __builtin_amdgcn_perm(sel[2 * e2 + 1], sel[2 * e2], 0x07060302u);
-          }
-          const bf16x8 ash = as_bf16x8(sh), asl = as_bf16x8(sl);
-          // operands of all KT tiles first, then the three part products tile-interleaved, so that
-          // consecutive MFMAs never wait on each other's accumulator
-          bf16x8 bh[KT], bm[KT];
-#pragma unroll
-          for (int mt_ = 0; mt_ < KT; ++mt_) {
-            const unsigned char* wrow = wst + (blk * K + mt_ * 32 + ln) * g::WST_ROWB + l0 * 2;
-            bh[mt_] = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow));
-            bm[mt_] = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow + g::WST_PLANEB));
-          }
-#pragma unroll
-          for (int mt_ = 0; mt_ < KT; ++mt_) gt[gr * KT + mt_] = CAFEQ_MFMA_BF16(asl, bh[mt_], gt[gr * KT + mt_]);
-#pragma unroll
-          for (int mt_ = 0; mt_ < KT; ++mt_) gt[gr * KT + mt_] = CAFEQ_MFMA_BF16(ash, bm[mt_], gt[gr * KT + mt_]);
-#pragma unroll
-          for (int mt_ = 0; mt_ < KT; ++mt_) gt[gr * KT + mt_] = CAFEQ_MFMA_BF16(ash, bh[mt_], gt[gr * KT + mt_]);
+          for (int c = s * per; c < (s + 1) * per && c < L / 8; ++c) loader.chunk(c);
         }
+        // eight lines' positions inside this tile row and packed coefficients
+        const uintx4 jv = *reinterpret_cast<const uintx4*>(jst + r * kMacroLines + l0);
+        const uintx4 c0 = *reinterpret_cast<const uintx4*>(cfp + r * kMacroLines + l0);
+        const uintx4 c1 = *reinterpret_cast<const uintx4*>(cfp + r * kMacroLines + l0 + 4);
+        uint32_t sel[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int js = int((jv[e / 2] >> (16 * (e % 2))) & 0xFFFFu);
+          const uint32_t cv = e < 4 ? c0[e] : c1[e - 4];
+          sel[e] = js == ln ? cv : 0u;
+        }
+        uintx4 sh, sl;
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+          sh[e2] = __builtin_amdgcn_perm(sel[2 * e2 + 1], sel[2 * e2], 0x05040100u);
+          sl[e2] = __builtin_amdgcn_perm(sel[2 * e2 + 1], sel[2 * e2], 0x07060302u);
+        }
+        const bf16x8 ash = as_bf16x8(sh), asl = as_bf16x8(sl);
+        // operands of all MT tiles first, then the three part products tile-interleaved, so that
+        // consecutive MFMAs never wait on each other's accumulator
+        bf16x8 bh[MT], bm[MT];
+#pragma unroll
+        for (int mt_ = 0; mt_ < MT; ++mt_) {
+          const unsigned char* wrow = wst + (mbase + mt_ * 32 + ln) * g::WST_ROWB + l0 * 2;
+          bh[mt_] = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow));
+          bm[mt_] = as_bf16x8(*reinterpret_cast<const uintx4*>(wrow + g::WST_PLANEB));
+        }
+#pragma unroll
+        for (int mt_ = 0; mt_ < MT; ++mt_) gt[gr * MT + mt_] = CAFEQ_MFMA_BF16(asl, bh[mt_], gt[gr * MT + mt_]);
+#pragma unroll
+        for (int mt_ = 0; mt_ < MT; ++mt_) gt[gr * MT + mt_] = CAFEQ_MFMA_BF16(ash, bm[mt_], gt[gr * MT + mt_]);
+#pragma unroll
+        for (int mt_ = 0; mt_ < MT; ++mt_) gt[gr * MT + mt_] = CAFEQ_MFMA_BF16(ash, bh[mt_], gt[gr * MT + mt_]);
       }
     }
     if (has_next) loader.finish();
@@ -273,6 +300,24 @@ __global__ __launch_bounds__(kThreads, 2) void grad_z_kernel(const CoreParams p)
     mis = nmis;
   }
   flush(cur_seg);
+}
+
+// grec[group][line] = the record of the group's first segment with the largest magnitude (ties: the lowest
+// index wins, as inside a segment), its index moved from the segment to the group.  One thread per
+// (group, line); rec is [segment][line] (one group per segment in that sweep).
+__global__ __launch_bounds__(256) void combine_records_kernel(const float2* __restrict__ rec, int gspan, int L,
+                                                               int64_t nlines, int64_t ngroups,
+                                                               float2* __restrict__ grec) {
+  const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= ngroups * nlines) return;
+  const int64_t gi = i / nlines, line = i - gi * nlines;
+  float2 best = rec[(gi * gspan) * nlines + line];
+  int bs = 0;
+  for (int s = 1; s < gspan; ++s) {
+    const float2 r = rec[(gi * gspan + s) * nlines + line];
+    if (fabsf(r.x) > fabsf(best.x)) { best = r; bs = s; }
+  }
+  grec[i] = make_float2(best.x, __int_as_float(bs * L + __float_as_int(best.y)));
 }
 
 }  // namespace cafeq

@@ -122,6 +122,15 @@ struct CoreParams {
   const float* hdr_ref;     // gradient pass, kLossLse: the first pass's partial headers ...
   int nslot_ref;            // ... and their number: the member's reference is their largest m_ref
   float* member_ref;        // gradient pass, kLossLse: [1] receives that reference
+  // Groups longer than a segment (a whole channel, or any multiple of the segment): gspan = segments per
+  // group.  A first, forward-only sweep records every segment's arg-max (rec), a small kernel combines the
+  // records of a group's segments into grec[group][line] = (signed value at the group's arg-max, its index
+  // inside the group), and the loss sweep takes the group's absmax from there instead of its own scan.
+  int longg;                // run the long-group kernel variant (both of its sweeps)
+  int gspan;                // 1: every group lies inside one segment
+  const float2* grec;       // loss sweep with gspan > 1 (else null)
+  // gradient pass: group length along the axis, records indexed [axis group][line], index inside the group
+  int grp;
 };
 
 __device__ __forceinline__ int64_t chunk_begin(int64_t w, int64_t n_mt, int64_t nwg) {
@@ -237,9 +246,12 @@ __device__ __forceinline__ void load_strip(const CoreParams& p, float (&wreg)[L 
 // (hi.hi, hi.lo, lo.hi; relative error per term below 2^-20, the same order as the float32
 // accumulation) instead of six bfloat16 ones; the accumulators are scaled back before anything reads
 // them.  The inverse transform keeps the bfloat16 parts.
-template <int K, int G, int AXIS, bool GRAD, bool F16 = false>
+// LONGG: the variant for groups that span several segments (CoreParams::gspan; one group per segment inside
+// the kernel): its record-only sweep and its loss sweep with the group's absmax taken from the combined records.
+template <int K, int G, int AXIS, bool GRAD, bool F16 = false, bool LONGG = false>
 __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) void xform_core_kernel(const CoreParams p) {
   static_assert(!F16 || (!GRAD && Geo<K, G>::NBLK == 1), "half-precision forward: gradient-free, one block per segment");
+  static_assert(!LONGG || (!GRAD && Geo<K, G>::NGRP == 1), "long groups: gradient-free, one group per segment");
   using g = Geo<K, G>;
   constexpr bool GRAD_ON = GRAD && g::GRAD_OK;
   constexpr int GTN = GRAD_ON ? g::GT : 1;
@@ -565,7 +577,9 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
     }
 
     float err[L / 2];   // quantization error E = dequant(Q(Z)) - Z, same layout as the accumulators
-    const bool want_q = p.codes || p.scales || p.do_inverse;
+    const bool want_q = p.codes || p.scales || p.do_inverse || (LONGG && p.rec);
+    const bool big = LONGG && p.gspan > 1;                           // the group spans several segments
+    const bool first_of_group = !big || seg % p.gspan == 0;          // group-level sums are taken once
     const bool lse_on = p.loss_kind == kLossLse && p.do_inverse;
     if (want_q) {
       // ---- per-group absmax (+ argmax), codes, error in place
@@ -587,15 +601,28 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
         const int oj = __shfl_xor(j, 32);
         const float oa = fabsf(oz);
         if (oa > a || (oa == a && oj < j)) { a = oa; zs = oz; j = oj; }
+        if (p.rec && valid && h == 0)   // index relative to the group's first element
+          p.rec[(int64_t(seg) * NGRP + gi) * p.nlines + line] = make_float2(zs, __int_as_float(j - gi * G));
+        if constexpr (LONGG) if (big) {
+          // the group's absmax comes from the combined records (NGRP == 1 here)
+          const float2 r = p.grec[int64_t(seg / p.gspan) * p.nlines + (valid ? line : p.nlines - 1)];
+          zs = valid ? r.x : 0.f;
+          a = fabsf(zs);
+        }
         gz[gi] = zs; gj[gi] = j;
-        if (p.rec && valid && h == 0)
-          p.rec[(int64_t(seg) * NGRP + gi) * p.nlines + line] = make_float2(zs, __int_as_float(j));
+        if constexpr (LONGG) if (!(p.codes || p.scales || p.do_inverse)) continue;   // record-only sweep
         const float inv = grid_inv(a, p.grid.qmax);
         const float s = grid_scale(a, p.grid.qmax);
-        if (p.scales && valid && h == 0) {
-          const int64_t gidx = ax0 / G + gi;   // group index along the axis
-          if (AXIS == CAFEQ_AXIS_COL) p.scales[line * (p.cols / G) + gidx] = s;
-          else p.scales[gidx * p.cols + line] = s;
+        if (p.scales && valid && h == 0 && first_of_group) {
+          if (big) {
+            const int64_t gidx = seg / p.gspan, ng = p.nseg / p.gspan;
+            if (AXIS == CAFEQ_AXIS_COL) p.scales[line * ng + gidx] = s;
+            else p.scales[gidx * p.cols + line] = s;
+          } else {
+            const int64_t gidx = ax0 / G + gi;   // group index along the axis
+            if (AXIS == CAFEQ_AXIS_COL) p.scales[line * (p.cols / G) + gidx] = s;
+            else p.scales[gidx * p.cols + line] = s;
+          }
         }
 #pragma unroll
         for (int f4 = gi * RPG / 4; f4 < (gi + 1) * RPG / 4; ++f4) {
@@ -668,7 +695,7 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
             coef = 2.f * p.beta * p.rG[seg * NGRP + gi] * gz[gi];
           } else {
             const float e = valid ? __expf(p.lse_t * (fabsf(gz[gi]) - m_ref)) : 0.f;
-            if (h == 0) s_sur += e;
+            if (h == 0 && first_of_group) s_sur += e;
             coef = gz[gi] < 0.f ? -e : e;
           }
           if (GRAD_ON && p.do_grad && h == 0) {

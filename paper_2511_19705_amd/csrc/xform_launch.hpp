@@ -18,9 +18,9 @@ constexpr size_t core_lds_bytes_t(bool do_grad) {
 template <int K, int G>
 constexpr bool core_has_f16() { return K == 128 && Geo<K, G>::NBLK == 1; }
 
-template <int K, int G, int AXIS, bool GRAD, bool F16 = false>
+template <int K, int G, int AXIS, bool GRAD, bool F16 = false, bool LONGG = false>
 int launch_core_v(const CoreParams& p, size_t lds, hipStream_t st) {
-  auto kern = xform_core_kernel<K, G, AXIS, GRAD, F16>;
+  auto kern = xform_core_kernel<K, G, AXIS, GRAD, F16, LONGG>;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -39,6 +39,18 @@ int launch_core_t(const CoreParams& p, hipStream_t st) {
   if (lds == 0 || lds > kMaxLds) return CAFEQ_ERR_UNSUPPORTED;
   // half-precision forward planes (p.fscale set): only for the gradient-free variant, where it exists
   if (p.fscale && (p.do_grad || !core_has_f16<K, G>())) return CAFEQ_ERR_INVALID_ARG;
+  // groups that span several segments: the segment is one group of max(K, 128) (or K) elements
+  if (p.longg) {
+    if constexpr (G >= K && (G == K || G == 128)) {
+      if (p.do_grad) return CAFEQ_ERR_INVALID_ARG;
+      if constexpr (core_has_f16<K, G>()) {
+        if (p.fscale) return launch_core_v<K, G, AXIS, false, true, true>(p, lds, st);
+      }
+      return launch_core_v<K, G, AXIS, false, false, true>(p, lds, st);
+    } else {
+      return CAFEQ_ERR_UNSUPPORTED;
+    }
+  }
   if constexpr (Geo<K, G>::GRAD_OK) {
     if (p.do_grad) return launch_core_v<K, G, AXIS, true>(p, lds, st);
   }

@@ -45,3 +45,57 @@ def check_grad(g_gpu, g_ref, rel=REL):
     err = np.abs(g_gpu.astype(np.float64) - g_ref)
     assert err.max() <= rel * np.abs(g_ref).max(), "gradient max error %g vs scale %g" % (err.max(), np.abs(g_ref).max())
     assert np.linalg.norm(err) <= rel * np.linalg.norm(g_ref)
+
+
+def dual_argmax_flip_slack(A, B, T, P, ref, group, rep, t, tol=4e-6):
+    """Entrywise slack for the LogSumExp gradient of a pair: the sub-gradient differentiates each group's absmax
+    at its arg-max element, and where the two largest magnitudes of a group differ by less than the float32
+    accuracy of the transformed weights (relative ``tol``) either element is a correct choice.  For every such
+    group the gradient may move by  p_G * (e_j2 a^T - e_j1 a^T)  (member A; through -P^T . P^T for member B);
+    the sum of the absolute values of those moves bounds what a different, equally valid choice changes.
+    Returns (slack [nb][k][k], number of ambiguous groups)."""
+    A = np.asarray(A, dtype=np.float64)
+    B = np.asarray(B, dtype=np.float64)
+    P = np.asarray(P, dtype=np.float64)
+    nb, k, _ = P.shape
+    lse = ref["lse"]
+    slack_u = np.zeros((nb, k, k))
+    slack_gp = np.zeros((nb, k, k))
+    n_amb = 0
+    U, V = ref["U"], ref["V"]
+    d1, d3 = A.shape[0], B.shape[1]
+    gu = group if group else U.shape[1]
+    Ug = np.abs(U).reshape(d1, U.shape[1] // gu, gu)
+    top = np.argsort(Ug, axis=2)[:, :, -2:]                               # second largest, largest
+    a2 = np.take_along_axis(Ug, top[:, :, :1], 2)[:, :, 0]
+    a1 = np.take_along_axis(Ug, top[:, :, 1:], 2)[:, :, 0]
+    for i, gi in zip(*np.nonzero(a1 - a2 <= tol * a1)):
+        n_amb += 1
+        p = np.exp(t * (a1[i, gi] - lse))
+        for j in top[i, gi]:
+            ax = gi * gu + j
+            b = ax // k
+            slack_u[b, :, ax % k] += p * np.abs(A[i, b * k:(b + 1) * k])   # gradT_b[m][j] += p sign A[i][m]
+    gv = group if group else V.shape[0]
+    Vg = np.abs(V).reshape(V.shape[0] // gv, gv, d3)
+    top = np.argsort(Vg, axis=1)[:, -2:, :]
+    a2 = np.take_along_axis(Vg, top[:, :1, :], 1)[:, 0, :]
+    a1 = np.take_along_axis(Vg, top[:, 1:, :], 1)[:, 0, :]
+    for gi, c in zip(*np.nonzero(a1 - a2 <= tol * a1)):
+        n_amb += 1
+        p = np.exp(t * (a1[gi, c] - lse))
+        for j in top[gi, :, c]:
+            ax = gi * gv + j
+            q = ax // k
+            b = q // rep
+            slack_gp[b, ax % k, :] += p * np.abs(B[q * k:(q + 1) * k, c])  # G_P[b][j][m] += p sign B[q k + m][c]
+    aPt = np.abs(P).transpose(0, 2, 1)
+    return slack_u + aPt @ slack_gp @ aPt, n_amb
+
+
+def check_grad_with_slack(g_gpu, g_ref, slack, rel=REL):
+    g_ref = np.asarray(g_ref, dtype=np.float64)
+    err = np.abs(g_gpu.astype(np.float64) - g_ref)
+    assert np.all(err <= rel * np.abs(g_ref).max() + slack), \
+        "gradient max error %g vs scale %g (beyond the arg-max slack)" % (err.max(), np.abs(g_ref).max())
+    assert np.linalg.norm(err) <= rel * np.linalg.norm(g_ref) + np.linalg.norm(slack)

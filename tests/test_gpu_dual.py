@@ -20,7 +20,7 @@ def _dev(torch, a):
     return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
 
 
-def _check_dual(env, A, B, T, bits, group, rep, t=5.0, want_codes=True, scale=1.0):
+def _check_dual(env, A, B, T, bits, group, rep, t=5.0, want_codes=True, scale=1.0, flip_slack=False):
     torch, cafeq = env
     P = O.block_inverse(T).astype(np.float32)
     losses, grad, outs = cafeq.dual_proxy_loss_fwd_bwd(_dev(torch, A), _dev(torch, B), _dev(torch, T),
@@ -31,7 +31,15 @@ def _check_dual(env, A, B, T, bits, group, rep, t=5.0, want_codes=True, scale=1.
     for i, name in enumerate(("errU_sq", "errV_sq", "l2A_sq", "l2B_sq", "lse")):
         parity.check_scalar(losses[i], ref[name], what=name)
     assert int(losses[5]) == ref["n_groups"] or abs(losses[5] - ref["n_groups"]) <= 1e-6 * ref["n_groups"]
-    parity.check_grad(grad.cpu().numpy(), ref["gradT"])
+    if flip_slack:
+        # hundreds of thousands of groups: a few have two elements within float32 accuracy of the absmax, and
+        # the sub-gradient may take either; the bound below is exactly what such a choice can change
+        slack, n_amb = parity.dual_argmax_flip_slack(A, B, T, P, ref, group, rep, t)
+        print("groups with an ambiguous arg-max: %d of %d" % (n_amb, ref["n_groups"]))
+        assert n_amb <= max(3, 1e-4 * ref["n_groups"])
+        parity.check_grad_with_slack(grad.cpu().numpy(), ref["gradT"], slack)
+    else:
+        parity.check_grad(grad.cpu().numpy(), ref["gradT"])
     if want_codes:
         cu, su, cv, sv = [x.cpu().numpy() for x in outs]
         cu_ref, su_ref, _ = O.rtn_sym(ref["U"], bits, group, O.COL)

@@ -110,7 +110,7 @@ def test_config4_paired_quantization_error_full_size(env):
 
 
 def test_config4_dual_forward_full_size(env):
-    """The pair's losses at k = 256 (forward only: the gradient is not available for k = 256)."""
+    """The pair's losses at k = 256 without the gradient (the gradient at full size: test_gpu_long_groups.py)."""
     torch, cafeq = env
     c = WL.config4()
     A, B, T, rep, group, bits = c["A"], c["B"], c["T"], c["rep"], c["group"], c["bits"][0]
