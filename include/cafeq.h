@@ -67,11 +67,19 @@ typedef enum { CAFEQ_SIDE_T = 0, CAFEQ_SIDE_TINV = 1 } cafeq_side;
 typedef enum { CAFEQ_Q_SYM_ABSMAX = 0, CAFEQ_Q_ASYM_MINMAX = 1 } cafeq_qmode;
 
 /* Row-major matrix view. data: device pointer, 16-byte aligned; ld in elements, a
- * multiple of 4 (float32) or 8 (bfloat16); dtype: cafeq_dtype. */
+ * multiple of 4 (float32) or 8 (bfloat16); dtype: cafeq_dtype.
+ * prepared: NULL, or a device buffer written by cafeq_prepare_weights() for this matrix (same data,
+ * shape and the axis the call transforms).  The weights are constant over the thousands of loss
+ * evaluations of a learning run (paper Sec. 4.1, Sec. 4.2); with a prepared copy the loss pass of
+ * cafeq_proxy_loss_fwd_bwd / cafeq_dual_proxy_loss_fwd_bwd / cafeq_optimize_* reads them in the form
+ * the matrix cores consume (where a kernel for it exists: blocks of 128, groups up to 128, up to
+ * 4 bits; ignored otherwise).  `data` must stay valid either way: the gradient pass and every other
+ * configuration read it.  Entry points that do not mention it ignore the field. */
 typedef struct {
   const void* data;
   int64_t rows, cols, ld;
   int32_t dtype;
+  const void* prepared;
 } cafeq_mat;
 
 /* Block-diagonal transform. T and Tinv: device, [nb][k][k] float32, 16-byte aligned.
@@ -188,6 +196,16 @@ int cafeq_infer_single(const float* X, int n, int64_t ldx, const cafeq_xform* xf
  * Z: float32 [rows][cols] dense, must not alias W. */
 int cafeq_apply_transform(const cafeq_mat* W, const cafeq_xform* x, int axis, int side,
                           float* Z, void* ws, void* stream);
+
+/* Prepared weights (see cafeq_mat::prepared).  cafeq_prepared_bytes: size of the buffer for W transformed
+ * along `axis` (0 if the axis length is not a multiple of 128); about rows * cols * 4 bytes whatever the
+ * storage type.  cafeq_prepare_weights fills it (device memory, 256-byte aligned, owned by the caller):
+ * per tile of 32 lines x 128 axis indices two float16 parts of every element -- the line's segment scaled
+ * by a power of two so that its largest magnitude lies in [2^14, 2^15), hi = fl16(y), lo = fl16(y - hi):
+ * 22 significant bits -- in the order the loss kernel's matrix instructions read them, the per-line
+ * factors that undo the scaling, and ||W||_F^2 (float64 sum).  To be called again whenever W changes. */
+size_t cafeq_prepared_bytes(const cafeq_mat* W, int axis);
+int cafeq_prepare_weights(const cafeq_mat* W, int axis, void* prepared, void* stream);
 
 /* One evaluation for a single matrix (paper Sec. 4 and 4.1), transform along cfg->axis:
  *   Z = transform(W, T); Zq = dequant(Q(Z)); E = Zq - Z; D = transform(E, Tinv)

@@ -26,7 +26,7 @@ EXPORTS = (
     "cafeq_orth_penalty", "cafeq_sgd_update", "cafeq_adam_update", "cafeq_optimize_single",
     "cafeq_optimize_pair", "cafeq_pqe", "cafeq_rtn_quantize_minmax", "cafeq_hadamard_rtn", "cafeq_hadamard_workspace_bytes",
     "cafeq_infer_single", "cafeq_infer_workspace_bytes", "cafeq_profile_enable",
-    "cafeq_profile_read", "cafeq_rtn_quantize_static",
+    "cafeq_profile_read", "cafeq_rtn_quantize_static", "cafeq_prepared_bytes", "cafeq_prepare_weights",
 )
 
 
@@ -36,7 +36,7 @@ class CafeqError(RuntimeError):
 
 class Mat(ctypes.Structure):
     _fields_ = [("data", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
-                ("ld", ctypes.c_int64), ("dtype", ctypes.c_int32)]
+                ("ld", ctypes.c_int64), ("dtype", ctypes.c_int32), ("prepared", ctypes.c_void_p)]
 
 
 class Xform(ctypes.Structure):
@@ -71,6 +71,9 @@ def _load():
                                           ctypes.POINTER(Xform), ctypes.POINTER(QuantCfg)]
     lib.cafeq_block_inverse.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.cafeq_rtn_quantize.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(QuantCfg), vp, vp, vp, vp, vp]
+    lib.cafeq_prepared_bytes.restype = ctypes.c_size_t
+    lib.cafeq_prepared_bytes.argtypes = [ctypes.POINTER(Mat), i32]
+    lib.cafeq_prepare_weights.argtypes = [ctypes.POINTER(Mat), i32, vp, vp]
     lib.cafeq_rtn_quantize_static.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(QuantCfg), vp, vp, vp, vp]
     lib.cafeq_apply_transform.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Xform), i32, i32, vp, vp, vp]
     lib.cafeq_proxy_loss_fwd_bwd.argtypes = [ctypes.POINTER(Mat), ctypes.POINTER(Xform),
@@ -121,8 +124,9 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
 
 
-def mat(t):
-    """Descriptor of a 2-D CUDA tensor (float32 or bfloat16, unit column stride)."""
+def mat(t, prepared=None):
+    """Descriptor of a 2-D CUDA tensor (float32 or bfloat16, unit column stride); `prepared`: the buffer
+    prepare_weights() returned for it, or None."""
     if t.dim() != 2 or t.stride(1) != 1 or not t.is_cuda:
         raise CafeqError("need a 2-D CUDA tensor with unit column stride")
     if t.dtype == torch.float32:
@@ -131,7 +135,7 @@ def mat(t):
         dt = BF16
     else:
         raise CafeqError("dtype must be float32 or bfloat16")
-    return Mat(t.data_ptr(), t.shape[0], t.shape[1], t.stride(0), dt)
+    return Mat(t.data_ptr(), t.shape[0], t.shape[1], t.stride(0), dt, prepared.data_ptr() if prepared is not None else 0)
 
 
 def xform(T, Tinv, rep=1):
@@ -179,6 +183,17 @@ def rtn_quantize(W, bits, group, axis=AXIS_COL, want_err=False):
     return codes, scales, err
 
 
+def prepare_weights(W, axis=AXIS_COL):
+    """The prepared copy of W for transforms along `axis` (a uint8 tensor; see cafeq_prepare_weights)."""
+    m = mat(W)
+    nbytes = int(lib.cafeq_prepared_bytes(ctypes.byref(m), axis))
+    if nbytes == 0:
+        raise CafeqError("weights cannot be prepared for this axis (its length must be a multiple of 128)")
+    buf = torch.empty(nbytes, dtype=torch.uint8, device=W.device)
+    _check(lib.cafeq_prepare_weights(ctypes.byref(m), axis, _ptr(buf), _stream()))
+    return buf
+
+
 def rtn_quantize_static(W, codes, scales, err, bits, group, axis=AXIS_COL):
     """The quantizer with built-in scratch: the caller passes every output buffer; nothing is allocated."""
     m = mat(W)
@@ -211,9 +226,10 @@ def apply_transform(W, T, Tinv=None, axis=AXIS_COL, side=SIDE_T, rep=1):
     return Z
 
 
-def proxy_loss_fwd_bwd(W, T, Tinv, bits, group, axis=AXIS_COL, rep=1, want_grad=True, want_codes=False):
+def proxy_loss_fwd_bwd(W, T, Tinv, bits, group, axis=AXIS_COL, rep=1, want_grad=True, want_codes=False,
+                       prepared=None):
     """Returns (losses[4], gradT or None, codes or None, scales or None)."""
-    m = mat(W)
+    m = mat(W, prepared)
     x = xform(T, Tinv, rep)
     cfg = QuantCfg(bits, group, axis, 0)
     dev = W.device
@@ -231,9 +247,10 @@ def proxy_loss_fwd_bwd(W, T, Tinv, bits, group, axis=AXIS_COL, rep=1, want_grad=
     return losses, grad, codes, scales
 
 
-def dual_proxy_loss_fwd_bwd(A, B, T, Tinv, bits, group, rep=1, lse_t=5.0, want_grad=True, want_codes=False):
+def dual_proxy_loss_fwd_bwd(A, B, T, Tinv, bits, group, rep=1, lse_t=5.0, want_grad=True, want_codes=False,
+                            prepared=(None, None)):
     """Returns (losses[6], gradT or None, (codesU, scalesU, codesV, scalesV) or None)."""
-    ma, mb = mat(A), mat(B)
+    ma, mb = mat(A, prepared[0]), mat(B, prepared[1])
     x = xform(T, Tinv, rep)
     cfg = QuantCfg(bits, group, 0, 0)
     dev = A.device
@@ -324,9 +341,9 @@ def optimize_single(W, T, bits, group, axis=AXIS_COL, rep=1, lr=1.0, steps=10, l
 
 
 def optimize_pair(A, B, T, bits, group, rep=1, lse_t=5.0, lr=1e-2, steps=10, lambda_orth=0.0, beta1=0.1,
-                  beta2=0.999, eps=1e-8):
+                  beta2=0.999, eps=1e-8, prepared=(None, None)):
     """Adam on the LogSumExp surrogate, T updated in place.  Returns (Tinv, history[steps][8], status)."""
-    ma, mb = mat(A), mat(B)
+    ma, mb = mat(A, prepared[0]), mat(B, prepared[1])
     nb, k, _ = T.shape
     Tinv = torch.empty_like(T)
     x = Xform(_ptr(T), _ptr(Tinv), k, nb, rep)

@@ -39,10 +39,11 @@ __global__ __launch_bounds__(256) void rho_kernel(const float* __restrict__ P, i
 // with the 32 inputs of a row arranged as four 16-byte chunks (MFMA step c2 = (in % 32) / 16, lane
 // half h -> chunk 2*c2 + h, holding inputs 16*c2 + 8u + 4h + e at position 4u + e), the chunk stored
 // at chunk ^ ((out >> 2) & 3) (LDS bank swizzle).
-struct SplitJob { const float* src; uint16_t* dst; int trans, nplanes; float* fscale; };   // fscale: see below
+struct SplitJob { const float* src; uint16_t* dst; int trans, nplanes; float* fscale; int natural, texp; };   // fscale, texp: see below
 struct SplitJobs { SplitJob job[4]; int njobs, K; float* hdr; int64_t nhdr; };   // hdr: partial headers to reset (may be null)
 // A job with fscale != null writes TWO float16 planes instead: the block is first scaled by the power of
-// two that puts its largest magnitude into [2^14, 2^15) (so that the low parts stay normal numbers), then
+// two that puts its largest magnitude into [2^texp, 2^(texp+1)) (14: the low parts stay normal numbers; 4: sums of
+// 128 products with operands below 2^4 stay below 2^16 -- the matrix cores take denormal float16 inputs exactly), then
 // x = hi + lo with both parts rounded to nearest; fscale[b] receives the factor that undoes the scale.
 // grid: (nb, njobs * K / 32).
 __global__ __launch_bounds__(256) void split_planes_kernel(const SplitJobs js) {
@@ -75,8 +76,8 @@ __global__ __launch_bounds__(256) void split_planes_kernel(const SplitJobs js) {
     m = fmaxf(fmaxf(wmx[0], wmx[1]), fmaxf(wmx[2], wmx[3]));
     int ex = int(__float_as_uint(m) >> 23);
     ex = ex < 32 ? 32 : (ex > 254 ? 254 : ex);
-    hsc = __uint_as_float(uint32_t(268 - ex) << 23);                       // 2^(14 - (ex - 127))
-    if (stage == 0 && threadIdx.x == 0) jb.fscale[blockIdx.x] = __uint_as_float(uint32_t(ex - 14) << 23);
+    hsc = __uint_as_float(uint32_t(254 + jb.texp - ex) << 23);             // 2^(texp - (ex - 127))
+    if (stage == 0 && threadIdx.x == 0) jb.fscale[blockIdx.x] = __uint_as_float(uint32_t(ex - jb.texp) << 23);
   }
   // a thread takes four inputs that are adjacent in the plane (e = 0..3 of one (row, step, half, u)):
   // one 128-bit load (or four coalesced loads of a transposed source) and one 64-bit LDS store per plane
@@ -92,7 +93,9 @@ __global__ __launch_bounds__(256) void split_planes_kernel(const SplitJobs js) {
       const float4 v = *reinterpret_cast<const float4*>(sb + size_t(out) * K + 32 * stage + 4 * wq);
       x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
     }
-    const int c2 = wq >> 2, u = (wq >> 1) & 1, hh = wq & 1;
+    // quad wq holds inputs 4 wq .. 4 wq + 3 of the stage = 16 c2 + 8 u + 4 hh + e; with the natural order the
+    // lane half takes eight consecutive inputs, i.e. the two middle bits swap their roles
+    const int c2 = wq >> 2, u = jb.natural ? (wq & 1) : (wq >> 1) & 1, hh = jb.natural ? (wq >> 1) & 1 : (wq & 1);
     const int chunk = (2 * c2 + hh) ^ ((out >> 2) & 3);
     const int at = out * 32 + chunk * 8 + 4 * u;
     if (jb.fscale) {
@@ -514,7 +517,7 @@ int launch_split_planes_multi(const SplitRequest* req, int n, int K, int nb, hip
   for (int i = 0; i < n && i < 4; ++i) {
     js.job[i].src = req[i].src; js.job[i].dst = req[i].dst;
     js.job[i].trans = req[i].trans; js.job[i].nplanes = req[i].fscale ? 2 : req[i].nplanes;
-    js.job[i].fscale = req[i].fscale;
+    js.job[i].fscale = req[i].fscale; js.job[i].natural = req[i].natural; js.job[i].texp = req[i].texp;
   }
   hipLaunchKernelGGL(split_planes_kernel, dim3(nb, n * (K / 32)), dim3(256), 0, st, js);
   CAFEQ_CHECK_LAUNCH();

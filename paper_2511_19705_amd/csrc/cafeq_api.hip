@@ -124,15 +124,31 @@ bool core_forward_f16(int K, int G, int bits) { return K == 128 && G <= 128 && b
 // The gradient runs as a second pass over the weights, from the loss pass's arg-max records, where the fused
 // kernel has no gradient (blocks of 256, groups of 256 with blocks of 64 or more), where the two passes are
 // faster (blocks of 128), and for groups that span several segments.
-struct PassPlans { CorePlan first, gpass; GroupPlan gp; bool two, fused; };
-int plan_passes(int K, const GroupPlan& gp, int64_t nlines, int64_t naxis, bool grad, PassPlans* pp) {
+struct PassPlans { CorePlan first, gpass; GroupPlan gp; bool two, fused, v2; };
+// The loss pass over prepared weights (loss_v2.hip): one workgroup of eight waves per compute unit,
+// macro-tiles of 256 lines.
+bool v2_eligible(const cafeq_mat* W, int K, const GroupPlan& gp, int bits) {
+  return W->prepared != nullptr && K == 128 && gp.Gk <= 128 && gp.gspan == 1 && bits <= 4;
+}
+void make_v2_plan(CorePlan* pl) {
+  pl->mt_per_seg = (pl->nlines + 255) / 256;
+  pl->n_mt = pl->mt_per_seg * pl->nseg;
+  int64_t nwg = std::min<int64_t>(pl->n_mt, int64_t(device_cu_count()));
+  if (nwg > 8) nwg -= nwg % 8;
+  pl->nwg = int(nwg);
+  pl->nslot = pl->nwg + pl->nseg;
+}
+int plan_passes(int K, const GroupPlan& gp, int64_t nlines, int64_t naxis, bool grad, PassPlans* pp,
+                bool v2 = false) {
   pp->gp = gp;
+  pp->v2 = v2;
   const size_t fl = core_lds_bytes(K, gp.Gk, true);
   const bool fused_ok = fl != 0 && fl <= 160 * 1024 && gp.gspan == 1 && !(K == 128 && gp.Gk <= 128);
   pp->two = grad && !fused_ok;
   pp->fused = grad && fused_ok;
   int rc = make_plan(K, gp.Gk, nlines, naxis, &pp->first, pp->fused);
   if (rc) return rc;
+  if (v2) make_v2_plan(&pp->first);
   if (pp->two) return make_grad_plan(K, nlines, naxis, &pp->gpass);
   pp->gpass = pp->first;
   return CAFEQ_OK;
@@ -140,7 +156,7 @@ int plan_passes(int K, const GroupPlan& gp, int64_t nlines, int64_t naxis, bool 
 
 // scratch of one matrix's passes
 struct MemberWs {
-  float *rG, *rGreal, *slot_grad, *fs;
+  float *rG, *rGreal, *slot_grad, *fs, *fsi;
   uint16_t *pfwd, *pinv;
   float2 *rec, *grec;
 };
@@ -148,6 +164,7 @@ void carve_member(Carver& c, const PassPlans& pp, int nb, bool grad, bool want_r
   const CorePlan& pl = pp.first;
   const bool big = pp.gp.gspan > 1;
   w->fs = c.take<float>(nb);
+  w->fsi = c.take<float>(nb);
   w->pfwd = c.take<uint16_t>(size_t(nb) * kFwdPlanes * pl.K * pl.K);
   w->pinv = c.take<uint16_t>(size_t(nb) * kInvPlanes * pl.K * pl.K);
   w->rG = c.take<float>(want_rG ? size_t(pl.naxis / pl.G) : 0);
@@ -278,6 +295,7 @@ void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep)
   p->rec = nullptr; p->hdr_ref = nullptr; p->nslot_ref = 0; p->member_ref = nullptr;
   p->fscale = nullptr;
   p->longg = 0; p->gspan = 1; p->grec = nullptr; p->grp = 0;
+  p->prep_planes = nullptr; p->prep_lscale = nullptr; p->prep_wsq = nullptr; p->fscale_inv = nullptr;
   p->grid = make_grid(4);
 }
 
@@ -287,8 +305,20 @@ void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep)
 // takes each group's absmax from the combined records (both sweeps run the same kernel variant, so they see
 // bit-identical transformed weights).
 int run_core(int K, int axis, const GroupPlan& gp, CoreParams p, float2* rec, float2* grec, bool want_rec,
-             hipStream_t st) {
+             hipStream_t st, const cafeq_mat* prepared_of = nullptr) {
   int rc;
+  if (prepared_of) {
+    // loss pass over the prepared copy of the weights
+    const bool col = axis == CAFEQ_AXIS_COL;
+    const PreparedLayout l = prepared_layout(col ? prepared_of->rows : prepared_of->cols,
+                                             col ? prepared_of->cols : prepared_of->rows);
+    const unsigned char* base = static_cast<const unsigned char*>(prepared_of->prepared);
+    p.prep_wsq = reinterpret_cast<const float*>(base);
+    p.prep_lscale = reinterpret_cast<const float*>(base + l.off_lscale);
+    p.prep_planes = base + l.off_planes;
+    p.rec = want_rec ? rec : nullptr;
+    return launch_loss_v2(gp.Gk, axis, p, st);
+  }
   if (gp.gspan > 1) {
     CoreParams s1 = p;
     s1.do_inverse = 0; s1.do_grad = 0; s1.codes = nullptr; s1.scales = nullptr; s1.Zout = nullptr;
@@ -573,6 +603,23 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
   }
 }
 
+size_t cafeq_prepared_bytes(const cafeq_mat* W, int axis) {
+  if (!W || W->rows <= 0 || W->cols <= 0 || (axis != CAFEQ_AXIS_COL && axis != CAFEQ_AXIS_ROW)) return 0;
+  const bool col = axis == CAFEQ_AXIS_COL;
+  const int64_t nlines = col ? W->rows : W->cols, naxis = col ? W->cols : W->rows;
+  if (naxis % 128 != 0) return 0;
+  return prepared_layout(nlines, naxis).bytes;
+}
+
+int cafeq_prepare_weights(const cafeq_mat* W, int axis, void* prepared, void* stream) {
+  int rc = check_mat(W);
+  if (rc) return rc;
+  if (axis != CAFEQ_AXIS_COL && axis != CAFEQ_AXIS_ROW) return CAFEQ_ERR_INVALID_ARG;
+  if (!prepared) return CAFEQ_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(prepared) & 255u) != 0) return CAFEQ_ERR_BAD_ALIGN;
+  return launch_prepare(W, axis, prepared, static_cast<hipStream_t>(stream));
+}
+
 int cafeq_rtn_quantize(const cafeq_mat* W, const cafeq_quant_cfg* cfg, int8_t* codes, float* scales,
                        float* err_sq, void* ws, void* stream) {
   int rc = check_mat(W);
@@ -679,8 +726,9 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   rc = resolve_group(cfg, naxis, K, &gp);
   if (rc) return rc;
   const bool grad = gradT != nullptr;
+  const bool v2 = v2_eligible(W, K, gp, cfg->bits);
   PassPlans pp;
-  rc = plan_passes(K, gp, nlines, naxis, grad, &pp);
+  rc = plan_passes(K, gp, nlines, naxis, grad, &pp, v2);
   if (rc) return rc;
   const CorePlan& pl = pp.first;
   {
@@ -702,14 +750,15 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   fill_common(&p, W, pl, x->rep);
   // forward operand [out][in]: T^T (COL) or T (ROW); inverse operand: Tinv^T or Tinv
   {
-    const SplitRequest req[2] = {{x->T, w.m.pfwd, col ? 1 : 0, kFwdPlanes, f16 ? w.m.fs : nullptr},
-                                 {x->Tinv, w.m.pinv, col ? 1 : 0, kInvPlanes}};
+    // (prepared weights: float16 planes for both operands, scaled so that the rounding error fits float16)
+    const SplitRequest req[2] = {{x->T, w.m.pfwd, col ? 1 : 0, kFwdPlanes, f16 ? w.m.fs : nullptr, v2 ? 1 : 0, v2 ? 4 : 14},
+                                 {x->Tinv, w.m.pinv, col ? 1 : 0, kInvPlanes, v2 ? w.m.fsi : nullptr, 0, 4}};
     if ((rc = launch_split_planes_multi(req, 2, K, nb, st, w.slot_hdr, pl.nslot))) return rc;
   }
-  p.Afwd = w.m.pfwd; p.Ainv = w.m.pinv; p.fscale = f16 ? w.m.fs : nullptr;
+  p.Afwd = w.m.pfwd; p.Ainv = w.m.pinv; p.fscale = f16 ? w.m.fs : nullptr; p.fscale_inv = v2 ? w.m.fsi : nullptr;
   p.grid = grid; p.do_inverse = 1; p.do_grad = pp.fused ? 1 : 0; p.loss_kind = kLossSur; p.beta = beta;
   p.rG = w.m.rG; p.codes = codes; p.scales = scales; p.slot_grad = w.m.slot_grad; p.slot_hdr = w.slot_hdr;
-  if ((rc = run_core(K, cfg->axis, gp, p, w.m.rec, w.m.grec, pp.two, st))) return rc;
+  if ((rc = run_core(K, cfg->axis, gp, p, w.m.rec, w.m.grec, pp.two, st, v2 ? W : nullptr))) return rc;
   if ((rc = launch_reduce_losses(kLossSur, w.slot_hdr, int(pl.nslot), nullptr, 0, beta, 0.f, 0, losses,
                                  w.lse_ms, st)))
     return rc;
@@ -749,9 +798,10 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   if ((rc = resolve_group(cfg, A->cols, K, &ga))) return rc;
   if ((rc = resolve_group(cfg, B->rows, K, &gb))) return rc;
   const bool grad = gradT != nullptr;
+  const bool v2A = v2_eligible(A, K, ga, cfg->bits), v2B = v2_eligible(B, K, gb, cfg->bits);
   PassPlans qa, qb;
-  if ((rc = plan_passes(K, ga, A->rows, A->cols, grad, &qa))) return rc;
-  if ((rc = plan_passes(K, gb, B->cols, B->rows, grad, &qb))) return rc;
+  if ((rc = plan_passes(K, ga, A->rows, A->cols, grad, &qa, v2A))) return rc;
+  if ((rc = plan_passes(K, gb, B->cols, B->rows, grad, &qb, v2B))) return rc;
   const CorePlan &pa = qa.first, &pb = qb.first;
   {
     const size_t la = core_lds_bytes(K, ga.Gk, qa.fused), lb = core_lds_bytes(K, gb.Gk, qb.fused);
@@ -764,8 +814,10 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   const bool f16A = core_forward_f16(K, ga.Gk, cfg->bits), f16B = core_forward_f16(K, gb.Gk, cfg->bits);
 
   {
-    const SplitRequest req[4] = {{x->T, w.a.pfwd, 1, kFwdPlanes, f16A ? w.a.fs : nullptr}, {x->Tinv, w.a.pinv, 1, kInvPlanes},
-                                 {x->Tinv, w.b.pfwd, 0, kFwdPlanes, f16B ? w.b.fs : nullptr}, {x->T, w.b.pinv, 0, kInvPlanes}};
+    const SplitRequest req[4] = {{x->T, w.a.pfwd, 1, kFwdPlanes, f16A ? w.a.fs : nullptr, v2A ? 1 : 0, v2A ? 4 : 14},
+                                 {x->Tinv, w.a.pinv, 1, kInvPlanes, v2A ? w.a.fsi : nullptr, 0, 4},
+                                 {x->Tinv, w.b.pfwd, 0, kFwdPlanes, f16B ? w.b.fs : nullptr, v2B ? 1 : 0, v2B ? 4 : 14},
+                                 {x->T, w.b.pinv, 0, kInvPlanes, v2B ? w.b.fsi : nullptr, 0, 4}};
     if ((rc = launch_split_planes_multi(req, 4, K, nb, st, w.hdrA, pa.nslot + pb.nslot))) return rc;
   }
   // Each member: the loss pass, then (two-pass gradient) straight away the gradient pass over
@@ -777,8 +829,8 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   a.Afwd = w.a.pfwd; a.Ainv = w.a.pinv;
   a.grid = grid; a.do_inverse = 1; a.do_grad = qa.fused ? 1 : 0; a.loss_kind = kLossLse; a.lse_t = lse_t;
   a.codes = codesU; a.scales = scalesU; a.slot_grad = w.a.slot_grad; a.slot_hdr = w.hdrA;
-  a.fscale = f16A ? w.a.fs : nullptr;
-  if ((rc = run_core(K, CAFEQ_AXIS_COL, ga, a, w.a.rec, w.a.grec, qa.two, st))) return rc;
+  a.fscale = f16A ? w.a.fs : nullptr; a.fscale_inv = v2A ? w.a.fsi : nullptr;
+  if ((rc = run_core(K, CAFEQ_AXIS_COL, ga, a, w.a.rec, w.a.grec, qa.two, st, v2A ? A : nullptr))) return rc;
   ag = a;
   if (qa.two && (rc = run_grad_pass(K, CAFEQ_AXIS_COL, A, 1, qa, w.a, kLossLse, 0.f, lse_t, w.hdrA, int(pa.nslot),
                                     w.member_ref, &ag, st)))
@@ -789,8 +841,8 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   b.Afwd = w.b.pfwd; b.Ainv = w.b.pinv;
   b.grid = grid; b.do_inverse = 1; b.do_grad = qb.fused ? 1 : 0; b.loss_kind = kLossLse; b.lse_t = lse_t;
   b.codes = codesV; b.scales = scalesV; b.slot_grad = w.b.slot_grad; b.slot_hdr = w.hdrB;
-  b.fscale = f16B ? w.b.fs : nullptr;
-  if ((rc = run_core(K, CAFEQ_AXIS_ROW, gb, b, w.b.rec, w.b.grec, qb.two, st))) return rc;
+  b.fscale = f16B ? w.b.fs : nullptr; b.fscale_inv = v2B ? w.b.fsi : nullptr;
+  if ((rc = run_core(K, CAFEQ_AXIS_ROW, gb, b, w.b.rec, w.b.grec, qb.two, st, v2B ? B : nullptr))) return rc;
   bg = b;
   if (qb.two && (rc = run_grad_pass(K, CAFEQ_AXIS_ROW, B, x->rep, qb, w.b, kLossLse, 0.f, lse_t, w.hdrB, int(pb.nslot),
                                     w.member_ref + 1, &bg, st)))

@@ -49,9 +49,19 @@ size_t core_lds_bytes_k128(int G, bool do_grad);
 size_t core_lds_bytes_k256(int G, bool do_grad);
 int device_cu_count();
 
+// loss_v2.hip: loss pass over prepared weights (128 x 128 blocks, groups up to 128)
+struct PreparedLayout { int64_t nlp, nseg, ntiles; size_t off_lscale, off_planes, off_partial, bytes; };
+PreparedLayout prepared_layout(int64_t nlines, int64_t naxis);
+int launch_prepare(const cafeq_mat* W, int axis, void* prepared, hipStream_t st);
+int launch_loss_v2(int G, int axis, const CoreParams& p, hipStream_t st);
+
 // aux_kernels.hip
-// fscale != null: two float16 planes of the block scaled by a power of two; fscale[block] = the factor back
-struct SplitRequest { const float* src; uint16_t* dst; int trans, nplanes; float* fscale = nullptr; };
+// fscale != null: two float16 planes of the block scaled by a power of two; fscale[block] = the factor back.
+// natural: a lane's eight inputs of an MFMA step are consecutive (16c + 8h + 0..7: operands read as prepared
+// 16-byte vectors) instead of two runs of four (16c + 8u + 4h + e: operands read as float4 from float32 lines
+// and the accumulator registers of the inverse transform).
+// texp: a float16 job scales the block's largest magnitude into [2^texp, 2^(texp+1)).
+struct SplitRequest { const float* src; uint16_t* dst; int trans, nplanes; float* fscale = nullptr; int natural = 0; int texp = 14; };
 int launch_split_planes(const float* src, int K, int nb, int trans, int nplanes, uint16_t* dst, hipStream_t st);
 // up to four splits in one launch; hdr (may be null): nslot partial headers reset by the same launch
 int launch_split_planes_multi(const SplitRequest* req, int n, int K, int nb, hipStream_t st, float* hdr = nullptr,

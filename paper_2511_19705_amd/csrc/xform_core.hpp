@@ -131,6 +131,11 @@ struct CoreParams {
   const float2* grec;       // loss sweep with gspan > 1 (else null)
   // gradient pass: group length along the axis, records indexed [axis group][line], index inside the group
   int grp;
+  // loss pass over prepared weights (loss_v2.hip): tiles of two float16 parts, per-line factors, ||W||^2
+  const unsigned char* prep_planes;
+  const float* prep_lscale;
+  const float* prep_wsq;
+  const float* fscale_inv;  // per-block factor of the float16 inverse operand planes
 };
 
 __device__ __forceinline__ int64_t chunk_begin(int64_t w, int64_t n_mt, int64_t nwg) {

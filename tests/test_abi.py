@@ -54,7 +54,7 @@ def test_argument_errors_of_every_entry_point_are_reported_before_any_launch():
 
     class Mat(ctypes.Structure):
         _fields_ = [("data", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
-                    ("ld", ctypes.c_int64), ("dtype", ctypes.c_int32)]
+                    ("ld", ctypes.c_int64), ("dtype", ctypes.c_int32), ("prepared", ctypes.c_void_p)]
 
     class Cfg(ctypes.Structure):
         _fields_ = [("bits", ctypes.c_int32), ("group", ctypes.c_int32), ("axis", ctypes.c_int32),
