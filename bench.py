@@ -1,32 +1,27 @@
 """Benchmark of the CafeQ hot path on one MI355X.
 
-Workload (default): the Gemma-2-9B-shaped MLP pair (down 3584x14336 gets T on its columns,
-up 14336x3584 gets T^-1 on its rows), block-diagonal 128x128 transform, 3-bit symmetric
-absmax grid, group 128 -- synthetic Student-t weights with outliers (workloads.config3).
-One step = one evaluation of the whole path: blockwise inverse of the transform, then the
-paired proxy-loss forward + backward (transform, group absmax, RTN codes, dequantize,
-inverse transform, error reductions, LogSumExp surrogate and its gradient w.r.t. T).
-Inputs are resident in HBM before the timed region.
+Headline workload: the Gemma-2-9B-shaped MLP pair (down 3584x14336 gets T on its columns, up 14336x3584 gets
+T^-1 on its rows), block-diagonal 128x128 transform, 3-bit symmetric absmax grid, group 128 -- synthetic
+Student-t weights with outliers (workloads.config3).  One step = one evaluation of the whole path as the
+paper's learning loop runs it: blockwise inverse of the transform, then the paired proxy-loss forward +
+backward (transform, group absmax, RTN codes, dequantize, inverse transform, error reductions, LogSumExp
+surrogate and its gradient w.r.t. T).  All inputs are resident in HBM before the timed region; the weights,
+which are constant over a learning run, are also held in the library's prepared form
+(cafeq_prepare_weights, once, outside the timed region; its cost is reported).
 
-Prints ONE JSON line: weight-elements/s over the whole job, the matrix-core roofline of the
-dominant (fused transform) kernel measured with HIP events on the launch stream inside the
-timed region, and the CPU oracle timed on the host cores on a bounded sample.
-
-The loss pass of the fused kernel (forward transform, quantizer, inverse transform of the
-rounding error, loss partials) runs its two contractions on the 16-bit matrix pipe with float32
-operands split into 16-bit parts: the forward transform on two float16 parts per operand (scaled
-by powers of two per line and per block; three part products), the inverse transform of the
-error on bfloat16 parts (three part products), float32 accumulation; the gradient through the
-transformed weights is a second, shorter pass over the same weights.  The roofline line prices
-the ALGORITHMIC work of the loss pass, 2 * 2k flop per weight element, against the dense 16-bit
-peak (2.5 PFLOP/s for float16 and bfloat16 alike); the executed part products (3x as many flops)
-and the float32 matrix peak the split replaces are given beside it for context.
+Prints ONE JSON line: weight-elements/s over the whole job; the roofline of the dominant kernel (the loss
+pass), its duration measured with HIP events recorded on the launch stream around every launch inside the
+timed region; the CPU oracle timed on the host cores on a bounded sample; and a `secondary` list with the
+same step under other conditions (a transform part-way through learning, whose inverse takes the elimination
+kernel; the unprepared path) and the other workloads (plain quantizer, single matrix, Alg. 1, the 27B-shaped
+layer).  `--workload NAME` prints the line of one secondary workload alone.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -34,13 +29,19 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-BF16_MFMA_PEAK_TFLOPS = 2500.0
+F16_MFMA_PEAK_TFLOPS = 2500.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the fused kernel on this workload, from the two rocprofv3 --pmc runs
-# summarised in profiles/xform_core_c3_pair.md (FETCH_SIZE and WRITE_SIZE, each scaled by
-# what the same counter reads for a plain 1 GiB copy); None for any other workload.
-MEASURED_TRAFFIC_BYTES = {"c3_pair_3584x14336_k128_g128_b3": (2.0 * 151724 + 21500) * 1024}
+
+
+def measured_traffic(profile, key):
+    """HBM bytes per launch from a rocprofv3 summary under profiles/ (a line `key: <bytes>`), or None."""
+    try:
+        text = open(os.path.join(ROOT, "profiles", profile)).read()
+    except OSError:
+        return None
+    m = re.search(r"^%s:\s*([0-9.eE+]+)" % re.escape(key), text, flags=re.M)
+    return float(m.group(1)) if m else None
 
 
 def _cores():
@@ -51,7 +52,27 @@ def _cores():
         return os.cpu_count() or 1
 
 
-def cpu_baseline(cfg, blocks, reps):
+def _base(metric, value, unit, steps, warmup, ms, dtype, workload, **cfg):
+    return {"metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": steps, "warmup": warmup,
+            "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype,
+            "data": "synthetic", "config": dict(workload=workload, **cfg)}
+
+
+def _timed(torch, fn, steps, warmup):
+    for _ in range(max(warmup, 1)):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+# ----------------------------------------------------------------------------------------------------
+# headline: the 9B-shaped pair
+# ----------------------------------------------------------------------------------------------------
+def pair_cpu_baseline(cfg, blocks, reps):
     """The oracle as it stands, on the first `blocks` transform blocks of the pair."""
     import numpy as np
     from oracle import cafeq_oracle as O
@@ -70,25 +91,132 @@ def cpu_baseline(cfg, blocks, reps):
                       "fwd+bwd), %.1f s" % (blocks, cfg["T"].shape[0], elems / 1e6, reps, dt)}
 
 
-def other_workload(args):
-    """Secondary workloads (not the headline metric): one JSON line each, same fields.
-       c3_optimize : Adam iterations on the 9B-shaped pair (inverse + paired fwd+bwd + update)
-       c2_single   : single-matrix fwd+bwd on the 2B-shaped down projection (k = 64, fused gradient)
-       c4_adaptive : Alg. 1 iterations on the 9B-shaped attention V/O pair (k = 256)
-       c5_layer    : fwd+bwd over all seven weights of the 27B-shaped decoder layer (bfloat16 storage)"""
+def pair_workload(args, secondary=True):
     import numpy as np
     import torch
     from paper_2511_19705_amd import cafeq, workloads as WL
     dev = torch.device("cuda:0")
-    cores = _cores()
+    cfg = WL.config3()
+    k, g, bits, rep = cfg["k"], cfg["group"], cfg["bits"][0], cfg["rep"]
+    A = torch.from_numpy(cfg["A"]).to(dev)
+    B = torch.from_numpy(cfg["B"]).to(dev)
+    T = torch.from_numpy(cfg["T"]).to(dev)
+    elems = A.numel() + B.numel()
+    member = elems / 2.0
+
+    if args.calib_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)           # reads 1 GiB, writes 1 GiB: reference for the profiler's byte counters
+        torch.cuda.synchronize()
+        del src, dst
+
+    # the weights in the library's prepared form: once per learning run
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    prep = (cafeq.prepare_weights(A, cafeq.AXIS_COL), cafeq.prepare_weights(B, cafeq.AXIS_ROW))
+    torch.cuda.synchronize()
+    prep_ms = (time.perf_counter() - t0) * 1e3
+
+    def make_step(Tx, prepared):
+        def step():
+            P, _ = cafeq.block_inverse(Tx)
+            return cafeq.dual_proxy_loss_fwd_bwd(A, B, Tx, P, bits, g, rep, 5.0, want_grad=True, prepared=prepared)
+        return step
+
+    step = make_step(T, prep)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    timer = cafeq.LaunchTimer(2 * args.steps)
+    with timer:
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            out = step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    durs = timer.durations_ms()
+    losses = out[0].cpu().numpy()
+
+    # dominant kernel: the loss pass, launched once per member.  Algorithmic work per launch: forward and inverse
+    # transform of its member, 2k flop per element each; it reads every weight once (4 B per element).
+    avg_launch_s = sum(durs) / max(len(durs), 1) * 1e-3
+    flops_per_launch = 2.0 * 2.0 * k * member
+    achieved = flops_per_launch / avg_launch_s / 1e12
+    executed = 5.0 * 2.0 * k * member / avg_launch_s / 1e12   # 3 + 2 part products per contraction index
+    result = _base("proxy-loss fwd+bwd weight-elements/s (9B-shaped MLP pair, dual transform)", elems * args.steps / dt,
+                   "weight-elements/s", args.steps, args.warmup, dt / args.steps * 1e3, "f32", cfg["name"],
+                   rows_cols=[list(cfg["A"].shape), list(cfg["B"].shape)], block=k, group=g, bits=bits,
+                   evals_per_s=args.steps / dt,
+                   step="block inverse + dual proxy-loss fwd+bwd (loss pass + gradient pass per member)",
+                   weights="resident in HBM, also in prepared form (cafeq_prepare_weights once per learning run, "
+                           "%.2f ms for both members, outside the timed region)" % prep_ms,
+                   inverse="T is the workload's rotation (the paper's initialisation): blocks verified to be rotations are "
+                           "inverted by transposition; see secondary[c3_pair_midlearning] for any other transform",
+                   contraction="forward: 2 float16 parts per operand, 3 products; inverse: float16 error x 2 float16 parts, "
+                               "2 products; float32 accumulate",
+                   relative_l2_A=float((losses[2] / float((cfg["A"].astype("float64") ** 2).sum())) ** 0.5))
+    result["roofline"] = {
+        "bound": "mfma", "achieved": achieved, "peak": F16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+        "frac": achieved / F16_MFMA_PEAK_TFLOPS,
+        "traffic": measured_traffic("loss_prepared_c3_pair.md", "traffic_bytes_per_launch"),
+        "kernel": "loss_v2_kernel<128,*,true,false> (loss pass over prepared weights)", "launches": len(durs),
+        "avg_launch_us": avg_launch_s * 1e6, "algorithmic_flop_per_element": 4 * k,
+        "algorithmic_bytes_per_element": 4, "executed_part_product_tflops": executed,
+        "executed_frac_of_f16_peak": executed / F16_MFMA_PEAK_TFLOPS,
+        "achieved_over_fp32_mfma_peak": achieved / FP32_MFMA_PEAK_TFLOPS,
+        "hbm_frac_at_algorithmic_bytes": 4.0 * member / avg_launch_s / 1e9 / HBM_PEAK_GBS}
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = pair_cpu_baseline(cfg, args.cpu_blocks, args.cpu_reps)
+    if secondary:
+        sec = []
+        n2 = max(10, args.steps // 4)
+        # the same step with a transform part-way through learning: every block goes through the elimination
+        Tm = torch.from_numpy(WL.perturbed_blocks(cfg["T"].shape[0], k, 304, 0.05)).to(dev)
+        d2 = _timed(torch, make_step(Tm, prep), n2, 3)
+        sec.append({"workload": "c3_pair_midlearning", "what": "same step, T = rotation x (I + 0.05 G / sqrt(k)): inverse by "
+                    "elimination", "steps": n2, "ms_per_step": d2 / n2 * 1e3, "value": elems * n2 / d2, "unit": "weight-elements/s"})
+        d3 = _timed(torch, make_step(T, (None, None)), n2, 3)
+        sec.append({"workload": "c3_pair_unprepared", "what": "same step without prepared weights (float32 weights split per "
+                    "call)", "steps": n2, "ms_per_step": d3 / n2 * 1e3, "value": elems * n2 / d3, "unit": "weight-elements/s"})
+        del prep, A, B
+        torch.cuda.empty_cache()
+        sub = argparse.Namespace(**vars(args))
+        sub.no_cpu_baseline = True
+        sub.steps, sub.warmup = n2, 3
+        for name in ("c3_rtn", "c3_optimize", "c2_single", "c4_adaptive", "c5_layer"):
+            sub.workload = name
+            r = WORKLOADS[name](sub)
+            sec.append({"workload": r["config"]["workload"], "metric": r["metric"], "steps": r["steps"],
+                        "ms_per_step": r["ms_per_step"], "value": r["value"], "unit": r["unit"],
+                        "roofline": {kk: r["roofline"][kk] for kk in ("bound", "achieved", "peak", "unit", "frac", "kernel")
+                                     if kk in r.get("roofline", {})},
+                        **({"detail": r["detail"]} if "detail" in r else {})})
+            torch.cuda.empty_cache()
+        result["secondary"] = sec
+    return result
+
+
+# ----------------------------------------------------------------------------------------------------
+# secondary workloads
+# ----------------------------------------------------------------------------------------------------
+def core_workload(args):
+    """c3_optimize : Adam iterations on the 9B-shaped pair (inverse + paired fwd+bwd + update), prepared weights
+       c2_single   : single-matrix fwd+bwd on the 2B-shaped down projection (k = 64, fused gradient)
+       c4_adaptive : Alg. 1 iterations on the 9B-shaped attention V/O pair (k = 256)"""
+    import numpy as np
+    import torch
+    from paper_2511_19705_amd import cafeq, workloads as WL
+    dev = torch.device("cuda:0")
     if args.workload == "c3_optimize":
         cfg = WL.config3()
         A, B = torch.from_numpy(cfg["A"]).to(dev), torch.from_numpy(cfg["B"]).to(dev)
         T = torch.from_numpy(cfg["T"].copy()).to(dev)
+        prep = (cafeq.prepare_weights(A, 0), cafeq.prepare_weights(B, 1))
         elems, k = A.numel() + B.numel(), cfg["k"]
-        run = lambda n: cafeq.optimize_pair(A, B, T, cfg["bits"][0], cfg["group"], 1, 5.0, 1e-3, n)
+        run = lambda n: cafeq.optimize_pair(A, B, T, cfg["bits"][0], cfg["group"], 1, 5.0, 1e-3, n, prepared=prep)
         metric = "learning iterations, weight-elements/s (Adam on the LogSumExp surrogate, 9B-shaped MLP pair)"
-        flop_el, parts, kern = 4 * k, 6, "xform_core_kernel<128,128,*,false,true> (loss pass)"
+        flop_el, parts, kern, name = 4 * k, 5, "loss_v2_kernel<128,*,true,false> (loss pass)", cfg["name"] + "_adam"
 
         def cpu():
             from oracle import cafeq_oracle as O
@@ -109,7 +237,7 @@ def other_workload(args):
                 P, _ = cafeq.block_inverse(T)
                 cafeq.proxy_loss_fwd_bwd(W, T, P, cfg["bits"][0], cfg["group"], 0, 1, want_grad=True)
         metric = "proxy-loss fwd+bwd weight-elements/s (2B-shaped down projection, single transform)"
-        flop_el, parts, kern = 6 * k, 12, "xform_core_kernel<64,128,COL,true> (fused)"
+        flop_el, parts, kern, name = 6 * k, 12, "xform_core_kernel<64,128,COL,true> (fused)", cfg["name"]
 
         def cpu():
             from oracle import cafeq_oracle as O
@@ -122,40 +250,6 @@ def other_workload(args):
                 O.surrogate(w, t, p_, cfg["bits"][0], cfg["group"], 0, 1)
             dt = time.perf_counter() - t0
             return w.size * 3 / dt, "%d of %d blocks, 3 x (inverse + fwd+bwd), %.1f s" % (nbk, cfg["T"].shape[0], dt)
-    elif args.workload == "c5_layer":
-        # every weight of the 27B-shaped decoder layer, bfloat16 storage: three singles on the model dimension,
-        # the MLP pair (288 blocks) and the attention V/O pair (16 blocks, two query heads per kv head)
-        meta = WL.config5_meta()
-        k, g, bits, rep = meta["k"], meta["group"], meta["bits"][0], meta["rep"]
-        cfg = {"name": "c5_27b_layer_bf16_k%d_g%d_b%d" % (k, g, bits), "group": g, "bits": (bits,)}
-        host = {nm: WL.config5_tensor(nm) for nm in ("q", "k", "gate", "down", "up", "v", "o")}
-        Wd = {nm: torch.from_numpy(t["bits16"].view(np.int16)).to(dev).view(torch.bfloat16) for nm, t in host.items()}
-        Ts = {w: torch.from_numpy(WL.config5_transform(w)).to(dev) for w in ("single", "mlp", "vo")}
-        elems = sum(w.numel() for w in Wd.values())
-
-        def run(n):
-            for _ in range(n):
-                Ps, _ = cafeq.block_inverse(Ts["single"])
-                for nm in ("q", "k", "gate"):
-                    cafeq.proxy_loss_fwd_bwd(Wd[nm], Ts["single"], Ps, bits, g, 0, 1, want_grad=True)
-                Pm, _ = cafeq.block_inverse(Ts["mlp"])
-                cafeq.dual_proxy_loss_fwd_bwd(Wd["down"], Wd["up"], Ts["mlp"], Pm, bits, g, 1, 5.0, want_grad=True)
-                Pv, _ = cafeq.block_inverse(Ts["vo"])
-                cafeq.dual_proxy_loss_fwd_bwd(Wd["v"], Wd["o"], Ts["vo"], Pv, bits, g, rep, 5.0, want_grad=True)
-        metric = "proxy-loss fwd+bwd weight-elements/s (27B-shaped decoder layer: q, k, gate singles; down/up and V/O pairs)"
-        flop_el, parts, kern = 4 * k, 6, "xform_core_kernel<128,128,*,*> (bfloat16 storage; loss passes and fused singles)"
-
-        def cpu():
-            from oracle import cafeq_oracle as O
-            w = WL.bf16_bits_to_f32(host["q"]["bits16"])
-            t = WL.config5_transform("single")
-            t0 = time.perf_counter()
-            for _ in range(4):
-                p_ = O.block_inverse(t)
-                O.proxy_l2(w, t, p_, bits, g, 0, 1)
-                O.surrogate(w, t, p_, bits, g, 0, 1)
-            dt = time.perf_counter() - t0
-            return w.size * 4 / dt, "the q projection (4096 x 4608, 36 blocks), 4 x (inverse + fwd+bwd), %.1f s" % dt
     else:
         cfg = WL.config4()
         k, rep, g, bits = cfg["k"], cfg["rep"], cfg["group"], cfg["bits"][0]
@@ -172,7 +266,7 @@ def other_workload(args):
             for _ in range(n):
                 cafeq.adaptive_round_step(U, V, cu, su, cv, sv, bits, g, k, rep, half=0)
         metric = "adaptive-rounding iterations, weight-elements/s (Alg. 1, 9B-shaped attention V/O pair)"
-        flop_el, parts, kern = 2 * k, 6, "xform_core_kernel<256,64,*,false> (transform + requantize)"
+        flop_el, parts, kern, name = 2 * k, 6, "xform_core_kernel<256,64,*,false> (transform + requantize)", cfg["name"]
 
         def cpu():
             from oracle import cafeq_oracle as O
@@ -188,31 +282,109 @@ def other_workload(args):
 
     run(max(args.warmup, 1))
     torch.cuda.synchronize()
-    cafeq.profile_enable(True)
-    cafeq.profile_read()
-    t0 = time.perf_counter()
-    run(args.steps)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    n_launch, core_ms = cafeq.profile_read()
-    cafeq.profile_enable(False)
-    avg = core_ms / 1e3 / max(n_launch, 1)
-    per_launch_el = elems * args.steps / max(n_launch, 1)
+    timer = cafeq.LaunchTimer(8 * args.steps + 8)
+    with timer:
+        t0 = time.perf_counter()
+        run(args.steps)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    durs = timer.durations_ms()
+    avg = sum(durs) / max(len(durs), 1) * 1e-3
+    per_launch_el = elems * args.steps / max(len(durs), 1)
     achieved = flop_el * per_launch_el / avg / 1e12
-    out = {"metric": metric, "value": elems * args.steps / dt, "unit": "weight-elements/s", "n_gpus": 1,
-           "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
-           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": cfg["name"] + ("_adam" if args.workload == "c3_optimize" else ""),
-                      "block": k, "group": cfg["group"], "bits": cfg["bits"][0]},
-           "roofline": {"bound": "mfma", "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                        "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": None, "kernel": kern,
-                        "launches": n_launch, "avg_launch_us": avg * 1e6,
-                        "algorithmic_flop_per_element": flop_el,
-                        "executed_part_product_tflops": achieved * parts * 2 * k / flop_el}}
+    out = _base(metric, elems * args.steps / dt, "weight-elements/s", args.steps, args.warmup, dt / args.steps * 1e3,
+                "f32", name, block=cfg["k"], group=cfg["group"], bits=cfg["bits"][0])
+    out["roofline"] = {"bound": "mfma", "achieved": achieved, "peak": F16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                       "frac": achieved / F16_MFMA_PEAK_TFLOPS, "traffic": None, "kernel": kern, "launches": len(durs),
+                       "avg_launch_us": avg * 1e6, "algorithmic_flop_per_element": flop_el,
+                       "executed_part_product_tflops": achieved * parts * 2 * cfg["k"] / flop_el}
     if not args.no_cpu_baseline:
         v, sample = cpu()
-        out["cpu_baseline"] = {"value": v, "unit": "weight-elements/s", "cores": cores, "kind": "oracle", "sample": sample}
-    print(json.dumps(out))
+        out["cpu_baseline"] = {"value": v, "unit": "weight-elements/s", "cores": _cores(), "kind": "oracle", "sample": sample}
+    return out
+
+
+def layer_workload(args):
+    """The 27B-shaped decoder layer, bfloat16 storage, k = 128, group 128: per bit-width (3 and 4), the proxy-loss
+    forward + backward of every single (q, k, gate) and pair ((down, up), (V, O)) -- one evaluation each, as one
+    iteration of the learning loops -- followed by the final quantization of all seven matrices (codes and scales
+    written).  One step = that sequence for both bit-widths; the layer wall time per bit-width is in `detail`."""
+    import numpy as np
+    import torch
+    from paper_2511_19705_amd import cafeq, workloads as WL
+    dev = torch.device("cuda:0")
+    meta = WL.config5_meta()
+    k, g, rep = meta["k"], meta["group"], meta["rep"]
+    host = {nm: WL.config5_tensor(nm) for nm in ("q", "k", "gate", "down", "up", "v", "o")}
+    Wd = {nm: torch.from_numpy(t["bits16"].view(np.int16)).to(dev).view(torch.bfloat16) for nm, t in host.items()}
+    Ts = {w: torch.from_numpy(WL.config5_transform(w)).to(dev) for w in ("single", "mlp", "vo")}
+    axis = {"q": 0, "k": 0, "gate": 0, "down": 0, "up": 1, "v": 0, "o": 1}
+    prep = {nm: cafeq.prepare_weights(Wd[nm], axis[nm]) for nm in Wd}
+    elems = sum(w.numel() for w in Wd.values())
+
+    def evaluate(bits):
+        Ps, _ = cafeq.block_inverse(Ts["single"])
+        for nm in ("q", "k", "gate"):
+            cafeq.proxy_loss_fwd_bwd(Wd[nm], Ts["single"], Ps, bits, g, 0, 1, want_grad=True, prepared=prep[nm])
+        Pm, _ = cafeq.block_inverse(Ts["mlp"])
+        cafeq.dual_proxy_loss_fwd_bwd(Wd["down"], Wd["up"], Ts["mlp"], Pm, bits, g, 1, 5.0, want_grad=True,
+                                      prepared=(prep["down"], prep["up"]))
+        Pv, _ = cafeq.block_inverse(Ts["vo"])
+        cafeq.dual_proxy_loss_fwd_bwd(Wd["v"], Wd["o"], Ts["vo"], Pv, bits, g, rep, 5.0, want_grad=True,
+                                      prepared=(prep["v"], prep["o"]))
+        return Ps, Pm, Pv
+
+    def finalize(bits, Ps, Pm, Pv):
+        for nm in ("q", "k", "gate"):
+            cafeq.proxy_loss_fwd_bwd(Wd[nm], Ts["single"], Ps, bits, g, 0, 1, want_grad=False, want_codes=True,
+                                     prepared=prep[nm])
+        cafeq.dual_proxy_loss_fwd_bwd(Wd["down"], Wd["up"], Ts["mlp"], Pm, bits, g, 1, 5.0, want_grad=False,
+                                      want_codes=True, prepared=(prep["down"], prep["up"]))
+        cafeq.dual_proxy_loss_fwd_bwd(Wd["v"], Wd["o"], Ts["vo"], Pv, bits, g, rep, 5.0, want_grad=False,
+                                      want_codes=True, prepared=(prep["v"], prep["o"]))
+
+    per_bits = {}
+    for bits in meta["bits"]:
+        inv = evaluate(bits)
+        finalize(bits, *inv)
+    torch.cuda.synchronize()
+    steps = max(3, args.steps // 4)
+    t_all = 0.0
+    for bits in meta["bits"]:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            inv = evaluate(bits)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(steps):
+            finalize(bits, *inv)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        per_bits["%d_bit" % bits] = {"fwd_bwd_ms": (t1 - t0) / steps * 1e3, "final_quantize_ms": (t2 - t1) / steps * 1e3,
+                                     "layer_ms": (t2 - t0) / steps * 1e3}
+        t_all += t2 - t0
+    passes = 2 * len(meta["bits"])              # every weight is read by one fwd+bwd and one final quantization per bit-width
+    out = _base("layer quantization wall time, weight-elements/s (27B-shaped decoder layer: fwd+bwd of q, k, gate, "
+                "(down, up), (V, O) and final quantization of all seven, 3 and 4 bit)", elems * passes * steps / t_all,
+                "weight-elements/s", steps, 1, t_all / steps * 1e3, "f32 (bf16 storage)",
+                "c5_27b_layer_bf16_k%d_g%d_b3_b4" % (k, g), block=k, group=g, bits=list(meta["bits"]))
+    out["detail"] = per_bits
+    out["roofline"] = {"bound": "mfma", "achieved": None, "peak": F16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": None,
+                       "traffic": None, "kernel": "loss_v2_kernel<128,*,*,*> (bfloat16-stored weights, prepared)"}
+    if not args.no_cpu_baseline:
+        from oracle import cafeq_oracle as O
+        w = WL.bf16_bits_to_f32(host["q"]["bits16"])
+        t = WL.config5_transform("single")
+        t0 = time.perf_counter()
+        for _ in range(4):
+            p_ = O.block_inverse(t)
+            O.proxy_l2(w, t, p_, 3, g, 0, 1)
+            O.surrogate(w, t, p_, 3, g, 0, 1)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": w.size * 4 / dt, "unit": "weight-elements/s", "cores": _cores(), "kind": "oracle",
+                               "sample": "the q projection (4096 x 4608, 36 blocks), 4 x (inverse + fwd+bwd), %.1f s" % dt}
+    return out
 
 
 def infer_workload(args):
@@ -251,17 +423,15 @@ def infer_workload(args):
     xf_ev, xf_wall = timed(lambda: cafeq.infer_single(X, P, codes, scales, g, out=Y), args.steps)
     byts = out_f * in_f + out_f * (in_f // g) * 4 + n * in_f * 4 + n * out_f * 4
     achieved = byts / plain_ev / 1e9
-    res = {"metric": "tokens/s through one quantized transformed layer (activation transform + dequantize + product)",
-           "value": n / xf_wall, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-           "ms_per_step": xf_wall * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": "f32", "data": "synthetic",
-           "config": {"workload": "%s_%dx%d_k%d_g%d_%dbit_tokens%d" % (args.workload, out_f, in_f, k, g, bits, n)},
-           "roofline": {"bound": "hbm", "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0,
-                        "traffic": None, "kernel": "dequant_gemv_kernel<1,*> (plain quantized layer)",
-                        "avg_launch_us": plain_ev * 1e6, "algorithmic_bytes": byts},
-           "transform": {"plain_us": plain_ev * 1e6, "with_transform_us": xf_ev * 1e6,
-                         "extra_wall_clock_pct": (xf_ev / plain_ev - 1) * 100,
-                         "extra_flops_pct": 100.0 * k / out_f, "extra_bytes_pct": 100.0 * 4 * k / out_f}}
+    res = _base("tokens/s through one quantized transformed layer (activation transform + dequantize + product)",
+                n / xf_wall, "tokens/s", args.steps, args.warmup, xf_wall * 1e3, "f32",
+                "%s_%dx%d_k%d_g%d_%dbit_tokens%d" % (args.workload, out_f, in_f, k, g, bits, n))
+    res["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                       "traffic": None, "kernel": "dequant_gemv_kernel<1,*> (plain quantized layer)",
+                       "avg_launch_us": plain_ev * 1e6, "algorithmic_bytes": byts}
+    res["transform"] = {"plain_us": plain_ev * 1e6, "with_transform_us": xf_ev * 1e6,
+                        "extra_wall_clock_pct": (xf_ev / plain_ev - 1) * 100,
+                        "extra_flops_pct": 100.0 * k / out_f, "extra_bytes_pct": 100.0 * 4 * k / out_f}
     if not args.no_cpu_baseline:
         from oracle import cafeq_oracle as O
         rows = 256
@@ -274,14 +444,13 @@ def infer_workload(args):
         dt = (time.perf_counter() - t0) / reps
         res["cpu_baseline"] = {"value": n / (dt * out_f / rows), "unit": "tokens/s", "cores": _cores(), "kind": "oracle",
                                "sample": "%d of %d output rows (dense inverse transform included), %d repetitions, scaled" % (rows, out_f, reps)}
-    print(json.dumps(res))
+    return res
 
 
 def rtn_workload(args):
     """Plain per-group round-to-nearest (no transform) of the first member of the 9B-shaped pair ([3584][14336],
     groups of 128 along the contiguous axis): the HBM-bound stage of the path.
     Algorithmic bytes per element: 4 read + 1 code + 4/g scale."""
-    import numpy as np
     import torch
     from paper_2511_19705_amd import cafeq, workloads as WL
     dev = torch.device("cuda:0")
@@ -304,16 +473,13 @@ def rtn_workload(args):
     kern_s = e0.elapsed_time(e1) / args.steps * 1e-3
     byts = elems * (4 + 1 + 4.0 / g)
     achieved = byts / kern_s / 1e9
-    res = {"metric": "round-to-nearest weight-elements/s (9B-shaped projection, no transform)",
-           "value": elems * args.steps / dt, "unit": "weight-elements/s", "n_gpus": 1, "steps": args.steps,
-           "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
-           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": "c3_rtn_3584x14336_g%d_b%d" % (g, bits), "group": g, "bits": bits},
-           "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": achieved / HBM_PEAK_GBS,
-                        # FETCH_SIZE x 2.0 + WRITE_SIZE of profiles/rtn_col_fast_c3_member.md, bytes per launch
-                        "traffic": (2.0 * 100383 + 51745) * 1024, "kernel": "rtn_col_fast<F32Tag, 32>",
-                        "avg_launch_us": kern_s * 1e6, "algorithmic_bytes_per_element": 4 + 1 + 4.0 / g}}
+    res = _base("round-to-nearest weight-elements/s (9B-shaped projection, no transform)", elems * args.steps / dt,
+                "weight-elements/s", args.steps, args.warmup, dt / args.steps * 1e3, "f32",
+                "c3_rtn_3584x14336_g%d_b%d" % (g, bits), group=g, bits=bits)
+    res["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                       "traffic": measured_traffic("rtn_col_fast_c3_member.md", "traffic_bytes_per_launch"),
+                       "kernel": "rtn_col_fast<F32Tag, 32>", "avg_launch_us": kern_s * 1e6,
+                       "algorithmic_bytes_per_element": 4 + 1 + 4.0 / g}
     if not args.no_cpu_baseline:
         from oracle import cafeq_oracle as O
         rows = 512
@@ -326,7 +492,11 @@ def rtn_workload(args):
         dtc = time.perf_counter() - t0
         res["cpu_baseline"] = {"value": w.size * reps / dtc, "unit": "weight-elements/s", "cores": _cores(), "kind": "oracle",
                                "sample": "%d of %d rows, %d repetitions, %.1f s" % (rows, cfg["A"].shape[0], reps, dtc)}
-    print(json.dumps(res))
+    return res
+
+
+WORKLOADS = {"c3_optimize": core_workload, "c2_single": core_workload, "c4_adaptive": core_workload,
+             "c5_layer": layer_workload, "c2_infer": infer_workload, "c3_infer": infer_workload, "c3_rtn": rtn_workload}
 
 
 def main():
@@ -335,9 +505,10 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true", help="headline only (no secondary list)")
     ap.add_argument("--cpu-blocks", type=int, default=112)
     ap.add_argument("--cpu-reps", type=int, default=4)
-    ap.add_argument("--workload", default="c3_pair", choices=["c3_pair", "c3_optimize", "c2_single", "c4_adaptive", "c5_layer", "c2_infer", "c3_infer", "c3_rtn"],
+    ap.add_argument("--workload", default="c3_pair", choices=["c3_pair"] + sorted(WORKLOADS),
                     help="c3_pair is the headline metric; the others are secondary measurements")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for the profiler's byte counters)")
@@ -345,86 +516,13 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (the path is sharded by transform block "
                  "in design only); --gpus %d is not available" % args.gpus)
-
     import torch
-    from paper_2511_19705_amd import cafeq, workloads as WL
-
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    if args.workload in ("c2_infer", "c3_infer"):
-        return infer_workload(args)
-    if args.workload == "c3_rtn":
-        return rtn_workload(args)
-    if args.workload != "c3_pair":
-        return other_workload(args)
-    dev = torch.device("cuda:0")
-    cfg = WL.config3()
-    k, g, bits, rep = cfg["k"], cfg["group"], cfg["bits"][0], cfg["rep"]
-    A = torch.from_numpy(cfg["A"]).to(dev)
-    B = torch.from_numpy(cfg["B"]).to(dev)
-    T = torch.from_numpy(cfg["T"]).to(dev)
-    elems = A.numel() + B.numel()
-
-    def step():
-        P, _ = cafeq.block_inverse(T)
-        return cafeq.dual_proxy_loss_fwd_bwd(A, B, T, P, bits, g, rep, 5.0, want_grad=True)
-
-    if args.calib_copy:
-        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
-        dst = torch.empty_like(src)
-        dst.copy_(src)           # reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del src, dst
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    cafeq.profile_enable(True)
-    cafeq.profile_read()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        out = step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    n_launch, core_ms = cafeq.profile_read()
-    cafeq.profile_enable(False)
-    losses = out[0].cpu().numpy()
-
-    ms_per_step = dt / args.steps * 1e3
-    value = elems * args.steps / dt
-    # dominant kernel: the loss pass of the fused transform core, launched once per member.
-    # Algorithmic work per launch: forward and inverse transform of its member, 2k flop per
-    # element each; it reads every weight once (4 B per element).
-    member = elems / 2.0
-    flops_per_launch = 2.0 * 2.0 * k * member
-    avg_launch_s = core_ms / 1e3 / max(n_launch, 1)
-    achieved = flops_per_launch / avg_launch_s / 1e12
-    executed = 6.0 * 2.0 * k * member / avg_launch_s / 1e12   # 3 + 3 part products per contraction index
-    result = {
-        "metric": "proxy-loss fwd+bwd weight-elements/s (9B-shaped MLP pair, dual transform)",
-        "value": value, "unit": "weight-elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": cfg["name"], "rows_cols": [list(cfg["A"].shape), list(cfg["B"].shape)],
-                   "block": k, "group": g, "bits": bits, "evals_per_s": args.steps / dt,
-                   "step": "block inverse + dual proxy-loss fwd+bwd (loss pass + gradient pass per member)",
-                   "inverse": "T is the workload's rotation (the paper's initialisation): blocks verified to be "
-                              "rotations are inverted by transposition (about 20 us); any other block takes the "
-                              "elimination kernel (about 100 us for these 112 blocks)",
-                   "contraction": "forward: 2 float16 parts per operand, 3 products; inverse: bfloat16 parts, 3 products; float32 accumulate",
-                   "relative_l2_A": float((losses[2] / float((cfg["A"].astype("float64") ** 2).sum())) ** 0.5)},
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg["name"]),
-                     "kernel": "xform_core_kernel<128,128,*,false,true> (loss pass)", "launches": n_launch,
-                     "avg_launch_us": avg_launch_s * 1e6,
-                     "algorithmic_flop_per_element": 4 * k, "algorithmic_bytes_per_element": 4,
-                     "executed_part_product_tflops": executed,
-                     "executed_frac_of_bf16_peak": executed / BF16_MFMA_PEAK_TFLOPS,
-                     "achieved_over_fp32_mfma_peak": achieved / FP32_MFMA_PEAK_TFLOPS,
-                     "hbm_frac_at_algorithmic_bytes": 4.0 * member / avg_launch_s / 1e9 / HBM_PEAK_GBS},
-    }
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_blocks, args.cpu_reps)
-    print(json.dumps(result))
+    if args.workload == "c3_pair":
+        res = pair_workload(args, secondary=not args.no_secondary)
+    else:
+        res = WORKLOADS[args.workload](args)
+    print(json.dumps(res))
 
 
 if __name__ == "__main__":

@@ -31,8 +31,9 @@
  *    s = fl32(a / qmax), dequantized value fl32(q*s); a == 0 gives s = 0, q = 0.
  *  - Every pointer named in a signature is a DEVICE pointer owned by the caller unless
  *    stated otherwise; descriptor structs themselves are host memory, read during the
- *    call only.  Nothing is allocated or freed by the library; scratch memory is the
- *    caller's `ws` buffer, sized by cafeq_workspace_bytes() and 256-byte aligned.
+ *    call only.  Nothing is allocated or freed by the library (no device memory, no events,
+ *    no streams); scratch memory is the caller's `ws` buffer, sized by
+ *    cafeq_workspace_bytes() and 256-byte aligned.
  *  - `stream` is a hipStream_t (NULL = default stream).  Calls enqueue work and return;
  *    outputs are valid once the stream has been synchronised.  Results (losses too) are
  *    written to device memory, never returned through the host.
@@ -323,13 +324,20 @@ int cafeq_optimize_pair(const cafeq_mat* A, const cafeq_mat* B, float* T, float*
                         const cafeq_opt_cfg* opt, float* moments, float* history, int* status,
                         void* ws, void* stream);
 
-/* Measurement aid (not part of the method): while enabled, every launch of the fused
- * transform kernel is bracketed by HIP events recorded on the launch stream.
- * cafeq_profile_read synchronises those events, returns the number of launches seen since
- * the last read and stores the sum of their durations in *total_ms (host pointer), then
- * forgets them.  Not thread-safe; at most 4096 launches are kept between reads. */
-int cafeq_profile_enable(int on);
-int cafeq_profile_read(float* total_ms);
+/* Measurement aid (not part of the method).  While a table is installed, every launch of the fused transform
+ * kernel (the loss pass; not the gradient pass or the small kernels around it) is bracketed by two of the
+ * CALLER's events, recorded on the launch stream: launch number i uses start[i] / stop[i] (hipEvent_t handles
+ * the caller created with timing enabled) and count is incremented; launches beyond `capacity` are not
+ * timed.  The library creates, destroys and synchronises nothing: the caller synchronises the stream and reads
+ * hipEventElapsedTime(start[i], stop[i]).  The table (host memory) must stay valid until it is replaced or
+ * removed with NULL.  One table per process; not thread-safe. */
+typedef struct {
+  void** start;
+  void** stop;
+  int capacity;
+  int count;
+} cafeq_launch_timing;
+int cafeq_set_launch_timing(cafeq_launch_timing* t);
 
 #ifdef __cplusplus
 }

@@ -25,8 +25,7 @@ EXPORTS = (
     "cafeq_dual_proxy_loss_fwd_bwd", "cafeq_adaptive_round_step",
     "cafeq_orth_penalty", "cafeq_sgd_update", "cafeq_adam_update", "cafeq_optimize_single",
     "cafeq_optimize_pair", "cafeq_pqe", "cafeq_rtn_quantize_minmax", "cafeq_hadamard_rtn", "cafeq_hadamard_workspace_bytes",
-    "cafeq_infer_single", "cafeq_infer_workspace_bytes", "cafeq_profile_enable",
-    "cafeq_profile_read", "cafeq_rtn_quantize_static", "cafeq_prepared_bytes", "cafeq_prepare_weights",
+    "cafeq_infer_single", "cafeq_infer_workspace_bytes", "cafeq_set_launch_timing", "cafeq_rtn_quantize_static", "cafeq_prepared_bytes", "cafeq_prepare_weights",
 )
 
 
@@ -47,6 +46,11 @@ class Xform(ctypes.Structure):
 class QuantCfg(ctypes.Structure):
     _fields_ = [("bits", ctypes.c_int32), ("group", ctypes.c_int32), ("axis", ctypes.c_int32),
                 ("mode", ctypes.c_int32)]
+
+
+class LaunchTiming(ctypes.Structure):
+    _fields_ = [("start", ctypes.POINTER(ctypes.c_void_p)), ("stop", ctypes.POINTER(ctypes.c_void_p)),
+                ("capacity", ctypes.c_int32), ("count", ctypes.c_int32)]
 
 
 class OptCfg(ctypes.Structure):
@@ -101,8 +105,7 @@ def _load():
     lib.cafeq_hadamard_rtn.argtypes = [ctypes.POINTER(Mat), vp, i32, ctypes.POINTER(QuantCfg), vp, vp, vp, vp, vp, vp]
     lib.cafeq_pqe.argtypes = [vp, vp, i64, i64, i64, i64, ctypes.POINTER(QuantCfg), i32, i32, i32, vp, vp, vp, vp,
                               vp, vp, vp]
-    lib.cafeq_profile_enable.argtypes = [i32]
-    lib.cafeq_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float)]
+    lib.cafeq_set_launch_timing.argtypes = [ctypes.POINTER(LaunchTiming)]
     for n in EXPORTS[3:]:
         getattr(lib, n).restype = i32
     return lib
@@ -294,15 +297,31 @@ def adaptive_round_step(U, V, codesU, scalesU, codesV, scalesV, bits, group, k, 
     return status
 
 
-def profile_enable(on):
-    lib.cafeq_profile_enable(1 if on else 0)
+class LaunchTimer:
+    """Caller-owned events around the fused-kernel launches (cafeq_set_launch_timing): `capacity` pairs of
+    torch events are created up front; the library only records them."""
 
+    def __init__(self, capacity):
+        self.ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(capacity)]
+        for a, b in self.ev:          # torch creates the underlying event on first use
+            a.record()
+            b.record()
+        torch.cuda.synchronize()
+        self.start = (ctypes.c_void_p * capacity)(*[a.cuda_event for a, _ in self.ev])
+        self.stop = (ctypes.c_void_p * capacity)(*[b.cuda_event for _, b in self.ev])
+        self.table = LaunchTiming(self.start, self.stop, capacity, 0)
 
-def profile_read():
-    """(number of fused-kernel launches since the last read, sum of their durations in ms)."""
-    ms = ctypes.c_float(0.0)
-    n = lib.cafeq_profile_read(ctypes.byref(ms))
-    return n, float(ms.value)
+    def __enter__(self):
+        self.table.count = 0
+        _check(lib.cafeq_set_launch_timing(ctypes.byref(self.table)))
+        return self
+
+    def __exit__(self, *exc):
+        _check(lib.cafeq_set_launch_timing(None))
+
+    def durations_ms(self):
+        """Per-launch durations (the caller has synchronised the stream)."""
+        return [self.ev[i][0].elapsed_time(self.ev[i][1]) for i in range(self.table.count)]
 
 
 def orth_penalty(T, lam, grad=None):

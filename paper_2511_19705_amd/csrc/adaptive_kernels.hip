@@ -331,7 +331,6 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_panel_kernel(const GjA
   __shared__ int pk[K], kinv[K];
   __shared__ int pvt[2][NB];
   __shared__ int deadflag;
-  __shared__ float cn[K];
   __shared__ S wred[16];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   if (a.need && a.need[b] == 0) return;   // uniform over the workgroup
@@ -377,7 +376,6 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_panel_kernel(const GjA
     for (int j = 0; j < CT; ++j) anorm = fmax(anorm, fabs(reg[i][j]));
   for (int m = 1; m < 64; m <<= 1) anorm = fmax(anorm, __shfl_xor(anorm, m));
   if (lane == 0) wred[tid >> 6] = anorm;
-  if (tid < K) cn[tid] = 0.f;
   if (tid == 0) deadflag = 0;
   __syncthreads();
   anorm = 0;
@@ -572,15 +570,17 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_panel_kernel(const GjA
     }
   }
   if (a.rho_col) {
-#pragma unroll
-    for (int j = 0; j < CT; ++j) {
-      S c2 = 0;
-#pragma unroll
-      for (int i = 0; i < RT; ++i) c2 += reg[i][j] * reg[i][j];
-      atomicAdd(&cn[ocol[j]], float(c2));
-    }
+    // column norms from the block just written, one thread per column, rows in order (fixed summation order:
+    // the result is reproducible run to run)
     __syncthreads();
-    if (tid < K) a.rho_col[size_t(b) * K + tid] = cn[tid];
+    if (tid < K) {
+      double c2 = 0;
+      for (int i = 0; i < K; ++i) {
+        const float v = O[i * K + tid];
+        c2 += double(v) * v;
+      }
+      a.rho_col[size_t(b) * K + tid] = float(c2);
+    }
   }
 }
 
@@ -1037,7 +1037,7 @@ int launch_block_inverse(const float* T, int K, int nb, double* work, float* Tin
     int* need = reinterpret_cast<int*>(work);
     const size_t lds = size_t(2 * K * (K + 1) + (K / 32) * (K / 32)) * sizeof(float);
     if (K == 128) {
-      static bool attr_set = false;
+      static std::atomic<bool> attr_set{false};
       if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(rotation_inverse_kernel<128>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
@@ -1077,7 +1077,7 @@ int launch_block_inverse_warm(const float* T, int K, int nb, double* work, float
   int* need = reinterpret_cast<int*>(work);
   const size_t lds = size_t(2 * K * (K + 1) + 2 * (K / 32) * (K / 32)) * sizeof(float);
   if (K == 128) {
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};
     if (!attr_set) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(newton_inverse_kernel<128>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)

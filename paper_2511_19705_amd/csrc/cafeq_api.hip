@@ -317,7 +317,7 @@ int run_core(int K, int axis, const GroupPlan& gp, CoreParams p, float2* rec, fl
     p.prep_lscale = reinterpret_cast<const float*>(base + l.off_lscale);
     p.prep_planes = base + l.off_planes;
     p.rec = want_rec ? rec : nullptr;
-    return launch_loss_v2(gp.Gk, axis, p, st);
+    return launch_loss_prepared(gp.Gk, axis, p, st);
   }
   if (gp.gspan > 1) {
     CoreParams s1 = p;
@@ -347,10 +347,9 @@ int run_grad_pass(int K, int axis, const cafeq_mat* W, int rep, const PassPlans&
 
 namespace cafeq {
 namespace {
-struct ProfileState {
-  bool on = false;
-  std::vector<std::pair<hipEvent_t, hipEvent_t>> ev;
-} g_prof;
+// Measurement aid: the caller's table of pre-created events (cafeq_set_launch_timing); nothing is created,
+// allocated or synchronised here.
+cafeq_launch_timing* g_timing = nullptr;
 int launch_core_raw(int K, int G, int axis, const CoreParams& p, hipStream_t st) {
   switch (K) {
     case 32: return launch_core_k32(G, axis, p, st);
@@ -360,16 +359,23 @@ int launch_core_raw(int K, int G, int axis, const CoreParams& p, hipStream_t st)
     default: return CAFEQ_ERR_UNSUPPORTED;
   }
 }
+template <typename F>
+int timed_launch(hipStream_t st, F&& launch) {
+  cafeq_launch_timing* t = g_timing;
+  if (!t || t->count >= t->capacity) return launch();
+  const int i = t->count;
+  (void)hipEventRecord(static_cast<hipEvent_t>(t->start[i]), st);
+  const int rc = launch();
+  (void)hipEventRecord(static_cast<hipEvent_t>(t->stop[i]), st);
+  t->count = i + 1;
+  return rc;
+}
 }  // namespace
 int launch_core(int K, int G, int axis, const CoreParams& p, hipStream_t st) {
-  if (!g_prof.on || g_prof.ev.size() >= 4096) return launch_core_raw(K, G, axis, p, st);
-  hipEvent_t e0, e1;
-  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return CAFEQ_ERR_LAUNCH;
-  (void)hipEventRecord(e0, st);
-  const int rc = launch_core_raw(K, G, axis, p, st);
-  (void)hipEventRecord(e1, st);
-  g_prof.ev.emplace_back(e0, e1);
-  return rc;
+  return timed_launch(st, [&] { return launch_core_raw(K, G, axis, p, st); });
+}
+int launch_loss_prepared(int G, int axis, const CoreParams& p, hipStream_t st) {
+  return timed_launch(st, [&] { return launch_loss_v2(G, axis, p, st); });
 }
 size_t core_lds_bytes(int K, int G, bool do_grad) {
   switch (K) {
@@ -507,26 +513,10 @@ int cafeq_optimize_pair(const cafeq_mat* A, const cafeq_mat* B, float* T, float*
 }
 
 
-int cafeq_profile_enable(int on) {
-  cafeq::g_prof.on = on != 0;
+int cafeq_set_launch_timing(cafeq_launch_timing* t) {
+  if (t && (t->capacity < 0 || t->count < 0 || (t->capacity > 0 && (!t->start || !t->stop)))) return CAFEQ_ERR_INVALID_ARG;
+  cafeq::g_timing = t;
   return CAFEQ_OK;
-}
-
-int cafeq_profile_read(float* total_ms) {
-  float total = 0.f;
-  int n = 0;
-  for (auto& pr : cafeq::g_prof.ev) {
-    float ms = 0.f;
-    if (hipEventSynchronize(pr.second) == hipSuccess && hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) {
-      total += ms;
-      ++n;
-    }
-    (void)hipEventDestroy(pr.first);
-    (void)hipEventDestroy(pr.second);
-  }
-  cafeq::g_prof.ev.clear();
-  if (total_ms) *total_ms = total;
-  return n;
 }
 
 size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b, const cafeq_xform* x,

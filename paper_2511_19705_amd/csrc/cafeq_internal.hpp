@@ -1,6 +1,7 @@
 // Host-side interfaces between the C-ABI layer (cafeq_api.hip) and the kernel files.
 #pragma once
 #include <algorithm>
+#include <atomic>
 
 #include "cafeq_common.hpp"
 
@@ -54,6 +55,7 @@ struct PreparedLayout { int64_t nlp, nseg, ntiles; size_t off_lscale, off_planes
 PreparedLayout prepared_layout(int64_t nlines, int64_t naxis);
 int launch_prepare(const cafeq_mat* W, int axis, void* prepared, hipStream_t st);
 int launch_loss_v2(int G, int axis, const CoreParams& p, hipStream_t st);
+int launch_loss_prepared(int G, int axis, const CoreParams& p, hipStream_t st);   // ... with the caller's timing events
 
 // aux_kernels.hip
 // fscale != null: two float16 planes of the block scaled by a power of two; fscale[block] = the factor back.

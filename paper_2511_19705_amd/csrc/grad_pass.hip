@@ -10,7 +10,7 @@ int launch_grad_t(const CoreParams& p, hipStream_t st) {
   constexpr size_t lds = size_t(g::LDSB);
   static_assert((K == 256 ? 1 : 2) * lds <= kMaxLds, "workgroups per compute unit");
   auto kern = grad_z_kernel<K, AXIS>;
-  static bool attr_set = false;   // per instantiation
+  static std::atomic<bool> attr_set{false};   // per instantiation
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             int(kMaxLds)) != hipSuccess)

@@ -494,7 +494,7 @@ __global__ __launch_bounds__(256) void prepare_sum_kernel(const double* __restri
 template <int G, int AXIS, bool REC, bool OUT>
 int launch_v2_v(const CoreParams& p, hipStream_t st) {
   auto kern = loss_v2_kernel<G, AXIS, REC, OUT>;
-  static bool attr_set = false;   // per instantiation
+  static std::atomic<bool> attr_set{false};   // per instantiation
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             160 * 1024) != hipSuccess)

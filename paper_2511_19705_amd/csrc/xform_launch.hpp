@@ -21,7 +21,7 @@ constexpr bool core_has_f16() { return K == 128 && Geo<K, G>::NBLK == 1; }
 template <int K, int G, int AXIS, bool GRAD, bool F16 = false, bool LONGG = false>
 int launch_core_v(const CoreParams& p, size_t lds, hipStream_t st) {
   auto kern = xform_core_kernel<K, G, AXIS, GRAD, F16, LONGG>;
-  static bool attr_set = false;   // per instantiation
+  static std::atomic<bool> attr_set{false};   // per instantiation
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             int(kMaxLds)) != hipSuccess)
