@@ -45,89 +45,95 @@ struct SplitJobs { SplitJob job[4]; int njobs, K; float* hdr; int64_t nhdr; };  
 // two that puts its largest magnitude into [2^texp, 2^(texp+1)) (14: the low parts stay normal numbers; 4: sums of
 // 128 products with operands below 2^4 stay below 2^16 -- the matrix cores take denormal float16 inputs exactly), then
 // x = hi + lo with both parts rounded to nearest; fscale[b] receives the factor that undoes the scale.
-// grid: (nb, njobs * K / 32).
-__global__ __launch_bounds__(256) void split_planes_kernel(const SplitJobs js) {
-  // one workgroup per (block, job, stage of 32 contraction indices): the stage's planes are
-  // assembled in LDS in their final order and leave as whole 16-byte vectors
+// grid: (nb, njobs): one workgroup per (block, job) walks the K / 32 stages, so that the block's largest
+// magnitude (float16 jobs) is found once.
+constexpr int kSplitThreads = 1024;
+__global__ __launch_bounds__(kSplitThreads) void split_planes_kernel(const SplitJobs js) {
+  // a stage's planes are assembled in LDS in their final order and leave as whole 16-byte vectors
   __shared__ __align__(16) uint16_t lds[3 * 256 * 32];
   const int K = js.K, nst = K / 32;
   // partial headers that no workgroup of the core writes (slots nobody owns) must read as empty
   if (js.hdr) {
-    const int64_t nthr = int64_t(gridDim.x) * gridDim.y * 256;
-    for (int64_t i = (int64_t(blockIdx.y) * gridDim.x + blockIdx.x) * 256 + threadIdx.x; i < js.nhdr; i += nthr)
+    const int64_t nthr = int64_t(gridDim.x) * gridDim.y * kSplitThreads;
+    for (int64_t i = (int64_t(blockIdx.y) * gridDim.x + blockIdx.x) * kSplitThreads + threadIdx.x; i < js.nhdr; i += nthr)
       js.hdr[i] = (i % kHdrFloats) == kHdrMref ? -INFINITY : 0.f;
   }
-  const SplitJob jb = js.job[blockIdx.y / nst];
-  const int stage = blockIdx.y % nst, nplanes = jb.nplanes;
+  const SplitJob jb = js.job[blockIdx.y];
+  const int nplanes = jb.nplanes;
   const float* sb = jb.src + size_t(blockIdx.x) * K * K;
-  uint16_t* db = jb.dst + (size_t(blockIdx.x) * nst + stage) * nplanes * K * 32;
   const int lk = 31 - __builtin_clz(unsigned(K));
   float hsc = 1.f;   // float16 job: the block's scale
   if (jb.fscale) {
-    __shared__ float wmx[4];
+    __shared__ float wmx[kSplitThreads / 64];
     float m = 0.f;
-    for (int e = threadIdx.x * 4; e < K * K; e += 256 * 4) {
+    for (int e = threadIdx.x * 4; e < K * K; e += kSplitThreads * 4) {
       const float4 v = *reinterpret_cast<const float4*>(sb + e);
       m = fmaxf(fmaxf(m, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
     }
     m = cluster_allmax<64>(m);
     if ((threadIdx.x & 63) == 0) wmx[threadIdx.x >> 6] = m;
     __syncthreads();
-    m = fmaxf(fmaxf(wmx[0], wmx[1]), fmaxf(wmx[2], wmx[3]));
+    m = 0.f;
+    for (int i = 0; i < kSplitThreads / 64; ++i) m = fmaxf(m, wmx[i]);
     int ex = int(__float_as_uint(m) >> 23);
     ex = ex < 32 ? 32 : (ex > 254 ? 254 : ex);
     hsc = __uint_as_float(uint32_t(254 + jb.texp - ex) << 23);             // 2^(texp - (ex - 127))
-    if (stage == 0 && threadIdx.x == 0) jb.fscale[blockIdx.x] = __uint_as_float(uint32_t(ex - jb.texp) << 23);
+    if (threadIdx.x == 0) jb.fscale[blockIdx.x] = __uint_as_float(uint32_t(ex - jb.texp) << 23);
   }
-  // a thread takes four inputs that are adjacent in the plane (e = 0..3 of one (row, step, half, u)):
-  // one 128-bit load (or four coalesced loads of a transposed source) and one 64-bit LDS store per plane
-  for (int qd = threadIdx.x; qd < K * 8; qd += 256) {
-    int out, wq;
-    float x[4];
-    if (jb.trans) {
-      out = qd & (K - 1); wq = qd >> lk;
+  for (int stage = 0; stage < nst; ++stage) {
+    uint16_t* buf = lds;
+    uint16_t* db = jb.dst + (size_t(blockIdx.x) * nst + stage) * nplanes * K * 32;
+    // a thread takes four inputs that are adjacent in the plane (e = 0..3 of one (row, step, half, u)):
+    // one 128-bit load (or four coalesced loads of a transposed source) and one 64-bit LDS store per plane
+    for (int qd = threadIdx.x; qd < K * 8; qd += kSplitThreads) {
+      int out, wq;
+      float x[4];
+      if (jb.trans) {
+        out = qd & (K - 1); wq = qd >> lk;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) x[e] = sb[size_t(32 * stage + 4 * wq + e) * K + out];
-    } else {
-      out = qd >> 3; wq = qd & 7;
-      const float4 v = *reinterpret_cast<const float4*>(sb + size_t(out) * K + 32 * stage + 4 * wq);
-      x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
-    }
-    // quad wq holds inputs 4 wq .. 4 wq + 3 of the stage = 16 c2 + 8 u + 4 hh + e; with the natural order the
-    // lane half takes eight consecutive inputs, i.e. the two middle bits swap their roles
-    const int c2 = wq >> 2, u = jb.natural ? (wq & 1) : (wq >> 1) & 1, hh = jb.natural ? (wq >> 1) & 1 : (wq & 1);
-    const int chunk = (2 * c2 + hh) ^ ((out >> 2) & 3);
-    const int at = out * 32 + chunk * 8 + 4 * u;
-    if (jb.fscale) {
-      uint32_t hi[4], lo[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float y = x[e] * hsc;
-        const _Float16 a = _Float16(y);
-        const _Float16 b = _Float16(y - float(a));
-        hi[e] = __builtin_bit_cast(uint16_t, a);
-        lo[e] = __builtin_bit_cast(uint16_t, b);
+        for (int e = 0; e < 4; ++e) x[e] = sb[size_t(32 * stage + 4 * wq + e) * K + out];
+      } else {
+        out = qd >> 3; wq = qd & 7;
+        const float4 v = *reinterpret_cast<const float4*>(sb + size_t(out) * K + 32 * stage + 4 * wq);
+        x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
       }
-      *reinterpret_cast<uint2*>(lds + at) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
-      *reinterpret_cast<uint2*>(lds + at + K * 32) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
-      continue;
-    }
-    for (int pl = 0; pl < nplanes; ++pl) {
-      uint32_t part[4];
+      // quad wq holds inputs 4 wq .. 4 wq + 3 of the stage = 16 c2 + 8 u + 4 hh + e; with the natural order the
+      // lane half takes eight consecutive inputs, i.e. the two middle bits swap their roles
+      const int c2 = wq >> 2, u = jb.natural ? (wq & 1) : (wq >> 1) & 1, hh = jb.natural ? (wq >> 1) & 1 : (wq & 1);
+      const int chunk = (2 * c2 + hh) ^ ((out >> 2) & 3);
+      const int at = out * 32 + chunk * 8 + 4 * u;
+      if (jb.fscale) {
+        uint32_t hi[4], lo[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        uint32_t bits = __float_as_uint(x[e]);
-        bits += 0x7FFFu + ((bits >> 16) & 1u);          // round to nearest even
-        part[e] = bits >> 16;
-        x[e] -= __uint_as_float(part[e] << 16);
+        for (int e = 0; e < 4; ++e) {
+          const float y = x[e] * hsc;
+          const _Float16 a = _Float16(y);
+          const _Float16 b = _Float16(y - float(a));
+          hi[e] = __builtin_bit_cast(uint16_t, a);
+          lo[e] = __builtin_bit_cast(uint16_t, b);
+        }
+        *reinterpret_cast<uint2*>(buf + at) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
+        *reinterpret_cast<uint2*>(buf + at + K * 32) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+        continue;
       }
-      *reinterpret_cast<uint2*>(lds + at + pl * K * 32) = make_uint2(part[0] | (part[1] << 16), part[2] | (part[3] << 16));
+      for (int pl = 0; pl < nplanes; ++pl) {
+        uint32_t part[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          uint32_t bits = __float_as_uint(x[e]);
+          bits += 0x7FFFu + ((bits >> 16) & 1u);          // round to nearest even
+          part[e] = bits >> 16;
+          x[e] -= __uint_as_float(part[e] << 16);
+        }
+        *reinterpret_cast<uint2*>(buf + at + pl * K * 32) = make_uint2(part[0] | (part[1] << 16), part[2] | (part[3] << 16));
+      }
     }
+    __syncthreads();
+    const uint4* s4 = reinterpret_cast<const uint4*>(buf);
+    uint4* d4 = reinterpret_cast<uint4*>(db);
+    for (int e = threadIdx.x; e < nplanes * K * 4; e += kSplitThreads) d4[e] = s4[e];
+    __syncthreads();   // drained before the next stage overwrites it
   }
-  __syncthreads();
-  const uint4* s4 = reinterpret_cast<const uint4*>(lds);
-  uint4* d4 = reinterpret_cast<uint4*>(db);
-  for (int e = threadIdx.x; e < nplanes * K * 4; e += 256) d4[e] = s4[e];
 }
 
 // rG[gi] = sum of rho over the axis indices of group gi (axis index a -> block (a/K)/rep, a%K).
@@ -187,7 +193,7 @@ __global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceJobs js) {
   constexpr int kBatch = 64;
   __shared__ const float* src[kBatch];
   __shared__ float scl[kBatch];
-  __shared__ int nsrc, more, next_q, next_w;
+  __shared__ int rng_lo, rng_hi;
   const int b = blockIdx.x;
   const int K = a.K;
   // this workgroup's 1024 elements: rows of KMr inputs inside one half
@@ -198,50 +204,54 @@ __global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceJobs js) {
   const int j = rg * rows_per_wg + (threadIdx.x * 4) / KMr, ml = (threadIdx.x * 4) % KMr;
   const bool active = j < K;
   const int poff = j * KMr + ml;                            // offset inside a partial (plus the block's base)
-  if (threadIdx.x == 0) { next_q = b * a.rep; next_w = -1; }
-  __syncthreads();
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (;;) {
+  // every partial of a two-pass member carries the same scale
+  float sc_all = 1.f;
+  if (a.lse_ms && a.member_ref) sc_all = float(exp(double(a.t) * (double(*a.member_ref) - a.lse_ms[0])) / a.lse_ms[1]);
+  for (int q = b * a.rep; q < (b + 1) * a.rep; ++q) {
+    int seg, base;
+    if (a.msplit == 2) { seg = 2 * q + half; base = 0; }
+    else { seg = int((int64_t(q) * K) / a.seg_len); base = int((int64_t(q) * K) % a.seg_len) * K; }
     if (threadIdx.x == 0) {
-      // gather up to kBatch (partial, scale) pairs, resuming where the last batch stopped
-      int n = 0, q = next_q, wres = next_w;
-      bool full = false;
-      for (; q < (b + 1) * a.rep && !full; ++q) {
-        int seg, base;
-        if (a.msplit == 2) { seg = 2 * q + half; base = 0; }
-        else { seg = int((int64_t(q) * K) / a.seg_len); base = int((int64_t(q) * K) % a.seg_len) * K; }
-        int lo, hi;
-        seg_wg_range(seg, a.mt_per_seg, a.n_mt, a.nwg, &lo, &hi);
-        int w = wres >= 0 ? wres : lo;
-        wres = -1;
-        for (; w < hi; ++w) {
-          if (n == kBatch) { full = true; wres = w; break; }
-          const int64_t slot = int64_t(w) + seg;
-          float sc = 1.f;
-          if (a.lse_ms) {
-            const float mref = a.member_ref ? *a.member_ref : a.slot_hdr[slot * kHdrFloats + kHdrMref];
-            sc = float(exp(double(a.t) * (double(mref) - a.lse_ms[0])) / a.lse_ms[1]);
+      int lo, hi;
+      seg_wg_range(seg, a.mt_per_seg, a.n_mt, a.nwg, &lo, &hi);
+      rng_lo = lo; rng_hi = hi;
+    }
+    __syncthreads();
+    const int lo = rng_lo, hi = rng_hi;
+    for (int w0 = lo; w0 < hi; w0 += kBatch) {
+      const int n = hi - w0 < kBatch ? hi - w0 : kBatch;
+      // the list of (partial, scale) pairs of this batch, one thread per entry
+      if (int(threadIdx.x) < n) {
+        const int64_t slot = int64_t(w0 + int(threadIdx.x)) + seg;
+        float sc = sc_all;
+        if (a.lse_ms && !a.member_ref)
+          sc = float(exp(double(a.t) * (double(a.slot_hdr[slot * kHdrFloats + kHdrMref]) - a.lse_ms[0])) / a.lse_ms[1]);
+        src[threadIdx.x] = a.slot_grad + slot * int64_t(a.part_floats) + base;
+        scl[threadIdx.x] = sc;
+      }
+      __syncthreads();
+      if (active) {
+        // four partials in flight per thread; the additions keep the order of the list
+        int s = 0;
+        for (; s + 4 <= n; s += 4) {
+          float4 v[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4*>(src[s + u] + poff);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const float sc = scl[s + u];
+            acc.x += sc * v[u].x; acc.y += sc * v[u].y; acc.z += sc * v[u].z; acc.w += sc * v[u].w;
           }
-          src[n] = a.slot_grad + slot * int64_t(a.part_floats) + base;
-          scl[n] = sc;
-          ++n;
         }
-        if (full) break;
+        for (; s < n; ++s) {
+          const float4 v = *reinterpret_cast<const float4*>(src[s] + poff);
+          const float sc = scl[s];
+          acc.x += sc * v.x; acc.y += sc * v.y; acc.z += sc * v.z; acc.w += sc * v.w;
+        }
       }
-      nsrc = n; more = full ? 1 : 0; next_q = q; next_w = wres;
+      __syncthreads();
     }
-    __syncthreads();
-    const int n = nsrc;
-    if (active) {
-      for (int s = 0; s < n; ++s) {
-        const float4 v = *reinterpret_cast<const float4*>(src[s] + poff);
-        const float sc = scl[s];
-        acc.x += sc * v.x; acc.y += sc * v.y; acc.z += sc * v.z; acc.w += sc * v.w;
-      }
-    }
-    const int again = more;
-    __syncthreads();
-    if (!again) break;
   }
   if (active) {
     float* dst = a.out + size_t(b) * K * K;
@@ -519,7 +529,7 @@ int launch_split_planes_multi(const SplitRequest* req, int n, int K, int nb, hip
     js.job[i].trans = req[i].trans; js.job[i].nplanes = req[i].fscale ? 2 : req[i].nplanes;
     js.job[i].fscale = req[i].fscale; js.job[i].natural = req[i].natural; js.job[i].texp = req[i].texp;
   }
-  hipLaunchKernelGGL(split_planes_kernel, dim3(nb, n * (K / 32)), dim3(256), 0, st, js);
+  hipLaunchKernelGGL(split_planes_kernel, dim3(nb, n), dim3(kSplitThreads), 0, st, js);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }
