@@ -93,8 +93,10 @@ typedef struct {
 } cafeq_xform;
 
 /* bits in [2, 8]; group: elements per scale along `axis` (0 = whole line);
- * axis: cafeq_axis; mode: cafeq_qmode (CAFEQ_Q_SYM_ABSMAX in the fused calls; the min/max grid of the
- * paper's Eq. (1) has its own entry point, cafeq_rtn_quantize_minmax). */
+ * axis: cafeq_axis; mode: cafeq_qmode.  CAFEQ_Q_ASYM_MINMAX, the min/max grid of the paper's Eq. (1), is
+ * taken by cafeq_proxy_loss_fwd_bwd, cafeq_dual_proxy_loss_fwd_bwd and the two cafeq_optimize_* loops (see
+ * there for the output layout); the untransformed quantizer on that grid is cafeq_rtn_quantize_minmax; the
+ * other calls return CAFEQ_ERR_UNSUPPORTED for it. */
 typedef struct {
   int32_t bits, group, axis, mode;
 } cafeq_quant_cfg;
@@ -202,7 +204,7 @@ int cafeq_apply_transform(const cafeq_mat* W, const cafeq_xform* x, int axis, in
  * along `axis` (0 if the axis length is not a multiple of 128); about rows * cols * 4 bytes whatever the
  * storage type.  cafeq_prepare_weights fills it (device memory, 256-byte aligned, owned by the caller):
  * per tile of 32 lines x 128 axis indices two float16 parts of every element -- the line's segment scaled
- * by a power of two so that its largest magnitude lies in [2^14, 2^15), hi = fl16(y), lo = fl16(y - hi):
+ * by a power of two so that its largest magnitude lies in [2^3, 2^4), hi = fl16(y), lo = fl16(y - hi):
  * 22 significant bits -- in the order the loss kernel's matrix instructions read them, the per-line
  * factors that undo the scaling, and ||W||_F^2 (float64 sum).  To be called again whenever W changes. */
 size_t cafeq_prepared_bytes(const cafeq_mat* W, int axis);
@@ -224,7 +226,13 @@ int cafeq_prepare_weights(const cafeq_mat* W, int axis, void* prepared, void* st
  * multiple of k and divides the axis -- group = 0, the whole channel (the per-channel setting of the paper's
  * experiments, Sec. 6), included.  A group longer than 256 spans several segments of the kernel: the
  * transform is then applied twice (a first sweep finds every group's absmax), and the gradient needs the
- * axis to be a multiple of 128.  Every block size has a gradient for every such group. */
+ * axis to be a multiple of 128.  Every block size has a gradient for every such group.
+ * cfg->mode = CAFEQ_Q_ASYM_MINMAX: Q is the grid of Eq. (1) in the single-precision recipe of
+ * cafeq_rtn_quantize_minmax (losses[0], losses[1], codes, scales follow it); L_sur keeps the group absmax
+ * and takes the constant the paper prints for that grid, beta = 1/(2^b - 1)^2 (Sec. 4.1); codes are then
+ * unsigned bytes in [0, 2^b - 1] and `scales` holds twice as many floats: the scales, then the group minima
+ * in the same layout.  On this grid the gradient always runs as the second pass (axis a multiple of 128),
+ * and a prepared copy of the weights is ignored. */
 int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x,
                              const cafeq_quant_cfg* cfg, float* losses, float* gradT,
                              int8_t* codes, float* scales, void* ws, void* stream);
@@ -238,8 +246,9 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x,
  *   losses[5] = number of groups (as float)
  *   gradT[nb][k][k] (may be NULL) = d LSE / d T.
  * codesU/scalesU/codesV/scalesV (may be NULL): Q(U), Q(V).
- * Groups as in cafeq_proxy_loss_fwd_bwd (with group = 0 the LSE is the paper's sum over the channel
- * maxima m_u(i), m_v(j) of Sec. 4.2). */
+ * Groups and cfg->mode as in cafeq_proxy_loss_fwd_bwd (with group = 0 the LSE is the paper's sum over the
+ * channel maxima m_u(i), m_v(j) of Sec. 4.2; the LSE is a function of the group maxima alone, so the grid
+ * changes losses[0..3] and the codes, not losses[4] or gradT). */
 int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B,
                                   const cafeq_xform* x, const cafeq_quant_cfg* cfg,
                                   float lse_t, float* losses, float* gradT,

@@ -175,7 +175,7 @@ def quantize(Z, bits, group, axis, mode=SYM, arith="f32"):
     """zhat only, for either grid."""
     if mode == SYM:
         return rtn_sym(Z, bits, group, axis, arith)[2]
-    return rtn_asym(Z, bits, group, axis)[3]
+    return rtn_asym(Z, bits, group, axis, arith)[3]
 
 
 # ----------------------------------------------------------------------------
@@ -323,7 +323,7 @@ def surrogate_printed(W_in_out, M, bits):
 # ----------------------------------------------------------------------------
 # paired transform: forward errors, LogSumExp surrogate and gradient
 # ----------------------------------------------------------------------------
-def dual_lse(A, B, T, P, bits, group, rep=1, t=5.0, arith="f32", want_grad=True):
+def dual_lse(A, B, T, P, bits, group, rep=1, t=5.0, arith="f32", want_grad=True, mode=SYM):
     """Member A [d1 x nb*k] gets T on its columns (U = A T); member B
     [nb*rep*k x d3] gets P = T^-1 on its rows (V = P B).
 
@@ -333,7 +333,8 @@ def dual_lse(A, B, T, P, bits, group, rep=1, t=5.0, arith="f32", want_grad=True)
       lse              : (1/t) log( sum over every group of U and of V of exp(t * absmax) )
       n_groups, gradT  : d lse / dT  (through U directly, through V via dP = -P dT P)
     One LSE term per quantization group; with group = whole channel this is the
-    paper's sum over m_u(i) and m_v(j)."""
+    paper's sum over m_u(i) and m_v(j).  ``mode`` selects the grid Q rounds to (the symmetric
+    one or Eq. (1)); the LogSumExp is a function of the group maxima alone and does not depend on it."""
     A = np.asarray(A, dtype=np.float64)
     B = np.asarray(B, dtype=np.float64)
     T = np.asarray(T, dtype=np.float64)
@@ -341,8 +342,8 @@ def dual_lse(A, B, T, P, bits, group, rep=1, t=5.0, arith="f32", want_grad=True)
     nb, k, _ = T.shape
     U = blockdiag_apply(A, T, COL)
     V = blockdiag_apply(B, P, ROW, rep)
-    Uh = quantize(U, bits, group, COL, SYM, arith)
-    Vh = quantize(V, bits, group, ROW, SYM, arith)
+    Uh = quantize(U, bits, group, COL, mode, arith)
+    Vh = quantize(V, bits, group, ROW, mode, arith)
     EU = Uh - U
     EV = Vh - V
     DA = blockdiag_apply(EU, P, COL)

@@ -15,6 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("CAFEQ_LIBRARY", os.path.join(_HERE, "libcafeq.so"))
 
 AXIS_COL, AXIS_ROW = 0, 1
+Q_SYM, Q_MINMAX = 0, 1   # the symmetric absmax grid; the min/max grid of the paper's Eq. (1)
 SIDE_T, SIDE_TINV = 0, 1
 F32, BF16 = 0, 1
 CALL_RTN, CALL_PROXY, CALL_DUAL, CALL_ADAPTIVE = 0, 1, 2, 3
@@ -173,6 +174,11 @@ def _scale_shape(rows, cols, group, axis):
     return (rows // (group or rows), cols)
 
 
+def _minmax_shape(shape, mode):
+    """Scale buffer of the fused calls: on the min/max grid the group minima follow the scales."""
+    return shape if mode == Q_SYM else (2,) + tuple(shape)
+
+
 def rtn_quantize(W, bits, group, axis=AXIS_COL, want_err=False):
     m = mat(W)
     cfg = QuantCfg(bits, group, axis, 0)
@@ -230,32 +236,37 @@ def apply_transform(W, T, Tinv=None, axis=AXIS_COL, side=SIDE_T, rep=1):
 
 
 def proxy_loss_fwd_bwd(W, T, Tinv, bits, group, axis=AXIS_COL, rep=1, want_grad=True, want_codes=False,
-                       prepared=None):
-    """Returns (losses[4], gradT or None, codes or None, scales or None)."""
+                       prepared=None, mode=Q_SYM):
+    """Returns (losses[4], gradT or None, codes or None, scales or None).  With mode=Q_MINMAX the codes are
+    unsigned bytes and `scales` is [2][...]: the scales, then the group minima."""
     m = mat(W, prepared)
     x = xform(T, Tinv, rep)
-    cfg = QuantCfg(bits, group, axis, 0)
+    cfg = QuantCfg(bits, group, axis, mode)
     dev = W.device
     losses = torch.empty(4, dtype=torch.float32, device=dev)
     grad = torch.empty_like(T) if want_grad else None
     R, C = W.shape
     codes = torch.empty((R, C), dtype=torch.int8, device=dev) if want_codes else None
-    scales = torch.empty(_scale_shape(R, C, group, axis), dtype=torch.float32, device=dev) if want_codes else None
+    scales = torch.empty(_minmax_shape(_scale_shape(R, C, group, axis), mode), dtype=torch.float32,
+                         device=dev) if want_codes else None
     nbytes = workspace_bytes(CALL_PROXY, m, x=x, cfg=cfg)
     if nbytes == 0:
         raise CafeqError("unsupported proxy-loss configuration (workspace query returned 0)")
     ws = workspace(nbytes, dev)
     _check(lib.cafeq_proxy_loss_fwd_bwd(ctypes.byref(m), ctypes.byref(x), ctypes.byref(cfg), _ptr(losses),
                                         _ptr(grad), _ptr(codes), _ptr(scales), _ptr(ws), _stream()))
+    if want_codes and mode == Q_MINMAX:
+        codes = codes.view(torch.uint8)
     return losses, grad, codes, scales
 
 
 def dual_proxy_loss_fwd_bwd(A, B, T, Tinv, bits, group, rep=1, lse_t=5.0, want_grad=True, want_codes=False,
-                            prepared=(None, None)):
-    """Returns (losses[6], gradT or None, (codesU, scalesU, codesV, scalesV) or None)."""
+                            prepared=(None, None), mode=Q_SYM):
+    """Returns (losses[6], gradT or None, (codesU, scalesU, codesV, scalesV) or None); mode as in
+    proxy_loss_fwd_bwd."""
     ma, mb = mat(A, prepared[0]), mat(B, prepared[1])
     x = xform(T, Tinv, rep)
-    cfg = QuantCfg(bits, group, 0, 0)
+    cfg = QuantCfg(bits, group, 0, mode)
     dev = A.device
     losses = torch.empty(6, dtype=torch.float32, device=dev)
     grad = torch.empty_like(T) if want_grad else None
@@ -263,10 +274,12 @@ def dual_proxy_loss_fwd_bwd(A, B, T, Tinv, bits, group, rep=1, lse_t=5.0, want_g
     cu = su = cv = sv = None
     if want_codes:
         cu = torch.empty(A.shape, dtype=torch.int8, device=dev)
-        su = torch.empty(_scale_shape(A.shape[0], A.shape[1], group, AXIS_COL), dtype=torch.float32, device=dev)
+        su = torch.empty(_minmax_shape(_scale_shape(A.shape[0], A.shape[1], group, AXIS_COL), mode),
+                         dtype=torch.float32, device=dev)
         cv = torch.empty(B.shape, dtype=torch.int8, device=dev)
-        sv = torch.empty(_scale_shape(B.shape[0], B.shape[1], group, AXIS_ROW), dtype=torch.float32, device=dev)
-        outs = (cu, su, cv, sv)
+        sv = torch.empty(_minmax_shape(_scale_shape(B.shape[0], B.shape[1], group, AXIS_ROW), mode),
+                         dtype=torch.float32, device=dev)
+        outs = (cu, su, cv, sv) if mode == Q_SYM else (cu.view(torch.uint8), su, cv.view(torch.uint8), sv)
     nbytes = workspace_bytes(CALL_DUAL, ma, mb, x, cfg)
     if nbytes == 0:
         raise CafeqError("unsupported dual configuration (workspace query returned 0)")
@@ -343,13 +356,14 @@ def adam_update(T, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8):
                                  _stream()))
 
 
-def optimize_single(W, T, bits, group, axis=AXIS_COL, rep=1, lr=1.0, steps=10, lambda_orth=0.0, normalize=True):
+def optimize_single(W, T, bits, group, axis=AXIS_COL, rep=1, lr=1.0, steps=10, lambda_orth=0.0, normalize=True,
+                    mode=Q_SYM):
     """Gradient descent on the surrogate, T updated in place.  Returns (Tinv, history[steps][8], status)."""
     m = mat(W)
     nb, k, _ = T.shape
     Tinv = torch.empty_like(T)
     x = Xform(_ptr(T), _ptr(Tinv), k, nb, rep)
-    cfg = QuantCfg(bits, group, axis, 0)
+    cfg = QuantCfg(bits, group, axis, mode)
     opt = OptCfg(steps, lr, lambda_orth, 1 if normalize else 0, 0.0, 0.0, 0.0)
     ws = workspace(int(lib.cafeq_workspace_bytes(7, ctypes.byref(m), None, ctypes.byref(x), ctypes.byref(cfg))), W.device)
     history = torch.empty((max(steps, 1), 8), dtype=torch.float32, device=W.device)
@@ -360,13 +374,13 @@ def optimize_single(W, T, bits, group, axis=AXIS_COL, rep=1, lr=1.0, steps=10, l
 
 
 def optimize_pair(A, B, T, bits, group, rep=1, lse_t=5.0, lr=1e-2, steps=10, lambda_orth=0.0, beta1=0.1,
-                  beta2=0.999, eps=1e-8, prepared=(None, None)):
+                  beta2=0.999, eps=1e-8, prepared=(None, None), mode=Q_SYM):
     """Adam on the LogSumExp surrogate, T updated in place.  Returns (Tinv, history[steps][8], status)."""
     ma, mb = mat(A, prepared[0]), mat(B, prepared[1])
     nb, k, _ = T.shape
     Tinv = torch.empty_like(T)
     x = Xform(_ptr(T), _ptr(Tinv), k, nb, rep)
-    cfg = QuantCfg(bits, group, 0, 0)
+    cfg = QuantCfg(bits, group, 0, mode)
     opt = OptCfg(steps, lr, lambda_orth, 0, beta1, beta2, eps)
     ws = workspace(int(lib.cafeq_workspace_bytes(8, ctypes.byref(ma), ctypes.byref(mb), ctypes.byref(x),
                                                  ctypes.byref(cfg))), A.device)

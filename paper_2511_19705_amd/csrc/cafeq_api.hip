@@ -20,11 +20,12 @@ int check_mat(const cafeq_mat* m) {
   return CAFEQ_OK;
 }
 
-int check_cfg(const cafeq_quant_cfg* c, bool need_axis) {
+// allow_minmax: the call has kernels for the min/max grid of Eq. (1)
+int check_cfg(const cafeq_quant_cfg* c, bool need_axis, bool allow_minmax = false) {
   if (!c) return CAFEQ_ERR_INVALID_ARG;
   if (c->bits < 2 || c->bits > 8 || c->group < 0) return CAFEQ_ERR_INVALID_ARG;
   if (need_axis && c->axis != CAFEQ_AXIS_COL && c->axis != CAFEQ_AXIS_ROW) return CAFEQ_ERR_INVALID_ARG;
-  if (c->mode == CAFEQ_Q_ASYM_MINMAX) return CAFEQ_ERR_UNSUPPORTED;
+  if (c->mode == CAFEQ_Q_ASYM_MINMAX) return allow_minmax ? CAFEQ_OK : CAFEQ_ERR_UNSUPPORTED;
   if (c->mode != CAFEQ_Q_SYM_ABSMAX) return CAFEQ_ERR_INVALID_ARG;
   return CAFEQ_OK;
 }
@@ -124,11 +125,26 @@ bool core_forward_f16(int K, int G, int bits) { return K == 128 && G <= 128 && b
 // The gradient runs as a second pass over the weights, from the loss pass's arg-max records, where the fused
 // kernel has no gradient (blocks of 256, groups of 256 with blocks of 64 or more), where the two passes are
 // faster (blocks of 128), and for groups that span several segments.
-struct PassPlans { CorePlan first, gpass; GroupPlan gp; bool two, fused, v2; };
+// asym: the min/max grid of Eq. (1); its kernel variants are gradient-free, so the gradient always takes the
+// second pass.
+struct PassPlans { CorePlan first, gpass; GroupPlan gp; bool two, fused, v2, asym; };
+bool is_minmax(const cafeq_quant_cfg* cfg) { return cfg->mode == CAFEQ_Q_ASYM_MINMAX; }
+// levels and the surrogate's constant for either grid (Sec. 4.1: 1 / (2^b - 1)^2 for Eq. (1); a quarter of the
+// squared step of the symmetric grid)
+QGrid grid_for(const cafeq_quant_cfg* cfg) {
+  if (!is_minmax(cfg)) return make_grid(cfg->bits);
+  QGrid g;
+  g.qmax = float((1 << cfg->bits) - 1);
+  g.qmin = 0.f;
+  return g;
+}
+float beta_for(const cafeq_quant_cfg* cfg, const QGrid& g) {
+  return is_minmax(cfg) ? 1.f / (g.qmax * g.qmax) : 1.f / (4.f * g.qmax * g.qmax);
+}
 // The loss pass over prepared weights (loss_v2.hip): one workgroup of eight waves per compute unit,
 // macro-tiles of 256 lines.
-bool v2_eligible(const cafeq_mat* W, int K, const GroupPlan& gp, int bits) {
-  return W->prepared != nullptr && K == 128 && gp.Gk <= 128 && gp.gspan == 1 && bits <= 4;
+bool v2_eligible(const cafeq_mat* W, int K, const GroupPlan& gp, const cafeq_quant_cfg* cfg) {
+  return W->prepared != nullptr && K == 128 && gp.Gk <= 128 && gp.gspan == 1 && cfg->bits <= 4 && !is_minmax(cfg);
 }
 void make_v2_plan(CorePlan* pl) {
   pl->mt_per_seg = (pl->nlines + 255) / 256;
@@ -139,11 +155,12 @@ void make_v2_plan(CorePlan* pl) {
   pl->nslot = pl->nwg + pl->nseg;
 }
 int plan_passes(int K, const GroupPlan& gp, int64_t nlines, int64_t naxis, bool grad, PassPlans* pp,
-                bool v2 = false) {
+                bool v2 = false, bool asym = false) {
   pp->gp = gp;
   pp->v2 = v2;
+  pp->asym = asym;
   const size_t fl = core_lds_bytes(K, gp.Gk, true);
-  const bool fused_ok = fl != 0 && fl <= 160 * 1024 && gp.gspan == 1 && !(K == 128 && gp.Gk <= 128);
+  const bool fused_ok = fl != 0 && fl <= 160 * 1024 && gp.gspan == 1 && !(K == 128 && gp.Gk <= 128) && !asym;
   pp->two = grad && !fused_ok;
   pp->fused = grad && fused_ok;
   int rc = make_plan(K, gp.Gk, nlines, naxis, &pp->first, pp->fused);
@@ -159,6 +176,7 @@ struct MemberWs {
   float *rG, *rGreal, *slot_grad, *fs, *fsi;
   uint16_t *pfwd, *pinv;
   float2 *rec, *grec;
+  float2 *rec_mm, *grec_mm;   // min/max grid with groups that span segments
 };
 void carve_member(Carver& c, const PassPlans& pp, int nb, bool grad, bool want_rG, MemberWs* w) {
   const CorePlan& pl = pp.first;
@@ -172,6 +190,10 @@ void carve_member(Carver& c, const PassPlans& pp, int nb, bool grad, bool want_r
   w->slot_grad = c.take<float>(grad ? size_t(pp.gpass.nslot) * pp.gpass.slot_grad_floats : 0);
   w->rec = c.take<float2>((pp.two || big) ? size_t(pl.naxis / pl.G) * size_t(pl.nlines) : 0);
   w->grec = big ? c.take<float2>(size_t(pl.naxis / pp.gp.G) * size_t(pl.nlines)) : w->rec;
+  const bool mm = big && pp.asym;
+  w->rec_mm = c.take<float2>(mm ? size_t(pl.naxis / pl.G) * size_t(pl.nlines) : 0);
+  w->grec_mm = c.take<float2>(mm ? size_t(pl.naxis / pp.gp.G) * size_t(pl.nlines) : 0);
+  if (!mm) w->rec_mm = w->grec_mm = nullptr;
 }
 
 struct SingleWs {
@@ -296,6 +318,7 @@ void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep)
   p->fscale = nullptr;
   p->longg = 0; p->gspan = 1; p->grec = nullptr; p->grp = 0;
   p->prep_planes = nullptr; p->prep_lscale = nullptr; p->prep_wsq = nullptr; p->fscale_inv = nullptr;
+  p->asym = 0; p->mins = nullptr; p->rec_mm = nullptr; p->grec_mm = nullptr;
   p->grid = make_grid(4);
 }
 
@@ -305,7 +328,8 @@ void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep)
 // takes each group's absmax from the combined records (both sweeps run the same kernel variant, so they see
 // bit-identical transformed weights).
 int run_core(int K, int axis, const GroupPlan& gp, CoreParams p, float2* rec, float2* grec, bool want_rec,
-             hipStream_t st, const cafeq_mat* prepared_of = nullptr) {
+             hipStream_t st, const cafeq_mat* prepared_of = nullptr, float2* rec_mm = nullptr,
+             float2* grec_mm = nullptr) {
   int rc;
   if (prepared_of) {
     // loss pass over the prepared copy of the weights
@@ -323,9 +347,13 @@ int run_core(int K, int axis, const GroupPlan& gp, CoreParams p, float2* rec, fl
     CoreParams s1 = p;
     s1.do_inverse = 0; s1.do_grad = 0; s1.codes = nullptr; s1.scales = nullptr; s1.Zout = nullptr;
     s1.slot_hdr = nullptr; s1.slot_grad = nullptr; s1.rec = rec; s1.longg = 1; s1.gspan = 1; s1.grec = nullptr;
+    s1.mins = nullptr; s1.rec_mm = p.asym ? rec_mm : nullptr;
+    if (p.asym && (!rec_mm || !grec_mm)) return CAFEQ_ERR_INVALID_ARG;
     if ((rc = launch_core(K, gp.Gk, axis, s1, st))) return rc;
-    if ((rc = launch_combine_records(rec, gp.gspan, gp.Gk, p.nlines, (p.nseg / gp.gspan), grec, st))) return rc;
-    p.longg = 1; p.gspan = gp.gspan; p.grec = grec; p.rec = nullptr;
+    if ((rc = launch_combine_records(rec, gp.gspan, gp.Gk, p.nlines, (p.nseg / gp.gspan), grec, st,
+                                     p.asym ? rec_mm : nullptr, p.asym ? grec_mm : nullptr)))
+      return rc;
+    p.longg = 1; p.gspan = gp.gspan; p.grec = grec; p.rec = nullptr; p.grec_mm = p.asym ? grec_mm : nullptr;
   } else {
     p.rec = want_rec ? rec : nullptr;
   }
@@ -351,6 +379,15 @@ namespace {
 // allocated or synchronised here.
 cafeq_launch_timing* g_timing = nullptr;
 int launch_core_raw(int K, int G, int axis, const CoreParams& p, hipStream_t st) {
+  if (p.asym) {
+    switch (K) {
+      case 32: return launch_core_asym_k32(G, axis, p, st);
+      case 64: return launch_core_asym_k64(G, axis, p, st);
+      case 128: return launch_core_asym_k128(G, axis, p, st);
+      case 256: return launch_core_asym_k256(G, axis, p, st);
+      default: return CAFEQ_ERR_UNSUPPORTED;
+    }
+  }
   switch (K) {
     case 32: return launch_core_k32(G, axis, p, st);
     case 64: return launch_core_k64(G, axis, p, st);
@@ -538,10 +575,11 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
       GroupPlan gp;
       if (resolve_group(cfg, naxis, x->k, &gp)) return 0;
       PassPlans pg, pn;
-      if (plan_passes(x->k, gp, nlines, naxis, false, &pn)) return 0;
+      const bool mm = is_minmax(cfg);
+      if (plan_passes(x->k, gp, nlines, naxis, false, &pn, false, mm)) return 0;
       size_t bytes = carve_single(nullptr, pn, x->nb, false).bytes;
       // (where the gradient has no kernel the forward-only size is still reported)
-      if (!plan_passes(x->k, gp, nlines, naxis, true, &pg)) bytes = std::max(bytes, carve_single(nullptr, pg, x->nb, true).bytes);
+      if (!plan_passes(x->k, gp, nlines, naxis, true, &pg, false, mm)) bytes = std::max(bytes, carve_single(nullptr, pg, x->nb, true).bytes);
       return bytes;
     }
     case CAFEQ_CALL_DUAL_PROXY_LOSS: {
@@ -549,10 +587,13 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
       GroupPlan ga, gb;
       if (resolve_group(cfg, a->cols, x->k, &ga) || resolve_group(cfg, b->rows, x->k, &gb)) return 0;
       PassPlans qa, qb, na, nbp;
-      if (plan_passes(x->k, ga, a->rows, a->cols, false, &na) || plan_passes(x->k, gb, b->cols, b->rows, false, &nbp))
+      const bool mm = is_minmax(cfg);
+      if (plan_passes(x->k, ga, a->rows, a->cols, false, &na, false, mm) ||
+          plan_passes(x->k, gb, b->cols, b->rows, false, &nbp, false, mm))
         return 0;
       size_t bytes = carve_dual(nullptr, na, nbp, x->nb, false).bytes;
-      if (!plan_passes(x->k, ga, a->rows, a->cols, true, &qa) && !plan_passes(x->k, gb, b->cols, b->rows, true, &qb))
+      if (!plan_passes(x->k, ga, a->rows, a->cols, true, &qa, false, mm) &&
+          !plan_passes(x->k, gb, b->cols, b->rows, true, &qb, false, mm))
         bytes = std::max(bytes, carve_dual(nullptr, qa, qb, x->nb, true).bytes);
       return bytes;
     }
@@ -699,7 +740,7 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
                              void* stream) {
   int rc = check_mat(W);
   if (rc) return rc;
-  rc = check_cfg(cfg, true);
+  rc = check_cfg(cfg, true, true);
   if (rc) return rc;
   rc = check_xform(x, true);
   if (rc) return rc;
@@ -716,9 +757,10 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   rc = resolve_group(cfg, naxis, K, &gp);
   if (rc) return rc;
   const bool grad = gradT != nullptr;
-  const bool v2 = v2_eligible(W, K, gp, cfg->bits);
+  const bool asym = is_minmax(cfg);
+  const bool v2 = v2_eligible(W, K, gp, cfg);
   PassPlans pp;
-  rc = plan_passes(K, gp, nlines, naxis, grad, &pp, v2);
+  rc = plan_passes(K, gp, nlines, naxis, grad, &pp, v2, asym);
   if (rc) return rc;
   const CorePlan& pl = pp.first;
   {
@@ -727,9 +769,9 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
   SingleWs w = carve_single(ws, pp, nb, grad);
-  const QGrid grid = make_grid(cfg->bits);
-  const float beta = 1.f / (4.f * grid.qmax * grid.qmax);
-  const bool f16 = core_forward_f16(K, gp.Gk, cfg->bits);
+  const QGrid grid = grid_for(cfg);
+  const float beta = beta_for(cfg, grid);
+  const bool f16 = !asym && core_forward_f16(K, gp.Gk, cfg->bits);
 
   // rho per axis index, its sums per segment-level group (the loss sweep) and per group (the gradient pass)
   if ((rc = launch_rho(x->Tinv, K, nb, col ? 1 : 0, w.rho, st))) return rc;
@@ -748,7 +790,10 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   p.Afwd = w.m.pfwd; p.Ainv = w.m.pinv; p.fscale = f16 ? w.m.fs : nullptr; p.fscale_inv = v2 ? w.m.fsi : nullptr;
   p.grid = grid; p.do_inverse = 1; p.do_grad = pp.fused ? 1 : 0; p.loss_kind = kLossSur; p.beta = beta;
   p.rG = w.m.rG; p.codes = codes; p.scales = scales; p.slot_grad = w.m.slot_grad; p.slot_hdr = w.slot_hdr;
-  if ((rc = run_core(K, cfg->axis, gp, p, w.m.rec, w.m.grec, pp.two, st, v2 ? W : nullptr))) return rc;
+  p.asym = asym ? 1 : 0;
+  p.mins = asym && scales ? scales + nlines * (naxis / gp.G) : nullptr;   // the minima follow the scales
+  if ((rc = run_core(K, cfg->axis, gp, p, w.m.rec, w.m.grec, pp.two, st, v2 ? W : nullptr, w.m.rec_mm, w.m.grec_mm)))
+    return rc;
   if ((rc = launch_reduce_losses(kLossSur, w.slot_hdr, int(pl.nslot), nullptr, 0, beta, 0.f, 0, losses,
                                  w.lse_ms, st)))
     return rc;
@@ -775,7 +820,7 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   if (rc) return rc;
   rc = check_mat(B);
   if (rc) return rc;
-  rc = check_cfg(cfg, false);
+  rc = check_cfg(cfg, false, true);
   if (rc) return rc;
   rc = check_xform(x, true);
   if (rc) return rc;
@@ -788,10 +833,11 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   if ((rc = resolve_group(cfg, A->cols, K, &ga))) return rc;
   if ((rc = resolve_group(cfg, B->rows, K, &gb))) return rc;
   const bool grad = gradT != nullptr;
-  const bool v2A = v2_eligible(A, K, ga, cfg->bits), v2B = v2_eligible(B, K, gb, cfg->bits);
+  const bool asym = is_minmax(cfg);
+  const bool v2A = v2_eligible(A, K, ga, cfg), v2B = v2_eligible(B, K, gb, cfg);
   PassPlans qa, qb;
-  if ((rc = plan_passes(K, ga, A->rows, A->cols, grad, &qa, v2A))) return rc;
-  if ((rc = plan_passes(K, gb, B->cols, B->rows, grad, &qb, v2B))) return rc;
+  if ((rc = plan_passes(K, ga, A->rows, A->cols, grad, &qa, v2A, asym))) return rc;
+  if ((rc = plan_passes(K, gb, B->cols, B->rows, grad, &qb, v2B, asym))) return rc;
   const CorePlan &pa = qa.first, &pb = qb.first;
   {
     const size_t la = core_lds_bytes(K, ga.Gk, qa.fused), lb = core_lds_bytes(K, gb.Gk, qb.fused);
@@ -799,9 +845,9 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
   DualWs w = carve_dual(ws, qa, qb, nb, grad);
-  const QGrid grid = make_grid(cfg->bits);
+  const QGrid grid = grid_for(cfg);
   // the gradient-free pass over 128 x 128 blocks (one block per segment) takes half-precision forward operands
-  const bool f16A = core_forward_f16(K, ga.Gk, cfg->bits), f16B = core_forward_f16(K, gb.Gk, cfg->bits);
+  const bool f16A = !asym && core_forward_f16(K, ga.Gk, cfg->bits), f16B = !asym && core_forward_f16(K, gb.Gk, cfg->bits);
 
   {
     const SplitRequest req[4] = {{x->T, w.a.pfwd, 1, kFwdPlanes, f16A ? w.a.fs : nullptr, v2A ? 1 : 0, v2A ? 4 : 14},
@@ -820,7 +866,10 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   a.grid = grid; a.do_inverse = 1; a.do_grad = qa.fused ? 1 : 0; a.loss_kind = kLossLse; a.lse_t = lse_t;
   a.codes = codesU; a.scales = scalesU; a.slot_grad = w.a.slot_grad; a.slot_hdr = w.hdrA;
   a.fscale = f16A ? w.a.fs : nullptr; a.fscale_inv = v2A ? w.a.fsi : nullptr;
-  if ((rc = run_core(K, CAFEQ_AXIS_COL, ga, a, w.a.rec, w.a.grec, qa.two, st, v2A ? A : nullptr))) return rc;
+  a.asym = asym ? 1 : 0;
+  a.mins = asym && scalesU ? scalesU + A->rows * (A->cols / ga.G) : nullptr;   // the minima follow the scales
+  if ((rc = run_core(K, CAFEQ_AXIS_COL, ga, a, w.a.rec, w.a.grec, qa.two, st, v2A ? A : nullptr, w.a.rec_mm, w.a.grec_mm)))
+    return rc;
   ag = a;
   if (qa.two && (rc = run_grad_pass(K, CAFEQ_AXIS_COL, A, 1, qa, w.a, kLossLse, 0.f, lse_t, w.hdrA, int(pa.nslot),
                                     w.member_ref, &ag, st)))
@@ -832,7 +881,10 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   b.grid = grid; b.do_inverse = 1; b.do_grad = qb.fused ? 1 : 0; b.loss_kind = kLossLse; b.lse_t = lse_t;
   b.codes = codesV; b.scales = scalesV; b.slot_grad = w.b.slot_grad; b.slot_hdr = w.hdrB;
   b.fscale = f16B ? w.b.fs : nullptr; b.fscale_inv = v2B ? w.b.fsi : nullptr;
-  if ((rc = run_core(K, CAFEQ_AXIS_ROW, gb, b, w.b.rec, w.b.grec, qb.two, st, v2B ? B : nullptr))) return rc;
+  b.asym = asym ? 1 : 0;
+  b.mins = asym && scalesV ? scalesV + (B->rows / gb.G) * B->cols : nullptr;
+  if ((rc = run_core(K, CAFEQ_AXIS_ROW, gb, b, w.b.rec, w.b.grec, qb.two, st, v2B ? B : nullptr, w.b.rec_mm, w.b.grec_mm)))
+    return rc;
   bg = b;
   if (qb.two && (rc = run_grad_pass(K, CAFEQ_AXIS_ROW, B, x->rep, qb, w.b, kLossLse, 0.f, lse_t, w.hdrB, int(pb.nslot),
                                     w.member_ref + 1, &bg, st)))

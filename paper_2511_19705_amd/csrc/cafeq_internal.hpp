@@ -36,12 +36,18 @@ int launch_core_k32(int G, int axis, const CoreParams& p, hipStream_t st);
 int launch_core_k64(int G, int axis, const CoreParams& p, hipStream_t st);
 int launch_core_k128(int G, int axis, const CoreParams& p, hipStream_t st);
 int launch_core_k256(int G, int axis, const CoreParams& p, hipStream_t st);
+// the same on the min/max grid of Eq. (1) (p.asym; gradient-free variants)
+int launch_core_asym_k32(int G, int axis, const CoreParams& p, hipStream_t st);
+int launch_core_asym_k64(int G, int axis, const CoreParams& p, hipStream_t st);
+int launch_core_asym_k128(int G, int axis, const CoreParams& p, hipStream_t st);
+int launch_core_asym_k256(int G, int axis, const CoreParams& p, hipStream_t st);
 // gradient pass of the two-pass scheme (grad_core.hpp): any block size, p.grp = group length
 int launch_grad_pass(int K, int axis, const CoreParams& p, hipStream_t st);
 size_t grad_pass_part_floats(int K);
-// records of the segments of every group -> one record per group (groups spanning gspan segments of L)
+// records of the segments of every group -> one record per group (groups spanning gspan segments of L);
+// rec_mm / grec_mm (may be null): the segments' (min, max) pairs and their combination
 int launch_combine_records(const float2* rec, int gspan, int L, int64_t nlines, int64_t ngroups, float2* grec,
-                           hipStream_t st);
+                           hipStream_t st, const float2* rec_mm = nullptr, float2* grec_mm = nullptr);
 // LDS bytes the core needs (0 if the gradient accumulator cannot fit with do_grad)
 size_t core_lds_bytes(int K, int G, bool do_grad);
 size_t core_lds_bytes_k32(int G, bool do_grad);

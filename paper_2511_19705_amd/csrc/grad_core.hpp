@@ -307,7 +307,9 @@ __global__ __launch_bounds__(kThreads, K == 256 ? 1 : 2) void grad_z_kernel(cons
 // (group, line); rec is [segment][line] (one group per segment in that sweep).
 __global__ __launch_bounds__(256) void combine_records_kernel(const float2* __restrict__ rec, int gspan, int L,
                                                                int64_t nlines, int64_t ngroups,
-                                                               float2* __restrict__ grec) {
+                                                               float2* __restrict__ grec,
+                                                               const float2* __restrict__ rec_mm,
+                                                               float2* __restrict__ grec_mm) {
   const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
   if (i >= ngroups * nlines) return;
   const int64_t gi = i / nlines, line = i - gi * nlines;
@@ -318,6 +320,15 @@ __global__ __launch_bounds__(256) void combine_records_kernel(const float2* __re
     if (fabsf(r.x) > fabsf(best.x)) { best = r; bs = s; }
   }
   grec[i] = make_float2(best.x, __int_as_float(bs * L + __float_as_int(best.y)));
+  if (rec_mm) {
+    float2 mm = rec_mm[(gi * gspan) * nlines + line];
+    for (int s = 1; s < gspan; ++s) {
+      const float2 r = rec_mm[(gi * gspan + s) * nlines + line];
+      mm.x = fminf(mm.x, r.x);
+      mm.y = fmaxf(mm.y, r.y);
+    }
+    grec_mm[i] = mm;
+  }
 }
 
 }  // namespace cafeq

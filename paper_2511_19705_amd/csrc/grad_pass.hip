@@ -46,10 +46,10 @@ int launch_grad_pass(int K, int axis, const CoreParams& p, hipStream_t st) {
 }
 
 int launch_combine_records(const float2* rec, int gspan, int L, int64_t nlines, int64_t ngroups, float2* grec,
-                           hipStream_t st) {
+                           hipStream_t st, const float2* rec_mm, float2* grec_mm) {
   const int64_t n = ngroups * nlines;
   hipLaunchKernelGGL(combine_records_kernel, dim3(unsigned((n + 255) / 256)), dim3(256), 0, st, rec, gspan, L, nlines,
-                     ngroups, grec);
+                     ngroups, grec, rec_mm, grec_mm);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }

@@ -1,0 +1,5 @@
+// Instantiations of the fused transform core on the min/max grid of Eq. (1) for 256 x 256 transform blocks.
+#include "xform_launch.hpp"
+namespace cafeq {
+int launch_core_asym_k256(int G, int axis, const CoreParams& p, hipStream_t st) { return launch_core_asym_k<256>(G, axis, p, st); }
+}  // namespace cafeq

@@ -136,6 +136,14 @@ struct CoreParams {
   const float* prep_lscale;
   const float* prep_wsq;
   const float* fscale_inv;  // per-block factor of the float16 inverse operand planes
+  // The min/max grid of Eq. (1) (ASYM kernel variant): grid.qmax = 2^b - 1 levels, grid.qmin = 0; the scale
+  // comes from the group's range, codes count from its minimum.  The surrogate and the arg-max records stay on
+  // the group absmax.  mins: like scales (may be null).  Long groups: the record sweep also writes every
+  // segment's (min, max), combined per group into grec_mm.
+  int asym;                 // run the ASYM variant
+  float* mins;
+  float2* rec_mm;           // [nseg][nlines] (record sweep of the long-group variant)
+  const float2* grec_mm;    // [groups][nlines] (loss sweep with gspan > 1)
 };
 
 __device__ __forceinline__ int64_t chunk_begin(int64_t w, int64_t n_mt, int64_t nwg) {
@@ -253,9 +261,12 @@ __device__ __forceinline__ void load_strip(const CoreParams& p, float (&wreg)[L 
 // them.  The inverse transform keeps the bfloat16 parts.
 // LONGG: the variant for groups that span several segments (CoreParams::gspan; one group per segment inside
 // the kernel): its record-only sweep and its loss sweep with the group's absmax taken from the combined records.
-template <int K, int G, int AXIS, bool GRAD, bool F16 = false, bool LONGG = false>
+// ASYM: the min/max grid of Eq. (1) instead of the symmetric absmax grid (gradient-free variants only: the
+// gradient of the surrogate depends on the grid through a constant alone and runs from the records).
+template <int K, int G, int AXIS, bool GRAD, bool F16 = false, bool LONGG = false, bool ASYM = false>
 __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) void xform_core_kernel(const CoreParams p) {
   static_assert(!F16 || (!GRAD && Geo<K, G>::NBLK == 1), "half-precision forward: gradient-free, one block per segment");
+  static_assert(!ASYM || (!GRAD && !F16), "min/max grid: gradient-free, full-precision forward");
   static_assert(!LONGG || (!GRAD && Geo<K, G>::NGRP == 1), "long groups: gradient-free, one group per segment");
   using g = Geo<K, G>;
   constexpr bool GRAD_ON = GRAD && g::GRAD_OK;
@@ -606,28 +617,50 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
         const int oj = __shfl_xor(j, 32);
         const float oa = fabsf(oz);
         if (oa > a || (oa == a && oj < j)) { a = oa; zs = oz; j = oj; }
-        if (p.rec && valid && h == 0)   // index relative to the group's first element
+        float mn = 0.f, mx = 0.f;   // ASYM: the group's minimum and maximum
+        if constexpr (ASYM) {
+          mn = mx = acc[(gi * RPG) / 16][(gi * RPG) % 16];
+#pragma unroll
+          for (int f = gi * RPG + 1; f < (gi + 1) * RPG; ++f) {
+            mn = fminf(mn, acc[f / 16][f % 16]);
+            mx = fmaxf(mx, acc[f / 16][f % 16]);
+          }
+          mn = fminf(mn, __shfl_xor(mn, 32));
+          mx = fmaxf(mx, __shfl_xor(mx, 32));
+        }
+        if (p.rec && valid && h == 0) {   // index relative to the group's first element
           p.rec[(int64_t(seg) * NGRP + gi) * p.nlines + line] = make_float2(zs, __int_as_float(j - gi * G));
+          if constexpr (ASYM && LONGG) if (p.rec_mm) p.rec_mm[int64_t(seg) * p.nlines + line] = make_float2(mn, mx);
+        }
         if constexpr (LONGG) if (big) {
           // the group's absmax comes from the combined records (NGRP == 1 here)
-          const float2 r = p.grec[int64_t(seg / p.gspan) * p.nlines + (valid ? line : p.nlines - 1)];
+          const int64_t at = int64_t(seg / p.gspan) * p.nlines + (valid ? line : p.nlines - 1);
+          const float2 r = p.grec[at];
           zs = valid ? r.x : 0.f;
           a = fabsf(zs);
+          if constexpr (ASYM) {
+            const float2 mm = p.grec_mm[at];
+            mn = valid ? mm.x : 0.f;
+            mx = valid ? mm.y : 0.f;
+          }
         }
         gz[gi] = zs; gj[gi] = j;
         if constexpr (LONGG) if (!(p.codes || p.scales || p.do_inverse)) continue;   // record-only sweep
-        const float inv = grid_inv(a, p.grid.qmax);
-        const float s = grid_scale(a, p.grid.qmax);
+        // symmetric grid: steps of absmax / qmax around zero; Eq. (1): steps of (max - min) / levels from min
+        const float span = ASYM ? mx - mn : a;
+        const float inv = grid_inv(span, p.grid.qmax);
+        const float s = grid_scale(span, p.grid.qmax);
         if (p.scales && valid && h == 0 && first_of_group) {
+          int64_t at;
           if (big) {
             const int64_t gidx = seg / p.gspan, ng = p.nseg / p.gspan;
-            if (AXIS == CAFEQ_AXIS_COL) p.scales[line * ng + gidx] = s;
-            else p.scales[gidx * p.cols + line] = s;
+            at = AXIS == CAFEQ_AXIS_COL ? line * ng + gidx : gidx * p.cols + line;
           } else {
             const int64_t gidx = ax0 / G + gi;   // group index along the axis
-            if (AXIS == CAFEQ_AXIS_COL) p.scales[line * (p.cols / G) + gidx] = s;
-            else p.scales[gidx * p.cols + line] = s;
+            at = AXIS == CAFEQ_AXIS_COL ? line * (p.cols / G) + gidx : gidx * p.cols + line;
           }
+          p.scales[at] = s;
+          if constexpr (ASYM) if (p.mins) p.mins[at] = mn;
         }
 #pragma unroll
         for (int f4 = gi * RPG / 4; f4 < (gi + 1) * RPG / 4; ++f4) {
@@ -636,8 +669,14 @@ __global__ __launch_bounds__(kThreads, (!GRAD && Geo<K, G>::L <= 128) ? 2 : 1) v
           for (int e = 0; e < 4; ++e) {
             const int f = 4 * f4 + e;
             const float z = acc[f / 16][f % 16];
-            q[e] = grid_code(z, inv, p.grid);
-            const float er = __fmul_rn(q[e], s) - z;
+            float er;
+            if constexpr (ASYM) {
+              q[e] = grid_code(z - mn, inv, p.grid);
+              er = __fadd_rn(__fmul_rn(q[e], s), mn) - z;
+            } else {
+              q[e] = grid_code(z, inv, p.grid);
+              er = __fmul_rn(q[e], s) - z;
+            }
             s_errz = fmaf(er, er, s_errz);
             err[f] = er;
           }

@@ -18,9 +18,9 @@ constexpr size_t core_lds_bytes_t(bool do_grad) {
 template <int K, int G>
 constexpr bool core_has_f16() { return K == 128 && Geo<K, G>::NBLK == 1; }
 
-template <int K, int G, int AXIS, bool GRAD, bool F16 = false, bool LONGG = false>
+template <int K, int G, int AXIS, bool GRAD, bool F16 = false, bool LONGG = false, bool ASYM = false>
 int launch_core_v(const CoreParams& p, size_t lds, hipStream_t st) {
-  auto kern = xform_core_kernel<K, G, AXIS, GRAD, F16, LONGG>;
+  auto kern = xform_core_kernel<K, G, AXIS, GRAD, F16, LONGG, ASYM>;
   static std::atomic<bool> attr_set{false};   // per instantiation
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -66,6 +66,39 @@ int launch_core_k(int G, int axis, const CoreParams& p, hipStream_t st) {
   case GG:                                                                            \
     return axis == CAFEQ_AXIS_COL ? launch_core_t<K, GG, CAFEQ_AXIS_COL>(p, st)       \
                                   : launch_core_t<K, GG, CAFEQ_AXIS_ROW>(p, st);
+  switch (G) {
+    CAFEQ_CORE_CASE(32)
+    CAFEQ_CORE_CASE(64)
+    CAFEQ_CORE_CASE(128)
+    CAFEQ_CORE_CASE(256)
+    default: return CAFEQ_ERR_UNSUPPORTED;
+  }
+#undef CAFEQ_CORE_CASE
+}
+
+// The variants for the min/max grid of Eq. (1) (instantiated in translation units of their own): gradient-free,
+// full-precision forward, with and without groups that span segments.
+template <int K, int G, int AXIS>
+int launch_core_asym_t(const CoreParams& p, hipStream_t st) {
+  const size_t lds = core_lds_bytes_t<K, G>(false);
+  if (lds == 0 || lds > kMaxLds) return CAFEQ_ERR_UNSUPPORTED;
+  if (p.do_grad || p.fscale) return CAFEQ_ERR_INVALID_ARG;
+  if (p.longg) {
+    if constexpr (G >= K && (G == K || G == 128)) {
+      return launch_core_v<K, G, AXIS, false, false, true, true>(p, lds, st);
+    } else {
+      return CAFEQ_ERR_UNSUPPORTED;
+    }
+  }
+  return launch_core_v<K, G, AXIS, false, false, false, true>(p, lds, st);
+}
+
+template <int K>
+int launch_core_asym_k(int G, int axis, const CoreParams& p, hipStream_t st) {
+#define CAFEQ_CORE_CASE(GG)                                                                \
+  case GG:                                                                                 \
+    return axis == CAFEQ_AXIS_COL ? launch_core_asym_t<K, GG, CAFEQ_AXIS_COL>(p, st)       \
+                                  : launch_core_asym_t<K, GG, CAFEQ_AXIS_ROW>(p, st);
   switch (G) {
     CAFEQ_CORE_CASE(32)
     CAFEQ_CORE_CASE(64)

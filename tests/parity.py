@@ -99,3 +99,27 @@ def check_grad_with_slack(g_gpu, g_ref, slack, rel=REL):
     assert np.all(err <= rel * np.abs(g_ref).max() + slack), \
         "gradient max error %g vs scale %g (beyond the arg-max slack)" % (err.max(), np.abs(g_ref).max())
     assert np.linalg.norm(err) <= rel * np.linalg.norm(g_ref) + np.linalg.norm(slack)
+
+
+def check_codes_minmax(codes_gpu, codes_ref, z_ref, scales_ref, mins_ref, axis, group, tie_tol=2e-4):
+    """The same rule on the min/max grid of Eq. (1): codes count steps of the group's scale from its minimum."""
+    diff = codes_gpu.astype(np.int32) != codes_ref.astype(np.int32)
+    n_bad = int(diff.sum())
+    allowed = max(1, int(np.ceil(CODE_FRAC * codes_ref.size)))
+    assert n_bad <= allowed, "%d of %d codes differ (allowed %d)" % (n_bad, codes_ref.size, allowed)
+    if n_bad:
+        d = np.abs(codes_gpu.astype(np.int32) - codes_ref.astype(np.int32))[diff]
+        assert d.max() == 1, "a code differs by more than one level"
+        g = group if group else (z_ref.shape[1] if axis == 0 else z_ref.shape[0])
+        s_el = np.repeat(scales_ref.astype(np.float64), g, axis=1 if axis == 0 else 0)
+        lo_el = np.repeat(mins_ref.astype(np.float64), g, axis=1 if axis == 0 else 0)
+        x = (z_ref[diff] - lo_el[diff]) / s_el[diff]
+        assert np.all(np.abs(x - np.floor(x) - 0.5) < tie_tol), "a differing code is not at a rounding tie"
+    print("codes differing from the oracle: %d of %d (%.2e)" % (n_bad, codes_ref.size, n_bad / codes_ref.size))
+    return n_bad
+
+
+def check_mins(m_gpu, m_ref, scales_ref, levels, rtol=5e-6):
+    """Group minima are transformed values themselves: compared relative to the group's range."""
+    rng = scales_ref.astype(np.float64) * levels
+    assert np.all(np.abs(m_gpu.astype(np.float64) - m_ref) <= rtol * rng + 1e-30)

@@ -54,11 +54,14 @@ def test_lse_literal_formula_bounds_and_limit():
     assert abs(big - mx) < 1e-3
 
 
-def test_dual_errors_are_dense_definitions():
+@pytest.mark.parametrize("mode", [O.SYM, O.ASYM])
+def test_dual_errors_are_dense_definitions(mode):
     A, B, T = WL.small_pair(7, 16, 8, 2, 35, eps=0.2)
     T = T.astype(np.float64)
     P = O.block_inverse(T)
-    out = O.dual_lse(A, B, T, P, 3, 8, 2, 5.0, arith="f64", want_grad=False)
+    out = O.dual_lse(A, B, T, P, 3, 8, 2, 5.0, arith="f64", want_grad=False, mode=mode)
+    sym_lse = O.dual_lse(A, B, T, P, 3, 8, 2, 5.0, arith="f64", want_grad=False)["lse"]
+    assert out["lse"] == sym_lse          # a function of the group maxima alone
 
     def dense(X, rep):
         nb, k, _ = X.shape
@@ -68,8 +71,21 @@ def test_dual_errors_are_dense_definitions():
         return M
     U = A.astype(np.float64) @ dense(T, 1)
     V = dense(P, 2) @ B.astype(np.float64)
-    Uh = O.rtn_sym(U, 3, 8, O.COL, "f64")[2]
-    Vh = O.rtn_sym(V, 3, 8, O.ROW, "f64")[2]
+    if mode == O.SYM:
+        Uh = O.rtn_sym(U, 3, 8, O.COL, "f64")[2]
+        Vh = O.rtn_sym(V, 3, 8, O.ROW, "f64")[2]
+    else:
+        # Eq. (1) with explicit loops over the groups
+        def eq1(X):
+            out_ = np.empty_like(X)
+            for i in range(X.shape[0]):
+                for g0 in range(0, X.shape[1], 8):
+                    x = X[i, g0:g0 + 8]
+                    s_ = (x.max() - x.min()) / 7.0
+                    out_[i, g0:g0 + 8] = s_ * np.rint((x - x.min()) / s_) + x.min()
+            return out_
+        Uh = eq1(U)
+        Vh = eq1(V.T).T
     np.testing.assert_allclose(out["errU_sq"], ((Uh - U) ** 2).sum(), rtol=1e-12)
     np.testing.assert_allclose(out["errV_sq"], ((Vh - V) ** 2).sum(), rtol=1e-12)
     np.testing.assert_allclose(out["l2A_sq"], ((Uh @ dense(P, 1) - A) ** 2).sum(), rtol=1e-10)
