@@ -201,8 +201,11 @@ int cafeq_apply_transform(const cafeq_mat* W, const cafeq_xform* x, int axis, in
                           float* Z, void* ws, void* stream);
 
 /* Prepared weights (see cafeq_mat::prepared).  cafeq_prepared_bytes: size of the buffer for W transformed
- * along `axis` (0 if the axis length is not a multiple of 128); about rows * cols * 4 bytes whatever the
- * storage type.  cafeq_prepare_weights fills it (device memory, 256-byte aligned, owned by the caller):
+ * along `axis` (0 if the axis length is not a multiple of 128); about rows * cols * 8 bytes whatever the
+ * storage type: one copy in the order the loss pass contracts (over the axis), one in the order the gradient
+ * pass contracts (over the lines; bfloat16 hi + mid parts, tiles of 128 lines x 128 axis indices; read by the
+ * gradient pass for blocks of 128 whatever the group and grid).
+ * cafeq_prepare_weights fills it (device memory, 256-byte aligned, owned by the caller).  The loss pass's copy:
  * per tile of 32 lines x 128 axis indices two float16 parts of every element -- the line's segment scaled
  * by a power of two so that its largest magnitude lies in [2^3, 2^4), hi = fl16(y), lo = fl16(y - hi):
  * 22 significant bits -- in the order the loss kernel's matrix instructions read them, the per-line

@@ -98,6 +98,14 @@ int make_grad_plan(int K, int64_t nlines, int64_t naxis, CorePlan* pl) {
   pl->n_mt = pl->mt_per_seg * pl->nseg;
   int64_t nwg = std::min<int64_t>(pl->n_mt, int64_t(device_cu_count()) * (K == 256 ? 1 : 2));
   if (nwg > 8) nwg -= nwg % 8;
+  // A whole number of workgroups per chunk, where the longest range gets no longer by it: no range then
+  // straddles two chunks (one partial per workgroup instead of up to two) and all ranges are equal.
+  {
+    const int64_t per = nwg / pl->nseg;
+    if (per >= 1 && pl->mt_per_seg % per == 0 && pl->mt_per_seg / per <= (pl->n_mt + nwg - 1) / nwg &&
+        (per * pl->nseg) % 8 == 0)
+      nwg = per * pl->nseg;
+  }
   pl->nwg = int(nwg);
   pl->nslot = pl->nwg + pl->nseg;
   pl->slot_grad_floats = grad_pass_part_floats(K);
@@ -318,6 +326,7 @@ void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep)
   p->fscale = nullptr;
   p->longg = 0; p->gspan = 1; p->grec = nullptr; p->grp = 0;
   p->prep_planes = nullptr; p->prep_lscale = nullptr; p->prep_wsq = nullptr; p->fscale_inv = nullptr;
+  p->prep_gtiles = nullptr;
   p->asym = 0; p->mins = nullptr; p->rec_mm = nullptr; p->grec_mm = nullptr;
   p->grid = make_grid(4);
 }
@@ -368,6 +377,13 @@ int run_grad_pass(int K, int axis, const cafeq_mat* W, int rep, const PassPlans&
   pg->loss_kind = loss_kind; pg->beta = beta; pg->lse_t = lse_t;
   pg->rG = m.rGreal; pg->slot_grad = m.slot_grad; pg->rec = m.grec; pg->grp = pp.gp.G;
   pg->hdr_ref = hdr_ref; pg->nslot_ref = nslot_ref; pg->member_ref = member_ref;
+  if (W->prepared && K == 128) {
+    // the prepared copy also holds the weights in the operand order of this contraction
+    const bool col = axis == CAFEQ_AXIS_COL;
+    const PreparedLayout l = prepared_layout(col ? W->rows : W->cols, col ? W->cols : W->rows);
+    pg->prep_gtiles = static_cast<const unsigned char*>(W->prepared) + l.off_gtiles;
+    return launch_grad_v2(*pg, st);
+  }
   return launch_grad_pass(K, axis, *pg, st);
 }
 

@@ -57,9 +57,14 @@ size_t core_lds_bytes_k256(int G, bool do_grad);
 int device_cu_count();
 
 // loss_v2.hip: loss pass over prepared weights (128 x 128 blocks, groups up to 128)
-struct PreparedLayout { int64_t nlp, nseg, ntiles; size_t off_lscale, off_planes, off_partial, bytes; };
+// header (||W||^2), per-line factors, the loss pass's tiles, their partial sums, the gradient pass's tiles
+struct PreparedLayout { int64_t nlp, nseg, ntiles; size_t off_lscale, off_planes, off_partial, off_gtiles, bytes; };
 PreparedLayout prepared_layout(int64_t nlines, int64_t naxis);
 int launch_prepare(const cafeq_mat* W, int axis, void* prepared, hipStream_t st);
+// gradient pass over prepared weights (blocks of 128; grad_v2.hip): p.prep_gtiles, p.rec, p.grp as launch_grad_pass
+size_t prepared_gtiles_bytes(int64_t nlines, int64_t naxis);
+int launch_prepare_gtiles(const cafeq_mat* W, int axis, unsigned char* gtiles, hipStream_t st);
+int launch_grad_v2(const CoreParams& p, hipStream_t st);
 int launch_loss_v2(int G, int axis, const CoreParams& p, hipStream_t st);
 int launch_loss_prepared(int G, int axis, const CoreParams& p, hipStream_t st);   // ... with the caller's timing events
 

@@ -522,7 +522,8 @@ PreparedLayout prepared_layout(int64_t nlines, int64_t naxis) {
   l.off_lscale = 256;
   l.off_planes = align_up(l.off_lscale + size_t(l.nseg) * l.nlp * sizeof(float), 256);
   l.off_partial = l.off_planes + size_t(l.ntiles) * kV2TileBytes;
-  l.bytes = align_up(l.off_partial + size_t(l.ntiles) * sizeof(double), 256);
+  l.off_gtiles = align_up(l.off_partial + size_t(l.ntiles) * sizeof(double), 256);
+  l.bytes = align_up(l.off_gtiles + prepared_gtiles_bytes(nlines, naxis), 256);
   return l;
 }
 
@@ -541,7 +542,7 @@ int launch_prepare(const cafeq_mat* W, int axis, void* prepared, hipStream_t st)
   CAFEQ_CHECK_LAUNCH();
   hipLaunchKernelGGL(prepare_sum_kernel, dim3(1), dim3(256), 0, st, a.partial, l.ntiles, reinterpret_cast<float*>(base));
   CAFEQ_CHECK_LAUNCH();
-  return CAFEQ_OK;
+  return launch_prepare_gtiles(W, axis, base + l.off_gtiles, st);
 }
 
 int launch_loss_v2(int G, int axis, const CoreParams& p, hipStream_t st) {

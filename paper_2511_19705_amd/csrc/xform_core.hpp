@@ -136,6 +136,8 @@ struct CoreParams {
   const float* prep_lscale;
   const float* prep_wsq;
   const float* fscale_inv;  // per-block factor of the float16 inverse operand planes
+  // gradient pass over prepared weights (grad_v2.hip): tiles of 128 lines x 128 inputs in operand order
+  const unsigned char* prep_gtiles;
   // The min/max grid of Eq. (1) (ASYM kernel variant): grid.qmax = 2^b - 1 levels, grid.qmin = 0; the scale
   // comes from the group's range, codes count from its minimum.  The surrogate and the arg-max records stay on
   // the group absmax.  mins: like scales (may be null).  Long groups: the record sweep also writes every

@@ -196,17 +196,20 @@ def test_config5_gate_sampled(env):
         parity.check_grad(g[b:b + 1], g_ref)
 
 
-def test_config5_mlp_pair_sampled(env):
-    """down 4608 x 36864 (T on its columns) with up 36864 x 4608 (T^-1 on its rows), 288 blocks."""
+@pytest.mark.parametrize("bits,prepared", [(3, False), (4, False), (3, True)])
+def test_config5_mlp_pair_sampled(env, bits, prepared):
+    """down 4608 x 36864 (T on its columns) with up 36864 x 4608 (T^-1 on its rows), 288 blocks; both bit
+    widths of the layer protocol, and the loss pass over prepared weights."""
     torch, cafeq = env
-    bits, group, k, t_lse = 3, 128, 128, 5.0
+    group, k, t_lse = 128, 128, 5.0
     ta, tb = WL.config5_tensor("down"), WL.config5_tensor("up")
     T = WL.config5_transform("mlp")
     P64 = O.block_inverse(T)
     P = P64.astype(np.float32)
-    losses, grad, outs = cafeq.dual_proxy_loss_fwd_bwd(_dev_bf16(torch, ta["bits16"]), _dev_bf16(torch, tb["bits16"]),
-                                                       _dev(torch, T), _dev(torch, P), bits, group, 1, t_lse,
-                                                       True, True)
+    Ad, Bd = _dev_bf16(torch, ta["bits16"]), _dev_bf16(torch, tb["bits16"])
+    prep = (cafeq.prepare_weights(Ad, cafeq.AXIS_COL), cafeq.prepare_weights(Bd, cafeq.AXIS_ROW)) if prepared else (None, None)
+    losses, grad, outs = cafeq.dual_proxy_loss_fwd_bwd(Ad, Bd, _dev(torch, T), _dev(torch, P), bits, group, 1, t_lse,
+                                                       True, True, prepared=prep)
     torch.cuda.synchronize()
     losses = losses.cpu().numpy().astype(np.float64)
     cu, su, cv, sv = outs
@@ -245,6 +248,32 @@ def test_config5_mlp_pair_sampled(env):
         ref = O.dual_lse(Ab, Bb, T[b:b + 1], P[b:b + 1], bits, group, 1, t_lse)
         g_ref = ref["gradT"] * np.exp(t_lse * (ref["lse"] - lse))
         parity.check_grad(g[b:b + 1], g_ref)
+
+
+def test_config5_vo_pair_3bit_full_oracle(env):
+    """The same pair at the layer protocol's other bit width: paired losses, gradient and codes."""
+    torch, cafeq = env
+    bits, group, rep = 3, 128, 2
+    ta, tb = WL.config5_tensor("v"), WL.config5_tensor("o")
+    A, B = WL.bf16_bits_to_f32(ta["bits16"]), WL.bf16_bits_to_f32(tb["bits16"])
+    T = WL.config5_transform("vo")
+    P = O.block_inverse(T).astype(np.float32)
+    losses, grad, outs = cafeq.dual_proxy_loss_fwd_bwd(_dev_bf16(torch, ta["bits16"]), _dev_bf16(torch, tb["bits16"]),
+                                                       _dev(torch, T), _dev(torch, P), bits, group, rep, 5.0,
+                                                       True, True)
+    torch.cuda.synchronize()
+    losses = losses.cpu().numpy().astype(np.float64)
+    ref = O.dual_lse(A, B, T, P, bits, group, rep, 5.0)
+    for i, name in enumerate(("errU_sq", "errV_sq", "l2A_sq", "l2B_sq", "lse")):
+        parity.check_scalar(losses[i], ref[name], what=name)
+    parity.check_grad(grad.cpu().numpy(), ref["gradT"])
+    cu, su, cv, sv = [x.cpu().numpy() for x in outs]
+    cu_ref, su_ref, _ = O.rtn_sym(ref["U"], bits, group, O.COL)
+    cv_ref, sv_ref, _ = O.rtn_sym(ref["V"], bits, group, O.ROW)
+    parity.check_scales(su, su_ref)
+    parity.check_scales(sv, sv_ref)
+    parity.check_codes(cu, cu_ref, ref["U"], su_ref, O.COL, group)
+    parity.check_codes(cv, cv_ref, ref["V"], sv_ref, O.ROW, group)
 
 
 def test_config5_vo_pair_full_oracle(env):

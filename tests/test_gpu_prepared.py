@@ -171,3 +171,20 @@ def test_prepared_optimize_pair_history(env):
         for i in range(5):
             parity.check_scalar(h[s, i], h_ref[s, i], rel=5e-4, what="history[%d][%d]" % (s, i))
     assert np.abs(Td.cpu().numpy() - T_ref).max() <= 3 * lr
+
+
+@pytest.mark.parametrize("bits,group,naxis", [(4, 256, 1024), (4, 0, 1024), (4, 512, 1024), (8, 64, 512)])
+@pytest.mark.parametrize("axis,rep", [(O.COL, 1), (O.ROW, 2)])
+def test_prepared_gradient_pass_with_the_generic_loss_pass(env, bits, group, naxis, axis, rep):
+    # groups of 256, groups that span blocks and fine grids take the loss pass over float32 weights; their
+    # gradient pass still reads the prepared copy (blocks of 128)
+    W, T, P = _case(axis, 200, naxis, 128, rep, 1700 + bits + group)
+    _check_single_prepared(env, W, T, P, bits, group, axis, rep)
+
+
+def test_prepared_gradient_pass_ragged_lines_and_many_tiles(env):
+    # 1000 lines: seven full tiles of 128 and one of 104; more tiles than one workgroup range holds
+    W, T, P = _case(O.COL, 1000, 512, 128, 1, 1751)
+    _check_single_prepared(env, W, T, P, 3, 128, O.COL, 1, want_codes=False)
+    W, T, P = _case(O.ROW, 1000, 512, 128, 2, 1752)
+    _check_single_prepared(env, W, T, P, 3, 32, O.ROW, 2, want_codes=False)
