@@ -34,6 +34,30 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBS = 8000.0
 
 
+def memory_probe(torch, dev):
+    """Streaming rates of two library kernels over 1 GiB buffers (larger than every cache of the part): a
+    read-only reduction and a copy.  Context for the roofline figures, not part of any timed step."""
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+
+    def rate(fn, nbytes, n=10):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return nbytes * n / (time.perf_counter() - t0) / 1e12
+
+    out = {"read_only_TBps": rate(lambda: src.sum(), src.numel() * 4),
+           "copy_read_plus_write_TBps": rate(lambda: dst.copy_(src), 2 * src.numel() * 4),
+           "what": "torch.sum / Tensor.copy_ over 1 GiB float32, 10 repetitions"}
+    del src, dst
+    torch.cuda.empty_cache()
+    return out
+
+
 def measured_traffic(profile, key):
     """HBM bytes per launch from a rocprofv3 summary under profiles/ (a line `key: <bytes>`), or None."""
     try:
@@ -166,6 +190,14 @@ def pair_workload(args, secondary=True):
         "executed_frac_of_f16_peak": executed / F16_MFMA_PEAK_TFLOPS,
         "achieved_over_fp32_mfma_peak": achieved / FP32_MFMA_PEAK_TFLOPS,
         "hbm_frac_at_algorithmic_bytes": 4.0 * member / avg_launch_s / 1e9 / HBM_PEAK_GBS}
+    # what this machine's memory system delivers to plain streaming kernels on data that no cache holds (the published
+    # 8 TB/s stays the roofline's peak; these two figures say how far any kernel gets towards it here)
+    probe = memory_probe(torch, dev)
+    traffic = result["roofline"]["traffic"]
+    result["roofline"]["memory_probe"] = probe
+    if traffic:
+        result["roofline"]["measured_traffic_TBps"] = traffic / avg_launch_s / 1e12
+        result["roofline"]["measured_traffic_over_read_probe"] = traffic / avg_launch_s / 1e12 / probe["read_only_TBps"]
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = pair_cpu_baseline(cfg, args.cpu_blocks, args.cpu_reps)
     if secondary:

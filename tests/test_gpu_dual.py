@@ -46,8 +46,13 @@ def _check_dual(env, A, B, T, bits, group, rep, t=5.0, want_codes=True, scale=1.
         cv_ref, sv_ref, _ = O.rtn_sym(ref["V"], bits, group, O.ROW)
         parity.check_scales(su, su_ref)
         parity.check_scales(sv, sv_ref)
-        parity.check_codes(cu, cu_ref, ref["U"], su_ref, O.COL, group)
-        parity.check_codes(cv, cv_ref, ref["V"], sv_ref, O.ROW, group)
+        k = T.shape[1]
+        unit_u = parity.forward_unit(k, group if group else A.shape[1], bits)
+        unit_v = parity.forward_unit(k, group if group else B.shape[0], bits)
+        tol_u = parity.tie_tolerance(A, T, O.COL, 1, ref["U"], su_ref, group, unit_u)
+        tol_v = parity.tie_tolerance(B, P, O.ROW, rep, ref["V"], sv_ref, group, unit_v)
+        parity.check_codes(cu, cu_ref, ref["U"], su_ref, O.COL, group, tie_tol=tol_u)
+        parity.check_codes(cv, cv_ref, ref["V"], sv_ref, O.ROW, group, tie_tol=tol_v)
 
 
 @pytest.mark.parametrize("k,group,rep", [(32, 32, 1), (64, 128, 1), (64, 64, 2), (128, 128, 1), (128, 64, 2)])

@@ -42,7 +42,9 @@ def _check_single_prepared(env, W, T, P, bits, group, axis, rep, bf16=False, wan
     if want_codes:
         c_ref, s_ref, _ = O.rtn_sym(ref["Z"], bits, group, axis)
         parity.check_scales(scales.cpu().numpy(), s_ref)
-        parity.check_codes(codes.cpu().numpy(), c_ref, ref["Z"], s_ref, axis, group)
+        gk = group if group else (W.shape[1] if axis == O.COL else W.shape[0])
+        tol = parity.tie_tolerance(W, T, axis, rep, ref["Z"], s_ref, group, parity.forward_unit(T.shape[1], gk, bits))
+        parity.check_codes(codes.cpu().numpy(), c_ref, ref["Z"], s_ref, axis, group, tie_tol=tol)
 
 
 @pytest.mark.parametrize("group", [32, 64, 128])
