@@ -1,6 +1,7 @@
 // Small kernels around the fused core: squared norms of the inverse transform (the
 // (M^-1)_{ij}^2 factors of the paper's surrogate, Sec. 4.1), fixed-order reduction of the
 // per-workgroup partials and the k x k products of the gradient's path through M^-1.  All are off the bandwidth path (k x k sized per block).
+#include <atomic>
 #include "xform_core.hpp"
 
 namespace cafeq {
@@ -436,16 +437,18 @@ __global__ __launch_bounds__(256) void bgemm_kernel(const float* __restrict__ A,
 
 // Same product on the matrix cores (v_mfma_f32_32x32x2_f32) for K a multiple of 64: one 64 x 64
 // output tile per workgroup, four waves of one 32 x 32 tile each, the operand panels staged in
-// LDS as [contraction index][64 tile indices] (row stride 97 floats: transposing stores, whose
+// LDS as [contraction index][64 tile indices] (row stride 65 floats: transposing stores, whose
 // lanes walk the contraction index, and the MFMA operand reads, whose lane halves take rows l
-// and l+1, both stay clear of bank conflicts).  Contraction in chunks of 64 (50 KB of LDS: three
-// workgroups per compute unit).
-template <bool TA, bool TB>
+// and l+1, both stay clear of bank conflicts).  Contraction in chunks of CH = min(K, 128): the blocks of
+// 128 the learning loops run on take one chunk -- every load of the workgroup is in flight at once and
+// there is one barrier -- at 65 KB of LDS, two workgroups per compute unit.
+template <bool TA, bool TB, int CH>
 __global__ __launch_bounds__(256) void bgemm_mfma_kernel(const float* __restrict__ A, const float* __restrict__ B,
                                                           float* __restrict__ C, int K, float alpha, float beta) {
-  constexpr int LD = 97, CH = 64;
-  __shared__ float sa[CH * LD];
-  __shared__ float sb[CH * LD];
+  constexpr int LD = 65;
+  extern __shared__ __align__(16) float bsm[];
+  float* sa = bsm;
+  float* sb = bsm + CH * LD;
   const int tpr = K / 64;
   const int b = blockIdx.x / (tpr * tpr), tile = blockIdx.x % (tpr * tpr);
   const int i0 = (tile / tpr) * 64, j0 = (tile % tpr) * 64;
@@ -457,40 +460,50 @@ __global__ __launch_bounds__(256) void bgemm_mfma_kernel(const float* __restrict
   floatx16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  // the old value of the output, where it is added to: requested before everything else
+  float cold[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) cold[v] = 0.f;
+  if (beta != 0.f) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      cold[v] = Cb[(i0 + wi * 32 + 8 * (v / 4) + 4 * h + (v % 4)) * K + j0 + wj * 32 + ln];
+  }
   for (int l0 = 0; l0 < K; l0 += CH) {
-    const int nl = CH;
-    const int sh = 6;
-    // sa[l][i] = op(A)[i0 + i][l0 + l];  sb[l][j] = op(B)[l0 + l][j0 + j]; eight elements of
-    // each panel per thread and round, all loads of a round issued before the first LDS store
-    for (int e0 = tid; e0 < nl * 64; e0 += 8 * 256) {
-      float va[8], vb[8];
-      int da[8], db[8];
+    // sa[l][i] = op(A)[i0 + i][l0 + l];  sb[l][j] = op(B)[l0 + l][j0 + j]: four consecutive elements of the
+    // operand's rows per load, all loads of the chunk issued before the first LDS store
+    constexpr int NV = CH * 64 / 4 / 256;   // float4 per thread and panel
+    float4 va[NV], vb[NV];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int e = e0 + u * 256;
-        if (TA) { const int l = e >> 6, i = e & 63; da[u] = l * LD + i; va[u] = Ab[(l0 + l) * K + i0 + i]; }
-        else    { const int i = e >> sh, l = e & (nl - 1); da[u] = l * LD + i; va[u] = Ab[(i0 + i) * K + l0 + l]; }
-        if (TB) { const int j = e >> sh, l = e & (nl - 1); db[u] = l * LD + j; vb[u] = Bb[(j0 + j) * K + l0 + l]; }
-        else    { const int l = e >> 6, j = e & 63; db[u] = l * LD + j; vb[u] = Bb[(l0 + l) * K + j0 + j]; }
-      }
+    for (int u = 0; u < NV; ++u) {
+      const int e = (tid + u * 256) * 4;
+      if (TA) { const int l = e >> 6, i = e & 63; va[u] = *reinterpret_cast<const float4*>(Ab + (l0 + l) * K + i0 + i); }
+      else    { const int i = e / CH, l = e % CH; va[u] = *reinterpret_cast<const float4*>(Ab + (i0 + i) * K + l0 + l); }
+      if (TB) { const int j = e / CH, l = e % CH; vb[u] = *reinterpret_cast<const float4*>(Bb + (j0 + j) * K + l0 + l); }
+      else    { const int l = e >> 6, j = e & 63; vb[u] = *reinterpret_cast<const float4*>(Bb + (l0 + l) * K + j0 + j); }
+    }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) { sa[da[u]] = va[u]; sb[db[u]] = vb[u]; }
+    for (int u = 0; u < NV; ++u) {
+      const int e = (tid + u * 256) * 4;
+      if (TA) { const int l = e >> 6, i = e & 63; float* d = sa + l * LD + i; d[0] = va[u].x; d[1] = va[u].y; d[2] = va[u].z; d[3] = va[u].w; }
+      else    { const int i = e / CH, l = e % CH; float* d = sa + l * LD + i; d[0] = va[u].x; d[LD] = va[u].y; d[2 * LD] = va[u].z; d[3 * LD] = va[u].w; }
+      if (TB) { const int j = e / CH, l = e % CH; float* d = sb + l * LD + j; d[0] = vb[u].x; d[LD] = vb[u].y; d[2 * LD] = vb[u].z; d[3 * LD] = vb[u].w; }
+      else    { const int l = e >> 6, j = e & 63; float* d = sb + l * LD + j; d[0] = vb[u].x; d[1] = vb[u].y; d[2] = vb[u].z; d[3] = vb[u].w; }
     }
     __syncthreads();
     const float* pa = sa + h * LD + wi * 32 + ln;
     const float* pb = sb + h * LD + wj * 32 + ln;
-    for (int s0 = 0; s0 < nl / 2; s0 += 8) {
+    for (int s0 = 0; s0 < CH / 2; s0 += 8) {
 #pragma unroll
       for (int u = 0; u < 8; ++u)
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[2 * (s0 + u) * LD], pb[2 * (s0 + u) * LD], acc, 0, 0, 0);
     }
-    __syncthreads();
+    if (l0 + CH < K) __syncthreads();
   }
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int i = i0 + wi * 32 + 8 * (v / 4) + 4 * h + (v % 4), j = j0 + wj * 32 + ln;
-    float* dst = Cb + i * K + j;
-    *dst = alpha * acc[v] + (beta != 0.f ? beta * *dst : 0.f);
+    Cb[i * K + j] = alpha * acc[v] + (beta != 0.f ? beta * cold[v] : 0.f);
   }
 }
 
@@ -613,10 +626,31 @@ int launch_bgemm(bool ta, bool tb, const float* A, const float* B, float* C, int
 #undef CAFEQ_G32
   } else {
     const unsigned grid = unsigned(nb) * (K / 64) * (K / 64);
-#define CAFEQ_G64(TA, TB) hipLaunchKernelGGL((bgemm_mfma_kernel<TA, TB>), dim3(grid), dim3(256), 0, st, A, B, C, K, alpha, beta)
-    if (ta && tb) CAFEQ_G64(true, true); else if (ta) CAFEQ_G64(true, false);
-    else if (tb) CAFEQ_G64(false, true); else CAFEQ_G64(false, false);
+    if (K % 128 == 0) {
+      constexpr int CH = 128;
+      constexpr size_t lds = 2 * CH * 65 * sizeof(float);
+      static std::atomic<bool> attr_set{false};
+      if (!attr_set) {
+        bool ok = true;
+#define CAFEQ_ATTR(TA, TB)                                                                                     \
+  ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(bgemm_mfma_kernel<TA, TB, CH>),                 \
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) == hipSuccess
+        CAFEQ_ATTR(true, true); CAFEQ_ATTR(true, false); CAFEQ_ATTR(false, true); CAFEQ_ATTR(false, false);
+#undef CAFEQ_ATTR
+        if (!ok) return CAFEQ_ERR_LAUNCH;
+        attr_set = true;
+      }
+#define CAFEQ_G128(TA, TB) hipLaunchKernelGGL((bgemm_mfma_kernel<TA, TB, CH>), dim3(grid), dim3(256), lds, st, A, B, C, K, alpha, beta)
+      if (ta && tb) CAFEQ_G128(true, true); else if (ta) CAFEQ_G128(true, false);
+      else if (tb) CAFEQ_G128(false, true); else CAFEQ_G128(false, false);
+#undef CAFEQ_G128
+    } else {
+      constexpr size_t lds = 2 * 64 * 65 * sizeof(float);
+#define CAFEQ_G64(TA, TB) hipLaunchKernelGGL((bgemm_mfma_kernel<TA, TB, 64>), dim3(grid), dim3(256), lds, st, A, B, C, K, alpha, beta)
+      if (ta && tb) CAFEQ_G64(true, true); else if (ta) CAFEQ_G64(true, false);
+      else if (tb) CAFEQ_G64(false, true); else CAFEQ_G64(false, false);
 #undef CAFEQ_G64
+    }
   }
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;

@@ -369,6 +369,30 @@ int run_core(int K, int axis, const GroupPlan& gp, CoreParams p, float2* rec, fl
   return launch_core(K, gp.Gk, axis, p, st);
 }
 
+// Whether the gradient passes of a call can run with one workgroup per (matrix, block) and write the gradient in
+// its final form (grad_v2.hip): prepared weights, blocks of 128, no row-blocks sharing a transform block, and
+// blocks that fill the chip once, not more.
+bool grad_owner_eligible(const cafeq_mat* const* mats, const PassPlans* const* pps, int n, int K, int rep) {
+  if (K != 128 || rep != 1) return false;
+  int64_t jobs = 0;
+  for (int i = 0; i < n; ++i) {
+    if (!mats[i]->prepared || !pps[i]->two) return false;
+    jobs += pps[i]->gpass.nseg;
+  }
+  const int cus = device_cu_count();
+  return jobs <= cus && jobs * 5 >= int64_t(cus) * 3;
+}
+GradOwnerJob grad_owner_job(const cafeq_mat* W, int axis, const PassPlans& pp, const MemberWs& m, float* out,
+                            int transpose_out) {
+  const bool col = axis == CAFEQ_AXIS_COL;
+  const PreparedLayout l = prepared_layout(col ? W->rows : W->cols, col ? W->cols : W->rows);
+  GradOwnerJob j;
+  j.gtiles = static_cast<const unsigned char*>(W->prepared) + l.off_gtiles;
+  j.rec = m.grec; j.rG = m.rGreal; j.out = out;
+  j.nlines = pp.gpass.nlines; j.nseg = pp.gpass.nseg; j.grp = pp.gp.G; j.transpose_out = transpose_out;
+  return j;
+}
+
 // The gradient pass of the two-pass scheme over one matrix (records in, gradient partials out).
 int run_grad_pass(int K, int axis, const cafeq_mat* W, int rep, const PassPlans& pp, const MemberWs& m,
                   int loss_kind, float beta, float lse_t, const float* hdr_ref, int nslot_ref, float* member_ref,
@@ -817,10 +841,17 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
     // path through Z (fused into the pass above, or a second pass over the weights from its
     // arg-max records), then the path through rho(P): -2 P^T Mmid P^T
     CoreParams pg = p;
-    if (pp.two &&
-        (rc = run_grad_pass(K, cfg->axis, W, x->rep, pp, w.m, kLossSur, beta, 0.f, nullptr, 0, nullptr, &pg, st)))
-      return rc;
-    if ((rc = launch_reduce_grad(pg, K, gp.Gk, pp.fused, nb, col ? 1 : 0, nullptr, nullptr, gradT, st))) return rc;
+    const cafeq_mat* mats[1] = {W};
+    const PassPlans* pps[1] = {&pp};
+    if (grad_owner_eligible(mats, pps, 1, K, x->rep)) {
+      const GradOwnerJob job = grad_owner_job(W, cfg->axis, pp, w.m, gradT, col ? 1 : 0);
+      if ((rc = launch_grad_v2_owner(&job, 1, kLossSur, beta, 0.f, nullptr, st))) return rc;
+    } else {
+      if (pp.two &&
+          (rc = run_grad_pass(K, cfg->axis, W, x->rep, pp, w.m, kLossSur, beta, 0.f, nullptr, 0, nullptr, &pg, st)))
+        return rc;
+      if ((rc = launch_reduce_grad(pg, K, gp.Gk, pp.fused, nb, col ? 1 : 0, nullptr, nullptr, gradT, st))) return rc;
+    }
     if ((rc = launch_build_mmid(p, K, gp.Gk, nb, x->Tinv, col ? 1 : 0, w.mmid, st))) return rc;
     if ((rc = launch_bgemm(true, false, x->Tinv, w.mmid, w.x1, K, nb, 1.f, 0.f, st))) return rc;
     if ((rc = launch_bgemm(false, true, w.x1, x->Tinv, gradT, K, nb, -2.f, 1.f, st))) return rc;
@@ -887,8 +918,11 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   if ((rc = run_core(K, CAFEQ_AXIS_COL, ga, a, w.a.rec, w.a.grec, qa.two, st, v2A ? A : nullptr, w.a.rec_mm, w.a.grec_mm)))
     return rc;
   ag = a;
-  if (qa.two && (rc = run_grad_pass(K, CAFEQ_AXIS_COL, A, 1, qa, w.a, kLossLse, 0.f, lse_t, w.hdrA, int(pa.nslot),
-                                    w.member_ref, &ag, st)))
+  const cafeq_mat* mats[2] = {A, B};
+  const PassPlans* pps[2] = {&qa, &qb};
+  const bool owner = grad && grad_owner_eligible(mats, pps, 2, K, x->rep);
+  if (!owner && qa.two && (rc = run_grad_pass(K, CAFEQ_AXIS_COL, A, 1, qa, w.a, kLossLse, 0.f, lse_t, w.hdrA, int(pa.nslot),
+                                              w.member_ref, &ag, st)))
     return rc;
 
   CoreParams b, bg;
@@ -902,15 +936,23 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   if ((rc = run_core(K, CAFEQ_AXIS_ROW, gb, b, w.b.rec, w.b.grec, qb.two, st, v2B ? B : nullptr, w.b.rec_mm, w.b.grec_mm)))
     return rc;
   bg = b;
-  if (qb.two && (rc = run_grad_pass(K, CAFEQ_AXIS_ROW, B, x->rep, qb, w.b, kLossLse, 0.f, lse_t, w.hdrB, int(pb.nslot),
-                                    w.member_ref + 1, &bg, st)))
+  if (!owner && qb.two && (rc = run_grad_pass(K, CAFEQ_AXIS_ROW, B, x->rep, qb, w.b, kLossLse, 0.f, lse_t, w.hdrB, int(pb.nslot),
+                                              w.member_ref + 1, &bg, st)))
     return rc;
 
   const int64_t ngroups = A->rows * (A->cols / ga.G) + (B->rows / gb.G) * B->cols;
   if ((rc = launch_reduce_losses(kLossLse, w.hdrA, int(pa.nslot), w.hdrB, int(pb.nslot), 0.f, lse_t, ngroups,
                                  losses, w.lse_ms, st)))
     return rc;
-  if (grad) {
+  if (grad && owner) {
+    // both members' gradient passes in one launch, after the pair's LogSumExp is known: one workgroup per block
+    // writes member A's share into gradT (transposed) and member B's G_P; d/dT = -P^T G_P P^T follows
+    const GradOwnerJob jobs[2] = {grad_owner_job(A, CAFEQ_AXIS_COL, qa, w.a, gradT, 1),
+                                  grad_owner_job(B, CAFEQ_AXIS_ROW, qb, w.b, w.gp, 0)};
+    if ((rc = launch_grad_v2_owner(jobs, 2, kLossLse, 0.f, lse_t, w.lse_ms, st))) return rc;
+    if ((rc = launch_bgemm(true, false, x->Tinv, w.gp, w.x1, K, nb, 1.f, 0.f, st))) return rc;
+    if ((rc = launch_bgemm(false, true, w.x1, x->Tinv, gradT, K, nb, -1.f, 1.f, st))) return rc;
+  } else if (grad) {
     // member A into gradT; member B: G_P of transform block b sums its rep row-blocks; d/dT = -P^T G_P P^T
     if ((rc = launch_reduce_grad_pair(ag, ga.Gk, qa.fused, qa.two ? w.member_ref : nullptr, gradT, bg, gb.Gk, qb.fused,
                                       qb.two ? w.member_ref + 1 : nullptr, w.gp, K, nb, w.lse_ms, st)))

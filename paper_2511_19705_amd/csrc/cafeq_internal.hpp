@@ -65,6 +65,14 @@ int launch_prepare(const cafeq_mat* W, int axis, void* prepared, hipStream_t st)
 size_t prepared_gtiles_bytes(int64_t nlines, int64_t naxis);
 int launch_prepare_gtiles(const cafeq_mat* W, int axis, unsigned char* gtiles, hipStream_t st);
 int launch_grad_v2(const CoreParams& p, hipStream_t st);
+// the same with one workgroup per (matrix, block of 128) and the gradient written in its final form (no partials):
+// up to two matrices per launch; the coefficients must be final when it starts (kLossLse: lse_ms = {m*, S})
+struct GradOwnerJob {
+  const unsigned char* gtiles; const float2* rec; const float* rG; float* out;
+  int64_t nlines; int nseg, grp, transpose_out;
+};
+int launch_grad_v2_owner(const GradOwnerJob* jobs, int n, int loss_kind, float beta, float lse_t, const double* lse_ms,
+                         hipStream_t st);
 int launch_loss_v2(int G, int axis, const CoreParams& p, hipStream_t st);
 int launch_loss_prepared(int G, int axis, const CoreParams& p, hipStream_t st);   // ... with the caller's timing events
 

@@ -218,6 +218,188 @@ __global__ __launch_bounds__(kThreads, 2) void grad_v2_kernel(const CoreParams p
   flush(cur_seg);
 }
 
+// The same contraction with one workgroup per (matrix, block): eight waves, the first four take the block's even
+// tiles and the last four the odd ones (an S area each), the two halves' accumulators are added through LDS at
+// the end and the block's gradient is written in its final form -- no partials, no reduction pass.  For calls
+// whose blocks fill the chip once (the pair on the 9B-shaped MLP: 2 x 112 blocks on 256 compute units) and
+// whose groups' coefficients are final when the pass starts: the surrogate's 2 beta rho_G z, or the LogSumExp's
+// exp(t (|z| - m*)) / S with the pair's m* and S already reduced (lse_ms).
+struct GvMember {
+  const unsigned char* gtiles;
+  const float2* rec;
+  const float* rG;
+  float* out;            // [nseg][128][128]
+  int64_t nlines;
+  int mt_per_seg, nseg, grp, transpose_out;
+};
+struct GvOwnerArgs {
+  GvMember m[2];
+  int nmem, loss_kind;
+  float beta, lse_t;
+  const double* lse_ms;   // kLossLse: {m*, S}
+};
+
+__global__ __launch_bounds__(512, 1) void grad_v2_owner_kernel(const GvOwnerArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ln = lane & 31, h = lane >> 5;
+  const int half = wave >> 2, wq = wave & 3;
+  unsigned char* sbuf = smem + half * kGvSbufB;
+
+  const int mi = (a.nmem > 1 && int(blockIdx.x) >= a.m[0].nseg) ? 1 : 0;
+  const GvMember& M = a.m[mi];
+  const int seg = int(blockIdx.x) - (mi ? a.m[0].nseg : 0);
+  const int mt_per_seg = M.mt_per_seg;
+  const int niter = (mt_per_seg + 1) / 2;
+
+  for (int i = tid; i < 2 * kGvSbufB / 16; i += 512) reinterpret_cast<uint4*>(smem)[i] = make_uint4(0u, 0u, 0u, 0u);
+  float mstar = 0.f, inv_s = 1.f;
+  if (a.loss_kind == kLossLse) {
+    mstar = float(a.lse_ms[0]);
+    inv_s = float(1.0 / a.lse_ms[1]);
+  }
+  __syncthreads();
+
+  floatx16 gt[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) gt[i][v] = 0.f;
+
+  // ---- the S side (as in grad_v2_kernel; the rows' groups are fixed: one block per workgroup)
+  const int L = wq * 32 + ln;
+  const int sl_off = ((L >> 4) * 2) * kGvOperandB + ((L >> 3) & 1) * 32 * 16 + (L & 7) * 2;
+  int64_t gidx[2];
+  int joff[2];
+  float rgv[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int64_t aj = int64_t(seg) * 128 + 32 * (2 * h + i);
+    gidx[i] = aj / M.grp;
+    joff[i] = int(aj - gidx[i] * M.grp);
+    rgv[i] = a.loss_kind == kLossSur ? M.rG[gidx[i]] : 0.f;
+  }
+  float2 recv[2];
+  bool rvalid = false;
+  auto load_rec = [&](int ms_) {
+    const int64_t line = int64_t(ms_) * kGvLines + L;
+    rvalid = line < M.nlines;
+    const int64_t lc = rvalid ? line : M.nlines - 1;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) recv[i] = M.rec[gidx[i] * M.nlines + lc];
+  };
+  int woff[2] = {-1, -1};
+
+  // ---- the W side
+  const unsigned char* gbase = M.gtiles + wq * 2 * kGvOperandB + lane * 16;
+  auto tile_ptr = [&](int ms_) { return gbase + (int64_t(seg) * mt_per_seg + ms_) * int64_t(8 * 4 * 2 * kGvOperandB); };
+  uintx4 breg[8][2];
+  auto load_step = [&](const unsigned char* tp, int s) {
+#pragma unroll
+    for (int part = 0; part < 2; ++part)
+      breg[s][part] = *reinterpret_cast<const uintx4*>(tp + (s * 4 * 2 + part) * kGvOperandB);
+  };
+  // (a half without a tile of its own -- the odd half of a block with one tile -- reads tile 0 and skips the work)
+  int mis = half < mt_per_seg ? half : 0;
+  const unsigned char* tile = tile_ptr(mis);
+  load_rec(mis);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    load_step(tile, s);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  for (int it = 0; it < niter; ++it) {
+    const bool active = 2 * it + half < mt_per_seg;          // uniform over the wave
+    const bool has_next = 2 * (it + 1) + half < mt_per_seg;
+    const int nmis = has_next ? mis + 2 : mis;
+    const unsigned char* ntile = tile_ptr(nmis);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      if (woff[i] >= 0) {
+        *reinterpret_cast<uint16_t*>(sbuf + woff[i]) = 0;
+        *reinterpret_cast<uint16_t*>(sbuf + woff[i] + kGvOperandB) = 0;
+        woff[i] = -1;
+      }
+      const float2 rc = recv[i];
+      const int jj = __float_as_int(rc.y) - joff[i];
+      if (active && rvalid && jj >= 0 && jj < 32) {
+        float coef;
+        if (a.loss_kind == kLossSur) {
+          coef = 2.f * a.beta * rgv[i] * rc.x;
+        } else {
+          const float e = __expf(a.lse_t * (fabsf(rc.x) - mstar)) * inv_s;
+          coef = rc.x < 0.f ? -e : e;
+        }
+        const uint32_t ch = pack_bf16(coef, 0.f);
+        const uint32_t cl = pack_bf16(coef - bf16_lo_f32(ch), 0.f);
+        const int off = (2 * h + i) * 8 * 2 * kGvOperandB + sl_off + jj * 16;
+        *reinterpret_cast<uint16_t*>(sbuf + off) = uint16_t(ch);
+        *reinterpret_cast<uint16_t*>(sbuf + off + kGvOperandB) = uint16_t(cl);
+        woff[i] = off;
+      }
+    }
+    load_rec(nmis);
+    __syncthreads();
+
+    bf16x8 ash[4], asl[4];
+    auto read_s = [&](bf16x8 (&dst)[4], int s, int part) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        dst[i] = as_bf16x8(*reinterpret_cast<const uintx4*>(sbuf + ((i * 8 + s) * 2 + part) * kGvOperandB + lane * 16));
+    };
+    read_s(asl, 0, 1);
+    read_s(ash, 0, 0);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const bf16x8 bh = as_bf16x8(breg[s][0]), bm = as_bf16x8(breg[s][1]);
+      __builtin_amdgcn_sched_barrier(0);
+      // (an inactive half multiplies zeros: its S area is empty)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) gt[i] = CAFEQ_MFMA_BF16(asl[i], bh, gt[i]);
+      __builtin_amdgcn_sched_barrier(0);
+      if (s + 1 < 8) read_s(asl, s + 1, 1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) gt[i] = CAFEQ_MFMA_BF16(ash[i], bm, gt[i]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) gt[i] = CAFEQ_MFMA_BF16(ash[i], bh, gt[i]);
+      __builtin_amdgcn_sched_barrier(0);
+      if (s + 1 < 8) read_s(ash, s + 1, 0);
+      load_step(ntile, s);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    __syncthreads();
+    tile = ntile;
+    mis = nmis;
+  }
+
+  // ---- the two halves' sums, and out: element [j = 32 i + 8 (v / 4) + 4 h + v % 4][m = 32 wq + ln]
+  float* xb = reinterpret_cast<float*>(smem);   // [wq][i][v][lane]: 64 KB (the S areas are done with)
+  if (half == 1) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) xb[((wq * 4 + i) * 16 + v) * 64 + lane] = gt[i][v];
+  }
+  __syncthreads();
+  if (half == 0) {
+    float* dst = M.out + int64_t(seg) * (128 * 128);
+    const uint32_t lo_n = uint32_t(4 * h * 128 + wq * 32 + ln);          // [j][m]
+    const uint32_t lo_t = uint32_t((wq * 32 + ln) * 128 + 4 * h);        // [m][j]
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float g = gt[i][v] + xb[((wq * 4 + i) * 16 + v) * 64 + lane];
+        const int jc = i * 32 + 8 * (v / 4) + (v % 4);                   // j without the lane-half term
+        if (M.transpose_out) (dst + jc)[lo_t] = g;
+        else (dst + jc * 128)[lo_n] = g;
+      }
+  }
+}
+
 // One workgroup per tile of 128 lines x 128 inputs: the bfloat16 hi + mid parts of every weight (hi = the
 // round-to-nearest of the value, mid = that of the remainder: 16 significant bits), in operand order.
 struct GtileArgs {
@@ -272,6 +454,36 @@ int launch_prepare_gtiles(const cafeq_mat* W, int axis, unsigned char* gtiles, h
   a.nlines = nlines; a.nmt = (nlines + kGvLines - 1) / kGvLines;
   a.gtiles = gtiles;
   hipLaunchKernelGGL(prepare_gtiles_kernel, dim3(unsigned(a.nmt * (naxis / 128))), dim3(256), 0, st, a);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+
+// Both members of a pair (or one matrix) with one workgroup per block; see grad_v2_owner_kernel.
+int launch_grad_v2_owner(const GradOwnerJob* jobs, int n, int loss_kind, float beta, float lse_t, const double* lse_ms,
+                         hipStream_t st) {
+  if (n < 1 || n > 2) return CAFEQ_ERR_INVALID_ARG;
+  GvOwnerArgs a;
+  int nwg = 0;
+  for (int i = 0; i < n; ++i) {
+    const GradOwnerJob& j = jobs[i];
+    if (!j.gtiles || !j.rec || !j.out || j.grp < 32 || j.grp % 32 != 0 || j.nseg < 1) return CAFEQ_ERR_INVALID_ARG;
+    if (loss_kind == kLossSur && !j.rG) return CAFEQ_ERR_INVALID_ARG;
+    a.m[i].gtiles = j.gtiles; a.m[i].rec = j.rec; a.m[i].rG = j.rG; a.m[i].out = j.out;
+    a.m[i].nlines = j.nlines; a.m[i].mt_per_seg = int((j.nlines + kGvLines - 1) / kGvLines);
+    a.m[i].nseg = j.nseg; a.m[i].grp = j.grp; a.m[i].transpose_out = j.transpose_out;
+    nwg += j.nseg;
+  }
+  if (n == 1) a.m[1] = a.m[0];
+  if (loss_kind == kLossLse && !lse_ms) return CAFEQ_ERR_INVALID_ARG;
+  a.nmem = n; a.loss_kind = loss_kind; a.beta = beta; a.lse_t = lse_t; a.lse_ms = lse_ms;
+  static std::atomic<bool> attr_set{false};
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(grad_v2_owner_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return CAFEQ_ERR_LAUNCH;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(grad_v2_owner_kernel, dim3(unsigned(nwg)), dim3(512), 2 * kGvSbufB + 64, st, a);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }
