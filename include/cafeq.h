@@ -340,7 +340,8 @@ int cafeq_optimize_pair(const cafeq_mat* A, const cafeq_mat* B, float* T, float*
  * kernel (the loss pass; not the gradient pass or the small kernels around it) is bracketed by two of the
  * CALLER's events, recorded on the launch stream: launch number i uses start[i] / stop[i] (hipEvent_t handles
  * the caller created with timing enabled) and count is incremented; launches beyond `capacity` are not
- * timed.  The library creates, destroys and synchronises nothing: the caller synchronises the stream and reads
+ * timed.  every > 1 times only every `every`-th such launch (an event pair costs the stream several
+ * microseconds; `seen` counts all of them and starts at 0).  The library creates, destroys and synchronises nothing: the caller synchronises the stream and reads
  * hipEventElapsedTime(start[i], stop[i]).  The table (host memory) must stay valid until it is replaced or
  * removed with NULL.  One table per process; not thread-safe. */
 typedef struct {
@@ -348,6 +349,8 @@ typedef struct {
   void** stop;
   int capacity;
   int count;
+  int every;
+  int seen;
 } cafeq_launch_timing;
 int cafeq_set_launch_timing(cafeq_launch_timing* t);
 

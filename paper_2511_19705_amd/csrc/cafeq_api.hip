@@ -440,6 +440,8 @@ template <typename F>
 int timed_launch(hipStream_t st, F&& launch) {
   cafeq_launch_timing* t = g_timing;
   if (!t || t->count >= t->capacity) return launch();
+  const int nth = t->seen++;
+  if (t->every > 1 && nth % t->every != 0) return launch();
   const int i = t->count;
   (void)hipEventRecord(static_cast<hipEvent_t>(t->start[i]), st);
   const int rc = launch();
