@@ -154,7 +154,7 @@ def pair_workload(args, secondary=True):
     torch.cuda.synchronize()
     # every fifth launch of the loss pass is timed (members alternate): an event pair holds the stream up for
     # several microseconds, which would otherwise be part of every step
-    timer = cafeq.LaunchTimer(2 * args.steps // 5 + 2, every=5)
+    timer = cafeq.LaunchTimer(2 * args.steps // 5 + 2, every=5)   # (one or two launches per step)
     with timer:
         t0 = time.perf_counter()
         for _ in range(args.steps):
@@ -166,10 +166,14 @@ def pair_workload(args, secondary=True):
 
     # dominant kernel: the loss pass, launched once per member.  Algorithmic work per launch: forward and inverse
     # transform of its member, 2k flop per element each; it reads every weight once (4 B per element).
+    # (with prepared weights and no codes requested the library runs both members' loss passes as ONE launch, each
+    # member on half of the chip: the timing table says how many launches there were)
+    launches_per_step = max(1, round(timer.table.seen / float(args.steps)))
+    per_launch = member * (2.0 / launches_per_step)           # weight elements one launch covers
     avg_launch_s = sum(durs) / max(len(durs), 1) * 1e-3
-    flops_per_launch = 2.0 * 2.0 * k * member
+    flops_per_launch = 2.0 * 2.0 * k * per_launch
     achieved = flops_per_launch / avg_launch_s / 1e12
-    executed = 5.0 * 2.0 * k * member / avg_launch_s / 1e12   # 3 + 2 part products per contraction index
+    executed = 5.0 * 2.0 * k * per_launch / avg_launch_s / 1e12   # 3 + 2 part products per contraction index
     result = _base("proxy-loss fwd+bwd weight-elements/s (9B-shaped MLP pair, dual transform)", elems * args.steps / dt,
                    "weight-elements/s", args.steps, args.warmup, dt / args.steps * 1e3, "f32", cfg["name"],
                    rows_cols=[list(cfg["A"].shape), list(cfg["B"].shape)], block=k, group=g, bits=bits,
@@ -186,13 +190,15 @@ def pair_workload(args, secondary=True):
         "bound": "mfma", "achieved": achieved, "peak": F16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
         "frac": achieved / F16_MFMA_PEAK_TFLOPS,
         "traffic": measured_traffic("loss_prepared_c3_pair.md", "traffic_bytes_per_launch"),
-        "kernel": "loss_v2_kernel<128,*,true,false> (loss pass over prepared weights)", "launches": len(durs),
-        "launches_in_timed_region": 2 * args.steps,
+        "kernel": "loss_v2_pair_kernel<128,true> (loss pass over prepared weights, both members of the pair in one "
+                  "launch)" if launches_per_step == 1 else "loss_v2_kernel<128,*,true,false> (loss pass over prepared weights)",
+        "launches": len(durs), "launches_in_timed_region": int(timer.table.seen),
+        "weight_elements_per_launch": per_launch,
         "avg_launch_us": avg_launch_s * 1e6, "algorithmic_flop_per_element": 4 * k,
         "algorithmic_bytes_per_element": 4, "executed_part_product_tflops": executed,
         "executed_frac_of_f16_peak": executed / F16_MFMA_PEAK_TFLOPS,
         "achieved_over_fp32_mfma_peak": achieved / FP32_MFMA_PEAK_TFLOPS,
-        "hbm_frac_at_algorithmic_bytes": 4.0 * member / avg_launch_s / 1e9 / HBM_PEAK_GBS}
+        "hbm_frac_at_algorithmic_bytes": 4.0 * per_launch / avg_launch_s / 1e9 / HBM_PEAK_GBS}
     # what this machine's memory system delivers to plain streaming kernels on data that no cache holds (the published
     # 8 TB/s stays the roofline's peak; these two figures say how far any kernel gets towards it here)
     probe = memory_probe(torch, dev)

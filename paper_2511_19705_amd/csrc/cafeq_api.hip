@@ -154,16 +154,17 @@ float beta_for(const cafeq_quant_cfg* cfg, const QGrid& g) {
 bool v2_eligible(const cafeq_mat* W, int K, const GroupPlan& gp, const cafeq_quant_cfg* cfg) {
   return W->prepared != nullptr && K == 128 && gp.Gk <= 128 && gp.gspan == 1 && cfg->bits <= 4 && !is_minmax(cfg);
 }
-void make_v2_plan(CorePlan* pl) {
+// share: the matrix gets 1 / share of the chip's compute units (2: the members of a pair that run in one launch)
+void make_v2_plan(CorePlan* pl, int share = 1) {
   pl->mt_per_seg = (pl->nlines + 255) / 256;
   pl->n_mt = pl->mt_per_seg * pl->nseg;
-  int64_t nwg = std::min<int64_t>(pl->n_mt, int64_t(device_cu_count()));
+  int64_t nwg = std::min<int64_t>(pl->n_mt, int64_t(device_cu_count()) / share);
   if (nwg > 8) nwg -= nwg % 8;
   pl->nwg = int(nwg);
   pl->nslot = pl->nwg + pl->nseg;
 }
 int plan_passes(int K, const GroupPlan& gp, int64_t nlines, int64_t naxis, bool grad, PassPlans* pp,
-                bool v2 = false, bool asym = false) {
+                bool v2 = false, bool asym = false, int v2_share = 1) {
   pp->gp = gp;
   pp->v2 = v2;
   pp->asym = asym;
@@ -173,7 +174,7 @@ int plan_passes(int K, const GroupPlan& gp, int64_t nlines, int64_t naxis, bool 
   pp->fused = grad && fused_ok;
   int rc = make_plan(K, gp.Gk, nlines, naxis, &pp->first, pp->fused);
   if (rc) return rc;
-  if (v2) make_v2_plan(&pp->first);
+  if (v2) make_v2_plan(&pp->first, v2_share);
   if (pp->two) return make_grad_plan(K, nlines, naxis, &pp->gpass);
   pp->gpass = pp->first;
   return CAFEQ_OK;
@@ -331,6 +332,16 @@ void fill_common(CoreParams* p, const cafeq_mat* W, const CorePlan& pl, int rep)
   p->grid = make_grid(4);
 }
 
+// where the loss pass over prepared weights finds them
+void set_prepared(CoreParams* p, const cafeq_mat* W, int axis) {
+  const bool col = axis == CAFEQ_AXIS_COL;
+  const PreparedLayout l = prepared_layout(col ? W->rows : W->cols, col ? W->cols : W->rows);
+  const unsigned char* base = static_cast<const unsigned char*>(W->prepared);
+  p->prep_wsq = reinterpret_cast<const float*>(base);
+  p->prep_lscale = reinterpret_cast<const float*>(base + l.off_lscale);
+  p->prep_planes = base + l.off_planes;
+}
+
 // Forward sweep(s) of the fused core over one matrix.  `p` holds everything but the group bookkeeping.  For
 // groups inside a segment this is one launch.  For groups that span gspan segments: a forward-only sweep that
 // records every segment's arg-max, the combination of the records per group, then the sweep proper, which
@@ -342,13 +353,7 @@ int run_core(int K, int axis, const GroupPlan& gp, CoreParams p, float2* rec, fl
   int rc;
   if (prepared_of) {
     // loss pass over the prepared copy of the weights
-    const bool col = axis == CAFEQ_AXIS_COL;
-    const PreparedLayout l = prepared_layout(col ? prepared_of->rows : prepared_of->cols,
-                                             col ? prepared_of->cols : prepared_of->rows);
-    const unsigned char* base = static_cast<const unsigned char*>(prepared_of->prepared);
-    p.prep_wsq = reinterpret_cast<const float*>(base);
-    p.prep_lscale = reinterpret_cast<const float*>(base + l.off_lscale);
-    p.prep_planes = base + l.off_planes;
+    set_prepared(&p, prepared_of, axis);
     p.rec = want_rec ? rec : nullptr;
     return launch_loss_prepared(gp.Gk, axis, p, st);
   }
@@ -455,6 +460,9 @@ int launch_core(int K, int G, int axis, const CoreParams& p, hipStream_t st) {
 }
 int launch_loss_prepared(int G, int axis, const CoreParams& p, hipStream_t st) {
   return timed_launch(st, [&] { return launch_loss_v2(G, axis, p, st); });
+}
+int launch_loss_prepared_pair(int G, const CoreParams& pa, const CoreParams& pb, hipStream_t st) {
+  return timed_launch(st, [&] { return launch_loss_v2_pair(G, pa, pb, st); });
 }
 size_t core_lds_bytes(int K, int G, bool do_grad) {
   switch (K) {
@@ -884,9 +892,12 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   const bool grad = gradT != nullptr;
   const bool asym = is_minmax(cfg);
   const bool v2A = v2_eligible(A, K, ga, cfg), v2B = v2_eligible(B, K, gb, cfg);
+  // both loss passes over prepared weights in one launch, each member on half of the chip: when neither writes
+  // codes or scales and both use the same group length
+  const bool pair_launch = v2A && v2B && !codesU && !scalesU && !codesV && !scalesV && ga.Gk == gb.Gk;
   PassPlans qa, qb;
-  if ((rc = plan_passes(K, ga, A->rows, A->cols, grad, &qa, v2A, asym))) return rc;
-  if ((rc = plan_passes(K, gb, B->cols, B->rows, grad, &qb, v2B, asym))) return rc;
+  if ((rc = plan_passes(K, ga, A->rows, A->cols, grad, &qa, v2A, asym, pair_launch ? 2 : 1))) return rc;
+  if ((rc = plan_passes(K, gb, B->cols, B->rows, grad, &qb, v2B, asym, pair_launch ? 2 : 1))) return rc;
   const CorePlan &pa = qa.first, &pb = qb.first;
   {
     const size_t la = core_lds_bytes(K, ga.Gk, qa.fused), lb = core_lds_bytes(K, gb.Gk, qb.fused);
@@ -909,7 +920,7 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   // the same weights, while they are still in the memory-side cache.  The gradient pass takes
   // its exponentials relative to the member's own largest group maximum; the final reduction
   // rescales to the pair's.
-  CoreParams a, ag;
+  CoreParams a, ag, b, bg;
   fill_common(&a, A, pa, 1);
   a.Afwd = w.a.pfwd; a.Ainv = w.a.pinv;
   a.grid = grid; a.do_inverse = 1; a.do_grad = qa.fused ? 1 : 0; a.loss_kind = kLossLse; a.lse_t = lse_t;
@@ -917,17 +928,6 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   a.fscale = f16A ? w.a.fs : nullptr; a.fscale_inv = v2A ? w.a.fsi : nullptr;
   a.asym = asym ? 1 : 0;
   a.mins = asym && scalesU ? scalesU + A->rows * (A->cols / ga.G) : nullptr;   // the minima follow the scales
-  if ((rc = run_core(K, CAFEQ_AXIS_COL, ga, a, w.a.rec, w.a.grec, qa.two, st, v2A ? A : nullptr, w.a.rec_mm, w.a.grec_mm)))
-    return rc;
-  ag = a;
-  const cafeq_mat* mats[2] = {A, B};
-  const PassPlans* pps[2] = {&qa, &qb};
-  const bool owner = grad && grad_owner_eligible(mats, pps, 2, K, x->rep);
-  if (!owner && qa.two && (rc = run_grad_pass(K, CAFEQ_AXIS_COL, A, 1, qa, w.a, kLossLse, 0.f, lse_t, w.hdrA, int(pa.nslot),
-                                              w.member_ref, &ag, st)))
-    return rc;
-
-  CoreParams b, bg;
   fill_common(&b, B, pb, x->rep);
   b.Afwd = w.b.pfwd; b.Ainv = w.b.pinv;
   b.grid = grid; b.do_inverse = 1; b.do_grad = qb.fused ? 1 : 0; b.loss_kind = kLossLse; b.lse_t = lse_t;
@@ -935,7 +935,26 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   b.fscale = f16B ? w.b.fs : nullptr; b.fscale_inv = v2B ? w.b.fsi : nullptr;
   b.asym = asym ? 1 : 0;
   b.mins = asym && scalesV ? scalesV + (B->rows / gb.G) * B->cols : nullptr;
-  if ((rc = run_core(K, CAFEQ_AXIS_ROW, gb, b, w.b.rec, w.b.grec, qb.two, st, v2B ? B : nullptr, w.b.rec_mm, w.b.grec_mm)))
+  const cafeq_mat* mats[2] = {A, B};
+  const PassPlans* pps[2] = {&qa, &qb};
+  const bool owner = grad && grad_owner_eligible(mats, pps, 2, K, x->rep);
+
+  if (pair_launch) {
+    set_prepared(&a, A, CAFEQ_AXIS_COL);
+    set_prepared(&b, B, CAFEQ_AXIS_ROW);
+    a.rec = qa.two ? w.a.rec : nullptr;
+    b.rec = qb.two ? w.b.rec : nullptr;
+    if ((rc = launch_loss_prepared_pair(ga.Gk, a, b, st))) return rc;
+  } else if ((rc = run_core(K, CAFEQ_AXIS_COL, ga, a, w.a.rec, w.a.grec, qa.two, st, v2A ? A : nullptr, w.a.rec_mm,
+                            w.a.grec_mm))) {
+    return rc;
+  }
+  ag = a;
+  if (!owner && qa.two && (rc = run_grad_pass(K, CAFEQ_AXIS_COL, A, 1, qa, w.a, kLossLse, 0.f, lse_t, w.hdrA, int(pa.nslot),
+                                              w.member_ref, &ag, st)))
+    return rc;
+  if (!pair_launch && (rc = run_core(K, CAFEQ_AXIS_ROW, gb, b, w.b.rec, w.b.grec, qb.two, st, v2B ? B : nullptr, w.b.rec_mm,
+                                     w.b.grec_mm)))
     return rc;
   bg = b;
   if (!owner && qb.two && (rc = run_grad_pass(K, CAFEQ_AXIS_ROW, B, x->rep, qb, w.b, kLossLse, 0.f, lse_t, w.hdrB, int(pb.nslot),

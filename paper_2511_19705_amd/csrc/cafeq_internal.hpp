@@ -75,6 +75,9 @@ int launch_grad_v2_owner(const GradOwnerJob* jobs, int n, int loss_kind, float b
                          hipStream_t st);
 int launch_loss_v2(int G, int axis, const CoreParams& p, hipStream_t st);
 int launch_loss_prepared(int G, int axis, const CoreParams& p, hipStream_t st);   // ... with the caller's timing events
+// both members of a pair in one launch (loss_v2.hip), plain and with the caller's timing events
+int launch_loss_v2_pair(int G, const CoreParams& pa, const CoreParams& pb, hipStream_t st);
+int launch_loss_prepared_pair(int G, const CoreParams& pa, const CoreParams& pb, hipStream_t st);
 
 // aux_kernels.hip
 // fscale != null: two float16 planes of the block scaled by a power of two; fscale[block] = the factor back.

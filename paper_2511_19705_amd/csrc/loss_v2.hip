@@ -47,8 +47,9 @@ __device__ __forceinline__ uint32_t pack_f16(float x0, float x1) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, halfx2));
 }
 
+// bidx: the workgroup's index among the p.nwg workgroups that share the matrix
 template <int G, int AXIS, bool REC, bool OUT>
-__global__ __launch_bounds__(kV2Threads, 1) void loss_v2_kernel(const CoreParams p) {
+__device__ __forceinline__ void loss_v2_body(const CoreParams& p, const unsigned bidx) {
   constexpr int L = 128, KT = 4, NGRP = L / G, RPG = G / 2;
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* lfw = smem;                      // forward planes [4 stages][hi, lo][128 rows][64 B]
@@ -60,8 +61,8 @@ __global__ __launch_bounds__(kV2Threads, 1) void loss_v2_kernel(const CoreParams
   const int grp = wave >> 2;                      // phase group: waves 4-7 run one phase behind (waves i and i + 4 share a SIMD)
   const int ln = lane & 31, h = lane >> 5;
 
-  int64_t w = blockIdx.x;
-  if ((p.nwg & 7) == 0) w = int64_t(blockIdx.x & 7) * (p.nwg >> 3) + (blockIdx.x >> 3);
+  int64_t w = bidx;
+  if ((p.nwg & 7) == 0) w = int64_t(bidx & 7) * (p.nwg >> 3) + (bidx >> 3);
   const int64_t mt0 = chunk_begin(w, p.n_mt, p.nwg), mt1 = chunk_begin(w + 1, p.n_mt, p.nwg);
   if (mt0 >= mt1) return;
   const int mt_per_seg = int(p.mt_per_seg);       // macro-tiles of 256 lines per segment
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(kV2Threads, 1) void loss_v2_kernel(const CoreParams
     const int seg = int(mt / mt_per_seg);
     const int mis0 = int(mt - int64_t(seg) * mt_per_seg);
     const int n = int(mt1 - mt < int64_t(mt_per_seg - mis0) ? mt1 - mt : int64_t(mt_per_seg - mis0));
-    const int bid = (AXIS == CAFEQ_AXIS_ROW && p.rep != 1) ? seg / p.rep : seg;
+    const int bid = p.rep != 1 ? seg / p.rep : seg;   // (rep is 1 on the column axis)
 
     // ---- the block's operand planes into LDS (the previous segment's readers are past flush's barriers)
     {
@@ -402,6 +403,20 @@ __global__ __launch_bounds__(kV2Threads, 1) void loss_v2_kernel(const CoreParams
   }
 }
 
+template <int G, int AXIS, bool REC, bool OUT>
+__global__ __launch_bounds__(kV2Threads, 1) void loss_v2_kernel(const CoreParams p) {
+  loss_v2_body<G, AXIS, REC, OUT>(p, blockIdx.x);
+}
+
+// Both members of a pair in one launch (no codes or scales requested): the first pa.nwg workgroups take member
+// A, the others member B.  With one workgroup per compute unit in total, half of the chip streams each member
+// and the ranges of the two members end together -- one kernel tail instead of two.
+template <int G, bool REC>
+__global__ __launch_bounds__(kV2Threads, 1) void loss_v2_pair_kernel(const CoreParams pa, const CoreParams pb) {
+  if (blockIdx.x < unsigned(pa.nwg)) loss_v2_body<G, CAFEQ_AXIS_COL, REC, false>(pa, blockIdx.x);
+  else loss_v2_body<G, CAFEQ_AXIS_ROW, REC, false>(pb, blockIdx.x - unsigned(pa.nwg));
+}
+
 // ---------------------------------------------------------------------------------------------------
 // preparation: one workgroup per tile of 32 lines x 128 axis indices
 // ---------------------------------------------------------------------------------------------------
@@ -543,6 +558,40 @@ int launch_prepare(const cafeq_mat* W, int axis, void* prepared, hipStream_t st)
   hipLaunchKernelGGL(prepare_sum_kernel, dim3(1), dim3(256), 0, st, a.partial, l.ntiles, reinterpret_cast<float*>(base));
   CAFEQ_CHECK_LAUNCH();
   return launch_prepare_gtiles(W, axis, base + l.off_gtiles, st);
+}
+
+namespace {
+template <int G, bool REC>
+int launch_v2_pair_v(const CoreParams& pa, const CoreParams& pb, hipStream_t st) {
+  auto kern = loss_v2_pair_kernel<G, REC>;
+  static std::atomic<bool> attr_set{false};   // per instantiation
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            160 * 1024) != hipSuccess)
+      return CAFEQ_ERR_LAUNCH;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(unsigned(pa.nwg + pb.nwg)), dim3(kV2Threads), kV2Lds, st, pa, pb);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+}  // namespace
+
+// Both members of a pair (member A on its columns, member B on its rows) in one launch; same group length and
+// the same choice of records for both, no codes or scales.
+int launch_loss_v2_pair(int G, const CoreParams& pa, const CoreParams& pb, hipStream_t st) {
+  for (const CoreParams* p : {&pa, &pb})
+    if (!p->prep_planes || !p->prep_lscale || !p->prep_wsq || !p->fscale || !p->fscale_inv || !p->slot_hdr || p->codes ||
+        p->scales)
+      return CAFEQ_ERR_INVALID_ARG;
+  if ((pa.rec != nullptr) != (pb.rec != nullptr)) return CAFEQ_ERR_INVALID_ARG;
+  const bool rec = pa.rec != nullptr;
+  switch (G) {
+    case 32: return rec ? launch_v2_pair_v<32, true>(pa, pb, st) : launch_v2_pair_v<32, false>(pa, pb, st);
+    case 64: return rec ? launch_v2_pair_v<64, true>(pa, pb, st) : launch_v2_pair_v<64, false>(pa, pb, st);
+    case 128: return rec ? launch_v2_pair_v<128, true>(pa, pb, st) : launch_v2_pair_v<128, false>(pa, pb, st);
+    default: return CAFEQ_ERR_UNSUPPORTED;
+  }
 }
 
 int launch_loss_v2(int G, int axis, const CoreParams& p, hipStream_t st) {
