@@ -84,8 +84,13 @@ typedef struct {
 } cafeq_mat;
 
 /* Block-diagonal transform. T and Tinv: device, [nb][k][k] float32, 16-byte aligned.
- * k in {32, 64, 128, 256}.  rep >= 1: number of consecutive row-blocks sharing one
- * block (AXIS_ROW only; must be 1 on AXIS_COL). */
+ * k in {32, 64, 128, 256}, or one of the smaller sizes of the paper's block-size sweep, {2, 4, 8, 16}: those
+ * are taken by cafeq_block_inverse, cafeq_apply_transform, cafeq_proxy_loss_fwd_bwd,
+ * cafeq_dual_proxy_loss_fwd_bwd (rep = 1), cafeq_orth_penalty and the cafeq_optimize_* loops, which run every
+ * 32 / k consecutive blocks as one block-diagonal block of 32 (the axis a multiple of 32; for
+ * cafeq_block_inverse and cafeq_orth_penalty nb a multiple of 32 / k; status of cafeq_block_inverse is then
+ * per run of 32 / k blocks); Alg. 1 and the paired error need k >= 32.
+ * rep >= 1: number of consecutive row-blocks sharing one block (AXIS_ROW only; must be 1 on AXIS_COL). */
 typedef struct {
   const float* T;
   const float* Tinv;
@@ -130,7 +135,7 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
  * max |I - T T^T| <= 2e-6 -- is inverted by transposition).  rho_row[nb*k] / rho_col[nb*k] (either may be NULL):
  * squared row / column norms of Tinv.  status[nb] (may be NULL): 0 ok, 1 singular to
  * working precision (Tinv, rho_row and rho_col of that block are then zero).
- * k in {32, 64, 128, 256} (else CAFEQ_ERR_UNSUPPORTED). */
+ * k as in cafeq_xform (else CAFEQ_ERR_UNSUPPORTED). */
 int cafeq_block_inverse(const float* T, int k, int nb, float* Tinv, float* rho_row,
                         float* rho_col, int* status, void* ws, void* stream);
 

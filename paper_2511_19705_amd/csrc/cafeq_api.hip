@@ -261,6 +261,39 @@ int check_axis_len(const cafeq_mat* W, const cafeq_xform* x, int axis) {
   return CAFEQ_OK;
 }
 
+// Transform blocks of 2, 4, 8 or 16: a run of 32 / k of them is one block-diagonal block of 32, which is how every
+// entry point below runs them (embed into scratch, call itself with blocks of 32, gather the gradient's diagonal
+// sub-blocks).  small_m: 32 / k for those sizes, 0 for any other.
+int small_m(int k) { return (k == 2 || k == 4 || k == 8 || k == 16) ? 32 / k : 0; }
+struct SmallWs { float *T32, *P32, *G32; int* st32; void* sub; size_t head; };
+SmallWs carve_small(void* ws, int64_t nb32) {
+  Carver c(ws);
+  SmallWs w;
+  w.T32 = c.take<float>(size_t(nb32) * 1024);
+  w.P32 = c.take<float>(size_t(nb32) * 1024);
+  w.G32 = c.take<float>(size_t(nb32) * 1024);
+  w.st32 = c.take<int>(size_t(nb32));
+  w.head = c.off;
+  w.sub = ws ? static_cast<char*>(ws) + c.off : nullptr;
+  return w;
+}
+// blocks of 32 that a small-block transform over `naxis` indices makes (0: not a whole number)
+int64_t small_nb32(const cafeq_xform* x, int64_t naxis) {
+  if (naxis % 32 != 0 || naxis != int64_t(x->nb) * x->rep * x->k) return 0;
+  return naxis / 32;
+}
+int check_small_xform(const cafeq_xform* x, bool need_inv) {
+  if (!x || !x->T || (need_inv && !x->Tinv)) return CAFEQ_ERR_INVALID_ARG;
+  if (x->nb <= 0 || x->rep <= 0) return CAFEQ_ERR_BAD_SHAPE;
+  if (!aligned16(x->T) || (x->Tinv && !aligned16(x->Tinv))) return CAFEQ_ERR_BAD_ALIGN;
+  return CAFEQ_OK;
+}
+size_t orth_ws_any(int k, int nb) {
+  if (!small_m(k)) return orth_workspace_bytes(k, nb);
+  const int64_t nb32 = int64_t(nb) * k / 32;
+  return carve_small(nullptr, nb32).head + orth_workspace_bytes(32, int(nb32));
+}
+
 struct AdaptivePlan {
   GroupPlan ga, gb;
   int nchunkA, nchunkB;
@@ -529,7 +562,7 @@ OptWs carve_opt(void* ws, int k, int nb) {
   OptWs w;
   w.grad = reinterpret_cast<float*>(base);
   w.orth = base + align_up(size_t(nb) * k * k * sizeof(float), 256);
-  w.sub = static_cast<char*>(w.orth) + orth_workspace_bytes(k, nb);
+  w.sub = static_cast<char*>(w.orth) + orth_ws_any(k, nb);
   return w;
 }
 // The inverse of iteration s of a learning loop: from scratch first, then warm-started from the previous one.
@@ -608,6 +641,31 @@ int cafeq_set_launch_timing(cafeq_launch_timing* t) {
 
 size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b, const cafeq_xform* x,
                              const cafeq_quant_cfg* cfg) {
+  if (x && small_m(x->k) && call_id != CAFEQ_CALL_ORTH_PENALTY && call_id != CAFEQ_CALL_OPTIMIZE_SINGLE &&
+      call_id != CAFEQ_CALL_OPTIMIZE_PAIR) {
+    // blocks smaller than 32: the embedding's scratch in front of what the same call needs with blocks of 32
+    int64_t nb32 = 0;
+    switch (call_id) {
+      case CAFEQ_CALL_PROXY_LOSS:
+        if (!a || !cfg) return 0;
+        nb32 = small_nb32(x, cfg->axis == CAFEQ_AXIS_COL ? a->cols : a->rows);
+        break;
+      case CAFEQ_CALL_DUAL_PROXY_LOSS:
+        if (!a || x->rep != 1) return 0;
+        nb32 = small_nb32(x, a->cols);
+        break;
+      case CAFEQ_CALL_APPLY_TRANSFORM:
+      case CAFEQ_CALL_BLOCK_INVERSE:
+        nb32 = (int64_t(x->nb) * (x->rep > 0 ? x->rep : 1) * x->k) / 32;
+        if (nb32 * 32 != int64_t(x->nb) * (x->rep > 0 ? x->rep : 1) * x->k) nb32 = 0;
+        break;
+      default: return 0;   // Alg. 1 and the paired error work per head: blocks of 32 and more
+    }
+    if (nb32 <= 0 || nb32 > (int64_t(1) << 30)) return 0;
+    const cafeq_xform x32{nullptr, nullptr, 32, int(nb32), 1};
+    const size_t sub = cafeq_workspace_bytes(call_id, a, b, &x32, cfg);
+    return sub ? carve_small(nullptr, nb32).head + sub : 0;
+  }
   switch (call_id) {
     case CAFEQ_CALL_RTN_QUANTIZE:
       if (!a) return 0;
@@ -649,7 +707,7 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
     }
     case CAFEQ_CALL_ORTH_PENALTY:
       if (!x) return 0;
-      return orth_workspace_bytes(x->k, x->nb);
+      return orth_ws_any(x->k, x->nb);
     case CAFEQ_CALL_OPTIMIZE_SINGLE:
     case CAFEQ_CALL_OPTIMIZE_PAIR: {
       // gradient buffer + regulariser scratch + the larger of the sub-calls' workspaces
@@ -659,7 +717,7 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
                                 a, b, x, cfg),
           cafeq_workspace_bytes(CAFEQ_CALL_BLOCK_INVERSE, a, b, x, cfg));
       if (sub == 0) return 0;
-      return align_up(size_t(x->nb) * x->k * x->k * sizeof(float), 256) + orth_workspace_bytes(x->k, x->nb) + sub;
+      return align_up(size_t(x->nb) * x->k * x->k * sizeof(float), 256) + orth_ws_any(x->k, x->nb) + sub;
     }
     case CAFEQ_CALL_PQE: {
       if (!a || !b || !x || !cfg) return 0;
@@ -747,6 +805,22 @@ int cafeq_block_inverse(const float* T, int k, int nb, float* Tinv, float* rho_r
                         int* status, void* ws, void* stream) {
   if (!T || !Tinv) return CAFEQ_ERR_INVALID_ARG;
   if (nb < 1) return CAFEQ_ERR_BAD_SHAPE;
+  if (const int m = small_m(k)) {
+    // a run of 32 / k blocks as one block-diagonal block of 32 (its inverse is block-diagonal too; the squared
+    // row / column norms keep their positions; a singular block marks its whole run)
+    if (nb % m != 0) return CAFEQ_ERR_BAD_SHAPE;
+    if (!ws) return CAFEQ_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int nb32 = nb / m;
+    const SmallWs w = carve_small(ws, nb32);
+    int rc;
+    if ((rc = launch_embed_blocks(T, k, nb, 1, nb32, w.T32, st))) return rc;
+    if ((rc = cafeq_block_inverse(w.T32, 32, nb32, w.P32, rho_row, rho_col, status ? w.st32 : nullptr, w.sub, stream)))
+      return rc;
+    if ((rc = launch_gather_blocks(w.P32, k, nb, 1, Tinv, st))) return rc;
+    if (status && (rc = launch_expand_status(w.st32, m, nb, status, st))) return rc;
+    return CAFEQ_OK;
+  }
   if (k != 32 && k != 64 && k != 128 && k != 256) return CAFEQ_ERR_UNSUPPORTED;
   if (!ws) return CAFEQ_ERR_WORKSPACE;
   return launch_block_inverse(T, k, nb, static_cast<double*>(ws), Tinv, rho_row, rho_col, status,
@@ -758,6 +832,19 @@ int cafeq_apply_transform(const cafeq_mat* W, const cafeq_xform* x, int axis, in
   int rc = check_mat(W);
   if (rc) return rc;
   if (side != CAFEQ_SIDE_T && side != CAFEQ_SIDE_TINV) return CAFEQ_ERR_INVALID_ARG;
+  if (x && small_m(x->k)) {
+    if ((rc = check_small_xform(x, side == CAFEQ_SIDE_TINV))) return rc;
+    if ((rc = check_axis_len(W, x, axis))) return rc;
+    if (!ws) return CAFEQ_ERR_WORKSPACE;
+    const int64_t nb32 = small_nb32(x, axis == CAFEQ_AXIS_COL ? W->cols : W->rows);
+    if (nb32 <= 0) return CAFEQ_ERR_BAD_SHAPE;
+    const SmallWs w = carve_small(ws, nb32);
+    if ((rc = launch_embed_blocks(side == CAFEQ_SIDE_T ? x->T : x->Tinv, x->k, x->nb, x->rep, int(nb32), w.T32,
+                                  static_cast<hipStream_t>(stream))))
+      return rc;
+    const cafeq_xform x32{w.T32, w.T32, 32, int(nb32), 1};
+    return cafeq_apply_transform(W, &x32, axis, side, Z, w.sub, stream);
+  }
   rc = check_xform(x, side == CAFEQ_SIDE_TINV);
   if (rc) return rc;
   rc = check_axis_len(W, x, axis);
@@ -792,6 +879,22 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   if (rc) return rc;
   rc = check_cfg(cfg, true, true);
   if (rc) return rc;
+  if (x && small_m(x->k)) {
+    if ((rc = check_small_xform(x, true))) return rc;
+    if ((rc = check_axis_len(W, x, cfg->axis))) return rc;
+    if (!ws) return CAFEQ_ERR_WORKSPACE;
+    if (gradT && !aligned16(gradT)) return CAFEQ_ERR_BAD_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t nb32 = small_nb32(x, cfg->axis == CAFEQ_AXIS_COL ? W->cols : W->rows);
+    if (nb32 <= 0) return CAFEQ_ERR_BAD_SHAPE;
+    const SmallWs w = carve_small(ws, nb32);
+    if ((rc = launch_embed_blocks(x->T, x->k, x->nb, x->rep, int(nb32), w.T32, st))) return rc;
+    if ((rc = launch_embed_blocks(x->Tinv, x->k, x->nb, x->rep, int(nb32), w.P32, st))) return rc;
+    const cafeq_xform x32{w.T32, w.P32, 32, int(nb32), 1};
+    if ((rc = cafeq_proxy_loss_fwd_bwd(W, &x32, cfg, losses, gradT ? w.G32 : nullptr, codes, scales, w.sub, stream)))
+      return rc;
+    return gradT ? launch_gather_blocks(w.G32, x->k, x->nb, x->rep, gradT, st) : CAFEQ_OK;
+  }
   rc = check_xform(x, true);
   if (rc) return rc;
   rc = check_axis_len(W, x, cfg->axis);
@@ -879,6 +982,25 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   if (rc) return rc;
   rc = check_cfg(cfg, false, true);
   if (rc) return rc;
+  if (x && small_m(x->k)) {
+    // (row-blocks that share a small block do not line up with blocks of 32: rep must be 1 here)
+    if ((rc = check_small_xform(x, true))) return rc;
+    if (x->rep != 1) return CAFEQ_ERR_UNSUPPORTED;
+    if (A->cols != int64_t(x->nb) * x->k || B->rows != A->cols) return CAFEQ_ERR_BAD_SHAPE;
+    if (!ws) return CAFEQ_ERR_WORKSPACE;
+    if (gradT && !aligned16(gradT)) return CAFEQ_ERR_BAD_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t nb32 = small_nb32(x, A->cols);
+    if (nb32 <= 0) return CAFEQ_ERR_BAD_SHAPE;
+    const SmallWs w = carve_small(ws, nb32);
+    if ((rc = launch_embed_blocks(x->T, x->k, x->nb, 1, int(nb32), w.T32, st))) return rc;
+    if ((rc = launch_embed_blocks(x->Tinv, x->k, x->nb, 1, int(nb32), w.P32, st))) return rc;
+    const cafeq_xform x32{w.T32, w.P32, 32, int(nb32), 1};
+    if ((rc = cafeq_dual_proxy_loss_fwd_bwd(A, B, &x32, cfg, lse_t, losses, gradT ? w.G32 : nullptr, codesU, scalesU,
+                                            codesV, scalesV, w.sub, stream)))
+      return rc;
+    return gradT ? launch_gather_blocks(w.G32, x->k, x->nb, 1, gradT, st) : CAFEQ_OK;
+  }
   rc = check_xform(x, true);
   if (rc) return rc;
   if (!losses) return CAFEQ_ERR_INVALID_ARG;

@@ -120,6 +120,12 @@ int launch_pqe(const float* U, const float* V, int64_t rowsA, int64_t colsA, int
                const float* scalesV, int64_t chunkA, int nchunkA, int64_t chunkB, int nchunkB, float* partialU,
                float* partialV, double* sums, float* out, hipStream_t st);
 int launch_fill(float* p, float value, int64_t n, hipStream_t st);
+// blocks smaller than 32 as block-diagonal blocks of 32 (opt_kernels.hip): T32[nb32][32][32] from T[nb][k][k]
+// (row-block q of the small transform uses block q / rep); G[nb][k][k] gathered from the diagonal sub-blocks
+int launch_embed_blocks(const float* T, int k, int nb, int rep, int nb32, float* T32, hipStream_t st);
+int launch_gather_blocks(const float* G32, int k, int nb, int rep, float* G, hipStream_t st);
+int launch_expand_status(const int* st32, int m, int nb, int* status, hipStream_t st);
+int launch_axpy(float* y, const float* x, float alpha, int64_t n, hipStream_t st);   // y += alpha x
 size_t orth_workspace_bytes(int k, int nb);
 int launch_div_by_device_scalar(float* g, const float* denom, int64_t n, hipStream_t st);
 }  // namespace cafeq

@@ -125,6 +125,81 @@ size_t orth_workspace_bytes(int k, int nb) {
          256;
 }
 
+
+// ---------------------------------------------------------------------------------------------------
+// Transform blocks smaller than 32 (the paper's block-size sweep goes down to 2): a run of 32 / k consecutive
+// k x k blocks IS one 32 x 32 block that happens to be block-diagonal, so every kernel written for blocks of 32
+// serves them.  embed: T32[Q] = blockdiag_i( T[(Q m + i) / rep] ), m = 32 / k (blocks past the end: identity);
+// gather: G[b] = sum over the positions block b was placed at of the k x k diagonal sub-block there (chain rule:
+// the entries outside the diagonal sub-blocks are derivatives with respect to entries that stay zero), in the
+// fixed order of the positions.
+namespace {
+__global__ __launch_bounds__(256) void embed_blocks_kernel(const float* __restrict__ T, int k, int nb, int rep, int nb32,
+                                                            float* __restrict__ T32) {
+  const int64_t e = int64_t(blockIdx.x) * 256 + threadIdx.x;
+  if (e >= int64_t(nb32) * 1024) return;
+  const int Q = int(e >> 10), r = int(e >> 5) & 31, c = int(e) & 31;
+  const int m = 32 / k, i = r / k;
+  float v = 0.f;
+  if (c / k == i) {
+    const int64_t sb = (int64_t(Q) * m + i) / rep;
+    v = sb < nb ? T[(sb * k + r % k) * k + c % k] : (r == c ? 1.f : 0.f);
+  }
+  T32[e] = v;
+}
+__global__ __launch_bounds__(256) void gather_blocks_kernel(const float* __restrict__ G32, int k, int nb, int rep,
+                                                             float* __restrict__ G) {
+  const int64_t e = int64_t(blockIdx.x) * 256 + threadIdx.x;
+  if (e >= int64_t(nb) * k * k) return;
+  const int b = int(e / (k * k)), r = int(e / k) % k, c = int(e % k);
+  const int m = 32 / k;
+  float acc = 0.f;
+  for (int j = 0; j < rep; ++j) {
+    const int64_t q = int64_t(b) * rep + j;
+    const int64_t Q = q / m;
+    const int i = int(q % m);
+    acc += G32[(Q * 32 + i * k + r) * 32 + i * k + c];
+  }
+  G[e] = acc;
+}
+}  // namespace
+
+namespace {
+__global__ __launch_bounds__(256) void axpy_kernel(float* __restrict__ y, const float* __restrict__ x, float alpha, int64_t n) {
+  const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
+  if (i < n) y[i] += alpha * x[i];
+}
+}  // namespace
+int launch_axpy(float* y, const float* x, float alpha, int64_t n, hipStream_t st) {
+  hipLaunchKernelGGL(axpy_kernel, dim3(unsigned((n + 255) / 256)), dim3(256), 0, st, y, x, alpha, n);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+namespace {
+__global__ __launch_bounds__(256) void expand_status_kernel(const int* __restrict__ st32, int m, int nb, int* __restrict__ status) {
+  const int b = blockIdx.x * 256 + threadIdx.x;
+  if (b < nb) status[b] = st32[b / m];
+}
+}  // namespace
+int launch_expand_status(const int* st32, int m, int nb, int* status, hipStream_t st) {
+  hipLaunchKernelGGL(expand_status_kernel, dim3(unsigned((nb + 255) / 256)), dim3(256), 0, st, st32, m, nb, status);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+
+int launch_embed_blocks(const float* T, int k, int nb, int rep, int nb32, float* T32, hipStream_t st) {
+  const int64_t n = int64_t(nb32) * 1024;
+  hipLaunchKernelGGL(embed_blocks_kernel, dim3(unsigned((n + 255) / 256)), dim3(256), 0, st, T, k, nb, rep, nb32, T32);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+int launch_gather_blocks(const float* G32, int k, int nb, int rep, float* G, hipStream_t st) {
+  const int64_t n = int64_t(nb) * k * k;
+  hipLaunchKernelGGL(gather_blocks_kernel, dim3(unsigned((n + 255) / 256)), dim3(256), 0, st, G32, k, nb, rep, G);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+
 }  // namespace cafeq
 
 using namespace cafeq;
@@ -135,6 +210,30 @@ int cafeq_orth_penalty(const float* T, int k, int nb, float lambda, float* value
                        void* stream) {
   if (!T || (!value && !gradT)) return CAFEQ_ERR_INVALID_ARG;
   if (nb < 1) return CAFEQ_ERR_BAD_SHAPE;
+  if (k == 2 || k == 4 || k == 8 || k == 16) {
+    // a run of 32 / k blocks as one block-diagonal block of 32: T T^T - I keeps its Frobenius norm and d = nb k;
+    // the gradient is gathered from the diagonal sub-blocks and ADDED, as for the larger blocks
+    const int m = 32 / k;
+    if (nb % m != 0) return CAFEQ_ERR_BAD_SHAPE;
+    if (!ws) return CAFEQ_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int nb32 = nb / m;
+    const size_t blk = align_up(size_t(nb32) * 1024 * sizeof(float), 256);
+    char* base = static_cast<char*>(ws);
+    float* T32 = reinterpret_cast<float*>(base);
+    float* G32 = reinterpret_cast<float*>(base + blk);
+    float* Gs = reinterpret_cast<float*>(base + 2 * blk);   // gathered gradient [nb][k][k]
+    void* sub = base + 3 * blk + align_up(size_t(nb32) * sizeof(int), 256);
+    int rc;
+    if ((rc = launch_embed_blocks(T, k, nb, 1, nb32, T32, st))) return rc;
+    if (gradT && (rc = launch_fill(G32, 0.f, int64_t(nb32) * 1024, st))) return rc;
+    if ((rc = cafeq_orth_penalty(T32, 32, nb32, lambda, value, gradT ? G32 : nullptr, sub, stream))) return rc;
+    if (gradT) {
+      if ((rc = launch_gather_blocks(G32, k, nb, 1, Gs, st))) return rc;
+      if ((rc = launch_axpy(gradT, Gs, 1.f, int64_t(nb) * k * k, st))) return rc;
+    }
+    return CAFEQ_OK;
+  }
   if (k != 32 && k != 64 && k != 128 && k != 256) return CAFEQ_ERR_UNSUPPORTED;
   if (!ws) return CAFEQ_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
