@@ -257,7 +257,8 @@ struct GjArgs {
   float* out;            // [nb][K][K]
   float* rho_row; float* rho_col;  // optional squared row / column norms of the inverse
   int* status; int status_stride, status_offset;
-  const int* need;       // optional [nb]: blocks whose entry is 0 are already done (see rotation_inverse_kernel)
+  const int* need;       // optional [nb][need_n]: blocks whose entries are all 0 are already done (see
+  int need_n = 1;        // rotation_inverse_kernel, rotation_slice_kernel)
 };
 
 // Compile-time loop: f(integral_constant<int, I>) for I in [B, E).
@@ -333,7 +334,11 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_panel_kernel(const GjA
   __shared__ int deadflag;
   __shared__ S wred[16];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
-  if (a.need && a.need[b] == 0) return;   // uniform over the workgroup
+  if (a.need) {                           // uniform over the workgroup
+    int any = 0;
+    for (int i = 0; i < a.need_n; ++i) any |= a.need[b * a.need_n + i];
+    if (!any) return;
+  }
   const int rt = tid / NCT, ct = tid % NCT;
   S reg[RT][CT];
   if (a.partial == nullptr) {
@@ -795,6 +800,103 @@ __global__ __launch_bounds__((K / 32) * (K / 32) * 64) void rotation_inverse_ker
   }
   if (status && tid == 0) status[b] = 0;
 }
+// The same for blocks of 128 with four workgroups per block, one per slice of 32 rows of T (one workgroup per
+// block keeps sixteen waves on one compute unit's float32 matrix pipe for 10 us; the 112 blocks of the 9B-shaped
+// pair leave more than half of the chip idle).  Every slice loads the whole block (transposed, into LDS), checks
+// its own rows -- unit length, then its 32 x 128 slice of R = I - T T^T, one 32 x 32 tile per wave -- and, if
+// they pass, writes its share of the result: columns 32 s .. of Tinv = T^T, their squared norms, and the squared
+// norms of the rows 32 s .. of Tinv.  need[4 b + s] = 0 / 1; a block with any slice failing is redone as a whole
+// by the elimination kernel, which runs afterwards and overwrites what the passing slices wrote.
+__global__ __launch_bounds__(256) void rotation_slice_kernel(const float* __restrict__ T, float* __restrict__ Tinv,
+                                                             float* __restrict__ rho_row, float* __restrict__ rho_col,
+                                                             int* __restrict__ status, int* __restrict__ need) {
+  constexpr int K = 128, LD = K + 1;
+  extern __shared__ __align__(16) float nsm[];
+  float* bufX = nsm;                 // T^T[l][j]
+  float* red = bufX + K * LD;        // [4]
+  const int b = blockIdx.x >> 2, sl = blockIdx.x & 3;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ln = lane & 31, h = lane >> 5;
+  const float* Tb = T + size_t(b) * K * K;
+  for (int e = tid * 4; e < K * K; e += 256 * 4) {
+    const float4 v = *reinterpret_cast<const float4*>(Tb + e);
+    const int r = e / K, c = e % K;
+    bufX[(c + 0) * LD + r] = v.x; bufX[(c + 1) * LD + r] = v.y;
+    bufX[(c + 2) * LD + r] = v.z; bufX[(c + 3) * LD + r] = v.w;
+  }
+  __syncthreads();
+  // squared lengths of this slice's rows of T (= columns of Tinv) and of its columns (= rows of Tinv): eight
+  // threads per vector, sixteen terms each, combined through LDS in fixed order
+  float* part = red + 4;             // [2][8][32]
+  {
+    const int i = sl * 32 + (tid & 31), q = tid >> 5;
+    float a0 = 0.f, a1 = 0.f;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+      const float x = bufX[(16 * q + c) * LD + i];   // T[i][16 q + c]
+      const float y = bufX[i * LD + 16 * q + c];     // T[16 q + c][i]
+      a0 = fmaf(x, x, a0);
+      a1 = fmaf(y, y, a1);
+    }
+    part[q * 32 + (tid & 31)] = a0;
+    part[256 + q * 32 + (tid & 31)] = a1;
+  }
+  __syncthreads();
+  float n2row = 0.f, n2col = 0.f;
+  // cheap necessary condition first: rows of unit length
+  {
+    float dev = 0.f;
+    if (tid < 32) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) { n2row += part[q * 32 + tid]; n2col += part[256 + q * 32 + tid]; }
+      dev = fabsf(n2row - 1.f);
+      if (!(dev <= 3.0e38f)) dev = INFINITY;
+    }
+    dev = cluster_allmax<64>(dev);
+    if (lane == 0) red[wave] = dev;
+    __syncthreads();
+    const float dmax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    if (!(dmax <= 4e-6f)) {
+      if (tid == 0) need[blockIdx.x] = 1;
+      return;
+    }
+  }
+  floatx16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  {
+    const float* pa = bufX + h * LD + sl * 32 + ln;      // a(l, i) = T[i][l] = T^T[l][i], l = 2 s + h
+    const float* pb = bufX + h * LD + wave * 32 + ln;    // b(l, j) = T^T[l][j]
+#pragma unroll 8
+    for (int s2 = 0; s2 < K / 2; ++s2) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[2 * s2 * LD], pb[2 * s2 * LD], acc, 0, 0, 0);
+  }
+  float m = 0.f;
+  bool bad = false;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int i = sl * 32 + 8 * (v / 4) + 4 * h + (v % 4), j = wave * 32 + ln;
+    const float ar = fabsf((i == j ? 1.f : 0.f) - acc[v]);
+    bad = bad || !(ar <= 3.0e38f);
+    m = fmaxf(m, ar);
+  }
+  if (bad) m = INFINITY;
+  m = cluster_allmax<64>(m);
+  if (lane == 0) red[wave] = m;
+  __syncthreads();
+  const float rmax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  const bool ok = rmax <= 2e-6f;
+  if (tid == 0) need[blockIdx.x] = ok ? 0 : 1;
+  if (!ok) return;
+  // Tinv[j][i] = T[i][j] for the slice's i: 32 consecutive floats of every row j
+  float* O = Tinv + size_t(b) * K * K + sl * 32;
+  for (int e = tid; e < K * 32; e += 256) O[(e >> 5) * K + (e & 31)] = bufX[(e >> 5) * LD + sl * 32 + (e & 31)];
+  if (tid < 32) {
+    const int i = sl * 32 + tid;
+    if (rho_col) rho_col[size_t(b) * K + i] = n2row;      // column i of Tinv is row i of T
+    if (rho_row) rho_row[size_t(b) * K + i] = n2col;      // row i of Tinv is column i of T
+  }
+  if (status && tid == 0) status[b] = 0;
+}
 // Warm start for the learning loops, where the transform moves a little per iteration and the previous
 // inverse X_0 is at hand: Newton's iteration  X <- X + X (I - T X), one workgroup per block, one wave per
 // 32 x 32 tile, T and X in LDS; residuals on the float32 matrix pipe, corrections with bfloat16 operands.  The residual R = I - T X is measured every round;
@@ -1037,14 +1139,17 @@ int launch_block_inverse(const float* T, int K, int nb, double* work, float* Tin
     int* need = reinterpret_cast<int*>(work);
     const size_t lds = size_t(2 * K * (K + 1) + (K / 32) * (K / 32)) * sizeof(float);
     if (K == 128) {
+      // four workgroups per block, one per slice of 32 rows (flags need[4 b + slice])
+      const size_t lds4 = size_t(K * (K + 1) + 4 + 512) * sizeof(float);
       static std::atomic<bool> attr_set{false};
       if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(rotation_inverse_kernel<128>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(rotation_slice_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(lds4)) != hipSuccess)
           return CAFEQ_ERR_LAUNCH;
         attr_set = true;
       }
-      hipLaunchKernelGGL(rotation_inverse_kernel<128>, dim3(nb), dim3(1024), lds, st, T, Tinv, rho_row, rho_col, status, need);
+      hipLaunchKernelGGL(rotation_slice_kernel, dim3(4 * nb), dim3(256), lds4, st, T, Tinv, rho_row, rho_col, status, need);
+      a.need_n = 4;
     } else {
       hipLaunchKernelGGL(rotation_inverse_kernel<64>, dim3(nb), dim3(256), lds, st, T, Tinv, rho_row, rho_col, status, need);
     }

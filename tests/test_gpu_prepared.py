@@ -190,3 +190,32 @@ def test_prepared_gradient_pass_ragged_lines_and_many_tiles(env):
     _check_single_prepared(env, W, T, P, 3, 128, O.COL, 1, want_codes=False)
     W, T, P = _case(O.ROW, 1000, 512, 128, 2, 1752)
     _check_single_prepared(env, W, T, P, 3, 32, O.ROW, 2, want_codes=False)
+
+
+@pytest.mark.parametrize("lines", [100, 200, 300, 520])
+def test_prepared_pair_with_one_workgroup_per_block(env, lines):
+    # 2 x 100 blocks of 128: the call takes the gradient pass that gives every (member, block) a workgroup of its
+    # own (its halves take even and odd tiles of 128 lines: 1, 2, 3 and 5 tiles here, the last one ragged), after
+    # a single loss launch for both members
+    torch, cafeq = env
+    A, B, T = WL.small_pair(lines, 12800, 128, 1, 1800 + lines, eps=0.05)
+    P = O.block_inverse(T).astype(np.float32)
+    Ad, Bd = _dev(torch, A), _dev(torch, B)
+    prep = (cafeq.prepare_weights(Ad, O.COL), cafeq.prepare_weights(Bd, O.ROW))
+    losses, grad, _ = cafeq.dual_proxy_loss_fwd_bwd(Ad, Bd, _dev(torch, T), _dev(torch, P), 3, 128, 1, 5.0, True, False,
+                                                    prepared=prep)
+    torch.cuda.synchronize()
+    losses = losses.cpu().numpy().astype(np.float64)
+    ref = O.dual_lse(A, B, T, P, 3, 128, 1, 5.0)
+    for i, name in enumerate(("errU_sq", "errV_sq", "l2A_sq", "l2B_sq", "lse")):
+        parity.check_scalar(losses[i], ref[name], what=name)
+    slack, n_amb = parity.dual_argmax_flip_slack(A, B, T, P, ref, 128, 1, 5.0)
+    assert n_amb <= 3
+    parity.check_grad_with_slack(grad.cpu().numpy(), ref["gradT"], slack)
+
+
+def test_prepared_single_with_one_workgroup_per_block(env):
+    # 160 blocks: the single-matrix call takes the same gradient pass (surrogate coefficients)
+    for axis, group in ((O.COL, 64), (O.ROW, 128)):
+        W, T, P = _case(axis, 200, 20480, 128, 1, 1900 + group)
+        _check_single_prepared(env, W, T, P, 4, group, axis, 1, want_codes=False)
