@@ -2,6 +2,7 @@
 // (M^-1)_{ij}^2 factors of the paper's surrogate, Sec. 4.1), fixed-order reduction of the
 // per-workgroup partials and the k x k products of the gradient's path through M^-1.  All are off the bandwidth path (k x k sized per block).
 #include <atomic>
+#include "cafeq_internal.hpp"
 #include "xform_core.hpp"
 
 namespace cafeq {
@@ -444,7 +445,8 @@ __global__ __launch_bounds__(256) void bgemm_kernel(const float* __restrict__ A,
 // there is one barrier -- at 65 KB of LDS, two workgroups per compute unit.
 template <bool TA, bool TB, int CH>
 __global__ __launch_bounds__(256) void bgemm_mfma_kernel(const float* __restrict__ A, const float* __restrict__ B,
-                                                          float* __restrict__ C, int K, float alpha, float beta) {
+                                                          float* __restrict__ C, int K, float alpha, float beta,
+                                                          const AdamHook adam) {
   constexpr int LD = 65;
   extern __shared__ __align__(16) float bsm[];
   float* sa = bsm;
@@ -503,7 +505,18 @@ __global__ __launch_bounds__(256) void bgemm_mfma_kernel(const float* __restrict
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int i = i0 + wi * 32 + 8 * (v / 4) + 4 * h + (v % 4), j = j0 + wj * 32 + ln;
-    Cb[i * K + j] = alpha * acc[v] + (beta != 0.f ? beta * cold[v] : 0.f);
+    const float g = alpha * acc[v] + (beta != 0.f ? beta * cold[v] : 0.f);
+    if (adam.T) {
+      // (the arithmetic of adam_kernel, on the gradient still in its register)
+      const size_t at = size_t(b) * K * K + size_t(i) * K + j;
+      const float mi = adam.beta1 * adam.m[at] + adam.omb1 * g;
+      const float vi = adam.beta2 * adam.v[at] + adam.omb2 * g * g;
+      adam.m[at] = mi;
+      adam.v[at] = vi;
+      adam.T[at] -= adam.lr * (mi * adam.c1) / (sqrtf(vi * adam.c2) + adam.eps);
+    } else {
+      Cb[i * K + j] = g;
+    }
   }
 }
 
@@ -618,7 +631,13 @@ int launch_reduce_losses(int kind, const float* hdrA, int nslotA, const float* h
   return CAFEQ_OK;
 }
 int launch_bgemm(bool ta, bool tb, const float* A, const float* B, float* C, int K, int nb, float alpha,
-                 float beta, hipStream_t st) {
+                 float beta, hipStream_t st, const AdamHook* adam) {
+  AdamHook hook;
+  hook.T = nullptr;
+  if (adam) {
+    if (K == 32) return CAFEQ_ERR_INVALID_ARG;
+    hook = *adam;
+  }
   if (K == 32) {
 #define CAFEQ_G32(TA, TB) hipLaunchKernelGGL((bgemm32_kernel<TA, TB>), dim3(nb), dim3(256), 0, st, A, B, C, alpha, beta)
     if (ta && tb) CAFEQ_G32(true, true); else if (ta) CAFEQ_G32(true, false);
@@ -640,13 +659,13 @@ int launch_bgemm(bool ta, bool tb, const float* A, const float* B, float* C, int
         if (!ok) return CAFEQ_ERR_LAUNCH;
         attr_set = true;
       }
-#define CAFEQ_G128(TA, TB) hipLaunchKernelGGL((bgemm_mfma_kernel<TA, TB, CH>), dim3(grid), dim3(256), lds, st, A, B, C, K, alpha, beta)
+#define CAFEQ_G128(TA, TB) hipLaunchKernelGGL((bgemm_mfma_kernel<TA, TB, CH>), dim3(grid), dim3(256), lds, st, A, B, C, K, alpha, beta, hook)
       if (ta && tb) CAFEQ_G128(true, true); else if (ta) CAFEQ_G128(true, false);
       else if (tb) CAFEQ_G128(false, true); else CAFEQ_G128(false, false);
 #undef CAFEQ_G128
     } else {
       constexpr size_t lds = 2 * 64 * 65 * sizeof(float);
-#define CAFEQ_G64(TA, TB) hipLaunchKernelGGL((bgemm_mfma_kernel<TA, TB, 64>), dim3(grid), dim3(256), lds, st, A, B, C, K, alpha, beta)
+#define CAFEQ_G64(TA, TB) hipLaunchKernelGGL((bgemm_mfma_kernel<TA, TB, 64>), dim3(grid), dim3(256), lds, st, A, B, C, K, alpha, beta, hook)
       if (ta && tb) CAFEQ_G64(true, true); else if (ta) CAFEQ_G64(true, false);
       else if (tb) CAFEQ_G64(false, true); else CAFEQ_G64(false, false);
 #undef CAFEQ_G64

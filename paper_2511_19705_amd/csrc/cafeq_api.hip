@@ -577,6 +577,10 @@ int check_opt(const cafeq_opt_cfg* opt) {
 }
 }  // namespace
 
+static int dual_impl(const cafeq_mat* A, const cafeq_mat* B, const cafeq_xform* x, const cafeq_quant_cfg* cfg,
+                     float lse_t, float* losses, float* gradT, int8_t* codesU, float* scalesU, int8_t* codesV,
+                     float* scalesV, void* ws, void* stream, const AdamHook* adam);
+
 int cafeq_optimize_single(const cafeq_mat* W, float* T, float* Tinv, int k, int nb, int rep,
                           const cafeq_quant_cfg* cfg, const cafeq_opt_cfg* opt, float* history, int* status,
                           void* ws, void* stream) {
@@ -616,9 +620,23 @@ int cafeq_optimize_pair(const cafeq_mat* A, const cafeq_mat* B, float* T, float*
   cafeq_xform x{T, Tinv, k, nb, rep};
   if ((rc = launch_fill(history, 0.f, int64_t(opt->steps) * 8, st))) return rc;
   if ((rc = launch_fill(moments, 0.f, 2 * n, st))) return rc;
+  const bool fuse_adam = !(opt->lambda_orth > 0.f) && (k == 64 || k == 128 || k == 256);
   for (int s = 0; s < opt->steps; ++s) {
     float* h = history + size_t(s) * 8;
     if ((rc = loop_inverse(s, T, k, nb, Tinv, status, w.sub, stream))) return rc;
+    if (fuse_adam) {
+      // the Adam step rides in the epilogue of the gradient's last kernel (no regulariser to add in between)
+      if (!(opt->beta1 >= 0.0 && opt->beta1 < 1.0 && opt->beta2 >= 0.0 && opt->beta2 < 1.0)) return CAFEQ_ERR_INVALID_ARG;
+      AdamHook hook;
+      hook.T = T; hook.m = moments; hook.v = moments + n;
+      hook.lr = float(opt->lr); hook.beta1 = float(opt->beta1); hook.omb1 = float(1.0 - opt->beta1);
+      hook.beta2 = float(opt->beta2); hook.omb2 = float(1.0 - opt->beta2); hook.eps = float(opt->eps);
+      hook.c1 = float(1.0 / (1.0 - pow(opt->beta1, double(s + 1))));
+      hook.c2 = float(1.0 / (1.0 - pow(opt->beta2, double(s + 1))));
+      if ((rc = dual_impl(A, B, &x, cfg, lse_t, h, w.grad, nullptr, nullptr, nullptr, nullptr, w.sub, stream, &hook)))
+        return rc;
+      continue;
+    }
     if ((rc = cafeq_dual_proxy_loss_fwd_bwd(A, B, &x, cfg, lse_t, h, w.grad, nullptr, nullptr, nullptr, nullptr, w.sub,
                                             stream)))
       return rc;
@@ -972,10 +990,11 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   return CAFEQ_OK;
 }
 
-int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const cafeq_xform* x,
-                                  const cafeq_quant_cfg* cfg, float lse_t, float* losses, float* gradT,
-                                  int8_t* codesU, float* scalesU, int8_t* codesV, float* scalesV,
-                                  void* ws, void* stream) {
+// adam (learning loop only; blocks of 64 and more): the last kernel of the gradient applies the Adam step to T, m
+// and v instead of storing the gradient (gradT is then scratch)
+static int dual_impl(const cafeq_mat* A, const cafeq_mat* B, const cafeq_xform* x, const cafeq_quant_cfg* cfg,
+                     float lse_t, float* losses, float* gradT, int8_t* codesU, float* scalesU, int8_t* codesV,
+                     float* scalesV, void* ws, void* stream, const AdamHook* adam) {
   int rc = check_mat(A);
   if (rc) return rc;
   rc = check_mat(B);
@@ -984,6 +1003,7 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
   if (rc) return rc;
   if (x && small_m(x->k)) {
     // (row-blocks that share a small block do not line up with blocks of 32: rep must be 1 here)
+    if (adam) return CAFEQ_ERR_INVALID_ARG;
     if ((rc = check_small_xform(x, true))) return rc;
     if (x->rep != 1) return CAFEQ_ERR_UNSUPPORTED;
     if (A->cols != int64_t(x->nb) * x->k || B->rows != A->cols) return CAFEQ_ERR_BAD_SHAPE;
@@ -1094,16 +1114,23 @@ int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const 
                                   grad_owner_job(B, CAFEQ_AXIS_ROW, qb, w.b, w.gp, 0)};
     if ((rc = launch_grad_v2_owner(jobs, 2, kLossLse, 0.f, lse_t, w.lse_ms, st))) return rc;
     if ((rc = launch_bgemm(true, false, x->Tinv, w.gp, w.x1, K, nb, 1.f, 0.f, st))) return rc;
-    if ((rc = launch_bgemm(false, true, w.x1, x->Tinv, gradT, K, nb, -1.f, 1.f, st))) return rc;
+    if ((rc = launch_bgemm(false, true, w.x1, x->Tinv, gradT, K, nb, -1.f, 1.f, st, adam))) return rc;
   } else if (grad) {
     // member A into gradT; member B: G_P of transform block b sums its rep row-blocks; d/dT = -P^T G_P P^T
     if ((rc = launch_reduce_grad_pair(ag, ga.Gk, qa.fused, qa.two ? w.member_ref : nullptr, gradT, bg, gb.Gk, qb.fused,
                                       qb.two ? w.member_ref + 1 : nullptr, w.gp, K, nb, w.lse_ms, st)))
       return rc;
     if ((rc = launch_bgemm(true, false, x->Tinv, w.gp, w.x1, K, nb, 1.f, 0.f, st))) return rc;
-    if ((rc = launch_bgemm(false, true, w.x1, x->Tinv, gradT, K, nb, -1.f, 1.f, st))) return rc;
+    if ((rc = launch_bgemm(false, true, w.x1, x->Tinv, gradT, K, nb, -1.f, 1.f, st, adam))) return rc;
   }
   return CAFEQ_OK;
+}
+
+int cafeq_dual_proxy_loss_fwd_bwd(const cafeq_mat* A, const cafeq_mat* B, const cafeq_xform* x,
+                                  const cafeq_quant_cfg* cfg, float lse_t, float* losses, float* gradT,
+                                  int8_t* codesU, float* scalesU, int8_t* codesV, float* scalesV,
+                                  void* ws, void* stream) {
+  return dual_impl(A, B, x, cfg, lse_t, losses, gradT, codesU, scalesU, codesV, scalesV, ws, stream, nullptr);
 }
 
 int cafeq_adaptive_round_step(const float* U, const float* V, int64_t rowsA, int64_t colsA, int64_t rowsB,

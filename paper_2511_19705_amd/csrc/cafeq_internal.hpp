@@ -101,8 +101,11 @@ int launch_build_mmid(const CoreParams& p, int K, int G, int nb, const float* P,
                       hipStream_t st);
 int launch_reduce_losses(int kind, const float* hdrA, int nslotA, const float* hdrB, int nslotB, float beta,
                          float t, int64_t ngroups, float* losses, double* lse_ms, hipStream_t st);
+// Adam step applied by the product's epilogue instead of storing the product: the value alpha op(A) op(B) + beta C is
+// taken as the gradient of element [b][i][j] and T, m, v are updated in place (C is only read).  K >= 64.
+struct AdamHook { float *T, *m, *v; float lr, beta1, omb1, beta2, omb2, eps, c1, c2; };
 int launch_bgemm(bool ta, bool tb, const float* A, const float* B, float* C, int K, int nb, float alpha,
-                 float beta, hipStream_t st);
+                 float beta, hipStream_t st, const AdamHook* adam = nullptr);
 // adaptive_kernels.hip
 int launch_gram_pair(int axis, const float* X, const int8_t* codes, const float* scales, int64_t rows,
                      int64_t cols, int K, int G, int nb, int rep, int64_t chunk, int nchunk, float* partial,
