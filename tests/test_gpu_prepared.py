@@ -219,3 +219,40 @@ def test_prepared_single_with_one_workgroup_per_block(env):
     for axis, group in ((O.COL, 64), (O.ROW, 128)):
         W, T, P = _case(axis, 200, 20480, 128, 1, 1900 + group)
         _check_single_prepared(env, W, T, P, 4, group, axis, 1, want_codes=False)
+
+
+def test_prepared_weights_with_padded_rows(env):
+    # a view with a leading dimension larger than its width: the preparation reads through it, the passes over the
+    # prepared copies never see it
+    torch, cafeq = env
+    W, T, P = _case(O.COL, 200, 512, 128, 1, 1950)
+    big = torch.zeros((200, 640), dtype=torch.float32, device="cuda:0")
+    big[:, :512] = _dev(torch, W)
+    Wd = big[:, :512]
+    assert Wd.stride(0) == 640
+    prep = cafeq.prepare_weights(Wd, O.COL)
+    losses, grad, _, _ = cafeq.proxy_loss_fwd_bwd(Wd, _dev(torch, T), _dev(torch, P), 4, 128, O.COL, prepared=prep)
+    torch.cuda.synchronize()
+    ref = O.proxy_l2(W, T, P, 4, 128, O.COL)
+    parity.check_scalar(float(losses[0]), ref["l2_sq"], what="l2_sq")
+    parity.check_scalar(float(losses[2]), ref["w_sq"], what="w_sq")
+    parity.check_grad(grad.cpu().numpy(), O.surrogate(W, T, P, 4, 128, O.COL)[1])
+
+
+def test_launch_timing_samples_every_nth_launch(env):
+    # the measurement aid: with every = 3, launches 0, 3, 6, ... of the loss pass are bracketed by the caller's events
+    torch, cafeq = env
+    W, T, P = _case(O.COL, 200, 512, 128, 1, 1960)
+    Wd, Td, Pd = _dev(torch, W), _dev(torch, T), _dev(torch, P)
+    timer = cafeq.LaunchTimer(8, every=3)
+    with timer:
+        for _ in range(7):
+            cafeq.proxy_loss_fwd_bwd(Wd, Td, Pd, 4, 128, O.COL, want_grad=False)
+        torch.cuda.synchronize()
+    assert timer.table.seen == 7 and timer.table.count == 3
+    d = timer.durations_ms()
+    assert len(d) == 3 and all(x > 0 for x in d)
+    # without a table nothing is recorded
+    cafeq.proxy_loss_fwd_bwd(Wd, Td, Pd, 4, 128, O.COL, want_grad=False)
+    torch.cuda.synchronize()
+    assert timer.table.seen == 7
