@@ -78,6 +78,23 @@ __device__ __forceinline__ void loss_v2_body(const CoreParams& p, const unsigned
 #pragma unroll
   for (int i = 0; i < NGRP; ++i) s_va2[i] = 0.f;
 
+  // Prepared B operands of the strip the next forward phase transforms, and that strip's line scale factor.
+  // They are requested a whole vector phase ahead of their use (at the start of the vector phase of the strip
+  // before, across run boundaries too), so that their latency never reaches the matrix pipe: requested at the
+  // start of the matrix phase they had only the inverse transform (about a microsecond) to arrive in.
+  uintx4 wq[16];
+  float lsc_nx = 0.f;
+  auto request_strip = [&](int sg, int64_t strip) {   // strip: the wave's strip inside segment sg
+    lsc_nx = p.prep_lscale[int64_t(sg) * nlp + strip * 32 + ln];
+    const unsigned char* tp = p.prep_planes + (int64_t(sg) * (nlp / 32) + strip) * kV2TileBytes + lane * 16;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) wq[i] = *reinterpret_cast<const uintx4*>(tp + i * 1024);
+  };
+  {
+    const int sg = int(mt0 / mt_per_seg);
+    request_strip(sg, (mt0 - int64_t(sg) * mt_per_seg) * kV2Waves + wave);
+  }
+
   for (int64_t mt = mt0; mt < mt1;) {
     const int seg = int(mt / mt_per_seg);
     const int mis0 = int(mt - int64_t(seg) * mt_per_seg);
@@ -101,20 +118,21 @@ __device__ __forceinline__ void loss_v2_body(const CoreParams& p, const unsigned
     const float fsi = p.fscale_inv[bid];
     __syncthreads();
 
-    uintx4 wq[16];            // prepared B operands of the strip the next forward phase transforms
     float usc = 0.f;          // the factor back to the units of Z for the strip in the accumulators
     float usc2_prev = 0.f;    // its square for the strip whose error the next inverse phase transforms
     floatx16 acc[KT];
     uint32_t ebf[L / 4];      // the error as packed float16 (accumulator units): B operands of the inverse phase
-    auto load_w = [&](int m) {
-      const int64_t strip = int64_t(mis0 + m) * kV2Waves + wave;          // within the segment
-      const unsigned char* tp = p.prep_planes + (int64_t(seg) * (nlp / 32) + strip) * kV2TileBytes + lane * 16;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) wq[i] = *reinterpret_cast<const uintx4*>(tp + i * 1024);
-    };
-    auto load_lsc = [&](int m) {
-      const int64_t strip = int64_t(mis0 + m) * kV2Waves + wave;
-      return p.prep_lscale[int64_t(seg) * nlp + strip * 32 + ln];
+    // the strip after strip m of this run: the run's next one, else the first of the next run (the next segment),
+    // else -- the range ends here -- strip m once more (an unconditional request keeps the wait counts exact)
+    const bool more_runs = mt + n < mt1;
+    auto request_next = [&](int m) {
+      int sg = seg;
+      int64_t strip = int64_t(mis0 + m + 1) * kV2Waves + wave;
+      if (m + 1 == n) {
+        if (more_runs) { sg = seg + 1; strip = wave; }
+        else strip -= kV2Waves;
+      }
+      request_strip(sg, strip);
     };
 
     // Both contractions walk the output tiles one after the other (tile t: 32 outputs, its accumulator a
@@ -262,10 +280,12 @@ __device__ __forceinline__ void loss_v2_body(const CoreParams& p, const unsigned
             // at most 2e-6 of the error's own size on grids of up to 4 bits).
             const float q = __builtin_rintf(__fmul_rn(z, inv));
             er[e] = fmaf(q, s, -z);
-            e2 = fmaf(er[e], er[e], e2);
             if constexpr (OUT) acc[f / 16][f % 16] = q;            // kept for the optional code output
           }
           ebf[f2] = pack_f16(er[0], er[1]);
+          // the sum of squared errors from the packed pair (one dot-product instruction per pair; the float16
+          // rounding of an error is 2^-12 relative and random in sign, far below the sum's budget)
+          e2 = __builtin_amdgcn_fdot2(__builtin_bit_cast(halfx2, ebf[f2]), __builtin_bit_cast(halfx2, ebf[f2]), e2, false);
         }
         const float a2 = a * a;
         if (h == 0) s_va2[gi] += a2;
@@ -325,18 +345,14 @@ __device__ __forceinline__ void loss_v2_body(const CoreParams& p, const unsigned
     };
     if (grp == 1) __builtin_amdgcn_s_barrier();
     {
-      load_w(0);
-      const float lsc = load_lsc(0);
       forward();
-      usc = lsc * fsc;
+      usc = lsc_nx * fsc;
       fence_m();
+      request_next(0);
       usc2_prev = epilogue(0);
       fence_v();
     }
     for (int m = 1; m < n; ++m) {
-      // the strip's operands and scale factor are requested here: they arrive while the inverse transform runs
-      const float lsc = load_lsc(m);
-      load_w(m);
       // The matrix phase wins the issue arbitration on its SIMD: its MFMAs go out as soon as the matrix pipe is
       // free and the other wave's vector phase fills the issue slots in between (at equal priority the vector
       // stream crowds out the first part of this phase and then leaves the rest of it without company).
@@ -344,8 +360,9 @@ __device__ __forceinline__ void loss_v2_body(const CoreParams& p, const unsigned
       inverse(usc2_prev);
       forward();
       __builtin_amdgcn_s_setprio(0);
-      usc = lsc * fsc;
+      usc = lsc_nx * fsc;
       fence_m();
+      request_next(m);
       usc2_prev = epilogue(m);
       fence_v();
     }
