@@ -520,6 +520,95 @@ __global__ __launch_bounds__(256) void bgemm_mfma_kernel(const float* __restrict
   }
 }
 
+// The gradient's way through the inverse in one launch for blocks of 128: C = beta C + alpha (P^T G) P^T per block
+// (Sec. 4.1 / 4.2: d/dT of a function of P = T^-1 is -P^T (d/dP) P^T).  Row i of the result needs row i of
+// X = P^T G only, so a workgroup that owns 64 rows computes its slice of X and then its slice of X P^T with no
+// exchange between workgroups: two workgroups per block, eight waves of one 32 x 32 tile each, both products on
+// v_mfma_f32_32x32x2_f32 in the arithmetic (and summation order) of bgemm_mfma_kernel.  P is staged once in LDS,
+// row-major with a row stride of 129 floats, which serves the first product's A operand (lanes along a row) and
+// the second's B operand (lanes along a column) without bank conflicts; G goes from memory straight into the
+// registers of the wave that multiplies by it; X passes through LDS transposed.
+constexpr int kChainLdP = 129, kChainLdX = 33;
+constexpr size_t kChainLds = (128 * kChainLdP + 2 * 128 * kChainLdX) * sizeof(float);
+__global__ __launch_bounds__(512) void bgemm_chain128_kernel(const float* __restrict__ P, const float* __restrict__ G,
+                                                             float* __restrict__ C, float alpha, float beta,
+                                                             const AdamHook adam) {
+  constexpr int K = 128;
+  extern __shared__ __align__(16) float csm[];
+  float* sp = csm;                          // P[r][c]
+  float* sx = csm + K * kChainLdP;          // [2 row halves][l][32 rows]: X^T of the workgroup's slice
+  const int b = blockIdx.x >> 1, i0 = (blockIdx.x & 1) * 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ln = lane & 31, h = lane >> 5;
+  const int wi = wave >> 2, wj = wave & 3;
+  const float* Pb = P + size_t(b) * K * K;
+  const float* Gb = G + size_t(b) * K * K;
+  float* Cb = C + size_t(b) * K * K;
+  // every load of the workgroup is requested before the first wait: P (for LDS), this wave's columns of G, and the
+  // old value of the output where it is added to
+  float4 vp[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) vp[u] = *reinterpret_cast<const float4*>(Pb + (tid + u * 512) * 4);
+  float g[64];
+#pragma unroll
+  for (int t = 0; t < 64; ++t) g[t] = Gb[(2 * t + h) * K + wj * 32 + ln];
+  float cold[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) cold[v] = 0.f;
+  if (beta != 0.f) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) cold[v] = Cb[(i0 + wi * 32 + 8 * (v / 4) + 4 * h + (v % 4)) * K + wj * 32 + ln];
+  }
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const int e = (tid + u * 512) * 4, r = e >> 7, c = e & 127;
+    float* d = sp + r * kChainLdP + c;
+    d[0] = vp[u].x; d[1] = vp[u].y; d[2] = vp[u].z; d[3] = vp[u].w;
+  }
+  __syncthreads();
+  floatx16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  {
+    // X[i][j] = sum_l P[l][i] G[l][j]
+    const float* pa = sp + h * kChainLdP + i0 + wi * 32 + ln;
+#pragma unroll
+    for (int t = 0; t < 64; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[2 * t * kChainLdP], g[t], acc, 0, 0, 0);
+  }
+  {
+    float* xw = sx + wi * (K * kChainLdX) + (wj * 32 + ln) * kChainLdX;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) xw[8 * (v / 4) + 4 * h + (v % 4)] = acc[v];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  {
+    // Y[i][j] = sum_l X[i][l] P[j][l]
+    const float* pa = sx + wi * (K * kChainLdX) + h * kChainLdX + ln;
+    const float* pb = sp + (wj * 32 + ln) * kChainLdP + h;
+#pragma unroll 8
+    for (int t = 0; t < 64; ++t)
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[2 * t * kChainLdX], pb[2 * t], acc, 0, 0, 0);
+  }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int i = i0 + wi * 32 + 8 * (v / 4) + 4 * h + (v % 4), j = wj * 32 + ln;
+    const float gr = alpha * acc[v] + (beta != 0.f ? beta * cold[v] : 0.f);
+    if (adam.T) {
+      // (the arithmetic of adam_kernel, on the gradient still in its register)
+      const size_t at = size_t(b) * K * K + size_t(i) * K + j;
+      const float mi = adam.beta1 * adam.m[at] + adam.omb1 * gr;
+      const float vi = adam.beta2 * adam.v[at] + adam.omb2 * gr * gr;
+      adam.m[at] = mi;
+      adam.v[at] = vi;
+      adam.T[at] -= adam.lr * (mi * adam.c1) / (sqrtf(vi * adam.c2) + adam.eps);
+    } else {
+      Cb[i * K + j] = gr;
+    }
+  }
+}
+
+
 // K == 32: one 32 x 32 tile per workgroup, thread per output element group
 template <bool TA, bool TB>
 __global__ __launch_bounds__(256) void bgemm32_kernel(const float* __restrict__ A, const float* __restrict__ B,
@@ -671,6 +760,28 @@ int launch_bgemm(bool ta, bool tb, const float* A, const float* B, float* C, int
 #undef CAFEQ_G64
     }
   }
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+// C = beta C + alpha (P^T G) P^T per block; x1: scratch of nb K K floats for block sizes other than 128
+int launch_bgemm_chain(const float* P, const float* G, float* x1, float* C, int K, int nb, float alpha, float beta,
+                       hipStream_t st, const AdamHook* adam) {
+  if (K != 128) {
+    const int rc = launch_bgemm(true, false, P, G, x1, K, nb, 1.f, 0.f, st);
+    if (rc) return rc;
+    return launch_bgemm(false, true, x1, P, C, K, nb, alpha, beta, st, adam);
+  }
+  AdamHook hook;
+  hook.T = nullptr;
+  if (adam) hook = *adam;
+  static std::atomic<bool> attr_set{false};
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(bgemm_chain128_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, int(kChainLds)) != hipSuccess)
+      return CAFEQ_ERR_LAUNCH;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(bgemm_chain128_kernel, dim3(unsigned(nb) * 2), dim3(512), kChainLds, st, P, G, C, alpha, beta, hook);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }

@@ -984,8 +984,7 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
       if ((rc = launch_reduce_grad(pg, K, gp.Gk, pp.fused, nb, col ? 1 : 0, nullptr, nullptr, gradT, st))) return rc;
     }
     if ((rc = launch_build_mmid(p, K, gp.Gk, nb, x->Tinv, col ? 1 : 0, w.mmid, st))) return rc;
-    if ((rc = launch_bgemm(true, false, x->Tinv, w.mmid, w.x1, K, nb, 1.f, 0.f, st))) return rc;
-    if ((rc = launch_bgemm(false, true, w.x1, x->Tinv, gradT, K, nb, -2.f, 1.f, st))) return rc;
+    if ((rc = launch_bgemm_chain(x->Tinv, w.mmid, w.x1, gradT, K, nb, -2.f, 1.f, st))) return rc;
   }
   return CAFEQ_OK;
 }
@@ -1113,15 +1112,13 @@ static int dual_impl(const cafeq_mat* A, const cafeq_mat* B, const cafeq_xform* 
     const GradOwnerJob jobs[2] = {grad_owner_job(A, CAFEQ_AXIS_COL, qa, w.a, gradT, 1),
                                   grad_owner_job(B, CAFEQ_AXIS_ROW, qb, w.b, w.gp, 0)};
     if ((rc = launch_grad_v2_owner(jobs, 2, kLossLse, 0.f, lse_t, w.lse_ms, st))) return rc;
-    if ((rc = launch_bgemm(true, false, x->Tinv, w.gp, w.x1, K, nb, 1.f, 0.f, st))) return rc;
-    if ((rc = launch_bgemm(false, true, w.x1, x->Tinv, gradT, K, nb, -1.f, 1.f, st, adam))) return rc;
+    if ((rc = launch_bgemm_chain(x->Tinv, w.gp, w.x1, gradT, K, nb, -1.f, 1.f, st, adam))) return rc;
   } else if (grad) {
     // member A into gradT; member B: G_P of transform block b sums its rep row-blocks; d/dT = -P^T G_P P^T
     if ((rc = launch_reduce_grad_pair(ag, ga.Gk, qa.fused, qa.two ? w.member_ref : nullptr, gradT, bg, gb.Gk, qb.fused,
                                       qb.two ? w.member_ref + 1 : nullptr, w.gp, K, nb, w.lse_ms, st)))
       return rc;
-    if ((rc = launch_bgemm(true, false, x->Tinv, w.gp, w.x1, K, nb, 1.f, 0.f, st))) return rc;
-    if ((rc = launch_bgemm(false, true, w.x1, x->Tinv, gradT, K, nb, -1.f, 1.f, st, adam))) return rc;
+    if ((rc = launch_bgemm_chain(x->Tinv, w.gp, w.x1, gradT, K, nb, -1.f, 1.f, st, adam))) return rc;
   }
   return CAFEQ_OK;
 }

@@ -106,6 +106,8 @@ int launch_reduce_losses(int kind, const float* hdrA, int nslotA, const float* h
 struct AdamHook { float *T, *m, *v; float lr, beta1, omb1, beta2, omb2, eps, c1, c2; };
 int launch_bgemm(bool ta, bool tb, const float* A, const float* B, float* C, int K, int nb, float alpha,
                  float beta, hipStream_t st, const AdamHook* adam = nullptr);
+int launch_bgemm_chain(const float* P, const float* G, float* x1, float* C, int K, int nb, float alpha, float beta,
+                       hipStream_t st, const AdamHook* adam = nullptr);
 // adaptive_kernels.hip
 int launch_gram_pair(int axis, const float* X, const int8_t* codes, const float* scales, int64_t rows,
                      int64_t cols, int K, int G, int nb, int rep, int64_t chunk, int nchunk, float* partial,
