@@ -34,9 +34,11 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBS = 8000.0
 
 
-def memory_probe(torch, dev):
-    """Streaming rates of two library kernels over 1 GiB buffers (larger than every cache of the part): a
-    read-only reduction and a copy.  Context for the roofline figures, not part of any timed step."""
+def memory_probe(torch, dev, cafeq):
+    """Streaming rates over 1 GiB buffers (larger than every cache of the part): the library's own plain streaming
+    read (cafeq_stream_read_probe: what the memory system delivers to a kernel that only reads), and, for
+    comparison, two of torch's kernels (a read-only reduction and a copy).  Context for the roofline figures, not
+    part of any timed step."""
     src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
     dst = torch.empty_like(src)
 
@@ -50,9 +52,11 @@ def memory_probe(torch, dev):
         torch.cuda.synchronize()
         return nbytes * n / (time.perf_counter() - t0) / 1e12
 
-    out = {"read_only_TBps": rate(lambda: src.sum(), src.numel() * 4),
-           "copy_read_plus_write_TBps": rate(lambda: dst.copy_(src), 2 * src.numel() * 4),
-           "what": "torch.sum / Tensor.copy_ over 1 GiB float32, 10 repetitions"}
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    out = {"read_only_TBps": rate(lambda: cafeq.stream_read_probe(src, sink), src.numel() * 4),
+           "torch_sum_TBps": rate(lambda: src.sum(), src.numel() * 4),
+           "torch_copy_read_plus_write_TBps": rate(lambda: dst.copy_(src), 2 * src.numel() * 4),
+           "what": "cafeq_stream_read_probe / torch.sum / Tensor.copy_ over 1 GiB float32, 10 repetitions"}
     del src, dst
     torch.cuda.empty_cache()
     return out
@@ -207,7 +211,7 @@ def pair_workload(args, secondary=True):
         "whole_step_hbm_frac_at_one_read_of_the_weights": 4.0 * elems * args.steps / dt / 1e9 / HBM_PEAK_GBS}
     # what this machine's memory system delivers to plain streaming kernels on data that no cache holds (the published
     # 8 TB/s stays the roofline's peak; these two figures say how far any kernel gets towards it here)
-    probe = memory_probe(torch, dev)
+    probe = memory_probe(torch, dev, cafeq)
     traffic = result["roofline"]["traffic"]
     result["roofline"]["memory_probe"] = probe
     if traffic:

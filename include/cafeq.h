@@ -359,6 +359,14 @@ typedef struct {
 } cafeq_launch_timing;
 int cafeq_set_launch_timing(cafeq_launch_timing* t);
 
+/* Measurement aid (not part of the method): one launch of a plain streaming read over `bytes` bytes of device
+ * memory at `buf` (16-byte aligned, bytes a multiple of 16; each lane issues four independent 128-bit loads per
+ * step, thousands of small workgroups) -- what the memory system delivers to a kernel that does nothing else,
+ * the yardstick for the bandwidth-bound passes.  sink: 4 bytes of device memory that the kernel may write (it
+ * writes only if the XOR of everything read equals one particular value).  Enqueued on `stream`; the caller times
+ * it.  CAFEQ_ERR_INVALID_ARG for NULL pointers, misalignment or bytes < 16. */
+int cafeq_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

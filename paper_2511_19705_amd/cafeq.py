@@ -27,6 +27,7 @@ EXPORTS = (
     "cafeq_orth_penalty", "cafeq_sgd_update", "cafeq_adam_update", "cafeq_optimize_single",
     "cafeq_optimize_pair", "cafeq_pqe", "cafeq_rtn_quantize_minmax", "cafeq_hadamard_rtn", "cafeq_hadamard_workspace_bytes",
     "cafeq_infer_single", "cafeq_infer_workspace_bytes", "cafeq_set_launch_timing", "cafeq_rtn_quantize_static", "cafeq_prepared_bytes", "cafeq_prepare_weights",
+    "cafeq_stream_read_probe",
 )
 
 
@@ -108,6 +109,7 @@ def _load():
     lib.cafeq_pqe.argtypes = [vp, vp, i64, i64, i64, i64, ctypes.POINTER(QuantCfg), i32, i32, i32, vp, vp, vp, vp,
                               vp, vp, vp]
     lib.cafeq_set_launch_timing.argtypes = [ctypes.POINTER(LaunchTiming)]
+    lib.cafeq_stream_read_probe.argtypes = [vp, ctypes.c_size_t, vp, vp]
     for n in EXPORTS[3:]:
         getattr(lib, n).restype = i32
     return lib
@@ -309,6 +311,15 @@ def adaptive_round_step(U, V, codesU, scalesU, codesV, scalesV, bits, group, k, 
                                          ctypes.byref(cfg), k, nb, rep, half, _ptr(codesU), _ptr(scalesU),
                                          _ptr(codesV), _ptr(scalesV), _ptr(status), _ptr(ws), _stream()))
     return status
+
+
+def stream_read_probe(buf, sink=None):
+    """One launch of the library's plain streaming read over the tensor `buf` (cafeq_stream_read_probe)."""
+    if sink is None:
+        sink = torch.zeros(1, dtype=torch.int32, device=buf.device)
+    _check(lib.cafeq_stream_read_probe(_ptr(buf), ctypes.c_size_t(buf.numel() * buf.element_size()), _ptr(sink),
+                                       _stream()))
+    return sink
 
 
 class LaunchTimer:

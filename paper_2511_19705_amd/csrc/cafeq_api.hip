@@ -651,6 +651,43 @@ int cafeq_optimize_pair(const cafeq_mat* A, const cafeq_mat* B, float* T, float*
 }
 
 
+namespace cafeq {
+namespace {
+__global__ __launch_bounds__(256) void stream_read_kernel(const uintx4* __restrict__ p, size_t n16, unsigned* sink) {
+  unsigned acc = 0;
+  const size_t stride = size_t(gridDim.x) * 1024;
+  size_t base = size_t(blockIdx.x) * 1024 + threadIdx.x;
+  for (; base + 768 < n16; base += stride) {
+    uintx4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(p + base + 256 * u);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc ^= v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {       // the last, partial step of 1024 vectors (every later step lies beyond the end)
+    const size_t i = base + 256 * u;
+    if (i < n16) {
+      const uintx4 v = p[i];
+      acc ^= v[0] ^ v[1] ^ v[2] ^ v[3];
+    }
+  }
+  if (acc == 0x5EEDF00Du) sink[0] = acc;
+}
+}  // namespace
+}  // namespace cafeq
+
+int cafeq_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {
+  if (!buf || !sink || bytes < 16 || bytes % 16 != 0 || reinterpret_cast<uintptr_t>(buf) % 16 != 0) return CAFEQ_ERR_INVALID_ARG;
+  const size_t n16 = bytes / 16;
+  const size_t steps = (n16 + 1023) / 1024;
+  const unsigned grid = unsigned(std::min<size_t>(steps, 8192));
+  hipLaunchKernelGGL(cafeq::stream_read_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const cafeq::uintx4*>(buf), n16, static_cast<unsigned*>(sink));
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
+
 int cafeq_set_launch_timing(cafeq_launch_timing* t) {
   if (t && (t->capacity < 0 || t->count < 0 || (t->capacity > 0 && (!t->start || !t->stop)))) return CAFEQ_ERR_INVALID_ARG;
   cafeq::g_timing = t;

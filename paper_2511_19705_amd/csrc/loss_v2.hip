@@ -90,7 +90,10 @@ __device__ __forceinline__ void loss_v2_body(const CoreParams& p, const unsigned
 #pragma unroll
     for (int i = 0; i < 16; ++i) wq[i] = *reinterpret_cast<const uintx4*>(tp + i * 1024);
   };
-  {
+  // (The variants that write codes or scales keep their requests at the start of the matrix phase: their vector
+  // phase has no registers to hold a strip in flight.)
+  constexpr bool EARLY = !OUT;
+  if constexpr (EARLY) {
     const int sg = int(mt0 / mt_per_seg);
     request_strip(sg, (mt0 - int64_t(sg) * mt_per_seg) * kV2Waves + wave);
   }
@@ -345,10 +348,11 @@ __device__ __forceinline__ void loss_v2_body(const CoreParams& p, const unsigned
     };
     if (grp == 1) __builtin_amdgcn_s_barrier();
     {
+      if constexpr (!EARLY) request_strip(seg, int64_t(mis0) * kV2Waves + wave);
       forward();
       usc = lsc_nx * fsc;
       fence_m();
-      request_next(0);
+      if constexpr (EARLY) request_next(0);
       usc2_prev = epilogue(0);
       fence_v();
     }
@@ -356,13 +360,14 @@ __device__ __forceinline__ void loss_v2_body(const CoreParams& p, const unsigned
       // The matrix phase wins the issue arbitration on its SIMD: its MFMAs go out as soon as the matrix pipe is
       // free and the other wave's vector phase fills the issue slots in between (at equal priority the vector
       // stream crowds out the first part of this phase and then leaves the rest of it without company).
+      if constexpr (!EARLY) request_strip(seg, int64_t(mis0 + m) * kV2Waves + wave);
       __builtin_amdgcn_s_setprio(3);
       inverse(usc2_prev);
       forward();
       __builtin_amdgcn_s_setprio(0);
       usc = lsc_nx * fsc;
       fence_m();
-      request_next(m);
+      if constexpr (EARLY) request_next(m);
       usc2_prev = epilogue(m);
       fence_v();
     }
