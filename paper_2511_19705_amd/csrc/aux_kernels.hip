@@ -4,6 +4,7 @@
 #include <atomic>
 #include "cafeq_internal.hpp"
 #include "xform_core.hpp"
+#include "loss_reduce.hpp"
 
 namespace cafeq {
 
@@ -309,87 +310,11 @@ __global__ __launch_bounds__(256) void build_mmid_kernel(const VArgs a) {
   for (int i = threadIdx.x; i < K * K; i += blockDim.x) Mb[i] = Pb[i] * (a.scale_rows ? v[i / K] : v[i % K]);
 }
 
-// losses: fixed-order float64 sums over every partial header.
-struct LossArgs {
-  const float* hdrA; int nslotA;     // member A (or the single matrix)
-  const float* hdrB; int nslotB;     // member B (dual only)
-  int kind; float beta, t;
-  int64_t ngroups;
-  float* losses;
-  double* lse_ms;                    // out: [m*, S]
-};
-constexpr int kLossThreads = 256;
+// losses: fixed-order float64 sums over every partial header (loss_reduce.hpp), as a launch of its own
 __global__ __launch_bounds__(kLossThreads) void reduce_losses_kernel(const LossArgs a) {
   __shared__ double red[5 * (kLossThreads / 64)];
-  // four sums and one maximum over the workgroup, fixed order
-  auto reduce5 = [&](double& v0, double& v1, double& v2, double& v3, double& vmax) {
-    for (int k = 1; k < 64; k <<= 1) {
-      v0 += __shfl_xor(v0, k); v1 += __shfl_xor(v1, k); v2 += __shfl_xor(v2, k); v3 += __shfl_xor(v3, k);
-      vmax = fmax(vmax, __shfl_xor(vmax, k));
-    }
-    constexpr int NW = kLossThreads / 64;
-    const int w = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) {
-      red[w] = v0; red[NW + w] = v1; red[2 * NW + w] = v2; red[3 * NW + w] = v3; red[4 * NW + w] = vmax;
-    }
-    __syncthreads();
-    v0 = v1 = v2 = v3 = 0;
-    vmax = -INFINITY;
-    for (int k = 0; k < NW; ++k) {
-      v0 += red[k]; v1 += red[NW + k]; v2 += red[2 * NW + k]; v3 += red[3 * NW + k];
-      vmax = fmax(vmax, red[4 * NW + k]);
-    }
-    __syncthreads();
-  };
-  if (a.kind == kLossSur) {
-    double l2 = 0, ez = 0, ws = 0, su = 0, dummy = 0;
-    for (int i = threadIdx.x; i < a.nslotA; i += kLossThreads) {
-      const float* h = a.hdrA + size_t(i) * kHdrFloats;
-      l2 += h[kHdrL2]; ez += h[kHdrErrZ]; ws += h[kHdrWsq]; su += h[kHdrSur];
-    }
-    reduce5(l2, ez, ws, su, dummy);
-    if (threadIdx.x == 0) {
-      a.losses[0] = float(l2); a.losses[1] = float(ez); a.losses[2] = float(ws);
-      a.losses[3] = float(su * a.beta);
-    }
-    return;
-  }
-  // one pass over both members' headers: four sums and the largest reference; each thread keeps
-  // its slots' (sum of exponentials, reference) pairs for the second step
-  constexpr int kMaxPer = 8;                       // slots per thread held in registers
-  const int ntot = a.nslotA + a.nslotB;
-  double ezA = 0, ezB = 0, l2A = 0, l2B = 0, m = -INFINITY;
-  float sur[kMaxPer], mref[kMaxPer];
-  int cnt = 0;
-  for (int i = threadIdx.x; i < ntot; i += kLossThreads, ++cnt) {
-    const bool isA = i < a.nslotA;
-    const float* h = isA ? a.hdrA + size_t(i) * kHdrFloats : a.hdrB + size_t(i - a.nslotA) * kHdrFloats;
-    const float ez = h[kHdrErrZ], l2 = h[kHdrL2], su = h[kHdrSur], mr = h[kHdrMref];
-    if (isA) { ezA += ez; l2A += l2; } else { ezB += ez; l2B += l2; }
-    m = fmax(m, double(mr));
-    if (cnt < kMaxPer) { sur[cnt] = su; mref[cnt] = mr; }
-  }
-  reduce5(ezA, ezB, l2A, l2B, m);
-  // global normaliser of the exponentials
-  double s = 0;
-  cnt = 0;
-  for (int i = threadIdx.x; i < ntot; i += kLossThreads, ++cnt) {
-    float su, mr;
-    if (cnt < kMaxPer) { su = sur[cnt]; mr = mref[cnt]; }
-    else {
-      const float* h = i < a.nslotA ? a.hdrA + size_t(i) * kHdrFloats : a.hdrB + size_t(i - a.nslotA) * kHdrFloats;
-      su = h[kHdrSur]; mr = h[kHdrMref];
-    }
-    if (su > 0.f) s += double(su) * exp(double(a.t) * (double(mr) - m));
-  }
-  double z1 = 0, z2 = 0, z3 = 0, zm = 0;
-  reduce5(s, z1, z2, z3, zm);
-  if (threadIdx.x == 0) {
-    a.losses[0] = float(ezA); a.losses[1] = float(ezB); a.losses[2] = float(l2A); a.losses[3] = float(l2B);
-    a.losses[4] = float(m + log(s) / double(a.t));
-    a.losses[5] = float(a.ngroups);
-    a.lse_ms[0] = m; a.lse_ms[1] = s;
-  }
+  double m, s;
+  reduce_losses_body<kLossThreads>(a, red, true, &m, &s);
 }
 
 // ---------------------------------------------------------------------------------------

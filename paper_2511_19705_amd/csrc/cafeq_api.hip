@@ -3,6 +3,7 @@
 #include <vector>
 
 #include "xform_core.hpp"
+#include "loss_reduce.hpp"
 
 using namespace cafeq;
 
@@ -1002,18 +1003,23 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   p.mins = asym && scales ? scales + nlines * (naxis / gp.G) : nullptr;   // the minima follow the scales
   if ((rc = run_core(K, cfg->axis, gp, p, w.m.rec, w.m.grec, pp.two, st, v2 ? W : nullptr, w.m.rec_mm, w.m.grec_mm)))
     return rc;
-  if ((rc = launch_reduce_losses(kLossSur, w.slot_hdr, int(pl.nslot), nullptr, 0, beta, 0.f, 0, losses,
-                                 w.lse_ms, st)))
+  const cafeq_mat* mats[1] = {W};
+  const PassPlans* pps[1] = {&pp};
+  const bool owner = grad && grad_owner_eligible(mats, pps, 1, K, x->rep);
+  // (with one workgroup per block in the gradient pass, its first workgroup reduces the losses: one launch less)
+  if (!owner && (rc = launch_reduce_losses(kLossSur, w.slot_hdr, int(pl.nslot), nullptr, 0, beta, 0.f, 0, losses,
+                                           w.lse_ms, st)))
     return rc;
   if (grad) {
     // path through Z (fused into the pass above, or a second pass over the weights from its
     // arg-max records), then the path through rho(P): -2 P^T Mmid P^T
     CoreParams pg = p;
-    const cafeq_mat* mats[1] = {W};
-    const PassPlans* pps[1] = {&pp};
-    if (grad_owner_eligible(mats, pps, 1, K, x->rep)) {
+    if (owner) {
       const GradOwnerJob job = grad_owner_job(W, cfg->axis, pp, w.m, gradT, col ? 1 : 0);
-      if ((rc = launch_grad_v2_owner(&job, 1, kLossSur, beta, 0.f, nullptr, st))) return rc;
+      LossArgs la{};
+      la.hdrA = w.slot_hdr; la.nslotA = int(pl.nslot); la.kind = kLossSur; la.beta = beta; la.losses = losses;
+      la.lse_ms = w.lse_ms;
+      if ((rc = launch_grad_v2_owner(&job, 1, kLossSur, beta, 0.f, nullptr, st, &la))) return rc;
     } else {
       if (pp.two &&
           (rc = run_grad_pass(K, cfg->axis, W, x->rep, pp, w.m, kLossSur, beta, 0.f, nullptr, 0, nullptr, &pg, st)))
@@ -1140,15 +1146,19 @@ static int dual_impl(const cafeq_mat* A, const cafeq_mat* B, const cafeq_xform* 
     return rc;
 
   const int64_t ngroups = A->rows * (A->cols / ga.G) + (B->rows / gb.G) * B->cols;
-  if ((rc = launch_reduce_losses(kLossLse, w.hdrA, int(pa.nslot), w.hdrB, int(pb.nslot), 0.f, lse_t, ngroups,
-                                 losses, w.lse_ms, st)))
+  if (!owner && (rc = launch_reduce_losses(kLossLse, w.hdrA, int(pa.nslot), w.hdrB, int(pb.nslot), 0.f, lse_t, ngroups,
+                                           losses, w.lse_ms, st)))
     return rc;
   if (grad && owner) {
-    // both members' gradient passes in one launch, after the pair's LogSumExp is known: one workgroup per block
-    // writes member A's share into gradT (transposed) and member B's G_P; d/dT = -P^T G_P P^T follows
+    // both members' gradient passes in one launch: one workgroup per block writes member A's share into gradT
+    // (transposed) and member B's G_P; d/dT = -P^T G_P P^T follows.  The pair's LogSumExp has to be known to
+    // them: every workgroup reduces the partial headers itself, the first also writes the losses.
     const GradOwnerJob jobs[2] = {grad_owner_job(A, CAFEQ_AXIS_COL, qa, w.a, gradT, 1),
                                   grad_owner_job(B, CAFEQ_AXIS_ROW, qb, w.b, w.gp, 0)};
-    if ((rc = launch_grad_v2_owner(jobs, 2, kLossLse, 0.f, lse_t, w.lse_ms, st))) return rc;
+    LossArgs la{};
+    la.hdrA = w.hdrA; la.nslotA = int(pa.nslot); la.hdrB = w.hdrB; la.nslotB = int(pb.nslot); la.kind = kLossLse;
+    la.t = lse_t; la.ngroups = ngroups; la.losses = losses; la.lse_ms = w.lse_ms;
+    if ((rc = launch_grad_v2_owner(jobs, 2, kLossLse, 0.f, lse_t, w.lse_ms, st, &la))) return rc;
     if ((rc = launch_bgemm_chain(x->Tinv, w.gp, w.x1, gradT, K, nb, -1.f, 1.f, st, adam))) return rc;
   } else if (grad) {
     // member A into gradT; member B: G_P of transform block b sums its rep row-blocks; d/dT = -P^T G_P P^T

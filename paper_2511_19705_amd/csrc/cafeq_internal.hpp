@@ -71,8 +71,9 @@ struct GradOwnerJob {
   const unsigned char* gtiles; const float2* rec; const float* rG; float* out;
   int64_t nlines; int nseg, grp, transpose_out;
 };
+struct LossArgs;   // loss_reduce.hpp; fold != nullptr: the loss reduction runs inside the launch
 int launch_grad_v2_owner(const GradOwnerJob* jobs, int n, int loss_kind, float beta, float lse_t, const double* lse_ms,
-                         hipStream_t st);
+                         hipStream_t st, const LossArgs* fold = nullptr);
 int launch_loss_v2(int G, int axis, const CoreParams& p, hipStream_t st);
 int launch_loss_prepared(int G, int axis, const CoreParams& p, hipStream_t st);   // ... with the caller's timing events
 // both members of a pair in one launch (loss_v2.hip), plain and with the caller's timing events

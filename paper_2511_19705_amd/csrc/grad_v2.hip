@@ -22,6 +22,7 @@
 
 #include "cafeq_internal.hpp"
 #include "xform_core.hpp"
+#include "loss_reduce.hpp"
 
 namespace cafeq {
 namespace {
@@ -236,7 +237,11 @@ struct GvOwnerArgs {
   GvMember m[2];
   int nmem, loss_kind;
   float beta, lse_t;
-  const double* lse_ms;   // kLossLse: {m*, S}
+  const double* lse_ms;   // kLossLse: {m*, S}, unless fold is set
+  // fold != 0: the call's loss reduction runs inside this launch instead of before it -- every workgroup forms
+  // {m*, S} from the partial headers itself (kLossLse), workgroup 0 also writes the losses
+  int fold;
+  LossArgs la;
 };
 
 __global__ __launch_bounds__(512, 1) void grad_v2_owner_kernel(const GvOwnerArgs a) {
@@ -254,7 +259,7 @@ __global__ __launch_bounds__(512, 1) void grad_v2_owner_kernel(const GvOwnerArgs
 
   for (int i = tid; i < 2 * kGvSbufB / 16; i += 512) reinterpret_cast<uint4*>(smem)[i] = make_uint4(0u, 0u, 0u, 0u);
   float mstar = 0.f, inv_s = 1.f;
-  if (a.loss_kind == kLossLse) {
+  if (a.loss_kind == kLossLse && !a.fold) {
     mstar = float(a.lse_ms[0]);
     inv_s = float(1.0 / a.lse_ms[1]);
   }
@@ -308,6 +313,20 @@ __global__ __launch_bounds__(512, 1) void grad_v2_owner_kernel(const GvOwnerArgs
   for (int s = 0; s < 8; ++s) {
     load_step(tile, s);
     __builtin_amdgcn_sched_barrier(0);
+  }
+
+  if (a.fold) {
+    // (after the first tile's requests, which are in flight meanwhile)
+    double* red = reinterpret_cast<double*>(smem + 2 * kGvSbufB);
+    if (a.loss_kind == kLossLse) {
+      double m = 0, sm = 1;
+      reduce_losses_body<512>(a.la, red, blockIdx.x == 0, &m, &sm);
+      mstar = float(m);
+      inv_s = float(1.0 / sm);
+    } else if (blockIdx.x == 0) {
+      double m, sm;
+      reduce_losses_body<512>(a.la, red, true, &m, &sm);
+    }
   }
 
   for (int it = 0; it < niter; ++it) {
@@ -460,7 +479,7 @@ int launch_prepare_gtiles(const cafeq_mat* W, int axis, unsigned char* gtiles, h
 
 // Both members of a pair (or one matrix) with one workgroup per block; see grad_v2_owner_kernel.
 int launch_grad_v2_owner(const GradOwnerJob* jobs, int n, int loss_kind, float beta, float lse_t, const double* lse_ms,
-                         hipStream_t st) {
+                         hipStream_t st, const LossArgs* fold) {
   if (n < 1 || n > 2) return CAFEQ_ERR_INVALID_ARG;
   GvOwnerArgs a;
   int nwg = 0;
@@ -476,6 +495,14 @@ int launch_grad_v2_owner(const GradOwnerJob* jobs, int n, int loss_kind, float b
   if (n == 1) a.m[1] = a.m[0];
   if (loss_kind == kLossLse && !lse_ms) return CAFEQ_ERR_INVALID_ARG;
   a.nmem = n; a.loss_kind = loss_kind; a.beta = beta; a.lse_t = lse_t; a.lse_ms = lse_ms;
+  a.fold = fold ? 1 : 0;
+  if (fold) {
+    if (fold->kind != loss_kind || !fold->hdrA || !fold->losses || (loss_kind == kLossLse && !fold->lse_ms))
+      return CAFEQ_ERR_INVALID_ARG;
+    a.la = *fold;
+  } else {
+    a.la = LossArgs{};
+  }
   static std::atomic<bool> attr_set{false};
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(grad_v2_owner_kernel),
@@ -483,7 +510,7 @@ int launch_grad_v2_owner(const GradOwnerJob* jobs, int n, int loss_kind, float b
       return CAFEQ_ERR_LAUNCH;
     attr_set = true;
   }
-  hipLaunchKernelGGL(grad_v2_owner_kernel, dim3(unsigned(nwg)), dim3(512), 2 * kGvSbufB + 64, st, a);
+  hipLaunchKernelGGL(grad_v2_owner_kernel, dim3(unsigned(nwg)), dim3(512), 2 * kGvSbufB + 5 * 8 * sizeof(double), st, a);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }
