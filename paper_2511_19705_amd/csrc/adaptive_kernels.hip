@@ -17,6 +17,7 @@
 //   gj_panel_kernel  : sums the chunk partials of S in float64 and inverts it by register-
 //                      resident Gauss-Jordan elimination with partial pivoting; also serves
 //                      cafeq_block_inverse.  C = I - S^-1 R follows as a batched product.
+#include <atomic>
 #include <type_traits>
 
 #include "xform_core.hpp"
@@ -193,6 +194,190 @@ __global__ __launch_bounds__(256) void gram_pair_kernel(const GramArgs a) {
         if (TRIPLE) out[2 * size_t(K) * K + size_t(row) * K + col] = accT[TRIPLE ? u : 0][v];
       }
     }
+}
+
+// The same pair of Gram matrices for heads of 128 and 256 on the 16-bit matrix pipe.  Every float32 value -- the
+// dequantized code Xq = fl(q s) and the error E = fl(Xq - X), the numbers the kernel above multiplies -- is split
+// exactly into three bfloat16 parts (8 + 8 + 8 significant bits) and a product keeps the six part products of
+// weight >= 2^-24 (hh, hm, mh, hl, lh, mm), float32 accumulation: the accuracy of the float32 instruction at 6/16 of
+// its time.  So that the split is not repeated per 32-row stripe, a workgroup of eight waves owns a whole 128 x 128
+// quadrant of a head's outputs (grid y: quadrant; 1 or 4 per head): per step of 16 contraction indices its 512
+// threads each take eight consecutive contraction indices of one free index -- waves 0-3 the quadrant's row side
+// (Xq), waves 4-7 its column side (Xq and E) -- dequantize, split, and store one 16-byte matrix-instruction operand
+// per part into LDS ([part][free index][16 contraction indices], two buffers, one barrier per step); then wave w
+// accumulates the tiles (row tile w / 2; column tiles 2 (w % 2), 2 (w % 2) + 1) of S and R: 24 matrix instructions
+// from 15 operand reads.  Partials in the layout of the kernel above.
+constexpr int kG16PlaneB = 128 * 32;                 // one part of one side: 128 free indices x 16 bfloat16
+constexpr int kG16BufB = 9 * kG16PlaneB;             // row side Xq, column side Xq, column side E: 3 parts each
+constexpr size_t kG16Lds = 2 * kG16BufB;
+
+__device__ __forceinline__ void split3_bf16(const float (&x)[8], uintx4& ph, uintx4& pm, uintx4& pl) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float x0 = x[2 * i], x1 = x[2 * i + 1];
+    const uint32_t h = pack_bf16(x0, x1);
+    const float r0 = x0 - bf16_lo_f32(h), r1 = x1 - bf16_hi_f32(h);
+    const uint32_t m = pack_bf16(r0, r1);
+    ph[i] = h;
+    pm[i] = m;
+    pl[i] = pack_bf16(r0 - bf16_lo_f32(m), r1 - bf16_hi_f32(m));
+  }
+}
+
+template <int AXIS, int K>
+__global__ __launch_bounds__(512) void gram_pair16_kernel(const GramArgs a) {
+  static_assert(K == 128 || K == 256, "quadrants of 128");
+  constexpr int QUADS = K / 128;
+  extern __shared__ __align__(16) unsigned char gsm[];
+  const int b = blockIdx.x, qI = blockIdx.y / QUADS, qJ = blockIdx.y % QUADS;
+  const int z = blockIdx.z;                      // (row-block within head, chunk)
+  const int qi = z / a.nchunk, ch = z % a.nchunk;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ln = lane & 31, h = lane >> 5;
+  const int64_t t0 = int64_t(ch) * a.chunk;
+  const int64_t t1 = t0 + a.chunk < a.tlen ? t0 + a.chunk : a.tlen;
+  const int64_t f0 = AXIS == CAFEQ_AXIS_COL ? int64_t(b) * K : (int64_t(b) * a.rep + qi) * K;
+  const int64_t C = a.cols;
+
+  // loader role: side (uniform over a wave), free index, half of the step's 16 contraction indices
+  const int side = __builtin_amdgcn_readfirstlane(tid >> 8), idx = (tid & 255) >> 1, half = tid & 1;
+  const int64_t fbase = f0 + 128 * (side ? qJ : qI);     // uniform over the wave
+  const int64_t fidx = fbase + idx;
+  struct LoadSet {
+    float lx[8], lsc[8];
+    uint32_t lc[AXIS == CAFEQ_AXIS_COL ? 8 : 2];
+    bool lok[AXIS == CAFEQ_AXIS_COL ? 8 : 2];
+  };
+  auto issue = [&](LoadSet& L, int64_t t) {
+    const int64_t tt = t + 8 * half;
+    if (AXIS == CAFEQ_AXIS_COL) {
+      // uniform bases of the step's first row plus 32-bit lane offsets (rows past the chunk: its last row, dropped)
+      const int64_t tb = t < t1 ? t : t1 - 1;            // (a step past the chunk: its last row, all dropped)
+      const float* bx = a.X + tb * C + fbase;
+      const int8_t* bc = a.codes + tb * C + fbase;
+      const float* bs = a.scales + tb * (C / a.G);
+      const int gcol = int(fidx / a.G), cg = int(C / a.G);
+      const int rmax = t < t1 ? int(t1 - 1 - t < 15 ? t1 - 1 - t : 15) : -1;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int r0 = 8 * half + e;
+        L.lok[e] = r0 <= rmax;
+        const int r = r0 <= rmax ? r0 : (rmax >= 0 ? rmax : 0);
+        const uint32_t off = uint32_t(r) * uint32_t(C) + uint32_t(idx);
+        L.lc[e] = uint32_t(uint8_t(bc[off]));
+        L.lx[e] = bx[off];
+        L.lsc[e] = bs[uint32_t(r) * uint32_t(cg) + uint32_t(gcol)];
+      }
+    } else {
+      const int64_t grow = fidx / a.G;
+#pragma unroll
+      for (int q4 = 0; q4 < 2; ++q4) {
+        const int64_t c = tt + 4 * q4;
+        L.lok[q4] = c < t1;                               // tlen and chunk are multiples of 4
+        const int64_t cc = L.lok[q4] ? c : t1 - 4;
+        L.lc[q4] = *reinterpret_cast<const uint32_t*>(a.codes + fidx * C + cc);
+        const float4 vx = *reinterpret_cast<const float4*>(a.X + fidx * C + cc);
+        const float4 vs = *reinterpret_cast<const float4*>(a.scales + grow * C + cc);
+        L.lx[4 * q4] = vx.x; L.lx[4 * q4 + 1] = vx.y; L.lx[4 * q4 + 2] = vx.z; L.lx[4 * q4 + 3] = vx.w;
+        L.lsc[4 * q4] = vs.x; L.lsc[4 * q4 + 1] = vs.y; L.lsc[4 * q4 + 2] = vs.z; L.lsc[4 * q4 + 3] = vs.w;
+      }
+    }
+  };
+  auto commit = [&](const LoadSet& L, unsigned char* buf) {
+    float q[8], er[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      bool ok;
+      int code;
+      if (AXIS == CAFEQ_AXIS_COL) { ok = L.lok[e]; code = int(int8_t(L.lc[e])); }
+      else { ok = L.lok[e >> 2]; code = int(int8_t(L.lc[e >> 2] >> (8 * (e & 3)))); }
+      const float v = __fmul_rn(float(code), L.lsc[e]);
+      q[e] = ok ? v : 0.f;
+      er[e] = ok ? v - L.lx[e] : 0.f;
+    }
+    uintx4 ph, pm, pl;
+    split3_bf16(q, ph, pm, pl);
+    unsigned char* dst = buf + (side ? 3 * kG16PlaneB : 0) + idx * 32 + 16 * half;
+    *reinterpret_cast<uintx4*>(dst) = ph;
+    *reinterpret_cast<uintx4*>(dst + kG16PlaneB) = pm;
+    *reinterpret_cast<uintx4*>(dst + 2 * kG16PlaneB) = pl;
+    if (side) {
+      split3_bf16(er, ph, pm, pl);
+      *reinterpret_cast<uintx4*>(dst + 3 * kG16PlaneB) = ph;
+      *reinterpret_cast<uintx4*>(dst + 4 * kG16PlaneB) = pm;
+      *reinterpret_cast<uintx4*>(dst + 5 * kG16PlaneB) = pl;
+    }
+  };
+
+  const int ta = wave >> 1, tc0 = 2 * (wave & 1);
+  floatx16 accS[2], accR[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { accS[u][v] = 0.f; accR[u][v] = 0.f; }
+
+  auto products = [&](const unsigned char* buf) {
+    const unsigned char* pa = buf + (ta * 32 + ln) * 32 + 16 * h;
+    bf16x8 ax[3];
+#pragma unroll
+    for (int p = 0; p < 3; ++p) ax[p] = as_bf16x8(*reinterpret_cast<const uintx4*>(pa + p * kG16PlaneB));
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const unsigned char* pb = buf + 3 * kG16PlaneB + ((tc0 + u) * 32 + ln) * 32 + 16 * h;
+      bf16x8 bq[3], be[3];
+#pragma unroll
+      for (int p = 0; p < 3; ++p) {
+        bq[p] = as_bf16x8(*reinterpret_cast<const uintx4*>(pb + p * kG16PlaneB));
+        be[p] = as_bf16x8(*reinterpret_cast<const uintx4*>(pb + (3 + p) * kG16PlaneB));
+      }
+      // (smallest terms first)
+      accS[u] = CAFEQ_MFMA_BF16(ax[1], bq[1], accS[u]);
+      accS[u] = CAFEQ_MFMA_BF16(ax[0], bq[2], accS[u]);
+      accS[u] = CAFEQ_MFMA_BF16(ax[2], bq[0], accS[u]);
+      accS[u] = CAFEQ_MFMA_BF16(ax[0], bq[1], accS[u]);
+      accS[u] = CAFEQ_MFMA_BF16(ax[1], bq[0], accS[u]);
+      accS[u] = CAFEQ_MFMA_BF16(ax[0], bq[0], accS[u]);
+      accR[u] = CAFEQ_MFMA_BF16(ax[1], be[1], accR[u]);
+      accR[u] = CAFEQ_MFMA_BF16(ax[0], be[2], accR[u]);
+      accR[u] = CAFEQ_MFMA_BF16(ax[2], be[0], accR[u]);
+      accR[u] = CAFEQ_MFMA_BF16(ax[0], be[1], accR[u]);
+      accR[u] = CAFEQ_MFMA_BF16(ax[1], be[0], accR[u]);
+      accR[u] = CAFEQ_MFMA_BF16(ax[0], be[0], accR[u]);
+    }
+  };
+  // Two steps of requests in flight (one register set per LDS buffer), and between two barriers a wave both
+  // multiplies the step in one buffer and prepares the next step in the other (one barrier per step).  Requests
+  // past the end of the chunk read in-range addresses and are dropped.
+  LoadSet L0, L1;
+  unsigned char* buf0 = gsm;
+  unsigned char* buf1 = gsm + kG16BufB;
+  issue(L0, t0);
+  issue(L1, t0 + 16);
+  commit(L0, buf0);
+  for (int64_t t = t0; t < t1; t += 32) {
+    __syncthreads();                       // buf0 holds step t; buf1's readers (step t - 16) are done
+    issue(L0, t + 32);
+    products(buf0);
+    if (t + 16 < t1) {
+      commit(L1, buf1);
+      __syncthreads();                     // buf1 holds step t + 16; buf0's readers are done
+      issue(L1, t + 48);
+      products(buf1);
+      if (t + 32 < t1) commit(L0, buf0);
+    }
+  }
+
+  // partial[b][z][0|1][row][col]
+  float* out = a.partial + ((size_t(b) * gridDim.z + z) * 2) * size_t(K) * K;
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int col = 128 * qJ + (tc0 + u) * 32 + ln;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = 128 * qI + ta * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+      out[size_t(row) * K + col] = accS[u][v];
+      out[size_t(K) * K + size_t(row) * K + col] = accR[u][v];
+    }
+  }
 }
 
 // ---- paired quantization error from the Gram triples -------------------------------------------
@@ -1071,6 +1256,31 @@ int launch_gram(int axis, const float* X, const int8_t* codes, const float* scal
   a.rep = axis == CAFEQ_AXIS_COL ? 1 : rep;
   a.tlen = axis == CAFEQ_AXIS_COL ? rows : cols;
   a.chunk = chunk; a.nchunk = nchunk; a.partial = partial;
+  if (!triple && (K == 128 || K == 256)) {
+    // heads of 128 and 256: the 16-bit kernel, one workgroup per (head, quadrant of 128 x 128, chunk)
+    const dim3 g16(nb, (K / 128) * (K / 128), a.rep * nchunk);
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set) {
+      bool ok = true;
+#define CAFEQ_ATTR16(AX, KK)                                                                                    \
+  ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(gram_pair16_kernel<AX, KK>),                    \
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, int(kG16Lds)) == hipSuccess
+      CAFEQ_ATTR16(CAFEQ_AXIS_COL, 128); CAFEQ_ATTR16(CAFEQ_AXIS_COL, 256);
+      CAFEQ_ATTR16(CAFEQ_AXIS_ROW, 128); CAFEQ_ATTR16(CAFEQ_AXIS_ROW, 256);
+#undef CAFEQ_ATTR16
+      if (!ok) return CAFEQ_ERR_LAUNCH;
+      attr_set = true;
+    }
+    if (axis == CAFEQ_AXIS_COL) {
+      if (K == 128) hipLaunchKernelGGL((gram_pair16_kernel<CAFEQ_AXIS_COL, 128>), g16, dim3(512), kG16Lds, st, a);
+      else hipLaunchKernelGGL((gram_pair16_kernel<CAFEQ_AXIS_COL, 256>), g16, dim3(512), kG16Lds, st, a);
+    } else {
+      if (K == 128) hipLaunchKernelGGL((gram_pair16_kernel<CAFEQ_AXIS_ROW, 128>), g16, dim3(512), kG16Lds, st, a);
+      else hipLaunchKernelGGL((gram_pair16_kernel<CAFEQ_AXIS_ROW, 256>), g16, dim3(512), kG16Lds, st, a);
+    }
+    CAFEQ_CHECK_LAUNCH();
+    return CAFEQ_OK;
+  }
   dim3 grid(nb, K / 32, a.rep * nchunk);
 #define CAFEQ_GRAM(KK)                                                                                          \
   case KK:                                                                                                      \

@@ -57,8 +57,9 @@ __global__ __launch_bounds__(kSplitThreads) void split_planes_kernel(const Split
   const int K = js.K, nst = K / 32;
   // partial headers that no workgroup of the core writes (slots nobody owns) must read as empty
   if (js.hdr) {
-    const int64_t nthr = int64_t(gridDim.x) * gridDim.y * kSplitThreads;
-    for (int64_t i = (int64_t(blockIdx.y) * gridDim.x + blockIdx.x) * kSplitThreads + threadIdx.x; i < js.nhdr; i += nthr)
+    const int64_t nthr = int64_t(gridDim.x) * gridDim.y * gridDim.z * kSplitThreads;
+    for (int64_t i = ((int64_t(blockIdx.z) * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * kSplitThreads + threadIdx.x;
+         i < js.nhdr; i += nthr)
       js.hdr[i] = (i % kHdrFloats) == kHdrMref ? -INFINITY : 0.f;
   }
   const SplitJob jb = js.job[blockIdx.y];
@@ -81,9 +82,10 @@ __global__ __launch_bounds__(kSplitThreads) void split_planes_kernel(const Split
     int ex = int(__float_as_uint(m) >> 23);
     ex = ex < 32 ? 32 : (ex > 254 ? 254 : ex);
     hsc = __uint_as_float(uint32_t(254 + jb.texp - ex) << 23);             // 2^(texp - (ex - 127))
-    if (threadIdx.x == 0) jb.fscale[blockIdx.x] = __uint_as_float(uint32_t(ex - jb.texp) << 23);
+    if (threadIdx.x == 0 && blockIdx.z == 0) jb.fscale[blockIdx.x] = __uint_as_float(uint32_t(ex - jb.texp) << 23);
   }
-  for (int stage = 0; stage < nst; ++stage) {
+  // (grid z: with few blocks the stages of a block are dealt out to several workgroups)
+  for (int stage = blockIdx.z; stage < nst; stage += gridDim.z) {
     uint16_t* buf = lds;
     uint16_t* db = jb.dst + (size_t(blockIdx.x) * nst + stage) * nplanes * K * 32;
     // a thread takes four inputs that are adjacent in the plane (e = 0..3 of one (row, step, half, u)):
@@ -569,7 +571,9 @@ int launch_split_planes_multi(const SplitRequest* req, int n, int K, int nb, hip
     js.job[i].trans = req[i].trans; js.job[i].nplanes = req[i].fscale ? 2 : req[i].nplanes;
     js.job[i].fscale = req[i].fscale; js.job[i].natural = req[i].natural; js.job[i].texp = req[i].texp;
   }
-  hipLaunchKernelGGL(split_planes_kernel, dim3(nb, n), dim3(kSplitThreads), 0, st, js);
+  // one workgroup per (block, job) when those fill the chip; else one per (block, job, stage)
+  const int zsplit = nb * n >= 128 ? 1 : K / 32;
+  hipLaunchKernelGGL(split_planes_kernel, dim3(nb, n, zsplit), dim3(kSplitThreads), 0, st, js);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }
