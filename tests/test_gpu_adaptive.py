@@ -39,12 +39,15 @@ def _dequant(codes, scales, group, axis):
     return codes.astype(np.float64) * np.repeat(scales.astype(np.float64), group, axis=1 if axis == O.COL else 0)
 
 
-@pytest.mark.parametrize("k,group,rep,bits", [(64, 64, 2, 4), (32, 32, 1, 3), (128, 64, 2, 4), (256, 64, 1, 4)])
-def test_each_line_against_oracle(env, k, group, rep, bits):
+# (the last two: contraction lengths that end 12 and 4 into a step of 16 of the Gram kernels for heads of 128 / 256,
+# shared heads with blocks of 256)
+@pytest.mark.parametrize("k,group,rep,bits,extra", [(64, 64, 2, 4, 0), (32, 32, 1, 3, 0), (128, 64, 2, 4, 0),
+                                                    (256, 64, 1, 4, 0), (256, 64, 2, 4, 260), (128, 64, 1, 4, 268)])
+def test_each_line_against_oracle(env, k, group, rep, bits, extra):
     torch, cafeq = env
     nb = 2
     # rows of U and columns of V: at least k (full rank), ragged against the 128-line macro-tile
-    U, V = _pair(200 if k <= 128 else 328, 136 if k <= 128 else 296, k, nb, rep, 500 + k)
+    U, V = _pair((200 if k <= 128 else 328) + extra, (136 if k <= 128 else 296) + extra, k, nb, rep, 500 + k + extra)
     cu, su, _ = O.rtn_sym(U, bits, group, O.COL)
     Uh = _dequant(cu, su, group, O.COL)
     # oracle: line 3 then line 4
