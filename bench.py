@@ -209,6 +209,28 @@ def pair_workload(args, secondary=True):
                  "executed_frac_of_f16_peak": executed / F16_MFMA_PEAK_TFLOPS,
                  "achieved_over_fp32_mfma_peak": achieved / FP32_MFMA_PEAK_TFLOPS},
         "whole_step_hbm_frac_at_one_read_of_the_weights": 4.0 * elems * args.steps / dt / 1e9 / HBM_PEAK_GBS}
+    # the step's other large kernel, timed the same way in a short loop of its own (one table times one kind of
+    # launch): the gradient pass reads both members' second prepared copy once, 4 B per element
+    gsteps = max(10, min(args.steps, 50))
+    gtimer = cafeq.LaunchTimer(gsteps // 5 + 2, every=5, kind=1)
+    with gtimer:
+        for _ in range(gsteps):
+            step()
+        torch.cuda.synchronize()
+    gd = gtimer.durations_ms()
+    if gd:
+        g_s = sum(gd) / len(gd) * 1e-3
+        g_launches = max(1, round(gtimer.table.seen / float(gsteps)))
+        g_el = elems / g_launches
+        result["roofline_gradient_pass"] = {
+            "bound": "hbm", "achieved": 4.0 * g_el / g_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": 4.0 * g_el / g_s / 1e9 / HBM_PEAK_GBS,
+            "traffic": measured_traffic("loss_prepared_c3_pair.md", "gradient_traffic_bytes_per_launch"),
+            "kernel": "grad_v2_owner_kernel (gradient pass over prepared weights, one workgroup per member and block)",
+            "launches": len(gd), "launches_in_timed_region": int(gtimer.table.seen),
+            "weight_elements_per_launch": g_el, "avg_launch_us": g_s * 1e6,
+            "algorithmic_bytes_per_element": 4, "algorithmic_flop_per_element": 2 * k,
+            "executed_part_product_tflops": 3.0 * 2.0 * k * g_el / g_s / 1e12}
     # what this machine's memory system delivers to plain streaming kernels on data that no cache holds (the published
     # 8 TB/s stays the roofline's peak; these two figures say how far any kernel gets towards it here)
     probe = memory_probe(torch, dev, cafeq)

@@ -348,7 +348,9 @@ int cafeq_optimize_pair(const cafeq_mat* A, const cafeq_mat* B, float* T, float*
  * timed.  every > 1 times only every `every`-th such launch (an event pair costs the stream several
  * microseconds; `seen` counts all of them and starts at 0).  The library creates, destroys and synchronises nothing: the caller synchronises the stream and reads
  * hipEventElapsedTime(start[i], stop[i]).  The table (host memory) must stay valid until it is replaced or
- * removed with NULL.  One table per process; not thread-safe. */
+ * removed with NULL.  One table per process; not thread-safe.
+ * kind selects what is timed: 0 the fused transform kernel (the loss pass), 1 the gradient pass over the weights
+ * (the second pass of the calls that take the gradient from arg-max records; fused-gradient kernels are kind 0). */
 typedef struct {
   void** start;
   void** stop;
@@ -356,6 +358,7 @@ typedef struct {
   int count;
   int every;
   int seen;
+  int kind;
 } cafeq_launch_timing;
 int cafeq_set_launch_timing(cafeq_launch_timing* t);
 

@@ -53,7 +53,7 @@ class QuantCfg(ctypes.Structure):
 class LaunchTiming(ctypes.Structure):
     _fields_ = [("start", ctypes.POINTER(ctypes.c_void_p)), ("stop", ctypes.POINTER(ctypes.c_void_p)),
                 ("capacity", ctypes.c_int32), ("count", ctypes.c_int32), ("every", ctypes.c_int32),
-                ("seen", ctypes.c_int32)]
+                ("seen", ctypes.c_int32), ("kind", ctypes.c_int32)]
 
 
 class OptCfg(ctypes.Structure):
@@ -325,9 +325,10 @@ def stream_read_probe(buf, sink=None):
 class LaunchTimer:
     """Caller-owned events around the fused-kernel launches (cafeq_set_launch_timing): `capacity` pairs of
     torch events are created up front; the library only records them.  every > 1: only every `every`-th launch
-    is timed (an event pair holds the stream up for several microseconds)."""
+    is timed (an event pair holds the stream up for several microseconds).  kind: 0 the loss pass (fused transform
+    kernel), 1 the gradient pass over the weights."""
 
-    def __init__(self, capacity, every=1):
+    def __init__(self, capacity, every=1, kind=0):
         self.ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(capacity)]
         for a, b in self.ev:          # torch creates the underlying event on first use
             a.record()
@@ -335,7 +336,7 @@ class LaunchTimer:
         torch.cuda.synchronize()
         self.start = (ctypes.c_void_p * capacity)(*[a.cuda_event for a, _ in self.ev])
         self.stop = (ctypes.c_void_p * capacity)(*[b.cuda_event for _, b in self.ev])
-        self.table = LaunchTiming(self.start, self.stop, capacity, 0, every, 0)
+        self.table = LaunchTiming(self.start, self.stop, capacity, 0, every, 0, kind)
 
     def __enter__(self):
         self.table.count = 0

@@ -6,6 +6,13 @@
 #include "loss_reduce.hpp"
 
 using namespace cafeq;
+namespace cafeq {
+// (defined further down, next to the timing table)
+int launch_grad_owner_timed(const GradOwnerJob* jobs, int n, int loss_kind, float beta, float lse_t, const double* lse_ms,
+                            hipStream_t st, const LossArgs* fold);
+int launch_grad_v2_timed(const CoreParams& p, hipStream_t st);
+int launch_grad_pass_timed(int K, int axis, const CoreParams& p, hipStream_t st);
+}  // namespace cafeq
 
 namespace {
 
@@ -445,9 +452,9 @@ int run_grad_pass(int K, int axis, const cafeq_mat* W, int rep, const PassPlans&
     const bool col = axis == CAFEQ_AXIS_COL;
     const PreparedLayout l = prepared_layout(col ? W->rows : W->cols, col ? W->cols : W->rows);
     pg->prep_gtiles = static_cast<const unsigned char*>(W->prepared) + l.off_gtiles;
-    return launch_grad_v2(*pg, st);
+    return launch_grad_v2_timed(*pg, st);
   }
-  return launch_grad_pass(K, axis, *pg, st);
+  return launch_grad_pass_timed(K, axis, *pg, st);
 }
 
 }  // namespace
@@ -476,9 +483,9 @@ int launch_core_raw(int K, int G, int axis, const CoreParams& p, hipStream_t st)
   }
 }
 template <typename F>
-int timed_launch(hipStream_t st, F&& launch) {
+int timed_launch(hipStream_t st, F&& launch, int kind = 0) {
   cafeq_launch_timing* t = g_timing;
-  if (!t || t->count >= t->capacity) return launch();
+  if (!t || t->kind != kind || t->count >= t->capacity) return launch();
   const int nth = t->seen++;
   if (t->every > 1 && nth % t->every != 0) return launch();
   const int i = t->count;
@@ -497,6 +504,17 @@ int launch_loss_prepared(int G, int axis, const CoreParams& p, hipStream_t st) {
 }
 int launch_loss_prepared_pair(int G, const CoreParams& pa, const CoreParams& pb, hipStream_t st) {
   return timed_launch(st, [&] { return launch_loss_v2_pair(G, pa, pb, st); });
+}
+// the gradient pass over the weights, with the caller's timing events when the table asks for kind 1
+int launch_grad_owner_timed(const GradOwnerJob* jobs, int n, int loss_kind, float beta, float lse_t, const double* lse_ms,
+                            hipStream_t st, const LossArgs* fold) {
+  return timed_launch(st, [&] { return launch_grad_v2_owner(jobs, n, loss_kind, beta, lse_t, lse_ms, st, fold); }, 1);
+}
+int launch_grad_v2_timed(const CoreParams& p, hipStream_t st) {
+  return timed_launch(st, [&] { return launch_grad_v2(p, st); }, 1);
+}
+int launch_grad_pass_timed(int K, int axis, const CoreParams& p, hipStream_t st) {
+  return timed_launch(st, [&] { return launch_grad_pass(K, axis, p, st); }, 1);
 }
 size_t core_lds_bytes(int K, int G, bool do_grad) {
   switch (K) {
@@ -1019,7 +1037,7 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
       LossArgs la{};
       la.hdrA = w.slot_hdr; la.nslotA = int(pl.nslot); la.kind = kLossSur; la.beta = beta; la.losses = losses;
       la.lse_ms = w.lse_ms;
-      if ((rc = launch_grad_v2_owner(&job, 1, kLossSur, beta, 0.f, nullptr, st, &la))) return rc;
+      if ((rc = launch_grad_owner_timed(&job, 1, kLossSur, beta, 0.f, nullptr, st, &la))) return rc;
     } else {
       if (pp.two &&
           (rc = run_grad_pass(K, cfg->axis, W, x->rep, pp, w.m, kLossSur, beta, 0.f, nullptr, 0, nullptr, &pg, st)))
@@ -1158,7 +1176,7 @@ static int dual_impl(const cafeq_mat* A, const cafeq_mat* B, const cafeq_xform* 
     LossArgs la{};
     la.hdrA = w.hdrA; la.nslotA = int(pa.nslot); la.hdrB = w.hdrB; la.nslotB = int(pb.nslot); la.kind = kLossLse;
     la.t = lse_t; la.ngroups = ngroups; la.losses = losses; la.lse_ms = w.lse_ms;
-    if ((rc = launch_grad_v2_owner(jobs, 2, kLossLse, 0.f, lse_t, w.lse_ms, st, &la))) return rc;
+    if ((rc = launch_grad_owner_timed(jobs, 2, kLossLse, 0.f, lse_t, w.lse_ms, st, &la))) return rc;
     if ((rc = launch_bgemm_chain(x->Tinv, w.gp, w.x1, gradT, K, nb, -1.f, 1.f, st, adam))) return rc;
   } else if (grad) {
     // member A into gradT; member B: G_P of transform block b sums its rep row-blocks; d/dT = -P^T G_P P^T
