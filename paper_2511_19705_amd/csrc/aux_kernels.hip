@@ -193,19 +193,17 @@ struct ReduceArgs {
 // over the partials of q's segment, in fixed order; each thread owns four consecutive inputs of one
 // output row, each workgroup 1024 elements that lie in one partial layout (one half when msplit == 2).
 struct ReduceJobs { ReduceArgs job[2]; };   // grid.z picks the job (the two members of a pair in one launch)
-__global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceJobs js) {
-  const ReduceArgs& a = js.job[blockIdx.z];
+__device__ __forceinline__ void reduce_grad_body(const ReduceArgs& a, const int b, const int by) {
   constexpr int kBatch = 64;
   __shared__ const float* src[kBatch];
   __shared__ float scl[kBatch];
   __shared__ int rng_lo, rng_hi;
-  const int b = blockIdx.x;
   const int K = a.K;
   // this workgroup's 1024 elements: rows of KMr inputs inside one half
   const int KMr = a.msplit == 2 ? 128 : K;
   const int rows_per_wg = 1024 / KMr;                       // K = 32: one workgroup covers the block
   const int nyh = K / rows_per_wg > 0 ? K / rows_per_wg : 1;
-  const int half = int(blockIdx.y) / nyh, rg = int(blockIdx.y) % nyh;
+  const int half = by / nyh, rg = by % nyh;
   const int j = rg * rows_per_wg + (threadIdx.x * 4) / KMr, ml = (threadIdx.x * 4) % KMr;
   const bool active = j < K;
   const int poff = j * KMr + ml;                            // offset inside a partial (plus the block's base)
@@ -269,6 +267,9 @@ __global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceJobs js) {
     }
   }
 }
+__global__ __launch_bounds__(256) void reduce_grad_kernel(const ReduceJobs js) {
+  reduce_grad_body(js.job[blockIdx.z], int(blockIdx.x), int(blockIdx.y));
+}
 
 // v[axis index] = beta * sum over partials of the group's sum a^2, expanded per index, then
 // Mmid_b = diag(v_b) P_b (scale_rows) or P_b diag(v_b).  For AXIS_ROW with rep > 1 the rep
@@ -283,10 +284,10 @@ struct VArgs {
   int scale_rows;
   float* Mmid;
 };
-__global__ __launch_bounds__(256) void build_mmid_kernel(const VArgs a) {
+__device__ __forceinline__ void build_mmid_body(const VArgs& a, const int b) {
   __shared__ float v[256];
   __shared__ int rng[2];
-  const int b = blockIdx.x, K = a.K, n = threadIdx.x;   // K <= 256 = blockDim.x: thread n owns index n
+  const int K = a.K, n = threadIdx.x;   // K <= 256 = blockDim.x: thread n owns index n
   double acc = 0;
   for (int q = b * a.rep; q < (b + 1) * a.rep; ++q) {
     // the K axis indices of a row-block lie in one segment (L is a multiple of K): its range of
@@ -311,12 +312,30 @@ __global__ __launch_bounds__(256) void build_mmid_kernel(const VArgs a) {
   float* Mb = a.Mmid + size_t(b) * K * K;
   for (int i = threadIdx.x; i < K * K; i += blockDim.x) Mb[i] = Pb[i] * (a.scale_rows ? v[i / K] : v[i % K]);
 }
+__global__ __launch_bounds__(256) void build_mmid_kernel(const VArgs a) { build_mmid_body(a, int(blockIdx.x)); }
 
 // losses: fixed-order float64 sums over every partial header (loss_reduce.hpp), as a launch of its own
 __global__ __launch_bounds__(kLossThreads) void reduce_losses_kernel(const LossArgs a) {
   __shared__ double red[5 * (kLossThreads / 64)];
   double m, s;
   reduce_losses_body<kLossThreads>(a, red, true, &m, &s);
+}
+
+// What follows the loss / gradient kernel of a single matrix whose gradient comes as partials, in one launch:
+// the gradient reduction (nred_x x nred_y workgroups), the middle factor of the gradient's way through rho(P) (one
+// workgroup per block) and the loss reduction (one workgroup) read the same partials and do not depend on each other.
+__global__ __launch_bounds__(256) void single_tail_kernel(const ReduceArgs ra, const VArgs va, const LossArgs la,
+                                                          const int nred_x, const int nred_y, const int nb) {
+  const int id = int(blockIdx.x), nred = nred_x * nred_y;
+  if (id < nred) {
+    reduce_grad_body(ra, id % nred_x, id / nred_x);
+  } else if (id < nred + nb) {
+    build_mmid_body(va, id - nred);
+  } else {
+    __shared__ double red[5 * (kLossThreads / 64)];
+    double m, sm;
+    reduce_losses_body<kLossThreads>(la, red, true, &m, &sm);
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -455,29 +474,33 @@ __global__ __launch_bounds__(256) void bgemm_mfma_kernel(const float* __restrict
 // row-major with a row stride of 129 floats, which serves the first product's A operand (lanes along a row) and
 // the second's B operand (lanes along a column) without bank conflicts; G goes from memory straight into the
 // registers of the wave that multiplies by it; X passes through LDS transposed.
-constexpr int kChainLdP = 129, kChainLdX = 33;
-constexpr size_t kChainLds = (128 * kChainLdP + 2 * 128 * kChainLdX) * sizeof(float);
-__global__ __launch_bounds__(512) void bgemm_chain128_kernel(const float* __restrict__ P, const float* __restrict__ G,
-                                                             float* __restrict__ C, float alpha, float beta,
-                                                             const AdamHook adam) {
-  constexpr int K = 128;
+// (Blocks of 64: one workgroup of four waves per block, the same scheme.)
+constexpr int kChainLdX = 33;
+constexpr size_t chain_lds(int K) { return size_t(K * (K + 1) + 2 * K * kChainLdX) * sizeof(float); }
+template <int K>
+__global__ __launch_bounds__(4 * K) void bgemm_chain_kernel(const float* __restrict__ P, const float* __restrict__ G,
+                                                            float* __restrict__ C, float alpha, float beta,
+                                                            const AdamHook adam) {
+  static_assert(K == 64 || K == 128, "slices of 64 rows");
+  constexpr int kChainLdP = K + 1, NT = 4 * K, WJ = K / 32, SL = K / 64;   // threads, column tiles, slices per block
   extern __shared__ __align__(16) float csm[];
   float* sp = csm;                          // P[r][c]
   float* sx = csm + K * kChainLdP;          // [2 row halves][l][32 rows]: X^T of the workgroup's slice
-  const int b = blockIdx.x >> 1, i0 = (blockIdx.x & 1) * 64;
+  const int b = blockIdx.x / SL, i0 = (blockIdx.x % SL) * 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ln = lane & 31, h = lane >> 5;
-  const int wi = wave >> 2, wj = wave & 3;
+  const int wi = wave / WJ, wj = wave % WJ;
   const float* Pb = P + size_t(b) * K * K;
   const float* Gb = G + size_t(b) * K * K;
   float* Cb = C + size_t(b) * K * K;
   // every load of the workgroup is requested before the first wait: P (for LDS), this wave's columns of G, and the
   // old value of the output where it is added to
-  float4 vp[8];
+  constexpr int NVP = K * K / 4 / NT;       // float4 of P per thread
+  float4 vp[NVP];
 #pragma unroll
-  for (int u = 0; u < 8; ++u) vp[u] = *reinterpret_cast<const float4*>(Pb + (tid + u * 512) * 4);
-  float g[64];
+  for (int u = 0; u < NVP; ++u) vp[u] = *reinterpret_cast<const float4*>(Pb + (tid + u * NT) * 4);
+  float g[K / 2];
 #pragma unroll
-  for (int t = 0; t < 64; ++t) g[t] = Gb[(2 * t + h) * K + wj * 32 + ln];
+  for (int t = 0; t < K / 2; ++t) g[t] = Gb[(2 * t + h) * K + wj * 32 + ln];
   float cold[16];
 #pragma unroll
   for (int v = 0; v < 16; ++v) cold[v] = 0.f;
@@ -486,8 +509,8 @@ __global__ __launch_bounds__(512) void bgemm_chain128_kernel(const float* __rest
     for (int v = 0; v < 16; ++v) cold[v] = Cb[(i0 + wi * 32 + 8 * (v / 4) + 4 * h + (v % 4)) * K + wj * 32 + ln];
   }
 #pragma unroll
-  for (int u = 0; u < 8; ++u) {
-    const int e = (tid + u * 512) * 4, r = e >> 7, c = e & 127;
+  for (int u = 0; u < NVP; ++u) {
+    const int e = (tid + u * NT) * 4, r = e / K, c = e % K;
     float* d = sp + r * kChainLdP + c;
     d[0] = vp[u].x; d[1] = vp[u].y; d[2] = vp[u].z; d[3] = vp[u].w;
   }
@@ -499,7 +522,7 @@ __global__ __launch_bounds__(512) void bgemm_chain128_kernel(const float* __rest
     // X[i][j] = sum_l P[l][i] G[l][j]
     const float* pa = sp + h * kChainLdP + i0 + wi * 32 + ln;
 #pragma unroll
-    for (int t = 0; t < 64; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[2 * t * kChainLdP], g[t], acc, 0, 0, 0);
+    for (int t = 0; t < K / 2; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[2 * t * kChainLdP], g[t], acc, 0, 0, 0);
   }
   {
     float* xw = sx + wi * (K * kChainLdX) + (wj * 32 + ln) * kChainLdX;
@@ -514,7 +537,7 @@ __global__ __launch_bounds__(512) void bgemm_chain128_kernel(const float* __rest
     const float* pa = sx + wi * (K * kChainLdX) + h * kChainLdX + ln;
     const float* pb = sp + (wj * 32 + ln) * kChainLdP + h;
 #pragma unroll 8
-    for (int t = 0; t < 64; ++t)
+    for (int t = 0; t < K / 2; ++t)
       acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[2 * t * kChainLdX], pb[2 * t], acc, 0, 0, 0);
   }
 #pragma unroll
@@ -639,6 +662,23 @@ int launch_build_mmid(const CoreParams& p, int K, int G, int nb, const float* P,
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }
+int launch_single_tail(const CoreParams& pgrad, const CoreParams& ploss, int K, int G, bool fused, int nb,
+                       int transpose_out, float* gradT, const float* P, int scale_rows, float* Mmid, float beta,
+                       int nslot, float* losses, double* lse_ms, hipStream_t st) {
+  const ReduceArgs ra = reduce_args(pgrad, K, G, fused, transpose_out, nullptr, nullptr, gradT);
+  VArgs va;
+  va.slot_hdr = ploss.slot_hdr; va.mt_per_seg = ploss.mt_per_seg; va.n_mt = ploss.n_mt; va.nwg = ploss.nwg;
+  va.K = K; va.L = K > G ? K : G; va.G = G; va.rep = ploss.rep; va.beta = ploss.beta; va.P = P;
+  va.scale_rows = scale_rows; va.Mmid = Mmid;
+  LossArgs la{};
+  la.hdrA = ploss.slot_hdr; la.nslotA = nslot; la.kind = kLossSur; la.beta = beta; la.losses = losses;
+  la.lse_ms = lse_ms;
+  const int nred_x = nb, nred_y = (K * K + 1023) / 1024;
+  hipLaunchKernelGGL(single_tail_kernel, dim3(unsigned(nred_x * nred_y + nb + 1)), dim3(256), 0, st, ra, va, la,
+                     nred_x, nred_y, nb);
+  CAFEQ_CHECK_LAUNCH();
+  return CAFEQ_OK;
+}
 int launch_reduce_losses(int kind, const float* hdrA, int nslotA, const float* hdrB, int nslotB, float beta,
                          float t, int64_t ngroups, float* losses, double* lse_ms, hipStream_t st) {
   LossArgs a;
@@ -695,7 +735,7 @@ int launch_bgemm(bool ta, bool tb, const float* A, const float* B, float* C, int
 // C = beta C + alpha (P^T G) P^T per block; x1: scratch of nb K K floats for block sizes other than 128
 int launch_bgemm_chain(const float* P, const float* G, float* x1, float* C, int K, int nb, float alpha, float beta,
                        hipStream_t st, const AdamHook* adam) {
-  if (K != 128) {
+  if (K != 128 && K != 64) {
     const int rc = launch_bgemm(true, false, P, G, x1, K, nb, 1.f, 0.f, st);
     if (rc) return rc;
     return launch_bgemm(false, true, x1, P, C, K, nb, alpha, beta, st, adam);
@@ -705,12 +745,17 @@ int launch_bgemm_chain(const float* P, const float* G, float* x1, float* C, int 
   if (adam) hook = *adam;
   static std::atomic<bool> attr_set{false};
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(bgemm_chain128_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, int(kChainLds)) != hipSuccess)
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(bgemm_chain_kernel<128>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, int(chain_lds(128))) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(bgemm_chain_kernel<64>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, int(chain_lds(64))) != hipSuccess)
       return CAFEQ_ERR_LAUNCH;
     attr_set = true;
   }
-  hipLaunchKernelGGL(bgemm_chain128_kernel, dim3(unsigned(nb) * 2), dim3(512), kChainLds, st, P, G, C, alpha, beta, hook);
+  if (K == 128)
+    hipLaunchKernelGGL(bgemm_chain_kernel<128>, dim3(unsigned(nb) * 2), dim3(512), chain_lds(128), st, P, G, C, alpha, beta, hook);
+  else
+    hipLaunchKernelGGL(bgemm_chain_kernel<64>, dim3(unsigned(nb)), dim3(256), chain_lds(64), st, P, G, C, alpha, beta, hook);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }

@@ -1025,8 +1025,9 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   const PassPlans* pps[1] = {&pp};
   const bool owner = grad && grad_owner_eligible(mats, pps, 1, K, x->rep);
   // (with one workgroup per block in the gradient pass, its first workgroup reduces the losses: one launch less)
-  if (!owner && (rc = launch_reduce_losses(kLossSur, w.slot_hdr, int(pl.nslot), nullptr, 0, beta, 0.f, 0, losses,
-                                           w.lse_ms, st)))
+  // (with gradient partials, the loss reduction rides in the launch that reduces them)
+  if (!grad && (rc = launch_reduce_losses(kLossSur, w.slot_hdr, int(pl.nslot), nullptr, 0, beta, 0.f, 0, losses,
+                                          w.lse_ms, st)))
     return rc;
   if (grad) {
     // path through Z (fused into the pass above, or a second pass over the weights from its
@@ -1042,9 +1043,12 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
       if (pp.two &&
           (rc = run_grad_pass(K, cfg->axis, W, x->rep, pp, w.m, kLossSur, beta, 0.f, nullptr, 0, nullptr, &pg, st)))
         return rc;
-      if ((rc = launch_reduce_grad(pg, K, gp.Gk, pp.fused, nb, col ? 1 : 0, nullptr, nullptr, gradT, st))) return rc;
+      // gradient reduction, the middle factor of the rho path and the loss reduction in one launch
+      if ((rc = launch_single_tail(pg, p, K, gp.Gk, pp.fused, nb, col ? 1 : 0, gradT, x->Tinv, col ? 1 : 0, w.mmid, beta,
+                                   int(pl.nslot), losses, w.lse_ms, st)))
+        return rc;
     }
-    if ((rc = launch_build_mmid(p, K, gp.Gk, nb, x->Tinv, col ? 1 : 0, w.mmid, st))) return rc;
+    if (owner && (rc = launch_build_mmid(p, K, gp.Gk, nb, x->Tinv, col ? 1 : 0, w.mmid, st))) return rc;
     if ((rc = launch_bgemm_chain(x->Tinv, w.mmid, w.x1, gradT, K, nb, -2.f, 1.f, st))) return rc;
   }
   return CAFEQ_OK;

@@ -100,6 +100,10 @@ int launch_reduce_grad_pair(const CoreParams& pa, int GA, bool fusedA, const flo
                             int nb, const double* lse_ms, hipStream_t st);
 int launch_build_mmid(const CoreParams& p, int K, int G, int nb, const float* P, int scale_rows, float* Mmid,
                       hipStream_t st);
+// gradient reduction + middle factor of the rho path + loss reduction of a single matrix in one launch
+int launch_single_tail(const CoreParams& pgrad, const CoreParams& ploss, int K, int G, bool fused, int nb,
+                       int transpose_out, float* gradT, const float* P, int scale_rows, float* Mmid, float beta,
+                       int nslot, float* losses, double* lse_ms, hipStream_t st);
 int launch_reduce_losses(int kind, const float* hdrA, int nslotA, const float* hdrB, int nslotB, float beta,
                          float t, int64_t ngroups, float* losses, double* lse_ms, hipStream_t st);
 // Adam step applied by the product's epilogue instead of storing the product: the value alpha op(A) op(B) + beta C is
