@@ -257,7 +257,7 @@ def pair_workload(args, secondary=True):
         sub = argparse.Namespace(**vars(args))
         sub.no_cpu_baseline = True
         sub.steps, sub.warmup = n2, 3
-        for name in ("c3_rtn", "c3_optimize", "c2_single", "c4_adaptive", "c5_layer"):
+        for name in ("c3_rtn", "c3_optimize", "c2_single", "c4_dual", "c4_adaptive", "c5_layer"):
             sub.workload = name
             r = WORKLOADS[name](sub)
             sec.append({"workload": r["config"]["workload"], "metric": r["metric"], "steps": r["steps"],
@@ -323,6 +323,32 @@ def core_workload(args):
                 O.surrogate(w, t, p_, cfg["bits"][0], cfg["group"], 0, 1)
             dt = time.perf_counter() - t0
             return w.size * 3 / dt, "%d of %d blocks, 3 x (inverse + fwd+bwd), %.1f s" % (nbk, cfg["T"].shape[0], dt)
+    elif args.workload == "c4_dual":
+        # the paired loss and gradient at the block size the paper runs the 9B model with (per-head 256 x 256, kv heads
+        # shared by two query heads): block inverse + cafeq_dual_proxy_loss_fwd_bwd with gradient
+        cfg = WL.config4()
+        k, rep, g, bits = cfg["k"], cfg["rep"], cfg["group"], cfg["bits"][0]
+        A, B = torch.from_numpy(cfg["A"]).to(dev), torch.from_numpy(cfg["B"]).to(dev)
+        T = torch.from_numpy(cfg["T"]).to(dev)
+        elems = A.numel() + B.numel()
+
+        def run(n):
+            for _ in range(n):
+                P, _ = cafeq.block_inverse(T)
+                cafeq.dual_proxy_loss_fwd_bwd(A, B, T, P, bits, g, rep, 5.0, want_grad=True)
+        metric = "proxy-loss fwd+bwd weight-elements/s (9B-shaped attention V/O pair, per-head 256 x 256 dual transform)"
+        flop_el, parts, kern, name = 4 * k, 9, "xform_core_kernel<256,64,*,false,true> (loss pass)", cfg["name"] + "_dual"
+
+        def cpu():
+            from oracle import cafeq_oracle as O
+            nh = 2
+            a = np.ascontiguousarray(cfg["A"][:, :nh * k]); b = np.ascontiguousarray(cfg["B"][:nh * rep * k, :])
+            t = cfg["T"][:nh]
+            t0 = time.perf_counter()
+            p_ = O.block_inverse(t)
+            O.dual_lse(a, b, t, p_, bits, g, rep, 5.0)
+            dt = time.perf_counter() - t0
+            return (a.size + b.size) / dt, "%d of %d heads, 1 x (inverse + fwd+bwd), %.1f s" % (nh, cfg["T"].shape[0], dt)
     else:
         cfg = WL.config4()
         k, rep, g, bits = cfg["k"], cfg["rep"], cfg["group"], cfg["bits"][0]
@@ -570,7 +596,7 @@ def rtn_workload(args):
     return res
 
 
-WORKLOADS = {"c3_optimize": core_workload, "c2_single": core_workload, "c4_adaptive": core_workload,
+WORKLOADS = {"c3_optimize": core_workload, "c2_single": core_workload, "c4_adaptive": core_workload, "c4_dual": core_workload,
              "c5_layer": layer_workload, "c2_infer": infer_workload, "c3_infer": infer_workload, "c3_rtn": rtn_workload}
 
 

@@ -873,6 +873,78 @@ __global__ __launch_bounds__(256) void sum_partials64_kernel(const float* __rest
     res[size_t(b) * K * K + e] = r;
   }
 }
+// ---- blocks of 256 near a (scaled) rotation: Newton-Schulz rounds on the matrix cores before any elimination.
+// X0 = T^T / alpha with alpha = ||T_b||_F^2 / K is the exact inverse of a rotation scaled by any factor and a
+// good start near one.  grid (nb, K / 32): workgroup (b, s) writes rows 32 s .. of X0 (columns of T).
+__global__ __launch_bounds__(1024) void ns_init_kernel(const float* __restrict__ T, float* __restrict__ X0,
+                                                       float* __restrict__ X0copy, int K) {
+  __shared__ float tile[256 * 33];
+  __shared__ double red[16];
+  const int b = blockIdx.x, s0 = blockIdx.y * 32, tid = threadIdx.x;
+  const float* Tb = T + size_t(b) * K * K;
+  double acc = 0;
+  for (int e = tid * 4; e < K * K; e += 1024 * 4) {
+    const float4 v = *reinterpret_cast<const float4*>(Tb + e);
+    acc += double(v.x) * v.x + double(v.y) * v.y + double(v.z) * v.z + double(v.w) * v.w;
+  }
+  for (int m = 1; m < 64; m <<= 1) acc += __shfl_xor(acc, m);
+  if ((tid & 63) == 0) red[tid >> 6] = acc;
+  // tile[j][ii] = T[j][s0 + ii]
+  for (int e = tid; e < K * 32; e += 1024) {
+    const int j = e >> 5, ii = e & 31;
+    tile[j * 33 + ii] = Tb[size_t(j) * K + s0 + ii];
+  }
+  __syncthreads();
+  double f2 = 0;
+  for (int w = 0; w < 16; ++w) f2 += red[w];
+  const float inv_alpha = f2 > 0 ? float(double(K) / f2) : 0.f;
+  float* Xb = X0 + size_t(b) * K * K;
+  float* Xc = X0copy + size_t(b) * K * K;      // (where the rounds' result lands: a block that needs none keeps X0)
+  for (int e = tid; e < K * 32; e += 1024) {
+    const int ii = e / K, j = e % K;
+    const float x = tile[j * 33 + ii] * inv_alpha;
+    Xb[size_t(s0 + ii) * K + j] = x;
+    Xc[size_t(s0 + ii) * K + j] = x;
+  }
+}
+// F = ||I - Y_b||_F per block, Y = T X.  mode 0 (after the first product): skip[b] = 1 when !(F <= thresh) -- such a
+// block is hopeless for the rounds --, 2 when F <= done_thresh already (a rotation: the start is the inverse), else 0;
+// the rounds leave blocks with skip != 0 alone.  mode 1 (after the last product): need[b] = skip[b] == 1 ||
+// !(F <= thresh): the elimination takes those, the others are done (status 0).  Comparisons written so that a NaN
+// fails them.  grid: nb.
+__global__ __launch_bounds__(1024) void ns_flag_kernel(const float* __restrict__ Y, int K, int mode, float thresh,
+                                                       float done_thresh, int* __restrict__ skip,
+                                                       int* __restrict__ need, int* __restrict__ status) {
+  __shared__ double red[16];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  if (mode == 1 && skip[b] == 1) {
+    if (tid == 0) need[b] = 1;
+    return;
+  }
+  const float* Yb = Y + size_t(b) * K * K;
+  double acc = 0;
+  for (int e = tid * 4; e < K * K; e += 1024 * 4) {
+    const float4 v = *reinterpret_cast<const float4*>(Yb + e);
+    const int r = e / K, c = e % K;
+    const double d0 = double(v.x) - (r == c ? 1.0 : 0.0), d1 = double(v.y) - (r == c + 1 ? 1.0 : 0.0);
+    const double d2 = double(v.z) - (r == c + 2 ? 1.0 : 0.0), d3 = double(v.w) - (r == c + 3 ? 1.0 : 0.0);
+    acc += d0 * d0 + d1 * d1 + d2 * d2 + d3 * d3;
+  }
+  for (int m = 1; m < 64; m <<= 1) acc += __shfl_xor(acc, m);
+  if ((tid & 63) == 0) red[tid >> 6] = acc;
+  __syncthreads();
+  if (tid == 0) {
+    double f2 = 0;
+  for (int w = 0; w < 16; ++w) f2 += red[w];
+    const bool ok = f2 <= double(thresh) * double(thresh);
+    if (mode == 0) {
+      skip[b] = !ok ? 1 : (f2 <= double(done_thresh) * double(done_thresh) ? 2 : 0);
+    } else {
+      need[b] = ok ? 0 : 1;
+      if (ok && status) status[b] = 0;
+    }
+  }
+}
 __global__ __launch_bounds__(256) void eye64_kernel(double* __restrict__ X, int K, int64_t n) {
   const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
   if (i >= n) return;
@@ -1337,6 +1409,8 @@ int launch_gj_solve(int K, int nb, int nz, const float* partial, double* work, f
   return CAFEQ_OK;
 }
 
+int launch_inverse256(const float* T, int nb, double* work, float* Tinv, float* rho_row, float* rho_col, int* status,
+                      bool warm, hipStream_t st);
 int launch_block_inverse(const float* T, int K, int nb, double* work, float* Tinv, float* rho_row,
                          float* rho_col, int* status, hipStream_t st) {
   GjArgs a;
@@ -1367,12 +1441,56 @@ int launch_block_inverse(const float* T, int K, int nb, double* work, float* Tin
     a.need = need;
   }
   if (K != 256) return launch_gj(a, nb, st);
-  // K == 256 is eliminated in float32; one Newton step X <- X + X (I - T X) with float64
-  // residuals brings the result back to float32 rounding accuracy.
-  a.rho_row = a.rho_col = nullptr;
-  int rc = launch_gj(a, nb, st);
-  if (rc) return rc;
+  return launch_inverse256(T, nb, work, Tinv, rho_row, rho_col, status, false, st);
+}
+
+// Blocks of 256.  Newton-Schulz rounds X <- 2 X - X (T X) on the float32 matrix pipe (batched products over the
+// whole chip) from X0 = T^T / alpha (cold) or from the inverse already in Tinv (warm: inside a learning loop),
+// accepted per block when ||I - T X||_F <= 3e-4 afterwards -- an a-posteriori bound, so a start that was not
+// good enough only costs the rounds; blocks that are hopeless after the first product (||I - T X0||_F > 1.2) skip
+// them, and so do blocks whose start already meets the bound (rotations).  Every other block is eliminated in float32 (one compute unit each, 283 us).  Either way one Newton step
+// with float64 residuals follows and brings the result to float32 rounding accuracy (it squares the residual).
+// work: 2 nb K K doubles; the rounds' two float32 matrices and the flags share it with the refinement's buffers.
+int launch_inverse256(const float* T, int nb, double* work, float* Tinv, float* rho_row, float* rho_col, int* status,
+                      bool warm, hipStream_t st) {
+  constexpr int K = 256;
+  int rc;
   const size_t mat = size_t(nb) * K * K;
+  float* Xs = reinterpret_cast<float*>(work);
+  float* Y = Xs + mat;
+  int* hop = reinterpret_cast<int*>(reinterpret_cast<unsigned char*>(work) + 2 * mat * sizeof(double) -
+                                    ((size_t(2 * nb) * sizeof(int) + 255) / 256) * 256);
+  int* need = hop + nb;
+  auto product_tx = [&](const float* X) { return launch_bgemm(false, false, T, X, Y, K, nb, 1.f, 0.f, st); };
+  auto round = [&](const float* X, float* Xn) {   // Xn = 2 X - X Y
+    return launch_bgemm(false, false, X, Y, Xn, K, nb, -1.f, 2.f, st, nullptr, X, hop);
+  };
+  if (!warm) {
+    hipLaunchKernelGGL(ns_init_kernel, dim3(nb, K / 32), dim3(1024), 0, st, T, Xs, Tinv, K);
+    CAFEQ_CHECK_LAUNCH();
+    if ((rc = product_tx(Xs))) return rc;
+    hipLaunchKernelGGL(ns_flag_kernel, dim3(nb), dim3(1024), 0, st, Y, K, 0, 1.2f, 3e-4f, hop, need, status);
+    if ((rc = round(Xs, Tinv))) return rc;
+    if ((rc = product_tx(Tinv))) return rc;
+    if ((rc = round(Tinv, Xs))) return rc;
+    if ((rc = product_tx(Xs))) return rc;
+    if ((rc = round(Xs, Tinv))) return rc;
+  } else {
+    if ((rc = product_tx(Tinv))) return rc;
+    hipLaunchKernelGGL(ns_flag_kernel, dim3(nb), dim3(1024), 0, st, Y, K, 0, 1.2f, 3e-4f, hop, need, status);
+    if ((rc = round(Tinv, Xs))) return rc;
+    if ((rc = product_tx(Xs))) return rc;
+    if ((rc = round(Xs, Tinv))) return rc;
+  }
+  if ((rc = product_tx(Tinv))) return rc;
+  hipLaunchKernelGGL(ns_flag_kernel, dim3(nb), dim3(1024), 0, st, Y, K, 1, 3e-4f, 0.f, hop, need, status);
+  CAFEQ_CHECK_LAUNCH();
+  GjArgs a;
+  a.mode = 0; a.K = K; a.nz = 0; a.T = T; a.partial = nullptr; a.work = work; a.out = Tinv;
+  a.rho_row = a.rho_col = nullptr; a.status = status; a.status_stride = 1; a.status_offset = 0;
+  a.need = need; a.need_n = 1;
+  if ((rc = launch_gj(a, nb, st))) return rc;
+  // one Newton step X <- X + X (I - T X) with float64 residuals
   double *res = work, *X64 = work + mat;
   const unsigned grid = unsigned(nb) * (K / 32) * (K / 64);
   const int64_t n = int64_t(mat);
@@ -1388,6 +1506,7 @@ int launch_block_inverse(const float* T, int K, int nb, double* work, float* Tin
 
 // The inverse inside a learning loop: Tinv holds the previous iteration's inverse on entry.
 int launch_block_inverse_warm(const float* T, int K, int nb, double* work, float* Tinv, int* status, hipStream_t st) {
+  if (K == 256) return launch_inverse256(T, nb, work, Tinv, nullptr, nullptr, status, true, st);
   if (K != 64 && K != 128) return launch_block_inverse(T, K, nb, work, Tinv, nullptr, nullptr, status, st);
   int* need = reinterpret_cast<int*>(work);
   const size_t lds = size_t(2 * K * (K + 1) + 2 * (K / 32) * (K / 32)) * sizeof(float);

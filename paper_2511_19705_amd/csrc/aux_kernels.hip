@@ -390,19 +390,24 @@ __global__ __launch_bounds__(256) void bgemm_kernel(const float* __restrict__ A,
 // 128 the learning loops run on take one chunk -- every load of the workgroup is in flight at once and
 // there is one barrier -- at 65 KB of LDS, two workgroups per compute unit.
 template <bool TA, bool TB, int CH>
+// D: where the beta term is read (null: C itself); skip: optional per-block flags, a block whose flag is set is
+// left alone.
 __global__ __launch_bounds__(256) void bgemm_mfma_kernel(const float* __restrict__ A, const float* __restrict__ B,
                                                           float* __restrict__ C, int K, float alpha, float beta,
-                                                          const AdamHook adam) {
+                                                          const AdamHook adam, const float* __restrict__ D,
+                                                          const int* __restrict__ skip) {
   constexpr int LD = 65;
   extern __shared__ __align__(16) float bsm[];
   float* sa = bsm;
   float* sb = bsm + CH * LD;
   const int tpr = K / 64;
   const int b = blockIdx.x / (tpr * tpr), tile = blockIdx.x % (tpr * tpr);
+  if (skip && skip[b]) return;
   const int i0 = (tile / tpr) * 64, j0 = (tile % tpr) * 64;
   const float* Ab = A + size_t(b) * K * K;
   const float* Bb = B + size_t(b) * K * K;
   float* Cb = C + size_t(b) * K * K;
+  const float* Db = (D ? D : C) + size_t(b) * K * K;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ln = lane & 31, h = lane >> 5;
   const int wi = wave >> 1, wj = wave & 1;
   floatx16 acc;
@@ -415,7 +420,7 @@ __global__ __launch_bounds__(256) void bgemm_mfma_kernel(const float* __restrict
   if (beta != 0.f) {
 #pragma unroll
     for (int v = 0; v < 16; ++v)
-      cold[v] = Cb[(i0 + wi * 32 + 8 * (v / 4) + 4 * h + (v % 4)) * K + j0 + wj * 32 + ln];
+      cold[v] = Db[(i0 + wi * 32 + 8 * (v / 4) + 4 * h + (v % 4)) * K + j0 + wj * 32 + ln];
   }
   for (int l0 = 0; l0 < K; l0 += CH) {
     // sa[l][i] = op(A)[i0 + i][l0 + l];  sb[l][j] = op(B)[l0 + l][j0 + j]: four consecutive elements of the
@@ -689,13 +694,14 @@ int launch_reduce_losses(int kind, const float* hdrA, int nslotA, const float* h
   return CAFEQ_OK;
 }
 int launch_bgemm(bool ta, bool tb, const float* A, const float* B, float* C, int K, int nb, float alpha,
-                 float beta, hipStream_t st, const AdamHook* adam) {
+                 float beta, hipStream_t st, const AdamHook* adam, const float* D, const int* skip) {
   AdamHook hook;
   hook.T = nullptr;
   if (adam) {
     if (K == 32) return CAFEQ_ERR_INVALID_ARG;
     hook = *adam;
   }
+  if ((D || skip) && K == 32) return CAFEQ_ERR_INVALID_ARG;
   if (K == 32) {
 #define CAFEQ_G32(TA, TB) hipLaunchKernelGGL((bgemm32_kernel<TA, TB>), dim3(nb), dim3(256), 0, st, A, B, C, alpha, beta)
     if (ta && tb) CAFEQ_G32(true, true); else if (ta) CAFEQ_G32(true, false);
@@ -717,13 +723,13 @@ int launch_bgemm(bool ta, bool tb, const float* A, const float* B, float* C, int
         if (!ok) return CAFEQ_ERR_LAUNCH;
         attr_set = true;
       }
-#define CAFEQ_G128(TA, TB) hipLaunchKernelGGL((bgemm_mfma_kernel<TA, TB, CH>), dim3(grid), dim3(256), lds, st, A, B, C, K, alpha, beta, hook)
+#define CAFEQ_G128(TA, TB) hipLaunchKernelGGL((bgemm_mfma_kernel<TA, TB, CH>), dim3(grid), dim3(256), lds, st, A, B, C, K, alpha, beta, hook, D, skip)
       if (ta && tb) CAFEQ_G128(true, true); else if (ta) CAFEQ_G128(true, false);
       else if (tb) CAFEQ_G128(false, true); else CAFEQ_G128(false, false);
 #undef CAFEQ_G128
     } else {
       constexpr size_t lds = 2 * 64 * 65 * sizeof(float);
-#define CAFEQ_G64(TA, TB) hipLaunchKernelGGL((bgemm_mfma_kernel<TA, TB, 64>), dim3(grid), dim3(256), lds, st, A, B, C, K, alpha, beta, hook)
+#define CAFEQ_G64(TA, TB) hipLaunchKernelGGL((bgemm_mfma_kernel<TA, TB, 64>), dim3(grid), dim3(256), lds, st, A, B, C, K, alpha, beta, hook, D, skip)
       if (ta && tb) CAFEQ_G64(true, true); else if (ta) CAFEQ_G64(true, false);
       else if (tb) CAFEQ_G64(false, true); else CAFEQ_G64(false, false);
 #undef CAFEQ_G64

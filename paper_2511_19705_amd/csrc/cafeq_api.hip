@@ -586,7 +586,7 @@ OptWs carve_opt(void* ws, int k, int nb) {
 }
 // The inverse of iteration s of a learning loop: from scratch first, then warm-started from the previous one.
 int loop_inverse(int s, const float* T, int k, int nb, float* Tinv, int* status, void* ws, void* stream) {
-  if (s == 0 || (k != 64 && k != 128)) return cafeq_block_inverse(T, k, nb, Tinv, nullptr, nullptr, status, ws, stream);
+  if (s == 0 || (k != 64 && k != 128 && k != 256)) return cafeq_block_inverse(T, k, nb, Tinv, nullptr, nullptr, status, ws, stream);
   return launch_block_inverse_warm(T, k, nb, static_cast<double*>(ws), Tinv, status, static_cast<hipStream_t>(stream));
 }
 int check_opt(const cafeq_opt_cfg* opt) {

@@ -109,8 +109,10 @@ int launch_reduce_losses(int kind, const float* hdrA, int nslotA, const float* h
 // Adam step applied by the product's epilogue instead of storing the product: the value alpha op(A) op(B) + beta C is
 // taken as the gradient of element [b][i][j] and T, m, v are updated in place (C is only read).  K >= 64.
 struct AdamHook { float *T, *m, *v; float lr, beta1, omb1, beta2, omb2, eps, c1, c2; };
+// C = alpha op(A) op(B) + beta D per block (D null: C); skip: per-block flags, set = leave the block alone
 int launch_bgemm(bool ta, bool tb, const float* A, const float* B, float* C, int K, int nb, float alpha,
-                 float beta, hipStream_t st, const AdamHook* adam = nullptr);
+                 float beta, hipStream_t st, const AdamHook* adam = nullptr, const float* D = nullptr,
+                 const int* skip = nullptr);
 int launch_bgemm_chain(const float* P, const float* G, float* x1, float* C, int K, int nb, float alpha, float beta,
                        hipStream_t st, const AdamHook* adam = nullptr);
 // adaptive_kernels.hip

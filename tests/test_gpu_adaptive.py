@@ -252,3 +252,41 @@ def test_block_inverse_of_rotations_and_of_their_neighbours(env, k):
     # exact rotations come back as the transpose, bit for bit
     for b in (0, 7):
         np.testing.assert_array_equal(Tinv[b].cpu().numpy(), T[b].T)
+
+
+def test_block_inverse_256_near_rotations_and_far_blocks(env):
+    """Blocks of 256: rotations, scaled rotations and their neighbours are inverted by Newton-Schulz rounds (accepted
+    on the residual they reach), everything else of the same call by the elimination -- all to float32 rounding
+    accuracy, with squared norms and status."""
+    torch, cafeq = env
+    k = 256
+    rng = np.random.default_rng(2560)
+    H = WL.haar_blocks(10, k, 2561).astype(np.float64)
+    T = H.copy()
+    T[1] += 1e-6 * rng.standard_normal((k, k))
+    T[2] += (1e-3 / np.sqrt(k)) * rng.standard_normal((k, k))
+    T[3] = T[3] @ (np.eye(k) + (0.05 / np.sqrt(k)) * rng.standard_normal((k, k)))     # a transform part-way through learning
+    T[4] = T[4] @ (np.eye(k) + (0.3 / np.sqrt(k)) * rng.standard_normal((k, k)))      # too far for the rounds
+    T[5] *= 37.5                                                                      # scaled rotations: any factor
+    T[6] *= 2e-3
+    T[7][:, 0] *= -1.0                                                                # reflection
+    T[8] = rng.standard_normal((k, k))                                                # dense, nothing like a rotation
+    T[9] = 0.0                                                                        # singular
+    T = T.astype(np.float32)
+    Tinv, rr, rc_, status = cafeq.block_inverse(_dev(torch, T), want_rho=True)
+    torch.cuda.synchronize()
+    st = status.cpu().numpy()
+    assert list(st[:9]) == [0] * 9 and st[9] == 1
+    for b in range(9):
+        ref = np.linalg.inv(T[b].astype(np.float64))
+        got = Tinv[b].cpu().numpy().astype(np.float64)
+        # float32 rounding of the result, amplified by the condition number for the dense block
+        tol = (2e-6 if b != 8 else 2e-4) * np.abs(ref).max()
+        np.testing.assert_allclose(got, ref, rtol=0, atol=tol, err_msg="block %d" % b)
+        np.testing.assert_allclose(rr.cpu().numpy()[b * k:(b + 1) * k], (ref ** 2).sum(1), rtol=1e-4 if b == 8 else 1e-5)
+        np.testing.assert_allclose(rc_.cpu().numpy()[b * k:(b + 1) * k], (ref ** 2).sum(0), rtol=1e-4 if b == 8 else 1e-5)
+    assert float(Tinv[9].abs().max()) == 0.0
+    # run-to-run identical
+    Tinv2, _, _, _ = cafeq.block_inverse(_dev(torch, T), want_rho=True)
+    torch.cuda.synchronize()
+    assert torch.equal(Tinv, Tinv2)

@@ -143,6 +143,27 @@ def test_pair_adam_with_large_steps_follows_the_oracle(env, k, lr):
     np.testing.assert_allclose(Tinv.cpu().numpy(), np.linalg.inv(Tg), rtol=0, atol=1e-5 * np.abs(np.linalg.inv(Tg)).max())
 
 
+@pytest.mark.parametrize("lr,rep", [(3e-3, 1), (6e-3, 2)])
+def test_pair_adam_with_blocks_of_256_follows_the_oracle(env, lr, rep):
+    """Blocks of 256 (the paper's setting for the 9B model): inside the loop the inverse comes from Newton-Schulz
+    rounds started at the previous iteration's inverse, with the elimination behind them."""
+    torch, cafeq = env
+    k, steps = 256, 5
+    A, B, T0 = WL.small_pair(136, 512, k, rep, 1256 + rep, eps=0.03)
+    T_ref, h_ref = O.optimize_pair(A, B, T0, 4, 64, rep, 5.0, lr, steps, 0.1)
+    Td = _dev(torch, T0.copy())
+    Tinv, hist, status = cafeq.optimize_pair(_dev(torch, A), _dev(torch, B), Td, 4, 64, rep, 5.0, lr, steps, 0.1)
+    torch.cuda.synchronize()
+    hist = hist.cpu().numpy().astype(np.float64)
+    assert int(status.abs().sum()) == 0
+    for s in range(steps):
+        for c, name in ((0, "errU_sq"), (1, "errV_sq"), (2, "l2A_sq"), (3, "l2B_sq"), (4, "lse")):
+            parity.check_scalar(hist[s, c], h_ref[s, c], rel=5e-4, what="step %d %s" % (s, name))
+    Tg = Td.cpu().numpy().astype(np.float64)
+    assert np.sqrt(((Tg - T_ref) ** 2).mean()) <= 0.05 * lr
+    np.testing.assert_allclose(Tinv.cpu().numpy(), np.linalg.inv(Tg), rtol=0, atol=1e-5 * np.abs(np.linalg.inv(Tg)).max())
+
+
 def test_learning_on_the_bench_workload_lowers_the_loss(env):
     """Ten Adam steps on the full 9B-shaped pair: the LogSumExp falls, nothing is singular.
     (Size-independent property; the small cases above carry the element-wise parity.)"""

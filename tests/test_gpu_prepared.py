@@ -256,3 +256,11 @@ def test_launch_timing_samples_every_nth_launch(env):
     cafeq.proxy_loss_fwd_bwd(Wd, Td, Pd, 4, 128, O.COL, want_grad=False)
     torch.cuda.synchronize()
     assert timer.table.seen == 7
+    # kind = 1 brackets the gradient pass instead: one per call with a gradient, none without
+    gt = cafeq.LaunchTimer(4, every=1, kind=1)
+    with gt:
+        cafeq.proxy_loss_fwd_bwd(Wd, Td, Pd, 4, 128, O.COL, want_grad=False)
+        cafeq.proxy_loss_fwd_bwd(Wd, Td, Pd, 4, 128, O.COL, want_grad=True)
+        cafeq.proxy_loss_fwd_bwd(Wd, Td, Pd, 4, 128, O.COL, want_grad=True)
+        torch.cuda.synchronize()
+    assert gt.table.seen == 2 and gt.table.count == 2 and all(x > 0 for x in gt.durations_ms())
