@@ -132,7 +132,9 @@ size_t cafeq_workspace_bytes(int call_id, const cafeq_mat* a, const cafeq_mat* b
 /* Blockwise inverse and the squared norms the surrogate needs (paper Sec. 4.1: the
  * (M^-1)_{ij}^2 factors).  Tinv[nb][k][k] = T^-1 per block (Gauss-Jordan with partial
  * pivoting, float64 internally; a block verified to be a rotation to float32 accuracy --
- * max |I - T T^T| <= 2e-6 -- is inverted by transposition).  rho_row[nb*k] / rho_col[nb*k] (either may be NULL):
+ * max |I - T T^T| <= 2e-6 -- is inverted by transposition; blocks of 256 are eliminated in float32 with one
+ * Newton step on float64 residuals, and those near a scaled rotation are first tried with Newton-Schulz rounds from
+ * T^T ||T||_F^-2 k, kept only where ||I - T X||_F <= 3e-4 afterwards).  rho_row[nb*k] / rho_col[nb*k] (either may be NULL):
  * squared row / column norms of Tinv.  status[nb] (may be NULL): 0 ok, 1 singular to
  * working precision (Tinv, rho_row and rho_col of that block are then zero).
  * k as in cafeq_xform (else CAFEQ_ERR_UNSUPPORTED). */
