@@ -257,7 +257,7 @@ def pair_workload(args, secondary=True):
         sub = argparse.Namespace(**vars(args))
         sub.no_cpu_baseline = True
         sub.steps, sub.warmup = n2, 3
-        for name in ("c3_rtn", "c3_optimize", "c2_single", "c4_dual", "c4_adaptive", "c5_layer"):
+        for name in ("c3_rtn", "c3_optimize", "c2_single", "c4_dual", "c4_optimize", "c4_adaptive", "c5_layer"):
             sub.workload = name
             r = WORKLOADS[name](sub)
             sec.append({"workload": r["config"]["workload"], "metric": r["metric"], "steps": r["steps"],
@@ -323,6 +323,25 @@ def core_workload(args):
                 O.surrogate(w, t, p_, cfg["bits"][0], cfg["group"], 0, 1)
             dt = time.perf_counter() - t0
             return w.size * 3 / dt, "%d of %d blocks, 3 x (inverse + fwd+bwd), %.1f s" % (nbk, cfg["T"].shape[0], dt)
+    elif args.workload == "c4_optimize":
+        # Adam iterations on the attention pair at the paper's 9B block size (inverse warm-started by Newton-Schulz rounds)
+        cfg = WL.config4()
+        k, rep, g, bits = cfg["k"], cfg["rep"], cfg["group"], cfg["bits"][0]
+        A, B = torch.from_numpy(cfg["A"]).to(dev), torch.from_numpy(cfg["B"]).to(dev)
+        T = torch.from_numpy(cfg["T"].copy()).to(dev)
+        elems = A.numel() + B.numel()
+        run = lambda n: cafeq.optimize_pair(A, B, T, bits, g, rep, 5.0, 1e-3, n)
+        metric = "learning iterations, weight-elements/s (Adam on the LogSumExp surrogate, 9B-shaped attention V/O pair, blocks of 256)"
+        flop_el, parts, kern, name = 4 * k, 9, "xform_core_kernel<256,64,*,false,true> (loss pass)", cfg["name"] + "_adam"
+
+        def cpu():
+            from oracle import cafeq_oracle as O
+            nh = 2
+            a = np.ascontiguousarray(cfg["A"][:, :nh * k]); b = np.ascontiguousarray(cfg["B"][:nh * rep * k, :])
+            t0 = time.perf_counter()
+            O.optimize_pair(a, b, cfg["T"][:nh], bits, g, rep, 5.0, 1e-3, 1)
+            dt = time.perf_counter() - t0
+            return (a.size + b.size) / dt, "%d of %d heads, 1 Adam iteration, %.1f s" % (nh, cfg["T"].shape[0], dt)
     elif args.workload == "c4_dual":
         # the paired loss and gradient at the block size the paper runs the 9B model with (per-head 256 x 256, kv heads
         # shared by two query heads): block inverse + cafeq_dual_proxy_loss_fwd_bwd with gradient
@@ -597,6 +616,7 @@ def rtn_workload(args):
 
 
 WORKLOADS = {"c3_optimize": core_workload, "c2_single": core_workload, "c4_adaptive": core_workload, "c4_dual": core_workload,
+             "c4_optimize": core_workload,
              "c5_layer": layer_workload, "c2_infer": infer_workload, "c3_infer": infer_workload, "c3_rtn": rtn_workload}
 
 
