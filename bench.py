@@ -239,8 +239,6 @@ def pair_workload(args, secondary=True):
     if traffic:
         result["roofline"]["measured_traffic_TBps"] = traffic / avg_launch_s / 1e12
         result["roofline"]["measured_traffic_over_read_probe"] = traffic / avg_launch_s / 1e12 / probe["read_only_TBps"]
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = pair_cpu_baseline(cfg, args.cpu_blocks, args.cpu_reps)
     if secondary:
         sec = []
         n2 = max(10, args.steps // 4)
@@ -267,6 +265,10 @@ def pair_workload(args, secondary=True):
                         **({"detail": r["detail"]} if "detail" in r else {})})
             torch.cuda.empty_cache()
         result["secondary"] = sec
+    # (the oracle on the host cores comes last: its thread pools keep spinning for a while after a run, and the
+    # secondary workloads with many small launches per step are then starved by the launching thread's neighbours)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = pair_cpu_baseline(cfg, args.cpu_blocks, args.cpu_reps)
     return result
 
 
