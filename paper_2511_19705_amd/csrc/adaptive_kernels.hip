@@ -204,10 +204,10 @@ __global__ __launch_bounds__(256) void gram_pair_kernel(const GramArgs a) {
 // quadrant of a head's outputs (grid y: quadrant; 1 or 4 per head): per step of 16 contraction indices its 512
 // threads each take eight consecutive contraction indices of one free index -- waves 0-3 the quadrant's row side
 // (Xq), waves 4-7 its column side (Xq and E) -- dequantize, split, and store one 16-byte matrix-instruction operand
-// per part into LDS ([part][free index][16 contraction indices], two buffers, one barrier per step); then wave w
+// per part into LDS ([part][half of the step][free index][8 contraction indices], two buffers, one barrier per step); then wave w
 // accumulates the tiles (row tile w / 2; column tiles 2 (w % 2), 2 (w % 2) + 1) of S and R: 24 matrix instructions
 // from 15 operand reads.  Partials in the layout of the kernel above.
-constexpr int kG16PlaneB = 128 * 32;                 // one part of one side: 128 free indices x 16 bfloat16
+constexpr int kG16PlaneB = 128 * 32;                 // one part of one side: 2 halves x 128 free indices x 8 bfloat16
 constexpr int kG16BufB = 9 * kG16PlaneB;             // row side Xq, column side Xq, column side E: 3 parts each
 constexpr size_t kG16Lds = 2 * kG16BufB;
 
@@ -239,7 +239,13 @@ __global__ __launch_bounds__(512) void gram_pair16_kernel(const GramArgs a) {
   const int64_t C = a.cols;
 
   // loader role: side (uniform over a wave), free index, half of the step's 16 contraction indices
-  const int side = __builtin_amdgcn_readfirstlane(tid >> 8), idx = (tid & 255) >> 1, half = tid & 1;
+  // (sixteen neighbouring lanes share a half and take consecutive free indices: their 16-byte LDS stores form one
+  // contiguous 256-byte run, like the operand reads)
+  // Along columns a wave takes 64 consecutive columns of one half; along rows it takes both halves of 32 rows, so
+  // that the two 32-byte pieces of a row's 64 bytes are asked for by one instruction.
+  const int side = __builtin_amdgcn_readfirstlane(tid >> 8);
+  const int idx = AXIS == CAFEQ_AXIS_COL ? (tid & 127) : ((tid >> 6) & 3) * 32 + ((lane >> 5) << 4) + (lane & 15);
+  const int half = AXIS == CAFEQ_AXIS_COL ? ((tid >> 7) & 1) : ((lane >> 4) & 1);
   const int64_t fbase = f0 + 128 * (side ? qJ : qI);     // uniform over the wave
   const int64_t fidx = fbase + idx;
   struct LoadSet {
@@ -296,7 +302,7 @@ __global__ __launch_bounds__(512) void gram_pair16_kernel(const GramArgs a) {
     }
     uintx4 ph, pm, pl;
     split3_bf16(q, ph, pm, pl);
-    unsigned char* dst = buf + (side ? 3 * kG16PlaneB : 0) + idx * 32 + 16 * half;
+    unsigned char* dst = buf + (side ? 3 * kG16PlaneB : 0) + half * (kG16PlaneB / 2) + idx * 16;
     *reinterpret_cast<uintx4*>(dst) = ph;
     *reinterpret_cast<uintx4*>(dst + kG16PlaneB) = pm;
     *reinterpret_cast<uintx4*>(dst + 2 * kG16PlaneB) = pl;
@@ -316,13 +322,13 @@ __global__ __launch_bounds__(512) void gram_pair16_kernel(const GramArgs a) {
     for (int v = 0; v < 16; ++v) { accS[u][v] = 0.f; accR[u][v] = 0.f; }
 
   auto products = [&](const unsigned char* buf) {
-    const unsigned char* pa = buf + (ta * 32 + ln) * 32 + 16 * h;
+    const unsigned char* pa = buf + h * (kG16PlaneB / 2) + (ta * 32 + ln) * 16;
     bf16x8 ax[3];
 #pragma unroll
     for (int p = 0; p < 3; ++p) ax[p] = as_bf16x8(*reinterpret_cast<const uintx4*>(pa + p * kG16PlaneB));
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      const unsigned char* pb = buf + 3 * kG16PlaneB + ((tc0 + u) * 32 + ln) * 32 + 16 * h;
+      const unsigned char* pb = buf + 3 * kG16PlaneB + h * (kG16PlaneB / 2) + ((tc0 + u) * 32 + ln) * 16;
       bf16x8 bq[3], be[3];
 #pragma unroll
       for (int p = 0; p < 3; ++p) {
@@ -438,6 +444,7 @@ struct GjArgs {
   const float* T;        // matrix to invert when partial == nullptr
   const float* partial;  // else [nb][nz][2][K][K]: chunk partials whose first matrix is summed and inverted
   const double* sum64 = nullptr;  // optional with partial: that float64 sum, already formed, [nb][K][K]
+  const float* sum32 = nullptr;   // optional with sum64: the same sum rounded to float32 (gj_spd256_kernel reads this)
   double* work;          // unused by the register-resident kernel
   float* out;            // [nb][K][K]
   float* rho_row; float* rho_col;  // optional squared row / column norms of the inverse
@@ -774,6 +781,258 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_panel_kernel(const GjA
   }
 }
 
+// The same inversion for a symmetric positive definite block of 256 in float32 (the Gram matrices of the adaptive
+// rounding: diagonal pivots in natural order, so no permutation), as a block elimination in panels of 16 columns
+// with everything but the 16 x 16 pivot block on the 16-bit matrix pipe.  With P the pivot block of panel t (rows
+// and columns 16 t .. 16 t + 15 of the current matrix), D = P^-1, A the panel's other rows and X the sixteen pivot
+// rows before the panel, sixteen elimination steps amount to
+//     pivot block <- D,   panel (other rows) <- C = -A D,   pivot rows <- D X,   elsewhere  R <- R + C X,
+// that is R += C' X on every row with C' = C (other rows) and D - I (pivot rows), and panel columns = C' + I.
+// Only D needs the serial chain of steps (wave 0, one row per lane, pivot row through scalar lane reads; 16 lanes
+// busy); C and the update are products of operands split exactly into three bfloat16 parts, the six part products
+// of weight >= 2^-24 kept (as in gram_pair16_kernel).  Wave w of eight keeps rows 32 w .. 32 w + 31 as eight
+// accumulator tiles: lane (ln, h) holds column 32 j + ln of tile j and rows 32 w + 8 (r / 4) + 4 h + r % 4,
+// r = 0..15.  While wave 0 inverts P, the wave that holds the pivot rows (wave t / 2) splits them into the B
+// operands of the update.  The contraction index c of the update is spread over the two lane halves as the
+// accumulator layout delivers it -- half h takes c = 4 h + i and 8 + 4 h + i, i = 0..3 -- so that C^T = (-D^T) A^T
+// comes out of the matrix pipe already in A-operand form (row 32 w + ln in lane ln), and the pivot rows' eight
+// values per lane and tile are one 16-byte B operand; C in accumulator form, for the panel's own columns, is the
+// same product with the operands exchanged.
+__global__ __launch_bounds__(512) void gj_spd256_kernel(const GjArgs a) {
+  constexpr int K = 256, NB = 16;
+  __shared__ __align__(16) float pan[2][K][NB];
+  __shared__ __align__(16) unsigned char xb[3 * 2 * K * 16];
+  __shared__ float dsm[16][17];          // D, float32
+  __shared__ int deadflag;
+  __shared__ float wred[8];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6, ln = lane & 31, h = lane >> 5;
+  if (a.need) {                           // uniform over the workgroup
+    int any = 0;
+    for (int i = 0; i < a.need_n; ++i) any |= a.need[b * a.need_n + i];
+    if (!any) return;
+  }
+  const int rbase = 32 * w + 4 * h;       // row of register r: rbase + 8 (r / 4) + r % 4
+  floatx16 reg[8];
+  if (a.partial == nullptr || a.sum32) {
+    // (float32 input: all 128 requests of a lane land in their registers, none waits for a conversion)
+    const float* src = (a.partial == nullptr ? a.T : a.sum32) + size_t(b) * K * K;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) reg[j][r] = src[(rbase + 8 * (r >> 2) + (r & 3)) * K + 32 * j + ln];
+  } else if (a.sum64) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        reg[j][r] = float(a.sum64[size_t(b) * K * K + size_t(rbase + 8 * (r >> 2) + (r & 3)) * K + 32 * j + ln]);
+  } else {
+    const float* src = a.partial + size_t(b) * a.nz * 2 * K * K;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        double acc = 0;
+        for (int z = 0; z < a.nz; ++z)
+          acc += double(src[size_t(z) * 2 * K * K + size_t(rbase + 8 * (r >> 2) + (r & 3)) * K + 32 * j + ln]);
+        reg[j][r] = float(acc);
+      }
+  }
+  float anorm = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) anorm = fmaxf(anorm, fabsf(reg[j][r]));
+  for (int m = 1; m < 64; m <<= 1) anorm = fmaxf(anorm, __shfl_xor(anorm, m));
+  if (lane == 0) wred[w] = anorm;
+  if (tid == 0) deadflag = 0;
+  __syncthreads();
+  anorm = 0;
+  for (int i = 0; i < 8; ++i) anorm = fmaxf(anorm, wred[i]);
+  int ex = 0;
+  (void)frexp(double(anorm), &ex);
+  const float scale = float(ldexp(1.0, -ex));    // exact power of two; 1 if the block is all zero
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) reg[j][r] *= scale;
+  const float tol = anorm * scale * (a.partial ? 1e-5f : 1e-6f);
+
+  // (the two panels of a tile are compile-time variants; the tile index is a run-time loop, so that the code of
+  // the whole elimination stays within the instruction cache)
+  auto panel = [&](auto half_c, const int jt) {
+    constexpr int half = decltype(half_c)::value, buf = half, c0 = NB * half;
+    const int t = 2 * jt + half;
+    const int q_own = ln - c0;
+    const bool owner = q_own >= 0 && q_own < NB;
+    if (owner) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (j == jt) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) pan[buf][rbase + 8 * (r >> 2) + (r & 3)][q_own] = reg[j][r];
+        }
+    }
+    __syncthreads();                      // (also: every reader of xb for the previous panel is done)
+    if (tid < 64) {
+      // D = P^-1 in place, row (lane % 16) of the pivot block per lane (the upper lanes repeat the lower sixteen)
+      float prow[NB];
+#pragma unroll
+      for (int c4 = 0; c4 < NB / 4; ++c4) {
+        const float4 v = *reinterpret_cast<const float4*>(&pan[buf][NB * t + (lane & 15)][4 * c4]);
+        prow[4 * c4] = v.x; prow[4 * c4 + 1] = v.y; prow[4 * c4 + 2] = v.z; prow[4 * c4 + 3] = v.w;
+      }
+      bool dd = false;
+#pragma unroll
+      for (int s = 0; s < NB; ++s) {
+        const float pv = read_lane(prow[s], s);
+        dd = dd || !(pv > tol);
+        // reciprocal of the pivot: hardware estimate (2^-22) + one Newton step
+        float ipiv = __builtin_amdgcn_rcpf(pv);
+        ipiv = ipiv * (2.f - pv * ipiv);
+        float rowp[NB];
+#pragma unroll
+        for (int c = 0; c < NB; ++c) rowp[c] = c == s ? 1.f : read_lane(prow[c], s);
+        const bool isp = (lane & 15) == s;
+        const float f = (isp ? 1.f - pv : -prow[s]) * ipiv;
+#pragma unroll
+        for (int c = 0; c < NB; ++c)
+          prow[c] = c == s ? (isp ? 1.f : 0.f) + f : fma_s(f, rowp[c], prow[c]);
+      }
+      if (lane < 16) {
+#pragma unroll
+        for (int c = 0; c < NB; ++c) dsm[lane][c] = prow[c];
+      }
+      if (dd && lane == 0) deadflag = 1;
+    }
+    // The pivot rows 16 t + c as they were before the panel: rows c0 .. c0 + 15 of wave t / 2.  Lane (ln, h)
+    // holds, for each of its columns, c = 8 g + 4 h + i (g = 0, 1; i = 0..3) in register 4 (2 (t % 2) + g) + i:
+    // the eight contraction indices of lane half h, in operand order.
+    if (w == jt) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float xv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) xv[e] = reg[j][8 * half + e];
+        uintx4 xh, xm, xl;
+        split3_bf16(xv, xh, xm, xl);
+        unsigned char* dst = xb + (size_t(h) * K + 32 * j + ln) * 16;
+        *reinterpret_cast<uintx4*>(dst) = xh;
+        *reinterpret_cast<uintx4*>(dst + 2 * K * 16) = xm;
+        *reinterpret_cast<uintx4*>(dst + 4 * K * 16) = xl;
+      }
+    }
+    __syncthreads();
+    {
+      float av[8], dv[8];
+      const float4 a_lo = *reinterpret_cast<const float4*>(&pan[buf][32 * w + ln][8 * h]);
+      const float4 a_hi = *reinterpret_cast<const float4*>(&pan[buf][32 * w + ln][8 * h + 4]);
+      av[0] = a_lo.x; av[1] = a_lo.y; av[2] = a_lo.z; av[3] = a_lo.w;
+      av[4] = a_hi.x; av[5] = a_hi.y; av[6] = a_hi.z; av[7] = a_hi.w;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dv[e] = owner ? -dsm[8 * h + e][owner ? q_own : 0] : 0.f;
+      uintx4 uh, um, ul;
+      split3_bf16(av, uh, um, ul);
+      const bf16x8 p0 = as_bf16x8(uh), p1 = as_bf16x8(um), p2 = as_bf16x8(ul);
+      split3_bf16(dv, uh, um, ul);
+      const bf16x8 d0 = as_bf16x8(uh), d1 = as_bf16x8(um), d2 = as_bf16x8(ul);
+      floatx16 ct, cn;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { ct[v] = 0.f; cn[v] = 0.f; }
+      // C^T (rows of the panel's columns c0 + c, column = this wave's row ln): operand order (-D^T, A^T)
+      ct = CAFEQ_MFMA_BF16(d1, p1, ct);
+      ct = CAFEQ_MFMA_BF16(d0, p2, ct);
+      ct = CAFEQ_MFMA_BF16(d2, p0, ct);
+      ct = CAFEQ_MFMA_BF16(d0, p1, ct);
+      ct = CAFEQ_MFMA_BF16(d1, p0, ct);
+      ct = CAFEQ_MFMA_BF16(d0, p0, ct);
+      // C in accumulator form, valid in the owner lanes: operand order (A, -D)
+      cn = CAFEQ_MFMA_BF16(p1, d1, cn);
+      cn = CAFEQ_MFMA_BF16(p0, d2, cn);
+      cn = CAFEQ_MFMA_BF16(p2, d0, cn);
+      cn = CAFEQ_MFMA_BF16(p0, d1, cn);
+      cn = CAFEQ_MFMA_BF16(p1, d0, cn);
+      cn = CAFEQ_MFMA_BF16(p0, d0, cn);
+      float cv[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) cv[e] = ct[8 * half + e];
+      if (w == jt && owner) {
+        // this lane's row is pivot row q_own: D - I there
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int c = 8 * (e >> 2) + 4 * h + (e & 3);
+          cv[e] = dsm[q_own][c] - (c == q_own ? 1.f : 0.f);
+        }
+      }
+      split3_bf16(cv, uh, um, ul);
+      const bf16x8 a0 = as_bf16x8(uh), a1 = as_bf16x8(um), a2 = as_bf16x8(ul);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const unsigned char* pb = xb + (size_t(h) * K + 32 * j + ln) * 16;
+        const bf16x8 b0 = as_bf16x8(*reinterpret_cast<const uintx4*>(pb));
+        const bf16x8 b1 = as_bf16x8(*reinterpret_cast<const uintx4*>(pb + 2 * K * 16));
+        const bf16x8 b2 = as_bf16x8(*reinterpret_cast<const uintx4*>(pb + 4 * K * 16));
+        // (smallest terms first)
+        floatx16 d = reg[j];
+        d = CAFEQ_MFMA_BF16(a1, b1, d);
+        d = CAFEQ_MFMA_BF16(a0, b2, d);
+        d = CAFEQ_MFMA_BF16(a2, b0, d);
+        d = CAFEQ_MFMA_BF16(a0, b1, d);
+        d = CAFEQ_MFMA_BF16(a1, b0, d);
+        d = CAFEQ_MFMA_BF16(a0, b0, d);
+        reg[j] = d;
+      }
+      // a panel column becomes the panel's own result: C' + I (D in the pivot rows)
+      if (owner) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) cn[r] += (rbase + 8 * (r >> 2) + (r & 3)) == NB * t + q_own ? 1.f : 0.f;
+        if (w == jt) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) cn[8 * half + e] = dsm[8 * (e >> 2) + 4 * h + (e & 3)][q_own];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (j == jt) reg[j] = cn;
+      }
+    }
+  };
+  for (int jt = 0; jt < 8; ++jt) {
+    panel(std::integral_constant<int, 0>{}, jt);
+    panel(std::integral_constant<int, 1>{}, jt);
+  }
+  __syncthreads();
+  const bool dead = deadflag != 0;
+  if (a.status && tid == 0) a.status[size_t(b) * a.status_stride + a.status_offset] = dead ? 1 : 0;
+  float* O = a.out + size_t(b) * K * K;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int row = rbase + 8 * (r >> 2) + (r & 3);
+    float rr = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float v = dead ? 0.f : reg[j][r] * scale;
+      O[size_t(row) * K + 32 * j + ln] = v;
+      rr += v * v;
+    }
+    if (a.rho_row) {
+      for (int m = 1; m < 32; m <<= 1) rr += __shfl_xor(rr, m);
+      if (ln == 0) a.rho_row[size_t(b) * K + row] = rr;
+    }
+  }
+  if (a.rho_col) {
+    // column norms from the block just written, one thread per column, rows in order
+    __syncthreads();
+    if (tid < K) {
+      double c2 = 0;
+      for (int i = 0; i < K; ++i) {
+        const float v = O[i * K + tid];
+        c2 += double(v) * v;
+      }
+      a.rho_col[size_t(b) * K + tid] = float(c2);
+    }
+  }
+}
+
 // R_b = float64 sum over the chunk partials of the second matrix of each partial; C_b = I.
 __global__ __launch_bounds__(256) void sum_r_init_c_kernel(const float* __restrict__ partial, int nz, int K,
                                                             float* __restrict__ R, float* __restrict__ C) {
@@ -856,10 +1115,11 @@ __global__ __launch_bounds__(256) void bgemm_f64acc_kernel(const AT* __restrict_
     }
 }
 
-// S64, R64 and a second copy of R64 (the residual's starting value) from the chunk partials.
+// S64, R64 and a second copy of R64 (the residual's starting value) from the chunk partials; optionally S64
+// rounded to float32.
 __global__ __launch_bounds__(256) void sum_partials64_kernel(const float* __restrict__ partial, int nz, int K,
                                                               double* __restrict__ S64, double* __restrict__ R64,
-                                                              double* __restrict__ res) {
+                                                              double* __restrict__ res, float* __restrict__ S32) {
   const int b = blockIdx.x;
   for (int e = blockIdx.y * 256 + threadIdx.x; e < K * K; e += gridDim.y * 256) {
     const float* p = partial + size_t(b) * nz * 2 * K * K + e;
@@ -869,6 +1129,7 @@ __global__ __launch_bounds__(256) void sum_partials64_kernel(const float* __rest
       r += double(p[size_t(z) * 2 * K * K + size_t(K) * K]);
     }
     S64[size_t(b) * K * K + e] = s;
+    if (S32) S32[size_t(b) * K * K + e] = float(s);
     R64[size_t(b) * K * K + e] = r;
     res[size_t(b) * K * K + e] = r;
   }
@@ -1284,7 +1545,10 @@ int launch_gj(const GjArgs& a, int nb, hipStream_t st) {
     case 32: CAFEQ_GJ(32, 4, 4, double, 64); break;
     case 64: CAFEQ_GJ(64, 4, 8, double, 128); break;
     case 128: CAFEQ_GJ(128, 4, 8, double, 512); break;
-    case 256: CAFEQ_GJ(256, 8, 16, float, 512); break;
+    case 256:
+      if (piv) hipLaunchKernelGGL((gj_panel_kernel<256, 8, 16, float, true>), dim3(nb), dim3(512), 0, st, a);
+      else hipLaunchKernelGGL(gj_spd256_kernel, dim3(nb), dim3(512), 0, st, a);
+      break;
     default: return CAFEQ_ERR_UNSUPPORTED;
   }
 #undef CAFEQ_GJ
@@ -1388,9 +1652,12 @@ int launch_gj_solve(int K, int nb, int nz, const float* partial, double* work, f
   double *S64 = work, *R64 = work + mat, *res = work + 2 * mat, *X64 = work + 3 * mat;
   if (K == 256 || nb <= 64) {
     // few blocks (always so for K = 256 shapes): the sums over the chunk partials are formed by the whole chip
-    hipLaunchKernelGGL(sum_partials64_kernel, dim3(nb, 32), dim3(256), 0, st, partial, nz, K, S64, R64, res);
+    // (K == 256 does not use the float32 scratch R otherwise: it holds the rounded sum the elimination reads)
+    float* S32 = K == 256 ? R : nullptr;
+    hipLaunchKernelGGL(sum_partials64_kernel, dim3(nb, 32), dim3(256), 0, st, partial, nz, K, S64, R64, res, S32);
     CAFEQ_CHECK_LAUNCH();
     a.sum64 = S64;
+    a.sum32 = S32;
   }
   int rc = launch_gj(a, nb, st);
   if (rc) return rc;
