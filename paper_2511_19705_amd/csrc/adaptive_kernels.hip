@@ -801,9 +801,10 @@ __global__ __launch_bounds__((K / RT) * (K / CT)) void gj_panel_kernel(const GjA
 __global__ __launch_bounds__(512) void gj_spd256_kernel(const GjArgs a) {
   constexpr int K = 256, NB = 16;
   __shared__ __align__(16) float pan[2][K][NB];
-  __shared__ __align__(16) unsigned char xb[3 * 2 * K * 16];
-  __shared__ float dsm[16][17];          // D, float32
-  __shared__ int deadflag;
+  constexpr int kXbB = 3 * 2 * K * 16;   // B operands of one panel's pivot rows: [part][lane half][column][8 rows]
+  __shared__ __align__(16) unsigned char xb[2 * kXbB];
+  __shared__ float dsm[2][16][17];       // D, float32
+  __shared__ int deadflag, ready;        // ready: panels handed over so far
   __shared__ float wred[8];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6, ln = lane & 31, h = lane >> 5;
   if (a.need) {                           // uniform over the workgroup
@@ -858,148 +859,180 @@ __global__ __launch_bounds__(512) void gj_spd256_kernel(const GjArgs a) {
     for (int r = 0; r < 16; ++r) reg[j][r] *= scale;
   const float tol = anorm * scale * (a.partial ? 1e-5f : 1e-6f);
 
-  // (the two panels of a tile are compile-time variants; the tile index is a run-time loop, so that the code of
-  // the whole elimination stays within the instruction cache)
-  auto panel = [&](auto half_c, const int jt) {
-    constexpr int half = decltype(half_c)::value, buf = half, c0 = NB * half;
-    const int t = 2 * jt + half;
+  // (every panel is a compile-time variant: tile and register indices are constants)
+  // the panel's columns, as they are now, into pan[half] (lanes that hold them: ln - 16 half in 0..15)
+  auto own_write = [&](auto t_c) __attribute__((always_inline)) {
+    constexpr int half = decltype(t_c)::value % 2, jt = decltype(t_c)::value / 2;
+    const int q_own = ln - NB * half;
+    if (q_own >= 0 && q_own < NB) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) pan[half][rbase + 8 * (r >> 2) + (r & 3)][q_own] = reg[jt][r];
+    }
+  };
+  // wave 0: D = P^-1 in place, P = rows 16 t .. of pan[buf]; row (lane % 16) of the pivot block per lane (the
+  // upper lanes repeat the lower sixteen)
+  auto chain = [&](const int t, const int buf) __attribute__((always_inline)) {
+    float prow[NB];
+#pragma unroll
+    for (int c4 = 0; c4 < NB / 4; ++c4) {
+      const float4 v = *reinterpret_cast<const float4*>(&pan[buf][NB * t + (lane & 15)][4 * c4]);
+      prow[4 * c4] = v.x; prow[4 * c4 + 1] = v.y; prow[4 * c4 + 2] = v.z; prow[4 * c4 + 3] = v.w;
+    }
+    bool dd = false;
+#pragma unroll
+    for (int s = 0; s < NB; ++s) {
+      const float pv = read_lane(prow[s], s);
+      dd = dd || !(pv > tol);
+      // reciprocal of the pivot: hardware estimate (2^-22) + one Newton step
+      float ipiv = __builtin_amdgcn_rcpf(pv);
+      ipiv = ipiv * (2.f - pv * ipiv);
+      float rowp[NB];
+#pragma unroll
+      for (int c = 0; c < NB; ++c) rowp[c] = c == s ? 1.f : read_lane(prow[c], s);
+      const bool isp = (lane & 15) == s;
+      const float f = (isp ? 1.f - pv : -prow[s]) * ipiv;
+#pragma unroll
+      for (int c = 0; c < NB; ++c)
+        prow[c] = c == s ? (isp ? 1.f : 0.f) + f : fma_s(f, rowp[c], prow[c]);
+    }
+    if (lane < 16) {
+#pragma unroll
+      for (int c = 0; c < NB; ++c) dsm[buf][lane][c] = prow[c];
+    }
+    if (dd && lane == 0) deadflag = 1;
+  };
+  // The wave that holds them splits the pivot rows 16 t + c, as they are now, into the B operands xb[half].
+  // Lane (ln, h) holds, for each of its columns, c = 8 g + 4 h + i (g = 0, 1; i = 0..3) in register
+  // 4 (2 half + g) + i: the eight contraction indices of lane half h, in operand order.
+  auto publish = [&](auto half_c) __attribute__((always_inline)) {
+    constexpr int half = decltype(half_c)::value;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float xv[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) xv[e] = reg[j][8 * half + e];
+      uintx4 xh, xm, xl;
+      split3_bf16(xv, xh, xm, xl);
+      unsigned char* dst = xb + half * kXbB + (size_t(h) * K + 32 * j + ln) * 16;
+      *reinterpret_cast<uintx4*>(dst) = xh;
+      *reinterpret_cast<uintx4*>(dst + 2 * K * 16) = xm;
+      *reinterpret_cast<uintx4*>(dst + 4 * K * 16) = xl;
+    }
+  };
+  // Panel t = 2 jt + half, entered with pan[half], xb[half] and dsm[half] ready.  Every wave first updates the
+  // tile that holds the next panel and hands that panel's columns over, so that wave 0 can invert the next pivot
+  // block, after its own share of the update, while the slower waves are still multiplying: one barrier per panel.
+  // (Measured without effect: a raised priority for wave 0; the inversion ahead of the rest of wave 0's update.)
+  auto panel = [&](auto t_c) __attribute__((always_inline)) {
+    constexpr int t = decltype(t_c)::value, half = t % 2, jt = t / 2, buf = half, nhalf = 1 - half, c0 = NB * half;
+    constexpr int nt = t + 1, njt = nt / 2;
+    constexpr bool has_next = nt < K / NB;
     const int q_own = ln - c0;
     const bool owner = q_own >= 0 && q_own < NB;
+    float av[8], dv[8];
+    const float4 a_lo = *reinterpret_cast<const float4*>(&pan[buf][32 * w + ln][8 * h]);
+    const float4 a_hi = *reinterpret_cast<const float4*>(&pan[buf][32 * w + ln][8 * h + 4]);
+    av[0] = a_lo.x; av[1] = a_lo.y; av[2] = a_lo.z; av[3] = a_lo.w;
+    av[4] = a_hi.x; av[5] = a_hi.y; av[6] = a_hi.z; av[7] = a_hi.w;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dv[e] = owner ? -dsm[buf][8 * h + e][owner ? q_own : 0] : 0.f;
+    uintx4 uh, um, ul;
+    split3_bf16(av, uh, um, ul);
+    const bf16x8 p0 = as_bf16x8(uh), p1 = as_bf16x8(um), p2 = as_bf16x8(ul);
+    split3_bf16(dv, uh, um, ul);
+    const bf16x8 d0 = as_bf16x8(uh), d1 = as_bf16x8(um), d2 = as_bf16x8(ul);
+    floatx16 ct, cn;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { ct[v] = 0.f; cn[v] = 0.f; }
+    // C^T (rows of the panel's columns c0 + c, column = this wave's row ln): operand order (-D^T, A^T)
+    ct = CAFEQ_MFMA_BF16(d1, p1, ct);
+    ct = CAFEQ_MFMA_BF16(d0, p2, ct);
+    ct = CAFEQ_MFMA_BF16(d2, p0, ct);
+    ct = CAFEQ_MFMA_BF16(d0, p1, ct);
+    ct = CAFEQ_MFMA_BF16(d1, p0, ct);
+    ct = CAFEQ_MFMA_BF16(d0, p0, ct);
+    // C in accumulator form, valid in the owner lanes: operand order (A, -D)
+    cn = CAFEQ_MFMA_BF16(p1, d1, cn);
+    cn = CAFEQ_MFMA_BF16(p0, d2, cn);
+    cn = CAFEQ_MFMA_BF16(p2, d0, cn);
+    cn = CAFEQ_MFMA_BF16(p0, d1, cn);
+    cn = CAFEQ_MFMA_BF16(p1, d0, cn);
+    cn = CAFEQ_MFMA_BF16(p0, d0, cn);
+    float cv[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) cv[e] = ct[8 * half + e];
+    if (w == jt && owner) {
+      // this lane's row is pivot row q_own: D - I there
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int c = 8 * (e >> 2) + 4 * h + (e & 3);
+        cv[e] = dsm[buf][q_own][c] - (c == q_own ? 1.f : 0.f);
+      }
+    }
+    split3_bf16(cv, uh, um, ul);
+    const bf16x8 a0 = as_bf16x8(uh), a1 = as_bf16x8(um), a2 = as_bf16x8(ul);
+    auto update = [&](auto j_c) __attribute__((always_inline)) {
+      constexpr int j = decltype(j_c)::value;
+      const unsigned char* pb = xb + buf * kXbB + (size_t(h) * K + 32 * j + ln) * 16;
+      const bf16x8 b0 = as_bf16x8(*reinterpret_cast<const uintx4*>(pb));
+      const bf16x8 b1 = as_bf16x8(*reinterpret_cast<const uintx4*>(pb + 2 * K * 16));
+      const bf16x8 b2 = as_bf16x8(*reinterpret_cast<const uintx4*>(pb + 4 * K * 16));
+      // (smallest terms first)
+      floatx16 d = reg[j];
+      d = CAFEQ_MFMA_BF16(a1, b1, d);
+      d = CAFEQ_MFMA_BF16(a0, b2, d);
+      d = CAFEQ_MFMA_BF16(a2, b0, d);
+      d = CAFEQ_MFMA_BF16(a0, b1, d);
+      d = CAFEQ_MFMA_BF16(a1, b0, d);
+      d = CAFEQ_MFMA_BF16(a0, b0, d);
+      reg[j] = d;
+    };
+    auto others = [&](auto j_c) __attribute__((always_inline)) {
+      if constexpr (!has_next || decltype(j_c)::value != njt) update(j_c);
+    };
+    if constexpr (has_next) {
+      update(std::integral_constant<int, njt>{});
+      // (the next panel's columns lie in the other half of the lanes of tile njt: the replacement of this
+      // panel's own columns below does not touch them)
+      own_write(std::integral_constant<int, nt>{});
+      if (w == njt && lane == 0) __hip_atomic_store(&ready, nt, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    StaticFor<0, 8>::run(others);
+    // a panel column becomes the panel's own result: C' + I (D in the pivot rows)
     if (owner) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (j == jt) {
+      for (int r = 0; r < 16; ++r) cn[r] += (rbase + 8 * (r >> 2) + (r & 3)) == NB * t + q_own ? 1.f : 0.f;
+      if (w == jt) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) pan[buf][rbase + 8 * (r >> 2) + (r & 3)][q_own] = reg[j][r];
+        for (int e = 0; e < 8; ++e) cn[8 * half + e] = dsm[buf][8 * (e >> 2) + 4 * h + (e & 3)][q_own];
+      }
+      reg[jt] = cn;
+    }
+    if constexpr (has_next) {
+      if (w == njt) publish(std::integral_constant<int, nhalf>{});
+      if (w == 0) {
+        // the pivot block of the next panel is part of what wave njt handed over; the wait is bounded (a wave
+        // that never saw the hand-over marks the block as failed and goes on)
+        int spins = 0;
+        while (__hip_atomic_load(&ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < nt && spins < (1 << 22)) {
+          __builtin_amdgcn_s_sleep(1);
+          ++spins;
         }
-    }
-    __syncthreads();                      // (also: every reader of xb for the previous panel is done)
-    if (tid < 64) {
-      // D = P^-1 in place, row (lane % 16) of the pivot block per lane (the upper lanes repeat the lower sixteen)
-      float prow[NB];
-#pragma unroll
-      for (int c4 = 0; c4 < NB / 4; ++c4) {
-        const float4 v = *reinterpret_cast<const float4*>(&pan[buf][NB * t + (lane & 15)][4 * c4]);
-        prow[4 * c4] = v.x; prow[4 * c4 + 1] = v.y; prow[4 * c4 + 2] = v.z; prow[4 * c4 + 3] = v.w;
-      }
-      bool dd = false;
-#pragma unroll
-      for (int s = 0; s < NB; ++s) {
-        const float pv = read_lane(prow[s], s);
-        dd = dd || !(pv > tol);
-        // reciprocal of the pivot: hardware estimate (2^-22) + one Newton step
-        float ipiv = __builtin_amdgcn_rcpf(pv);
-        ipiv = ipiv * (2.f - pv * ipiv);
-        float rowp[NB];
-#pragma unroll
-        for (int c = 0; c < NB; ++c) rowp[c] = c == s ? 1.f : read_lane(prow[c], s);
-        const bool isp = (lane & 15) == s;
-        const float f = (isp ? 1.f - pv : -prow[s]) * ipiv;
-#pragma unroll
-        for (int c = 0; c < NB; ++c)
-          prow[c] = c == s ? (isp ? 1.f : 0.f) + f : fma_s(f, rowp[c], prow[c]);
-      }
-      if (lane < 16) {
-#pragma unroll
-        for (int c = 0; c < NB; ++c) dsm[lane][c] = prow[c];
-      }
-      if (dd && lane == 0) deadflag = 1;
-    }
-    // The pivot rows 16 t + c as they were before the panel: rows c0 .. c0 + 15 of wave t / 2.  Lane (ln, h)
-    // holds, for each of its columns, c = 8 g + 4 h + i (g = 0, 1; i = 0..3) in register 4 (2 (t % 2) + g) + i:
-    // the eight contraction indices of lane half h, in operand order.
-    if (w == jt) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        float xv[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) xv[e] = reg[j][8 * half + e];
-        uintx4 xh, xm, xl;
-        split3_bf16(xv, xh, xm, xl);
-        unsigned char* dst = xb + (size_t(h) * K + 32 * j + ln) * 16;
-        *reinterpret_cast<uintx4*>(dst) = xh;
-        *reinterpret_cast<uintx4*>(dst + 2 * K * 16) = xm;
-        *reinterpret_cast<uintx4*>(dst + 4 * K * 16) = xl;
+        if (spins >= (1 << 22) && lane == 0) deadflag = 1;
+        chain(nt, nhalf);
       }
     }
     __syncthreads();
-    {
-      float av[8], dv[8];
-      const float4 a_lo = *reinterpret_cast<const float4*>(&pan[buf][32 * w + ln][8 * h]);
-      const float4 a_hi = *reinterpret_cast<const float4*>(&pan[buf][32 * w + ln][8 * h + 4]);
-      av[0] = a_lo.x; av[1] = a_lo.y; av[2] = a_lo.z; av[3] = a_lo.w;
-      av[4] = a_hi.x; av[5] = a_hi.y; av[6] = a_hi.z; av[7] = a_hi.w;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) dv[e] = owner ? -dsm[8 * h + e][owner ? q_own : 0] : 0.f;
-      uintx4 uh, um, ul;
-      split3_bf16(av, uh, um, ul);
-      const bf16x8 p0 = as_bf16x8(uh), p1 = as_bf16x8(um), p2 = as_bf16x8(ul);
-      split3_bf16(dv, uh, um, ul);
-      const bf16x8 d0 = as_bf16x8(uh), d1 = as_bf16x8(um), d2 = as_bf16x8(ul);
-      floatx16 ct, cn;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) { ct[v] = 0.f; cn[v] = 0.f; }
-      // C^T (rows of the panel's columns c0 + c, column = this wave's row ln): operand order (-D^T, A^T)
-      ct = CAFEQ_MFMA_BF16(d1, p1, ct);
-      ct = CAFEQ_MFMA_BF16(d0, p2, ct);
-      ct = CAFEQ_MFMA_BF16(d2, p0, ct);
-      ct = CAFEQ_MFMA_BF16(d0, p1, ct);
-      ct = CAFEQ_MFMA_BF16(d1, p0, ct);
-      ct = CAFEQ_MFMA_BF16(d0, p0, ct);
-      // C in accumulator form, valid in the owner lanes: operand order (A, -D)
-      cn = CAFEQ_MFMA_BF16(p1, d1, cn);
-      cn = CAFEQ_MFMA_BF16(p0, d2, cn);
-      cn = CAFEQ_MFMA_BF16(p2, d0, cn);
-      cn = CAFEQ_MFMA_BF16(p0, d1, cn);
-      cn = CAFEQ_MFMA_BF16(p1, d0, cn);
-      cn = CAFEQ_MFMA_BF16(p0, d0, cn);
-      float cv[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) cv[e] = ct[8 * half + e];
-      if (w == jt && owner) {
-        // this lane's row is pivot row q_own: D - I there
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int c = 8 * (e >> 2) + 4 * h + (e & 3);
-          cv[e] = dsm[q_own][c] - (c == q_own ? 1.f : 0.f);
-        }
-      }
-      split3_bf16(cv, uh, um, ul);
-      const bf16x8 a0 = as_bf16x8(uh), a1 = as_bf16x8(um), a2 = as_bf16x8(ul);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const unsigned char* pb = xb + (size_t(h) * K + 32 * j + ln) * 16;
-        const bf16x8 b0 = as_bf16x8(*reinterpret_cast<const uintx4*>(pb));
-        const bf16x8 b1 = as_bf16x8(*reinterpret_cast<const uintx4*>(pb + 2 * K * 16));
-        const bf16x8 b2 = as_bf16x8(*reinterpret_cast<const uintx4*>(pb + 4 * K * 16));
-        // (smallest terms first)
-        floatx16 d = reg[j];
-        d = CAFEQ_MFMA_BF16(a1, b1, d);
-        d = CAFEQ_MFMA_BF16(a0, b2, d);
-        d = CAFEQ_MFMA_BF16(a2, b0, d);
-        d = CAFEQ_MFMA_BF16(a0, b1, d);
-        d = CAFEQ_MFMA_BF16(a1, b0, d);
-        d = CAFEQ_MFMA_BF16(a0, b0, d);
-        reg[j] = d;
-      }
-      // a panel column becomes the panel's own result: C' + I (D in the pivot rows)
-      if (owner) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) cn[r] += (rbase + 8 * (r >> 2) + (r & 3)) == NB * t + q_own ? 1.f : 0.f;
-        if (w == jt) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) cn[8 * half + e] = dsm[8 * (e >> 2) + 4 * h + (e & 3)][q_own];
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-          if (j == jt) reg[j] = cn;
-      }
-    }
   };
-  for (int jt = 0; jt < 8; ++jt) {
-    panel(std::integral_constant<int, 0>{}, jt);
-    panel(std::integral_constant<int, 1>{}, jt);
+  own_write(std::integral_constant<int, 0>{});
+  if (tid == 0) ready = 0;
+  __syncthreads();
+  if (w == 0) {
+    chain(0, 0);
+    publish(std::integral_constant<int, 0>{});
   }
+  __syncthreads();
+  StaticFor<0, K / NB>::run(panel);
   __syncthreads();
   const bool dead = deadflag != 0;
   if (a.status && tid == 0) a.status[size_t(b) * a.status_stride + a.status_offset] = dead ? 1 : 0;
