@@ -14,9 +14,13 @@
 //   gram_pair_kernel : fp32 MFMA (v_mfma_f32_32x32x2_f32), one workgroup per (head, 32-row
 //                      output stripe, chunk of the contraction range); codes are dequantized
 //                      on the fly; chunk partials are written out, not atomically added.
+//   gram_pair16_kernel : the same pair for heads of 128 and 256 on the 16-bit matrix pipe, operands
+//                      split exactly into three bfloat16 parts.
 //   gj_panel_kernel  : sums the chunk partials of S in float64 and inverts it by register-
 //                      resident Gauss-Jordan elimination with partial pivoting; also serves
 //                      cafeq_block_inverse.  C = I - S^-1 R follows as a batched product.
+//   gj_spd256_kernel : the inversion of S for heads of 256 as a block elimination whose products
+//                      run on the 16-bit matrix pipe.
 #include <atomic>
 #include <type_traits>
 
