@@ -1085,70 +1085,78 @@ __global__ __launch_bounds__(256) void sum_r_init_c_kernel(const float* __restri
 
 
 // Float64-accumulating batched product for the iterative refinement of the K = 256 solve:
-// C_b (double) = alpha * A_b B_b + beta * C_b, A and B float or double, a 32 x 64 tile per workgroup
-// (the few blocks of a k = 256 workload then give one workgroup per compute unit), 2 x 4 per thread.
+// C_b (double) = alpha * A_b B_b + beta * C_b, A and B float or double, on the float64 matrix instruction
+// (v_mfma_f64_16x16x4_f64: the vector pipe's float64 rate at a sixth of the operand traffic; a version on vector
+// multiply-adds, 2 x 4 results per thread, was bound by its LDS reads: 18 us against 12-15).  A 32 x 64 tile per
+// workgroup (the few blocks of a k = 256 workload then give one workgroup per compute unit) of four
+// waves, wave w the 16 x 16 tiles (w / 2, 2 (w % 2)) and (w / 2, 2 (w % 2) + 1); chunks of 64 contraction indices
+// through LDS, the next chunk's requests in flight while one is multiplied; K a multiple of 64.  (All four chunks
+// of K = 256 requested at the start measured the same.)  Operand layouts: lane l gives A[i = l % 16][k = l / 16] and B[k = l / 16][j = l % 16];
+// its four results are rows l / 16 + 4 r (r = 0..3) of column l % 16.
+typedef double doublex4 __attribute__((ext_vector_type(4)));
 template <typename AT, typename BT>
-__global__ __launch_bounds__(256) void bgemm_f64acc_kernel(const AT* __restrict__ A, const BT* __restrict__ B,
-                                                            double* __restrict__ C, int K, double alpha, double beta) {
-  __shared__ double sa[16][34];   // [l][i]
-  __shared__ double sb[16][66];   // [l][j]
+__global__ __launch_bounds__(256) void bgemm_f64mfma_kernel(const AT* __restrict__ A, const BT* __restrict__ B,
+                                                             double* __restrict__ C, int K, double alpha, double beta) {
+  constexpr int LC = 64;
+  __shared__ double sa[32][LC + 2];   // [i][l]   (row strides chosen so that the operand reads of 32 lanes cover
+  __shared__ double sb[LC][80];       // [l][j]    all banks once)
   const int tpc = K / 64, tpr = K / 32;
   const int b = blockIdx.x / (tpr * tpc), tile = blockIdx.x % (tpr * tpc);
   const int i0 = (tile / tpc) * 32, j0 = (tile % tpc) * 64;
   const AT* Ab = A + size_t(b) * K * K;
   const BT* Bb = B + size_t(b) * K * K;
   double* Cb = C + size_t(b) * K * K;
-  const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
-  double acc[2][4] = {};
-  // the next chunk of 16 contraction indices is fetched into registers while the current one is multiplied
-  AT pa[2];
-  BT pb[4];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, li = lane & 15, lk = lane >> 4;
+  const int ti = w >> 1, tj0 = 2 * (w & 1);
+  doublex4 acc[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc[t][r] = 0.0;
+  AT pa[8];
+  BT pb[16];
   auto fetch = [&](int l0) {
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int e = threadIdx.x + 256 * q;
-      pa[q] = Ab[(i0 + e / 16) * K + l0 + e % 16];
+    for (int q = 0; q < 8; ++q) {
+      const int e = tid + 256 * q;
+      pa[q] = Ab[(i0 + e / LC) * K + l0 + e % LC];
     }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int e = threadIdx.x + 256 * q;
+    for (int q = 0; q < 16; ++q) {
+      const int e = tid + 256 * q;
       pb[q] = Bb[(l0 + e / 64) * K + j0 + e % 64];
     }
   };
   fetch(0);
-  for (int l0 = 0; l0 < K; l0 += 16) {
+  for (int l0 = 0; l0 < K; l0 += LC) {
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int e = threadIdx.x + 256 * q;
-      sa[e % 16][e / 16] = double(pa[q]);
+    for (int q = 0; q < 8; ++q) {
+      const int e = tid + 256 * q;
+      sa[e / LC][e % LC] = double(pa[q]);
     }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int e = threadIdx.x + 256 * q;
+    for (int q = 0; q < 16; ++q) {
+      const int e = tid + 256 * q;
       sb[e / 64][e % 64] = double(pb[q]);
     }
     __syncthreads();
-    if (l0 + 16 < K) fetch(l0 + 16);
+    if (l0 + LC < K) fetch(l0 + LC);
 #pragma unroll
-    for (int l = 0; l < 16; ++l) {
-      double av[2], bv[4];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) av[u] = sa[l][ty * 2 + u];
-#pragma unroll
-      for (int v = 0; v < 4; ++v) bv[v] = sb[l][tx * 4 + v];
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) acc[u][v] = fma(av[u], bv[v], acc[u][v]);
+    for (int s4 = 0; s4 < LC / 4; ++s4) {
+      const double av = sa[16 * ti + li][4 * s4 + lk];
+      const double b0 = sb[4 * s4 + lk][16 * tj0 + li];
+      const double b1 = sb[4 * s4 + lk][16 * (tj0 + 1) + li];
+      acc[0] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, b0, acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, b1, acc[1], 0, 0, 0);
     }
     __syncthreads();
   }
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
+  for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      double* dst = Cb + (i0 + ty * 2 + u) * K + j0 + tx * 4 + v;
-      *dst = alpha * acc[u][v] + (beta != 0.0 ? beta * *dst : 0.0);
+    for (int r = 0; r < 4; ++r) {
+      double* dst = Cb + (i0 + 16 * ti + lk + 4 * r) * K + j0 + 16 * (tj0 + t) + li;
+      *dst = alpha * acc[t][r] + (beta != 0.0 ? beta * *dst : 0.0);
     }
 }
 
@@ -1704,9 +1712,9 @@ int launch_gj_solve(int K, int nb, int nz, const float* partial, double* work, f
     return launch_bgemm(false, false, Sinv, R, out, K, nb, -1.f, 1.f, st);
   }
   const unsigned grid = unsigned(nb) * (K / 32) * (K / 64);
-  hipLaunchKernelGGL((bgemm_f64acc_kernel<float, double>), dim3(grid), dim3(256), 0, st, Sinv, R64, X64, K, 1.0, 0.0);
-  hipLaunchKernelGGL((bgemm_f64acc_kernel<double, double>), dim3(grid), dim3(256), 0, st, S64, X64, res, K, -1.0, 1.0);
-  hipLaunchKernelGGL((bgemm_f64acc_kernel<float, double>), dim3(grid), dim3(256), 0, st, Sinv, res, X64, K, 1.0, 1.0);
+  hipLaunchKernelGGL((bgemm_f64mfma_kernel<float, double>), dim3(grid), dim3(256), 0, st, Sinv, R64, X64, K, 1.0, 0.0);
+  hipLaunchKernelGGL((bgemm_f64mfma_kernel<double, double>), dim3(grid), dim3(256), 0, st, S64, X64, res, K, -1.0, 1.0);
+  hipLaunchKernelGGL((bgemm_f64mfma_kernel<float, double>), dim3(grid), dim3(256), 0, st, Sinv, res, X64, K, 1.0, 1.0);
   const int64_t n = int64_t(mat);
   hipLaunchKernelGGL(eye_minus_kernel, dim3(unsigned((n + 255) / 256)), dim3(256), 0, st, X64, K, n, out);
   CAFEQ_CHECK_LAUNCH();
@@ -1799,8 +1807,8 @@ int launch_inverse256(const float* T, int nb, double* work, float* Tinv, float* 
   const unsigned grid = unsigned(nb) * (K / 32) * (K / 64);
   const int64_t n = int64_t(mat);
   hipLaunchKernelGGL(eye64_kernel, dim3(unsigned((n + 255) / 256)), dim3(256), 0, st, res, K, n);
-  hipLaunchKernelGGL((bgemm_f64acc_kernel<float, float>), dim3(grid), dim3(256), 0, st, T, Tinv, res, K, -1.0, 1.0);
-  hipLaunchKernelGGL((bgemm_f64acc_kernel<float, double>), dim3(grid), dim3(256), 0, st, Tinv, res, X64, K, 1.0, 0.0);
+  hipLaunchKernelGGL((bgemm_f64mfma_kernel<float, float>), dim3(grid), dim3(256), 0, st, T, Tinv, res, K, -1.0, 1.0);
+  hipLaunchKernelGGL((bgemm_f64mfma_kernel<float, double>), dim3(grid), dim3(256), 0, st, Tinv, res, X64, K, 1.0, 0.0);
   hipLaunchKernelGGL(add64_kernel, dim3(unsigned((n + 255) / 256)), dim3(256), 0, st, X64, n, Tinv);
   CAFEQ_CHECK_LAUNCH();
   if (rho_row && (rc = launch_rho(Tinv, K, nb, 1, rho_row, st))) return rc;
