@@ -93,6 +93,8 @@ __device__ __forceinline__ void loss_v2_body(const CoreParams& p, const unsigned
   // (The variants that write codes or scales keep their requests at the start of the matrix phase: their vector
   // phase has no registers to hold a strip in flight.)
   constexpr bool EARLY = !OUT;
+  // (16-byte code stores need the code matrix aligned to 16 bytes; its row length is a multiple of 128)
+  const bool wide_codes = OUT && (reinterpret_cast<uintptr_t>(p.codes) & 15) == 0;
   if constexpr (EARLY) {
     const int sg = int(mt0 / mt_per_seg);
     request_strip(sg, (mt0 - int64_t(sg) * mt_per_seg) * kV2Waves + wave);
@@ -305,7 +307,33 @@ __device__ __forceinline__ void loss_v2_body(const CoreParams& p, const unsigned
         }
       }
       s_errz = fmaf(e2, usc2, s_errz);
-      if (OUT && p.codes && valid) {
+      if (OUT && AXIS == CAFEQ_AXIS_COL && L == 128 && p.codes && wide_codes) {
+        // A line's 128 codes are spread over its two lanes in alternating 4-byte words (word f4 of lane half h:
+        // codes 8 f4 + 4 h ..).  Swapping the upper lanes' word a with the lower lanes' word a + 8 leaves codes
+        // 0..63 in the lower lane and 64..127 in the upper one: four 16-byte stores per lane instead of sixteen
+        // 4-byte ones.
+        uint32_t wd[16];
+#pragma unroll
+        for (int f4 = 0; f4 < 16; ++f4) {
+          const int f = 4 * f4;
+          wd[f4] = pack4(acc[f / 16][f % 16], acc[f / 16][f % 16 + 1], acc[f / 16][f % 16 + 2], acc[f / 16][f % 16 + 3]);
+        }
+#pragma unroll
+        for (int a = 0; a < 8; ++a) {
+          const auto r = __builtin_amdgcn_permlane32_swap(wd[a], wd[a + 8], false, false);
+          wd[a] = r[0];
+          wd[a + 8] = r[1];
+        }
+        if (valid) {
+          int8_t* dst = p.codes + line * p.cols + ax0 + 64 * h;
+#pragma unroll
+          for (int m = 0; m < 4; ++m) {
+            uintx4 v;
+            v[0] = wd[2 * m]; v[1] = wd[2 * m + 8]; v[2] = wd[2 * m + 1]; v[3] = wd[2 * m + 9];
+            *reinterpret_cast<uintx4*>(dst + 16 * m) = v;
+          }
+        }
+      } else if (OUT && p.codes && valid) {
 #pragma unroll
         for (int f4 = 0; f4 < L / 8; ++f4) {
           const int f = 4 * f4;
