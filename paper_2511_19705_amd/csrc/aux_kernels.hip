@@ -11,27 +11,59 @@ namespace cafeq {
 namespace {
 
 // rho[b*K + j]: squared norm of row j (by_row) or column j of P_b, summed in float64.  256 / K threads share a
-// line (K = 256: one each); they take its elements interleaved and meet in LDS, added in thread order.
+// line (K = 256: one each); they take its elements interleaved and meet in LDS, added in thread order.  A workgroup
+// takes nbk consecutive blocks.
+// With rG != null the workgroup also writes the sums of rho over groups of G axis indices (what rho_group_kernel
+// computes, in its arithmetic: lanes interleaved over a group's indices, then a wave sum):
+//   G <= K, G | K, nbk = 1: rG[(b rep + r) (K / G) + q] = sum over indices q G .. q G + G - 1 of block b, for each
+//                           of the rep row-blocks that share the block;
+//   G = nbk K <= 256, rep = 1: rG[workgroup] = sum over its nbk blocks.
 __global__ __launch_bounds__(256) void rho_kernel(const float* __restrict__ P, int K, int by_row,
-                                                   float* __restrict__ rho) {
+                                                   float* __restrict__ rho, float* __restrict__ rG, int G, int rep,
+                                                   int nbk) {
   __shared__ double part[256];
-  const float* Pb = P + size_t(blockIdx.x) * K * K;
+  __shared__ float line[256];
   const int tpl = 256 / K;                       // threads per line: K is 32, 64, 128 or 256
   // by_row: neighbouring threads share a row (their loads fall into the same cache lines);
   // by column: neighbouring threads take neighbouring columns (coalesced rows)
   const int j = by_row ? threadIdx.x / tpl : threadIdx.x % K;
   const int s = by_row ? threadIdx.x % tpl : threadIdx.x / K;
-  double acc = 0;
-  for (int i = s; i < K; i += tpl) {
-    const float v = by_row ? Pb[j * K + i] : Pb[i * K + j];
-    acc += double(v) * v;
+  for (int bb = 0; bb < nbk; ++bb) {
+    const size_t b = size_t(blockIdx.x) * nbk + bb;
+    const float* Pb = P + b * K * K;
+    double acc = 0;
+    for (int i = s; i < K; i += tpl) {
+      const float v = by_row ? Pb[j * K + i] : Pb[i * K + j];
+      acc += double(v) * v;
+    }
+    part[s * K + j] = acc;
+    __syncthreads();
+    if (threadIdx.x < K) {
+      double t = part[threadIdx.x];
+      for (int q = 1; q < tpl; ++q) t += part[q * K + threadIdx.x];
+      rho[b * K + threadIdx.x] = float(t);
+      if (rG) line[bb * K + threadIdx.x] = float(t);      // (rG set: nbk K <= 256)
+    }
+    __syncthreads();
   }
-  part[s * K + j] = acc;
-  __syncthreads();
-  if (threadIdx.x < K) {
-    double t = part[threadIdx.x];
-    for (int q = 1; q < tpl; ++q) t += part[q * K + threadIdx.x];
-    rho[size_t(blockIdx.x) * K + threadIdx.x] = float(t);
+  if (rG == nullptr) return;                     // uniform
+  const int lane = threadIdx.x % kWave;
+  if (nbk > 1) {
+    if (threadIdx.x < kWave) {
+      float acc = 0.f;
+      for (int e = lane; e < G; e += kWave) acc += line[e];
+      acc = wave_sum(acc);
+      if (lane == 0) rG[blockIdx.x] = acc;
+    }
+    return;
+  }
+  const int ng = K / G;
+  for (int q = threadIdx.x / kWave; q < ng; q += 256 / kWave) {
+    float acc = 0.f;
+    for (int e = lane; e < G; e += kWave) acc += line[q * G + e];
+    acc = wave_sum(acc);
+    if (lane == 0)
+      for (int r = 0; r < rep; ++r) rG[(size_t(blockIdx.x) * rep + r) * ng + q] = acc;
   }
 }
 
@@ -609,8 +641,15 @@ int launch_split_planes(const float* src, int K, int nb, int trans, int nplanes,
   SplitRequest r{src, dst, trans, nplanes};
   return launch_split_planes_multi(&r, 1, K, nb, st);
 }
-int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_t st) {
-  hipLaunchKernelGGL(rho_kernel, dim3(nb), dim3(256), 0, st, P, K, by_row, rho);
+// Whether launch_rho can also form the group sums of rho_group_kernel for groups of G axis indices.
+bool rho_groups_inline(int K, int nb, int G, int rep) {
+  if (G >= 1 && G <= K) return K % G == 0;
+  return rep == 1 && G <= 256 && G % K == 0 && nb % (G / K) == 0;
+}
+int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_t st, float* rG, int G, int rep) {
+  if (rG && !rho_groups_inline(K, nb, G, rep)) return CAFEQ_ERR_INVALID_ARG;
+  const int nbk = rG && G > K ? G / K : 1;
+  hipLaunchKernelGGL(rho_kernel, dim3(nb / nbk), dim3(256), 0, st, P, K, by_row, rho, rG, G, rep, nbk);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }

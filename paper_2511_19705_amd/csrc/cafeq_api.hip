@@ -1002,8 +1002,10 @@ int cafeq_proxy_loss_fwd_bwd(const cafeq_mat* W, const cafeq_xform* x, const caf
   const bool f16 = !asym && core_forward_f16(K, gp.Gk, cfg->bits);
 
   // rho per axis index, its sums per segment-level group (the loss sweep) and per group (the gradient pass)
-  if ((rc = launch_rho(x->Tinv, K, nb, col ? 1 : 0, w.rho, st))) return rc;
-  if ((rc = launch_rho_groups(w.rho, K, x->rep, gp.Gk, naxis / gp.Gk, w.m.rG, st))) return rc;
+  // (groups inside a block, or of a few whole blocks: the same launch)
+  const bool rg_inline = rho_groups_inline(K, nb, gp.Gk, x->rep);
+  if ((rc = launch_rho(x->Tinv, K, nb, col ? 1 : 0, w.rho, st, rg_inline ? w.m.rG : nullptr, gp.Gk, x->rep))) return rc;
+  if (!rg_inline && (rc = launch_rho_groups(w.rho, K, x->rep, gp.Gk, naxis / gp.Gk, w.m.rG, st))) return rc;
   if (gp.gspan > 1 && (rc = launch_rho_groups(w.rho, K, x->rep, gp.G, naxis / gp.G, w.m.rGreal, st))) return rc;
 
   CoreParams p;

@@ -91,7 +91,9 @@ int launch_split_planes(const float* src, int K, int nb, int trans, int nplanes,
 // up to four splits in one launch; hdr (may be null): nslot partial headers reset by the same launch
 int launch_split_planes_multi(const SplitRequest* req, int n, int K, int nb, hipStream_t st, float* hdr = nullptr,
                               int64_t nslot = 0);
-int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_t st);
+bool rho_groups_inline(int K, int nb, int G, int rep);
+int launch_rho(const float* P, int K, int nb, int by_row, float* rho, hipStream_t st, float* rG = nullptr, int G = 0,
+               int rep = 1);   // rG: also the sums over groups of G indices, where rho_groups_inline (see rho_kernel)
 int launch_rho_groups(const float* rho, int K, int rep, int G, int64_t ngroups, float* rG, hipStream_t st);
 int launch_reduce_grad(const CoreParams& p, int K, int G, bool fused, int nb, int transpose_out,
                        const double* lse_ms, const float* member_ref, float* out, hipStream_t st);
