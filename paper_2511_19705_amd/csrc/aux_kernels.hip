@@ -316,7 +316,9 @@ struct VArgs {
   int scale_rows;
   float* Mmid;
 };
-__device__ __forceinline__ void build_mmid_body(const VArgs& a, const int b) {
+constexpr int kMmidParts = 4;   // workgroups per block in the middle factor of the rho path
+// (part of nparts: the workgroup scales that share of the block's elements; every part forms the same sums)
+__device__ __forceinline__ void build_mmid_body(const VArgs& a, const int b, const int part, const int nparts) {
   __shared__ float v[256];
   __shared__ int rng[2];
   const int K = a.K, n = threadIdx.x;   // K <= 256 = blockDim.x: thread n owns index n
@@ -334,7 +336,17 @@ __device__ __forceinline__ void build_mmid_body(const VArgs& a, const int b) {
     const int lo = rng[0], hi = rng[1];
     if (n < K) {
       const int gi = int(((int64_t(q) * K + n) % a.L) / a.G);
-      for (int w = lo; w < hi; ++w) acc += a.slot_hdr[(int64_t(w) + seg) * kHdrFloats + kHdrVa2 + gi];
+      const float* h0 = a.slot_hdr + seg * kHdrFloats + kHdrVa2 + gi;
+      // eight requests in flight; the additions keep the order of the workgroups
+      int w = lo;
+      for (; w + 8 <= hi; w += 8) {
+        float t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = h0[int64_t(w + u) * kHdrFloats];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += t[u];
+      }
+      for (; w < hi; ++w) acc += h0[int64_t(w) * kHdrFloats];
     }
     __syncthreads();
   }
@@ -342,9 +354,24 @@ __device__ __forceinline__ void build_mmid_body(const VArgs& a, const int b) {
   __syncthreads();
   const float* Pb = a.P + size_t(b) * K * K;
   float* Mb = a.Mmid + size_t(b) * K * K;
-  for (int i = threadIdx.x; i < K * K; i += blockDim.x) Mb[i] = Pb[i] * (a.scale_rows ? v[i / K] : v[i % K]);
+  // K * K / nparts elements, four per thread and step (K is a multiple of 32: rows are multiples of 4)
+  const int per = K * K / nparts, e0 = part * per;
+  for (int i = e0 + 4 * int(threadIdx.x); i < e0 + per; i += 4 * int(blockDim.x)) {
+    const float4 pv = *reinterpret_cast<const float4*>(Pb + i);
+    float4 o;
+    if (a.scale_rows) {
+      const float f = v[i / K];
+      o = make_float4(pv.x * f, pv.y * f, pv.z * f, pv.w * f);
+    } else {
+      const int c = i % K;
+      o = make_float4(pv.x * v[c], pv.y * v[c + 1], pv.z * v[c + 2], pv.w * v[c + 3]);
+    }
+    *reinterpret_cast<float4*>(Mb + i) = o;
+  }
 }
-__global__ __launch_bounds__(256) void build_mmid_kernel(const VArgs a) { build_mmid_body(a, int(blockIdx.x)); }
+__global__ __launch_bounds__(256) void build_mmid_kernel(const VArgs a) {
+  build_mmid_body(a, int(blockIdx.x) / kMmidParts, int(blockIdx.x) % kMmidParts, kMmidParts);
+}
 
 // losses: fixed-order float64 sums over every partial header (loss_reduce.hpp), as a launch of its own
 __global__ __launch_bounds__(kLossThreads) void reduce_losses_kernel(const LossArgs a) {
@@ -354,15 +381,16 @@ __global__ __launch_bounds__(kLossThreads) void reduce_losses_kernel(const LossA
 }
 
 // What follows the loss / gradient kernel of a single matrix whose gradient comes as partials, in one launch:
-// the gradient reduction (nred_x x nred_y workgroups), the middle factor of the gradient's way through rho(P) (one
-// workgroup per block) and the loss reduction (one workgroup) read the same partials and do not depend on each other.
+// the gradient reduction (nred_x x nred_y workgroups), the middle factor of the gradient's way through rho(P)
+// (kMmidParts workgroups per block) and the loss reduction (one workgroup) read the same partials and do not depend
+// on each other.
 __global__ __launch_bounds__(256) void single_tail_kernel(const ReduceArgs ra, const VArgs va, const LossArgs la,
                                                           const int nred_x, const int nred_y, const int nb) {
   const int id = int(blockIdx.x), nred = nred_x * nred_y;
   if (id < nred) {
     reduce_grad_body(ra, id % nred_x, id / nred_x);
-  } else if (id < nred + nb) {
-    build_mmid_body(va, id - nred);
+  } else if (id < nred + nb * kMmidParts) {
+    build_mmid_body(va, (id - nred) / kMmidParts, (id - nred) % kMmidParts, kMmidParts);
   } else {
     __shared__ double red[5 * (kLossThreads / 64)];
     double m, sm;
@@ -702,7 +730,7 @@ int launch_build_mmid(const CoreParams& p, int K, int G, int nb, const float* P,
   a.slot_hdr = p.slot_hdr; a.mt_per_seg = p.mt_per_seg; a.n_mt = p.n_mt; a.nwg = p.nwg;
   a.K = K; a.L = K > G ? K : G; a.G = G; a.rep = p.rep; a.beta = p.beta; a.P = P;
   a.scale_rows = scale_rows; a.Mmid = Mmid;
-  hipLaunchKernelGGL(build_mmid_kernel, dim3(nb), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(build_mmid_kernel, dim3(nb * kMmidParts), dim3(256), 0, st, a);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
 }
@@ -718,7 +746,7 @@ int launch_single_tail(const CoreParams& pgrad, const CoreParams& ploss, int K, 
   la.hdrA = ploss.slot_hdr; la.nslotA = nslot; la.kind = kLossSur; la.beta = beta; la.losses = losses;
   la.lse_ms = lse_ms;
   const int nred_x = nb, nred_y = (K * K + 1023) / 1024;
-  hipLaunchKernelGGL(single_tail_kernel, dim3(unsigned(nred_x * nred_y + nb + 1)), dim3(256), 0, st, ra, va, la,
+  hipLaunchKernelGGL(single_tail_kernel, dim3(unsigned(nred_x * nred_y + nb * kMmidParts + 1)), dim3(256), 0, st, ra, va, la,
                      nred_x, nred_y, nb);
   CAFEQ_CHECK_LAUNCH();
   return CAFEQ_OK;
