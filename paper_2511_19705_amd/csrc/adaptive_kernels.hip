@@ -999,7 +999,8 @@ __global__ __launch_bounds__(512) void gj_spd256_kernel(const GjArgs a) {
       // (the next panel's columns lie in the other half of the lanes of tile njt: the replacement of this
       // panel's own columns below does not touch them)
       own_write(std::integral_constant<int, nt>{});
-      if (w == njt && lane == 0) __hip_atomic_store(&ready, nt, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+      // (every lane of the wave stores the count: each lane's own panel entries are released by its own store)
+      if (w == njt) __hip_atomic_store(&ready, nt, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
     StaticFor<0, 8>::run(others);
     // a panel column becomes the panel's own result: C' + I (D in the pivot rows)
